@@ -1,0 +1,191 @@
+/*
+ * qgx.h -- C ABI of the MI355X (gfx950) Q-GenX hot-path library.
+ *
+ * The calls follow the paper's own statement of the method (arXiv 2308.09187):
+ *   Q_l(v), random quantisation of normalised coordinates     Definition 1
+ *   CODE o Q / DEQ o CODE, norm + sign + integer code Psi       Section 3.2, Appendix J (Encoding)
+ *   adaptive levels from the weighted empirical CDF             Section 3.3, eq. (QAda)
+ *   aggregate and the two extra-gradient half-steps             Algorithm 1, eq. (Q-GenX)
+ *   adaptive step size gamma_t                                  Theorem 3 / Theorem 4
+ *
+ * Conventions
+ *   - No C++ types, no exceptions.  Every function returns a qgx_status (negative = error); after
+ *     an error the context stays usable and outputs are unspecified but never written out of bounds.
+ *   - Pointers marked DEVICE are caller-owned HIP device memory on the device that was current in
+ *     qgx_create; pointers marked HOST are ordinary host memory.  Device buffers must be 16-byte
+ *     aligned.  The library allocates only inside qgx_create (tables, state, scratch) and frees in
+ *     qgx_destroy.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work on
+ *     it and return; only the calls documented as synchronising wait for it.
+ *   - The K workers of the paper are a batch: V is [K][d] worker-major, contiguous, binary32.
+ *   - Errors found on the device (non-finite bucket, stream capacity, malformed stream) set bits in
+ *     a device error word that qgx_poll_error returns and clears.
+ *   - Determinism: the same (config, levels, V, call_id) gives a byte-identical qgx_stream.
+ *
+ * Stream container (the paper fixes only the bit string {0,1}*; the container is this library's):
+ *   Coordinates of one worker are cut into segments (tensors), segments into buckets of at most
+ *   `bucket` coordinates (own norm each; the last bucket of a segment may be short), buckets into
+ *   chunks of at most QGX_CHUNK coordinates.  A chunk's bits are: for every coordinate in index
+ *   order the code word Psi(idx), first-written bit first, then one sign bit (1 = negative) iff
+ *   idx != 0.  Stream bit p of a chunk lives in 32-bit word p>>5, bit p&31.  Every chunk starts at
+ *   a multiple of 4 words; pad bits are 0.
+ *     norms     [K][NB]       binary32 norm of every bucket (C_b = 32 bits), 0 for a rejected bucket
+ *     chunk_off [K][NC+1]     word offset of chunk c inside worker k's payload; entry NC = words used
+ *     sub_end   [K][NC][64]   bit offset, from the chunk start, one past the last bit of the j-th run
+ *                             of QGX_SUB coordinates (entries past the chunk's last run repeat the
+ *                             chunk's bit length); makes the decode parallel
+ *     payload   [K][payload_words_per_worker]
+ *   Psi is Elias' recursive (omega) code of idx+1 (QGX_CODE_ELIAS_OMEGA), or a caller-supplied
+ *   prefix code table (QGX_CODE_TABLE).
+ */
+#ifndef QGX_H
+#define QGX_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QGX_CHUNK 4096u      /* coordinates per chunk */
+#define QGX_SUB 64u          /* coordinates per sub-chunk table entry */
+#define QGX_MAX_BUCKET 65536u
+#define QGX_MAX_SYM 127u     /* largest level table (l_0 .. l_{s+1}) */
+#define QGX_MAX_BINS 4096u
+#define QGX_MAX_CODE_BITS 13u
+
+typedef struct qgx_ctx qgx_ctx;
+
+typedef enum {
+    QGX_OK = 0,
+    QGX_ERR_ARG = -1,        /* null pointer, zero size, misaligned or out-of-range argument */
+    QGX_ERR_LEVELS = -2,     /* level table not 0 = l_0 < l_1 < ... < l_last = 1 */
+    QGX_ERR_CAPACITY = -3,   /* a worker's stream does not fit payload_words_per_worker */
+    QGX_ERR_STREAM = -4,     /* malformed stream: unknown code word, overrun, table mismatch */
+    QGX_ERR_NONFINITE = -5,  /* a bucket held a non-finite value; it was coded as all-zero */
+    QGX_ERR_HIP = -6,        /* a HIP runtime call failed */
+    QGX_ERR_STATE = -7       /* call order (levels not set, state not initialised) or internal wait expired */
+} qgx_status;
+
+/* bits of the device error word returned by qgx_poll_error */
+#define QGX_EBIT_CAPACITY 1u
+#define QGX_EBIT_STREAM 2u
+#define QGX_EBIT_NONFINITE 4u
+#define QGX_EBIT_STATE 8u
+
+typedef enum { QGX_NORM_LINF = 0, QGX_NORM_L2 = 2 } qgx_norm;           /* q of ||v||_q, Section 3.2 */
+typedef enum { QGX_CODE_ELIAS_OMEGA = 0, QGX_CODE_TABLE = 1 } qgx_code; /* Psi, Appendix J */
+
+typedef struct {
+    uint64_t d;                   /* coordinates per worker, 1 <= d < 2^31 */
+    uint32_t K;                   /* workers, 1 <= K <= 65535 */
+    uint32_t bucket;              /* coordinates per bucket, multiple of 4, <= QGX_MAX_BUCKET */
+    uint32_t n_segments;          /* 0 or 1 => one segment of length d */
+    const uint64_t* segment_len;  /* HOST, n_segments lengths summing to d; all but the last multiples of 4 */
+    int32_t norm;                 /* qgx_norm */
+    int32_t code;                 /* qgx_code */
+    uint64_t seed;                /* key of the counter-based generator */
+} qgx_config;
+
+/* One CODE o Q result for all K workers.  All pointers DEVICE, caller-owned. */
+typedef struct {
+    float* norms;                       /* [K][NB] */
+    uint32_t* chunk_off;                /* [K][NC+1] */
+    uint16_t* sub_end;                  /* [K][NC][64] */
+    uint32_t* payload;                  /* [K][payload_words_per_worker] */
+    uint64_t payload_words_per_worker;  /* multiple of 4 */
+} qgx_stream;
+
+/* Creates a context on the current device: validates the configuration, builds the bucket and chunk
+ * tables, allocates state (Y, anchor), tables and scratch.  Synchronises the device. */
+qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg);
+void qgx_destroy(qgx_ctx* ctx);
+
+/* Sizes a caller needs to allocate a qgx_stream: buckets and chunks per worker and the payload
+ * words per worker that can never overflow (14 bits per coordinate plus chunk padding). */
+qgx_status qgx_stream_sizes(const qgx_ctx* ctx, uint64_t* n_buckets, uint64_t* n_chunks,
+                            uint64_t* worst_case_payload_words);
+
+/* Level table l of Definition 1: levels_host HOST [n_sym], 2 <= n_sym <= QGX_MAX_SYM,
+ * 0 = l[0] < ... < l[n_sym-1] = 1 (QGX_ERR_LEVELS otherwise).  Synchronises `stream`. */
+qgx_status qgx_set_levels(qgx_ctx* ctx, const float* levels_host, uint32_t n_sym, void* stream);
+/* Reads the current table back (after qgx_fit_levels).  levels_host HOST [QGX_MAX_SYM]. Synchronises. */
+qgx_status qgx_get_levels(qgx_ctx* ctx, float* levels_host, uint32_t* n_sym, void* stream);
+
+/* Psi as a prefix code table (Appendix J: Huffman or any other prefix code), only with
+ * QGX_CODE_TABLE: code_len HOST [n_sym] in 1..QGX_MAX_CODE_BITS, code_bits HOST [n_sym] with the
+ * first-written bit in bit 0.  Must be prefix-free (QGX_ERR_ARG otherwise) and cover the level
+ * table in use.  Synchronises `stream`. */
+qgx_status qgx_set_code_table(qgx_ctx* ctx, const uint8_t* code_len, const uint32_t* code_bits,
+                              uint32_t n_sym, void* stream);
+
+/* Q_l(v) of Definition 1, bucket by bucket (norm, normalise, level below, stochastic rounding).
+ *   V         DEVICE [K][d] binary32
+ *   call_id   distinguishes quantisation calls under one seed (e.g. 2t + half): coordinate i of
+ *             worker k draws word (i mod 4) of Philox4x32-10(key = seed, counter = (i/4, 0, k, call_id)),
+ *             top 24 bits as r in [0,1); rounds up iff r * (l_{j+1}-l_j) < u - l_j.
+ *   norms_in  DEVICE [K][NB] or NULL: norms to use instead of computing them
+ *   norms_out DEVICE [K][NB]: the norm used (0 for a rejected bucket)
+ *   sym       DEVICE [K][d] bytes: level index in bits 0..6, sign bit of v in bit 7 */
+qgx_status qgx_quantize(qgx_ctx* ctx, const float* V, uint32_t call_id, const float* norms_in,
+                        float* norms_out, uint8_t* sym, void* stream);
+
+/* CODE of Section 3.2 / Appendix J applied to symbols from qgx_quantize.  `norms` DEVICE [K][NB] is
+ * copied into out->norms unless it is the same pointer. */
+qgx_status qgx_encode(qgx_ctx* ctx, const float* norms, const uint8_t* sym, qgx_stream* out, void* stream);
+
+/* CODE o Q in one pass over V (the fast path): V crosses HBM once, symbols never leave registers.
+ * norms_in as in qgx_quantize (NULL = compute). */
+qgx_status qgx_quantize_encode(qgx_ctx* ctx, const float* V, uint32_t call_id, const float* norms_in,
+                               qgx_stream* out, void* stream);
+
+/* DEQ o CODE: Vhat DEVICE [K][d], vhat_i = +-(norm * l_idx). */
+qgx_status qgx_decode(qgx_ctx* ctx, const qgx_stream* in, float* Vhat, void* stream);
+
+/* Aggregate of Algorithm 1: mean DEVICE [d] = (1/K) sum_k DEQ(CODE_k), decoded on the fly. */
+qgx_status qgx_decode_average(qgx_ctx* ctx, const qgx_stream* in, float* mean, void* stream);
+
+/* Adaptive levels, eq. (QAda): weighted histogram of the normalised coordinates of V (each bucket
+ * weighted by its squared norm) over n_bins bins on the binary32 grid (64 bins per octave, n_bins a
+ * multiple of 64, <= QGX_MAX_BINS), then `sweeps` passes that move one interior level at a time to
+ * the stationary point between its neighbours, starting from the current table.  n_sym must equal
+ * the current table's length.  The new table replaces the context's.  hist_out DEVICE [n_bins]
+ * doubles or NULL. */
+qgx_status qgx_fit_levels(qgx_ctx* ctx, const float* V, uint32_t n_sym, uint32_t n_bins, uint32_t sweeps,
+                          double* hist_out, void* stream);
+
+/* State of eq. (Q-GenX): Y_1 = 0, S = 0, t = 1, gamma_1 = K, anchor = X1 (DEVICE [d] or NULL = 0).
+ * The paper's X_{t+1} = gamma_{t+1} Y_{t+1} is the X1 = 0 case of X_{t+1} = X1 + gamma_{t+1} Y_{t+1}. */
+qgx_status qgx_state_init(qgx_ctx* ctx, const float* X1, void* stream);
+
+/* One half-step of eq. (Q-GenX), decoding the K streams on the fly.
+ *   half = 0: X_out DEVICE [d] <- X_t - (gamma_t/K) sum_k Vhat_{k,t},  X_t = X1 + gamma_t Y_t.
+ *             `cur` holds CODE(Q(V_{k,t})); prev must be NULL.
+ *   half = 1: Y <- Y - (1/K) sum_k Vhat_{k,t+1/2};  S += sum_k ||Vhat_{k,t} - Vhat_{k,t+1/2}||^2;
+ *             gamma_{t+1} = K / sqrt(1 + S);  t += 1;  X_out (may be NULL) <- X1 + gamma_{t+1} Y.
+ *             `cur` holds the t+1/2 streams, `prev` the t streams (NULL: Vhat_{k,t} = 0, the
+ *             dual-averaging case).  Both must have been coded with the context's current levels. */
+qgx_status qgx_eg_step(qgx_ctx* ctx, int half, const qgx_stream* cur, const qgx_stream* prev,
+                       float* X_out, void* stream);
+
+/* Scalars of the iteration and of the last coding call.  Any pointer may be NULL.  Synchronises.
+ * total_bits: symbols + signs of the last qgx_encode / qgx_quantize_encode over all workers,
+ * without padding and without the 32 bits per bucket for the norm. */
+qgx_status qgx_get_scalars(qgx_ctx* ctx, double* S, double* gamma, uint64_t* t, uint64_t* total_bits,
+                           void* stream);
+
+/* Copies the dual state out (checkpoint) or in (resume).  Y, anchor DEVICE [d]; NULL skips. */
+qgx_status qgx_state_export(qgx_ctx* ctx, float* Y, float* anchor, void* stream);
+qgx_status qgx_state_import(qgx_ctx* ctx, const float* Y, const float* anchor, double S, uint64_t t,
+                            void* stream);
+
+/* Returns and clears the device error word (QGX_EBIT_*).  Synchronises `stream`. */
+uint32_t qgx_poll_error(qgx_ctx* ctx, void* stream);
+
+/* Human-readable text of the last host-side error of this context (never NULL). */
+const char* qgx_last_error(const qgx_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QGX_H */

@@ -130,7 +130,7 @@ def bucket_norm(v, norm_kind):
     return np.float32(n), bool(fin.value)
 
 
-def quantize(V, lay: Layout, norm_kind, levels, seed, call_id, norms_in=None):
+def quantize(V, lay: Layout, norm_kind, levels, seed, call_id, norms_in=None, k0=0, i0=0):
     """Q_l of Definition 1 per bucket.  V is [K][d] float32.
     Returns (norms [K][NB] f32, idx [K][d] u8, neg [K][d] u8, n_nonfinite_buckets)."""
     V = _c(V, np.float32)
@@ -146,7 +146,7 @@ def quantize(V, lay: Layout, norm_kind, levels, seed, call_id, norms_in=None):
                              _p(levels, C.c_float), C.c_uint32(len(levels)),
                              C.c_uint64(seed), C.c_uint32(call_id),
                              _p(norms_in, C.c_float), _p(norms, C.c_float),
-                             _p(idx, C.c_uint8), _p(neg, C.c_uint8))
+                             _p(idx, C.c_uint8), _p(neg, C.c_uint8), C.c_uint32(k0), C.c_uint64(i0))
     return norms, idx, neg, int(bad)
 
 

@@ -174,14 +174,17 @@ static uint32_t level_below(const float* levels, uint32_t n_sym, float u)
 /* V is [K][d]; norms_in (may be NULL) overrides the computed norms;         */
 /* norms_out [K][NB]; idx [K][d] level index of q_l(u_i); neg [K][d] sign    */
 /* bit of v_i.  Returns the number of non-finite buckets (all their symbols  */
-/* are 0 and the stored norm is 0).                                          */
+/* are 0 and the stored norm is 0).  k0 and i0 shift the worker and          */
+/* coordinate numbers the draws are keyed by, so that a slice of a larger    */
+/* problem can be checked on its own (0 for a whole problem).                */
 /* ------------------------------------------------------------------------ */
 uint64_t orc_quantize(const float* V, uint32_t K, uint64_t d,
                       const uint64_t* bucket_start, uint64_t NB, int norm_kind,
                       const float* levels, uint32_t n_sym,
                       uint64_t seed, uint32_t call_id,
                       const float* norms_in, float* norms_out,
-                      uint8_t* idx, uint8_t* neg)
+                      uint8_t* idx, uint8_t* neg,
+                      uint32_t k0, uint64_t i0)
 {
     uint64_t bad = 0;
 #pragma omp parallel for collapse(2) schedule(static) reduction(+ : bad)
@@ -204,7 +207,7 @@ uint64_t orc_quantize(const float* V, uint32_t K, uint64_t d,
                     const uint32_t j = level_below(levels, n_sym, u);
                     const float t = u - levels[j];
                     const float g = levels[j + 1] - levels[j];
-                    const float r = orc_uniform24(seed, k, call_id, i);
+                    const float r = orc_uniform24(seed, k0 + k, call_id, i0 + i);
                     /* up with probability xi = t / g, written without a division */
                     sym = j + ((r * g < t) ? 1u : 0u);
                 }

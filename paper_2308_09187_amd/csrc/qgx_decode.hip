@@ -1,0 +1,344 @@
+// DEQ o CODE and everything fused onto it: plain decode, the mean over K workers, and the two
+// extra-gradient half-steps with the step-size accumulator.
+// (Section 3.2 / Appendix J for the decoding; Algorithm 1 and eq. (Q-GenX) for the updates;
+// Theorem 3 for gamma_t.)
+//
+// One wave per chunk position.  The wave copies a worker's chunk from the payload into LDS with
+// coalesced 16-byte loads (the next worker's chunk is already in flight in registers), then every
+// lane parses its own run of 64 coordinates, starting at the bit offset the sub-chunk table gives:
+// a 32-bit window from two LDS words, one 13-bit table lookup for (symbol, length), the sign bit,
+// one multiply by the bucket norm.  The K decoded values of a coordinate are summed in registers, so
+// decoded vectors never go to HBM in the fused modes.
+#include "qgx_device.h"
+
+namespace qgx {
+
+constexpr int kStageWords = kChunkWordsMax + 4;
+constexpr int kPre = kChunkWordsMax / (kWave * 4);   // 7 x uint4 per lane cover a worst-case chunk
+
+struct ChunkRef {            // where one worker's chunk lives and how long it is
+    const uint4* src;
+    uint32_t words;          // multiple of 4, 0 when the tables are inconsistent
+};
+
+__device__ __forceinline__ ChunkRef chunk_ref(const uint32_t* payload, uint64_t cap, const uint32_t* chunk_off,
+                                              uint32_t k, uint32_t c, uint32_t NC, Scalars* sc)
+{
+    const uint32_t off = chunk_off[(size_t)k * (NC + 1) + c];
+    const uint32_t end = chunk_off[(size_t)k * (NC + 1) + c + 1];
+    ChunkRef r;
+    r.src = reinterpret_cast<const uint4*>(payload + (size_t)k * cap + off);
+    r.words = end - off;
+    if (end < off || r.words > (uint32_t)kChunkWordsMax || (off & 3u) || (r.words & 3u) || (uint64_t)end > cap) {
+        if (lane_id() == 0) raise_error(sc, QGX_EBIT_STREAM);
+        r.words = 0;
+    }
+    return r;
+}
+
+__device__ __forceinline__ void prefetch_chunk(const ChunkRef& cr, uint4 (&pre)[kPre])
+{
+    const uint32_t lane = (uint32_t)lane_id();
+#pragma unroll
+    for (int q = 0; q < kPre; ++q) {
+        const uint32_t i = lane + (uint32_t)q * kWave;
+        pre[q] = (i < (cr.words >> 2)) ? cr.src[i] : make_uint4(0, 0, 0, 0);
+    }
+}
+
+__device__ __forceinline__ void commit_chunk(uint32_t* stage, const uint4 (&pre)[kPre])
+{
+    const uint32_t lane = (uint32_t)lane_id();
+#pragma unroll
+    for (int q = 0; q < kPre; ++q) reinterpret_cast<uint4*>(stage)[lane + (uint32_t)q * kWave] = pre[q];
+}
+
+// One symbol at bit cursor p of the staged chunk: returns the signed value norm * l_idx.
+__device__ __forceinline__ float take_symbol(const uint32_t* stage, const uint16_t* dlut, const float* lval,
+                                             uint32_t& p, float n, bool& malformed)
+{
+    const uint32_t wi = min(p >> 5, (uint32_t)kChunkWordsMax);
+    const uint32_t w0 = stage[wi], w1 = stage[wi + 1];
+    const uint32_t win = __builtin_amdgcn_alignbit(w1, w0, p & 31u);
+    uint32_t e = dlut[win & (uint32_t)(kDlut - 1)];
+    if (e == 0xFFFFu) { malformed = true; e = 1u; }        // keep going in bounds: symbol 0, one bit
+    const uint32_t len = e & 15u, idx = e >> 4;
+    const uint32_t nz = idx != 0u ? 1u : 0u;
+    const uint32_t sg = (win >> len) & nz;
+    p += len + nz;
+    const float mag = n * lval[idx];
+    return __uint_as_float(__float_as_uint(mag) ^ (sg << 31));
+}
+
+template <DecMode MODE>
+__global__ __launch_bounds__(256) void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArgs a)
+{
+    extern __shared__ __align__(16) uint32_t s_dyn[];    // [waves][1 or 2][kStageWords]
+    __shared__ uint16_t s_dlut[kDlut];
+    __shared__ float s_lval[kSymMax];
+
+    const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
+    constexpr int kBufs = (MODE == DecMode::Half1) ? 2 : 1;
+    uint32_t* stage = s_dyn + (size_t)w * kBufs * kStageWords;
+    uint32_t* stage_p = stage + kStageWords;
+
+    for (int i = tid; i < kDlut / 2; i += (int)blockDim.x)
+        reinterpret_cast<uint32_t*>(s_dlut)[i] = reinterpret_cast<const uint32_t*>(tab->dlut)[i];
+    for (int i = tid; i < kSymMax; i += (int)blockDim.x) s_lval[i] = tab->lval[i];
+    // words past a chunk's end are read by the window of its last symbols: keep them defined
+    for (int q = lane; q < kBufs * kStageWords; q += kWave) stage[q] = 0;
+    __syncthreads();
+
+    const uint32_t g = (uint32_t)blockIdx.x * (blockDim.x >> 6) + (uint32_t)w;   // global wave number
+    uint32_t c, k_first, k_count;
+    if (MODE == DecMode::Decode) {
+        if (g >= lay.K * lay.NC) return;
+        k_first = g / lay.NC; c = g - k_first * lay.NC; k_count = 1;
+    } else {
+        if (g >= lay.NC) return;
+        c = g; k_first = 0; k_count = lay.K;
+    }
+    const uint32_t clo = lay.chunk_start[c];
+    const uint32_t clen = lay.chunk_start[c + 1] - clo;
+    const uint32_t bkt = lay.chunk_bucket[c];
+    const int cnt = (int)min(64u, clen > 64u * (uint32_t)lane ? clen - 64u * (uint32_t)lane : 0u);
+    const bool have_prev = (MODE == DecMode::Half1) && a.payload_p != nullptr;
+
+    float acc[kSub];
+#pragma unroll
+    for (int s = 0; s < kSub; ++s) acc[s] = 0.0f;
+    double sdiff = 0.0;
+    bool malformed = false;
+
+    uint4 pre[kPre], pre_p[(MODE == DecMode::Half1) ? kPre : 1];
+    ChunkRef cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, k_first, c, lay.NC, sc);
+    prefetch_chunk(cr, pre);
+    if constexpr (MODE == DecMode::Half1) {
+        if (have_prev) {
+            ChunkRef cp = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, k_first, c, lay.NC, sc);
+            prefetch_chunk(cp, reinterpret_cast<uint4(&)[kPre]>(pre_p));
+        }
+    }
+
+    for (uint32_t kk = 0; kk < k_count; ++kk) {
+        const uint32_t k = k_first + kk;
+        commit_chunk(stage, pre);
+        if constexpr (MODE == DecMode::Half1) {
+            if (have_prev) commit_chunk(stage_p, reinterpret_cast<uint4(&)[kPre]>(pre_p));
+        }
+        if (kk + 1 < k_count) {                      // next worker's chunk: in flight while this one is parsed
+            cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, k + 1, c, lay.NC, sc);
+            prefetch_chunk(cr, pre);
+            if constexpr (MODE == DecMode::Half1) {
+                if (have_prev) {
+                    ChunkRef cp = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, k + 1, c, lay.NC, sc);
+                    prefetch_chunk(cp, reinterpret_cast<uint4(&)[kPre]>(pre_p));
+                }
+            }
+        }
+        const uint16_t* se = a.sub_end + ((size_t)k * lay.NC + c) * kSubs;
+        const uint32_t p_end = se[lane];
+        uint32_t p = lane ? (uint32_t)se[lane - 1] : 0u;
+        const float n = a.norms[(size_t)k * lay.NB + bkt];
+        uint32_t pp = 0, pp_end = 0;
+        float np = 0.0f;
+        if constexpr (MODE == DecMode::Half1) {
+            if (have_prev) {
+                const uint16_t* sp = a.sub_end_p + ((size_t)k * lay.NC + c) * kSubs;
+                pp_end = sp[lane];
+                pp = lane ? (uint32_t)sp[lane - 1] : 0u;
+                np = a.norms_p[(size_t)k * lay.NB + bkt];
+            }
+        }
+        float* vout = nullptr;
+        if constexpr (MODE == DecMode::Decode) vout = a.out + (size_t)k * lay.d + clo + 64u * (uint32_t)lane;
+#pragma unroll
+        for (int s = 0; s < kSub; ++s) {
+            if (s < cnt) {
+                const float val = take_symbol(stage, s_dlut, s_lval, p, n, malformed);
+                if constexpr (MODE == DecMode::Decode) vout[s] = val;
+                else acc[s] += val;
+                if constexpr (MODE == DecMode::Half1) {
+                    float pv = 0.0f;
+                    if (have_prev) pv = take_symbol(stage_p, s_dlut, s_lval, pp, np, malformed);
+                    const double df = (double)pv - (double)val;
+                    sdiff = fma(df, df, sdiff);
+                }
+            }
+        }
+        if (cnt > 0 && p != p_end) malformed = true;
+        if constexpr (MODE == DecMode::Half1) {
+            if (have_prev && cnt > 0 && pp != pp_end) malformed = true;
+        }
+    }
+    if (__any(malformed) && lane == 0) raise_error(sc, QGX_EBIT_STREAM);
+    if (MODE == DecMode::Decode) return;
+
+    // ---- aggregate and update: lane owns coordinates clo + 64*lane .. + cnt ---------------------
+    const float Kf = (float)lay.K;
+    const uint32_t i0 = clo + 64u * (uint32_t)lane;
+    const float gam = sc->gamma_f;
+    if constexpr (MODE == DecMode::Half1) {
+        sdiff = wave_sum(sdiff);
+        if (lane == 0) a.s_partial[c] = sdiff;
+    }
+    if (cnt == kSub) {
+#pragma unroll
+        for (int s = 0; s < kSub; s += 4) {
+            float4 m = make_float4(acc[s] / Kf, acc[s + 1] / Kf, acc[s + 2] / Kf, acc[s + 3] / Kf);
+            if (MODE == DecMode::Average) {
+                *reinterpret_cast<float4*>(a.out + i0 + s) = m;
+            } else if (MODE == DecMode::Half0) {
+                const float4 y = *reinterpret_cast<const float4*>(a.Y + i0 + s);
+                float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (a.anchor) x = *reinterpret_cast<const float4*>(a.anchor + i0 + s);
+                x.x = (x.x + gam * y.x) - gam * m.x;
+                x.y = (x.y + gam * y.y) - gam * m.y;
+                x.z = (x.z + gam * y.z) - gam * m.z;
+                x.w = (x.w + gam * y.w) - gam * m.w;
+                *reinterpret_cast<float4*>(a.out + i0 + s) = x;
+            } else {
+                float4 y = *reinterpret_cast<const float4*>(a.Y + i0 + s);
+                y.x -= m.x; y.y -= m.y; y.z -= m.z; y.w -= m.w;
+                *reinterpret_cast<float4*>(a.Y + i0 + s) = y;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int s = 0; s < kSub; ++s) {
+            if (s < cnt) {
+                const float m = acc[s] / Kf;
+                if (MODE == DecMode::Average) a.out[i0 + s] = m;
+                else if (MODE == DecMode::Half0) {
+                    const float x = a.anchor ? a.anchor[i0 + s] : 0.0f;
+                    a.out[i0 + s] = (x + gam * a.Y[i0 + s]) - gam * m;
+                } else a.Y[i0 + s] -= m;
+            }
+        }
+    }
+}
+
+template <DecMode MODE>
+static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
+{
+    constexpr int waves = 4;
+    constexpr int bufs = (MODE == DecMode::Half1) ? 2 : 1;
+    const size_t lds = (size_t)waves * bufs * kStageWords * sizeof(uint32_t);
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<MODE>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    const uint64_t nwork = (MODE == DecMode::Decode) ? (uint64_t)lay.K * lay.NC : (uint64_t)lay.NC;
+    const uint32_t grid = (uint32_t)((nwork + waves - 1) / waves);
+    hipLaunchKernelGGL(k_decode<MODE>, dim3(grid), dim3(waves * kWave), lds, st, lay, tab, sc, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode(DecMode mode, const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a,
+                         hipStream_t st)
+{
+    switch (mode) {
+        case DecMode::Decode: return launch_mode<DecMode::Decode>(lay, tab, sc, a, st);
+        case DecMode::Average: return launch_mode<DecMode::Average>(lay, tab, sc, a, st);
+        case DecMode::Half0: return launch_mode<DecMode::Half0>(lay, tab, sc, a, st);
+        default: return launch_mode<DecMode::Half1>(lay, tab, sc, a, st);
+    }
+}
+
+// ---- the scalar end of the second half-step: S, gamma_{t+1}, t; then X_{t+1} on request -----------
+__global__ __launch_bounds__(256) void k_finish_half1(uint32_t NC, uint32_t K, Scalars* sc, const double* s_partial)
+{
+    __shared__ double s_red[256];
+    double acc = 0.0;
+    for (uint32_t i = threadIdx.x; i < NC; i += 256) acc += s_partial[i];     // fixed order: reproducible
+    s_red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) s_red[threadIdx.x] += s_red[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const double S = sc->S + s_red[0];
+        const double gamma = (double)K / sqrt(1.0 + S);       // Theorem 3: gamma_t = K (1 + sum ...)^(-1/2)
+        sc->S = S;
+        sc->gamma = gamma;
+        sc->gamma_f = (float)gamma;
+        sc->t += 1ull;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_x_from_y(uint32_t d, const Scalars* sc, const float* __restrict__ Y,
+                                                  const float* __restrict__ anchor, float* __restrict__ X)
+{
+    const float gam = sc->gamma_f;
+    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < d; i += gridDim.x * 256u)
+        X[i] = (anchor ? anchor[i] : 0.0f) + gam * Y[i];
+}
+
+hipError_t launch_finish_half1(const Layout& lay, Scalars* sc, const double* s_partial, const float* Y,
+                               const float* anchor, float* X_out, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_finish_half1, dim3(1), dim3(256), 0, st, lay.NC, lay.K, sc, s_partial);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || X_out == nullptr) return e;
+    const uint32_t grid = min((lay.d + 255u) / 256u, 4096u);
+    hipLaunchKernelGGL(k_x_from_y, dim3(grid), dim3(256), 0, st, lay.d, sc, Y, anchor, X_out);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void k_state_init(uint32_t d, uint32_t K, Scalars* sc, float* Y, float* anchor,
+                                                    const float* X1)
+{
+    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < d; i += gridDim.x * 256u) {
+        Y[i] = 0.0f;
+        anchor[i] = X1 ? X1[i] : 0.0f;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        sc->S = 0.0; sc->gamma = (double)K; sc->gamma_f = (float)K; sc->t = 1ull;
+    }
+}
+
+hipError_t launch_state_init(const Layout& lay, Scalars* sc, float* Y, float* anchor, const float* X1, hipStream_t st)
+{
+    const uint32_t grid = min((lay.d + 255u) / 256u, 4096u);
+    hipLaunchKernelGGL(k_state_init, dim3(grid), dim3(256), 0, st, lay.d, lay.K, sc, Y, anchor, X1);
+    return hipGetLastError();
+}
+
+__global__ void k_state_set(Scalars* sc, double S, unsigned long long t, uint32_t K)
+{
+    const double gamma = (double)K / sqrt(1.0 + S);
+    sc->S = S; sc->gamma = gamma; sc->gamma_f = (float)gamma; sc->t = t;
+}
+
+hipError_t launch_state_set(Scalars* sc, double S, unsigned long long t, uint32_t K, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_state_set, dim3(1), dim3(1), 0, st, sc, S, t, K);
+    return hipGetLastError();
+}
+
+// Bits of the last coded streams, without padding: the last sub-chunk entry of every chunk.
+__global__ __launch_bounds__(256) void k_sum_bits(uint64_t n_chunks, const uint16_t* sub_end, Scalars* sc)
+{
+    __shared__ unsigned long long s_red[256];
+    unsigned long long acc = 0;
+    for (uint64_t i = threadIdx.x; i < n_chunks; i += 256) acc += sub_end[i * kSubs + (kSubs - 1)];
+    s_red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) s_red[threadIdx.x] += s_red[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) sc->total_bits = s_red[0];
+}
+
+hipError_t launch_sum_bits(const Layout& lay, const uint16_t* sub_end, Scalars* sc, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_sum_bits, dim3(1), dim3(256), 0, st, (uint64_t)lay.K * lay.NC, sub_end, sc);
+    return hipGetLastError();
+}
+
+}  // namespace qgx

@@ -1,0 +1,287 @@
+// Adaptive levels (Section 3.3): the weighted empirical CDF of eq. (QAda) as a histogram of the
+// normalised coordinates, and the one-level-at-a-time solver on it.
+//
+// Histogram: persistent workgroups walk the (worker, bucket) pairs with a fixed stride; per bucket the
+// data is read once into registers (same row layout as the encoder), the norm is reduced, every
+// coordinate bumps an integer LDS counter of its bin, and the counters are folded into per-workgroup
+// binary64 sums weighted by the squared norm.  Workgroup sums go to scratch and are added in a fixed
+// order, so the histogram is reproducible bit for bit.
+//
+// Bins follow the binary32 grid: 64 equal-width bins per octave over n_bins/64 octaves below 1 (bin 0
+// also takes everything smaller, u = 1 goes to the last bin), so the bin of u is an integer function
+// of its bits and the resolution follows the heavy concentration of u near zero.
+#include "qgx_device.h"
+
+namespace qgx {
+
+__device__ __forceinline__ uint32_t bin_of(float u, uint32_t n_bins)
+{
+    const int key = (int)(__float_as_uint(u) >> 17) - (127 * 64 - (int)n_bins);
+    return (uint32_t)min(max(key, 0), (int)n_bins - 1);
+}
+
+__device__ __forceinline__ double bin_edge(uint32_t b, uint32_t n_bins)
+{
+    if (b == 0) return 0.0;
+    if (b >= n_bins) return 1.0;
+    return (double)__uint_as_float((uint32_t)((int)b + (127 * 64 - (int)n_bins)) << 17);
+}
+
+__global__ __launch_bounds__(1024) void k_histogram(Layout lay, const float* __restrict__ V, int norm_kind,
+                                                    uint32_t n_bins, double* __restrict__ partial, Scalars* sc)
+{
+    extern __shared__ __align__(16) unsigned char s_raw[];
+    double* s_acc = reinterpret_cast<double*>(s_raw);                    // [n_bins]
+    uint32_t* s_cnt = reinterpret_cast<uint32_t*>(s_acc + n_bins);       // [n_bins]
+    __shared__ double s_red[kMaxWaves];
+    __shared__ uint32_t s_bad[kMaxWaves];
+
+    const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
+    const int nwaves = (int)(blockDim.x >> 6);
+    for (uint32_t i = (uint32_t)tid; i < n_bins; i += blockDim.x) { s_acc[i] = 0.0; s_cnt[i] = 0; }
+    __syncthreads();
+
+    const uint32_t n_work = lay.K * lay.NB;
+    for (uint32_t t = blockIdx.x; t < n_work; t += gridDim.x) {
+        const uint32_t b = t / lay.K, k = t - b * lay.K;
+        const uint32_t lo = lay.bucket_start[b], hi = lay.bucket_start[b + 1];
+        const uint32_t clo = lo + (uint32_t)w * kChunk;
+        const uint32_t clen = clo < hi ? min((uint32_t)kChunk, hi - clo) : 0u;
+        const uint32_t cend = clo + clen;
+        const size_t kbase = (size_t)k * lay.d;
+        const bool vec_ok = (kbase & 3u) == 0;
+        const float* __restrict__ Vk = V + kbase;
+        float4 v[kRows];
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) {
+            const uint32_t i0 = clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i0 + 4u <= cend) {
+                if (vec_ok) x = *reinterpret_cast<const float4*>(Vk + i0);
+                else x = make_float4(Vk[i0], Vk[i0 + 1], Vk[i0 + 2], Vk[i0 + 3]);
+            } else if (i0 < cend) {
+                x.x = Vk[i0];
+                if (i0 + 1 < cend) x.y = Vk[i0 + 1];
+                if (i0 + 2 < cend) x.z = Vk[i0 + 2];
+            }
+            v[r] = x;
+        }
+        double acc = 0.0;
+        float mx = 0.0f;
+        uint32_t bad = 0;
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) {
+            const float e[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float ax = fabsf(e[q]);
+                bad |= !(ax <= 3.402823466e+38f);
+                if (norm_kind == QGX_NORM_L2) acc = fma((double)e[q], (double)e[q], acc);
+                else mx = fmaxf(mx, ax);
+            }
+        }
+        if (norm_kind == QGX_NORM_L2) acc = wave_sum(acc);
+        else acc = (double)wave_max(mx);
+        bad = wave_or(bad);
+        if (lane == 0) { s_red[w] = acc; s_bad[w] = bad; }
+        __syncthreads();
+        double tot = 0.0;
+        uint32_t anybad = 0;
+        for (int i = 0; i < nwaves; ++i) {
+            if (norm_kind == QGX_NORM_L2) tot += s_red[i];
+            else tot = fmax(tot, s_red[i]);
+            anybad |= s_bad[i];
+        }
+        const float n = (norm_kind == QGX_NORM_L2) ? (float)sqrt(tot) : (float)tot;
+        const bool usable = (anybad == 0) && (n > 0.0f) && (n <= 3.402823466e+38f);
+        if (anybad != 0 && tid == 0) raise_error(sc, QGX_EBIT_NONFINITE);
+        if (usable) {
+            const float rinv = 1.0f / n;
+#pragma unroll
+            for (int r = 0; r < kRows; ++r) {
+                const uint32_t i0 = clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
+                const float e[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (i0 + (uint32_t)q < cend) {
+                        const float u = fminf(fabsf(e[q]) * rinv, 1.0f);
+                        atomicAdd(&s_cnt[bin_of(u, n_bins)], 1u);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        if (usable) {
+            const double wgt = (double)n * (double)n;           // lambda of Section 3.3, unnormalised
+            for (uint32_t i = (uint32_t)tid; i < n_bins; i += blockDim.x) {
+                const uint32_t cnt = s_cnt[i];
+                if (cnt) { s_acc[i] += (double)cnt * wgt; s_cnt[i] = 0; }
+            }
+        }
+        __syncthreads();
+    }
+    for (uint32_t i = (uint32_t)tid; i < n_bins; i += blockDim.x)
+        partial[(size_t)blockIdx.x * n_bins + i] = s_acc[i];
+}
+
+__global__ __launch_bounds__(256) void k_hist_reduce(uint32_t n_bins, uint32_t n_partial,
+                                                     const double* __restrict__ partial, double* __restrict__ hist)
+{
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= n_bins) return;
+    double acc = 0.0;
+    for (uint32_t g = 0; g < n_partial; ++g) acc += partial[(size_t)g * n_bins + i];
+    hist[i] = acc;
+}
+
+uint32_t histogram_groups(const Layout& lay)
+{
+    const uint32_t n_work = lay.K * lay.NB;
+    return n_work < 512u ? n_work : 512u;
+}
+
+hipError_t launch_histogram(const Layout& lay, const float* V, int norm_kind, uint32_t n_bins, double* partial,
+                            uint32_t n_partial, double* hist, Scalars* sc, hipStream_t st)
+{
+    const size_t lds = (size_t)n_bins * (sizeof(double) + sizeof(uint32_t));
+    hipLaunchKernelGGL(k_histogram, dim3(n_partial), dim3(lay.waves_per_bucket * kWave), lds, st, lay, V, norm_kind,
+                       n_bins, partial, sc);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_hist_reduce, dim3((n_bins + 255u) / 256u), dim3(256), 0, st, n_bins, n_partial, partial, hist);
+    return hipGetLastError();
+}
+
+// ---- solver ---------------------------------------------------------------------------------------
+// With F~ piecewise uniform inside bins, the stationarity condition of (QAda) in l_j between its
+// neighbours a = l_{j-1}, c = l_{j+1},
+//     int_a^x (u - a) dF~ = int_x^c (c - u) dF~ ,
+// is linear in the mass M0(x) = F~ mass below x:  M0(x) = M0(a) + int_a^c (c - u) dF~ / (c - a).
+// So each update is an inverse-CDF lookup: prefix sums of mass and first moment, one binary search.
+
+struct Cdf {
+    const double* H;      // global [n_bins]
+    const double* M0;     // LDS [n_bins+1]
+    const double* M1;     // LDS [n_bins+1]
+    uint32_t n_bins;
+};
+
+__device__ uint32_t bin_containing(const Cdf& F, double x)
+{
+    uint32_t b = bin_of((float)x, F.n_bins);
+    while (b + 1 < F.n_bins && bin_edge(b + 1, F.n_bins) <= x) ++b;
+    while (b > 0 && bin_edge(b, F.n_bins) > x) --b;
+    return b;
+}
+
+__device__ void cum_at(const Cdf& F, double x, double* m0, double* m1)
+{
+    const uint32_t b = bin_containing(F, x);
+    const double e0 = bin_edge(b, F.n_bins), e1 = bin_edge(b + 1, F.n_bins);
+    const double h = F.H[b];
+    *m0 = F.M0[b] + h * (x - e0) / (e1 - e0);
+    *m1 = F.M1[b] + h / (e1 - e0) * 0.5 * (x * x - e0 * e0);
+}
+
+__device__ double stationary_point(const Cdf& F, double a, double c)
+{
+    double m0a, m1a, m0c, m1c;
+    cum_at(F, a, &m0a, &m1a);
+    cum_at(F, c, &m0c, &m1c);
+    const double right_all = c * (m0c - m0a) - (m1c - m1a);      // int_a^c (c - u) dF~
+    if (!(right_all > 0.0)) return a;                             // no mass between the neighbours
+    const double target = m0a + right_all / (c - a);
+    // smallest i in [1, n_bins] with M0[i] >= target; the root lies in bin i-1
+    uint32_t lo = 1, hi = F.n_bins;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (F.M0[mid] >= target) hi = mid; else lo = mid + 1;
+    }
+    const uint32_t b = lo - 1;
+    const double e0 = bin_edge(b, F.n_bins), e1 = bin_edge(b + 1, F.n_bins);
+    const double h = F.H[b];
+    double x = e0;
+    if (h > 0.0) x = e0 + (target - F.M0[b]) / h * (e1 - e0);
+    return fmin(fmax(x, a), c);
+}
+
+__global__ __launch_bounds__(256) void k_fit(Tables* tab, const double* __restrict__ hist, uint32_t n_bins,
+                                             uint32_t sweeps)
+{
+    extern __shared__ __align__(16) unsigned char s_raw[];
+    double* M0 = reinterpret_cast<double*>(s_raw);               // [n_bins+1]
+    double* M1 = M0 + (n_bins + 1);                              // [n_bins+1]
+    __shared__ double s_part0[256], s_part1[256];
+    __shared__ double s_lev[kSymMax];
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t per = (n_bins + 255u) / 256u;
+    const uint32_t b0 = tid * per, b1 = min(b0 + per, n_bins);
+    double a0 = 0.0, a1 = 0.0;
+    for (uint32_t b = b0; b < b1; ++b) {
+        const double h = hist[b];
+        a0 += h;
+        a1 += h * 0.5 * (bin_edge(b, n_bins) + bin_edge(b + 1, n_bins));
+    }
+    s_part0[tid] = a0; s_part1[tid] = a1;
+    __syncthreads();
+    if (tid == 0) {
+        double r0 = 0.0, r1 = 0.0;
+        for (int i = 0; i < 256; ++i) {
+            const double t0 = s_part0[i], t1 = s_part1[i];
+            s_part0[i] = r0; s_part1[i] = r1;
+            r0 += t0; r1 += t1;
+        }
+        M0[n_bins] = r0; M1[n_bins] = r1;
+    }
+    __syncthreads();
+    a0 = s_part0[tid]; a1 = s_part1[tid];
+    for (uint32_t b = b0; b < b1; ++b) {
+        M0[b] = a0; M1[b] = a1;
+        const double h = hist[b];
+        a0 += h;
+        a1 += h * 0.5 * (bin_edge(b, n_bins) + bin_edge(b + 1, n_bins));
+    }
+    const uint32_t n_sym = tab->n_sym;
+    if (tid < n_sym) s_lev[tid] = (double)tab->levels[tid];
+    __syncthreads();
+
+    if (tid == 0) {
+        const Cdf F = {hist, M0, M1, n_bins};
+        if (M0[n_bins] > 0.0) {
+            for (uint32_t s = 0; s < sweeps; ++s)
+                for (uint32_t j = 1; j + 1 < n_sym; ++j) s_lev[j] = stationary_point(F, s_lev[j - 1], s_lev[j + 1]);
+        }
+        // back to binary32, strictly increasing with gaps of at least 2^-24
+        float* lv = tab->levels;
+        lv[0] = 0.0f; lv[n_sym - 1] = 1.0f;
+        for (uint32_t j = 1; j + 1 < n_sym; ++j) {
+            float x = (float)s_lev[j];
+            const float floor_ = lv[j - 1] + 0x1p-24f;
+            lv[j] = x < floor_ ? floor_ : x;
+        }
+        for (uint32_t j = n_sym - 2; j >= 1; --j) {
+            const float ceil_ = lv[j + 1] - 0x1p-24f;
+            if (lv[j] > ceil_) lv[j] = ceil_;
+        }
+    }
+}
+
+hipError_t launch_fit(Tables* tab, const double* hist, uint32_t n_bins, uint32_t sweeps, hipStream_t st)
+{
+    const size_t lds = 2 * (size_t)(n_bins + 1) * sizeof(double);
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fit),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           2 * (QGX_MAX_BINS + 1) * (int)sizeof(double));
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(k_fit, dim3(1), dim3(256), lds, st, tab, hist, n_bins, sweeps);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_build_tables(tab, st);
+}
+
+}  // namespace qgx

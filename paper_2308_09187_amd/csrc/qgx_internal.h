@@ -1,0 +1,116 @@
+// Internal declarations shared by the host side of the library and its gfx950 kernels.
+// Nothing here is part of the C ABI (include/qgx.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/qgx.h"
+
+namespace qgx {
+
+constexpr int kWave = 64;                 // CDNA wavefront
+constexpr int kChunk = QGX_CHUNK;         // coordinates per chunk = one wave's share
+constexpr int kRows = 16;                 // rows of 256 coordinates per chunk (4 per lane and row)
+constexpr int kSub = QGX_SUB;
+constexpr int kSubs = 64;                 // sub-chunk table entries per chunk
+constexpr int kMaxCode = QGX_MAX_CODE_BITS;             // longest code word
+constexpr int kMaxSymBits = kMaxCode + 1;               // plus the sign bit
+constexpr int kChunkWordsMax = kChunk * kMaxSymBits / 32;  // 1792
+constexpr int kAlignWords = 4;
+constexpr int kMaxWaves = QGX_MAX_BUCKET / kChunk;      // 16 waves = 1024 threads per bucket
+constexpr int kSymMax = 128;              // table storage (QGX_MAX_SYM = 127 entries used at most)
+
+// tau lookup: one cell per 1/32 octave over 24 octaves below 1, plus the cell of u = 1.
+constexpr int kCellMant = 5;
+constexpr int kCellOct = 24;
+constexpr int kCellKey0 = (127 - kCellOct) << kCellMant;
+constexpr int kCells = (kCellOct << kCellMant) + 1;     // 769
+constexpr int kCellsPad = 784;
+
+constexpr int kDlutBits = kMaxCode;       // decode window
+constexpr int kDlut = 1 << kDlutBits;     // 8192 entries
+
+// Device-resident tables: rebuilt on the device whenever the level table or the code changes.
+struct Tables {
+    float4 lev[kSymMax];        // {l_j, (l_{j+1}-l_j)*2^-24, l_{j+1} (+inf for the last gap), 0}
+    float lval[kSymMax];        // l_j
+    float levels[kSymMax];      // the table as set or fitted (source of the two above)
+    uint32_t code[kSymMax];     // code word (first-written bit in bit 0) | length << 16
+    uint32_t n_sym;
+    uint32_t code_kind;
+    uint32_t pad_[2];
+    uint8_t cell[kCellsPad];    // largest j <= n_sym-2 with l_j <= lower edge of the cell
+    uint16_t dlut[kDlut];       // next 13 stream bits -> idx << 4 | length; 0xFFFF = no code word
+};
+
+// Scalars of the iteration; lives in device memory, read by kernels, copied out on request.
+struct Scalars {
+    double S;                   // sum of squared half-step differences (Theorem 3)
+    double gamma;               // K / sqrt(1 + S)
+    unsigned long long t;       // iteration counter, starts at 1
+    unsigned long long total_bits;
+    float gamma_f;              // gamma rounded to binary32, what the update kernels multiply by
+    unsigned int err;           // QGX_EBIT_*
+    unsigned int ticket;        // ever-increasing workgroup ticket of the encoder
+    unsigned int pad_;
+};
+
+struct Layout {                 // device pointers into one allocation
+    const uint32_t* bucket_start;   // [NB+1]
+    const uint32_t* bucket_chunk0;  // [NB+1] first chunk of each bucket
+    const uint32_t* chunk_start;    // [NC+1]
+    const uint32_t* chunk_bucket;   // [NC]
+    uint32_t NB, NC, K, d;
+    uint32_t waves_per_bucket;      // ceil(bucket / kChunk)
+};
+
+enum class EncMode { Fused, QuantOnly, EncodeOnly };
+enum class DecMode { Decode, Average, Half0, Half1 };
+
+struct EncodeArgs {
+    const float* V;             // [K][d]           (Fused, QuantOnly)
+    const float* norms_in;      // [K][NB] or null
+    float* norms_out;           // [K][NB] or null
+    uint8_t* sym_out;           // [K][d]           (QuantOnly)
+    const uint8_t* sym_in;      // [K][d]           (EncodeOnly)
+    uint32_t* chunk_off;        // [K][NC+1]
+    uint16_t* sub_end;          // [K][NC][64]
+    uint32_t* payload;          // [K][cap]
+    uint64_t cap_words;
+    unsigned long long* scan_state;  // [K][NB] look-back words
+    uint32_t epoch;             // tags scan_state entries of this launch
+    uint32_t ticket_base;       // value of Scalars::ticket before this launch
+    uint32_t seed_lo, seed_hi, call_id;
+    int norm_kind;
+};
+
+struct DecodeArgs {
+    const float* norms;  const uint32_t* chunk_off;  const uint16_t* sub_end;  const uint32_t* payload;
+    uint64_t cap_words;
+    // previous half-step's streams (Half1 only; payload_p null => all-zero vectors)
+    const float* norms_p;  const uint32_t* chunk_off_p;  const uint16_t* sub_end_p;  const uint32_t* payload_p;
+    uint64_t cap_words_p;
+    float* out;                 // Decode: Vhat [K][d]; Average: mean [d]; Half0: X_{t+1/2} [d]
+    float* Y;                   // [d] dual state (Half0 reads, Half1 updates)
+    const float* anchor;        // [d] or null
+    double* s_partial;          // [NC] per-chunk partial of S (Half1)
+};
+
+hipError_t launch_build_tables(Tables* tab, hipStream_t st);
+hipError_t launch_encode(EncMode mode, const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a,
+                         hipStream_t st);
+hipError_t launch_decode(DecMode mode, const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a,
+                         hipStream_t st);
+hipError_t launch_finish_half1(const Layout& lay, Scalars* sc, const double* s_partial, const float* Y,
+                               const float* anchor, float* X_out, hipStream_t st);
+hipError_t launch_state_init(const Layout& lay, Scalars* sc, float* Y, float* anchor, const float* X1,
+                             hipStream_t st);
+hipError_t launch_state_set(Scalars* sc, double S, unsigned long long t, uint32_t K, hipStream_t st);
+hipError_t launch_sum_bits(const Layout& lay, const uint16_t* sub_end, Scalars* sc, hipStream_t st);
+hipError_t launch_histogram(const Layout& lay, const float* V, int norm_kind, uint32_t n_bins, double* partial,
+                            uint32_t n_partial, double* hist, Scalars* sc, hipStream_t st);
+hipError_t launch_fit(Tables* tab, const double* hist, uint32_t n_bins, uint32_t sweeps, hipStream_t st);
+uint32_t histogram_groups(const Layout& lay);
+
+}  // namespace qgx

@@ -1,0 +1,474 @@
+// Host side of the C ABI: context, validation, layout tables, launches.  No arithmetic of the
+// method happens here; every step runs in the gfx950 kernels.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "qgx_internal.h"
+
+using namespace qgx;
+
+struct qgx_ctx {
+    qgx_config cfg{};
+    std::vector<uint64_t> seg;
+    int device = 0;
+    Layout lay{};
+    uint32_t* d_layout = nullptr;
+    Tables* d_tab = nullptr;
+    Scalars* d_sc = nullptr;
+    float* d_Y = nullptr;
+    float* d_anchor = nullptr;
+    unsigned long long* d_scan = nullptr;
+    double* d_spartial = nullptr;
+    double* d_hpartial = nullptr;
+    double* d_hist = nullptr;
+    uint32_t h_groups = 0;
+    uint32_t epoch = 0;
+    uint32_t ticket_count = 0;
+    uint32_t n_sym = 0;
+    bool levels_set = false, code_set = false, state_ready = false, has_anchor = false;
+    const uint16_t* last_sub_end = nullptr;
+    uint64_t worst_words = 0;
+    char err[256] = "";
+};
+
+namespace {
+
+qgx_status fail(qgx_ctx* ctx, qgx_status st, const char* fmt, ...)
+{
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+        va_end(ap);
+    }
+    return st;
+}
+
+#define QGX_HIP(ctx, call)                                                                             \
+    do {                                                                                               \
+        hipError_t e_ = (call);                                                                        \
+        if (e_ != hipSuccess) return fail((ctx), QGX_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+qgx_status check_stream(qgx_ctx* ctx, const qgx_stream* s, const char* what)
+{
+    if (!s || !s->norms || !s->chunk_off || !s->sub_end || !s->payload)
+        return fail(ctx, QGX_ERR_ARG, "%s: null stream pointer", what);
+    if (!aligned16(s->norms) || !aligned16(s->chunk_off) || !aligned16(s->sub_end) || !aligned16(s->payload))
+        return fail(ctx, QGX_ERR_ARG, "%s: stream buffers must be 16-byte aligned", what);
+    if (s->payload_words_per_worker == 0 || (s->payload_words_per_worker & 3u) ||
+        s->payload_words_per_worker > 0xFFFFFFFFull)
+        return fail(ctx, QGX_ERR_ARG, "%s: payload_words_per_worker must be a non-zero multiple of 4 below 2^32", what);
+    return QGX_OK;
+}
+
+qgx_status need_levels(qgx_ctx* ctx)
+{
+    if (!ctx->levels_set) return fail(ctx, QGX_ERR_STATE, "level table not set");
+    if (ctx->cfg.code == QGX_CODE_TABLE && !ctx->code_set) return fail(ctx, QGX_ERR_STATE, "code table not set");
+    return QGX_OK;
+}
+
+void free_all(qgx_ctx* c)
+{
+    void* all[] = {c->d_layout, c->d_tab, c->d_sc, c->d_Y, c->d_anchor, c->d_scan, c->d_spartial, c->d_hpartial, c->d_hist};
+    for (void* p : all) (void)hipFree(p);
+}
+
+}  // namespace
+
+extern "C" {
+
+qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
+{
+    if (!out || !cfg) return QGX_ERR_ARG;
+    *out = nullptr;
+    if (cfg->d == 0 || cfg->d >= (1ull << 31) || cfg->K == 0 || cfg->K > 65535u) return QGX_ERR_ARG;
+    if (cfg->bucket == 0 || (cfg->bucket & 3u) || cfg->bucket > QGX_MAX_BUCKET) return QGX_ERR_ARG;
+    if (cfg->norm != QGX_NORM_L2 && cfg->norm != QGX_NORM_LINF) return QGX_ERR_ARG;
+    if (cfg->code != QGX_CODE_ELIAS_OMEGA && cfg->code != QGX_CODE_TABLE) return QGX_ERR_ARG;
+    qgx_ctx* c = new (std::nothrow) qgx_ctx;
+    if (!c) return QGX_ERR_ARG;
+    c->cfg = *cfg;
+    if (cfg->n_segments > 1) {
+        if (!cfg->segment_len) { delete c; return QGX_ERR_ARG; }
+        c->seg.assign(cfg->segment_len, cfg->segment_len + cfg->n_segments);
+    } else {
+        c->seg.assign(1, cfg->n_segments == 1 && cfg->segment_len ? cfg->segment_len[0] : cfg->d);
+    }
+    c->cfg.segment_len = nullptr;
+    uint64_t sum = 0;
+    for (size_t s = 0; s < c->seg.size(); ++s) {
+        if (c->seg[s] == 0 || (s + 1 < c->seg.size() && (c->seg[s] & 3u))) { delete c; return QGX_ERR_ARG; }
+        sum += c->seg[s];
+    }
+    if (sum != cfg->d) { delete c; return QGX_ERR_ARG; }
+
+    // buckets and chunks of one worker
+    std::vector<uint32_t> bstart, bchunk0, cstart, cbucket;
+    uint64_t pos = 0, worst = 0;
+    for (uint64_t len_s : c->seg) {
+        uint64_t left = len_s;
+        while (left) {
+            const uint64_t len = left < cfg->bucket ? left : cfg->bucket;
+            bstart.push_back((uint32_t)pos);
+            bchunk0.push_back((uint32_t)cstart.size());
+            for (uint64_t o = 0; o < len; o += kChunk) {
+                const uint64_t cl = (len - o) < (uint64_t)kChunk ? (len - o) : (uint64_t)kChunk;
+                cstart.push_back((uint32_t)(pos + o));
+                cbucket.push_back((uint32_t)(bstart.size() - 1));
+                uint64_t wds = (cl * kMaxSymBits + 31) / 32;
+                worst += (wds + kAlignWords - 1) / kAlignWords * kAlignWords;
+            }
+            pos += len;
+            left -= len;
+        }
+    }
+    bstart.push_back((uint32_t)pos);
+    bchunk0.push_back((uint32_t)cstart.size());
+    cstart.push_back((uint32_t)pos);
+    const uint32_t NB = (uint32_t)bstart.size() - 1, NC = (uint32_t)cbucket.size();
+    if ((uint64_t)NB * cfg->K >= (1ull << 31)) { delete c; return QGX_ERR_ARG; }
+    c->worst_words = worst;
+
+    if (hipGetDevice(&c->device) != hipSuccess) { delete c; return QGX_ERR_HIP; }
+    const size_t n_lay = (size_t)(NB + 1) * 2 + (NC + 1) + NC;
+    std::vector<uint32_t> flat;
+    flat.reserve(n_lay);
+    flat.insert(flat.end(), bstart.begin(), bstart.end());
+    flat.insert(flat.end(), bchunk0.begin(), bchunk0.end());
+    flat.insert(flat.end(), cstart.begin(), cstart.end());
+    flat.insert(flat.end(), cbucket.begin(), cbucket.end());
+
+    c->lay.NB = NB; c->lay.NC = NC; c->lay.K = cfg->K; c->lay.d = (uint32_t)cfg->d;
+    uint32_t max_len = 0;
+    for (uint32_t b = 0; b < NB; ++b) max_len = bstart[b + 1] - bstart[b] > max_len ? bstart[b + 1] - bstart[b] : max_len;
+    c->lay.waves_per_bucket = (max_len + kChunk - 1) / kChunk;
+    c->h_groups = histogram_groups(c->lay);
+
+    bool ok = true;
+    ok = ok && hipMalloc(&c->d_layout, n_lay * sizeof(uint32_t)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_tab, sizeof(Tables)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_sc, sizeof(Scalars)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_Y, cfg->d * sizeof(float)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_anchor, cfg->d * sizeof(float)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_scan, (size_t)cfg->K * NB * sizeof(unsigned long long)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_spartial, (size_t)NC * sizeof(double)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_hpartial, (size_t)c->h_groups * QGX_MAX_BINS * sizeof(double)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_hist, QGX_MAX_BINS * sizeof(double)) == hipSuccess;
+    ok = ok && hipMemcpy(c->d_layout, flat.data(), n_lay * sizeof(uint32_t), hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemset(c->d_tab, 0, sizeof(Tables)) == hipSuccess;
+    ok = ok && hipMemset(c->d_sc, 0, sizeof(Scalars)) == hipSuccess;
+    ok = ok && hipMemset(c->d_scan, 0, (size_t)cfg->K * NB * sizeof(unsigned long long)) == hipSuccess;
+    if (ok) {
+        const uint32_t kind = (uint32_t)cfg->code;
+        ok = hipMemcpy(&c->d_tab->code_kind, &kind, sizeof(kind), hipMemcpyHostToDevice) == hipSuccess;
+    }
+    ok = ok && hipDeviceSynchronize() == hipSuccess;
+    if (!ok) { free_all(c); delete c; return QGX_ERR_HIP; }
+    c->lay.bucket_start = c->d_layout;
+    c->lay.bucket_chunk0 = c->d_layout + (NB + 1);
+    c->lay.chunk_start = c->d_layout + 2 * (size_t)(NB + 1);
+    c->lay.chunk_bucket = c->lay.chunk_start + (NC + 1);
+    *out = c;
+    return QGX_OK;
+}
+
+void qgx_destroy(qgx_ctx* ctx)
+{
+    if (!ctx) return;
+    (void)hipDeviceSynchronize();
+    free_all(ctx);
+    delete ctx;
+}
+
+qgx_status qgx_stream_sizes(const qgx_ctx* ctx, uint64_t* n_buckets, uint64_t* n_chunks,
+                            uint64_t* worst_case_payload_words)
+{
+    if (!ctx) return QGX_ERR_ARG;
+    if (n_buckets) *n_buckets = ctx->lay.NB;
+    if (n_chunks) *n_chunks = ctx->lay.NC;
+    if (worst_case_payload_words) *worst_case_payload_words = ctx->worst_words;
+    return QGX_OK;
+}
+
+qgx_status qgx_set_levels(qgx_ctx* ctx, const float* levels_host, uint32_t n_sym, void* stream)
+{
+    if (!ctx || !levels_host) return fail(ctx, QGX_ERR_ARG, "qgx_set_levels: null argument");
+    if (n_sym < 2 || n_sym > QGX_MAX_SYM) return fail(ctx, QGX_ERR_ARG, "qgx_set_levels: n_sym out of range");
+    if (levels_host[0] != 0.0f || levels_host[n_sym - 1] != 1.0f)
+        return fail(ctx, QGX_ERR_LEVELS, "level table must start at 0 and end at 1");
+    for (uint32_t j = 0; j + 1 < n_sym; ++j)
+        if (!(levels_host[j] < levels_host[j + 1]))
+            return fail(ctx, QGX_ERR_LEVELS, "level table not strictly increasing at %u", j);
+    hipStream_t st = (hipStream_t)stream;
+    if (ctx->cfg.code == QGX_CODE_TABLE && ctx->code_set && n_sym != ctx->n_sym) ctx->code_set = false;
+    QGX_HIP(ctx, hipMemcpyAsync(ctx->d_tab->levels, levels_host, n_sym * sizeof(float), hipMemcpyHostToDevice, st));
+    QGX_HIP(ctx, hipMemcpyAsync(&ctx->d_tab->n_sym, &n_sym, sizeof(n_sym), hipMemcpyHostToDevice, st));
+    QGX_HIP(ctx, launch_build_tables(ctx->d_tab, st));
+    QGX_HIP(ctx, hipStreamSynchronize(st));
+    ctx->n_sym = n_sym;
+    ctx->levels_set = true;
+    return QGX_OK;
+}
+
+qgx_status qgx_get_levels(qgx_ctx* ctx, float* levels_host, uint32_t* n_sym, void* stream)
+{
+    if (!ctx || !levels_host || !n_sym) return fail(ctx, QGX_ERR_ARG, "qgx_get_levels: null argument");
+    if (!ctx->levels_set) return fail(ctx, QGX_ERR_STATE, "level table not set");
+    hipStream_t st = (hipStream_t)stream;
+    QGX_HIP(ctx, hipMemcpyAsync(levels_host, ctx->d_tab->levels, ctx->n_sym * sizeof(float), hipMemcpyDeviceToHost, st));
+    QGX_HIP(ctx, hipStreamSynchronize(st));
+    *n_sym = ctx->n_sym;
+    return QGX_OK;
+}
+
+qgx_status qgx_set_code_table(qgx_ctx* ctx, const uint8_t* code_len, const uint32_t* code_bits, uint32_t n_sym,
+                              void* stream)
+{
+    if (!ctx || !code_len || !code_bits) return fail(ctx, QGX_ERR_ARG, "qgx_set_code_table: null argument");
+    if (ctx->cfg.code != QGX_CODE_TABLE) return fail(ctx, QGX_ERR_STATE, "context was not created with QGX_CODE_TABLE");
+    if (!ctx->levels_set || n_sym != ctx->n_sym)
+        return fail(ctx, QGX_ERR_STATE, "set the level table first; the code table must have as many entries");
+    double kraft = 0.0;
+    for (uint32_t j = 0; j < n_sym; ++j) {
+        if (code_len[j] < 1 || code_len[j] > QGX_MAX_CODE_BITS || (code_bits[j] >> code_len[j]))
+            return fail(ctx, QGX_ERR_ARG, "code word %u: length must be 1..13 and bits must fit it", j);
+        kraft += std::ldexp(1.0, -(int)code_len[j]);
+        for (uint32_t i = 0; i < j; ++i) {
+            const uint32_t m = code_len[i] < code_len[j] ? code_len[i] : code_len[j];
+            if (((code_bits[i] ^ code_bits[j]) & ((1u << m) - 1u)) == 0)
+                return fail(ctx, QGX_ERR_ARG, "code words %u and %u: one is a prefix of the other", i, j);
+        }
+    }
+    if (kraft > 1.0) return fail(ctx, QGX_ERR_ARG, "code table violates the Kraft inequality");
+    uint32_t packed[kSymMax] = {0};
+    for (uint32_t j = 0; j < n_sym; ++j) packed[j] = code_bits[j] | ((uint32_t)code_len[j] << 16);
+    hipStream_t st = (hipStream_t)stream;
+    QGX_HIP(ctx, hipMemcpyAsync(ctx->d_tab->code, packed, sizeof(packed), hipMemcpyHostToDevice, st));
+    QGX_HIP(ctx, launch_build_tables(ctx->d_tab, st));
+    QGX_HIP(ctx, hipStreamSynchronize(st));
+    ctx->code_set = true;
+    return QGX_OK;
+}
+
+static qgx_status run_encode(qgx_ctx* ctx, EncMode mode, const float* V, uint32_t call_id, const float* norms_in,
+                             float* norms_out, uint8_t* sym_out, const uint8_t* sym_in, qgx_stream* out, void* stream)
+{
+    qgx_status s = need_levels(ctx);
+    if (s != QGX_OK) return s;
+    EncodeArgs a{};
+    a.V = V; a.norms_in = norms_in; a.norms_out = norms_out; a.sym_out = sym_out; a.sym_in = sym_in;
+    a.seed_lo = (uint32_t)ctx->cfg.seed; a.seed_hi = (uint32_t)(ctx->cfg.seed >> 32); a.call_id = call_id;
+    a.norm_kind = ctx->cfg.norm;
+    if (mode != EncMode::QuantOnly) {
+        a.chunk_off = out->chunk_off; a.sub_end = out->sub_end; a.payload = out->payload;
+        a.cap_words = out->payload_words_per_worker;
+        a.scan_state = ctx->d_scan;
+        ctx->epoch = (ctx->epoch + 1u) & 0x3FFFFFFFu;
+        if (ctx->epoch == 0) ctx->epoch = 1;
+        a.epoch = ctx->epoch;
+        a.ticket_base = ctx->ticket_count;
+    }
+    QGX_HIP(ctx, launch_encode(mode, ctx->lay, ctx->d_tab, ctx->d_sc, a, (hipStream_t)stream));
+    if (mode != EncMode::QuantOnly) {
+        ctx->ticket_count += ctx->lay.K * ctx->lay.NB;
+        ctx->last_sub_end = out->sub_end;
+    }
+    return QGX_OK;
+}
+
+qgx_status qgx_quantize(qgx_ctx* ctx, const float* V, uint32_t call_id, const float* norms_in, float* norms_out,
+                        uint8_t* sym, void* stream)
+{
+    if (!ctx || !V || !norms_out || !sym) return fail(ctx, QGX_ERR_ARG, "qgx_quantize: null argument");
+    if (!aligned16(V) || !aligned16(sym) || !aligned16(norms_out) || !aligned16(norms_in))
+        return fail(ctx, QGX_ERR_ARG, "qgx_quantize: buffers must be 16-byte aligned");
+    return run_encode(ctx, EncMode::QuantOnly, V, call_id, norms_in, norms_out, sym, nullptr, nullptr, stream);
+}
+
+qgx_status qgx_encode(qgx_ctx* ctx, const float* norms, const uint8_t* sym, qgx_stream* out, void* stream)
+{
+    if (!ctx || !norms || !sym) return fail(ctx, QGX_ERR_ARG, "qgx_encode: null argument");
+    qgx_status s = check_stream(ctx, out, "qgx_encode");
+    if (s != QGX_OK) return s;
+    if (!aligned16(sym)) return fail(ctx, QGX_ERR_ARG, "qgx_encode: sym must be 16-byte aligned");
+    if (norms != out->norms)
+        QGX_HIP(ctx, hipMemcpyAsync(out->norms, norms, (size_t)ctx->lay.K * ctx->lay.NB * sizeof(float),
+                                    hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    return run_encode(ctx, EncMode::EncodeOnly, nullptr, 0, nullptr, nullptr, nullptr, sym, out, stream);
+}
+
+qgx_status qgx_quantize_encode(qgx_ctx* ctx, const float* V, uint32_t call_id, const float* norms_in, qgx_stream* out,
+                               void* stream)
+{
+    if (!ctx || !V) return fail(ctx, QGX_ERR_ARG, "qgx_quantize_encode: null argument");
+    qgx_status s = check_stream(ctx, out, "qgx_quantize_encode");
+    if (s != QGX_OK) return s;
+    if (!aligned16(V) || !aligned16(norms_in)) return fail(ctx, QGX_ERR_ARG, "qgx_quantize_encode: V must be 16-byte aligned");
+    return run_encode(ctx, EncMode::Fused, V, call_id, norms_in, out->norms, nullptr, nullptr, out, stream);
+}
+
+static void fill_decode_args(DecodeArgs& a, const qgx_stream* cur, const qgx_stream* prev)
+{
+    a.norms = cur->norms; a.chunk_off = cur->chunk_off; a.sub_end = cur->sub_end; a.payload = cur->payload;
+    a.cap_words = cur->payload_words_per_worker;
+    if (prev) {
+        a.norms_p = prev->norms; a.chunk_off_p = prev->chunk_off; a.sub_end_p = prev->sub_end;
+        a.payload_p = prev->payload; a.cap_words_p = prev->payload_words_per_worker;
+    }
+}
+
+qgx_status qgx_decode(qgx_ctx* ctx, const qgx_stream* in, float* Vhat, void* stream)
+{
+    if (!ctx || !Vhat) return fail(ctx, QGX_ERR_ARG, "qgx_decode: null argument");
+    qgx_status s = check_stream(ctx, in, "qgx_decode");
+    if (s == QGX_OK) s = need_levels(ctx);
+    if (s != QGX_OK) return s;
+    DecodeArgs a{};
+    fill_decode_args(a, in, nullptr);
+    a.out = Vhat;
+    QGX_HIP(ctx, launch_decode(DecMode::Decode, ctx->lay, ctx->d_tab, ctx->d_sc, a, (hipStream_t)stream));
+    return QGX_OK;
+}
+
+qgx_status qgx_decode_average(qgx_ctx* ctx, const qgx_stream* in, float* mean, void* stream)
+{
+    if (!ctx || !mean || !aligned16(mean)) return fail(ctx, QGX_ERR_ARG, "qgx_decode_average: mean null or misaligned");
+    qgx_status s = check_stream(ctx, in, "qgx_decode_average");
+    if (s == QGX_OK) s = need_levels(ctx);
+    if (s != QGX_OK) return s;
+    DecodeArgs a{};
+    fill_decode_args(a, in, nullptr);
+    a.out = mean;
+    QGX_HIP(ctx, launch_decode(DecMode::Average, ctx->lay, ctx->d_tab, ctx->d_sc, a, (hipStream_t)stream));
+    return QGX_OK;
+}
+
+qgx_status qgx_fit_levels(qgx_ctx* ctx, const float* V, uint32_t n_sym, uint32_t n_bins, uint32_t sweeps,
+                          double* hist_out, void* stream)
+{
+    if (!ctx || !V || !aligned16(V)) return fail(ctx, QGX_ERR_ARG, "qgx_fit_levels: V null or misaligned");
+    if (!ctx->levels_set) return fail(ctx, QGX_ERR_STATE, "qgx_fit_levels starts from the current table: set one first");
+    if (n_sym != ctx->n_sym) return fail(ctx, QGX_ERR_ARG, "qgx_fit_levels: n_sym differs from the current table");
+    if (n_bins == 0 || (n_bins & 63u) || n_bins > QGX_MAX_BINS)
+        return fail(ctx, QGX_ERR_ARG, "qgx_fit_levels: n_bins must be a multiple of 64, at most 4096");
+    hipStream_t st = (hipStream_t)stream;
+    QGX_HIP(ctx, launch_histogram(ctx->lay, V, ctx->cfg.norm, n_bins, ctx->d_hpartial, ctx->h_groups, ctx->d_hist,
+                                  ctx->d_sc, st));
+    if (hist_out)
+        QGX_HIP(ctx, hipMemcpyAsync(hist_out, ctx->d_hist, n_bins * sizeof(double), hipMemcpyDeviceToDevice, st));
+    QGX_HIP(ctx, launch_fit(ctx->d_tab, ctx->d_hist, n_bins, sweeps, st));
+    return QGX_OK;
+}
+
+qgx_status qgx_state_init(qgx_ctx* ctx, const float* X1, void* stream)
+{
+    if (!ctx || !aligned16(X1)) return fail(ctx, QGX_ERR_ARG, "qgx_state_init: null context or misaligned X1");
+    QGX_HIP(ctx, launch_state_init(ctx->lay, ctx->d_sc, ctx->d_Y, ctx->d_anchor, X1, (hipStream_t)stream));
+    ctx->has_anchor = X1 != nullptr;
+    ctx->state_ready = true;
+    return QGX_OK;
+}
+
+qgx_status qgx_eg_step(qgx_ctx* ctx, int half, const qgx_stream* cur, const qgx_stream* prev, float* X_out,
+                       void* stream)
+{
+    if (!ctx || (half != 0 && half != 1)) return fail(ctx, QGX_ERR_ARG, "qgx_eg_step: half must be 0 or 1");
+    if (!ctx->state_ready) return fail(ctx, QGX_ERR_STATE, "qgx_eg_step before qgx_state_init");
+    qgx_status s = check_stream(ctx, cur, "qgx_eg_step(cur)");
+    if (s == QGX_OK && prev) s = check_stream(ctx, prev, "qgx_eg_step(prev)");
+    if (s == QGX_OK) s = need_levels(ctx);
+    if (s != QGX_OK) return s;
+    if (!aligned16(X_out)) return fail(ctx, QGX_ERR_ARG, "qgx_eg_step: X_out misaligned");
+    hipStream_t st = (hipStream_t)stream;
+    DecodeArgs a{};
+    a.Y = ctx->d_Y;
+    a.anchor = ctx->has_anchor ? ctx->d_anchor : nullptr;
+    if (half == 0) {
+        if (prev) return fail(ctx, QGX_ERR_ARG, "qgx_eg_step: prev must be NULL for half = 0");
+        if (!X_out) return fail(ctx, QGX_ERR_ARG, "qgx_eg_step: X_out is required for half = 0");
+        fill_decode_args(a, cur, nullptr);
+        a.out = X_out;
+        QGX_HIP(ctx, launch_decode(DecMode::Half0, ctx->lay, ctx->d_tab, ctx->d_sc, a, st));
+        return QGX_OK;
+    }
+    fill_decode_args(a, cur, prev);
+    a.s_partial = ctx->d_spartial;
+    QGX_HIP(ctx, launch_decode(DecMode::Half1, ctx->lay, ctx->d_tab, ctx->d_sc, a, st));
+    QGX_HIP(ctx, launch_finish_half1(ctx->lay, ctx->d_sc, ctx->d_spartial, ctx->d_Y, a.anchor, X_out, st));
+    return QGX_OK;
+}
+
+qgx_status qgx_get_scalars(qgx_ctx* ctx, double* S, double* gamma, uint64_t* t, uint64_t* total_bits, void* stream)
+{
+    if (!ctx) return QGX_ERR_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if (total_bits) {
+        if (!ctx->last_sub_end) return fail(ctx, QGX_ERR_STATE, "no coding call yet");
+        QGX_HIP(ctx, launch_sum_bits(ctx->lay, ctx->last_sub_end, ctx->d_sc, st));
+    }
+    Scalars h;
+    QGX_HIP(ctx, hipMemcpyAsync(&h, ctx->d_sc, sizeof(h), hipMemcpyDeviceToHost, st));
+    QGX_HIP(ctx, hipStreamSynchronize(st));
+    if (S) *S = h.S;
+    if (gamma) *gamma = h.gamma;
+    if (t) *t = h.t;
+    if (total_bits) *total_bits = h.total_bits;
+    return QGX_OK;
+}
+
+qgx_status qgx_state_export(qgx_ctx* ctx, float* Y, float* anchor, void* stream)
+{
+    if (!ctx) return QGX_ERR_ARG;
+    if (!ctx->state_ready) return fail(ctx, QGX_ERR_STATE, "state not initialised");
+    hipStream_t st = (hipStream_t)stream;
+    const size_t bytes = (size_t)ctx->lay.d * sizeof(float);
+    if (Y) QGX_HIP(ctx, hipMemcpyAsync(Y, ctx->d_Y, bytes, hipMemcpyDeviceToDevice, st));
+    if (anchor) QGX_HIP(ctx, hipMemcpyAsync(anchor, ctx->d_anchor, bytes, hipMemcpyDeviceToDevice, st));
+    return QGX_OK;
+}
+
+qgx_status qgx_state_import(qgx_ctx* ctx, const float* Y, const float* anchor, double S, uint64_t t, void* stream)
+{
+    if (!ctx) return QGX_ERR_ARG;
+    if (!(S >= 0.0) || t == 0) return fail(ctx, QGX_ERR_ARG, "qgx_state_import: S must be >= 0 and t >= 1");
+    hipStream_t st = (hipStream_t)stream;
+    const size_t bytes = (size_t)ctx->lay.d * sizeof(float);
+    if (!ctx->state_ready) {
+        QGX_HIP(ctx, launch_state_init(ctx->lay, ctx->d_sc, ctx->d_Y, ctx->d_anchor, nullptr, st));
+        ctx->state_ready = true;
+    }
+    if (Y) QGX_HIP(ctx, hipMemcpyAsync(ctx->d_Y, Y, bytes, hipMemcpyDeviceToDevice, st));
+    if (anchor) {
+        QGX_HIP(ctx, hipMemcpyAsync(ctx->d_anchor, anchor, bytes, hipMemcpyDeviceToDevice, st));
+        ctx->has_anchor = true;
+    }
+    QGX_HIP(ctx, launch_state_set(ctx->d_sc, S, t, ctx->lay.K, st));
+    return QGX_OK;
+}
+
+uint32_t qgx_poll_error(qgx_ctx* ctx, void* stream)
+{
+    if (!ctx) return 0;
+    hipStream_t st = (hipStream_t)stream;
+    uint32_t e = 0;
+    const uint32_t zero = 0;
+    if (hipMemcpyAsync(&e, &ctx->d_sc->err, sizeof(e), hipMemcpyDeviceToHost, st) != hipSuccess) return QGX_EBIT_STATE;
+    if (hipStreamSynchronize(st) != hipSuccess) return QGX_EBIT_STATE;
+    if (e) {
+        (void)hipMemcpyAsync(&ctx->d_sc->err, &zero, sizeof(zero), hipMemcpyHostToDevice, st);
+        (void)hipStreamSynchronize(st);
+    }
+    return e;
+}
+
+const char* qgx_last_error(const qgx_ctx* ctx) { return ctx ? ctx->err : "null context"; }
+
+}  // extern "C"

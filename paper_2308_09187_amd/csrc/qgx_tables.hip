@@ -1,0 +1,80 @@
+// Derived device tables: level pairs for the rounding step, the tau lookup cells, the code words of
+// Psi and the 13-bit decode table.  Rebuilt on the device whenever the level table or the code
+// changes, so that a refit never goes through the host.
+#include "qgx_device.h"
+
+namespace qgx {
+
+// Elias' recursive (omega) code of N >= 1 (Appendix J, "Elias recursive coding"), returned with the
+// first-written bit in bit 0: write "0", then while N > 1 prepend binary(N) and continue with the
+// number of bits of N minus one.
+__device__ inline uint32_t elias_omega(uint32_t N, uint32_t* len_out)
+{
+    uint32_t bits = 0, len = 1;
+    while (N > 1) {
+        const uint32_t nb = 32u - (uint32_t)__clz((int)N);
+        const uint32_t rev = __brev(N) >> (32u - nb);   // most significant bit of the group first
+        bits = rev | (bits << nb);
+        len += nb;
+        N = nb - 1;
+    }
+    *len_out = len;
+    return bits;
+}
+
+__device__ void build_tables_block(Tables* tab)
+{
+    const uint32_t n_sym = tab->n_sym;
+    const int tid = (int)threadIdx.x, nt = (int)blockDim.x;
+    const float* lv = tab->levels;
+    const float inf = __uint_as_float(0x7f800000u);
+
+    for (int j = tid; j < kSymMax; j += nt) {
+        float4 e = make_float4(1.0f, 0.0f, inf, 0.0f);
+        float l = 1.0f;
+        if ((uint32_t)j < n_sym) l = lv[j];
+        if ((uint32_t)j + 1 < n_sym) {
+            const float g = lv[j + 1] - lv[j];
+            e = make_float4(lv[j], g * 0x1p-24f, ((uint32_t)j + 2 < n_sym) ? lv[j + 1] : inf, 0.0f);
+        }
+        tab->lev[j] = e;
+        tab->lval[j] = l;
+    }
+    for (int c = tid; c < kCellsPad; c += nt) {
+        uint32_t j = 0;
+        if (c > 0 && c < kCells) {
+            const float edge = __uint_as_float((uint32_t)(c + kCellKey0) << (23 - kCellMant));
+            while (j + 2 < n_sym && lv[j + 1] <= edge) ++j;
+        }
+        tab->cell[c] = (uint8_t)j;
+    }
+    if (tab->code_kind == QGX_CODE_ELIAS_OMEGA) {
+        for (int j = tid; j < kSymMax; j += nt) {
+            uint32_t len = 0, bits = 0;
+            if ((uint32_t)j < n_sym) bits = elias_omega((uint32_t)j + 1u, &len);
+            tab->code[j] = bits | (len << 16);
+        }
+    }
+    for (int i = tid; i < kDlut; i += nt) tab->dlut[i] = 0xFFFFu;
+    __syncthreads();
+    // every 13-bit window that starts with code word j decodes to j
+    for (uint32_t j = 0; j < n_sym; ++j) {
+        const uint32_t cw = tab->code[j];
+        const uint32_t len = cw >> 16, bits = cw & 0xFFFFu;
+        if (len == 0 || len > (uint32_t)kMaxCode) continue;
+        const uint32_t reps = 1u << (kDlutBits - len);
+        for (uint32_t s = (uint32_t)tid; s < reps; s += (uint32_t)nt)
+            tab->dlut[bits | (s << len)] = (uint16_t)((j << 4) | len);
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(256) void k_build_tables(Tables* tab) { build_tables_block(tab); }
+
+hipError_t launch_build_tables(Tables* tab, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_build_tables, dim3(1), dim3(256), 0, st, tab);
+    return hipGetLastError();
+}
+
+}  // namespace qgx

@@ -1,0 +1,223 @@
+"""Thin ctypes binding over libqgx.so (include/qgx.h): argument marshalling only.
+
+Every step of the path runs in the library's gfx950 kernels; torch is used for device memory and
+streams.  Loading fails loudly when the library has not been built
+(``python -m paper_2308_09187_amd.build``); there is no fallback of any kind.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqgx.so")
+
+OK = 0
+ERR_ARG, ERR_LEVELS, ERR_CAPACITY, ERR_STREAM, ERR_NONFINITE, ERR_HIP, ERR_STATE = -1, -2, -3, -4, -5, -6, -7
+EBIT_CAPACITY, EBIT_STREAM, EBIT_NONFINITE, EBIT_STATE = 1, 2, 4, 8
+NORM_LINF, NORM_L2 = 0, 2
+CODE_ELIAS_OMEGA, CODE_TABLE = 0, 1
+CHUNK, SUB, MAX_SYM, MAX_BINS = 4096, 64, 127, 4096
+
+EXPORTS = [
+    "qgx_create", "qgx_destroy", "qgx_stream_sizes", "qgx_set_levels", "qgx_get_levels", "qgx_set_code_table",
+    "qgx_quantize", "qgx_encode", "qgx_quantize_encode", "qgx_decode", "qgx_decode_average", "qgx_fit_levels",
+    "qgx_state_init", "qgx_eg_step", "qgx_get_scalars", "qgx_state_export", "qgx_state_import",
+    "qgx_poll_error", "qgx_last_error",
+]
+
+
+class QgxError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__("qgx status %d: %s" % (status, text))
+        self.status = status
+
+
+class _Config(C.Structure):
+    _fields_ = [("d", C.c_uint64), ("K", C.c_uint32), ("bucket", C.c_uint32), ("n_segments", C.c_uint32),
+                ("segment_len", C.POINTER(C.c_uint64)), ("norm", C.c_int32), ("code", C.c_int32),
+                ("seed", C.c_uint64)]
+
+
+class _Stream(C.Structure):
+    _fields_ = [("norms", C.c_void_p), ("chunk_off", C.c_void_p), ("sub_end", C.c_void_p),
+                ("payload", C.c_void_p), ("payload_words_per_worker", C.c_uint64)]
+
+
+_lib = None
+
+
+def load():
+    """Loads libqgx.so; raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libqgx.so is not built: run `python -m paper_2308_09187_amd.build` "
+                              "(hipcc, gfx950); there is no fallback path")
+        lib = C.CDLL(LIB_PATH)
+        for name in EXPORTS:
+            getattr(lib, name)
+        lib.qgx_destroy.restype = None
+        lib.qgx_poll_error.restype = C.c_uint32
+        lib.qgx_last_error.restype = C.c_char_p
+        _lib = lib
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream_handle(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+class Stream:
+    """Device buffers of one CODE o Q result for K workers."""
+
+    def __init__(self, K, NB, NC, cap_words, device="cuda"):
+        cap_words = (int(cap_words) + 3) // 4 * 4
+        self.norms = torch.zeros((K, NB), dtype=torch.float32, device=device)
+        self.chunk_off = torch.zeros((K, NC + 1), dtype=torch.int32, device=device)
+        self.sub_end = torch.zeros((K, NC, 64), dtype=torch.int16, device=device)
+        self.payload = torch.zeros((K, cap_words), dtype=torch.int32, device=device)
+        self.cap_words = cap_words
+
+    def c_struct(self):
+        return _Stream(self.norms.data_ptr(), self.chunk_off.data_ptr(), self.sub_end.data_ptr(),
+                       self.payload.data_ptr(), self.cap_words)
+
+    def to_host(self):
+        """numpy views in the container's unsigned types."""
+        return dict(norms=self.norms.cpu().numpy(),
+                    chunk_off=self.chunk_off.cpu().numpy().view(np.uint32),
+                    sub_end=self.sub_end.cpu().numpy().view(np.uint16),
+                    payload=self.payload.cpu().numpy().view(np.uint32))
+
+
+class Context:
+    def __init__(self, d, K, bucket, norm=NORM_L2, code=CODE_ELIAS_OMEGA, seed=0, segment_len=None, device="cuda"):
+        self.lib = load()
+        self.d, self.K, self.bucket, self.device = int(d), int(K), int(bucket), device
+        seg = None
+        nseg = 0
+        if segment_len is not None:
+            seg = (C.c_uint64 * len(segment_len))(*[int(x) for x in segment_len])
+            nseg = len(segment_len)
+        cfg = _Config(self.d, self.K, self.bucket, nseg, seg, norm, code, seed)
+        self._h = C.c_void_p()
+        with torch.cuda.device(device):
+            st = self.lib.qgx_create(C.byref(self._h), C.byref(cfg))
+        if st != OK:
+            raise QgxError(st, "qgx_create rejected the configuration")
+        nb, nc, ww = C.c_uint64(), C.c_uint64(), C.c_uint64()
+        self._check(self.lib.qgx_stream_sizes(self._h, C.byref(nb), C.byref(nc), C.byref(ww)))
+        self.NB, self.NC, self.worst_words = nb.value, nc.value, ww.value
+
+    def _check(self, st):
+        if st != OK:
+            raise QgxError(st, self.lib.qgx_last_error(self._h).decode())
+
+    def close(self):
+        if self._h:
+            self.lib.qgx_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def new_stream(self, cap_words=None):
+        return Stream(self.K, self.NB, self.NC, self.worst_words if cap_words is None else cap_words, self.device)
+
+    # -- tables ---------------------------------------------------------------------------------
+    def set_levels(self, levels, stream=None):
+        lv = np.ascontiguousarray(levels, dtype=np.float32)
+        self._check(self.lib.qgx_set_levels(self._h, lv.ctypes.data_as(C.c_void_p), C.c_uint32(len(lv)),
+                                            _stream_handle(stream)))
+
+    def get_levels(self, stream=None):
+        lv = np.zeros(MAX_SYM, np.float32)
+        n = C.c_uint32()
+        self._check(self.lib.qgx_get_levels(self._h, lv.ctypes.data_as(C.c_void_p), C.byref(n), _stream_handle(stream)))
+        return lv[: n.value].copy()
+
+    def set_code_table(self, code_len, code_bits, stream=None):
+        cl = np.ascontiguousarray(code_len, dtype=np.uint8)
+        cb = np.ascontiguousarray(code_bits, dtype=np.uint32)
+        self._check(self.lib.qgx_set_code_table(self._h, cl.ctypes.data_as(C.c_void_p), cb.ctypes.data_as(C.c_void_p),
+                                                C.c_uint32(len(cl)), _stream_handle(stream)))
+
+    # -- CODE o Q -------------------------------------------------------------------------------
+    def quantize(self, V, call_id, norms_in=None, stream=None):
+        norms = torch.empty((self.K, self.NB), dtype=torch.float32, device=V.device)
+        sym = torch.empty((self.K, self.d), dtype=torch.uint8, device=V.device)
+        self._check(self.lib.qgx_quantize(self._h, _ptr(V), C.c_uint32(call_id), _ptr(norms_in), _ptr(norms),
+                                          _ptr(sym), _stream_handle(stream)))
+        return norms, sym
+
+    def encode(self, norms, sym, out: Stream, stream=None):
+        s = out.c_struct()
+        self._check(self.lib.qgx_encode(self._h, _ptr(norms), _ptr(sym), C.byref(s), _stream_handle(stream)))
+        return out
+
+    def quantize_encode(self, V, call_id, out: Stream, norms_in=None, stream=None):
+        s = out.c_struct()
+        self._check(self.lib.qgx_quantize_encode(self._h, _ptr(V), C.c_uint32(call_id), _ptr(norms_in), C.byref(s),
+                                                 _stream_handle(stream)))
+        return out
+
+    # -- DEQ o CODE and the fused updates ---------------------------------------------------------
+    def decode(self, st: Stream, out=None, stream=None):
+        if out is None:
+            out = torch.empty((self.K, self.d), dtype=torch.float32, device=st.payload.device)
+        s = st.c_struct()
+        self._check(self.lib.qgx_decode(self._h, C.byref(s), _ptr(out), _stream_handle(stream)))
+        return out
+
+    def decode_average(self, st: Stream, out=None, stream=None):
+        if out is None:
+            out = torch.empty(self.d, dtype=torch.float32, device=st.payload.device)
+        s = st.c_struct()
+        self._check(self.lib.qgx_decode_average(self._h, C.byref(s), _ptr(out), _stream_handle(stream)))
+        return out
+
+    def fit_levels(self, V, n_sym, n_bins=4096, sweeps=10, hist_out=None, stream=None):
+        self._check(self.lib.qgx_fit_levels(self._h, _ptr(V), C.c_uint32(n_sym), C.c_uint32(n_bins),
+                                            C.c_uint32(sweeps), _ptr(hist_out), _stream_handle(stream)))
+
+    def state_init(self, X1=None, stream=None):
+        self._check(self.lib.qgx_state_init(self._h, _ptr(X1), _stream_handle(stream)))
+
+    def eg_step(self, half, cur: Stream, prev: Stream = None, X_out=None, stream=None):
+        c = cur.c_struct()
+        p = prev.c_struct() if prev is not None else None
+        self._check(self.lib.qgx_eg_step(self._h, C.c_int(half), C.byref(c), C.byref(p) if p is not None else None,
+                                         _ptr(X_out), _stream_handle(stream)))
+        return X_out
+
+    def scalars(self, want_bits=False, stream=None):
+        S, g, t, b = C.c_double(), C.c_double(), C.c_uint64(), C.c_uint64()
+        self._check(self.lib.qgx_get_scalars(self._h, C.byref(S), C.byref(g), C.byref(t),
+                                             C.byref(b) if want_bits else None, _stream_handle(stream)))
+        return dict(S=S.value, gamma=g.value, t=t.value, total_bits=b.value if want_bits else None)
+
+    def state_export(self, stream=None):
+        Y = torch.empty(self.d, dtype=torch.float32, device=self.device)
+        A = torch.empty(self.d, dtype=torch.float32, device=self.device)
+        self._check(self.lib.qgx_state_export(self._h, _ptr(Y), _ptr(A), _stream_handle(stream)))
+        return Y, A
+
+    def state_import(self, Y, anchor, S, t, stream=None):
+        self._check(self.lib.qgx_state_import(self._h, _ptr(Y), _ptr(anchor), C.c_double(S), C.c_uint64(t),
+                                              _stream_handle(stream)))
+
+    def poll_error(self, stream=None):
+        return int(self.lib.qgx_poll_error(self._h, _stream_handle(stream)))

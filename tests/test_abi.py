@@ -1,0 +1,65 @@
+"""The C-ABI library: it loads, exports every function include/qgx.h declares, and rejects bad
+configurations on the host before anything touches a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2308_09187_amd", "libqgx.so")
+HEADER = os.path.join(ROOT, "include", "qgx.h")
+
+
+def _lib():
+    if not os.path.exists(LIB):
+        from paper_2308_09187_amd import build
+        build.build()
+    return C.CDLL(LIB)
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qgx_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_function_is_exported():
+    lib = _lib()
+    names = _declared()
+    assert len(names) >= 19
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_lists_the_same_functions():
+    from paper_2308_09187_amd import qgx
+    assert sorted(qgx.EXPORTS) == _declared()
+
+
+def test_create_rejects_bad_configurations_on_the_host():
+    from paper_2308_09187_amd.qgx import _Config
+    lib = _lib()
+    h = C.c_void_p()
+
+    def create(**kw):
+        base = dict(d=1024, K=2, bucket=256, n_segments=0, segment_len=None, norm=2, code=0, seed=1)
+        base.update(kw)
+        cfg = _Config(**base)
+        return lib.qgx_create(C.byref(h), C.byref(cfg))
+
+    assert create(d=0) == -1
+    assert create(d=1 << 31) == -1
+    assert create(K=0) == -1
+    assert create(bucket=0) == -1
+    assert create(bucket=250) == -1            # not a multiple of 4
+    assert create(bucket=1 << 17) == -1        # above the largest bucket
+    assert create(norm=3) == -1
+    assert create(code=7) == -1
+    seg = (C.c_uint64 * 2)(1000, 25)           # does not sum to d
+    assert create(n_segments=2, segment_len=seg) == -1
+    seg = (C.c_uint64 * 2)(1022, 2)            # inner segment not a multiple of 4
+    assert create(n_segments=2, segment_len=seg) == -1
+    assert lib.qgx_create(None, None) == -1
+    lib.qgx_last_error.restype = C.c_char_p
+    assert lib.qgx_last_error(None) == b"null context"

@@ -1,0 +1,412 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Bit-exact for symbols, signs, the bit stream and its tables (given the same norms and the
+same Philox stream); <= 1e-6 relative for norms, decoded means and iterates."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle
+from paper_2308_09187_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+REL = 1e-6      # tolerance named by the task for floating-point results
+
+
+@pytest.fixture(scope="module")
+def qgx():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2308_09187_amd import qgx as m
+    m.load()
+    return m
+
+
+def rel_err(a, b):
+    a = np.asarray(a, np.float64); b = np.asarray(b, np.float64)
+    nb = np.linalg.norm(b)
+    return np.linalg.norm(a - b) / (nb if nb > 0 else 1.0)
+
+
+def dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def make_ctx(qgx, d, K, bucket, norm, levels, seed=7, segs=None, code=0):
+    ctx = qgx.Context(d, K, bucket, norm=norm, code=code, seed=seed, segment_len=segs)
+    ctx.set_levels(levels)
+    lay = oracle.layout(d, bucket, segs)
+    assert (ctx.NB, ctx.NC) == (lay.NB, lay.NC)
+    return ctx, lay
+
+
+def oracle_stream(V, lay, norm, levels, seed, call, norms_gpu, cap):
+    n, idx, neg, bad = oracle.quantize(V, lay, norm, levels, seed, call, norms_in=norms_gpu)
+    st = oracle.encode(idx, neg, lay, cap)
+    return n, idx, neg, st
+
+
+def assert_stream_equal(h, st, lay):
+    """h: host copy of the GPU stream; st: oracle Stream."""
+    np.testing.assert_array_equal(h["chunk_off"], st.chunk_off)
+    np.testing.assert_array_equal(h["sub_end"], st.sub_end)
+    for k in range(st.payload.shape[0]):
+        used = int(st.chunk_off[k, lay.NC])
+        np.testing.assert_array_equal(h["payload"][k, :used], st.payload[k, :used])
+
+
+CASES = [
+    # d, K, bucket, norm, table, segments
+    (3 * 4096 + 1000, 3, 8192, oracle.NORM_L2, "exp16", None),       # several tiles and a ragged tail
+    (20000, 2, 16384, oracle.NORM_L2, "uni16", None),
+    (9000, 4, 4096, oracle.NORM_LINF, "exp16", None),
+    (1024, 4, 1024, oracle.NORM_L2, "exp8", None),                   # workload 1 shape
+    (10 * 1024 + 64 + 128 + 4, 2, 2048, oracle.NORM_LINF, "exp16", [5 * 1024, 64, 128, 5 * 1024, 4]),
+    (70000, 1, 65536, oracle.NORM_L2, "fine", None),                 # largest bucket, 127 symbols
+]
+
+
+def table(name):
+    return {"exp16": synth.levels_exponential(16), "uni16": synth.levels_uniform(16),
+            "exp8": synth.levels_exponential(8), "fine": np.linspace(0, 1, 127).astype(np.float32)}[name]
+
+
+@pytest.mark.parametrize("d,K,bucket,norm,tab,segs", CASES)
+def test_quantize_encode_decode_parity(qgx, d, K, bucket, norm, tab, segs):
+    print("case", d, K, bucket, norm, tab, flush=True)
+    levels = table(tab)
+    seed, call = 1234567, 5
+    ctx, lay = make_ctx(qgx, d, K, bucket, norm, levels, seed, segs)
+    V = synth.student_t3(K, d, seed=2)
+    Vd = dev(V)
+
+    # Q: norms to 1e-6, symbols and signs bit-exact given the GPU's norms
+    norms_g, sym_g = ctx.quantize(Vd, call)
+    norms_g, sym_g = norms_g.cpu().numpy(), sym_g.cpu().numpy()
+    n_o, _, _, _ = oracle.quantize(V, lay, norm, levels, seed, call)
+    assert np.max(np.abs(norms_g - n_o) / n_o) <= REL
+    if norm == oracle.NORM_LINF:
+        np.testing.assert_array_equal(norms_g, n_o)
+    cap = ctx.worst_words
+    _, idx_o, neg_o, st_o = oracle_stream(V, lay, norm, levels, seed, call, norms_g, cap)
+    np.testing.assert_array_equal(sym_g & 0x7F, idx_o)
+    np.testing.assert_array_equal(sym_g >> 7, neg_o)
+
+    # CODE o Q fused: stream, offset table and sub-chunk table byte for byte
+    out = ctx.new_stream()
+    ctx.quantize_encode(Vd, call, out)
+    h = out.to_host()
+    np.testing.assert_array_equal(h["norms"], norms_g)
+    assert_stream_equal(h, st_o, lay)
+    assert ctx.scalars(want_bits=True)["total_bits"] == int(st_o.total_bits.sum())
+
+    # CODE from stored symbols gives the same stream
+    out2 = ctx.new_stream()
+    ctx.encode(dev(norms_g), dev(sym_g), out2)
+    assert_stream_equal(out2.to_host(), st_o, lay)
+
+    # DEQ o CODE: one binary32 product per coordinate => exact
+    Vhat_o, _, _ = oracle.decode(st_o, norms_g, lay, levels)
+    Vhat_g = ctx.decode(out).cpu().numpy()
+    np.testing.assert_array_equal(Vhat_g, Vhat_o)
+
+    # aggregate
+    mean_g = ctx.decode_average(out).cpu().numpy()
+    assert rel_err(mean_g, oracle.mean(Vhat_o)) <= REL
+    assert ctx.poll_error() == 0
+
+    # determinism: the same call again gives the same bytes
+    out3 = ctx.new_stream()
+    ctx.quantize_encode(Vd, call, out3)
+    h3 = out3.to_host()
+    for key in ("chunk_off", "sub_end", "payload", "norms"):
+        np.testing.assert_array_equal(h3[key], h[key])
+    # and another call_id gives another draw
+    ctx.quantize_encode(Vd, call + 1, out3)
+    assert not np.array_equal(out3.to_host()["payload"], h["payload"])
+    ctx.close()
+
+
+def test_norms_in_override_and_unaligned_worker_stride(qgx):
+    """d not a multiple of 4 puts workers 1.. on unaligned rows; norms_in replaces the norm."""
+    d, K, bucket = 4096 + 513, 3, 2048
+    levels = synth.levels_exponential(16)
+    ctx, lay = make_ctx(qgx, d, K, bucket, oracle.NORM_L2, levels, seed=3)
+    V = synth.student_t3(K, d, seed=9)
+    norms_in = (np.abs(V).max() * 1.5 * np.ones((K, lay.NB))).astype(np.float32)
+    out = ctx.new_stream()
+    ctx.quantize_encode(dev(V), 0, out, norms_in=dev(norms_in))
+    h = out.to_host()
+    np.testing.assert_array_equal(h["norms"], norms_in)
+    _, _, _, st_o = oracle_stream(V, lay, oracle.NORM_L2, levels, 3, 0, norms_in, ctx.worst_words)
+    assert_stream_equal(h, st_o, lay)
+    Vhat_o, _, _ = oracle.decode(st_o, norms_in, lay, levels)
+    np.testing.assert_array_equal(ctx.decode(out).cpu().numpy(), Vhat_o)
+    assert ctx.poll_error() == 0
+    ctx.close()
+
+
+@pytest.mark.parametrize("d", [1, 3, 4, 7, 63, 64, 65, 255, 257])
+def test_tiny_vectors(qgx, d):
+    levels = synth.levels_uniform(4)
+    ctx, lay = make_ctx(qgx, d, 2, 64, oracle.NORM_LINF, levels, seed=11)
+    V = synth.student_t3(2, d, seed=d)
+    out = ctx.new_stream()
+    ctx.quantize_encode(dev(V), 1, out)
+    h = out.to_host()
+    _, _, _, st_o = oracle_stream(V, lay, oracle.NORM_LINF, levels, 11, 1, h["norms"], ctx.worst_words)
+    assert_stream_equal(h, st_o, lay)
+    Vhat_o, _, _ = oracle.decode(st_o, h["norms"], lay, levels)
+    np.testing.assert_array_equal(ctx.decode(out).cpu().numpy(), Vhat_o)
+    assert rel_err(ctx.decode_average(out).cpu().numpy(), oracle.mean(Vhat_o)) <= REL
+    assert ctx.poll_error() == 0
+    ctx.close()
+
+
+def test_degenerate_inputs_and_error_word(qgx):
+    d, K, bucket = 8192, 2, 4096
+    levels = synth.levels_exponential(8)
+    ctx, lay = make_ctx(qgx, d, K, bucket, oracle.NORM_L2, levels, seed=1)
+    # zero vector: norm 0, all symbols 0, one bit per coordinate, decodes to zeros
+    out = ctx.new_stream()
+    ctx.quantize_encode(torch.zeros((K, d), device="cuda"), 0, out)
+    h = out.to_host()
+    assert not h["norms"].any()
+    assert (h["sub_end"][:, :, 63] == 4096).all()
+    assert not ctx.decode(out).cpu().numpy().any()
+    assert ctx.poll_error() == 0
+    # a non-finite coordinate: its bucket is coded as zeros with norm 0 and the error bit is raised
+    V = synth.student_t3(K, d, seed=4)
+    for poison in (np.nan, np.inf, -np.inf):
+        Vp = V.copy(); Vp[1, 5000] = poison
+        ctx.quantize_encode(dev(Vp), 0, out)
+        assert ctx.poll_error() == qgx.EBIT_NONFINITE
+        h = out.to_host()
+        n_o, idx_o, neg_o, bad = oracle.quantize(Vp, lay, oracle.NORM_L2, levels, 1, 0)
+        assert bad == 1 and h["norms"][1, 1] == 0.0 and n_o[1, 1] == 0.0
+        st_o = oracle.encode(idx_o, neg_o, lay, ctx.worst_words)
+        _, _, _, st_o = oracle_stream(Vp, lay, oracle.NORM_L2, levels, 1, 0, h["norms"], ctx.worst_words)
+        assert_stream_equal(h, st_o, lay)
+        assert ctx.poll_error() == 0           # the word was cleared by the poll
+    # capacity: a payload that is too small raises the capacity bit and writes nothing out of bounds
+    small = ctx.new_stream(cap_words=64)
+    guard = small.payload.clone()
+    ctx.quantize_encode(dev(V), 0, small)
+    assert ctx.poll_error() & qgx.EBIT_CAPACITY
+    assert small.payload.shape == guard.shape
+    # host-side argument errors
+    with pytest.raises(qgx.QgxError) as e:
+        ctx.set_levels([0, 0.5, 0.4, 1])
+    assert e.value.status == qgx.ERR_LEVELS
+    with pytest.raises(qgx.QgxError) as e:
+        ctx.set_levels([0.1, 0.5, 1])
+    assert e.value.status == qgx.ERR_LEVELS
+    with pytest.raises(qgx.QgxError) as e:
+        ctx.eg_step(0, out, None, torch.empty(d, device="cuda"))
+    assert e.value.status == qgx.ERR_STATE         # state not initialised
+    ctx.close()
+    c2 = qgx.Context(d, K, bucket)
+    with pytest.raises(qgx.QgxError) as e:
+        c2.quantize_encode(dev(V), 0, c2.new_stream())
+    assert e.value.status == qgx.ERR_STATE         # no level table yet
+    c2.close()
+
+
+def test_malformed_stream_sets_error_bit(qgx):
+    d, K = 8192, 1
+    levels = synth.levels_exponential(8)            # 9 symbols: many 13-bit windows are not code words
+    ctx, lay = make_ctx(qgx, d, K, 4096, oracle.NORM_L2, levels, seed=1)
+    out = ctx.new_stream()
+    ctx.quantize_encode(dev(synth.student_t3(K, d, seed=4)), 0, out)
+    out.payload[0, 3] ^= 0x00F0F000                 # corrupt some bits
+    ctx.decode(out)
+    assert ctx.poll_error() & qgx.EBIT_STREAM
+    out.chunk_off[0, 1] = 7                         # inconsistent offset table
+    ctx.decode(out)
+    assert ctx.poll_error() & qgx.EBIT_STREAM
+    ctx.close()
+
+
+def test_table_code(qgx):
+    """A caller-supplied prefix code (fixed 4-bit words) through the same kernels."""
+    d, K = 3 * 4096 + 5, 2
+    levels = synth.levels_uniform(15)               # 16 symbols
+    code_len = np.full(16, 4, np.uint8)
+    code_bits = np.array([int(format(j, "04b")[::-1], 2) for j in range(16)], np.uint32)
+    ctx = qgx.Context(d, K, 8192, norm=oracle.NORM_LINF, code=qgx.CODE_TABLE, seed=5)
+    ctx.set_levels(levels)
+    ctx.set_code_table(code_len, code_bits)
+    lay = oracle.layout(d, 8192)
+    V = synth.student_t3(K, d, seed=6)
+    out = ctx.new_stream()
+    ctx.quantize_encode(dev(V), 2, out)
+    h = out.to_host()
+    n, idx, neg, _ = oracle.quantize(V, lay, oracle.NORM_LINF, levels, 5, 2, norms_in=h["norms"])
+    st_o = oracle.encode(idx, neg, lay, ctx.worst_words, code_len=code_len, code_bits=code_bits)
+    assert_stream_equal(h, st_o, lay)
+    Vhat_o, _, _ = oracle.decode(st_o, h["norms"], lay, levels, code_len=code_len, code_bits=code_bits)
+    np.testing.assert_array_equal(ctx.decode(out).cpu().numpy(), Vhat_o)
+    with pytest.raises(qgx.QgxError):               # not prefix-free
+        ctx.set_code_table(np.array([1] + [4] * 15, np.uint8), code_bits)
+    assert ctx.poll_error() == 0
+    ctx.close()
+
+
+def run_lockstep(qgx, game, levels, norm, bucket, T, seed, anchor, refit=None, n_bins=4096):
+    """Q-GenX iterations in lock-step: every half-step the oracle consumes the GPU's dual vectors and
+    norms, keeps its own binary64 state, and every result is compared."""
+    d, K = game.d, game.K
+    ctx, lay = make_ctx(qgx, d, K, bucket, norm, levels, seed)
+    x1 = game.x1() if anchor else None
+    ctx.state_init(dev(x1) if anchor else None)
+    st = oracle.EGState(d, K, X1=x1)
+    cur, prev = ctx.new_stream(), ctx.new_stream()
+    Xh = torch.empty(d, device="cuda"); Xn = torch.empty(d, device="cuda")
+    X = (x1 if anchor else np.zeros(d, np.float32)).astype(np.float32)
+    worst = 0.0
+    for t in range(T):
+        V0 = game.dual_vectors(X, 2 * t)
+        if refit and t % refit == 0:
+            ctx.fit_levels(dev(V0), len(levels), n_bins, sweeps=8)
+            levels = ctx.get_levels()              # the oracle follows the GPU's table (checked elsewhere)
+        ctx.quantize_encode(dev(V0), 2 * t, prev)
+        ctx.eg_step(0, prev, None, Xh)
+        hp = prev.to_host()
+        _, _, _, so = oracle_stream(V0, lay, norm, levels, seed, 2 * t, hp["norms"], ctx.worst_words)
+        assert_stream_equal(hp, so, lay)
+        Vhat0, _, _ = oracle.decode(so, hp["norms"], lay, levels)
+        Xh_o = st.half0(Vhat0)
+        worst = max(worst, rel_err(Xh.cpu().numpy(), Xh_o))
+        V1 = game.dual_vectors(Xh.cpu().numpy(), 2 * t + 1)
+        ctx.quantize_encode(dev(V1), 2 * t + 1, cur)
+        ctx.eg_step(1, cur, prev, Xn)
+        hc = cur.to_host()
+        _, _, _, so1 = oracle_stream(V1, lay, norm, levels, seed, 2 * t + 1, hc["norms"], ctx.worst_words)
+        assert_stream_equal(hc, so1, lay)
+        Vhat1, _, _ = oracle.decode(so1, hc["norms"], lay, levels)
+        Xn_o = st.half1(Vhat1, Vhat0)
+        sc = ctx.scalars()
+        assert abs(sc["S"] - st.S) <= REL * max(st.S, 1e-30)
+        assert abs(sc["gamma"] - st.gamma) <= REL * st.gamma
+        assert sc["t"] == st.t
+        worst = max(worst, rel_err(Xn.cpu().numpy(), Xn_o))
+        Y, _ = ctx.state_export()
+        worst = max(worst, rel_err(Y.cpu().numpy(), st.Y))
+        X = Xn.cpu().numpy()
+    assert ctx.poll_error() == 0
+    ctx.close()
+    return worst, st
+
+
+def test_bilinear_game_100_iterations_lockstep(qgx):
+    """Workload 1: x, y in R^512, K = 4, L2, bucket = whole vector, 8 exponential levels, 100 iterations."""
+    game = synth.BilinearGame(n=512, K=4, noise=0.1)
+    worst, st = run_lockstep(qgx, game, synth.levels_exponential(8), oracle.NORM_L2, 1024, 100, seed=99, anchor=True)
+    print("worst relative deviation over 100 iterations:", worst, "gamma_T:", st.gamma, flush=True)
+    assert worst <= REL
+    assert st.gamma < st.K
+
+
+def test_quadratic_game_lockstep_with_refit(qgx):
+    """Workload 5 in small: d = 2^15, K = 3, bucket 8192, fitted 17-symbol table refitted every 3
+    iterations, X_1 = 0 (no anchor)."""
+    game = synth.QuadraticGame(d=1 << 15, K=3)
+    game.x1 = lambda: np.zeros(game.d, np.float32)
+    worst, st = run_lockstep(qgx, game, synth.levels_exponential(16), oracle.NORM_L2, 8192, 7, seed=5, anchor=False,
+                             refit=3)
+    print("worst relative deviation:", worst, flush=True)
+    assert worst <= REL
+
+
+def test_dual_averaging_case_prev_null(qgx):
+    d, K = 5000, 2
+    levels = synth.levels_uniform(8)
+    ctx, lay = make_ctx(qgx, d, K, 4096, oracle.NORM_LINF, levels, seed=2)
+    x1 = synth.gaussian_vector(d, seed=1)
+    ctx.state_init(dev(x1))
+    V = synth.student_t3(K, d, seed=3)
+    cur = ctx.new_stream()
+    ctx.quantize_encode(dev(V), 0, cur)
+    Xn = torch.empty(d, device="cuda")
+    ctx.eg_step(1, cur, None, Xn)
+    h = cur.to_host()
+    _, _, _, so = oracle_stream(V, lay, oracle.NORM_LINF, levels, 2, 0, h["norms"], ctx.worst_words)
+    Vhat, _, _ = oracle.decode(so, h["norms"], lay, levels)
+    st = oracle.EGState(d, K, X1=x1)
+    Xn_o = st.half1(Vhat, None)
+    sc = ctx.scalars()
+    assert abs(sc["S"] - st.S) <= REL * st.S and abs(sc["gamma"] - st.gamma) <= REL * st.gamma
+    assert rel_err(Xn.cpu().numpy(), Xn_o) <= REL
+    # checkpoint / resume: import what was exported, continue, same result as continuing directly
+    Y, A = ctx.state_export()
+    ctx2, _ = make_ctx(qgx, d, K, 4096, oracle.NORM_LINF, levels, seed=2)
+    ctx2.state_import(Y, A, sc["S"], sc["t"])
+    Xa = torch.empty(d, device="cuda"); Xb = torch.empty(d, device="cuda")
+    ctx.eg_step(0, cur, None, Xa)
+    ctx2.eg_step(0, cur, None, Xb)
+    assert torch.equal(Xa, Xb)
+    ctx.close(); ctx2.close()
+
+
+@pytest.mark.parametrize("norm,bucket,n_bins", [(oracle.NORM_L2, 16384, 4096), (oracle.NORM_LINF, 4096, 1024)])
+def test_fit_levels_parity(qgx, norm, bucket, n_bins):
+    d, K, n_sym = (1 << 17) + 300, 3, 33
+    start = synth.levels_exponential(n_sym - 1)
+    ctx, lay = make_ctx(qgx, d, K, bucket, norm, start, seed=0)
+    V = synth.student_t3(K, d, seed=20)
+    hist = torch.zeros(n_bins, dtype=torch.float64, device="cuda")
+    ctx.fit_levels(dev(V), n_sym, n_bins, sweeps=12, hist_out=hist)
+    H_g = hist.cpu().numpy()
+    H_o = oracle.histogram(V, lay, norm, n_bins)
+    np.testing.assert_allclose(H_g, H_o, rtol=1e-12, atol=0)
+    assert (H_g > 0).sum() > 100
+    lv_g = ctx.get_levels()
+    lv_o = oracle.fit_levels(H_o, start, sweeps=12)
+    assert lv_g[0] == 0 and lv_g[-1] == 1 and (np.diff(lv_g) > 0).all()
+    np.testing.assert_allclose(lv_g, lv_o, rtol=REL, atol=1e-9)
+    # what is unique is the objective value: the GPU's table is as good as the oracle's
+    assert oracle.qada_objective(H_o, lv_g) <= oracle.qada_objective(H_o, lv_o) * (1 + 1e-9)
+    # the fitted table is what the next coding call uses
+    out = ctx.new_stream()
+    ctx.quantize_encode(dev(V), 3, out)
+    h = out.to_host()
+    _, _, _, so = oracle_stream(V, lay, norm, lv_g, 0, 3, h["norms"], ctx.worst_words)
+    assert_stream_equal(h, so, lay)
+    # reproducible: a second fit from the same start gives the same bits
+    ctx.set_levels(start)
+    ctx.fit_levels(dev(V), n_sym, n_bins, sweeps=12, hist_out=hist)
+    np.testing.assert_array_equal(hist.cpu().numpy(), H_g)
+    np.testing.assert_array_equal(ctx.get_levels(), lv_g)
+    assert ctx.poll_error() == 0
+    ctx.close()
+
+
+def test_gan_layout_full_iteration(qgx):
+    """Workload 4 at a tenth of its size: 14 segments of very different scale, per-segment buckets of
+    8192 with short ones, L-infinity norm, 16 exponential levels, K = 8, both half-steps."""
+    segs = np.maximum(synth.GAN_SEGMENTS // 16 // 4 * 4, 4).astype(np.uint64)
+    d, K = int(segs.sum()), 8
+    levels = synth.levels_exponential(16)
+    ctx, lay = make_ctx(qgx, d, K, 8192, oracle.NORM_LINF, levels, seed=31, segs=segs)
+    ctx.state_init(None)
+    st = oracle.EGState(d, K)
+    V0 = synth.gan_dual_vectors(K, 0, segments=segs)
+    V1 = synth.gan_dual_vectors(K, 1, segments=segs)
+    a, b = ctx.new_stream(), ctx.new_stream()
+    Xh = torch.empty(d, device="cuda"); Xn = torch.empty(d, device="cuda")
+    ctx.quantize_encode(dev(V0), 0, a); ctx.eg_step(0, a, None, Xh)
+    ctx.quantize_encode(dev(V1), 1, b); ctx.eg_step(1, b, a, Xn)
+    ha, hb = a.to_host(), b.to_host()
+    _, _, _, sa = oracle_stream(V0, lay, oracle.NORM_LINF, levels, 31, 0, ha["norms"], ctx.worst_words)
+    _, _, _, sb = oracle_stream(V1, lay, oracle.NORM_LINF, levels, 31, 1, hb["norms"], ctx.worst_words)
+    np.testing.assert_array_equal(ha["norms"], oracle.quantize(V0, lay, oracle.NORM_LINF, levels, 31, 0)[0])
+    assert_stream_equal(ha, sa, lay); assert_stream_equal(hb, sb, lay)
+    Va, _, _ = oracle.decode(sa, ha["norms"], lay, levels)
+    Vb, _, _ = oracle.decode(sb, hb["norms"], lay, levels)
+    assert rel_err(Xh.cpu().numpy(), st.half0(Va)) <= REL
+    assert rel_err(Xn.cpu().numpy(), st.half1(Vb, Va)) <= REL
+    sc = ctx.scalars()
+    assert abs(sc["S"] - st.S) <= REL * st.S
+    assert ctx.poll_error() == 0
+    ctx.close()
