@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the Q-GenX hot path on one MI355X.
+
+A step is one pass of the path over one batch of K synthetic dual vectors already resident in HBM:
+CODE o Q of all K vectors (fused quantise + encode), then the fused decode + average + first
+extra-gradient half-step.  The level table is fitted once from a histogram of the same batch before
+timing (it is refitted only at the update steps of Algorithm 1).  Default workload: K = 8 vectors of
+d = 2^24 Student-t(3) * 1e-2 coordinates, buckets of 16384, L2 norm, 33-symbol fitted table.
+
+Prints one JSON line: whole-job GB/s of fp32 dual vectors, the roofline of the dominant kernel
+(the encoder) from event timings on the launch stream, and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--logd", type=int, default=24, help="log2 of coordinates per worker")
+    ap.add_argument("--K", type=int, default=8)
+    ap.add_argument("--bucket", type=int, default=16384)
+    ap.add_argument("--n-sym", type=int, default=33)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-logd", type=int, default=23, help="log2 of coordinates per worker in the oracle sample")
+    ap.add_argument("--full-iteration", action="store_true", help="also time encode + second half-step")
+    return ap.parse_args()
+
+
+def measured_traffic():
+    """HBM bytes per encoder launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "encode_t3_K8_d2p24_pmc.txt")
+    try:
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def cpu_baseline(args, levels, seed, V):
+    """The oracle as it stands on a bounded sample of the same workload: CODE o Q, DEQ, mean, half-step."""
+    import numpy as np
+
+    import oracle
+    K, d = V.shape
+    lay = oracle.layout(d, args.bucket)
+    st = oracle.EGState(d, K)
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    t0 = time.perf_counter()
+    norms, idx, neg, _ = oracle.quantize(V, lay, oracle.NORM_L2, levels, seed, 0)
+    s = oracle.encode(idx, neg, lay, cap_words=d // 2)
+    Vhat, _, _ = oracle.decode(s, norms, lay, levels)
+    st.half0(Vhat)
+    dt = time.perf_counter() - t0
+    return {"value": 4.0 * K * d / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": "first 2^%d coordinates of each of the %d workers, one pass quantise+encode+decode+half-step, %.2f s"
+                      % (args.cpu_sample_logd, K, dt)}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the K workers are a batch on it); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    from paper_2308_09187_amd import qgx, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    qgx.load()
+    torch.cuda.set_device(0)
+    d, K, seed = 1 << args.logd, args.K, 2308
+    V = synth.student_t3_device(K, d, seed=20)
+    V1 = synth.student_t3_device(K, d, seed=21) if args.full_iteration else None
+    ctx = qgx.Context(d, K, args.bucket, norm=qgx.NORM_L2, seed=seed)
+    ctx.set_levels(synth.levels_exponential(args.n_sym - 1))
+    ctx.fit_levels(V, args.n_sym, 4096, sweeps=10)
+    levels = ctx.get_levels()
+    ctx.state_init(None)
+    a, b = ctx.new_stream(), ctx.new_stream()
+    Xh = torch.empty(d, dtype=torch.float32, device="cuda")
+
+    def step(i, ev=None):
+        if ev: ev[0].record()
+        ctx.quantize_encode(V, 2 * i, a)
+        if ev: ev[1].record()
+        ctx.eg_step(0, a, None, Xh)
+        if ev: ev[2].record()
+        if args.full_iteration:
+            ctx.quantize_encode(V1, 2 * i + 1, b)
+            if ev: ev[3].record()
+            ctx.eg_step(1, b, a, None)
+            if ev: ev[4].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() == 0
+    n_ev = 5 if args.full_iteration else 3
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(n_ev)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    assert ctx.poll_error() == 0
+
+    ms_step = wall * 1e3 / args.steps
+    enc_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    upd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    h_off = a.chunk_off.cpu().numpy().view(np.uint32)
+    words = int(h_off[:, ctx.NC].astype(np.int64).sum())
+    bits = ctx.scalars(want_bits=True)["total_bits"]
+    side_bytes = K * ((ctx.NC + 1) * 4 + ctx.NC * 128 + ctx.NB * 4)
+    stream_bytes = words * 4 + side_bytes
+    enc_bytes = 4 * K * d + stream_bytes                 # read V once, write the coded streams
+    upd_bytes = stream_bytes + 4 * d + 4 * d             # read streams and Y, write X_{t+1/2}
+    passes = 2 if args.full_iteration else 1
+    value = 4.0 * K * d * passes / (wall / args.steps) / 1e9
+    achieved = enc_bytes / (enc_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "GB/s of fp32 dual vectors through quantize->encode->decode->avg->EG step; % HBM peak",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "K=%d x d=2^%d Student-t(3)*1e-2, bucket %d, L2, %d-symbol fitted table, Elias-omega; "
+                               "step = fused CODE.Q + fused decode/average/half-step%s"
+                               % (K, args.logd, args.bucket, args.n_sym,
+                                  " + CODE.Q + second half-step" if args.full_iteration else ""),
+                   "K": K, "d": d, "bucket": args.bucket, "n_sym": args.n_sym,
+                   "bits_per_coordinate": bits / float(K * d), "stream_bytes": stream_bytes},
+        "hbm_frac_step": (enc_bytes + upd_bytes) / ((enc_ms + upd_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "kernels_ms": {"encode": enc_ms, "decode_avg_half0": upd_ms},
+        "roofline": {"kernel": "k_encode<Fused>", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(),
+                     "algorithmic_bytes": enc_bytes},
+    }
+    if args.full_iteration:
+        out["kernels_ms"]["encode_2"] = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
+        out["kernels_ms"]["decode_avg_half1"] = float(np.mean([e[3].elapsed_time(e[4]) for e in events]))
+    ctx.close()
+    if not args.no_cpu_baseline:
+        ds = min(d, 1 << args.cpu_sample_logd)
+        args.cpu_sample_logd = ds.bit_length() - 1
+        V_host = V[:, :ds].contiguous().cpu().numpy()
+        del V, V1, a, b
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(args, levels, seed, V_host)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

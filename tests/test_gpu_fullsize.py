@@ -1,0 +1,94 @@
+"""Parity at the headline size and in the benchmark's launch configuration (K = 8 vectors of
+d = 2^24 coordinates, buckets of 16384, L2, 33-symbol fitted table): properties that hold at any size
+over the whole output, and sampled buckets / chunks recomputed one by one by the oracle."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle
+from paper_2308_09187_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+REL = 1e-6
+
+
+def mini_stream(h, k, c0, c1):
+    """The chunks c0..c1-1 of worker k as a stand-alone oracle Stream."""
+    off = h["chunk_off"][k, c0:c1 + 1].astype(np.int64)
+    words = h["payload"][k, off[0]:off[-1]].copy()
+    return oracle.Stream(words[None, :], (off - off[0]).astype(np.uint32)[None, :],
+                         h["sub_end"][k:k + 1, c0:c1], np.zeros(1, np.uint64))
+
+
+def test_headline_configuration_sampled_against_oracle():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2308_09187_amd import qgx
+    qgx.load()
+    K, d, bucket, n_sym, seed, call = 8, 1 << 24, 16384, 33, 2308, 6
+    print("generating", flush=True)
+    V = synth.student_t3_device(K, d, seed=20)
+    ctx = qgx.Context(d, K, bucket, norm=qgx.NORM_L2, seed=seed)
+    ctx.set_levels(synth.levels_exponential(n_sym - 1))
+    ctx.fit_levels(V, n_sym, 4096, sweeps=10)
+    levels = ctx.get_levels()
+    assert (np.diff(levels) > 0).all()
+    x1 = torch.randn(d, device="cuda", generator=torch.Generator(device="cuda").manual_seed(3))
+    ctx.state_init(x1)
+    a = ctx.new_stream()
+    Xh = torch.empty(d, device="cuda")
+    print("encode + half-step", flush=True)
+    ctx.quantize_encode(V, call, a)
+    ctx.eg_step(0, a, None, Xh)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() == 0
+    h = a.to_host()
+    NC, NB, CPB = ctx.NC, ctx.NB, bucket // 4096
+
+    # -- whole-output properties ---------------------------------------------------------------
+    off = h["chunk_off"].astype(np.int64)
+    bits = h["sub_end"][:, :, 63].astype(np.int64)
+    assert (off[:, 0] == 0).all()
+    words = (bits + 31) // 32
+    words = (words + 3) // 4 * 4
+    np.testing.assert_array_equal(np.diff(off, axis=1), words)            # exclusive scan of chunk sizes
+    assert (np.diff(h["sub_end"].astype(np.int64), axis=2) >= 64).all()    # >= 1 bit per coordinate
+    assert (h["sub_end"][:, :, 0] >= 64).all()
+    assert (bits <= 4096 * 13).all()                                       # 33 symbols: <= 12 + 1 bits
+    assert ctx.scalars(want_bits=True)["total_bits"] == int(bits.sum())
+    assert np.isfinite(h["norms"]).all() and (h["norms"] > 0).all()
+
+    # -- sampled buckets: norm, symbols -> stream bits, exactly --------------------------------
+    rng = np.random.default_rng(0)
+    picks = [(0, 0), (K - 1, NB - 1)] + [(int(rng.integers(K)), int(rng.integers(NB))) for _ in range(6)]
+    lay_b = oracle.layout(bucket, bucket)
+    for k, b in picks:
+        print("bucket", k, b, flush=True)
+        vb = V[k, b * bucket:(b + 1) * bucket].cpu().numpy()[None, :]
+        n_o, _, _, _ = oracle.quantize(vb, lay_b, oracle.NORM_L2, levels, seed, call, k0=k, i0=b * bucket)
+        assert abs(h["norms"][k, b] - n_o[0, 0]) <= REL * n_o[0, 0]
+        _, idx, neg, _ = oracle.quantize(vb, lay_b, oracle.NORM_L2, levels, seed, call,
+                                         norms_in=h["norms"][k:k + 1, b:b + 1], k0=k, i0=b * bucket)
+        so = oracle.encode(idx, neg, lay_b, cap_words=bucket)
+        ms = mini_stream(h, k, b * CPB, (b + 1) * CPB)
+        np.testing.assert_array_equal(ms.chunk_off, so.chunk_off)
+        np.testing.assert_array_equal(ms.sub_end, so.sub_end)
+        np.testing.assert_array_equal(ms.payload[0], so.payload[0, :ms.payload.shape[1]])
+
+    # -- sampled chunks: decode all K workers, mean and first half-step --------------------------
+    lay_c = oracle.layout(4096, 4096)
+    gamma = ctx.scalars()["gamma"]
+    assert gamma == K
+    for c in [0, NC - 1] + [int(rng.integers(NC)) for _ in range(4)]:
+        print("chunk", c, flush=True)
+        dec = []
+        for k in range(K):
+            ms = mini_stream(h, k, c, c + 1)
+            dec.append(oracle.decode(ms, h["norms"][k:k + 1, c // CPB:c // CPB + 1], lay_c, levels)[0][0])
+        st = oracle.EGState(4096, K, X1=x1[c * 4096:(c + 1) * 4096].cpu().numpy())
+        want = st.half0(np.stack(dec))
+        got = Xh[c * 4096:(c + 1) * 4096].cpu().numpy()
+        assert np.linalg.norm(got - want) <= REL * np.linalg.norm(want)
+    ctx.close()
