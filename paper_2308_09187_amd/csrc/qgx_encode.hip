@@ -9,23 +9,25 @@
 // between the norm reduction and the rounding pass, (c) one Philox4x32 block (four words) serves
 // exactly the four coordinates of a lane and row.
 //
+// The kernel is bound by vector-ALU issue, not by HBM, so the per-coordinate path is kept to a
+// straight line: u -> 1/16-octave cell -> (boundary level, two candidate table rows) -> one 16-byte
+// LDS row holding the level, the scaled gap and the two candidate code words with the sign already
+// appended -> compare against the Philox draw -> select.  Chunks that are not full, buckets with a
+// zero norm and level tables too fine for the cell table take a general path.
+//
 // The stream keeps coordinate order: per row the lanes' code lengths are prefix-summed across the wave
-// and every lane ORs its (at most 56) bits into the wave's LDS staging buffer.  Chunks are placed in
-// the payload in chunk order, so a workgroup needs the total length of all earlier buckets of its
-// worker: a decoupled look-back over per-bucket (flag, length) words gives it without a second pass
-// over V.  Workgroups take their (bucket, worker) from an atomic ticket, so every workgroup a waiting
-// one depends on is already running; the wait is bounded all the same.
+// (DPP) and every lane ORs its (at most 56) bits into the wave's LDS staging buffer.  Chunks are
+// placed in the payload in chunk order, so a workgroup needs the total length of all earlier buckets
+// of its worker: a decoupled look-back over per-bucket (flag, length) words gives it without a second
+// pass over V.  A workgroup's worker is fixed by its block index and its bucket comes from that
+// worker's atomic ticket, so every workgroup a waiting one depends on is already running; the wait is
+// bounded all the same.
 #include "qgx_device.h"
 
 namespace qgx {
 
 constexpr int kStageWords = kChunkWordsMax + 4;   // per-wave LDS staging, 16-byte multiple
 constexpr unsigned kSpinLimit = 1u << 22;
-
-struct Sym4 {                // the four symbols of one lane and row
-    uint32_t idx[4];
-    uint32_t neg[4];
-};
 
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x)
 {
@@ -87,16 +89,73 @@ __device__ uint32_t lookback_exclusive(unsigned long long* state, uint32_t b, ui
     return excl;
 }
 
+// tau(u) by the general route: start at the cell's lower level and walk up.  lev is the LDS copy of
+// Tables::lev2 (positive half); returns the byte offset of row j.
+__device__ __forceinline__ uint32_t level_row_general(const unsigned char* lev, const float4* cell, float u,
+                                                      uint32_t n_sym)
+{
+    const float um = fmaxf(u, __uint_as_float((uint32_t)kCellKey0 << kCellShift));
+    const float4 c = cell[(__float_as_uint(um) >> kCellShift) - kCellKey0];
+    uint32_t j = __float_as_uint(c.y) >> 4;
+    while (j + 2 < n_sym && reinterpret_cast<const float4*>(lev)[j + 1].x <= u) ++j;
+    return j << 4;
+}
+
+// One coordinate: the packed code entry E(idx, sign) = bits | length << 16 of q_l(u) with sign.
+// FAST: straight-line cell route; otherwise the general route.
+template <bool FAST>
+__device__ __forceinline__ uint32_t quantize_one(float x, float rinv, uint32_t rnd, const unsigned char* lev,
+                                                 const float4* cell, uint32_t n_sym, uint32_t& idx_out)
+{
+    // u = min(|v| / ||v||, 1)
+    const float u = fminf(fabsf(x) * rinv, 1.0f);
+    uint32_t row;
+    if (FAST) {
+        const float um = fmaxf(u, __uint_as_float((uint32_t)kCellKey0 << kCellShift));
+        const float4 c = cell[(__float_as_uint(um) >> kCellShift) - kCellKey0];
+        row = (u >= c.x) ? __float_as_uint(c.z) : __float_as_uint(c.y);
+    } else {
+        row = level_row_general(lev, cell, u, n_sym);
+    }
+    const uint32_t sg = (__float_as_uint(x) >> 20) & (uint32_t)kLevRegion;   // sign selects the table half
+    const float4 t = *reinterpret_cast<const float4*>(lev + (row | sg));
+    // up with probability xi = (u - l_j) / (l_{j+1} - l_j):  r * gap < u - l_j, r = top 24 bits * 2^-24
+    const float rr = (float)(rnd >> 8);                 // exact
+    const bool up = rr * t.y < u - t.x;                 // t.y = gap * 2^-24 (exact scaling)
+    idx_out = (row >> 4) + (up ? 1u : 0u);
+    return up ? __float_as_uint(t.w) : __float_as_uint(t.z);
+}
+
+// Appends one row (four entries per lane) to the wave's staging buffer; returns the row's bit count.
+__device__ __forceinline__ uint32_t pack_row(uint32_t* stage, uint16_t* sub_row, uint32_t row_base,
+                                             const uint32_t (&e)[4], int lane)
+{
+    const uint32_t l0 = e[0] >> 16, l1 = e[1] >> 16, l2 = e[2] >> 16, l3 = e[3] >> 16;
+    const uint32_t c01 = (e[0] & 0xFFFFu) | ((e[1] & 0xFFFFu) << l0);     // <= 28 bits
+    const uint32_t c23 = (e[2] & 0xFFFFu) | ((e[3] & 0xFFFFu) << l2);
+    const uint32_t l01 = l0 + l1, len = l01 + l2 + l3;
+    const uint64_t bits = (uint64_t)c01 | ((uint64_t)c23 << l01);         // <= 56 bits
+    const uint32_t incl = wave_incl_scan(len);
+    const uint32_t pos = row_base + incl - len;
+    const uint32_t wi = pos >> 5, sh = pos & 31u;
+    const uint64_t lo64 = (uint64_t)(uint32_t)bits << sh;
+    const uint64_t hi64 = (uint64_t)(uint32_t)(bits >> 32) << sh;
+    __hip_atomic_fetch_or(&stage[wi], (uint32_t)lo64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    __hip_atomic_fetch_or(&stage[wi + 1], (uint32_t)(lo64 >> 32) | (uint32_t)hi64, __ATOMIC_RELAXED,
+                          __HIP_MEMORY_SCOPE_WORKGROUP);
+    __hip_atomic_fetch_or(&stage[wi + 2], (uint32_t)(hi64 >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if ((lane & 15) == 15) sub_row[lane >> 4] = (uint16_t)(row_base + incl);
+    return (uint32_t)__builtin_amdgcn_readlane((int)incl, kWave - 1);
+}
+
 template <EncMode MODE>
 __global__ __launch_bounds__(1024) void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc,
                                                  EncodeArgs a)
 {
     extern __shared__ __align__(16) uint32_t s_stage[];          // [waves][kStageWords]
-    __shared__ float4 s_lev[kSymMax];
-    __shared__ uint32_t s_code[kSymMax];
-    __shared__ __align__(4) uint8_t s_cell[kCellsPad];
+    __shared__ __align__(16) unsigned char s_lev[2 * kLevRegion];
+    __shared__ float4 s_cell[kCellsPad];
     __shared__ double s_red[kMaxWaves];
-    __shared__ uint32_t s_bad[kMaxWaves];
     __shared__ uint32_t s_words[kMaxWaves];
     __shared__ __align__(4) uint16_t s_sub[kMaxWaves][kSubs];
     __shared__ uint32_t s_misc[2];
@@ -104,25 +163,23 @@ __global__ __launch_bounds__(1024) void k_encode(Layout lay, const Tables* __res
     const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
     const int nwaves = (int)(blockDim.x >> 6);
     const uint32_t n_sym = tab->n_sym;
+    const uint32_t k = (uint32_t)blockIdx.x % lay.K;    // worker fixed by the block, bucket by ticket
 
     if (MODE != EncMode::QuantOnly) {
-        if (tid == 0) s_misc[0] = atomicAdd(&sc->ticket, 1u) - a.ticket_base;
+        if (tid == 0) s_misc[0] = atomicAdd(&a.tickets[k * kTicketStride], 1u) - a.ticket_base;
     }
-    for (int i = tid; i < kSymMax; i += (int)blockDim.x) {
-        s_lev[i] = tab->lev[i];
-        s_code[i] = tab->code[i];
+    for (int i = tid; i < (int)n_sym; i += (int)blockDim.x) {
+        reinterpret_cast<float4*>(s_lev)[i] = tab->lev2[0][i];
+        reinterpret_cast<float4*>(s_lev)[kSymMax + i] = tab->lev2[1][i];
     }
-    for (int i = tid; i < kCellsPad / 4; i += (int)blockDim.x)
-        reinterpret_cast<uint32_t*>(s_cell)[i] = reinterpret_cast<const uint32_t*>(tab->cell)[i];
+    for (int i = tid; i < kCells; i += (int)blockDim.x) s_cell[i] = tab->cell[i];
     uint32_t* stage = s_stage + (size_t)w * kStageWords;
     if (MODE != EncMode::QuantOnly) {
         for (int q = lane; q < kStageWords / 4; q += kWave) reinterpret_cast<uint4*>(stage)[q] = make_uint4(0, 0, 0, 0);
     }
     __syncthreads();
 
-    const uint32_t ticket = (MODE != EncMode::QuantOnly) ? s_misc[0] : (uint32_t)blockIdx.x;
-    const uint32_t b = ticket / lay.K;                 // bucket-major: the K scans advance together
-    const uint32_t k = ticket - b * lay.K;
+    const uint32_t b = (MODE != EncMode::QuantOnly) ? s_misc[0] : (uint32_t)blockIdx.x / lay.K;
     const uint32_t lo = lay.bucket_start[b], hi = lay.bucket_start[b + 1];
     const uint32_t c = lay.bucket_chunk0[b] + (uint32_t)w;
     const uint32_t clo = lo + (uint32_t)w * kChunk;
@@ -131,56 +188,68 @@ __global__ __launch_bounds__(1024) void k_encode(Layout lay, const Tables* __res
     const int nrows = (int)((clen + 255u) >> 8);
     const size_t kbase = (size_t)k * lay.d;
     const bool vec_ok = (kbase & 3u) == 0;             // 16-byte aligned rows for this worker
+    const bool full = clen == (uint32_t)kChunk;
 
     // ---- read the chunk once; norm of the bucket ------------------------------------------------
     float4 v[kRows];
     float n = 0.0f;
-    bool bucket_bad = false;
     if (MODE != EncMode::EncodeOnly) {
         const float* __restrict__ Vk = a.V + kbase;
+        if (full && vec_ok) {
 #pragma unroll
-        for (int r = 0; r < kRows; ++r) {
-            const uint32_t i0 = clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
-            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (i0 + 4u <= cend) {
-                if (vec_ok) x = *reinterpret_cast<const float4*>(Vk + i0);
-                else x = make_float4(Vk[i0], Vk[i0 + 1], Vk[i0 + 2], Vk[i0 + 3]);
-            } else if (i0 < cend) {
-                x.x = Vk[i0];
+            for (int r = 0; r < kRows; ++r)
+                v[r] = *reinterpret_cast<const float4*>(Vk + clo + (uint32_t)r * 256u + (uint32_t)lane * 4u);
+        } else {
+#pragma unroll
+            for (int r = 0; r < kRows; ++r) {
+                const uint32_t i0 = clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
+                float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (i0 < cend) x.x = Vk[i0];
                 if (i0 + 1 < cend) x.y = Vk[i0 + 1];
                 if (i0 + 2 < cend) x.z = Vk[i0 + 2];
-            }
-            v[r] = x;
-        }
-        double acc = 0.0;
-        float mx = 0.0f;
-        uint32_t bad = 0;
-#pragma unroll
-        for (int r = 0; r < kRows; ++r) {
-            const float e[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float ax = fabsf(e[q]);
-                bad |= !(ax <= 3.402823466e+38f);
-                if (a.norm_kind == QGX_NORM_L2) acc = fma((double)e[q], (double)e[q], acc);
-                else mx = fmaxf(mx, ax);
+                if (i0 + 3 < cend) x.w = Vk[i0 + 3];
+                v[r] = x;
             }
         }
-        if (a.norm_kind == QGX_NORM_L2) acc = wave_sum(acc);
-        else acc = (double)wave_max(mx);
-        bad = wave_or(bad);
-        if (lane == 0) { s_red[w] = acc; s_bad[w] = bad; }
+        // A non-finite coordinate shows in the reduced value itself: the binary64 sum of squares cannot
+        // overflow from finite binary32 inputs, and the maximum is taken on the magnitude bits.
+        double red;
+        if (a.norm_kind == QGX_NORM_L2) {
+            double acc0 = 0.0, acc1 = 0.0;
+#pragma unroll
+            for (int r = 0; r < kRows; ++r) {
+                acc0 = fma((double)v[r].x, (double)v[r].x, acc0);
+                acc1 = fma((double)v[r].y, (double)v[r].y, acc1);
+                acc0 = fma((double)v[r].z, (double)v[r].z, acc0);
+                acc1 = fma((double)v[r].w, (double)v[r].w, acc1);
+            }
+            red = wave_sum(acc0 + acc1);
+        } else {
+            uint32_t mx = 0;
+#pragma unroll
+            for (int r = 0; r < kRows; ++r) {
+                mx = max(mx, __float_as_uint(v[r].x) & 0x7FFFFFFFu);
+                mx = max(mx, __float_as_uint(v[r].y) & 0x7FFFFFFFu);
+                mx = max(mx, __float_as_uint(v[r].z) & 0x7FFFFFFFu);
+                mx = max(mx, __float_as_uint(v[r].w) & 0x7FFFFFFFu);
+            }
+#pragma unroll
+            for (int off = kWave / 2; off > 0; off >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, off, kWave));
+            red = (double)__uint_as_float(mx);          // inf or NaN bits survive the conversion
+        }
+        if (lane == 0) s_red[w] = red;
         __syncthreads();
         double tot = 0.0;
-        uint32_t anybad = 0;
         for (int i = 0; i < nwaves; ++i) {
             if (a.norm_kind == QGX_NORM_L2) tot += s_red[i];
-            else tot = fmax(tot, s_red[i]);
-            anybad |= s_bad[i];
+            else tot = (s_red[i] > tot || s_red[i] != s_red[i]) ? s_red[i] : tot;
         }
         n = (a.norm_kind == QGX_NORM_L2) ? (float)sqrt(tot) : (float)tot;
-        if (a.norms_in) n = a.norms_in[(size_t)k * lay.NB + b];
-        bucket_bad = (anybad != 0) || !(fabsf(n) <= 3.402823466e+38f);
+        if (a.norms_in) {
+            const float forced = a.norms_in[(size_t)k * lay.NB + b];
+            n = (n == n && fabsf(n) <= 3.402823466e+38f) ? forced : n;   // a poisoned bucket stays rejected
+        }
+        const bool bucket_bad = !(fabsf(n) <= 3.402823466e+38f);
         if (bucket_bad) n = 0.0f;
         if (tid == 0) {
             if (bucket_bad) raise_error(sc, QGX_EBIT_NONFINITE);
@@ -189,96 +258,76 @@ __global__ __launch_bounds__(1024) void k_encode(Layout lay, const Tables* __res
     }
     const float rinv = 1.0f / n;                       // one IEEE division per bucket
     const bool live = n > 0.0f;
+    const bool fast = full && live && vec_ok && (tab->cell_exact != 0u) && MODE != EncMode::EncodeOnly;
 
     // ---- per row: quantise, code, pack ----------------------------------------------------------
     uint32_t row_base = 0;                             // bits of this chunk written so far (wave-uniform)
+    if (fast) {
 #pragma unroll
-    for (int r = 0; r < kRows; ++r) {
-        if (r < nrows) {
+        for (int r = 0; r < kRows; ++r) {
             const uint32_t i0 = clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
-            Sym4 s;
+            uint32_t rnd[4], e[4], idx[4];
+            philox4x32_10(i0 >> 2, 0u, k, a.call_id, a.seed_lo, a.seed_hi, rnd);
+            e[0] = quantize_one<true>(v[r].x, rinv, rnd[0], s_lev, s_cell, n_sym, idx[0]);
+            e[1] = quantize_one<true>(v[r].y, rinv, rnd[1], s_lev, s_cell, n_sym, idx[1]);
+            e[2] = quantize_one<true>(v[r].z, rinv, rnd[2], s_lev, s_cell, n_sym, idx[2]);
+            e[3] = quantize_one<true>(v[r].w, rinv, rnd[3], s_lev, s_cell, n_sym, idx[3]);
+            if (MODE == EncMode::QuantOnly) {
+                uint32_t pk = 0;
+                const float xs[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) pk |= (idx[q] | ((__float_as_uint(xs[q]) >> 31) << 7)) << (8 * q);
+                *reinterpret_cast<uint32_t*>(a.sym_out + kbase + i0) = pk;
+            } else {
+                row_base += pack_row(stage, &s_sub[w][4 * r], row_base, e, lane);
+            }
+        }
+    } else {
+#pragma unroll 1
+        for (int r = 0; r < nrows; ++r) {
+            const uint32_t i0 = clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
+            uint32_t e[4], idx[4], neg[4];
             if (MODE == EncMode::EncodeOnly) {
                 const uint8_t* __restrict__ Sk = a.sym_in + kbase;
-                uint32_t pk = 0;
-                if (i0 + 4u <= cend && vec_ok) pk = *reinterpret_cast<const uint32_t*>(Sk + i0);
-                else {
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        if (i0 + (uint32_t)q < cend) pk |= (uint32_t)Sk[i0 + q] << (8 * q);
-                }
                 bool unknown = false;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const uint32_t by = (pk >> (8 * q)) & 0xFFu;
-                    s.idx[q] = by & 0x7Fu;
-                    s.neg[q] = by >> 7;
-                    if (s.idx[q] >= n_sym) { s.idx[q] = 0; unknown = true; }
+                    const uint32_t by = (i0 + (uint32_t)q < cend) ? (uint32_t)Sk[i0 + q] : 0u;
+                    idx[q] = by & 0x7Fu;
+                    neg[q] = by >> 7;
+                    if (idx[q] >= n_sym) { idx[q] = 0; unknown = true; }
                 }
                 if (__any(unknown) && lane == 0) raise_error(sc, QGX_EBIT_STREAM);
             } else {
                 uint32_t rnd[4];
                 philox4x32_10(i0 >> 2, 0u, k, a.call_id, a.seed_lo, a.seed_hi, rnd);
-                const float e[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
+                // the register copy is indexed by compile-time row numbers only: this path reads the row again
+                const float* __restrict__ Vk = a.V + kbase;
+                float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (i0 < cend) x.x = Vk[i0];
+                if (i0 + 1 < cend) x.y = Vk[i0 + 1];
+                if (i0 + 2 < cend) x.z = Vk[i0 + 2];
+                if (i0 + 3 < cend) x.w = Vk[i0 + 3];
+                const float xs[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const float x = e[q];
-                    uint32_t sym = 0;
-                    if (live) {
-                        // u = min(|v| / ||v||, 1); tau(u) from the cell table, then at most a few steps up
-                        const float u = fminf(fabsf(x) * rinv, 1.0f);
-                        int key = (int)(__float_as_uint(u) >> (23 - kCellMant)) - kCellKey0;
-                        key = key < 0 ? 0 : key;
-                        uint32_t j = s_cell[key];
-                        float4 t = s_lev[j];
-                        while (t.z <= u) { ++j; t = s_lev[j]; }
-                        // up with probability xi = (u - l_j) / (l_{j+1} - l_j):  r * gap < u - l_j
-                        const float rr = (float)(rnd[q] >> 8);           // r * 2^24, exact
-                        sym = j + ((rr * t.y < u - t.x) ? 1u : 0u);     // t.y = gap * 2^-24, exact scaling
-                    }
-                    s.idx[q] = sym;
-                    s.neg[q] = __float_as_uint(x) >> 31;
+                    idx[q] = 0;
+                    neg[q] = __float_as_uint(xs[q]) >> 31;
+                    if (live) (void)quantize_one<false>(xs[q], rinv, rnd[q], s_lev, s_cell, n_sym, idx[q]);
                 }
             }
             if (MODE == EncMode::QuantOnly) {
-                uint8_t* __restrict__ Sk = a.sym_out + kbase;
-                uint32_t pk = 0;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) pk |= (s.idx[q] | (s.neg[q] << 7)) << (8 * q);
-                if (i0 + 4u <= cend && vec_ok) *reinterpret_cast<uint32_t*>(Sk + i0) = pk;
-                else {
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        if (i0 + (uint32_t)q < cend) Sk[i0 + q] = (uint8_t)(pk >> (8 * q));
-                }
+                for (int q = 0; q < 4; ++q)
+                    if (i0 + (uint32_t)q < cend) a.sym_out[kbase + i0 + q] = (uint8_t)(idx[q] | (neg[q] << 7));
             } else {
-                // Psi(idx) then the sign bit of a non-zero symbol; four symbols -> at most 56 bits
-                uint64_t bits = 0;
-                uint32_t len = 0;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    if (i0 + (uint32_t)q < cend) {
-                        const uint32_t cw = s_code[s.idx[q]];
-                        uint32_t cb = cw & 0xFFFFu, cl = cw >> 16;
-                        if (s.idx[q] != 0) { cb |= s.neg[q] << cl; cl += 1; }
-                        bits |= (uint64_t)cb << len;
-                        len += cl;
-                    }
+                    // E(idx, sign) from the table row of idx (its third word), nothing for a padded slot
+                    const float4 t = reinterpret_cast<const float4*>(s_lev)[idx[q] + neg[q] * kSymMax];
+                    e[q] = (i0 + (uint32_t)q < cend) ? __float_as_uint(t.z) : 0u;
                 }
-                const uint32_t incl = wave_incl_scan(len);
-                const uint32_t pos = row_base + incl - len;
-                if (len != 0) {
-                    const uint32_t wi = pos >> 5, sh = pos & 31u;
-                    const uint64_t lo64 = (uint64_t)(uint32_t)bits << sh;
-                    const uint64_t hi64 = (uint64_t)(uint32_t)(bits >> 32) << sh;
-                    const uint32_t x0 = (uint32_t)lo64;
-                    const uint32_t x1 = (uint32_t)(lo64 >> 32) | (uint32_t)hi64;
-                    const uint32_t x2 = (uint32_t)(hi64 >> 32);
-                    __hip_atomic_fetch_or(&stage[wi], x0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                    if (x1) __hip_atomic_fetch_or(&stage[wi + 1], x1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                    if (x2) __hip_atomic_fetch_or(&stage[wi + 2], x2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                }
-                if ((lane & 15) == 15) s_sub[w][4 * r + (lane >> 4)] = (uint16_t)(row_base + incl);
-                row_base += bcast_lane(incl, kWave - 1);
+                row_base += pack_row(stage, &s_sub[w][4 * r], row_base, e, lane);
             }
         }
     }

@@ -19,28 +19,38 @@ constexpr int kMaxSymBits = kMaxCode + 1;               // plus the sign bit
 constexpr int kChunkWordsMax = kChunk * kMaxSymBits / 32;  // 1792
 constexpr int kAlignWords = 4;
 constexpr int kMaxWaves = QGX_MAX_BUCKET / kChunk;      // 16 waves = 1024 threads per bucket
+constexpr int kTicketStride = 32;           // one 128-byte line per worker's counter
 constexpr int kSymMax = 128;              // table storage (QGX_MAX_SYM = 127 entries used at most)
 
-// tau lookup: one cell per 1/32 octave over 24 octaves below 1, plus the cell of u = 1.
-constexpr int kCellMant = 5;
+// tau lookup: one cell per 1/16 octave over 24 octaves below 1, plus the cell of u = 1.
+constexpr int kCellMant = 4;
 constexpr int kCellOct = 24;
+constexpr int kCellShift = 23 - kCellMant;
 constexpr int kCellKey0 = (127 - kCellOct) << kCellMant;
-constexpr int kCells = (kCellOct << kCellMant) + 1;     // 769
-constexpr int kCellsPad = 784;
+constexpr int kCells = (kCellOct << kCellMant) + 1;     // 385
+constexpr int kCellsPad = 388;
+constexpr int kLevRegion = kSymMax * 16;                // bytes between the two sign halves of lev2
 
 constexpr int kDlutBits = kMaxCode;       // decode window
 constexpr int kDlut = 1 << kDlutBits;     // 8192 entries
 
 // Device-resident tables: rebuilt on the device whenever the level table or the code changes.
 struct Tables {
-    float4 lev[kSymMax];        // {l_j, (l_{j+1}-l_j)*2^-24, l_{j+1} (+inf for the last gap), 0}
+    // lev2[sg][j] = {l_j, (l_{j+1}-l_j)*2^-24, E(j, sg), E(j+1, sg)}: everything the rounding of a
+    // coordinate with sign sg between levels j and j+1 needs.  E(idx, sg) = code word of idx with the
+    // sign bit appended (idx != 0), first-written bit in bit 0, total length << 16.
+    float4 lev2[2][kSymMax];
+    // cell[c] = {B, a0, a1, 0} for the c-th 1/16-octave of u: a0 = byte offset in lev2 of the entry of
+    // the last level <= the cell's lower edge; B = the level inside the cell (+inf if none), a1 = the
+    // entry to use when u >= B.  Exact only if no cell holds two levels (cell_exact).
+    float4 cell[kCellsPad];
     float lval[kSymMax];        // l_j
-    float levels[kSymMax];      // the table as set or fitted (source of the two above)
-    uint32_t code[kSymMax];     // code word (first-written bit in bit 0) | length << 16
+    float levels[kSymMax];      // the table as set or fitted (source of the ones above)
+    uint32_t code[kSymMax];     // code word (first-written bit in bit 0) | length << 16, no sign
     uint32_t n_sym;
     uint32_t code_kind;
-    uint32_t pad_[2];
-    uint8_t cell[kCellsPad];    // largest j <= n_sym-2 with l_j <= lower edge of the cell
+    uint32_t cell_exact;
+    uint32_t pad_;
     uint16_t dlut[kDlut];       // next 13 stream bits -> idx << 4 | length; 0xFFFF = no code word
 };
 
@@ -52,8 +62,7 @@ struct Scalars {
     unsigned long long total_bits;
     float gamma_f;              // gamma rounded to binary32, what the update kernels multiply by
     unsigned int err;           // QGX_EBIT_*
-    unsigned int ticket;        // ever-increasing workgroup ticket of the encoder
-    unsigned int pad_;
+    unsigned int pad_[2];
 };
 
 struct Layout {                 // device pointers into one allocation
@@ -79,8 +88,9 @@ struct EncodeArgs {
     uint32_t* payload;          // [K][cap]
     uint64_t cap_words;
     unsigned long long* scan_state;  // [K][NB] look-back words
+    uint32_t* tickets;          // [K] ever-increasing bucket tickets, kTicketStride words apart
     uint32_t epoch;             // tags scan_state entries of this launch
-    uint32_t ticket_base;       // value of Scalars::ticket before this launch
+    uint32_t ticket_base;       // value of every ticket counter before this launch
     uint32_t seed_lo, seed_hi, call_id;
     int norm_kind;
 };

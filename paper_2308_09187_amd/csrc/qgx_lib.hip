@@ -22,6 +22,7 @@ struct qgx_ctx {
     float* d_Y = nullptr;
     float* d_anchor = nullptr;
     unsigned long long* d_scan = nullptr;
+    uint32_t* d_tickets = nullptr;
     double* d_spartial = nullptr;
     double* d_hpartial = nullptr;
     double* d_hist = nullptr;
@@ -77,7 +78,7 @@ qgx_status need_levels(qgx_ctx* ctx)
 
 void free_all(qgx_ctx* c)
 {
-    void* all[] = {c->d_layout, c->d_tab, c->d_sc, c->d_Y, c->d_anchor, c->d_scan, c->d_spartial, c->d_hpartial, c->d_hist};
+    void* all[] = {c->d_layout, c->d_tab, c->d_sc, c->d_Y, c->d_anchor, c->d_scan, c->d_tickets, c->d_spartial, c->d_hpartial, c->d_hist};
     for (void* p : all) (void)hipFree(p);
 }
 
@@ -159,6 +160,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     ok = ok && hipMalloc(&c->d_Y, cfg->d * sizeof(float)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_anchor, cfg->d * sizeof(float)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_scan, (size_t)cfg->K * NB * sizeof(unsigned long long)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_tickets, (size_t)cfg->K * kTicketStride * sizeof(uint32_t)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_spartial, (size_t)NC * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_hpartial, (size_t)c->h_groups * QGX_MAX_BINS * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_hist, QGX_MAX_BINS * sizeof(double)) == hipSuccess;
@@ -166,6 +168,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     ok = ok && hipMemset(c->d_tab, 0, sizeof(Tables)) == hipSuccess;
     ok = ok && hipMemset(c->d_sc, 0, sizeof(Scalars)) == hipSuccess;
     ok = ok && hipMemset(c->d_scan, 0, (size_t)cfg->K * NB * sizeof(unsigned long long)) == hipSuccess;
+    ok = ok && hipMemset(c->d_tickets, 0, (size_t)cfg->K * kTicketStride * sizeof(uint32_t)) == hipSuccess;
     if (ok) {
         const uint32_t kind = (uint32_t)cfg->code;
         ok = hipMemcpy(&c->d_tab->code_kind, &kind, sizeof(kind), hipMemcpyHostToDevice) == hipSuccess;
@@ -275,10 +278,11 @@ static qgx_status run_encode(qgx_ctx* ctx, EncMode mode, const float* V, uint32_
         if (ctx->epoch == 0) ctx->epoch = 1;
         a.epoch = ctx->epoch;
         a.ticket_base = ctx->ticket_count;
+        a.tickets = ctx->d_tickets;
     }
     QGX_HIP(ctx, launch_encode(mode, ctx->lay, ctx->d_tab, ctx->d_sc, a, (hipStream_t)stream));
     if (mode != EncMode::QuantOnly) {
-        ctx->ticket_count += ctx->lay.K * ctx->lay.NB;
+        ctx->ticket_count += ctx->lay.NB;
         ctx->last_sub_end = out->sub_end;
     }
     return QGX_OK;

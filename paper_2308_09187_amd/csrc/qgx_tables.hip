@@ -22,32 +22,21 @@ __device__ inline uint32_t elias_omega(uint32_t N, uint32_t* len_out)
     return bits;
 }
 
-__device__ void build_tables_block(Tables* tab)
+// E(idx, sg): code word of idx with the sign bit appended when idx != 0, total length << 16.
+__device__ inline uint32_t coded_entry(uint32_t cw, uint32_t idx, uint32_t sg)
+{
+    uint32_t bits = cw & 0xFFFFu, len = cw >> 16;
+    if (idx != 0) { bits |= sg << len; len += 1; }
+    return bits | (len << 16);
+}
+
+static __device__ void build_tables_block(Tables* tab)
 {
     const uint32_t n_sym = tab->n_sym;
     const int tid = (int)threadIdx.x, nt = (int)blockDim.x;
     const float* lv = tab->levels;
     const float inf = __uint_as_float(0x7f800000u);
 
-    for (int j = tid; j < kSymMax; j += nt) {
-        float4 e = make_float4(1.0f, 0.0f, inf, 0.0f);
-        float l = 1.0f;
-        if ((uint32_t)j < n_sym) l = lv[j];
-        if ((uint32_t)j + 1 < n_sym) {
-            const float g = lv[j + 1] - lv[j];
-            e = make_float4(lv[j], g * 0x1p-24f, ((uint32_t)j + 2 < n_sym) ? lv[j + 1] : inf, 0.0f);
-        }
-        tab->lev[j] = e;
-        tab->lval[j] = l;
-    }
-    for (int c = tid; c < kCellsPad; c += nt) {
-        uint32_t j = 0;
-        if (c > 0 && c < kCells) {
-            const float edge = __uint_as_float((uint32_t)(c + kCellKey0) << (23 - kCellMant));
-            while (j + 2 < n_sym && lv[j + 1] <= edge) ++j;
-        }
-        tab->cell[c] = (uint8_t)j;
-    }
     if (tab->code_kind == QGX_CODE_ELIAS_OMEGA) {
         for (int j = tid; j < kSymMax; j += nt) {
             uint32_t len = 0, bits = 0;
@@ -57,6 +46,41 @@ __device__ void build_tables_block(Tables* tab)
     }
     for (int i = tid; i < kDlut; i += nt) tab->dlut[i] = 0xFFFFu;
     __syncthreads();
+
+    for (int j = tid; j < kSymMax; j += nt) {
+        float l = 1.0f, g = 0.0f;
+        if ((uint32_t)j < n_sym) l = lv[j];
+        if ((uint32_t)j + 1 < n_sym) g = (lv[j + 1] - lv[j]) * 0x1p-24f;
+        for (uint32_t sg = 0; sg < 2; ++sg) {
+            float4 e = make_float4(l, g, 0.0f, 0.0f);
+            if ((uint32_t)j < n_sym) e.z = __uint_as_float(coded_entry(tab->code[j], (uint32_t)j, sg));
+            if ((uint32_t)j + 1 < n_sym) e.w = __uint_as_float(coded_entry(tab->code[j + 1], (uint32_t)j + 1, sg));
+            tab->lev2[sg][j] = e;
+        }
+        tab->lval[j] = l;
+    }
+    // cells: lower level, the level inside (if any), and whether a second one makes the cell inexact
+    if (tid == 0) tab->cell_exact = 1u;
+    __syncthreads();
+    for (int c = tid; c < kCellsPad; c += nt) {
+        uint32_t j = 0;
+        float B = inf;
+        uint32_t a1 = 0;
+        bool crowded = false;
+        if (c < kCells) {
+            const float edge = c == 0 ? 0.0f : __uint_as_float((uint32_t)(c + kCellKey0) << kCellShift);
+            const float next = c + 1 < kCells ? __uint_as_float((uint32_t)(c + 1 + kCellKey0) << kCellShift) : inf;
+            while (j + 2 < n_sym && lv[j + 1] <= edge) ++j;
+            a1 = j;
+            if (j + 2 < n_sym && lv[j + 1] < next) {      // a level strictly inside the cell
+                B = lv[j + 1];
+                a1 = j + 1;
+                if (j + 3 < n_sym && lv[j + 2] < next) crowded = true;
+            }
+        }
+        tab->cell[c] = make_float4(B, __uint_as_float(j << 4), __uint_as_float(a1 << 4), 0.0f);
+        if (crowded) tab->cell_exact = 0u;
+    }
     // every 13-bit window that starts with code word j decodes to j
     for (uint32_t j = 0; j < n_sym; ++j) {
         const uint32_t cw = tab->code[j];
