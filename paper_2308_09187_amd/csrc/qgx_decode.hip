@@ -13,8 +13,15 @@
 
 namespace qgx {
 
-constexpr int kStageWords = kChunkWordsMax + 4;
 constexpr int kPre = kChunkWordsMax / (kWave * 4);   // 7 x uint4 per lane cover a worst-case chunk
+constexpr int kDecWaves = 8;                          // waves per workgroup: they share the decode table
+
+// Staged chunk layout in LDS.  Lane j parses the j-th run of 64 coordinates, whose bits start roughly
+// 64 * (bits per coordinate) / 32 words after lane j-1's: a power-of-two stride that would put all
+// lanes on a few banks.  So one pad word is inserted after every 32 words (word i lives at
+// i + i/32), and the pad slot repeats the word that follows it, so that a lane always finds the two
+// words of its 32-bit window next to each other.
+__device__ __forceinline__ uint32_t staged(uint32_t i) { return i + (i >> 5); }
 
 struct ChunkRef {            // where one worker's chunk lives and how long it is
     const uint4* src;
@@ -22,14 +29,14 @@ struct ChunkRef {            // where one worker's chunk lives and how long it i
 };
 
 __device__ __forceinline__ ChunkRef chunk_ref(const uint32_t* payload, uint64_t cap, const uint32_t* chunk_off,
-                                              uint32_t k, uint32_t c, uint32_t NC, Scalars* sc)
+                                              uint32_t k, uint32_t c, uint32_t NC, uint32_t max_words, Scalars* sc)
 {
     const uint32_t off = chunk_off[(size_t)k * (NC + 1) + c];
     const uint32_t end = chunk_off[(size_t)k * (NC + 1) + c + 1];
     ChunkRef r;
     r.src = reinterpret_cast<const uint4*>(payload + (size_t)k * cap + off);
     r.words = end - off;
-    if (end < off || r.words > (uint32_t)kChunkWordsMax || (off & 3u) || (r.words & 3u) || (uint64_t)end > cap) {
+    if (end < off || r.words > max_words || (off & 3u) || (r.words & 3u) || (uint64_t)end > cap) {
         if (lane_id() == 0) raise_error(sc, QGX_EBIT_STREAM);
         r.words = 0;
     }
@@ -46,22 +53,30 @@ __device__ __forceinline__ void prefetch_chunk(const ChunkRef& cr, uint4 (&pre)[
     }
 }
 
-__device__ __forceinline__ void commit_chunk(uint32_t* stage, const uint4 (&pre)[kPre])
+__device__ __forceinline__ void commit_chunk(uint32_t* stage, const uint4 (&pre)[kPre], uint32_t stage_words)
 {
     const uint32_t lane = (uint32_t)lane_id();
 #pragma unroll
-    for (int q = 0; q < kPre; ++q) reinterpret_cast<uint4*>(stage)[lane + (uint32_t)q * kWave] = pre[q];
+    for (int q = 0; q < kPre; ++q) {
+        const uint32_t i0 = (lane + (uint32_t)q * kWave) * 4u;
+        if (i0 < stage_words) {
+            const uint32_t s0 = staged(i0);
+            stage[s0] = pre[q].x; stage[s0 + 1] = pre[q].y; stage[s0 + 2] = pre[q].z; stage[s0 + 3] = pre[q].w;
+            if ((i0 & 31u) == 0u && i0 != 0u) stage[s0 - 1] = pre[q].x;     // the pad slot repeats its successor
+        }
+    }
 }
 
 // One symbol at bit cursor p of the staged chunk: returns the signed value norm * l_idx.
+// A window that starts with no code word decodes through the table's reject entry (flag bit 15).
 __device__ __forceinline__ float take_symbol(const uint32_t* stage, const uint16_t* dlut, const float* lval,
-                                             uint32_t& p, float n, bool& malformed)
+                                             uint32_t& p, float n, uint32_t& flags)
 {
-    const uint32_t wi = min(p >> 5, (uint32_t)kChunkWordsMax);
-    const uint32_t w0 = stage[wi], w1 = stage[wi + 1];
-    const uint32_t win = __builtin_amdgcn_alignbit(w1, w0, p & 31u);
-    uint32_t e = dlut[win & (uint32_t)(kDlut - 1)];
-    if (e == 0xFFFFu) { malformed = true; e = 1u; }        // keep going in bounds: symbol 0, one bit
+    const uint32_t wi = p >> 5;
+    const uint32_t* wp = stage + staged(wi);
+    const uint32_t win = __builtin_amdgcn_alignbit(wp[1], wp[0], p & 31u);
+    const uint32_t e = dlut[win & (uint32_t)(kDlut - 1)];
+    flags |= e;
     const uint32_t len = e & 15u, idx = e >> 4;
     const uint32_t nz = idx != 0u ? 1u : 0u;
     const uint32_t sg = (win >> len) & nz;
@@ -71,22 +86,30 @@ __device__ __forceinline__ float take_symbol(const uint32_t* stage, const uint16
 }
 
 template <DecMode MODE>
-__global__ __launch_bounds__(256) void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArgs a)
+__global__ __launch_bounds__(kDecWaves * kWave) __attribute__((amdgpu_waves_per_eu(MODE == DecMode::Half1 ? 3 : 4))) void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc,
+                                                              DecodeArgs a)
 {
-    extern __shared__ __align__(16) uint32_t s_dyn[];    // [waves][1 or 2][kStageWords]
-    __shared__ uint16_t s_dlut[kDlut];
-    __shared__ float s_lval[kSymMax];
+    extern __shared__ __align__(16) uint32_t s_dyn[];    // [waves][1 or 2][stage_words_padded]
+    __shared__ float s_lval[kSymMax];                    // just below the decode table: a reject entry's
+    __shared__ uint16_t s_dlut[kDlut];                   // index lands inside it, not outside the block
 
     const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
     constexpr int kBufs = (MODE == DecMode::Half1) ? 2 : 1;
-    uint32_t* stage = s_dyn + (size_t)w * kBufs * kStageWords;
-    uint32_t* stage_p = stage + kStageWords;
+    const uint32_t stage_words = a.stage_words;          // words a chunk of this code can take
+    const uint32_t stage_stride = a.stage_stride;        // padded size of one staging buffer, words
+    uint32_t* stage = s_dyn + (size_t)w * kBufs * stage_stride;
+    uint32_t* stage_p = stage + stage_stride;
 
-    for (int i = tid; i < kDlut / 2; i += (int)blockDim.x)
-        reinterpret_cast<uint32_t*>(s_dlut)[i] = reinterpret_cast<const uint32_t*>(tab->dlut)[i];
+    for (int i = tid; i < kDlut / 2; i += (int)blockDim.x) {
+        uint32_t two = reinterpret_cast<const uint32_t*>(tab->dlut)[i];
+        // reject entries: flag in bit 15, one bit long, so that the parse goes on inside the buffer
+        if ((two & 0xFFFFu) == 0xFFFFu) two = (two & 0xFFFF0000u) | 0x8001u;
+        if ((two >> 16) == 0xFFFFu) two = (two & 0x0000FFFFu) | 0x80010000u;
+        reinterpret_cast<uint32_t*>(s_dlut)[i] = two;
+    }
     for (int i = tid; i < kSymMax; i += (int)blockDim.x) s_lval[i] = tab->lval[i];
     // words past a chunk's end are read by the window of its last symbols: keep them defined
-    for (int q = lane; q < kBufs * kStageWords; q += kWave) stage[q] = 0;
+    for (uint32_t q = (uint32_t)lane; q < kBufs * stage_stride; q += kWave) stage[q] = 0;
     __syncthreads();
 
     const uint32_t g = (uint32_t)blockIdx.x * (blockDim.x >> 6) + (uint32_t)w;   // global wave number
@@ -102,43 +125,40 @@ __global__ __launch_bounds__(256) void k_decode(Layout lay, const Tables* __rest
     const uint32_t clen = lay.chunk_start[c + 1] - clo;
     const uint32_t bkt = lay.chunk_bucket[c];
     const int cnt = (int)min(64u, clen > 64u * (uint32_t)lane ? clen - 64u * (uint32_t)lane : 0u);
+    const bool full = clen == (uint32_t)kChunk;           // wave-uniform: every lane has 64 coordinates
     const bool have_prev = (MODE == DecMode::Half1) && a.payload_p != nullptr;
+    // a cursor from a corrupt table is pulled back so that 64 symbols from it stay inside the buffer
+    const uint32_t p_limit = stage_words * 32u - 64u * (uint32_t)kMaxSymBits - 64u;
 
     float acc[kSub];
 #pragma unroll
     for (int s = 0; s < kSub; ++s) acc[s] = 0.0f;
     double sdiff = 0.0;
+    uint32_t flags = 0;
     bool malformed = false;
 
-    uint4 pre[kPre], pre_p[(MODE == DecMode::Half1) ? kPre : 1];
-    ChunkRef cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, k_first, c, lay.NC, sc);
+    uint4 pre[kPre];
+    ChunkRef cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, k_first, c, lay.NC, stage_words, sc);
     prefetch_chunk(cr, pre);
-    if constexpr (MODE == DecMode::Half1) {
-        if (have_prev) {
-            ChunkRef cp = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, k_first, c, lay.NC, sc);
-            prefetch_chunk(cp, reinterpret_cast<uint4(&)[kPre]>(pre_p));
-        }
-    }
 
     for (uint32_t kk = 0; kk < k_count; ++kk) {
         const uint32_t k = k_first + kk;
-        commit_chunk(stage, pre);
+        commit_chunk(stage, pre, stage_words);
         if constexpr (MODE == DecMode::Half1) {
-            if (have_prev) commit_chunk(stage_p, reinterpret_cast<uint4(&)[kPre]>(pre_p));
+            if (have_prev) {                         // the previous half-step's chunk goes through the same registers
+                ChunkRef cp = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, k, c, lay.NC, stage_words, sc);
+                prefetch_chunk(cp, pre);
+                commit_chunk(stage_p, pre, stage_words);
+            }
         }
         if (kk + 1 < k_count) {                      // next worker's chunk: in flight while this one is parsed
-            cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, k + 1, c, lay.NC, sc);
+            cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, k + 1, c, lay.NC, stage_words, sc);
             prefetch_chunk(cr, pre);
-            if constexpr (MODE == DecMode::Half1) {
-                if (have_prev) {
-                    ChunkRef cp = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, k + 1, c, lay.NC, sc);
-                    prefetch_chunk(cp, reinterpret_cast<uint4(&)[kPre]>(pre_p));
-                }
-            }
         }
         const uint16_t* se = a.sub_end + ((size_t)k * lay.NC + c) * kSubs;
         const uint32_t p_end = se[lane];
         uint32_t p = lane ? (uint32_t)se[lane - 1] : 0u;
+        if (p > p_limit) { p = p_limit; malformed = true; }
         const float n = a.norms[(size_t)k * lay.NB + bkt];
         uint32_t pp = 0, pp_end = 0;
         float np = 0.0f;
@@ -147,22 +167,38 @@ __global__ __launch_bounds__(256) void k_decode(Layout lay, const Tables* __rest
                 const uint16_t* sp = a.sub_end_p + ((size_t)k * lay.NC + c) * kSubs;
                 pp_end = sp[lane];
                 pp = lane ? (uint32_t)sp[lane - 1] : 0u;
+                if (pp > p_limit) { pp = p_limit; malformed = true; }
                 np = a.norms_p[(size_t)k * lay.NB + bkt];
             }
         }
         float* vout = nullptr;
         if constexpr (MODE == DecMode::Decode) vout = a.out + (size_t)k * lay.d + clo + 64u * (uint32_t)lane;
+        if (full && MODE != DecMode::Half1) {
 #pragma unroll
-        for (int s = 0; s < kSub; ++s) {
-            if (s < cnt) {
-                const float val = take_symbol(stage, s_dlut, s_lval, p, n, malformed);
+            for (int s = 0; s < kSub; ++s) {
+                const float val = take_symbol(stage, s_dlut, s_lval, p, n, flags);
                 if constexpr (MODE == DecMode::Decode) vout[s] = val;
                 else acc[s] += val;
                 if constexpr (MODE == DecMode::Half1) {
                     float pv = 0.0f;
-                    if (have_prev) pv = take_symbol(stage_p, s_dlut, s_lval, pp, np, malformed);
+                    if (have_prev) pv = take_symbol(stage_p, s_dlut, s_lval, pp, np, flags);
                     const double df = (double)pv - (double)val;
                     sdiff = fma(df, df, sdiff);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < kSub; ++s) {
+                if (s < cnt) {
+                    const float val = take_symbol(stage, s_dlut, s_lval, p, n, flags);
+                    if constexpr (MODE == DecMode::Decode) vout[s] = val;
+                    else acc[s] += val;
+                    if constexpr (MODE == DecMode::Half1) {
+                        float pv = 0.0f;
+                        if (have_prev) pv = take_symbol(stage_p, s_dlut, s_lval, pp, np, flags);
+                        const double df = (double)pv - (double)val;
+                        sdiff = fma(df, df, sdiff);
+                    }
                 }
             }
         }
@@ -171,11 +207,12 @@ __global__ __launch_bounds__(256) void k_decode(Layout lay, const Tables* __rest
             if (have_prev && cnt > 0 && pp != pp_end) malformed = true;
         }
     }
+    malformed = malformed || (flags & 0x8000u) != 0u;
     if (__any(malformed) && lane == 0) raise_error(sc, QGX_EBIT_STREAM);
     if (MODE == DecMode::Decode) return;
 
     // ---- aggregate and update: lane owns coordinates clo + 64*lane .. + cnt ---------------------
-    const float Kf = (float)lay.K;
+    const float invK = 1.0f / (float)lay.K;
     const uint32_t i0 = clo + 64u * (uint32_t)lane;
     const float gam = sc->gamma_f;
     if constexpr (MODE == DecMode::Half1) {
@@ -185,7 +222,7 @@ __global__ __launch_bounds__(256) void k_decode(Layout lay, const Tables* __rest
     if (cnt == kSub) {
 #pragma unroll
         for (int s = 0; s < kSub; s += 4) {
-            float4 m = make_float4(acc[s] / Kf, acc[s + 1] / Kf, acc[s + 2] / Kf, acc[s + 3] / Kf);
+            float4 m = make_float4(acc[s] * invK, acc[s + 1] * invK, acc[s + 2] * invK, acc[s + 3] * invK);
             if (MODE == DecMode::Average) {
                 *reinterpret_cast<float4*>(a.out + i0 + s) = m;
             } else if (MODE == DecMode::Half0) {
@@ -207,7 +244,7 @@ __global__ __launch_bounds__(256) void k_decode(Layout lay, const Tables* __rest
 #pragma unroll
         for (int s = 0; s < kSub; ++s) {
             if (s < cnt) {
-                const float m = acc[s] / Kf;
+                const float m = acc[s] * invK;
                 if (MODE == DecMode::Average) a.out[i0 + s] = m;
                 else if (MODE == DecMode::Half0) {
                     const float x = a.anchor ? a.anchor[i0 + s] : 0.0f;
@@ -221,19 +258,18 @@ __global__ __launch_bounds__(256) void k_decode(Layout lay, const Tables* __rest
 template <DecMode MODE>
 static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
 {
-    constexpr int waves = 4;
     constexpr int bufs = (MODE == DecMode::Half1) ? 2 : 1;
-    const size_t lds = (size_t)waves * bufs * kStageWords * sizeof(uint32_t);
+    const size_t lds = (size_t)kDecWaves * bufs * a.stage_stride * sizeof(uint32_t);
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<MODE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 140 * 1024);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
     const uint64_t nwork = (MODE == DecMode::Decode) ? (uint64_t)lay.K * lay.NC : (uint64_t)lay.NC;
-    const uint32_t grid = (uint32_t)((nwork + waves - 1) / waves);
-    hipLaunchKernelGGL(k_decode<MODE>, dim3(grid), dim3(waves * kWave), lds, st, lay, tab, sc, a);
+    const uint32_t grid = (uint32_t)((nwork + kDecWaves - 1) / kDecWaves);
+    hipLaunchKernelGGL(k_decode<MODE>, dim3(grid), dim3(kDecWaves * kWave), lds, st, lay, tab, sc, a);
     return hipGetLastError();
 }
 

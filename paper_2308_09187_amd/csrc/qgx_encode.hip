@@ -26,7 +26,6 @@
 
 namespace qgx {
 
-constexpr int kStageWords = kChunkWordsMax + 4;   // per-wave LDS staging, 16-byte multiple
 constexpr unsigned kSpinLimit = 1u << 22;
 
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x)
@@ -89,36 +88,43 @@ __device__ uint32_t lookback_exclusive(unsigned long long* state, uint32_t b, ui
     return excl;
 }
 
-// tau(u) by the general route: start at the cell's lower level and walk up.  lev is the LDS copy of
-// Tables::lev2 (positive half); returns the byte offset of row j.
-__device__ __forceinline__ uint32_t level_row_general(const unsigned char* lev, const float4* cell, float u,
-                                                      uint32_t n_sym)
+struct LdsPlan {                 // where things live in the workgroup's LDS (byte offsets)
+    const float2* cell;
+    const unsigned char* lev;    // two sign halves, lev_stride bytes apart
+    uint32_t lev_stride, sign_shift;
+};
+
+// tau(u) by the general route: start at the cell's lower level and walk up; returns the byte offset
+// of row j in the level table.
+__device__ __forceinline__ uint32_t level_row_general(const LdsPlan& L, float u, uint32_t n_sym)
 {
-    const float um = fmaxf(u, __uint_as_float((uint32_t)kCellKey0 << kCellShift));
-    const float4 c = cell[(__float_as_uint(um) >> kCellShift) - kCellKey0];
-    uint32_t j = __float_as_uint(c.y) >> 4;
-    while (j + 2 < n_sym && reinterpret_cast<const float4*>(lev)[j + 1].x <= u) ++j;
+    const float um = fminf(fmaxf(u, __uint_as_float((uint32_t)kCellKey0 << kCellShift)), 1.0f);
+    const float2 c = L.cell[(__float_as_uint(um) >> kCellShift) - kCellKey0];
+    uint32_t j = (__float_as_uint(c.y) & 0xFFFFu) >> 4;
+    while (j + 2 < n_sym && reinterpret_cast<const float4*>(L.lev)[j + 1].x <= u) ++j;
     return j << 4;
 }
 
 // One coordinate: the packed code entry E(idx, sign) = bits | length << 16 of q_l(u) with sign.
-// FAST: straight-line cell route; otherwise the general route.
+// FAST: straight-line cell route, valid when u <= 1 up to rounding (so the clamp of u to 1 can be
+// left out: at u >= 1 the coordinate rounds up whatever the draw) and no cell holds two levels.
 template <bool FAST>
-__device__ __forceinline__ uint32_t quantize_one(float x, float rinv, uint32_t rnd, const unsigned char* lev,
-                                                 const float4* cell, uint32_t n_sym, uint32_t& idx_out)
+__device__ __forceinline__ uint32_t quantize_one(float x, float rinv, uint32_t rnd, const LdsPlan& L, uint32_t n_sym,
+                                                 uint32_t& idx_out)
 {
-    // u = min(|v| / ||v||, 1)
-    const float u = fminf(fabsf(x) * rinv, 1.0f);
+    float u = fabsf(x) * rinv;                          // |v| / ||v||
     uint32_t row;
     if (FAST) {
         const float um = fmaxf(u, __uint_as_float((uint32_t)kCellKey0 << kCellShift));
-        const float4 c = cell[(__float_as_uint(um) >> kCellShift) - kCellKey0];
-        row = (u >= c.x) ? __float_as_uint(c.z) : __float_as_uint(c.y);
+        const float2 c = L.cell[(__float_as_uint(um) >> kCellShift) - kCellKey0];
+        const uint32_t a = __float_as_uint(c.y);
+        row = (u >= c.x) ? (a >> 16) : (a & 0xFFFFu);
     } else {
-        row = level_row_general(lev, cell, u, n_sym);
+        u = fminf(u, 1.0f);
+        row = level_row_general(L, u, n_sym);
     }
-    const uint32_t sg = (__float_as_uint(x) >> 20) & (uint32_t)kLevRegion;   // sign selects the table half
-    const float4 t = *reinterpret_cast<const float4*>(lev + (row | sg));
+    const uint32_t sg = (__float_as_uint(x) >> L.sign_shift) & L.lev_stride;   // sign selects the table half
+    const float4 t = *reinterpret_cast<const float4*>(L.lev + (row | sg));
     // up with probability xi = (u - l_j) / (l_{j+1} - l_j):  r * gap < u - l_j, r = top 24 bits * 2^-24
     const float rr = (float)(rnd >> 8);                 // exact
     const bool up = rr * t.y < u - t.x;                 // t.y = gap * 2^-24 (exact scaling)
@@ -149,33 +155,37 @@ __device__ __forceinline__ uint32_t pack_row(uint32_t* stage, uint16_t* sub_row,
 }
 
 template <EncMode MODE>
-__global__ __launch_bounds__(1024) void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc,
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc,
                                                  EncodeArgs a)
 {
-    extern __shared__ __align__(16) uint32_t s_stage[];          // [waves][kStageWords]
-    __shared__ __align__(16) unsigned char s_lev[2 * kLevRegion];
-    __shared__ float4 s_cell[kCellsPad];
-    __shared__ double s_red[kMaxWaves];
-    __shared__ uint32_t s_words[kMaxWaves];
-    __shared__ __align__(4) uint16_t s_sub[kMaxWaves][kSubs];
-    __shared__ uint32_t s_misc[2];
-
+    extern __shared__ __align__(16) unsigned char s_all[];
     const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
     const int nwaves = (int)(blockDim.x >> 6);
     const uint32_t n_sym = tab->n_sym;
     const uint32_t k = (uint32_t)blockIdx.x % lay.K;    // worker fixed by the block, bucket by ticket
+
+    // LDS plan: [cell][lev + / lev -][sub-chunk ends][reduction scratch][one staging buffer per wave]
+    float2* s_cell = reinterpret_cast<float2*>(s_all);
+    unsigned char* s_lev = s_all + kCellsPad * sizeof(float2);
+    uint16_t (*s_sub)[kSubs] = reinterpret_cast<uint16_t (*)[kSubs]>(s_lev + 2 * a.lev_stride);
+    double* s_red = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(s_sub) + nwaves * kSubs * 2);
+    uint32_t* s_words = reinterpret_cast<uint32_t*>(s_red + kMaxWaves);
+    uint32_t* s_misc = s_words + kMaxWaves;
+    uint32_t* stage = reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(s_misc) + 32 + (size_t)w * a.stage_bytes);
+    LdsPlan L;
+    L.cell = s_cell; L.lev = s_lev; L.lev_stride = a.lev_stride; L.sign_shift = a.sign_shift;
 
     if (MODE != EncMode::QuantOnly) {
         if (tid == 0) s_misc[0] = atomicAdd(&a.tickets[k * kTicketStride], 1u) - a.ticket_base;
     }
     for (int i = tid; i < (int)n_sym; i += (int)blockDim.x) {
         reinterpret_cast<float4*>(s_lev)[i] = tab->lev2[0][i];
-        reinterpret_cast<float4*>(s_lev)[kSymMax + i] = tab->lev2[1][i];
+        reinterpret_cast<float4*>(s_lev + a.lev_stride)[i] = tab->lev2[1][i];
     }
     for (int i = tid; i < kCells; i += (int)blockDim.x) s_cell[i] = tab->cell[i];
-    uint32_t* stage = s_stage + (size_t)w * kStageWords;
     if (MODE != EncMode::QuantOnly) {
-        for (int q = lane; q < kStageWords / 4; q += kWave) reinterpret_cast<uint4*>(stage)[q] = make_uint4(0, 0, 0, 0);
+        for (uint32_t q = (uint32_t)lane; q < a.stage_bytes / 16; q += kWave)
+            reinterpret_cast<uint4*>(stage)[q] = make_uint4(0, 0, 0, 0);
     }
     __syncthreads();
 
@@ -193,6 +203,7 @@ __global__ __launch_bounds__(1024) void k_encode(Layout lay, const Tables* __res
     // ---- read the chunk once; norm of the bucket ------------------------------------------------
     float4 v[kRows];
     float n = 0.0f;
+    bool u_le_1 = true;
     if (MODE != EncMode::EncodeOnly) {
         const float* __restrict__ Vk = a.V + kbase;
         if (full && vec_ok) {
@@ -247,6 +258,7 @@ __global__ __launch_bounds__(1024) void k_encode(Layout lay, const Tables* __res
         n = (a.norm_kind == QGX_NORM_L2) ? (float)sqrt(tot) : (float)tot;
         if (a.norms_in) {
             const float forced = a.norms_in[(size_t)k * lay.NB + b];
+            u_le_1 = forced >= n;                                        // else |v| / norm may exceed 1
             n = (n == n && fabsf(n) <= 3.402823466e+38f) ? forced : n;   // a poisoned bucket stays rejected
         }
         const bool bucket_bad = !(fabsf(n) <= 3.402823466e+38f);
@@ -258,7 +270,7 @@ __global__ __launch_bounds__(1024) void k_encode(Layout lay, const Tables* __res
     }
     const float rinv = 1.0f / n;                       // one IEEE division per bucket
     const bool live = n > 0.0f;
-    const bool fast = full && live && vec_ok && (tab->cell_exact != 0u) && MODE != EncMode::EncodeOnly;
+    const bool fast = full && live && vec_ok && u_le_1 && (tab->cell_exact != 0u) && MODE != EncMode::EncodeOnly;
 
     // ---- per row: quantise, code, pack ----------------------------------------------------------
     uint32_t row_base = 0;                             // bits of this chunk written so far (wave-uniform)
@@ -268,10 +280,10 @@ __global__ __launch_bounds__(1024) void k_encode(Layout lay, const Tables* __res
             const uint32_t i0 = clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
             uint32_t rnd[4], e[4], idx[4];
             philox4x32_10(i0 >> 2, 0u, k, a.call_id, a.seed_lo, a.seed_hi, rnd);
-            e[0] = quantize_one<true>(v[r].x, rinv, rnd[0], s_lev, s_cell, n_sym, idx[0]);
-            e[1] = quantize_one<true>(v[r].y, rinv, rnd[1], s_lev, s_cell, n_sym, idx[1]);
-            e[2] = quantize_one<true>(v[r].z, rinv, rnd[2], s_lev, s_cell, n_sym, idx[2]);
-            e[3] = quantize_one<true>(v[r].w, rinv, rnd[3], s_lev, s_cell, n_sym, idx[3]);
+            e[0] = quantize_one<true>(v[r].x, rinv, rnd[0], L, n_sym, idx[0]);
+            e[1] = quantize_one<true>(v[r].y, rinv, rnd[1], L, n_sym, idx[1]);
+            e[2] = quantize_one<true>(v[r].z, rinv, rnd[2], L, n_sym, idx[2]);
+            e[3] = quantize_one<true>(v[r].w, rinv, rnd[3], L, n_sym, idx[3]);
             if (MODE == EncMode::QuantOnly) {
                 uint32_t pk = 0;
                 const float xs[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
@@ -313,7 +325,7 @@ __global__ __launch_bounds__(1024) void k_encode(Layout lay, const Tables* __res
                 for (int q = 0; q < 4; ++q) {
                     idx[q] = 0;
                     neg[q] = __float_as_uint(xs[q]) >> 31;
-                    if (live) (void)quantize_one<false>(xs[q], rinv, rnd[q], s_lev, s_cell, n_sym, idx[q]);
+                    if (live) (void)quantize_one<false>(xs[q], rinv, rnd[q], L, n_sym, idx[q]);
                 }
             }
             if (MODE == EncMode::QuantOnly) {
@@ -324,7 +336,7 @@ __global__ __launch_bounds__(1024) void k_encode(Layout lay, const Tables* __res
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     // E(idx, sign) from the table row of idx (its third word), nothing for a padded slot
-                    const float4 t = reinterpret_cast<const float4*>(s_lev)[idx[q] + neg[q] * kSymMax];
+                    const float4 t = *reinterpret_cast<const float4*>(s_lev + idx[q] * 16u + neg[q] * a.lev_stride);
                     e[q] = (i0 + (uint32_t)q < cend) ? __float_as_uint(t.z) : 0u;
                 }
                 row_base += pack_row(stage, &s_sub[w][4 * r], row_base, e, lane);
@@ -368,16 +380,23 @@ __global__ __launch_bounds__(1024) void k_encode(Layout lay, const Tables* __res
     for (uint32_t q = (uint32_t)lane; q < (words >> 2); q += kWave) dst[q] = src[q];
 }
 
+static size_t encode_lds_bytes(int waves, const EncodeArgs& a, bool with_stage)
+{
+    size_t n = kCellsPad * sizeof(float2) + 2 * (size_t)a.lev_stride + (size_t)waves * kSubs * 2 +
+               kMaxWaves * (sizeof(double) + sizeof(uint32_t)) + 32;
+    if (with_stage) n += (size_t)waves * a.stage_bytes;
+    return n;
+}
+
 template <EncMode MODE>
 static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a, hipStream_t st)
 {
     const int waves = (int)lay.waves_per_bucket;
-    const size_t lds = (MODE == EncMode::QuantOnly) ? 16 : (size_t)waves * kStageWords * sizeof(uint32_t);
+    const size_t lds = encode_lds_bytes(waves, a, MODE != EncMode::QuantOnly);
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_encode<MODE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           kMaxWaves * kStageWords * (int)sizeof(uint32_t));
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_done = true;
     }

@@ -40,10 +40,10 @@ struct Tables {
     // coordinate with sign sg between levels j and j+1 needs.  E(idx, sg) = code word of idx with the
     // sign bit appended (idx != 0), first-written bit in bit 0, total length << 16.
     float4 lev2[2][kSymMax];
-    // cell[c] = {B, a0, a1, 0} for the c-th 1/16-octave of u: a0 = byte offset in lev2 of the entry of
+    // cell[c] = {B, a0 | a1 << 16} for the c-th 1/16-octave of u: a0 = byte offset in lev2 of the row of
     // the last level <= the cell's lower edge; B = the level inside the cell (+inf if none), a1 = the
-    // entry to use when u >= B.  Exact only if no cell holds two levels (cell_exact).
-    float4 cell[kCellsPad];
+    // row to use when u >= B.  Exact only if no cell holds two levels (cell_exact).
+    float2 cell[kCellsPad];
     float lval[kSymMax];        // l_j
     float levels[kSymMax];      // the table as set or fitted (source of the ones above)
     uint32_t code[kSymMax];     // code word (first-written bit in bit 0) | length << 16, no sign
@@ -93,6 +93,10 @@ struct EncodeArgs {
     uint32_t ticket_base;       // value of every ticket counter before this launch
     uint32_t seed_lo, seed_hi, call_id;
     int norm_kind;
+    // LDS plan of the launch (bytes): [cell][lev: two sign halves lev_stride apart][sub][misc][stage x waves]
+    uint32_t lev_stride;        // power of two >= 16 * n_sym
+    uint32_t sign_shift;        // (bits of v) >> sign_shift puts the sign bit on lev_stride
+    uint32_t stage_bytes;       // per wave, multiple of 16, covers 4096 symbols of the longest code + sign
 };
 
 struct DecodeArgs {
@@ -105,6 +109,8 @@ struct DecodeArgs {
     float* Y;                   // [d] dual state (Half0 reads, Half1 updates)
     const float* anchor;        // [d] or null
     double* s_partial;          // [NC] per-chunk partial of S (Half1)
+    uint32_t stage_words;       // most words a chunk can take with the code in use (multiple of 4)
+    uint32_t stage_stride;      // words of one LDS staging buffer (padded layout plus slack)
 };
 
 hipError_t launch_build_tables(Tables* tab, hipStream_t st);

@@ -30,6 +30,7 @@ struct qgx_ctx {
     uint32_t epoch = 0;
     uint32_t ticket_count = 0;
     uint32_t n_sym = 0;
+    uint32_t max_code_len = 0;      // longest code word of the code in use (without the sign bit)
     bool levels_set = false, code_set = false, state_ready = false, has_anchor = false;
     const uint16_t* last_sub_end = nullptr;
     uint64_t worst_words = 0;
@@ -54,6 +55,19 @@ qgx_status fail(qgx_ctx* ctx, qgx_status st, const char* fmt, ...)
         hipError_t e_ = (call);                                                                        \
         if (e_ != hipSuccess) return fail((ctx), QGX_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
     } while (0)
+
+// Length of Elias' recursive (omega) code of N >= 1: one terminating bit plus every prefixed group.
+uint32_t omega_length(uint32_t N)
+{
+    uint32_t len = 1;
+    while (N > 1) {
+        uint32_t nb = 0;
+        for (uint32_t x = N; x; x >>= 1) ++nb;
+        len += nb;
+        N = nb - 1;
+    }
+    return len;
+}
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -218,6 +232,7 @@ qgx_status qgx_set_levels(qgx_ctx* ctx, const float* levels_host, uint32_t n_sym
     QGX_HIP(ctx, hipStreamSynchronize(st));
     ctx->n_sym = n_sym;
     ctx->levels_set = true;
+    if (ctx->cfg.code == QGX_CODE_ELIAS_OMEGA) ctx->max_code_len = omega_length(n_sym);
     return QGX_OK;
 }
 
@@ -258,6 +273,8 @@ qgx_status qgx_set_code_table(qgx_ctx* ctx, const uint8_t* code_len, const uint3
     QGX_HIP(ctx, launch_build_tables(ctx->d_tab, st));
     QGX_HIP(ctx, hipStreamSynchronize(st));
     ctx->code_set = true;
+    ctx->max_code_len = 0;
+    for (uint32_t j = 0; j < n_sym; ++j) ctx->max_code_len = code_len[j] > ctx->max_code_len ? code_len[j] : ctx->max_code_len;
     return QGX_OK;
 }
 
@@ -270,6 +287,14 @@ static qgx_status run_encode(qgx_ctx* ctx, EncMode mode, const float* V, uint32_
     a.V = V; a.norms_in = norms_in; a.norms_out = norms_out; a.sym_out = sym_out; a.sym_in = sym_in;
     a.seed_lo = (uint32_t)ctx->cfg.seed; a.seed_hi = (uint32_t)(ctx->cfg.seed >> 32); a.call_id = call_id;
     a.norm_kind = ctx->cfg.norm;
+    a.lev_stride = 16;
+    while (a.lev_stride < 16u * ctx->n_sym) a.lev_stride <<= 1;
+    a.sign_shift = 31;
+    while ((1u << (31 - a.sign_shift)) < a.lev_stride) --a.sign_shift;
+    {
+        const uint32_t words = (kChunk * (ctx->max_code_len + 1) + 31) / 32 + 4;
+        a.stage_bytes = (words + 3) / 4 * 16;
+    }
     if (mode != EncMode::QuantOnly) {
         a.chunk_off = out->chunk_off; a.sub_end = out->sub_end; a.payload = out->payload;
         a.cap_words = out->payload_words_per_worker;
@@ -319,8 +344,11 @@ qgx_status qgx_quantize_encode(qgx_ctx* ctx, const float* V, uint32_t call_id, c
     return run_encode(ctx, EncMode::Fused, V, call_id, norms_in, out->norms, nullptr, nullptr, out, stream);
 }
 
-static void fill_decode_args(DecodeArgs& a, const qgx_stream* cur, const qgx_stream* prev)
+static void fill_decode_args(const qgx_ctx* ctx, DecodeArgs& a, const qgx_stream* cur, const qgx_stream* prev)
 {
+    const uint32_t words = (kChunk * (ctx->max_code_len + 1) + 31) / 32;
+    a.stage_words = (words + 3) / 4 * 4;
+    a.stage_stride = (a.stage_words + a.stage_words / 32 + 8 + 3) / 4 * 4;
     a.norms = cur->norms; a.chunk_off = cur->chunk_off; a.sub_end = cur->sub_end; a.payload = cur->payload;
     a.cap_words = cur->payload_words_per_worker;
     if (prev) {
@@ -336,7 +364,7 @@ qgx_status qgx_decode(qgx_ctx* ctx, const qgx_stream* in, float* Vhat, void* str
     if (s == QGX_OK) s = need_levels(ctx);
     if (s != QGX_OK) return s;
     DecodeArgs a{};
-    fill_decode_args(a, in, nullptr);
+    fill_decode_args(ctx, a, in, nullptr);
     a.out = Vhat;
     QGX_HIP(ctx, launch_decode(DecMode::Decode, ctx->lay, ctx->d_tab, ctx->d_sc, a, (hipStream_t)stream));
     return QGX_OK;
@@ -349,7 +377,7 @@ qgx_status qgx_decode_average(qgx_ctx* ctx, const qgx_stream* in, float* mean, v
     if (s == QGX_OK) s = need_levels(ctx);
     if (s != QGX_OK) return s;
     DecodeArgs a{};
-    fill_decode_args(a, in, nullptr);
+    fill_decode_args(ctx, a, in, nullptr);
     a.out = mean;
     QGX_HIP(ctx, launch_decode(DecMode::Average, ctx->lay, ctx->d_tab, ctx->d_sc, a, (hipStream_t)stream));
     return QGX_OK;
@@ -398,12 +426,12 @@ qgx_status qgx_eg_step(qgx_ctx* ctx, int half, const qgx_stream* cur, const qgx_
     if (half == 0) {
         if (prev) return fail(ctx, QGX_ERR_ARG, "qgx_eg_step: prev must be NULL for half = 0");
         if (!X_out) return fail(ctx, QGX_ERR_ARG, "qgx_eg_step: X_out is required for half = 0");
-        fill_decode_args(a, cur, nullptr);
+        fill_decode_args(ctx, a, cur, nullptr);
         a.out = X_out;
         QGX_HIP(ctx, launch_decode(DecMode::Half0, ctx->lay, ctx->d_tab, ctx->d_sc, a, st));
         return QGX_OK;
     }
-    fill_decode_args(a, cur, prev);
+    fill_decode_args(ctx, a, cur, prev);
     a.s_partial = ctx->d_spartial;
     QGX_HIP(ctx, launch_decode(DecMode::Half1, ctx->lay, ctx->d_tab, ctx->d_sc, a, st));
     QGX_HIP(ctx, launch_finish_half1(ctx->lay, ctx->d_sc, ctx->d_spartial, ctx->d_Y, a.anchor, X_out, st));

@@ -78,7 +78,7 @@ static __device__ void build_tables_block(Tables* tab)
                 if (j + 3 < n_sym && lv[j + 2] < next) crowded = true;
             }
         }
-        tab->cell[c] = make_float4(B, __uint_as_float(j << 4), __uint_as_float(a1 << 4), 0.0f);
+        tab->cell[c] = make_float2(B, __uint_as_float((j << 4) | (a1 << 20)));
         if (crowded) tab->cell_exact = 0u;
     }
     // every 13-bit window that starts with code word j decodes to j
