@@ -75,7 +75,7 @@ __device__ __forceinline__ float take_symbol(const uint32_t* stage, const uint16
     const uint32_t wi = p >> 5;
     const uint32_t* wp = stage + staged(wi);
     const uint32_t win = __builtin_amdgcn_alignbit(wp[1], wp[0], p & 31u);
-    const uint32_t e = dlut[win & (uint32_t)(kDlut - 1)];
+    const uint32_t e = dlut[dlut_slot(win)];
     flags |= e;
     const uint32_t len = e & 15u, idx = e >> 4;
     const uint32_t nz = idx != 0u ? 1u : 0u;

@@ -19,9 +19,9 @@
 // (DPP) and every lane ORs its (at most 56) bits into the wave's LDS staging buffer.  Chunks are
 // placed in the payload in chunk order, so a workgroup needs the total length of all earlier buckets
 // of its worker: a decoupled look-back over per-bucket (flag, length) words gives it without a second
-// pass over V.  A workgroup's worker is fixed by its block index and its bucket comes from that
-// worker's atomic ticket, so every workgroup a waiting one depends on is already running; the wait is
-// bounded all the same.
+// pass over V.  A workgroup's worker is fixed by its block index and its buckets come from that
+// worker's atomic ticket, so every bucket a waiting workgroup depends on is held by a running
+// workgroup that needs nothing from later tickets; the wait is bounded all the same.
 #include "qgx_device.h"
 
 namespace qgx {
@@ -154,15 +154,67 @@ __device__ __forceinline__ uint32_t pack_row(uint32_t* stage, uint16_t* sub_row,
     return (uint32_t)__builtin_amdgcn_readlane((int)incl, kWave - 1);
 }
 
+struct ChunkGeom {            // one wave's share of a bucket
+    uint32_t c;               // chunk number
+    uint32_t clo, clen, cend; // first coordinate, length, one past the last
+    int nrows;                // rows of 256 coordinates that hold data
+    bool full;                // all 4096 coordinates present
+};
+
+__device__ __forceinline__ ChunkGeom chunk_geom(const Layout& lay, uint32_t b, int w)
+{
+    uint32_t lo, hi, c0;
+    if (lay.uniform_bucket) {                      // one segment: no table look-ups on the critical path
+        lo = b * lay.uniform_bucket;
+        hi = min(lo + lay.uniform_bucket, lay.d);
+        c0 = b * lay.waves_per_bucket;
+    } else {
+        lo = lay.bucket_start[b]; hi = lay.bucket_start[b + 1]; c0 = lay.bucket_chunk0[b];
+    }
+    ChunkGeom g;
+    g.c = c0 + (uint32_t)w;
+    g.clo = lo + (uint32_t)w * kChunk;
+    g.clen = g.clo < hi ? min((uint32_t)kChunk, hi - g.clo) : 0u;
+    g.cend = g.clo + g.clen;
+    g.nrows = (int)((g.clen + 255u) >> 8);
+    g.full = g.clen == (uint32_t)kChunk;
+    return g;
+}
+
+// Issues the loads of one chunk into registers (16 rows x 4 coordinates per lane).
+__device__ __forceinline__ void load_chunk(float4 (&v)[kRows], const float* __restrict__ Vk, const ChunkGeom& g,
+                                           bool vec_ok, int lane)
+{
+    if (g.full && vec_ok) {
+#pragma unroll
+        for (int r = 0; r < kRows; ++r)
+            v[r] = *reinterpret_cast<const float4*>(Vk + g.clo + (uint32_t)r * 256u + (uint32_t)lane * 4u);
+    } else {
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) {
+            const uint32_t i0 = g.clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i0 < g.cend) x.x = Vk[i0];
+            if (i0 + 1 < g.cend) x.y = Vk[i0 + 1];
+            if (i0 + 2 < g.cend) x.z = Vk[i0 + 2];
+            if (i0 + 3 < g.cend) x.w = Vk[i0 + 3];
+            v[r] = x;
+        }
+    }
+}
+
+// One workgroup per (worker, bucket).  Workgroups are short-lived on purpose: with five of them per
+// compute unit at different points of their life, the load, ticket and look-back latencies of one
+// overlap the arithmetic of the others (a persistent, lock-stepped variant measured slower).
 template <EncMode MODE>
-__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc,
-                                                 EncodeArgs a)
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5)))
+void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArgs a)
 {
     extern __shared__ __align__(16) unsigned char s_all[];
     const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
     const int nwaves = (int)(blockDim.x >> 6);
     const uint32_t n_sym = tab->n_sym;
-    const uint32_t k = (uint32_t)blockIdx.x % lay.K;    // worker fixed by the block, bucket by ticket
+    const uint32_t k = (uint32_t)blockIdx.x % lay.K;    // worker fixed by the block, buckets by ticket
 
     // LDS plan: [cell][lev + / lev -][sub-chunk ends][reduction scratch][one staging buffer per wave]
     float2* s_cell = reinterpret_cast<float2*>(s_all);
@@ -175,9 +227,8 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) void 
     LdsPlan L;
     L.cell = s_cell; L.lev = s_lev; L.lev_stride = a.lev_stride; L.sign_shift = a.sign_shift;
 
-    if (MODE != EncMode::QuantOnly) {
-        if (tid == 0) s_misc[0] = atomicAdd(&a.tickets[k * kTicketStride], 1u) - a.ticket_base;
-    }
+    // the ticket first: everything else that does not need the bucket number overlaps its latency
+    if (tid == 0) s_misc[2] = atomicAdd(a.tickets + k * kTicketStride, 1u) - a.ticket_base;
     for (int i = tid; i < (int)n_sym; i += (int)blockDim.x) {
         reinterpret_cast<float4*>(s_lev)[i] = tab->lev2[0][i];
         reinterpret_cast<float4*>(s_lev + a.lev_stride)[i] = tab->lev2[1][i];
@@ -187,197 +238,183 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) void 
         for (uint32_t q = (uint32_t)lane; q < a.stage_bytes / 16; q += kWave)
             reinterpret_cast<uint4*>(stage)[q] = make_uint4(0, 0, 0, 0);
     }
+    const uint32_t cell_exact = tab->cell_exact;
     __syncthreads();
 
-    const uint32_t b = (MODE != EncMode::QuantOnly) ? s_misc[0] : (uint32_t)blockIdx.x / lay.K;
-    const uint32_t lo = lay.bucket_start[b], hi = lay.bucket_start[b + 1];
-    const uint32_t c = lay.bucket_chunk0[b] + (uint32_t)w;
-    const uint32_t clo = lo + (uint32_t)w * kChunk;
-    const uint32_t clen = clo < hi ? min((uint32_t)kChunk, hi - clo) : 0u;
-    const uint32_t cend = clo + clen;
-    const int nrows = (int)((clen + 255u) >> 8);
     const size_t kbase = (size_t)k * lay.d;
     const bool vec_ok = (kbase & 3u) == 0;             // 16-byte aligned rows for this worker
-    const bool full = clen == (uint32_t)kChunk;
-
-    // ---- read the chunk once; norm of the bucket ------------------------------------------------
+    const float* __restrict__ Vk = (MODE != EncMode::EncodeOnly) ? a.V + kbase : nullptr;
+    const uint32_t b = s_misc[2];
+    if (b >= lay.NB) return;                           // cannot happen: one ticket per workgroup, NB per worker
+    const ChunkGeom g = chunk_geom(lay, b, w);
     float4 v[kRows];
-    float n = 0.0f;
-    bool u_le_1 = true;
-    if (MODE != EncMode::EncodeOnly) {
-        const float* __restrict__ Vk = a.V + kbase;
-        if (full && vec_ok) {
-#pragma unroll
-            for (int r = 0; r < kRows; ++r)
-                v[r] = *reinterpret_cast<const float4*>(Vk + clo + (uint32_t)r * 256u + (uint32_t)lane * 4u);
-        } else {
-#pragma unroll
-            for (int r = 0; r < kRows; ++r) {
-                const uint32_t i0 = clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
-                float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (i0 < cend) x.x = Vk[i0];
-                if (i0 + 1 < cend) x.y = Vk[i0 + 1];
-                if (i0 + 2 < cend) x.z = Vk[i0 + 2];
-                if (i0 + 3 < cend) x.w = Vk[i0 + 3];
-                v[r] = x;
-            }
-        }
-        // A non-finite coordinate shows in the reduced value itself: the binary64 sum of squares cannot
-        // overflow from finite binary32 inputs, and the maximum is taken on the magnitude bits.
-        double red;
-        if (a.norm_kind == QGX_NORM_L2) {
-            double acc0 = 0.0, acc1 = 0.0;
-#pragma unroll
-            for (int r = 0; r < kRows; ++r) {
-                acc0 = fma((double)v[r].x, (double)v[r].x, acc0);
-                acc1 = fma((double)v[r].y, (double)v[r].y, acc1);
-                acc0 = fma((double)v[r].z, (double)v[r].z, acc0);
-                acc1 = fma((double)v[r].w, (double)v[r].w, acc1);
-            }
-            red = wave_sum(acc0 + acc1);
-        } else {
-            uint32_t mx = 0;
-#pragma unroll
-            for (int r = 0; r < kRows; ++r) {
-                mx = max(mx, __float_as_uint(v[r].x) & 0x7FFFFFFFu);
-                mx = max(mx, __float_as_uint(v[r].y) & 0x7FFFFFFFu);
-                mx = max(mx, __float_as_uint(v[r].z) & 0x7FFFFFFFu);
-                mx = max(mx, __float_as_uint(v[r].w) & 0x7FFFFFFFu);
-            }
-#pragma unroll
-            for (int off = kWave / 2; off > 0; off >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, off, kWave));
-            red = (double)__uint_as_float(mx);          // inf or NaN bits survive the conversion
-        }
-        if (lane == 0) s_red[w] = red;
-        __syncthreads();
-        double tot = 0.0;
-        for (int i = 0; i < nwaves; ++i) {
-            if (a.norm_kind == QGX_NORM_L2) tot += s_red[i];
-            else tot = (s_red[i] > tot || s_red[i] != s_red[i]) ? s_red[i] : tot;
-        }
-        n = (a.norm_kind == QGX_NORM_L2) ? (float)sqrt(tot) : (float)tot;
-        if (a.norms_in) {
-            const float forced = a.norms_in[(size_t)k * lay.NB + b];
-            u_le_1 = forced >= n;                                        // else |v| / norm may exceed 1
-            n = (n == n && fabsf(n) <= 3.402823466e+38f) ? forced : n;   // a poisoned bucket stays rejected
-        }
-        const bool bucket_bad = !(fabsf(n) <= 3.402823466e+38f);
-        if (bucket_bad) n = 0.0f;
-        if (tid == 0) {
-            if (bucket_bad) raise_error(sc, QGX_EBIT_NONFINITE);
-            if (a.norms_out) a.norms_out[(size_t)k * lay.NB + b] = n;
-        }
-    }
-    const float rinv = 1.0f / n;                       // one IEEE division per bucket
-    const bool live = n > 0.0f;
-    const bool fast = full && live && vec_ok && u_le_1 && (tab->cell_exact != 0u) && MODE != EncMode::EncodeOnly;
+    if (MODE != EncMode::EncodeOnly) load_chunk(v, Vk, g, vec_ok, lane);
+    {
 
-    // ---- per row: quantise, code, pack ----------------------------------------------------------
-    uint32_t row_base = 0;                             // bits of this chunk written so far (wave-uniform)
-    if (fast) {
+        // ---- norm of the bucket from the rows in registers ---------------------------------------
+        float n = 0.0f;
+        bool u_le_1 = true;
+        if (MODE != EncMode::EncodeOnly) {
+            // A non-finite coordinate shows in the reduced value itself: the binary64 sum of squares
+            // cannot overflow from finite binary32 inputs, and the maximum is taken on magnitude bits.
+            double red;
+            if (a.norm_kind == QGX_NORM_L2) {
+                double acc0 = 0.0, acc1 = 0.0;
 #pragma unroll
-        for (int r = 0; r < kRows; ++r) {
-            const uint32_t i0 = clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
-            uint32_t rnd[4], e[4], idx[4];
-            philox4x32_10(i0 >> 2, 0u, k, a.call_id, a.seed_lo, a.seed_hi, rnd);
-            e[0] = quantize_one<true>(v[r].x, rinv, rnd[0], L, n_sym, idx[0]);
-            e[1] = quantize_one<true>(v[r].y, rinv, rnd[1], L, n_sym, idx[1]);
-            e[2] = quantize_one<true>(v[r].z, rinv, rnd[2], L, n_sym, idx[2]);
-            e[3] = quantize_one<true>(v[r].w, rinv, rnd[3], L, n_sym, idx[3]);
-            if (MODE == EncMode::QuantOnly) {
-                uint32_t pk = 0;
-                const float xs[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
-#pragma unroll
-                for (int q = 0; q < 4; ++q) pk |= (idx[q] | ((__float_as_uint(xs[q]) >> 31) << 7)) << (8 * q);
-                *reinterpret_cast<uint32_t*>(a.sym_out + kbase + i0) = pk;
+                for (int r = 0; r < kRows; ++r) {
+                    acc0 = fma((double)v[r].x, (double)v[r].x, acc0);
+                    acc1 = fma((double)v[r].y, (double)v[r].y, acc1);
+                    acc0 = fma((double)v[r].z, (double)v[r].z, acc0);
+                    acc1 = fma((double)v[r].w, (double)v[r].w, acc1);
+                }
+                red = wave_sum(acc0 + acc1);
             } else {
-                row_base += pack_row(stage, &s_sub[w][4 * r], row_base, e, lane);
+                uint32_t mx = 0;
+#pragma unroll
+                for (int r = 0; r < kRows; ++r) {
+                    mx = max(mx, __float_as_uint(v[r].x) & 0x7FFFFFFFu);
+                    mx = max(mx, __float_as_uint(v[r].y) & 0x7FFFFFFFu);
+                    mx = max(mx, __float_as_uint(v[r].z) & 0x7FFFFFFFu);
+                    mx = max(mx, __float_as_uint(v[r].w) & 0x7FFFFFFFu);
+                }
+#pragma unroll
+                for (int off = kWave / 2; off > 0; off >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, off, kWave));
+                red = (double)__uint_as_float(mx);      // inf or NaN bits survive the conversion
+            }
+            if (lane == 0) s_red[w] = red;
+            __syncthreads();
+            double tot = 0.0;
+            for (int i = 0; i < nwaves; ++i) {
+                if (a.norm_kind == QGX_NORM_L2) tot += s_red[i];
+                else tot = (s_red[i] > tot || s_red[i] != s_red[i]) ? s_red[i] : tot;
+            }
+            n = (a.norm_kind == QGX_NORM_L2) ? (float)sqrt(tot) : (float)tot;
+            if (a.norms_in) {
+                const float forced = a.norms_in[(size_t)k * lay.NB + b];
+                u_le_1 = forced >= n;                                        // else |v| / norm may exceed 1
+                n = (n == n && fabsf(n) <= 3.402823466e+38f) ? forced : n;   // a poisoned bucket stays rejected
+            }
+            const bool bucket_bad = !(fabsf(n) <= 3.402823466e+38f);
+            if (bucket_bad) n = 0.0f;
+            if (tid == 0) {
+                if (bucket_bad) raise_error(sc, QGX_EBIT_NONFINITE);
+                if (a.norms_out) a.norms_out[(size_t)k * lay.NB + b] = n;
             }
         }
-    } else {
-#pragma unroll 1
-        for (int r = 0; r < nrows; ++r) {
-            const uint32_t i0 = clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
-            uint32_t e[4], idx[4], neg[4];
-            if (MODE == EncMode::EncodeOnly) {
-                const uint8_t* __restrict__ Sk = a.sym_in + kbase;
-                bool unknown = false;
+        const float rinv = 1.0f / n;                   // one IEEE division per bucket
+        const bool live = n > 0.0f;
+        const bool fast = g.full && live && vec_ok && u_le_1 && (cell_exact != 0u) && MODE != EncMode::EncodeOnly;
+
+        // ---- per row: quantise, code, pack -------------------------------------------------------
+        uint32_t row_base = 0;                         // bits of this chunk written so far (wave-uniform)
+        if (fast) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const uint32_t by = (i0 + (uint32_t)q < cend) ? (uint32_t)Sk[i0 + q] : 0u;
-                    idx[q] = by & 0x7Fu;
-                    neg[q] = by >> 7;
-                    if (idx[q] >= n_sym) { idx[q] = 0; unknown = true; }
-                }
-                if (__any(unknown) && lane == 0) raise_error(sc, QGX_EBIT_STREAM);
-            } else {
-                uint32_t rnd[4];
+            for (int r = 0; r < kRows; ++r) {
+                const uint32_t i0 = g.clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
+                uint32_t rnd[4], e[4], idx[4];
                 philox4x32_10(i0 >> 2, 0u, k, a.call_id, a.seed_lo, a.seed_hi, rnd);
-                // the register copy is indexed by compile-time row numbers only: this path reads the row again
-                const float* __restrict__ Vk = a.V + kbase;
-                float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (i0 < cend) x.x = Vk[i0];
-                if (i0 + 1 < cend) x.y = Vk[i0 + 1];
-                if (i0 + 2 < cend) x.z = Vk[i0 + 2];
-                if (i0 + 3 < cend) x.w = Vk[i0 + 3];
-                const float xs[4] = {x.x, x.y, x.z, x.w};
+                e[0] = quantize_one<true>(v[r].x, rinv, rnd[0], L, n_sym, idx[0]);
+                e[1] = quantize_one<true>(v[r].y, rinv, rnd[1], L, n_sym, idx[1]);
+                e[2] = quantize_one<true>(v[r].z, rinv, rnd[2], L, n_sym, idx[2]);
+                e[3] = quantize_one<true>(v[r].w, rinv, rnd[3], L, n_sym, idx[3]);
+                if (MODE == EncMode::QuantOnly) {
+                    uint32_t pk = 0;
+                    const float xs[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    idx[q] = 0;
-                    neg[q] = __float_as_uint(xs[q]) >> 31;
-                    if (live) (void)quantize_one<false>(xs[q], rinv, rnd[q], L, n_sym, idx[q]);
+                    for (int q = 0; q < 4; ++q) pk |= (idx[q] | ((__float_as_uint(xs[q]) >> 31) << 7)) << (8 * q);
+                    *reinterpret_cast<uint32_t*>(a.sym_out + kbase + i0) = pk;
+                } else {
+                    row_base += pack_row(stage, &s_sub[w][4 * r], row_base, e, lane);
                 }
             }
-            if (MODE == EncMode::QuantOnly) {
+        } else {
+#pragma unroll 1
+            for (int r = 0; r < g.nrows; ++r) {
+                const uint32_t i0 = g.clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
+                uint32_t e[4], idx[4], neg[4];
+                if (MODE == EncMode::EncodeOnly) {
+                    const uint8_t* __restrict__ Sk = a.sym_in + kbase;
+                    bool unknown = false;
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    if (i0 + (uint32_t)q < cend) a.sym_out[kbase + i0 + q] = (uint8_t)(idx[q] | (neg[q] << 7));
-            } else {
+                    for (int q = 0; q < 4; ++q) {
+                        const uint32_t by = (i0 + (uint32_t)q < g.cend) ? (uint32_t)Sk[i0 + q] : 0u;
+                        idx[q] = by & 0x7Fu;
+                        neg[q] = by >> 7;
+                        if (idx[q] >= n_sym) { idx[q] = 0; unknown = true; }
+                    }
+                    if (__any(unknown) && lane == 0) raise_error(sc, QGX_EBIT_STREAM);
+                } else {
+                    uint32_t rnd[4];
+                    philox4x32_10(i0 >> 2, 0u, k, a.call_id, a.seed_lo, a.seed_hi, rnd);
+                    // the register copy is indexed by compile-time row numbers only: this path reads the row again
+                    float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (i0 < g.cend) x.x = Vk[i0];
+                    if (i0 + 1 < g.cend) x.y = Vk[i0 + 1];
+                    if (i0 + 2 < g.cend) x.z = Vk[i0 + 2];
+                    if (i0 + 3 < g.cend) x.w = Vk[i0 + 3];
+                    const float xs[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    // E(idx, sign) from the table row of idx (its third word), nothing for a padded slot
-                    const float4 t = *reinterpret_cast<const float4*>(s_lev + idx[q] * 16u + neg[q] * a.lev_stride);
-                    e[q] = (i0 + (uint32_t)q < cend) ? __float_as_uint(t.z) : 0u;
+                    for (int q = 0; q < 4; ++q) {
+                        idx[q] = 0;
+                        neg[q] = __float_as_uint(xs[q]) >> 31;
+                        if (live) (void)quantize_one<false>(xs[q], rinv, rnd[q], L, n_sym, idx[q]);
+                    }
                 }
-                row_base += pack_row(stage, &s_sub[w][4 * r], row_base, e, lane);
+                if (MODE == EncMode::QuantOnly) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (i0 + (uint32_t)q < g.cend) a.sym_out[kbase + i0 + q] = (uint8_t)(idx[q] | (neg[q] << 7));
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        // E(idx, sign) from the table row of idx (its third word), nothing for a padded slot
+                        const float4 t = *reinterpret_cast<const float4*>(s_lev + idx[q] * 16u + neg[q] * a.lev_stride);
+                        e[q] = (i0 + (uint32_t)q < g.cend) ? __float_as_uint(t.z) : 0u;
+                    }
+                    row_base += pack_row(stage, &s_sub[w][4 * r], row_base, e, lane);
+                }
+            }
+        }
+
+        // ---- sizes, ordered offsets, flush ---------------------------------------------------------
+        const uint32_t total_bits = row_base;
+        uint32_t words = (total_bits + 31u) >> 5;
+        words = (words + (kAlignWords - 1)) & ~(uint32_t)(kAlignWords - 1);
+        if (MODE != EncMode::QuantOnly) {
+            if (lane >= 4 * g.nrows) s_sub[w][lane] = (uint16_t)total_bits;
+            if (lane == 0) s_words[w] = words;
+        }
+        if (MODE != EncMode::QuantOnly) {
+            __syncthreads();
+            uint32_t bucket_words = 0, wave_excl = 0;
+            for (int i = 0; i < nwaves; ++i) {
+                if (i == w) wave_excl = bucket_words;
+                bucket_words += s_words[i];
+            }
+            if (w == 0) {
+                const uint32_t excl = lookback_exclusive(a.scan_state + (size_t)k * lay.NB, b, bucket_words, a.epoch, sc);
+                if (lane == 0) s_misc[1] = excl;
+            }
+            __syncthreads();
+            if (g.clen != 0) {
+                const uint32_t off = s_misc[1] + wave_excl;
+                if (lane == 0) {
+                    a.chunk_off[(size_t)k * (lay.NC + 1) + g.c] = off;
+                    if (g.c + 1 == lay.NC) a.chunk_off[(size_t)k * (lay.NC + 1) + lay.NC] = off + words;
+                }
+                if (lane < 32)
+                    reinterpret_cast<uint32_t*>(a.sub_end + ((size_t)k * lay.NC + g.c) * kSubs)[lane] =
+                        reinterpret_cast<const uint32_t*>(s_sub[w])[lane];
+                if ((uint64_t)off + words > a.cap_words) {
+                    if (lane == 0) raise_error(sc, QGX_EBIT_CAPACITY);
+                } else {
+                    uint4* __restrict__ dst = reinterpret_cast<uint4*>(a.payload + (size_t)k * a.cap_words + off);
+                    uint4* src = reinterpret_cast<uint4*>(stage);
+                    for (uint32_t q = (uint32_t)lane; q < (words >> 2); q += kWave) dst[q] = src[q];
+                }
             }
         }
     }
-    if (MODE == EncMode::QuantOnly) return;
-
-    // ---- sizes, ordered offsets, flush ----------------------------------------------------------
-    const uint32_t total_bits = row_base;
-    uint32_t words = (total_bits + 31u) >> 5;
-    words = (words + (kAlignWords - 1)) & ~(uint32_t)(kAlignWords - 1);
-    if (lane >= 4 * nrows) s_sub[w][lane] = (uint16_t)total_bits;
-    if (lane == 0) s_words[w] = words;
-    __syncthreads();
-    uint32_t bucket_words = 0, wave_excl = 0;
-    for (int i = 0; i < nwaves; ++i) {
-        if (i == w) wave_excl = bucket_words;
-        bucket_words += s_words[i];
-    }
-    if (w == 0) {
-        const uint32_t excl = lookback_exclusive(a.scan_state + (size_t)k * lay.NB, b, bucket_words, a.epoch, sc);
-        if (lane == 0) s_misc[1] = excl;
-    }
-    __syncthreads();
-    if (clen == 0) return;
-    const uint32_t off = s_misc[1] + wave_excl;
-    if (lane == 0) {
-        a.chunk_off[(size_t)k * (lay.NC + 1) + c] = off;
-        if (c + 1 == lay.NC) a.chunk_off[(size_t)k * (lay.NC + 1) + lay.NC] = off + words;
-    }
-    if (lane < 32)
-        reinterpret_cast<uint32_t*>(a.sub_end + ((size_t)k * lay.NC + c) * kSubs)[lane] =
-            reinterpret_cast<const uint32_t*>(s_sub[w])[lane];
-    if ((uint64_t)off + words > a.cap_words) {
-        if (lane == 0) raise_error(sc, QGX_EBIT_CAPACITY);
-        return;
-    }
-    uint4* __restrict__ dst = reinterpret_cast<uint4*>(a.payload + (size_t)k * a.cap_words + off);
-    const uint4* src = reinterpret_cast<const uint4*>(stage);
-    for (uint32_t q = (uint32_t)lane; q < (words >> 2); q += kWave) dst[q] = src[q];
 }
 
 static size_t encode_lds_bytes(int waves, const EncodeArgs& a, bool with_stage)
@@ -389,7 +426,8 @@ static size_t encode_lds_bytes(int waves, const EncodeArgs& a, bool with_stage)
 }
 
 template <EncMode MODE>
-static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a, hipStream_t st)
+static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a, hipStream_t st,
+                              uint32_t* tickets_per_worker)
 {
     const int waves = (int)lay.waves_per_bucket;
     const size_t lds = encode_lds_bytes(waves, a, MODE != EncMode::QuantOnly);
@@ -400,17 +438,18 @@ static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc,
         if (e != hipSuccess) return e;
         attr_done = true;
     }
+    *tickets_per_worker = lay.NB;                      // one workgroup, one ticket per bucket
     hipLaunchKernelGGL(k_encode<MODE>, dim3(lay.K * lay.NB), dim3(waves * kWave), lds, st, lay, tab, sc, a);
     return hipGetLastError();
 }
 
 hipError_t launch_encode(EncMode mode, const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a,
-                         hipStream_t st)
+                         hipStream_t st, uint32_t* tickets_per_worker)
 {
     switch (mode) {
-        case EncMode::Fused: return launch_mode<EncMode::Fused>(lay, tab, sc, a, st);
-        case EncMode::QuantOnly: return launch_mode<EncMode::QuantOnly>(lay, tab, sc, a, st);
-        default: return launch_mode<EncMode::EncodeOnly>(lay, tab, sc, a, st);
+        case EncMode::Fused: return launch_mode<EncMode::Fused>(lay, tab, sc, a, st, tickets_per_worker);
+        case EncMode::QuantOnly: return launch_mode<EncMode::QuantOnly>(lay, tab, sc, a, st, tickets_per_worker);
+        default: return launch_mode<EncMode::EncodeOnly>(lay, tab, sc, a, st, tickets_per_worker);
     }
 }
 

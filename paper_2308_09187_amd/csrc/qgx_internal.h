@@ -34,6 +34,16 @@ constexpr int kLevRegion = kSymMax * 16;                // bytes between the two
 constexpr int kDlutBits = kMaxCode;       // decode window
 constexpr int kDlut = 1 << kDlutBits;     // 8192 entries
 
+// Slot of a 13-bit window in the decode table.  The first bits of a window are the length prefix of
+// a code word and take few values, so the LDS bank (bits 1..5 of the slot) is mixed with window bits
+// 6..10, which hold the digits of the symbol.  A bijection: only low bits change, by a function of
+// higher bits.
+__host__ __device__ inline uint32_t dlut_slot(uint32_t window)
+{
+    const uint32_t w = window & (uint32_t)(kDlut - 1);
+    return w ^ ((w >> 5) & 0x3Eu);
+}
+
 // Device-resident tables: rebuilt on the device whenever the level table or the code changes.
 struct Tables {
     // lev2[sg][j] = {l_j, (l_{j+1}-l_j)*2^-24, E(j, sg), E(j+1, sg)}: everything the rounding of a
@@ -51,7 +61,7 @@ struct Tables {
     uint32_t code_kind;
     uint32_t cell_exact;
     uint32_t pad_;
-    uint16_t dlut[kDlut];       // next 13 stream bits -> idx << 4 | length; 0xFFFF = no code word
+    uint16_t dlut[kDlut];       // dlut[dlut_slot(next 13 stream bits)] = idx << 4 | length; 0xFFFF = no code word
 };
 
 // Scalars of the iteration; lives in device memory, read by kernels, copied out on request.
@@ -72,6 +82,7 @@ struct Layout {                 // device pointers into one allocation
     const uint32_t* chunk_bucket;   // [NC]
     uint32_t NB, NC, K, d;
     uint32_t waves_per_bucket;      // ceil(bucket / kChunk)
+    uint32_t uniform_bucket;        // bucket size if there is one segment (offsets are then arithmetic), else 0
 };
 
 enum class EncMode { Fused, QuantOnly, EncodeOnly };
@@ -114,8 +125,9 @@ struct DecodeArgs {
 };
 
 hipError_t launch_build_tables(Tables* tab, hipStream_t st);
+// tickets_per_worker: how far the launch advances every worker's ticket counter
 hipError_t launch_encode(EncMode mode, const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a,
-                         hipStream_t st);
+                         hipStream_t st, uint32_t* tickets_per_worker);
 hipError_t launch_decode(DecMode mode, const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a,
                          hipStream_t st);
 hipError_t launch_finish_half1(const Layout& lay, Scalars* sc, const double* s_partial, const float* Y,

@@ -165,6 +165,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     uint32_t max_len = 0;
     for (uint32_t b = 0; b < NB; ++b) max_len = bstart[b + 1] - bstart[b] > max_len ? bstart[b + 1] - bstart[b] : max_len;
     c->lay.waves_per_bucket = (max_len + kChunk - 1) / kChunk;
+    c->lay.uniform_bucket = c->seg.size() == 1 ? cfg->bucket : 0u;
     c->h_groups = histogram_groups(c->lay);
 
     bool ok = true;
@@ -302,14 +303,14 @@ static qgx_status run_encode(qgx_ctx* ctx, EncMode mode, const float* V, uint32_
         ctx->epoch = (ctx->epoch + 1u) & 0x3FFFFFFFu;
         if (ctx->epoch == 0) ctx->epoch = 1;
         a.epoch = ctx->epoch;
-        a.ticket_base = ctx->ticket_count;
-        a.tickets = ctx->d_tickets;
     }
-    QGX_HIP(ctx, launch_encode(mode, ctx->lay, ctx->d_tab, ctx->d_sc, a, (hipStream_t)stream));
-    if (mode != EncMode::QuantOnly) {
-        ctx->ticket_count += ctx->lay.NB;
-        ctx->last_sub_end = out->sub_end;
-    }
+    a.ticket_base = ctx->ticket_count;
+    a.tickets = ctx->d_tickets;
+    uint32_t groups = 0;
+    hipError_t le = launch_encode(mode, ctx->lay, ctx->d_tab, ctx->d_sc, a, (hipStream_t)stream, &groups);
+    if (le != hipSuccess) return fail(ctx, QGX_ERR_HIP, "encode launch: %s", hipGetErrorString(le));
+    ctx->ticket_count += groups;
+    if (mode != EncMode::QuantOnly) ctx->last_sub_end = out->sub_end;
     return QGX_OK;
 }
 

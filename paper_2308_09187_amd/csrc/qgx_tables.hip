@@ -88,7 +88,7 @@ static __device__ void build_tables_block(Tables* tab)
         if (len == 0 || len > (uint32_t)kMaxCode) continue;
         const uint32_t reps = 1u << (kDlutBits - len);
         for (uint32_t s = (uint32_t)tid; s < reps; s += (uint32_t)nt)
-            tab->dlut[bits | (s << len)] = (uint16_t)((j << 4) | len);
+            tab->dlut[dlut_slot(bits | (s << len))] = (uint16_t)((j << 4) | len);
     }
     __syncthreads();
 }
