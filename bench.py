@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-logd", type=int, default=23, help="log2 of coordinates per worker in the oracle sample")
     ap.add_argument("--full-iteration", action="store_true", help="also time encode + second half-step")
+    ap.add_argument("--placement", choices=["slotted", "compact"], default="slotted",
+                    help="chunk placement of the coded streams handed from the encoder to the update kernel")
     return ap.parse_args()
 
 
@@ -94,7 +96,8 @@ def main():
     ctx.fit_levels(V, args.n_sym, 4096, sweeps=10)
     levels = ctx.get_levels()
     ctx.state_init(None)
-    a, b = ctx.new_stream(), ctx.new_stream()
+    slotted = args.placement == "slotted"
+    a, b = ctx.new_stream(slotted=slotted), ctx.new_stream(slotted=slotted)
     Xh = torch.empty(d, dtype=torch.float32, device="cuda")
 
     def step(i, ev=None):
@@ -126,8 +129,8 @@ def main():
     ms_step = wall * 1e3 / args.steps
     enc_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
     upd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
-    h_off = a.chunk_off.cpu().numpy().view(np.uint32)
-    words = int(h_off[:, ctx.NC].astype(np.int64).sum())
+    h_bits = a.sub_end.cpu().numpy().view(np.uint16)[:, :, 63].astype(np.int64)
+    words = int((((h_bits + 31) // 32 + 3) // 4 * 4).sum())
     bits = ctx.scalars(want_bits=True)["total_bits"]
     side_bytes = K * ((ctx.NC + 1) * 4 + ctx.NC * 128 + ctx.NB * 4)
     stream_bytes = words * 4 + side_bytes
@@ -143,8 +146,8 @@ def main():
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "K=%d x d=2^%d Student-t(3)*1e-2, bucket %d, L2, %d-symbol fitted table, Elias-omega; "
-                               "step = fused CODE.Q + fused decode/average/half-step%s"
-                               % (K, args.logd, args.bucket, args.n_sym,
+                               "%s chunk placement; step = fused CODE.Q + fused decode/average/half-step%s"
+                               % (K, args.logd, args.bucket, args.n_sym, args.placement,
                                   " + CODE.Q + second half-step" if args.full_iteration else ""),
                    "K": K, "d": d, "bucket": args.bucket, "n_sym": args.n_sym,
                    "bits_per_coordinate": bits / float(K * d), "stream_bytes": stream_bytes},

@@ -37,6 +37,13 @@
  *     payload   [K][payload_words_per_worker]
  *   Psi is Elias' recursive (omega) code of idx+1 (QGX_CODE_ELIAS_OMEGA), or a caller-supplied
  *   prefix code table (QGX_CODE_TABLE).
+ *   Two placements of the chunks inside a worker's payload:
+ *     compact (slot_words = 0): chunk_off is the exclusive scan of the chunk sizes in chunk order, the
+ *       payload has no gaps and chunk_off[k][NC] is the number of words used: the form to ship;
+ *     slotted (slot_words > 0): chunk c starts at c * slot_words, slot_words = what qgx_slot_words
+ *       reports; no workgroup waits for another, so coding is faster; the bits of every chunk are the
+ *       same as in the compact form, and qgx_compact turns one into the other.
+ *   A chunk's size in words is always ceil(sub_end[k][c][63] / 32) rounded up to a multiple of 4.
  */
 #ifndef QGX_H
 #define QGX_H
@@ -94,6 +101,7 @@ typedef struct {
     uint16_t* sub_end;                  /* [K][NC][64] */
     uint32_t* payload;                  /* [K][payload_words_per_worker] */
     uint64_t payload_words_per_worker;  /* multiple of 4 */
+    uint64_t slot_words;                /* 0 = compact placement; else the fixed chunk slot (see above) */
 } qgx_stream;
 
 /* Creates a context on the current device: validates the configuration, builds the bucket and chunk
@@ -105,6 +113,14 @@ void qgx_destroy(qgx_ctx* ctx);
  * words per worker that can never overflow (14 bits per coordinate plus chunk padding). */
 qgx_status qgx_stream_sizes(const qgx_ctx* ctx, uint64_t* n_buckets, uint64_t* n_chunks,
                             uint64_t* worst_case_payload_words);
+
+/* The chunk slot of the slotted placement for the level table and code in use: the words a full chunk
+ * can take at most.  A slotted stream needs payload_words_per_worker >= n_chunks * slot_words. */
+qgx_status qgx_slot_words(const qgx_ctx* ctx, uint64_t* slot_words);
+
+/* Rewrites a slotted stream as a compact one (same bits per chunk, exclusive-scan offsets).
+ * `out` must be compact (slot_words = 0) and may not alias `in`. */
+qgx_status qgx_compact(qgx_ctx* ctx, const qgx_stream* in, qgx_stream* out, void* stream);
 
 /* Level table l of Definition 1: levels_host HOST [n_sym], 2 <= n_sym <= QGX_MAX_SYM,
  * 0 = l[0] < ... < l[n_sym-1] = 1 (QGX_ERR_LEVELS otherwise).  Synchronises `stream`. */

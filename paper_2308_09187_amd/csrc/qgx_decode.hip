@@ -28,15 +28,18 @@ struct ChunkRef {            // where one worker's chunk lives and how long it i
     uint32_t words;          // multiple of 4, 0 when the tables are inconsistent
 };
 
+// A chunk's size comes from its bit length (last sub-chunk entry), so compact and slotted
+// placements read alike; its start comes from the offset table.
 __device__ __forceinline__ ChunkRef chunk_ref(const uint32_t* payload, uint64_t cap, const uint32_t* chunk_off,
-                                              uint32_t k, uint32_t c, uint32_t NC, uint32_t max_words, Scalars* sc)
+                                              const uint16_t* sub_end, uint32_t k, uint32_t c, uint32_t NC,
+                                              uint32_t max_words, Scalars* sc)
 {
     const uint32_t off = chunk_off[(size_t)k * (NC + 1) + c];
-    const uint32_t end = chunk_off[(size_t)k * (NC + 1) + c + 1];
+    const uint32_t bits = sub_end[((size_t)k * NC + c) * kSubs + (kSubs - 1)];
     ChunkRef r;
     r.src = reinterpret_cast<const uint4*>(payload + (size_t)k * cap + off);
-    r.words = end - off;
-    if (end < off || r.words > max_words || (off & 3u) || (r.words & 3u) || (uint64_t)end > cap) {
+    r.words = (((bits + 31u) >> 5) + 3u) & ~3u;
+    if (r.words > max_words || (off & 3u) || (uint64_t)off + r.words > cap) {
         if (lane_id() == 0) raise_error(sc, QGX_EBIT_STREAM);
         r.words = 0;
     }
@@ -138,7 +141,7 @@ __global__ __launch_bounds__(kDecWaves * kWave) __attribute__((amdgpu_waves_per_
     bool malformed = false;
 
     uint4 pre[kPre];
-    ChunkRef cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, k_first, c, lay.NC, stage_words, sc);
+    ChunkRef cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, a.sub_end, k_first, c, lay.NC, stage_words, sc);
     prefetch_chunk(cr, pre);
 
     for (uint32_t kk = 0; kk < k_count; ++kk) {
@@ -146,13 +149,13 @@ __global__ __launch_bounds__(kDecWaves * kWave) __attribute__((amdgpu_waves_per_
         commit_chunk(stage, pre, stage_words);
         if constexpr (MODE == DecMode::Half1) {
             if (have_prev) {                         // the previous half-step's chunk goes through the same registers
-                ChunkRef cp = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, k, c, lay.NC, stage_words, sc);
+                ChunkRef cp = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, a.sub_end_p, k, c, lay.NC, stage_words, sc);
                 prefetch_chunk(cp, pre);
                 commit_chunk(stage_p, pre, stage_words);
             }
         }
         if (kk + 1 < k_count) {                      // next worker's chunk: in flight while this one is parsed
-            cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, k + 1, c, lay.NC, stage_words, sc);
+            cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, a.sub_end, k + 1, c, lay.NC, stage_words, sc);
             prefetch_chunk(cr, pre);
         }
         const uint16_t* se = a.sub_end + ((size_t)k * lay.NC + c) * kSubs;
@@ -374,6 +377,71 @@ __global__ __launch_bounds__(256) void k_sum_bits(uint64_t n_chunks, const uint1
 hipError_t launch_sum_bits(const Layout& lay, const uint16_t* sub_end, Scalars* sc, hipStream_t st)
 {
     hipLaunchKernelGGL(k_sum_bits, dim3(1), dim3(256), 0, st, (uint64_t)lay.K * lay.NC, sub_end, sc);
+    return hipGetLastError();
+}
+
+// ---- slotted -> compact ---------------------------------------------------------------------------
+// One workgroup per worker scans the chunk sizes (from the bit lengths) into exclusive offsets; then
+// one wave per chunk copies its words.
+__global__ __launch_bounds__(1024) void k_compact_offsets(uint32_t NC, const uint16_t* __restrict__ sub_end,
+                                                          uint32_t* __restrict__ out_off, uint64_t out_cap, Scalars* sc)
+{
+    __shared__ uint32_t s_part[1024];
+    const uint32_t k = blockIdx.x, tid = threadIdx.x;
+    const uint32_t per = (NC + 1023u) / 1024u;
+    const uint32_t c0 = tid * per, c1 = min(c0 + per, NC);
+    uint32_t sum = 0;
+    for (uint32_t c = c0; c < c1; ++c) {
+        const uint32_t bits = sub_end[((size_t)k * NC + c) * kSubs + (kSubs - 1)];
+        sum += (((bits + 31u) >> 5) + 3u) & ~3u;
+    }
+    s_part[tid] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t run = 0;
+        for (int i = 0; i < 1024; ++i) { const uint32_t t = s_part[i]; s_part[i] = run; run += t; }
+        out_off[(size_t)k * (NC + 1) + NC] = run;
+        if ((uint64_t)run > out_cap) raise_error(sc, QGX_EBIT_CAPACITY);
+    }
+    __syncthreads();
+    uint32_t run = s_part[tid];
+    for (uint32_t c = c0; c < c1; ++c) {
+        out_off[(size_t)k * (NC + 1) + c] = run;
+        const uint32_t bits = sub_end[((size_t)k * NC + c) * kSubs + (kSubs - 1)];
+        run += (((bits + 31u) >> 5) + 3u) & ~3u;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_compact_copy(uint32_t NC, uint32_t K, const uint16_t* __restrict__ sub_end,
+                                                      const uint32_t* __restrict__ in_off, const uint32_t* __restrict__ in_payload,
+                                                      uint64_t in_cap, const uint32_t* __restrict__ out_off,
+                                                      uint32_t* __restrict__ out_payload, uint64_t out_cap, Scalars* sc)
+{
+    const uint32_t g = blockIdx.x * (blockDim.x >> 6) + (uint32_t)wave_id();
+    if (g >= K * NC) return;
+    const uint32_t k = g / NC, c = g - k * NC, lane = (uint32_t)lane_id();
+    const uint32_t bits = sub_end[((size_t)k * NC + c) * kSubs + (kSubs - 1)];
+    const uint32_t words = (((bits + 31u) >> 5) + 3u) & ~3u;
+    const uint32_t src = in_off[(size_t)k * (NC + 1) + c], dst = out_off[(size_t)k * (NC + 1) + c];
+    if ((src & 3u) || (uint64_t)src + words > in_cap || (uint64_t)dst + words > out_cap) {
+        if (lane == 0) raise_error(sc, (uint64_t)dst + words > out_cap ? QGX_EBIT_CAPACITY : QGX_EBIT_STREAM);
+        return;
+    }
+    const uint4* s = reinterpret_cast<const uint4*>(in_payload + (size_t)k * in_cap + src);
+    uint4* d = reinterpret_cast<uint4*>(out_payload + (size_t)k * out_cap + dst);
+    for (uint32_t q = lane; q < (words >> 2); q += kWave) d[q] = s[q];
+}
+
+hipError_t launch_compact(const Layout& lay, const uint16_t* sub_end, const uint32_t* in_off, const uint32_t* in_payload,
+                          uint64_t in_cap, uint32_t* out_off, uint32_t* out_payload, uint64_t out_cap, Scalars* sc,
+                          hipStream_t st)
+{
+    hipLaunchKernelGGL(k_compact_offsets, dim3(lay.K), dim3(1024), 0, st, lay.NC, sub_end, out_off, out_cap, sc);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const uint32_t grid = (lay.K * lay.NC + 3u) / 4u;
+    hipLaunchKernelGGL(k_compact_copy, dim3(grid), dim3(256), 0, st, lay.NC, lay.K, sub_end, in_off, in_payload, in_cap,
+                       out_off, out_payload, out_cap, sc);
     return hipGetLastError();
 }
 

@@ -227,8 +227,12 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
     LdsPlan L;
     L.cell = s_cell; L.lev = s_lev; L.lev_stride = a.lev_stride; L.sign_shift = a.sign_shift;
 
-    // the ticket first: everything else that does not need the bucket number overlaps its latency
-    if (tid == 0) s_misc[2] = atomicAdd(a.tickets + k * kTicketStride, 1u) - a.ticket_base;
+    // Compact placement: buckets by ticket (the ticket first: the table loads overlap its latency).
+    // Slotted placement and plain quantisation have no order to keep: the bucket is the block's own.
+    const bool ordered = MODE != EncMode::QuantOnly && a.slot_words == 0u;
+    if (ordered) {
+        if (tid == 0) s_misc[2] = atomicAdd(a.tickets + k * kTicketStride, 1u) - a.ticket_base;
+    }
     for (int i = tid; i < (int)n_sym; i += (int)blockDim.x) {
         reinterpret_cast<float4*>(s_lev)[i] = tab->lev2[0][i];
         reinterpret_cast<float4*>(s_lev + a.lev_stride)[i] = tab->lev2[1][i];
@@ -244,8 +248,8 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
     const size_t kbase = (size_t)k * lay.d;
     const bool vec_ok = (kbase & 3u) == 0;             // 16-byte aligned rows for this worker
     const float* __restrict__ Vk = (MODE != EncMode::EncodeOnly) ? a.V + kbase : nullptr;
-    const uint32_t b = s_misc[2];
-    if (b >= lay.NB) return;                           // cannot happen: one ticket per workgroup, NB per worker
+    const uint32_t b = ordered ? s_misc[2] : (uint32_t)blockIdx.x / lay.K;
+    if (b >= lay.NB) return;                           // cannot happen: one workgroup per bucket and worker
     const ChunkGeom g = chunk_geom(lay, b, w);
     float4 v[kRows];
     if (MODE != EncMode::EncodeOnly) load_chunk(v, Vk, g, vec_ok, lane);
@@ -382,25 +386,30 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
         words = (words + (kAlignWords - 1)) & ~(uint32_t)(kAlignWords - 1);
         if (MODE != EncMode::QuantOnly) {
             if (lane >= 4 * g.nrows) s_sub[w][lane] = (uint16_t)total_bits;
-            if (lane == 0) s_words[w] = words;
+            if (lane == 0 && ordered) s_words[w] = words;
         }
         if (MODE != EncMode::QuantOnly) {
-            __syncthreads();
-            uint32_t bucket_words = 0, wave_excl = 0;
-            for (int i = 0; i < nwaves; ++i) {
-                if (i == w) wave_excl = bucket_words;
-                bucket_words += s_words[i];
+            uint32_t off;
+            if (ordered) {
+                __syncthreads();
+                uint32_t bucket_words = 0, wave_excl = 0;
+                for (int i = 0; i < nwaves; ++i) {
+                    if (i == w) wave_excl = bucket_words;
+                    bucket_words += s_words[i];
+                }
+                if (w == 0) {
+                    const uint32_t excl = lookback_exclusive(a.scan_state + (size_t)k * lay.NB, b, bucket_words, a.epoch, sc);
+                    if (lane == 0) s_misc[1] = excl;
+                }
+                __syncthreads();
+                off = s_misc[1] + wave_excl;
+            } else {
+                off = g.c * a.slot_words;
             }
-            if (w == 0) {
-                const uint32_t excl = lookback_exclusive(a.scan_state + (size_t)k * lay.NB, b, bucket_words, a.epoch, sc);
-                if (lane == 0) s_misc[1] = excl;
-            }
-            __syncthreads();
             if (g.clen != 0) {
-                const uint32_t off = s_misc[1] + wave_excl;
                 if (lane == 0) {
                     a.chunk_off[(size_t)k * (lay.NC + 1) + g.c] = off;
-                    if (g.c + 1 == lay.NC) a.chunk_off[(size_t)k * (lay.NC + 1) + lay.NC] = off + words;
+                    if (g.c + 1 == lay.NC) a.chunk_off[(size_t)k * (lay.NC + 1) + lay.NC] = off + (ordered ? words : a.slot_words);
                 }
                 if (lane < 32)
                     reinterpret_cast<uint32_t*>(a.sub_end + ((size_t)k * lay.NC + g.c) * kSubs)[lane] =
@@ -438,7 +447,8 @@ static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc,
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    *tickets_per_worker = lay.NB;                      // one workgroup, one ticket per bucket
+    // one workgroup per bucket; in compact placement each takes one ticket of its worker
+    *tickets_per_worker = (MODE != EncMode::QuantOnly && a.slot_words == 0u) ? lay.NB : 0u;
     hipLaunchKernelGGL(k_encode<MODE>, dim3(lay.K * lay.NB), dim3(waves * kWave), lds, st, lay, tab, sc, a);
     return hipGetLastError();
 }

@@ -108,6 +108,7 @@ struct EncodeArgs {
     uint32_t lev_stride;        // power of two >= 16 * n_sym
     uint32_t sign_shift;        // (bits of v) >> sign_shift puts the sign bit on lev_stride
     uint32_t stage_bytes;       // per wave, multiple of 16, covers 4096 symbols of the longest code + sign
+    uint32_t slot_words;        // 0: compact placement (ordered scan); else chunk c goes to c * slot_words
 };
 
 struct DecodeArgs {
@@ -138,6 +139,9 @@ hipError_t launch_state_set(Scalars* sc, double S, unsigned long long t, uint32_
 hipError_t launch_sum_bits(const Layout& lay, const uint16_t* sub_end, Scalars* sc, hipStream_t st);
 hipError_t launch_histogram(const Layout& lay, const float* V, int norm_kind, uint32_t n_bins, double* partial,
                             uint32_t n_partial, double* hist, Scalars* sc, hipStream_t st);
+hipError_t launch_compact(const Layout& lay, const uint16_t* sub_end, const uint32_t* in_off, const uint32_t* in_payload,
+                          uint64_t in_cap, uint32_t* out_off, uint32_t* out_payload, uint64_t out_cap, Scalars* sc,
+                          hipStream_t st);
 hipError_t launch_fit(Tables* tab, const double* hist, uint32_t n_bins, uint32_t sweeps, hipStream_t st);
 uint32_t histogram_groups(const Layout& lay);
 

@@ -80,7 +80,15 @@ qgx_status check_stream(qgx_ctx* ctx, const qgx_stream* s, const char* what)
     if (s->payload_words_per_worker == 0 || (s->payload_words_per_worker & 3u) ||
         s->payload_words_per_worker > 0xFFFFFFFFull)
         return fail(ctx, QGX_ERR_ARG, "%s: payload_words_per_worker must be a non-zero multiple of 4 below 2^32", what);
+    if (s->slot_words & 3u) return fail(ctx, QGX_ERR_ARG, "%s: slot_words must be a multiple of 4", what);
     return QGX_OK;
+}
+
+// most words a full chunk can take with the code in use, multiple of 4
+uint32_t chunk_slot_words(const qgx_ctx* ctx)
+{
+    const uint32_t words = (kChunk * (ctx->max_code_len + 1) + 31) / 32;
+    return (words + 3) / 4 * 4;
 }
 
 qgx_status need_levels(qgx_ctx* ctx)
@@ -216,6 +224,35 @@ qgx_status qgx_stream_sizes(const qgx_ctx* ctx, uint64_t* n_buckets, uint64_t* n
     return QGX_OK;
 }
 
+qgx_status qgx_slot_words(const qgx_ctx* ctx, uint64_t* slot_words)
+{
+    if (!ctx || !slot_words) return QGX_ERR_ARG;
+    if (!ctx->levels_set || (ctx->cfg.code == QGX_CODE_TABLE && !ctx->code_set)) return QGX_ERR_STATE;
+    *slot_words = chunk_slot_words(ctx);
+    return QGX_OK;
+}
+
+qgx_status qgx_compact(qgx_ctx* ctx, const qgx_stream* in, qgx_stream* out, void* stream)
+{
+    if (!ctx) return QGX_ERR_ARG;
+    qgx_status s = check_stream(ctx, in, "qgx_compact(in)");
+    if (s == QGX_OK) s = check_stream(ctx, out, "qgx_compact(out)");
+    if (s != QGX_OK) return s;
+    if (out->slot_words != 0) return fail(ctx, QGX_ERR_ARG, "qgx_compact: out must be a compact stream");
+    if (in->payload == out->payload || in->chunk_off == out->chunk_off)
+        return fail(ctx, QGX_ERR_ARG, "qgx_compact: in and out must not alias");
+    hipStream_t st = (hipStream_t)stream;
+    const Layout& lay = ctx->lay;
+    if (in->norms != out->norms)
+        QGX_HIP(ctx, hipMemcpyAsync(out->norms, in->norms, (size_t)lay.K * lay.NB * sizeof(float), hipMemcpyDeviceToDevice, st));
+    if (in->sub_end != out->sub_end)
+        QGX_HIP(ctx, hipMemcpyAsync(out->sub_end, in->sub_end, (size_t)lay.K * lay.NC * kSubs * sizeof(uint16_t),
+                                    hipMemcpyDeviceToDevice, st));
+    QGX_HIP(ctx, launch_compact(lay, in->sub_end, in->chunk_off, in->payload, in->payload_words_per_worker,
+                                out->chunk_off, out->payload, out->payload_words_per_worker, ctx->d_sc, st));
+    return QGX_OK;
+}
+
 qgx_status qgx_set_levels(qgx_ctx* ctx, const float* levels_host, uint32_t n_sym, void* stream)
 {
     if (!ctx || !levels_host) return fail(ctx, QGX_ERR_ARG, "qgx_set_levels: null argument");
@@ -297,6 +334,14 @@ static qgx_status run_encode(qgx_ctx* ctx, EncMode mode, const float* V, uint32_
         a.stage_bytes = (words + 3) / 4 * 16;
     }
     if (mode != EncMode::QuantOnly) {
+        if (out->slot_words) {
+            if (out->slot_words < chunk_slot_words(ctx))
+                return fail(ctx, QGX_ERR_ARG, "slot_words %llu is below the %u words a chunk can take",
+                            (unsigned long long)out->slot_words, chunk_slot_words(ctx));
+            if (out->slot_words * ctx->lay.NC > out->payload_words_per_worker)
+                return fail(ctx, QGX_ERR_CAPACITY, "slotted stream needs n_chunks * slot_words payload words per worker");
+            a.slot_words = (uint32_t)out->slot_words;
+        }
         a.chunk_off = out->chunk_off; a.sub_end = out->sub_end; a.payload = out->payload;
         a.cap_words = out->payload_words_per_worker;
         a.scan_state = ctx->d_scan;
@@ -347,8 +392,7 @@ qgx_status qgx_quantize_encode(qgx_ctx* ctx, const float* V, uint32_t call_id, c
 
 static void fill_decode_args(const qgx_ctx* ctx, DecodeArgs& a, const qgx_stream* cur, const qgx_stream* prev)
 {
-    const uint32_t words = (kChunk * (ctx->max_code_len + 1) + 31) / 32;
-    a.stage_words = (words + 3) / 4 * 4;
+    a.stage_words = chunk_slot_words(ctx);
     a.stage_stride = (a.stage_words + a.stage_words / 32 + 8 + 3) / 4 * 4;
     a.norms = cur->norms; a.chunk_off = cur->chunk_off; a.sub_end = cur->sub_end; a.payload = cur->payload;
     a.cap_words = cur->payload_words_per_worker;

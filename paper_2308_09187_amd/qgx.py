@@ -23,7 +23,7 @@ CODE_ELIAS_OMEGA, CODE_TABLE = 0, 1
 CHUNK, SUB, MAX_SYM, MAX_BINS = 4096, 64, 127, 4096
 
 EXPORTS = [
-    "qgx_create", "qgx_destroy", "qgx_stream_sizes", "qgx_set_levels", "qgx_get_levels", "qgx_set_code_table",
+    "qgx_create", "qgx_destroy", "qgx_stream_sizes", "qgx_slot_words", "qgx_compact", "qgx_set_levels", "qgx_get_levels", "qgx_set_code_table",
     "qgx_quantize", "qgx_encode", "qgx_quantize_encode", "qgx_decode", "qgx_decode_average", "qgx_fit_levels",
     "qgx_state_init", "qgx_eg_step", "qgx_get_scalars", "qgx_state_export", "qgx_state_import",
     "qgx_poll_error", "qgx_last_error",
@@ -44,7 +44,7 @@ class _Config(C.Structure):
 
 class _Stream(C.Structure):
     _fields_ = [("norms", C.c_void_p), ("chunk_off", C.c_void_p), ("sub_end", C.c_void_p),
-                ("payload", C.c_void_p), ("payload_words_per_worker", C.c_uint64)]
+                ("payload", C.c_void_p), ("payload_words_per_worker", C.c_uint64), ("slot_words", C.c_uint64)]
 
 
 _lib = None
@@ -80,8 +80,9 @@ def _stream_handle(stream):
 class Stream:
     """Device buffers of one CODE o Q result for K workers."""
 
-    def __init__(self, K, NB, NC, cap_words, device="cuda"):
+    def __init__(self, K, NB, NC, cap_words, device="cuda", slot_words=0):
         cap_words = (int(cap_words) + 3) // 4 * 4
+        self.slot_words = int(slot_words)
         self.norms = torch.zeros((K, NB), dtype=torch.float32, device=device)
         self.chunk_off = torch.zeros((K, NC + 1), dtype=torch.int32, device=device)
         self.sub_end = torch.zeros((K, NC, 64), dtype=torch.int16, device=device)
@@ -90,7 +91,7 @@ class Stream:
 
     def c_struct(self):
         return _Stream(self.norms.data_ptr(), self.chunk_off.data_ptr(), self.sub_end.data_ptr(),
-                       self.payload.data_ptr(), self.cap_words)
+                       self.payload.data_ptr(), self.cap_words, self.slot_words)
 
     def to_host(self):
         """numpy views in the container's unsigned types."""
@@ -134,8 +135,22 @@ class Context:
         except Exception:
             pass
 
-    def new_stream(self, cap_words=None):
+    def slot_words(self):
+        sw = C.c_uint64()
+        self._check(self.lib.qgx_slot_words(self._h, C.byref(sw)))
+        return sw.value
+
+    def new_stream(self, cap_words=None, slotted=False):
+        """Compact stream (worst-case capacity unless cap_words is given), or a slotted one."""
+        if slotted:
+            sw = self.slot_words()
+            return Stream(self.K, self.NB, self.NC, sw * self.NC, self.device, slot_words=sw)
         return Stream(self.K, self.NB, self.NC, self.worst_words if cap_words is None else cap_words, self.device)
+
+    def compact(self, src: Stream, dst: Stream, stream=None):
+        a, b = src.c_struct(), dst.c_struct()
+        self._check(self.lib.qgx_compact(self._h, C.byref(a), C.byref(b), _stream_handle(stream)))
+        return dst
 
     # -- tables ---------------------------------------------------------------------------------
     def set_levels(self, levels, stream=None):

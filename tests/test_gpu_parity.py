@@ -56,6 +56,18 @@ def assert_stream_equal(h, st, lay):
         np.testing.assert_array_equal(h["payload"][k, :used], st.payload[k, :used])
 
 
+def assert_slotted_equal(h, st, lay, slot):
+    """h: host copy of a slotted GPU stream; st: the oracle's compact Stream: same bits chunk by chunk."""
+    K = st.payload.shape[0]
+    np.testing.assert_array_equal(h["sub_end"], st.sub_end)
+    np.testing.assert_array_equal(h["chunk_off"], np.tile(np.arange(lay.NC + 1, dtype=np.uint32) * np.uint32(slot), (K, 1)))
+    for k in range(K):
+        for c in range(lay.NC):
+            a, b = int(st.chunk_off[k, c]), int(st.chunk_off[k, c + 1])
+            assert b - a <= slot
+            np.testing.assert_array_equal(h["payload"][k, c * slot:c * slot + (b - a)], st.payload[k, a:b])
+
+
 CASES = [
     # d, K, bucket, norm, table, segments
     (3 * 4096 + 1000, 3, 8192, oracle.NORM_L2, "exp16", None),       # several tiles and a ragged tail
@@ -101,6 +113,18 @@ def test_quantize_encode_decode_parity(qgx, d, K, bucket, norm, tab, segs):
     assert_stream_equal(h, st_o, lay)
     assert ctx.scalars(want_bits=True)["total_bits"] == int(st_o.total_bits.sum())
 
+    # slotted placement: the same bits chunk by chunk at fixed slots; decodes alike; compacts to the same bytes
+    slot = ctx.slot_words()
+    outs = ctx.new_stream(slotted=True)
+    ctx.quantize_encode(Vd, call, outs)
+    hs = outs.to_host()
+    assert_slotted_equal(hs, st_o, lay, slot)
+    outc = ctx.new_stream()
+    ctx.compact(outs, outc)
+    hc = outc.to_host()
+    np.testing.assert_array_equal(hc["norms"], norms_g)
+    assert_stream_equal(hc, st_o, lay)
+
     # CODE from stored symbols gives the same stream
     out2 = ctx.new_stream()
     ctx.encode(dev(norms_g), dev(sym_g), out2)
@@ -110,6 +134,7 @@ def test_quantize_encode_decode_parity(qgx, d, K, bucket, norm, tab, segs):
     Vhat_o, _, _ = oracle.decode(st_o, norms_g, lay, levels)
     Vhat_g = ctx.decode(out).cpu().numpy()
     np.testing.assert_array_equal(Vhat_g, Vhat_o)
+    np.testing.assert_array_equal(ctx.decode(outs).cpu().numpy(), Vhat_o)
 
     # aggregate
     mean_g = ctx.decode_average(out).cpu().numpy()
@@ -205,6 +230,15 @@ def test_degenerate_inputs_and_error_word(qgx):
     with pytest.raises(qgx.QgxError) as e:
         ctx.eg_step(0, out, None, torch.empty(d, device="cuda"))
     assert e.value.status == qgx.ERR_STATE         # state not initialised
+    bad = ctx.new_stream(slotted=True)
+    bad.slot_words -= 4                              # a slot smaller than a chunk can get
+    with pytest.raises(qgx.QgxError) as e:
+        ctx.quantize_encode(dev(V), 0, bad)
+    assert e.value.status == qgx.ERR_ARG
+    bad.slot_words += 4; bad.cap_words -= 4          # not room for every slot
+    with pytest.raises(qgx.QgxError) as e:
+        ctx.quantize_encode(dev(V), 0, bad)
+    assert e.value.status == qgx.ERR_CAPACITY
     ctx.close()
     c2 = qgx.Context(d, K, bucket)
     with pytest.raises(qgx.QgxError) as e:
@@ -261,7 +295,8 @@ def run_lockstep(qgx, game, levels, norm, bucket, T, seed, anchor, refit=None, n
     x1 = game.x1() if anchor else None
     ctx.state_init(dev(x1) if anchor else None)
     st = oracle.EGState(d, K, X1=x1)
-    cur, prev = ctx.new_stream(), ctx.new_stream()
+    cur, prev = ctx.new_stream(slotted=True), ctx.new_stream(slotted=True)
+    tmp = ctx.new_stream()
     Xh = torch.empty(d, device="cuda"); Xn = torch.empty(d, device="cuda")
     X = (x1 if anchor else np.zeros(d, np.float32)).astype(np.float32)
     worst = 0.0
@@ -272,7 +307,7 @@ def run_lockstep(qgx, game, levels, norm, bucket, T, seed, anchor, refit=None, n
             levels = ctx.get_levels()              # the oracle follows the GPU's table (checked elsewhere)
         ctx.quantize_encode(dev(V0), 2 * t, prev)
         ctx.eg_step(0, prev, None, Xh)
-        hp = prev.to_host()
+        hp = ctx.compact(prev, tmp).to_host()
         _, _, _, so = oracle_stream(V0, lay, norm, levels, seed, 2 * t, hp["norms"], ctx.worst_words)
         assert_stream_equal(hp, so, lay)
         Vhat0, _, _ = oracle.decode(so, hp["norms"], lay, levels)
@@ -281,7 +316,7 @@ def run_lockstep(qgx, game, levels, norm, bucket, T, seed, anchor, refit=None, n
         V1 = game.dual_vectors(Xh.cpu().numpy(), 2 * t + 1)
         ctx.quantize_encode(dev(V1), 2 * t + 1, cur)
         ctx.eg_step(1, cur, prev, Xn)
-        hc = cur.to_host()
+        hc = ctx.compact(cur, tmp).to_host()
         _, _, _, so1 = oracle_stream(V1, lay, norm, levels, seed, 2 * t + 1, hc["norms"], ctx.worst_words)
         assert_stream_equal(hc, so1, lay)
         Vhat1, _, _ = oracle.decode(so1, hc["norms"], lay, levels)
