@@ -70,47 +70,69 @@ __device__ __forceinline__ void commit_chunk(uint32_t* stage, const uint4 (&pre)
     }
 }
 
+// LDS tables of the decoder in one array: level values first, then the decode table, so that the
+// level index of a reject entry (flag bit set) still lands inside the array.
+constexpr int kTabLvalBytes = kSymMax * 4;
+constexpr int kTabBytes = kTabLvalBytes + kDlutStore * 2;
+
 // One symbol at bit cursor p of the staged chunk: returns the signed value norm * l_idx.
-// A window that starts with no code word decodes through the table's reject entry (flag bit 15).
-__device__ __forceinline__ float take_symbol(const uint32_t* stage, const uint16_t* dlut, const float* lval,
-                                             uint32_t& p, float n, uint32_t& flags)
+// EXACT_ZERO: give +0 for the zero symbol (whose sign bit is not in the stream); the accumulating
+// modes leave the stray sign on the zero, which adds nothing.
+template <bool EXACT_ZERO>
+__device__ __forceinline__ float take_symbol(const uint32_t* stage, const unsigned char* tab, uint32_t& p, float n,
+                                             uint32_t& flags)
 {
     const uint32_t wi = p >> 5;
-    const uint32_t* wp = stage + staged(wi);
-    const uint32_t win = __builtin_amdgcn_alignbit(wp[1], wp[0], p & 31u);
-    const uint32_t e = dlut[dlut_slot(win)];
+    const uint32_t* wp = stage + wi + (wi >> 5);
+    const uint32_t win = __builtin_amdgcn_alignbit(wp[1], wp[0], p);          // shift uses p mod 32
+    const uint32_t w13 = win & (uint32_t)(kDlut - 1);
+    const uint32_t hi = (win >> 6) & 0x7Fu;
+    const uint32_t e = *reinterpret_cast<const uint16_t*>(tab + kTabLvalBytes + (w13 << 1) + (hi << 2));
     flags |= e;
-    const uint32_t len = e & 15u, idx = e >> 4;
-    const uint32_t nz = idx != 0u ? 1u : 0u;
-    const uint32_t sg = (win >> len) & nz;
-    p += len + nz;
-    const float mag = n * lval[idx];
-    return __uint_as_float(__float_as_uint(mag) ^ (sg << 31));
+    const uint32_t tlen = e & 15u;                      // code word plus sign bit
+    const float lv = *reinterpret_cast<const float*>(tab + (e >> 4));         // 4 * idx
+    p += tlen;
+    const uint32_t sg = win << (32u - tlen);            // the last bit of the symbol, in bit 31
+    const float mag = n * lv;
+    float val = __uint_as_float((__float_as_uint(mag) & 0x7FFFFFFFu) | (sg & 0x80000000u));
+    if (EXACT_ZERO) val = (e >> 4) == 0u ? 0.0f : val;
+    return val;
+}
+
+struct SubMeta {             // what a lane needs to parse its run of one worker's chunk
+    uint32_t p0, p_end;      // bit cursor at the start and expected at the end
+    float n;                 // norm of the bucket
+};
+
+__device__ __forceinline__ SubMeta load_meta(const uint16_t* sub_end, const float* norms, uint32_t k, uint32_t c,
+                                             uint32_t bkt, const Layout& lay, int lane)
+{
+    const uint16_t* se = sub_end + ((size_t)k * lay.NC + c) * kSubs;
+    SubMeta m;
+    m.p_end = se[lane];
+    m.p0 = lane ? (uint32_t)se[lane - 1] : 0u;
+    m.n = norms[(size_t)k * lay.NB + bkt];
+    return m;
 }
 
 template <DecMode MODE>
-__global__ __launch_bounds__(kDecWaves * kWave) __attribute__((amdgpu_waves_per_eu(MODE == DecMode::Half1 ? 3 : 4))) void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc,
-                                                              DecodeArgs a)
+__global__ __launch_bounds__(kDecWaves * kWave) __attribute__((amdgpu_waves_per_eu(MODE == DecMode::Half1 ? 3 : 4)))
+void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArgs a)
 {
-    extern __shared__ __align__(16) uint32_t s_dyn[];    // [waves][1 or 2][stage_words_padded]
-    __shared__ float s_lval[kSymMax];                    // just below the decode table: a reject entry's
-    __shared__ uint16_t s_dlut[kDlut];                   // index lands inside it, not outside the block
+    extern __shared__ __align__(16) uint32_t s_dyn[];    // [waves][1 or 2][stage_stride]
+    __shared__ __align__(16) unsigned char s_tab[kTabBytes];
 
     const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
     constexpr int kBufs = (MODE == DecMode::Half1) ? 2 : 1;
+    constexpr bool kExact = MODE == DecMode::Decode;
     const uint32_t stage_words = a.stage_words;          // words a chunk of this code can take
     const uint32_t stage_stride = a.stage_stride;        // padded size of one staging buffer, words
     uint32_t* stage = s_dyn + (size_t)w * kBufs * stage_stride;
     uint32_t* stage_p = stage + stage_stride;
 
-    for (int i = tid; i < kDlut / 2; i += (int)blockDim.x) {
-        uint32_t two = reinterpret_cast<const uint32_t*>(tab->dlut)[i];
-        // reject entries: flag in bit 15, one bit long, so that the parse goes on inside the buffer
-        if ((two & 0xFFFFu) == 0xFFFFu) two = (two & 0xFFFF0000u) | 0x8001u;
-        if ((two >> 16) == 0xFFFFu) two = (two & 0x0000FFFFu) | 0x80010000u;
-        reinterpret_cast<uint32_t*>(s_dlut)[i] = two;
-    }
-    for (int i = tid; i < kSymMax; i += (int)blockDim.x) s_lval[i] = tab->lval[i];
+    for (int i = tid; i < kSymMax; i += (int)blockDim.x) reinterpret_cast<float*>(s_tab)[i] = tab->lval[i];
+    for (int i = tid; i < kDlutStore / 2; i += (int)blockDim.x)
+        reinterpret_cast<uint32_t*>(s_tab + kTabLvalBytes)[i] = reinterpret_cast<const uint32_t*>(tab->dlut)[i];
     // words past a chunk's end are read by the window of its last symbols: keep them defined
     for (uint32_t q = (uint32_t)lane; q < kBufs * stage_stride; q += kWave) stage[q] = 0;
     __syncthreads();
@@ -124,9 +146,17 @@ __global__ __launch_bounds__(kDecWaves * kWave) __attribute__((amdgpu_waves_per_
         if (g >= lay.NC) return;
         c = g; k_first = 0; k_count = lay.K;
     }
-    const uint32_t clo = lay.chunk_start[c];
-    const uint32_t clen = lay.chunk_start[c + 1] - clo;
-    const uint32_t bkt = lay.chunk_bucket[c];
+    uint32_t clo, clen, bkt;
+    if (lay.uniform_bucket) {                             // one segment: chunk geometry is arithmetic
+        bkt = c / lay.waves_per_bucket;
+        const uint32_t lo = bkt * lay.uniform_bucket, hi = min(lo + lay.uniform_bucket, lay.d);
+        clo = lo + (c - bkt * lay.waves_per_bucket) * (uint32_t)kChunk;
+        clen = min((uint32_t)kChunk, hi - clo);
+    } else {
+        clo = lay.chunk_start[c];
+        clen = lay.chunk_start[c + 1] - clo;
+        bkt = lay.chunk_bucket[c];
+    }
     const int cnt = (int)min(64u, clen > 64u * (uint32_t)lane ? clen - 64u * (uint32_t)lane : 0u);
     const bool full = clen == (uint32_t)kChunk;           // wave-uniform: every lane has 64 coordinates
     const bool have_prev = (MODE == DecMode::Half1) && a.payload_p != nullptr;
@@ -140,15 +170,20 @@ __global__ __launch_bounds__(kDecWaves * kWave) __attribute__((amdgpu_waves_per_
     uint32_t flags = 0;
     bool malformed = false;
 
+    // worker k's chunk and its per-lane cursors travel one iteration ahead, in registers
     uint4 pre[kPre];
     ChunkRef cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, a.sub_end, k_first, c, lay.NC, stage_words, sc);
     prefetch_chunk(cr, pre);
+    SubMeta nxt = load_meta(a.sub_end, a.norms, k_first, c, bkt, lay, lane);
 
     for (uint32_t kk = 0; kk < k_count; ++kk) {
         const uint32_t k = k_first + kk;
+        const SubMeta cur = nxt;
         commit_chunk(stage, pre, stage_words);
+        SubMeta prv{0u, 0u, 0.0f};
         if constexpr (MODE == DecMode::Half1) {
             if (have_prev) {                         // the previous half-step's chunk goes through the same registers
+                prv = load_meta(a.sub_end_p, a.norms_p, k, c, bkt, lay, lane);
                 ChunkRef cp = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, a.sub_end_p, k, c, lay.NC, stage_words, sc);
                 prefetch_chunk(cp, pre);
                 commit_chunk(stage_p, pre, stage_words);
@@ -156,94 +191,91 @@ __global__ __launch_bounds__(kDecWaves * kWave) __attribute__((amdgpu_waves_per_
         }
         if (kk + 1 < k_count) {                      // next worker's chunk: in flight while this one is parsed
             cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, a.sub_end, k + 1, c, lay.NC, stage_words, sc);
+            nxt = load_meta(a.sub_end, a.norms, k + 1, c, bkt, lay, lane);
             prefetch_chunk(cr, pre);
         }
-        const uint16_t* se = a.sub_end + ((size_t)k * lay.NC + c) * kSubs;
-        const uint32_t p_end = se[lane];
-        uint32_t p = lane ? (uint32_t)se[lane - 1] : 0u;
+        uint32_t p = cur.p0, pp = prv.p0;
         if (p > p_limit) { p = p_limit; malformed = true; }
-        const float n = a.norms[(size_t)k * lay.NB + bkt];
-        uint32_t pp = 0, pp_end = 0;
-        float np = 0.0f;
-        if constexpr (MODE == DecMode::Half1) {
-            if (have_prev) {
-                const uint16_t* sp = a.sub_end_p + ((size_t)k * lay.NC + c) * kSubs;
-                pp_end = sp[lane];
-                pp = lane ? (uint32_t)sp[lane - 1] : 0u;
-                if (pp > p_limit) { pp = p_limit; malformed = true; }
-                np = a.norms_p[(size_t)k * lay.NB + bkt];
-            }
-        }
+        if (pp > p_limit) { pp = p_limit; malformed = true; }
+        const float n = cur.n, np = prv.n;
         float* vout = nullptr;
         if constexpr (MODE == DecMode::Decode) vout = a.out + (size_t)k * lay.d + clo + 64u * (uint32_t)lane;
         if (full && MODE != DecMode::Half1) {
 #pragma unroll
             for (int s = 0; s < kSub; ++s) {
-                const float val = take_symbol(stage, s_dlut, s_lval, p, n, flags);
+                const float val = take_symbol<kExact>(stage, s_tab, p, n, flags);
                 if constexpr (MODE == DecMode::Decode) vout[s] = val;
                 else acc[s] += val;
-                if constexpr (MODE == DecMode::Half1) {
-                    float pv = 0.0f;
-                    if (have_prev) pv = take_symbol(stage_p, s_dlut, s_lval, pp, np, flags);
-                    const double df = (double)pv - (double)val;
-                    sdiff = fma(df, df, sdiff);
-                }
             }
         } else {
 #pragma unroll
             for (int s = 0; s < kSub; ++s) {
                 if (s < cnt) {
-                    const float val = take_symbol(stage, s_dlut, s_lval, p, n, flags);
+                    const float val = take_symbol<kExact>(stage, s_tab, p, n, flags);
                     if constexpr (MODE == DecMode::Decode) vout[s] = val;
                     else acc[s] += val;
                     if constexpr (MODE == DecMode::Half1) {
                         float pv = 0.0f;
-                        if (have_prev) pv = take_symbol(stage_p, s_dlut, s_lval, pp, np, flags);
+                        if (have_prev) pv = take_symbol<true>(stage_p, s_tab, pp, np, flags);
                         const double df = (double)pv - (double)val;
                         sdiff = fma(df, df, sdiff);
                     }
                 }
             }
         }
-        if (cnt > 0 && p != p_end) malformed = true;
+        if (cnt > 0 && p != cur.p_end) malformed = true;
         if constexpr (MODE == DecMode::Half1) {
-            if (have_prev && cnt > 0 && pp != pp_end) malformed = true;
+            if (have_prev && cnt > 0 && pp != prv.p_end) malformed = true;
         }
     }
     malformed = malformed || (flags & 0x8000u) != 0u;
     if (__any(malformed) && lane == 0) raise_error(sc, QGX_EBIT_STREAM);
     if (MODE == DecMode::Decode) return;
 
-    // ---- aggregate and update: lane owns coordinates clo + 64*lane .. + cnt ---------------------
+    // ---- aggregate and update ---------------------------------------------------------------------
     const float invK = 1.0f / (float)lay.K;
-    const uint32_t i0 = clo + 64u * (uint32_t)lane;
     const float gam = sc->gamma_f;
     if constexpr (MODE == DecMode::Half1) {
         sdiff = wave_sum(sdiff);
         if (lane == 0) a.s_partial[c] = sdiff;
     }
-    if (cnt == kSub) {
+    if (full) {
+        // Lane L holds coordinates 64L..64L+63 of the chunk.  Through LDS, 16 symbols at a time, the
+        // wave turns them so that four consecutive lanes own 16 consecutive floats: global accesses
+        // then touch whole 64-byte pieces instead of 16 bytes per 256.
+        float* tr = reinterpret_cast<float*>(stage);          // 64 rows of 20 floats (16 + pad), 5120 bytes
 #pragma unroll
-        for (int s = 0; s < kSub; s += 4) {
-            float4 m = make_float4(acc[s] * invK, acc[s + 1] * invK, acc[s + 2] * invK, acc[s + 3] * invK);
-            if (MODE == DecMode::Average) {
-                *reinterpret_cast<float4*>(a.out + i0 + s) = m;
-            } else if (MODE == DecMode::Half0) {
-                const float4 y = *reinterpret_cast<const float4*>(a.Y + i0 + s);
-                float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (a.anchor) x = *reinterpret_cast<const float4*>(a.anchor + i0 + s);
-                x.x = (x.x + gam * y.x) - gam * m.x;
-                x.y = (x.y + gam * y.y) - gam * m.y;
-                x.z = (x.z + gam * y.z) - gam * m.z;
-                x.w = (x.w + gam * y.w) - gam * m.w;
-                *reinterpret_cast<float4*>(a.out + i0 + s) = x;
-            } else {
-                float4 y = *reinterpret_cast<const float4*>(a.Y + i0 + s);
-                y.x -= m.x; y.y -= m.y; y.z -= m.z; y.w -= m.w;
-                *reinterpret_cast<float4*>(a.Y + i0 + s) = y;
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                *reinterpret_cast<float4*>(tr + lane * 20 + 4 * j) =
+                    make_float4(acc[16 * q + 4 * j] * invK, acc[16 * q + 4 * j + 1] * invK,
+                                acc[16 * q + 4 * j + 2] * invK, acc[16 * q + 4 * j + 3] * invK);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = (lane >> 2) + 16 * i;             // whose 16 symbols
+                const float4 m = *reinterpret_cast<const float4*>(tr + row * 20 + 4 * (lane & 3));
+                const uint32_t at = clo + 64u * (uint32_t)row + 16u * (uint32_t)q + 4u * (uint32_t)(lane & 3);
+                if (MODE == DecMode::Average) {
+                    *reinterpret_cast<float4*>(a.out + at) = m;
+                } else if (MODE == DecMode::Half0) {
+                    const float4 y = *reinterpret_cast<const float4*>(a.Y + at);
+                    float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (a.anchor) x = *reinterpret_cast<const float4*>(a.anchor + at);
+                    x.x = (x.x + gam * y.x) - gam * m.x;
+                    x.y = (x.y + gam * y.y) - gam * m.y;
+                    x.z = (x.z + gam * y.z) - gam * m.z;
+                    x.w = (x.w + gam * y.w) - gam * m.w;
+                    *reinterpret_cast<float4*>(a.out + at) = x;
+                } else {
+                    float4 y = *reinterpret_cast<const float4*>(a.Y + at);
+                    y.x -= m.x; y.y -= m.y; y.z -= m.z; y.w -= m.w;
+                    *reinterpret_cast<float4*>(a.Y + at) = y;
+                }
             }
         }
     } else {
+        const uint32_t i0 = clo + 64u * (uint32_t)lane;
 #pragma unroll
         for (int s = 0; s < kSub; ++s) {
             if (s < cnt) {

@@ -35,14 +35,16 @@ constexpr int kDlutBits = kMaxCode;       // decode window
 constexpr int kDlut = 1 << kDlutBits;     // 8192 entries
 
 // Slot of a 13-bit window in the decode table.  The first bits of a window are the length prefix of
-// a code word and take few values, so the LDS bank (bits 1..5 of the slot) is mixed with window bits
-// 6..10, which hold the digits of the symbol.  A bijection: only low bits change, by a function of
-// higher bits.
+// a code word and take few values, so consecutive 64-entry rows are skewed by two entries (one LDS
+// bank): the bank then follows window bits 6..12, which hold the digits of the symbol.
+constexpr int kDlutRow = 66;              // 64 entries + 2 of skew
+constexpr int kDlutStore = (kDlut / 64) * kDlutRow;   // 8448 entries
 __host__ __device__ inline uint32_t dlut_slot(uint32_t window)
 {
     const uint32_t w = window & (uint32_t)(kDlut - 1);
-    return w ^ ((w >> 5) & 0x3Eu);
+    return w + 2u * (w >> 6);
 }
+constexpr uint32_t kDlutReject = 0x8001u; // no code word starts this window: flag, one bit long, symbol 0
 
 // Device-resident tables: rebuilt on the device whenever the level table or the code changes.
 struct Tables {
@@ -61,7 +63,8 @@ struct Tables {
     uint32_t code_kind;
     uint32_t cell_exact;
     uint32_t pad_;
-    uint16_t dlut[kDlut];       // dlut[dlut_slot(next 13 stream bits)] = idx << 4 | length; 0xFFFF = no code word
+    // dlut[dlut_slot(next 13 stream bits)] = (length + 1 if idx != 0) | (4 * idx) << 4, or kDlutReject
+    uint16_t dlut[kDlutStore];
 };
 
 // Scalars of the iteration; lives in device memory, read by kernels, copied out on request.

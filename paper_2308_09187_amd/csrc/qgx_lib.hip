@@ -394,6 +394,7 @@ static void fill_decode_args(const qgx_ctx* ctx, DecodeArgs& a, const qgx_stream
 {
     a.stage_words = chunk_slot_words(ctx);
     a.stage_stride = (a.stage_words + a.stage_words / 32 + 8 + 3) / 4 * 4;
+    if (a.stage_stride < 1280u) a.stage_stride = 1280u;   // the buffer also turns the output (64 rows of 20 floats)
     a.norms = cur->norms; a.chunk_off = cur->chunk_off; a.sub_end = cur->sub_end; a.payload = cur->payload;
     a.cap_words = cur->payload_words_per_worker;
     if (prev) {

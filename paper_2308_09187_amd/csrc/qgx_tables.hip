@@ -44,7 +44,7 @@ static __device__ void build_tables_block(Tables* tab)
             tab->code[j] = bits | (len << 16);
         }
     }
-    for (int i = tid; i < kDlut; i += nt) tab->dlut[i] = 0xFFFFu;
+    for (int i = tid; i < kDlutStore; i += nt) tab->dlut[i] = (uint16_t)kDlutReject;
     __syncthreads();
 
     for (int j = tid; j < kSymMax; j += nt) {
@@ -88,7 +88,7 @@ static __device__ void build_tables_block(Tables* tab)
         if (len == 0 || len > (uint32_t)kMaxCode) continue;
         const uint32_t reps = 1u << (kDlutBits - len);
         for (uint32_t s = (uint32_t)tid; s < reps; s += (uint32_t)nt)
-            tab->dlut[dlut_slot(bits | (s << len))] = (uint16_t)((j << 4) | len);
+            tab->dlut[dlut_slot(bits | (s << len))] = (uint16_t)((j << 6) | (len + (j != 0u ? 1u : 0u)));
     }
     __syncthreads();
 }
