@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-logd", type=int, default=23, help="log2 of coordinates per worker in the oracle sample")
     ap.add_argument("--full-iteration", action="store_true", help="also time encode + second half-step")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain device copy of the input (known size) to calibrate rocprofv3 HBM counters")
     ap.add_argument("--placement", choices=["slotted", "compact"], default="slotted",
                     help="chunk placement of the coded streams handed from the encoder to the update kernel")
     return ap.parse_args()
@@ -112,6 +114,10 @@ def main():
             ctx.eg_step(1, b, a, None)
             if ev: ev[4].record()
 
+    if args.copy_probe:
+        probe = V.clone()          # plain copy kernel: reads and writes 4*K*d bytes
+        torch.cuda.synchronize()
+        del probe
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
