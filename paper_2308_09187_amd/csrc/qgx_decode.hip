@@ -18,10 +18,10 @@ constexpr int kDecWaves = 8;                          // waves per workgroup: th
 
 // Staged chunk layout in LDS.  Lane j parses the j-th run of 64 coordinates, whose bits start roughly
 // 64 * (bits per coordinate) / 32 words after lane j-1's: a power-of-two stride that would put all
-// lanes on a few banks.  So one pad word is inserted after every 32 words (word i lives at
-// i + i/32), and the pad slot repeats the word that follows it, so that a lane always finds the two
-// words of its 32-bit window next to each other.
-__device__ __forceinline__ uint32_t staged(uint32_t i) { return i + (i >> 5); }
+// lanes on a few banks.  So two pad words are inserted after every 32 words (word i lives at
+// i + 2 (i / 32)), and the pad slots repeat the two words that follow them, so that a lane always
+// finds the three words of its 64-bit window next to each other.
+__device__ __forceinline__ uint32_t staged(uint32_t i) { return i + ((i >> 5) << 1); }
 
 struct ChunkRef {            // where one worker's chunk lives and how long it is
     const uint4* src;
@@ -63,9 +63,10 @@ __device__ __forceinline__ void commit_chunk(uint32_t* stage, const uint4 (&pre)
     for (int q = 0; q < kPre; ++q) {
         const uint32_t i0 = (lane + (uint32_t)q * kWave) * 4u;
         if (i0 < stage_words) {
-            const uint32_t s0 = staged(i0);
-            stage[s0] = pre[q].x; stage[s0 + 1] = pre[q].y; stage[s0 + 2] = pre[q].z; stage[s0 + 3] = pre[q].w;
-            if ((i0 & 31u) == 0u && i0 != 0u) stage[s0 - 1] = pre[q].x;     // the pad slot repeats its successor
+            uint2* at = reinterpret_cast<uint2*>(stage + staged(i0));          // even slot: 8-byte aligned
+            at[0] = make_uint2(pre[q].x, pre[q].y);
+            at[1] = make_uint2(pre[q].z, pre[q].w);
+            if ((i0 & 31u) == 0u && i0 != 0u) at[-1] = make_uint2(pre[q].x, pre[q].y);   // pads repeat their successors
         }
     }
 }
@@ -75,27 +76,54 @@ __device__ __forceinline__ void commit_chunk(uint32_t* stage, const uint4 (&pre)
 constexpr int kTabLvalBytes = kSymMax * 4;
 constexpr int kTabBytes = kTabLvalBytes + kDlutStore * 2;
 
-// One symbol at bit cursor p of the staged chunk: returns the signed value norm * l_idx.
+// Symbols are parsed in groups of up to three from one 64-bit window (three LDS words): a symbol
+// takes at most 14 bits, so the third one still starts inside the low word.  A table entry is
+// (length incl. sign) | 4 idx << 4 with bits 4 and 5 clear, so sums of entries carry the consumed
+// bits in their low six bits and an entry can be used as a shift count as it is.
+// The three steps are separate so that the caller can issue the next group's window reads before
+// it turns the current group's entries into values.
+struct Window { uint32_t w0, w1, w2; };
+
+__device__ __forceinline__ Window read_window(const uint32_t* stage, uint32_t p)
+{
+    const uint32_t* wp = stage + (p >> 5) + ((p >> 10) << 1);
+    return Window{wp[0], wp[1], wp[2]};
+}
+
+// The dependent chain: window i needs the lengths of the symbols before it.  Advances the cursor.
+template <int N>
+__device__ __forceinline__ void parse_group(const Window& w, const unsigned char* tab, uint32_t& p,
+                                            uint32_t (&win)[3], uint32_t (&e)[3])
+{
+    const uint32_t lo = __builtin_amdgcn_alignbit(w.w1, w.w0, p);             // shifts use p mod 32
+    const uint32_t hi = __builtin_amdgcn_alignbit(w.w2, w.w1, p);
+    uint32_t used = 0;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        win[i] = i == 0 ? lo : __builtin_amdgcn_alignbit(hi, lo, used);
+        const uint32_t t = win[i] & (uint32_t)(kDlut - 1);
+        const uint32_t h = (win[i] >> 6) & 0x7Fu;
+        e[i] = *reinterpret_cast<const uint16_t*>(tab + kTabLvalBytes + ((t + (h << 1)) << 1));
+        used += e[i];
+    }
+    p += used & 63u;
+}
+
+__device__ __forceinline__ float level_of(const unsigned char* tab, uint32_t e)
+{
+    return *reinterpret_cast<const float*>(tab + (e >> 4));                  // the entry holds 4 * idx
+}
+
+// Signed value norm * l_idx of one parsed symbol, lv = level_of(entry).
 // EXACT_ZERO: give +0 for the zero symbol (whose sign bit is not in the stream); the accumulating
 // modes leave the stray sign on the zero, which adds nothing.
 template <bool EXACT_ZERO>
-__device__ __forceinline__ float take_symbol(const uint32_t* stage, const unsigned char* tab, uint32_t& p, float n,
-                                             uint32_t& flags)
+__device__ __forceinline__ float symbol_value(float lv, uint32_t win, uint32_t e, float n)
 {
-    const uint32_t wi = p >> 5;
-    const uint32_t* wp = stage + wi + (wi >> 5);
-    const uint32_t win = __builtin_amdgcn_alignbit(wp[1], wp[0], p);          // shift uses p mod 32
-    const uint32_t w13 = win & (uint32_t)(kDlut - 1);
-    const uint32_t hi = (win >> 6) & 0x7Fu;
-    const uint32_t e = *reinterpret_cast<const uint16_t*>(tab + kTabLvalBytes + (w13 << 1) + (hi << 2));
-    flags |= e;
-    const uint32_t tlen = e & 15u;                      // code word plus sign bit
-    const float lv = *reinterpret_cast<const float*>(tab + (e >> 4));         // 4 * idx
-    p += tlen;
-    const uint32_t sg = win << (32u - tlen);            // the last bit of the symbol, in bit 31
-    const float mag = n * lv;
-    float val = __uint_as_float((__float_as_uint(mag) & 0x7FFFFFFFu) | (sg & 0x80000000u));
-    if (EXACT_ZERO) val = (e >> 4) == 0u ? 0.0f : val;
+    const uint32_t sg = __builtin_amdgcn_alignbit(win, win, e);                // last bit of the symbol -> bit 31
+    // norm and level are not negative: the sign goes in with one OR
+    const float val = __uint_as_float((sg & 0x80000000u) | __float_as_uint(n * lv));
+    if (EXACT_ZERO) return (e >> 4) == 0u ? 0.0f : val;
     return val;
 }
 
@@ -115,15 +143,19 @@ __device__ __forceinline__ SubMeta load_meta(const uint16_t* sub_end, const floa
     return m;
 }
 
-template <DecMode MODE>
-__global__ __launch_bounds__(kDecWaves * kWave) __attribute__((amdgpu_waves_per_eu(MODE == DecMode::Half1 ? 3 : 4)))
+// FULL: the launch covers the chunk positions that hold 4096 coordinates (straight-line parse, output
+// turned through LDS); otherwise it covers the ragged positions listed in the layout.
+// PREV (Half1): the previous half-step's streams are there; without them the vectors count as zero.
+template <DecMode MODE, bool FULL, bool PREV>
+__global__ __launch_bounds__(kDecWaves * kWave) __attribute__((amdgpu_waves_per_eu(MODE == DecMode::Half1 ? 2 : 4)))
 void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArgs a)
 {
+    static_assert(!PREV || MODE == DecMode::Half1, "only the second half-step reads two streams");
     extern __shared__ __align__(16) uint32_t s_dyn[];    // [waves][1 or 2][stage_stride]
     __shared__ __align__(16) unsigned char s_tab[kTabBytes];
 
     const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
-    constexpr int kBufs = (MODE == DecMode::Half1) ? 2 : 1;
+    constexpr int kBufs = PREV ? 2 : 1;
     constexpr bool kExact = MODE == DecMode::Decode;
     const uint32_t stage_words = a.stage_words;          // words a chunk of this code can take
     const uint32_t stage_stride = a.stage_stride;        // padded size of one staging buffer, words
@@ -138,14 +170,16 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
     __syncthreads();
 
     const uint32_t g = (uint32_t)blockIdx.x * (blockDim.x >> 6) + (uint32_t)w;   // global wave number
+    const uint32_t n_pos = FULL ? lay.NC : lay.n_ragged;
     uint32_t c, k_first, k_count;
     if (MODE == DecMode::Decode) {
-        if (g >= lay.K * lay.NC) return;
-        k_first = g / lay.NC; c = g - k_first * lay.NC; k_count = 1;
+        if (g >= lay.K * n_pos) return;
+        k_first = g / n_pos; c = g - k_first * n_pos; k_count = 1;
     } else {
-        if (g >= lay.NC) return;
+        if (g >= n_pos) return;
         c = g; k_first = 0; k_count = lay.K;
     }
+    if (!FULL) c = lay.ragged_chunk[c];
     uint32_t clo, clen, bkt;
     if (lay.uniform_bucket) {                             // one segment: chunk geometry is arithmetic
         bkt = c / lay.waves_per_bucket;
@@ -158,8 +192,7 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
         bkt = lay.chunk_bucket[c];
     }
     const int cnt = (int)min(64u, clen > 64u * (uint32_t)lane ? clen - 64u * (uint32_t)lane : 0u);
-    const bool full = clen == (uint32_t)kChunk;           // wave-uniform: every lane has 64 coordinates
-    const bool have_prev = (MODE == DecMode::Half1) && a.payload_p != nullptr;
+    if ((clen == (uint32_t)kChunk) != FULL) return;      // wave-uniform: the other launch takes this position
     // a cursor from a corrupt table is pulled back so that 64 symbols from it stay inside the buffer
     const uint32_t p_limit = stage_words * 32u - 64u * (uint32_t)kMaxSymBits - 64u;
 
@@ -170,29 +203,33 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
     uint32_t flags = 0;
     bool malformed = false;
 
-    // worker k's chunk and its per-lane cursors travel one iteration ahead, in registers
+    // worker k's chunk(s) and the per-lane cursors travel one iteration ahead, in registers
     uint4 pre[kPre];
+    uint4 pre_p[PREV ? kPre : 1];
     ChunkRef cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, a.sub_end, k_first, c, lay.NC, stage_words, sc);
     prefetch_chunk(cr, pre);
     SubMeta nxt = load_meta(a.sub_end, a.norms, k_first, c, bkt, lay, lane);
+    SubMeta nxt_p{0u, 0u, 0.0f};
+    if constexpr (PREV) {
+        cr = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, a.sub_end_p, k_first, c, lay.NC, stage_words, sc);
+        prefetch_chunk(cr, pre_p);
+        nxt_p = load_meta(a.sub_end_p, a.norms_p, k_first, c, bkt, lay, lane);
+    }
 
     for (uint32_t kk = 0; kk < k_count; ++kk) {
         const uint32_t k = k_first + kk;
-        const SubMeta cur = nxt;
+        const SubMeta cur = nxt, prv = nxt_p;
         commit_chunk(stage, pre, stage_words);
-        SubMeta prv{0u, 0u, 0.0f};
-        if constexpr (MODE == DecMode::Half1) {
-            if (have_prev) {                         // the previous half-step's chunk goes through the same registers
-                prv = load_meta(a.sub_end_p, a.norms_p, k, c, bkt, lay, lane);
-                ChunkRef cp = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, a.sub_end_p, k, c, lay.NC, stage_words, sc);
-                prefetch_chunk(cp, pre);
-                commit_chunk(stage_p, pre, stage_words);
-            }
-        }
-        if (kk + 1 < k_count) {                      // next worker's chunk: in flight while this one is parsed
+        if constexpr (PREV) commit_chunk(stage_p, pre_p, stage_words);
+        if (kk + 1 < k_count) {                      // next worker's chunks: in flight while these are parsed
             cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, a.sub_end, k + 1, c, lay.NC, stage_words, sc);
             nxt = load_meta(a.sub_end, a.norms, k + 1, c, bkt, lay, lane);
             prefetch_chunk(cr, pre);
+            if constexpr (PREV) {
+                cr = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, a.sub_end_p, k + 1, c, lay.NC, stage_words, sc);
+                nxt_p = load_meta(a.sub_end_p, a.norms_p, k + 1, c, bkt, lay, lane);
+                prefetch_chunk(cr, pre_p);
+            }
         }
         uint32_t p = cur.p0, pp = prv.p0;
         if (p > p_limit) { p = p_limit; malformed = true; }
@@ -200,23 +237,60 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
         const float n = cur.n, np = prv.n;
         float* vout = nullptr;
         if constexpr (MODE == DecMode::Decode) vout = a.out + (size_t)k * lay.d + clo + 64u * (uint32_t)lane;
-        if (full && MODE != DecMode::Half1) {
+        uint32_t win[3], e[3], win_p[3] = {0u, 0u, 0u}, e_p[3] = {0u, 0u, 0u};
+        if constexpr (FULL) {                        // 21 groups of three symbols and a last one
+            Window wn = read_window(stage, p), wn_p{0u, 0u, 0u};
+            if constexpr (PREV) wn_p = read_window(stage_p, pp);
 #pragma unroll
-            for (int s = 0; s < kSub; ++s) {
-                const float val = take_symbol<kExact>(stage, s_tab, p, n, flags);
-                if constexpr (MODE == DecMode::Decode) vout[s] = val;
-                else acc[s] += val;
+            for (int s = 0; s < kSub; s += 3) {
+                if (s + 3 <= kSub) parse_group<3>(wn, s_tab, p, win, e);
+                else parse_group<1>(wn, s_tab, p, win, e);
+                if (s + 3 < kSub) wn = read_window(stage, p);        // the next group's words: issued before the values
+                if constexpr (PREV) {
+                    if (s + 3 <= kSub) parse_group<3>(wn_p, s_tab, pp, win_p, e_p);
+                    else parse_group<1>(wn_p, s_tab, pp, win_p, e_p);
+                    if (s + 3 < kSub) wn_p = read_window(stage_p, pp);
+                }
+                float lv[3], lv_p[3] = {0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int i = 0; i < 3; ++i) {
+                    if (s + i < kSub) {
+                        lv[i] = level_of(s_tab, e[i]);
+                        flags |= e[i];
+                        if constexpr (PREV) { lv_p[i] = level_of(s_tab, e_p[i]); flags |= e_p[i]; }
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 3; ++i) {
+                    if (s + i < kSub) {
+                        const float val = symbol_value<kExact>(lv[i], win[i], e[i], n);
+                        if constexpr (MODE == DecMode::Decode) vout[s + i] = val;
+                        else acc[s + i] += val;
+                        if constexpr (MODE == DecMode::Half1) {
+                            float pv = 0.0f;
+                            if constexpr (PREV) pv = symbol_value<true>(lv_p[i], win_p[i], e_p[i], np);
+                            const double df = (double)pv - (double)val;
+                            sdiff = fma(df, df, sdiff);
+                        }
+                    }
+                }
             }
         } else {
 #pragma unroll
             for (int s = 0; s < kSub; ++s) {
                 if (s < cnt) {
-                    const float val = take_symbol<kExact>(stage, s_tab, p, n, flags);
+                    parse_group<1>(read_window(stage, p), s_tab, p, win, e);
+                    flags |= e[0];
+                    const float val = symbol_value<kExact>(level_of(s_tab, e[0]), win[0], e[0], n);
                     if constexpr (MODE == DecMode::Decode) vout[s] = val;
                     else acc[s] += val;
                     if constexpr (MODE == DecMode::Half1) {
                         float pv = 0.0f;
-                        if (have_prev) pv = take_symbol<true>(stage_p, s_tab, pp, np, flags);
+                        if constexpr (PREV) {
+                            parse_group<1>(read_window(stage_p, pp), s_tab, pp, win_p, e_p);
+                            flags |= e_p[0];
+                            pv = symbol_value<true>(level_of(s_tab, e_p[0]), win_p[0], e_p[0], np);
+                        }
                         const double df = (double)pv - (double)val;
                         sdiff = fma(df, df, sdiff);
                     }
@@ -224,8 +298,8 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
             }
         }
         if (cnt > 0 && p != cur.p_end) malformed = true;
-        if constexpr (MODE == DecMode::Half1) {
-            if (have_prev && cnt > 0 && pp != prv.p_end) malformed = true;
+        if constexpr (PREV) {
+            if (cnt > 0 && pp != prv.p_end) malformed = true;
         }
     }
     malformed = malformed || (flags & 0x8000u) != 0u;
@@ -239,7 +313,7 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
         sdiff = wave_sum(sdiff);
         if (lane == 0) a.s_partial[c] = sdiff;
     }
-    if (full) {
+    if constexpr (FULL) {
         // Lane L holds coordinates 64L..64L+63 of the chunk.  Through LDS, 16 symbols at a time, the
         // wave turns them so that four consecutive lanes own 16 consecutive floats: global accesses
         // then touch whole 64-byte pieces instead of 16 bytes per 256.
@@ -290,32 +364,44 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
     }
 }
 
-template <DecMode MODE>
-static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
+template <DecMode MODE, bool FULL, bool PREV>
+static hipError_t launch_one(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
 {
-    constexpr int bufs = (MODE == DecMode::Half1) ? 2 : 1;
-    const size_t lds = (size_t)kDecWaves * bufs * a.stage_stride * sizeof(uint32_t);
+    const uint64_t n_pos = FULL ? lay.NC : lay.n_ragged;
+    if (n_pos == 0 || (FULL && lay.n_ragged == lay.NC)) return hipSuccess;
+    const size_t lds = (size_t)kDecWaves * (PREV ? 2 : 1) * a.stage_stride * sizeof(uint32_t);
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<MODE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<MODE, FULL, PREV>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 140 * 1024);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    const uint64_t nwork = (MODE == DecMode::Decode) ? (uint64_t)lay.K * lay.NC : (uint64_t)lay.NC;
+    const uint64_t nwork = (MODE == DecMode::Decode) ? (uint64_t)lay.K * n_pos : n_pos;
     const uint32_t grid = (uint32_t)((nwork + kDecWaves - 1) / kDecWaves);
-    hipLaunchKernelGGL(k_decode<MODE>, dim3(grid), dim3(kDecWaves * kWave), lds, st, lay, tab, sc, a);
+    hipLaunchKernelGGL((k_decode<MODE, FULL, PREV>), dim3(grid), dim3(kDecWaves * kWave), lds, st, lay, tab, sc, a);
     return hipGetLastError();
+}
+
+// Two launches cover the chunk positions: the full ones, then the ragged ones (if the layout has any).
+template <DecMode MODE, bool PREV>
+static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
+{
+    hipError_t e = launch_one<MODE, true, PREV>(lay, tab, sc, a, st);
+    if (e != hipSuccess) return e;
+    return launch_one<MODE, false, PREV>(lay, tab, sc, a, st);
 }
 
 hipError_t launch_decode(DecMode mode, const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a,
                          hipStream_t st)
 {
     switch (mode) {
-        case DecMode::Decode: return launch_mode<DecMode::Decode>(lay, tab, sc, a, st);
-        case DecMode::Average: return launch_mode<DecMode::Average>(lay, tab, sc, a, st);
-        case DecMode::Half0: return launch_mode<DecMode::Half0>(lay, tab, sc, a, st);
-        default: return launch_mode<DecMode::Half1>(lay, tab, sc, a, st);
+        case DecMode::Decode: return launch_mode<DecMode::Decode, false>(lay, tab, sc, a, st);
+        case DecMode::Average: return launch_mode<DecMode::Average, false>(lay, tab, sc, a, st);
+        case DecMode::Half0: return launch_mode<DecMode::Half0, false>(lay, tab, sc, a, st);
+        default:
+            return a.payload_p ? launch_mode<DecMode::Half1, true>(lay, tab, sc, a, st)
+                               : launch_mode<DecMode::Half1, false>(lay, tab, sc, a, st);
     }
 }
 

@@ -83,7 +83,9 @@ struct Layout {                 // device pointers into one allocation
     const uint32_t* bucket_chunk0;  // [NB+1] first chunk of each bucket
     const uint32_t* chunk_start;    // [NC+1]
     const uint32_t* chunk_bucket;   // [NC]
+    const uint32_t* ragged_chunk;   // [n_ragged] chunk positions with fewer than kChunk coordinates, ascending
     uint32_t NB, NC, K, d;
+    uint32_t n_ragged;
     uint32_t waves_per_bucket;      // ceil(bucket / kChunk)
     uint32_t uniform_bucket;        // bucket size if there is one segment (offsets are then arithmetic), else 0
 };

@@ -134,7 +134,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     if (sum != cfg->d) { delete c; return QGX_ERR_ARG; }
 
     // buckets and chunks of one worker
-    std::vector<uint32_t> bstart, bchunk0, cstart, cbucket;
+    std::vector<uint32_t> bstart, bchunk0, cstart, cbucket, ragged;
     uint64_t pos = 0, worst = 0;
     for (uint64_t len_s : c->seg) {
         uint64_t left = len_s;
@@ -144,6 +144,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
             bchunk0.push_back((uint32_t)cstart.size());
             for (uint64_t o = 0; o < len; o += kChunk) {
                 const uint64_t cl = (len - o) < (uint64_t)kChunk ? (len - o) : (uint64_t)kChunk;
+                if (cl < (uint64_t)kChunk) ragged.push_back((uint32_t)cstart.size());
                 cstart.push_back((uint32_t)(pos + o));
                 cbucket.push_back((uint32_t)(bstart.size() - 1));
                 uint64_t wds = (cl * kMaxSymBits + 31) / 32;
@@ -161,15 +162,18 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     c->worst_words = worst;
 
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return QGX_ERR_HIP; }
-    const size_t n_lay = (size_t)(NB + 1) * 2 + (NC + 1) + NC;
+    const size_t n_lay = (size_t)(NB + 1) * 2 + (NC + 1) + NC + ragged.size() + 1;
     std::vector<uint32_t> flat;
     flat.reserve(n_lay);
     flat.insert(flat.end(), bstart.begin(), bstart.end());
     flat.insert(flat.end(), bchunk0.begin(), bchunk0.end());
     flat.insert(flat.end(), cstart.begin(), cstart.end());
     flat.insert(flat.end(), cbucket.begin(), cbucket.end());
+    flat.insert(flat.end(), ragged.begin(), ragged.end());
+    flat.push_back(0u);
 
     c->lay.NB = NB; c->lay.NC = NC; c->lay.K = cfg->K; c->lay.d = (uint32_t)cfg->d;
+    c->lay.n_ragged = (uint32_t)ragged.size();
     uint32_t max_len = 0;
     for (uint32_t b = 0; b < NB; ++b) max_len = bstart[b + 1] - bstart[b] > max_len ? bstart[b + 1] - bstart[b] : max_len;
     c->lay.waves_per_bucket = (max_len + kChunk - 1) / kChunk;
@@ -202,6 +206,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     c->lay.bucket_chunk0 = c->d_layout + (NB + 1);
     c->lay.chunk_start = c->d_layout + 2 * (size_t)(NB + 1);
     c->lay.chunk_bucket = c->lay.chunk_start + (NC + 1);
+    c->lay.ragged_chunk = c->lay.chunk_bucket + NC;
     *out = c;
     return QGX_OK;
 }
@@ -393,7 +398,7 @@ qgx_status qgx_quantize_encode(qgx_ctx* ctx, const float* V, uint32_t call_id, c
 static void fill_decode_args(const qgx_ctx* ctx, DecodeArgs& a, const qgx_stream* cur, const qgx_stream* prev)
 {
     a.stage_words = chunk_slot_words(ctx);
-    a.stage_stride = (a.stage_words + a.stage_words / 32 + 8 + 3) / 4 * 4;
+    a.stage_stride = (a.stage_words + a.stage_words / 16 + 12 + 3) / 4 * 4;
     if (a.stage_stride < 1280u) a.stage_stride = 1280u;   // the buffer also turns the output (64 rows of 20 floats)
     a.norms = cur->norms; a.chunk_off = cur->chunk_off; a.sub_end = cur->sub_end; a.payload = cur->payload;
     a.cap_words = cur->payload_words_per_worker;
