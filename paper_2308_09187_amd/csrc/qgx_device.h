@@ -71,6 +71,29 @@ __device__ __forceinline__ uint32_t bcast_lane(uint32_t x, int src)
     return (uint32_t)__shfl((int)x, src, kWave);
 }
 
+// LDS accesses by byte address.  A pointer derived from the dynamic LDS array carries the array's
+// base as a late-bound addend that the compiler adds again on every access; an address computed once
+// as an integer does not.
+__device__ __forceinline__ uint32_t lds_address(const void* p)
+{
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
+}
+
+typedef uint32_t lds_u32x2 __attribute__((ext_vector_type(2)));
+typedef float lds_f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint2 lds_load_u2(uint32_t addr)
+{
+    const lds_u32x2 r = *(const __attribute__((address_space(3))) lds_u32x2*)(uintptr_t)addr;
+    return make_uint2(r.x, r.y);
+}
+
+__device__ __forceinline__ float4 lds_load_f4(uint32_t addr)
+{
+    const lds_f32x4 r = *(const __attribute__((address_space(3))) lds_f32x4*)(uintptr_t)addr;
+    return make_float4(r.x, r.y, r.z, r.w);
+}
+
 __device__ __forceinline__ void raise_error(Scalars* sc, unsigned int bit)
 {
     atomicOr(&sc->err, bit);

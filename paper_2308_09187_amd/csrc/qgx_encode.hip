@@ -88,9 +88,10 @@ __device__ uint32_t lookback_exclusive(unsigned long long* state, uint32_t b, ui
     return excl;
 }
 
-struct LdsPlan {                 // where things live in the workgroup's LDS (byte offsets)
-    const float2* cell;
-    const unsigned char* lev;    // two sign halves, lev_stride bytes apart
+struct LdsPlan {                 // where things live in the workgroup's LDS
+    const float2* cell;          // cell table; an entry's second word is the LDS address of a level row
+    const unsigned char* lev;    // level rows, two sign halves, lev_stride bytes apart
+    uint32_t lev_addr;           // LDS byte address of the level rows (the cell table sits at address 0)
     uint32_t lev_stride, sign_shift;
 };
 
@@ -100,7 +101,7 @@ __device__ __forceinline__ uint32_t level_row_general(const LdsPlan& L, float u,
 {
     const float um = fminf(fmaxf(u, __uint_as_float((uint32_t)kCellKey0 << kCellShift)), 1.0f);
     const float2 c = L.cell[(__float_as_uint(um) >> kCellShift) - kCellKey0];
-    uint32_t j = (__float_as_uint(c.y) & 0xFFFFu) >> 4;
+    uint32_t j = (__float_as_uint(c.y) - L.lev_addr) >> 4;
     while (j + 2 < n_sym && reinterpret_cast<const float4*>(L.lev)[j + 1].x <= u) ++j;
     return j << 4;
 }
@@ -113,18 +114,23 @@ __device__ __forceinline__ uint32_t quantize_one(float x, float rinv, uint32_t r
                                                  uint32_t& idx_out)
 {
     float u = fabsf(x) * rinv;                          // |v| / ||v||
-    uint32_t row;
+    const uint32_t sg = (__float_as_uint(x) >> L.sign_shift) & L.lev_stride;   // sign selects the table half
+    float4 t;
+    uint32_t row;                                       // byte offset of the level row in its half
     if (FAST) {
-        const float um = fmaxf(u, __uint_as_float((uint32_t)kCellKey0 << kCellShift));
-        const float2 c = L.cell[(__float_as_uint(um) >> kCellShift) - kCellKey0];
-        const uint32_t a = __float_as_uint(c.y);
-        row = (u >= c.x) ? (a >> 16) : (a & 0xFFFFu);
+        // cell number times eight; a saturating subtraction sends everything below the first cell there
+        const uint32_t key8 = (__builtin_elementwise_sub_sat(__float_as_uint(u), (uint32_t)kCellKey0 << kCellShift)
+                               >> (kCellShift - 3)) & 0xFFF8u;
+        const uint2 c = lds_load_u2(key8);          // the cell table starts at LDS address 0 (checked at entry)
+        // the cell's lower row, or the next one from the boundary level on (one level per cell at most)
+        const uint32_t at = sg + c.y + (u >= __uint_as_float(c.x) ? 16u : 0u);
+        t = lds_load_f4(at);
+        row = (at - L.lev_addr) & (L.lev_stride - 1u);
     } else {
         u = fminf(u, 1.0f);
         row = level_row_general(L, u, n_sym);
+        t = *reinterpret_cast<const float4*>(L.lev + (row | sg));
     }
-    const uint32_t sg = (__float_as_uint(x) >> L.sign_shift) & L.lev_stride;   // sign selects the table half
-    const float4 t = *reinterpret_cast<const float4*>(L.lev + (row | sg));
     // up with probability xi = (u - l_j) / (l_{j+1} - l_j):  r * gap < u - l_j, r = top 24 bits * 2^-24
     const float rr = (float)(rnd >> 8);                 // exact
     const bool up = rr * t.y < u - t.x;                 // t.y = gap * 2^-24 (exact scaling)
@@ -221,11 +227,18 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
     unsigned char* s_lev = s_all + kCellsPad * sizeof(float2);
     uint16_t (*s_sub)[kSubs] = reinterpret_cast<uint16_t (*)[kSubs]>(s_lev + 2 * a.lev_stride);
     double* s_red = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(s_sub) + nwaves * kSubs * 2);
-    uint32_t* s_words = reinterpret_cast<uint32_t*>(s_red + kMaxWaves);
-    uint32_t* s_misc = s_words + kMaxWaves;
+    uint32_t* s_words = reinterpret_cast<uint32_t*>(s_red + nwaves);
+    uint32_t* s_misc = s_words + (nwaves + 3) / 4 * 4;
     uint32_t* stage = reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(s_misc) + 32 + (size_t)w * a.stage_bytes);
     LdsPlan L;
     L.cell = s_cell; L.lev = s_lev; L.lev_stride = a.lev_stride; L.sign_shift = a.sign_shift;
+    L.lev_addr = lds_address(s_lev);
+    // The straight-line lookup addresses the cell table by number: the kernel has no static LDS, so
+    // the dynamic array (and with it the table) starts at address 0.
+    if (lds_address(s_all) != 0u) {
+        if (tid == 0) raise_error(sc, QGX_EBIT_STATE);
+        return;
+    }
 
     // Compact placement: buckets by ticket (the ticket first: the table loads overlap its latency).
     // Slotted placement and plain quantisation have no order to keep: the bucket is the block's own.
@@ -237,7 +250,11 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
         reinterpret_cast<float4*>(s_lev)[i] = tab->lev2[0][i];
         reinterpret_cast<float4*>(s_lev + a.lev_stride)[i] = tab->lev2[1][i];
     }
-    for (int i = tid; i < kCells; i += (int)blockDim.x) s_cell[i] = tab->cell[i];
+    for (int i = tid; i < kCells; i += (int)blockDim.x) {
+        float2 c = tab->cell[i];                       // row offset -> LDS address of the row
+        c.y = __uint_as_float((__float_as_uint(c.y) & 0xFFFFu) + L.lev_addr);
+        s_cell[i] = c;
+    }
     if (MODE != EncMode::QuantOnly) {
         for (uint32_t q = (uint32_t)lane; q < a.stage_bytes / 16; q += kWave)
             reinterpret_cast<uint4*>(stage)[q] = make_uint4(0, 0, 0, 0);
@@ -429,7 +446,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
 static size_t encode_lds_bytes(int waves, const EncodeArgs& a, bool with_stage)
 {
     size_t n = kCellsPad * sizeof(float2) + 2 * (size_t)a.lev_stride + (size_t)waves * kSubs * 2 +
-               kMaxWaves * (sizeof(double) + sizeof(uint32_t)) + 32;
+               (size_t)waves * sizeof(double) + (size_t)(waves + 3) / 4 * 4 * sizeof(uint32_t) + 32;
     if (with_stage) n += (size_t)waves * a.stage_bytes;
     return n;
 }

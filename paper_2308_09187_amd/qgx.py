@@ -13,7 +13,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libqgx.so")
+# QGX_LIB names another build of the same library (to time two builds side by side)
+LIB_PATH = os.environ.get("QGX_LIB") or os.path.join(_HERE, "libqgx.so")
 
 OK = 0
 ERR_ARG, ERR_LEVELS, ERR_CAPACITY, ERR_STREAM, ERR_NONFINITE, ERR_HIP, ERR_STATE = -1, -2, -3, -4, -5, -6, -7
