@@ -124,14 +124,30 @@ __global__ __launch_bounds__(1024) void k_histogram(Layout lay, const float* __r
         partial[(size_t)blockIdx.x * n_bins + i] = s_acc[i];
 }
 
+// Workgroup sums -> histogram, in an order that does not depend on timing: a thread adds a run of
+// kRedRun consecutive workgroups' values of one bin, then the runs of a bin are added in order.
+constexpr uint32_t kRedRun = 32;
+constexpr uint32_t kRedBins = 32;      // bins per workgroup of 256 threads: 8 runs in flight per bin
+
 __global__ __launch_bounds__(256) void k_hist_reduce(uint32_t n_bins, uint32_t n_partial,
                                                      const double* __restrict__ partial, double* __restrict__ hist)
 {
-    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
-    if (i >= n_bins) return;
-    double acc = 0.0;
-    for (uint32_t g = 0; g < n_partial; ++g) acc += partial[(size_t)g * n_bins + i];
-    hist[i] = acc;
+    __shared__ double s_run[8][kRedBins];
+    const uint32_t bl = threadIdx.x & (kRedBins - 1u), seg = threadIdx.x / kRedBins;     // 8 segments
+    const uint32_t i = blockIdx.x * kRedBins + bl;
+    double tot = 0.0;
+    for (uint32_t g0 = 0; g0 < n_partial; g0 += 8u * kRedRun) {
+        const uint32_t lo = g0 + seg * kRedRun, hi = min(lo + kRedRun, n_partial);
+        double acc = 0.0;
+        if (i < n_bins)
+            for (uint32_t g = lo; g < hi; ++g) acc += partial[(size_t)g * n_bins + i];
+        s_run[seg][bl] = acc;
+        __syncthreads();
+        if (seg == 0)
+            for (int q = 0; q < 8; ++q) tot += s_run[q][bl];
+        __syncthreads();
+    }
+    if (seg == 0 && i < n_bins) hist[i] = tot;
 }
 
 uint32_t histogram_groups(const Layout& lay)
@@ -148,7 +164,8 @@ hipError_t launch_histogram(const Layout& lay, const float* V, int norm_kind, ui
                        n_bins, partial, sc);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_hist_reduce, dim3((n_bins + 255u) / 256u), dim3(256), 0, st, n_bins, n_partial, partial, hist);
+    hipLaunchKernelGGL(k_hist_reduce, dim3((n_bins + kRedBins - 1u) / kRedBins), dim3(256), 0, st, n_bins, n_partial,
+                       partial, hist);
     return hipGetLastError();
 }
 
@@ -160,7 +177,7 @@ hipError_t launch_histogram(const Layout& lay, const float* V, int norm_kind, ui
 // So each update is an inverse-CDF lookup: prefix sums of mass and first moment, one binary search.
 
 struct Cdf {
-    const double* H;      // global [n_bins]
+    const double* H;      // LDS [n_bins]
     const double* M0;     // LDS [n_bins+1]
     const double* M1;     // LDS [n_bins+1]
     uint32_t n_bins;
@@ -174,30 +191,58 @@ __device__ uint32_t bin_containing(const Cdf& F, double x)
     return b;
 }
 
-__device__ void cum_at(const Cdf& F, double x, double* m0, double* m1)
+// 1 / w for the width w of a bin other than the first: widths on the binary32 grid are powers of
+// two, so the reciprocal is an exponent flip and multiplying by it is the division, exactly.
+// (Bin 0 reaches from 0 to the second bin's edge, which is no power of two.)
+__device__ __forceinline__ double inv_pow2(double w)
+{
+    return __longlong_as_double(0x7FE0000000000000ll - __double_as_longlong(w));
+}
+
+struct Cum { double m0, m1; };      // mass and first moment of F~ below a point
+
+__device__ Cum cum_at(const Cdf& F, double x)
 {
     const uint32_t b = bin_containing(F, x);
     const double e0 = bin_edge(b, F.n_bins), e1 = bin_edge(b + 1, F.n_bins);
     const double h = F.H[b];
-    *m0 = F.M0[b] + h * (x - e0) / (e1 - e0);
-    *m1 = F.M1[b] + h / (e1 - e0) * 0.5 * (x * x - e0 * e0);
+    Cum c;
+    if (b == 0) {
+        c.m0 = F.M0[b] + h * (x - e0) / (e1 - e0);
+        c.m1 = F.M1[b] + h / (e1 - e0) * 0.5 * (x * x - e0 * e0);
+    } else {
+        const double iw = inv_pow2(e1 - e0);
+        c.m0 = F.M0[b] + h * (x - e0) * iw;
+        c.m1 = F.M1[b] + h * iw * 0.5 * (x * x - e0 * e0);
+    }
+    return c;
 }
 
-__device__ double stationary_point(const Cdf& F, double a, double c)
+// Smallest i in [1, n_bins] with M0[i] >= target, for 0 = M0[0] < target (M0 is non-decreasing; a
+// target a rounding above the total gives n_bins).  Sixteen-way: the 15 probes of a round do not
+// depend on each other.
+__device__ uint32_t first_at_least(const Cdf& F, double target)
 {
-    double m0a, m1a, m0c, m1c;
-    cum_at(F, a, &m0a, &m1a);
-    cum_at(F, c, &m0c, &m1c);
-    const double right_all = c * (m0c - m0a) - (m1c - m1a);      // int_a^c (c - u) dF~
-    if (!(right_all > 0.0)) return a;                             // no mass between the neighbours
-    const double target = m0a + right_all / (c - a);
-    // smallest i in [1, n_bins] with M0[i] >= target; the root lies in bin i-1
-    uint32_t lo = 1, hi = F.n_bins;
-    while (lo < hi) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (F.M0[mid] >= target) hi = mid; else lo = mid + 1;
+    uint32_t lo = 0, hi = F.n_bins;                 // M0[lo] < target, and the answer is at most hi
+    while (hi - lo > 1u) {
+        const uint32_t span = hi - lo;
+        uint32_t below = 0;                         // probes whose value is still under the target
+#pragma unroll
+        for (uint32_t q = 1; q < 16u; ++q) below += F.M0[lo + ((span * q) >> 4)] < target ? 1u : 0u;
+        const uint32_t nlo = lo + ((span * below) >> 4);
+        hi = below == 15u ? hi : lo + ((span * (below + 1u)) >> 4);
+        lo = nlo;
     }
-    const uint32_t b = lo - 1;
+    return hi;
+}
+
+// ca, cc: cumulatives at the neighbours a and c.
+__device__ double stationary_point(const Cdf& F, double a, double c, const Cum& ca, const Cum& cc)
+{
+    const double right_all = c * (cc.m0 - ca.m0) - (cc.m1 - ca.m1);   // int_a^c (c - u) dF~
+    if (!(right_all > 0.0)) return a;                                  // no mass between the neighbours
+    const double target = ca.m0 + right_all / (c - a);
+    const uint32_t b = first_at_least(F, target) - 1u;                 // the root lies in bin b
     const double e0 = bin_edge(b, F.n_bins), e1 = bin_edge(b + 1, F.n_bins);
     const double h = F.H[b];
     double x = e0;
@@ -205,14 +250,28 @@ __device__ double stationary_point(const Cdf& F, double a, double c)
     return fmin(fmax(x, a), c);
 }
 
+__device__ __forceinline__ Cum shfl_up1(const Cum& c)
+{
+    Cum r;
+    r.m0 = __shfl_up(c.m0, 1, kWave);
+    r.m1 = __shfl_up(c.m1, 1, kWave);
+    return r;
+}
+
+// The sweeps update level j from the new l_{j-1} and the old l_{j+1}, one level after the other.
+// Update (sweep s, level j) therefore only waits for (s, j-1) and (s-1, j+1), and all updates with
+// the same 2s + j can run together: lane s of one wave carries sweep s, two levels behind lane s-1,
+// and takes its upper neighbour from that lane's previous step.  Same arithmetic, same order, same
+// result as the plain double loop, in 2 sweeps + n_sym steps instead of sweeps * n_sym.
 __global__ __launch_bounds__(256) void k_fit(Tables* tab, const double* __restrict__ hist, uint32_t n_bins,
                                              uint32_t sweeps)
 {
     extern __shared__ __align__(16) unsigned char s_raw[];
     double* M0 = reinterpret_cast<double*>(s_raw);               // [n_bins+1]
     double* M1 = M0 + (n_bins + 1);                              // [n_bins+1]
+    double* H = M1 + (n_bins + 1);                               // [n_bins]
     __shared__ double s_part0[256], s_part1[256];
-    __shared__ double s_lev[kSymMax];
+    __shared__ double s_lev[kSymMax + 1], s_c0[kSymMax + 1], s_c1[kSymMax + 1];   // table between passes
 
     const uint32_t tid = threadIdx.x;
     const uint32_t per = (n_bins + 255u) / 256u;
@@ -220,6 +279,7 @@ __global__ __launch_bounds__(256) void k_fit(Tables* tab, const double* __restri
     double a0 = 0.0, a1 = 0.0;
     for (uint32_t b = b0; b < b1; ++b) {
         const double h = hist[b];
+        H[b] = h;
         a0 += h;
         a1 += h * 0.5 * (bin_edge(b, n_bins) + bin_edge(b + 1, n_bins));
     }
@@ -238,29 +298,59 @@ __global__ __launch_bounds__(256) void k_fit(Tables* tab, const double* __restri
     a0 = s_part0[tid]; a1 = s_part1[tid];
     for (uint32_t b = b0; b < b1; ++b) {
         M0[b] = a0; M1[b] = a1;
-        const double h = hist[b];
+        const double h = H[b];
         a0 += h;
         a1 += h * 0.5 * (bin_edge(b, n_bins) + bin_edge(b + 1, n_bins));
     }
-    const uint32_t n_sym = tab->n_sym;
-    if (tid < n_sym) s_lev[tid] = (double)tab->levels[tid];
     __syncthreads();
 
-    if (tid == 0) {
-        const Cdf F = {hist, M0, M1, n_bins};
-        if (M0[n_bins] > 0.0) {
-            for (uint32_t s = 0; s < sweeps; ++s)
-                for (uint32_t j = 1; j + 1 < n_sym; ++j) s_lev[j] = stationary_point(F, s_lev[j - 1], s_lev[j + 1]);
+    const Cdf F = {H, M0, M1, n_bins};
+    const uint32_t n_sym = tab->n_sym;
+    if (tid < n_sym) {
+        const double l = (double)tab->levels[tid];
+        const Cum c = cum_at(F, l);
+        s_lev[tid] = l; s_c0[tid] = c.m0; s_c1[tid] = c.m1;
+    }
+    __syncthreads();
+    if (tid >= (uint32_t)kWave) return;
+
+    const uint32_t lane = tid, top = n_sym - 1u;
+    const Cum c_top = {M0[n_bins], M1[n_bins]};                  // cumulatives at l_s = 1
+    if (M0[n_bins] > 0.0 && n_sym > 2u) {
+        for (uint32_t first = 0; first < sweeps; first += (uint32_t)kWave) {
+            const uint32_t ns = min((uint32_t)kWave, sweeps - first);    // sweeps of this pass, one per lane
+            double mine = 0.0;                      // the level this lane moved in its last step
+            Cum mine_c = {0.0, 0.0};
+            const uint32_t steps = 2u * (ns - 1u) + (top - 1u);
+            for (uint32_t t = 1; t <= steps; ++t) {
+                // the lane below moved level j + 1 one step ago
+                double above = __shfl_up(mine, 1, kWave);
+                Cum above_c = shfl_up1(mine_c);
+                const int j = (int)t - 2 * (int)lane;
+                const bool active = lane < ns && j >= 1 && j < (int)top;
+                if (active) {
+                    if (lane == 0) { above = s_lev[j + 1]; above_c.m0 = s_c0[j + 1]; above_c.m1 = s_c1[j + 1]; }
+                    if (j + 1 == (int)top) { above = 1.0; above_c = c_top; }
+                    const double below = j == 1 ? 0.0 : mine;
+                    const Cum below_c = j == 1 ? Cum{0.0, 0.0} : mine_c;
+                    mine = stationary_point(F, below, above, below_c, above_c);
+                    mine_c = cum_at(F, mine);
+                    if (lane == ns - 1u) { s_lev[j] = mine; s_c0[j] = mine_c.m0; s_c1[j] = mine_c.m1; }
+                }
+            }
         }
-        // back to binary32, strictly increasing with gaps of at least 2^-24
+    }
+    // back to binary32, strictly increasing with gaps of at least 2^-24: up from l_0 = 0, then down
+    // from l_s = 1; one lane, the table is short
+    if (lane == 0) {
         float* lv = tab->levels;
-        lv[0] = 0.0f; lv[n_sym - 1] = 1.0f;
-        for (uint32_t j = 1; j + 1 < n_sym; ++j) {
-            float x = (float)s_lev[j];
+        lv[0] = 0.0f; lv[top] = 1.0f;
+        for (uint32_t j = 1; j < top; ++j) {
+            const float x = (float)s_lev[j];
             const float floor_ = lv[j - 1] + 0x1p-24f;
             lv[j] = x < floor_ ? floor_ : x;
         }
-        for (uint32_t j = n_sym - 2; j >= 1; --j) {
+        for (uint32_t j = top - 1u; j >= 1u; --j) {
             const float ceil_ = lv[j + 1] - 0x1p-24f;
             if (lv[j] > ceil_) lv[j] = ceil_;
         }
@@ -269,12 +359,12 @@ __global__ __launch_bounds__(256) void k_fit(Tables* tab, const double* __restri
 
 hipError_t launch_fit(Tables* tab, const double* hist, uint32_t n_bins, uint32_t sweeps, hipStream_t st)
 {
-    const size_t lds = 2 * (size_t)(n_bins + 1) * sizeof(double);
+    const size_t lds = (3 * (size_t)n_bins + 2) * sizeof(double);
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fit),
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           2 * (QGX_MAX_BINS + 1) * (int)sizeof(double));
+                                           (3 * QGX_MAX_BINS + 2) * (int)sizeof(double));
         if (e != hipSuccess) return e;
         attr_done = true;
     }

@@ -73,6 +73,15 @@ def gaussian_vector(d: int = 1 << 20, seed: int = 10) -> np.ndarray:
 # ---------------------------------------------------------------------------
 
 
+def uniform_vectors(K: int, d: int, seed: int = 50) -> np.ndarray:
+    """[K][d] float32, iid U(-1, 1): with the L-infinity norm the normalised magnitudes fill (0, 1]
+    densely, so that a level fit on them has a unique answer."""
+    out = np.empty((K, d), np.float32)
+    for k in range(K):
+        out[k] = _rng(seed, k).uniform(-1.0, 1.0, d).astype(np.float32)
+    return out
+
+
 def student_t3(K: int, d: int, seed: int = 20, scale: float = 1e-2) -> np.ndarray:
     out = np.empty((K, d), np.float32)
     for k in range(K):

@@ -384,6 +384,27 @@ def test_dual_averaging_case_prev_null(qgx):
     ctx.close(); ctx2.close()
 
 
+def test_fit_levels_many_levels_and_sweeps(qgx):
+    """More sweeps than one pass of the solver carries (64) and more levels than one register set (64)."""
+    d, K, n_sym, n_bins, sweeps = (1 << 16) + 40, 2, 100, 256, 70
+    start = (np.linspace(0, 1, n_sym) ** 2).astype(np.float32)      # far from the fit, which is near uniform here
+    ctx, lay = make_ctx(qgx, d, K, 8192, oracle.NORM_LINF, start, seed=0)
+    # dense in (0, 1] under the L-infinity norm, and few enough bins that none is empty: unique roots
+    V = synth.uniform_vectors(K, d, seed=50)
+    hist = torch.zeros(n_bins, dtype=torch.float64, device="cuda")
+    ctx.fit_levels(dev(V), n_sym, n_bins, sweeps=sweeps, hist_out=hist)
+    H_o = oracle.histogram(V, lay, oracle.NORM_LINF, n_bins)
+    np.testing.assert_allclose(hist.cpu().numpy(), H_o, rtol=1e-12, atol=0)
+    assert (H_o > 0).all()
+    lv_g = ctx.get_levels()
+    lv_o = oracle.fit_levels(H_o, start, sweeps=sweeps)
+    assert np.abs(lv_o - oracle.fit_levels(H_o, start, sweeps=64)).max() > 1e-4     # the second pass matters
+    assert len(lv_g) == n_sym and lv_g[0] == 0 and lv_g[-1] == 1 and (np.diff(lv_g) > 0).all()
+    np.testing.assert_allclose(lv_g, lv_o, rtol=REL, atol=1e-9)
+    assert oracle.qada_objective(H_o, lv_g) <= oracle.qada_objective(H_o, lv_o) * (1 + 1e-9)
+    ctx.close()
+
+
 @pytest.mark.parametrize("norm,bucket,n_bins", [(oracle.NORM_L2, 16384, 4096), (oracle.NORM_LINF, 4096, 1024)])
 def test_fit_levels_parity(qgx, norm, bucket, n_bins):
     d, K, n_sym = (1 << 17) + 300, 3, 33
