@@ -269,6 +269,48 @@ def fit_levels(H, levels, sweeps):
     return lv
 
 
+def symbol_probabilities(H, levels):
+    """p_j of Proposition 1 on the histogram's piecewise-uniform density."""
+    H = _c(H, np.float64); lv = _c(levels, np.float32)
+    p = np.zeros(len(lv), np.float64)
+    lib().orc_symbol_probabilities(_p(H, C.c_double), C.c_uint32(len(H)), _p(lv, C.c_float), C.c_uint32(len(lv)),
+                                   _p(p, C.c_double))
+    return p
+
+
+def code_weights(p):
+    p = _c(p, np.float64)
+    w = np.zeros(len(p), np.uint64)
+    lib().orc_code_weights(_p(p, C.c_double), C.c_uint32(len(p)), _p(w, C.c_uint64))
+    return w
+
+
+def limited_prefix_lengths(w, max_len):
+    """Lengths of an optimal prefix code for integer weights w with no word longer than max_len."""
+    w = _c(w, np.uint64)
+    ln = np.zeros(len(w), np.uint8)
+    rc = lib().orc_limited_prefix_lengths(_p(w, C.c_uint64), C.c_uint32(len(w)), C.c_uint32(max_len), _p(ln, C.c_uint8))
+    if rc != 0:
+        raise ValueError("no prefix code with these limits")
+    return ln
+
+
+def canonical_code(lengths):
+    ln = _c(lengths, np.uint8)
+    bits = np.zeros(len(ln), np.uint32)
+    rc = lib().orc_canonical_code(_p(ln, C.c_uint8), C.c_uint32(len(ln)), _p(bits, C.c_uint32))
+    if rc != 0:
+        raise ValueError("lengths overfill the code space")
+    return bits
+
+
+def huffman_table(H, levels, max_len=13):
+    """(p, code_len, code_bits): Proposition 1's probabilities and the optimal prefix code on them."""
+    p = symbol_probabilities(H, levels)
+    ln = limited_prefix_lengths(code_weights(p), max_len)
+    return p, ln, canonical_code(ln)
+
+
 def qada_objective(H, levels):
     H = _c(H, np.float64); lv = _c(levels, np.float32)
     return float(lib().orc_qada_objective(_p(H, C.c_double), C.c_uint32(len(H)),

@@ -10,6 +10,9 @@
  *   mean over K workers + the two half-steps    Algorithm 1, eq. (Q-GenX)
  *   adaptive step size gamma_t                  Theorem 3 / Theorem 4
  *   adaptive levels from an empirical CDF       Section 3.3, eq. (QAda)
+ *   symbol probabilities p_j                    Proposition 1
+ *   Psi as an optimal prefix code on the p_j    Appendix J (Huffman), with a
+ *                                               limit on the word length
  *
  * Only tests, the smoke check and the cpu_baseline leg of the benchmark may
  * call this file.  It shares no source, header, table or helper with the HIP
@@ -21,7 +24,10 @@
  * eq. (var), the variance bound of Theorem 1, Lemma 2 (expected non-zeros),
  * exact expected code length, decode(encode(x)) == x, gamma_1 = K and
  * monotone gamma, the dual-averaging special case, the fine-level limit against
- * a textbook extra-gradient run, uniform-density => uniform levels for (QAda).
+ * a textbook extra-gradient run, uniform-density => uniform levels for (QAda),
+ * closed-form p_j on a uniform density and p_j against emitted symbol counts,
+ * the optimal code against a textbook Huffman merge (cost and H <= E[L] <= H+1)
+ * and, with the length limit active, against brute force over all lengths.
  *
  * parity unpinned: the container around the paper's bit string (chunk offset
  * table, sub-chunk table, 128-bit chunk alignment) is this project's own
@@ -627,6 +633,135 @@ double orc_qada_objective(const double* H, uint32_t n_bins, const float* levels,
         }
     }
     return total;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Symbol probabilities of Proposition 1: p_j is the mass F~ puts on l_j      */
+/* through the random rounding, i.e. the integral of the "hat" function that  */
+/* rises linearly from l_{j-1} to l_j and falls linearly to l_{j+1} (only the */
+/* falling half for l_0 = 0, read as (l_1 - u)/l_1 so that it is a            */
+/* probability; only the rising half for the last level), normalised by the   */
+/* total mass.  Evaluated bin by bin on the same piecewise-uniform density as */
+/* the fit: over a piece [lo, hi] of a bin the integral of a linear function  */
+/* is its value at the midpoint times the mass of the piece.                  */
+/* ------------------------------------------------------------------------ */
+void orc_symbol_probabilities(const double* H, uint32_t n_bins, const float* levels, uint32_t n_sym, double* p)
+{
+    double total = 0.0;
+    for (uint32_t b = 0; b < n_bins; ++b) total += H[b];
+    for (uint32_t j = 0; j < n_sym; ++j) p[j] = 0.0;
+    if (!(total > 0.0)) return;
+    for (uint32_t j = 0; j + 1 < n_sym; ++j) {          /* gap [a, c] feeds l_j (falling) and l_{j+1} (rising) */
+        const double a = (double)levels[j], c = (double)levels[j + 1];
+        for (uint32_t b = 0; b < n_bins; ++b) {
+            const double e0 = orc_bin_edge(b, n_bins), e1 = orc_bin_edge(b + 1, n_bins);
+            const double lo = a > e0 ? a : e0, hi = c < e1 ? c : e1;
+            if (!(hi > lo) || H[b] == 0.0) continue;
+            const double mass = H[b] * (hi - lo) / (e1 - e0);
+            const double mid = 0.5 * (lo + hi);
+            const double up = (mid - a) / (c - a);      /* probability of rounding up at the midpoint */
+            p[j] += mass * (1.0 - up);
+            p[j + 1] += mass * up;
+        }
+    }
+    for (uint32_t j = 0; j < n_sym; ++j) p[j] /= total;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Psi as an optimal prefix code for given symbol weights (Appendix J: Huffman*/
+/* coding when the symbol distribution is known or estimated), with no word   */
+/* longer than max_len bits.  Without the limit this is Huffman's code; with  */
+/* it, the optimal length-limited code, by the package-merge construction     */
+/* (Larmore and Hirschberg 1990): symbol i may buy one "coin" per level       */
+/* 1..max_len at price w_i; level by level, from the deepest up, the sorted   */
+/* coins are paired into packages that compete with the next level's coins;   */
+/* the cheapest 2(n-1) items of the top level are bought, and len_i is the    */
+/* number of coins of symbol i among them.  Weights are integers (exact       */
+/* sums); among equal weights a single coin goes before a package and a       */
+/* lower symbol index before a higher one.  n >= 2, 2^max_len >= n.           */
+/* Returns 0, or -1 if no such code exists.                                   */
+/* ------------------------------------------------------------------------ */
+int orc_limited_prefix_lengths(const uint64_t* w, uint32_t n, uint32_t max_len, uint8_t* len)
+{
+    if (n < 2 || max_len < 1 || max_len > 32 || (max_len < 32 && (1ull << max_len) < n)) return -1;
+    uint32_t* order = (uint32_t*)malloc(sizeof(uint32_t) * n);          /* symbols by weight, then index */
+    for (uint32_t i = 0; i < n; ++i) order[i] = i;
+    for (uint32_t i = 1; i < n; ++i) {                                   /* insertion sort: stable */
+        const uint32_t x = order[i];
+        uint32_t q = i;
+        while (q > 0 && w[order[q - 1]] > w[x]) { order[q] = order[q - 1]; --q; }
+        order[q] = x;
+    }
+    const uint32_t cap = 2 * n;
+    uint64_t* cur = (uint64_t*)malloc(sizeof(uint64_t) * cap);          /* weights of the list of the level */
+    uint64_t* nxt = (uint64_t*)malloc(sizeof(uint64_t) * cap);
+    uint8_t* is_pkg = (uint8_t*)calloc((size_t)max_len * cap, 1);        /* per level: 1 where the item is a package */
+    uint32_t* count = (uint32_t*)malloc(sizeof(uint32_t) * max_len);     /* items in the list of each level */
+    /* deepest level: the coins alone */
+    uint32_t m = n;
+    for (uint32_t i = 0; i < n; ++i) cur[i] = w[order[i]];
+    count[max_len - 1] = m;
+    for (int l = (int)max_len - 2; l >= 0; --l) {
+        /* packages of the level below, merged with this level's coins */
+        const uint32_t n_pk = m / 2;
+        uint32_t a = 0, b = 0, o = 0;
+        uint8_t* flag = is_pkg + (size_t)l * cap;
+        while (a < n || b < n_pk) {
+            const uint64_t wa = a < n ? w[order[a]] : 0, wb = b < n_pk ? cur[2 * b] + cur[2 * b + 1] : 0;
+            if (b >= n_pk || (a < n && wa <= wb)) { nxt[o] = wa; flag[o] = 0; ++a; }
+            else { nxt[o] = wb; flag[o] = 1; ++b; }
+            ++o;
+        }
+        m = o;
+        count[l] = m;
+        uint64_t* t = cur; cur = nxt; nxt = t;
+    }
+    /* buy the cheapest 2(n-1) items of the top level; a package stands for two items of the level below */
+    for (uint32_t i = 0; i < n; ++i) len[i] = 0;
+    uint32_t take = 2 * (n - 1);
+    for (uint32_t l = 0; l < max_len && take > 0; ++l) {
+        if (take > count[l]) take = count[l];
+        const uint8_t* flag = is_pkg + (size_t)l * cap;
+        uint32_t singles = 0, packages = 0;
+        for (uint32_t i = 0; i < take; ++i) { if (flag[i]) ++packages; else ++singles; }
+        for (uint32_t i = 0; i < singles; ++i) len[order[i]] += 1;       /* the coins of a level come in weight order */
+        take = 2 * packages;
+    }
+    free(order); free(cur); free(nxt); free(is_pkg); free(count);
+    return 0;
+}
+
+/* Integer weights for the code construction from probabilities: round(p * 2^32), at least 1 so   */
+/* that a symbol never seen in the fitted sample still gets a word.                                 */
+void orc_code_weights(const double* p, uint32_t n, uint64_t* w)
+{
+    for (uint32_t i = 0; i < n; ++i) {
+        const double x = floor(p[i] * 4294967296.0 + 0.5);
+        w[i] = x >= 1.0 ? (uint64_t)x : 1ull;
+    }
+}
+
+/* Canonical words for given lengths: symbols in order of (length, index) take consecutive binary  */
+/* numbers, read most significant bit first; bits[i] holds word i with its first bit in bit 0 (the */
+/* container's bit order).  Returns 0, or -1 if the lengths overfill the code space.               */
+int orc_canonical_code(const uint8_t* len, uint32_t n, uint32_t* bits)
+{
+    uint32_t code = 0, prev_len = 0;
+    uint64_t kraft = 0;                                     /* in units of 2^-32 */
+    for (uint32_t L = 1; L <= 32; ++L) {
+        for (uint32_t i = 0; i < n; ++i) {
+            if (len[i] != L) continue;
+            code <<= (L - prev_len);
+            prev_len = L;
+            kraft += 1ull << (32 - L);
+            if (kraft > (1ull << 32)) return -1;
+            uint32_t rev = 0;
+            for (uint32_t q = 0; q < L; ++q) rev |= ((code >> (L - 1 - q)) & 1u) << q;
+            bits[i] = rev;
+            ++code;
+        }
+    }
+    return 0;
 }
 
 uint32_t orc_chunk_coords(void) { return ORC_CH; }
