@@ -39,6 +39,9 @@ def parse_args():
     ap.add_argument("--full-iteration", action="store_true", help="also time encode + second half-step")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of the input (known size) to calibrate rocprofv3 HBM counters")
+    ap.add_argument("--code", choices=["omega", "huffman"], default="omega",
+                    help="Psi: Elias' recursive code of the level index (default) or the optimal prefix code "
+                         "fitted to the estimated symbol probabilities")
     ap.add_argument("--placement", choices=["slotted", "compact"], default="slotted",
                     help="chunk placement of the coded streams handed from the encoder to the update kernel")
     return ap.parse_args()
@@ -54,7 +57,7 @@ def measured_traffic():
         return None
 
 
-def cpu_baseline(args, levels, seed, V):
+def cpu_baseline(args, levels, seed, V, code=(None, None)):
     """The oracle as it stands on a bounded sample of the same workload: CODE o Q, DEQ, mean, half-step."""
     import numpy as np
 
@@ -65,8 +68,8 @@ def cpu_baseline(args, levels, seed, V):
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     t0 = time.perf_counter()
     norms, idx, neg, _ = oracle.quantize(V, lay, oracle.NORM_L2, levels, seed, 0)
-    s = oracle.encode(idx, neg, lay, cap_words=d // 2)
-    Vhat, _, _ = oracle.decode(s, norms, lay, levels)
+    s = oracle.encode(idx, neg, lay, cap_words=d // 2, code_len=code[0], code_bits=code[1])
+    Vhat, _, _ = oracle.decode(s, norms, lay, levels, code_len=code[0], code_bits=code[1])
     st.half0(Vhat)
     dt = time.perf_counter() - t0
     return {"value": 4.0 * K * d / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
@@ -93,10 +96,14 @@ def main():
     d, K, seed = 1 << args.logd, args.K, 2308
     V = synth.student_t3_device(K, d, seed=20)
     V1 = synth.student_t3_device(K, d, seed=21) if args.full_iteration else None
-    ctx = qgx.Context(d, K, args.bucket, norm=qgx.NORM_L2, seed=seed)
+    huffman = args.code == "huffman"
+    default_workload = (args.logd, args.K, args.bucket, args.n_sym, args.code, args.placement) == (24, 8, 16384, 33, "omega", "slotted")
+    ctx = qgx.Context(d, K, args.bucket, norm=qgx.NORM_L2, seed=seed,
+                      code=qgx.CODE_TABLE if huffman else qgx.CODE_ELIAS_OMEGA)
     ctx.set_levels(synth.levels_exponential(args.n_sym - 1))
     ctx.fit_levels(V, args.n_sym, 4096, sweeps=10)
     levels = ctx.get_levels()
+    code = ctx.fit_code()[1:] if huffman else (None, None)
     ctx.state_init(None)
     slotted = args.placement == "slotted"
     a, b = ctx.new_stream(slotted=slotted), ctx.new_stream(slotted=slotted)
@@ -151,16 +158,19 @@ def main():
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "K=%d x d=2^%d Student-t(3)*1e-2, bucket %d, L2, %d-symbol fitted table, Elias-omega; "
+        "config": {"workload": "K=%d x d=2^%d Student-t(3)*1e-2, bucket %d, L2, %d-symbol fitted table, %s; "
                                "%s chunk placement; step = fused CODE.Q + fused decode/average/half-step%s"
-                               % (K, args.logd, args.bucket, args.n_sym, args.placement,
+                               % (K, args.logd, args.bucket, args.n_sym,
+                                  "fitted optimal prefix code" if huffman else "Elias-omega", args.placement,
                                   " + CODE.Q + second half-step" if args.full_iteration else ""),
                    "K": K, "d": d, "bucket": args.bucket, "n_sym": args.n_sym,
                    "bits_per_coordinate": bits / float(K * d), "stream_bytes": stream_bytes},
         "hbm_frac_step": (enc_bytes + upd_bytes) / ((enc_ms + upd_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernels_ms": {"encode": enc_ms, "decode_avg_half0": upd_ms},
         "roofline": {"kernel": "k_encode<Fused>", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(),
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     # the committed counter run covers the default workload only
+                     "traffic": measured_traffic() if default_workload else None,
                      "algorithmic_bytes": enc_bytes},
     }
     if args.full_iteration:
@@ -173,7 +183,7 @@ def main():
         V_host = V[:, :ds].contiguous().cpu().numpy()
         del V, V1, a, b
         torch.cuda.empty_cache()
-        out["cpu_baseline"] = cpu_baseline(args, levels, seed, V_host)
+        out["cpu_baseline"] = cpu_baseline(args, levels, seed, V_host, code)
     print(json.dumps(out))
 
 

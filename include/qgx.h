@@ -170,6 +170,18 @@ qgx_status qgx_decode_average(qgx_ctx* ctx, const qgx_stream* in, float* mean, v
 qgx_status qgx_fit_levels(qgx_ctx* ctx, const float* V, uint32_t n_sym, uint32_t n_bins, uint32_t sweeps,
                           double* hist_out, void* stream);
 
+/* Psi from estimated symbol probabilities (Appendix J: Huffman coding when the distribution of the
+ * symbols can be estimated), only with QGX_CODE_TABLE.  p_j of Proposition 1 is taken from the
+ * histogram of the last qgx_fit_levels call (with sweeps = 0 that call only measures: a table whose
+ * gaps are at least 2^-24 stays as it is) and the current level table; the code is the optimal prefix code for the weights
+ * round(p_j 2^32), at least 1, with no word longer than QGX_MAX_CODE_BITS (Huffman's code whenever
+ * that limit is slack), words numbered canonically by (length, index).  It replaces the context's
+ * code table; the slot size of slotted streams follows its longest word (qgx_slot_words).
+ * p_host HOST [n_sym] doubles, code_len_host HOST [n_sym], code_bits_host HOST [n_sym] (layout as in
+ * qgx_set_code_table), each may be NULL.  Synchronises `stream`.
+ * QGX_ERR_STATE without a histogram, a level table, or QGX_CODE_TABLE. */
+qgx_status qgx_fit_code(qgx_ctx* ctx, double* p_host, uint8_t* code_len_host, uint32_t* code_bits_host, void* stream);
+
 /* State of eq. (Q-GenX): Y_1 = 0, S = 0, t = 1, gamma_1 = K, anchor = X1 (DEVICE [d] or NULL = 0).
  * The paper's X_{t+1} = gamma_{t+1} Y_{t+1} is the X1 = 0 case of X_{t+1} = X1 + gamma_{t+1} Y_{t+1}. */
 qgx_status qgx_state_init(qgx_ctx* ctx, const float* X1, void* stream);

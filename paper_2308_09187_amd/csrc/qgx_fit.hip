@@ -374,4 +374,126 @@ hipError_t launch_fit(Tables* tab, const double* hist, uint32_t n_bins, uint32_t
     return launch_build_tables(tab, st);
 }
 
+// ---- Psi from estimated symbol probabilities (Proposition 1; Appendix J, Huffman coding) ---------------
+// p_j: the mass F~ sends to level j through the random rounding.  Thread j walks the bins under the
+// gap below its level (rising part of its hat function) and then the gap above (falling part); a
+// piece of a bin contributes its mass times the rounding probability at its midpoint, which is exact
+// for the piecewise-uniform density.
+//
+// The code: optimal prefix code for the weights round(p 2^32) (at least 1) with no word longer than
+// max_len, by package-merge (Larmore and Hirschberg 1990); with a slack limit that is Huffman's code.
+// Every level offers each symbol one coin at the symbol's weight; from the deepest level up, the
+// sorted list of a level is paired into packages that are merged into the next level's coins; the
+// cheapest 2 (n - 1) entries of the top list are bought, a package standing for its two entries one
+// level down.  A symbol's length is the number of its coins bought.  Equal weights: coin before
+// package, lower index first.  Words are numbered canonically by (length, index), first bit first.
+__global__ __launch_bounds__(256) void k_fit_code(Tables* tab, const double* __restrict__ hist, uint32_t n_bins,
+                                                  uint32_t max_len, double* __restrict__ p_out)
+{
+    extern __shared__ __align__(16) unsigned char s_raw[];
+    double* H = reinterpret_cast<double*>(s_raw);                      // [n_bins]
+    __shared__ double s_part[256];
+    __shared__ double s_lev[kSymMax];
+    __shared__ unsigned long long s_w[kSymMax], s_cur[2 * kSymMax], s_nxt[2 * kSymMax];
+    __shared__ uint8_t s_pkg[kMaxCode][2 * kSymMax];
+    __shared__ uint32_t s_count[kMaxCode];
+    __shared__ uint8_t s_order[kSymMax], s_len[kSymMax];
+
+    const uint32_t tid = threadIdx.x, n = tab->n_sym;
+    double part = 0.0;
+    for (uint32_t b = tid; b < n_bins; b += 256u) { const double h = hist[b]; H[b] = h; part += h; }
+    s_part[tid] = part;
+    if (tid < n) s_lev[tid] = (double)tab->levels[tid];
+    __syncthreads();
+    for (uint32_t off = 128; off > 0; off >>= 1) {
+        if (tid < off) s_part[tid] += s_part[tid + off];
+        __syncthreads();
+    }
+    const double total = s_part[0];
+
+    if (tid < n) {
+        double acc = 0.0;
+        if (total > 0.0) {
+            for (int side = 0; side < 2; ++side) {                         // 0: gap below (rising), 1: gap above (falling)
+                if ((side == 0 && tid == 0) || (side == 1 && tid + 1 >= n)) continue;
+                const double a = side == 0 ? s_lev[tid - 1] : s_lev[tid], c = side == 0 ? s_lev[tid] : s_lev[tid + 1];
+                uint32_t b = bin_of((float)a, n_bins);
+                while (b > 0 && bin_edge(b, n_bins) > a) --b;
+                for (; b < n_bins; ++b) {
+                    const double e0 = bin_edge(b, n_bins), e1 = bin_edge(b + 1, n_bins);
+                    if (e0 >= c) break;
+                    const double lo = a > e0 ? a : e0, hi = c < e1 ? c : e1;
+                    if (!(hi > lo) || H[b] == 0.0) continue;
+                    const double mass = H[b] * (hi - lo) / (e1 - e0);
+                    const double up = (0.5 * (lo + hi) - a) / (c - a);
+                    acc += side == 0 ? mass * up : mass * (1.0 - up);
+                }
+            }
+            acc /= total;
+        }
+        p_out[tid] = acc;
+        const double x = floor(acc * 4294967296.0 + 0.5);
+        s_w[tid] = x >= 1.0 ? (unsigned long long)x : 1ull;
+    }
+    __syncthreads();
+    if (tid != 0) return;
+
+    // symbols by weight, then index (stable insertion sort)
+    for (uint32_t i = 0; i < n; ++i) s_order[i] = (uint8_t)i;
+    for (uint32_t i = 1; i < n; ++i) {
+        const uint8_t x = s_order[i];
+        uint32_t q = i;
+        while (q > 0 && s_w[s_order[q - 1]] > s_w[x]) { s_order[q] = s_order[q - 1]; --q; }
+        s_order[q] = x;
+    }
+    unsigned long long* cur = s_cur;
+    unsigned long long* nxt = s_nxt;
+    uint32_t m = n;
+    for (uint32_t i = 0; i < n; ++i) { cur[i] = s_w[s_order[i]]; s_pkg[max_len - 1][i] = 0; }
+    s_count[max_len - 1] = m;
+    for (int l = (int)max_len - 2; l >= 0; --l) {
+        const uint32_t n_pk = m >> 1;
+        uint32_t ia = 0, ib = 0, o = 0;
+        while (ia < n || ib < n_pk) {
+            const unsigned long long wa = ia < n ? s_w[s_order[ia]] : 0ull;
+            const unsigned long long wb = ib < n_pk ? cur[2 * ib] + cur[2 * ib + 1] : 0ull;
+            if (ib >= n_pk || (ia < n && wa <= wb)) { nxt[o] = wa; s_pkg[l][o] = 0; ++ia; }
+            else { nxt[o] = wb; s_pkg[l][o] = 1; ++ib; }
+            ++o;
+        }
+        m = o;
+        s_count[l] = m;
+        unsigned long long* t = cur; cur = nxt; nxt = t;
+    }
+    for (uint32_t i = 0; i < n; ++i) s_len[i] = 0;
+    uint32_t take = 2u * (n - 1u);
+    for (uint32_t l = 0; l < max_len && take > 0; ++l) {
+        take = min(take, s_count[l]);
+        uint32_t singles = 0, packages = 0;
+        for (uint32_t i = 0; i < take; ++i) { if (s_pkg[l][i]) ++packages; else ++singles; }
+        for (uint32_t i = 0; i < singles; ++i) s_len[s_order[i]] += 1;
+        take = 2u * packages;
+    }
+    // canonical words; the table wants the first-written bit in bit 0
+    uint32_t code = 0, prev_len = 0;
+    for (uint32_t L = 1; L <= max_len; ++L) {
+        for (uint32_t i = 0; i < n; ++i) {
+            if (s_len[i] != L) continue;
+            code <<= (L - prev_len);
+            prev_len = L;
+            tab->code[i] = (__brev(code) >> (32u - L)) | (L << 16);
+            ++code;
+        }
+    }
+}
+
+hipError_t launch_fit_code(Tables* tab, const double* hist, uint32_t n_bins, uint32_t max_len, double* p_out,
+                           hipStream_t st)
+{
+    hipLaunchKernelGGL(k_fit_code, dim3(1), dim3(256), (size_t)n_bins * sizeof(double), st, tab, hist, n_bins, max_len, p_out);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_build_tables(tab, st);
+}
+
 }  // namespace qgx

@@ -148,6 +148,8 @@ hipError_t launch_compact(const Layout& lay, const uint16_t* sub_end, const uint
                           uint64_t in_cap, uint32_t* out_off, uint32_t* out_payload, uint64_t out_cap, Scalars* sc,
                           hipStream_t st);
 hipError_t launch_fit(Tables* tab, const double* hist, uint32_t n_bins, uint32_t sweeps, hipStream_t st);
+hipError_t launch_fit_code(Tables* tab, const double* hist, uint32_t n_bins, uint32_t max_len, double* p_out,
+                           hipStream_t st);
 uint32_t histogram_groups(const Layout& lay);
 
 }  // namespace qgx

@@ -26,6 +26,8 @@ struct qgx_ctx {
     double* d_spartial = nullptr;
     double* d_hpartial = nullptr;
     double* d_hist = nullptr;
+    double* d_prob = nullptr;       // [kSymMax] symbol probabilities of the last qgx_fit_code
+    uint32_t hist_bins = 0;         // bins of the histogram d_hist holds (0: none yet)
     uint32_t h_groups = 0;
     uint32_t epoch = 0;
     uint32_t ticket_count = 0;
@@ -100,7 +102,7 @@ qgx_status need_levels(qgx_ctx* ctx)
 
 void free_all(qgx_ctx* c)
 {
-    void* all[] = {c->d_layout, c->d_tab, c->d_sc, c->d_Y, c->d_anchor, c->d_scan, c->d_tickets, c->d_spartial, c->d_hpartial, c->d_hist};
+    void* all[] = {c->d_layout, c->d_tab, c->d_sc, c->d_Y, c->d_anchor, c->d_scan, c->d_tickets, c->d_spartial, c->d_hpartial, c->d_hist, c->d_prob};
     for (void* p : all) (void)hipFree(p);
 }
 
@@ -191,6 +193,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     ok = ok && hipMalloc(&c->d_spartial, (size_t)NC * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_hpartial, (size_t)c->h_groups * QGX_MAX_BINS * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_hist, QGX_MAX_BINS * sizeof(double)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_prob, kSymMax * sizeof(double)) == hipSuccess;
     ok = ok && hipMemcpy(c->d_layout, flat.data(), n_lay * sizeof(uint32_t), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemset(c->d_tab, 0, sizeof(Tables)) == hipSuccess;
     ok = ok && hipMemset(c->d_sc, 0, sizeof(Scalars)) == hipSuccess;
@@ -448,6 +451,33 @@ qgx_status qgx_fit_levels(qgx_ctx* ctx, const float* V, uint32_t n_sym, uint32_t
     if (hist_out)
         QGX_HIP(ctx, hipMemcpyAsync(hist_out, ctx->d_hist, n_bins * sizeof(double), hipMemcpyDeviceToDevice, st));
     QGX_HIP(ctx, launch_fit(ctx->d_tab, ctx->d_hist, n_bins, sweeps, st));
+    ctx->hist_bins = n_bins;
+    return QGX_OK;
+}
+
+qgx_status qgx_fit_code(qgx_ctx* ctx, double* p_host, uint8_t* code_len_host, uint32_t* code_bits_host, void* stream)
+{
+    if (!ctx) return QGX_ERR_ARG;
+    if (ctx->cfg.code != QGX_CODE_TABLE) return fail(ctx, QGX_ERR_STATE, "context was not created with QGX_CODE_TABLE");
+    if (!ctx->levels_set || ctx->hist_bins == 0)
+        return fail(ctx, QGX_ERR_STATE, "qgx_fit_code needs the histogram of a qgx_fit_levels call (sweeps = 0 leaves the table as it is)");
+    uint32_t need = 1;
+    while ((1u << need) < ctx->n_sym) ++need;
+    if (need > QGX_MAX_CODE_BITS) return fail(ctx, QGX_ERR_ARG, "too many symbols for the longest code word");
+    hipStream_t st = (hipStream_t)stream;
+    QGX_HIP(ctx, launch_fit_code(ctx->d_tab, ctx->d_hist, ctx->hist_bins, QGX_MAX_CODE_BITS, ctx->d_prob, st));
+    uint32_t packed[kSymMax];
+    QGX_HIP(ctx, hipMemcpyAsync(packed, ctx->d_tab->code, sizeof(packed), hipMemcpyDeviceToHost, st));
+    if (p_host) QGX_HIP(ctx, hipMemcpyAsync(p_host, ctx->d_prob, ctx->n_sym * sizeof(double), hipMemcpyDeviceToHost, st));
+    QGX_HIP(ctx, hipStreamSynchronize(st));
+    ctx->max_code_len = 0;
+    for (uint32_t j = 0; j < ctx->n_sym; ++j) {
+        const uint32_t len = packed[j] >> 16;
+        ctx->max_code_len = len > ctx->max_code_len ? len : ctx->max_code_len;
+        if (code_len_host) code_len_host[j] = (uint8_t)len;
+        if (code_bits_host) code_bits_host[j] = packed[j] & 0xFFFFu;
+    }
+    ctx->code_set = true;
     return QGX_OK;
 }
 

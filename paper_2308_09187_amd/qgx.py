@@ -25,7 +25,7 @@ CHUNK, SUB, MAX_SYM, MAX_BINS = 4096, 64, 127, 4096
 
 EXPORTS = [
     "qgx_create", "qgx_destroy", "qgx_stream_sizes", "qgx_slot_words", "qgx_compact", "qgx_set_levels", "qgx_get_levels", "qgx_set_code_table",
-    "qgx_quantize", "qgx_encode", "qgx_quantize_encode", "qgx_decode", "qgx_decode_average", "qgx_fit_levels",
+    "qgx_quantize", "qgx_encode", "qgx_quantize_encode", "qgx_decode", "qgx_decode_average", "qgx_fit_levels", "qgx_fit_code",
     "qgx_state_init", "qgx_eg_step", "qgx_get_scalars", "qgx_state_export", "qgx_state_import",
     "qgx_poll_error", "qgx_last_error",
 ]
@@ -208,6 +208,14 @@ class Context:
     def fit_levels(self, V, n_sym, n_bins=4096, sweeps=10, hist_out=None, stream=None):
         self._check(self.lib.qgx_fit_levels(self._h, _ptr(V), C.c_uint32(n_sym), C.c_uint32(n_bins),
                                             C.c_uint32(sweeps), _ptr(hist_out), _stream_handle(stream)))
+
+    def fit_code(self, stream=None):
+        """Returns (p, code_len, code_bits) of the code the context now uses."""
+        n = len(self.get_levels(stream))
+        p = np.zeros(n, np.float64); cl = np.zeros(n, np.uint8); cb = np.zeros(n, np.uint32)
+        self._check(self.lib.qgx_fit_code(self._h, p.ctypes.data_as(C.c_void_p), cl.ctypes.data_as(C.c_void_p),
+                                          cb.ctypes.data_as(C.c_void_p), _stream_handle(stream)))
+        return p, cl, cb
 
     def state_init(self, X1=None, stream=None):
         self._check(self.lib.qgx_state_init(self._h, _ptr(X1), _stream_handle(stream)))

@@ -287,6 +287,72 @@ def test_table_code(qgx):
     ctx.close()
 
 
+@pytest.mark.parametrize("norm,table,limit_active", [(oracle.NORM_L2, "fit33", False), (oracle.NORM_LINF, "exp16", True)])
+def test_fit_code_parity(qgx, norm, table, limit_active):
+    """Psi from estimated symbol probabilities: p_j, the code and everything coded with it."""
+    d, K, bucket, n_bins = 5 * 4096 + 700, 3, 8192, 4096
+    start = synth.levels_exponential(32 if table == "fit33" else 16)
+    ctx = qgx.Context(d, K, bucket, norm=norm, code=qgx.CODE_TABLE, seed=11)
+    ctx.set_levels(start)
+    lay = oracle.layout(d, bucket)
+    V = synth.student_t3(K, d, seed=26) if norm == oracle.NORM_L2 else synth.uniform_vectors(K, d, seed=51)
+    with pytest.raises(qgx.QgxError):               # no histogram yet
+        ctx.fit_code()
+    hist = torch.zeros(n_bins, dtype=torch.float64, device="cuda")
+    ctx.fit_levels(dev(V), len(start), n_bins, sweeps=10 if table == "fit33" else 0, hist_out=hist)
+    lv = ctx.get_levels()
+    if table == "exp16":
+        np.testing.assert_array_equal(lv, start)    # sweeps = 0 only measures (gaps of 2^-24 or more stay)
+    p_g, cl_g, cb_g = ctx.fit_code()
+    H_g = hist.cpu().numpy()
+    np.testing.assert_allclose(H_g, oracle.histogram(V, lay, norm, n_bins), rtol=1e-12, atol=0)
+    p_o, cl_o, cb_o = oracle.huffman_table(H_g, lv, max_len=13)
+    np.testing.assert_allclose(p_g, p_o, rtol=1e-12, atol=1e-15)
+    assert abs(p_g.sum() - 1) < 1e-12
+    # the code is unique up to ties between equal weights; what is unique is its cost
+    w = oracle.code_weights(p_o)
+    assert int((w * cl_g.astype(np.uint64)).sum()) == int((w * cl_o.astype(np.uint64)).sum())
+    assert cl_g.max() <= 13 and sum(2.0 ** -int(x) for x in cl_g) <= 1.0
+    assert (cl_g.max() == 13) == limit_active or not limit_active
+    np.testing.assert_array_equal(cl_g, cl_o)       # and on these inputs no tie falls differently
+    np.testing.assert_array_equal(cb_g, cb_o)
+    # coding with it, both placements
+    out = ctx.new_stream()
+    ctx.quantize_encode(dev(V), 4, out)
+    h = out.to_host()
+    n, idx, neg, _ = oracle.quantize(V, lay, norm, lv, 11, 4, norms_in=h["norms"])
+    st_o = oracle.encode(idx, neg, lay, ctx.worst_words, code_len=cl_g, code_bits=cb_g)
+    assert_stream_equal(h, st_o, lay)
+    st_e = oracle.encode(idx, neg, lay, ctx.worst_words)
+    assert st_o.total_bits.sum() < st_e.total_bits.sum()         # fewer bits than the universal code
+    slot = ctx.slot_words()
+    outs = ctx.new_stream(slotted=True)
+    ctx.quantize_encode(dev(V), 4, outs)
+    assert_slotted_equal(outs.to_host(), st_o, lay, slot)
+    Vhat_o, _, _ = oracle.decode(st_o, h["norms"], lay, lv, code_len=cl_g, code_bits=cb_g)
+    np.testing.assert_array_equal(ctx.decode(out).cpu().numpy(), Vhat_o)
+    # and the fused updates on such streams
+    ctx.state_init(None)
+    eg = oracle.EGState(d, K)
+    Xh = torch.empty(d, device="cuda"); Xn = torch.empty(d, device="cuda")
+    ctx.eg_step(0, outs, None, Xh)
+    x_half = eg.half0(Vhat_o)
+    assert np.linalg.norm(Xh.cpu().numpy() - x_half) <= REL * max(np.linalg.norm(x_half), 1e-30)
+    cur = ctx.new_stream(slotted=True)
+    ctx.quantize_encode(dev(V[::-1].copy()), 5, cur)
+    hc = cur.to_host()
+    n2, idx2, neg2, _ = oracle.quantize(V[::-1].copy(), lay, norm, lv, 11, 5, norms_in=hc["norms"])
+    st2 = oracle.encode(idx2, neg2, lay, ctx.worst_words, code_len=cl_g, code_bits=cb_g)
+    Vhat2, _, _ = oracle.decode(st2, hc["norms"], lay, lv, code_len=cl_g, code_bits=cb_g)
+    ctx.eg_step(1, cur, outs, Xn)
+    x_next = eg.half1(Vhat2, Vhat_o)
+    sc = ctx.scalars()
+    assert abs(sc["S"] - eg.S) <= REL * eg.S and abs(sc["gamma"] - eg.gamma) <= REL * eg.gamma
+    assert np.linalg.norm(Xn.cpu().numpy() - x_next) <= REL * max(np.linalg.norm(x_next), 1e-30)
+    assert ctx.poll_error() == 0
+    ctx.close()
+
+
 def run_lockstep(qgx, game, levels, norm, bucket, T, seed, anchor, refit=None, n_bins=4096):
     """Q-GenX iterations in lock-step: every half-step the oracle consumes the GPU's dual vectors and
     norms, keeps its own binary64 state, and every result is compared."""
