@@ -420,6 +420,48 @@ def test_quadratic_game_lockstep_with_refit(qgx):
     assert worst <= REL
 
 
+def test_optimistic_dual_averaging_lockstep(qgx):
+    """The optimistic dual averaging case of eq. (Q-GenX): the first half-step reuses the previous
+    iteration's coded feedback g_{k,t-1/2} (nothing at t = 1), so every iteration codes once; the step
+    size follows the differences of consecutive half-step feedbacks."""
+    game = synth.BilinearGame(n=256, K=3, noise=0.1)
+    d, K, norm, seed, T = game.d, game.K, oracle.NORM_L2, 17, 30
+    levels = synth.levels_exponential(8)
+    ctx, lay = make_ctx(qgx, d, K, 512, norm, levels, seed)
+    x1 = game.x1()
+    ctx.state_init(dev(x1))
+    st = oracle.EGState(d, K, X1=x1)
+    streams = [ctx.new_stream(slotted=True), ctx.new_stream(slotted=True)]
+    tmp = ctx.new_stream()
+    Xh = torch.empty(d, device="cuda"); Xn = torch.empty(d, device="cuda")
+    X = x1.astype(np.float32)
+    Vhat_prev, worst = None, 0.0
+    for t in range(T):
+        cur, prev = streams[t & 1], streams[(t + 1) & 1]
+        if t == 0:
+            Xh_host, Xh_o = X, st.X()                     # no feedback yet: X_{3/2} = X_1
+        else:
+            ctx.eg_step(0, prev, None, Xh)
+            Xh_o = st.half0(Vhat_prev)
+            Xh_host = Xh.cpu().numpy()
+            worst = max(worst, rel_err(Xh_host, Xh_o))
+        V1 = game.dual_vectors(Xh_host, t)
+        ctx.quantize_encode(dev(V1), t, cur)
+        ctx.eg_step(1, cur, prev if t else None, Xn)
+        hc = ctx.compact(cur, tmp).to_host()
+        _, _, _, so = oracle_stream(V1, lay, norm, levels, seed, t, hc["norms"], ctx.worst_words)
+        assert_stream_equal(hc, so, lay)
+        Vhat, _, _ = oracle.decode(so, hc["norms"], lay, levels)
+        Xn_o = st.half1(Vhat, Vhat_prev)
+        sc = ctx.scalars()
+        assert abs(sc["S"] - st.S) <= REL * max(st.S, 1e-30) and abs(sc["gamma"] - st.gamma) <= REL * st.gamma
+        worst = max(worst, rel_err(Xn.cpu().numpy(), Xn_o))
+        X, Vhat_prev = Xn.cpu().numpy(), Vhat
+    assert ctx.poll_error() == 0
+    assert worst <= REL and st.gamma < K
+    ctx.close()
+
+
 def test_dual_averaging_case_prev_null(qgx):
     d, K = 5000, 2
     levels = synth.levels_uniform(8)
