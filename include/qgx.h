@@ -80,7 +80,10 @@ typedef enum {
 #define QGX_EBIT_NONFINITE 4u
 #define QGX_EBIT_STATE 8u
 
-typedef enum { QGX_NORM_LINF = 0, QGX_NORM_L2 = 2 } qgx_norm;           /* q of ||v||_q, Section 3.2 */
+/* q of ||v||_q (Definition 1: q in Z_+): 0 stands for the q -> infinity limit, 2 has a route of its
+ * own, any other q in 1..QGX_MAX_NORM_Q is (sum |v_i|^q)^(1/q) accumulated in binary64. */
+typedef enum { QGX_NORM_LINF = 0, QGX_NORM_L2 = 2 } qgx_norm;
+#define QGX_MAX_NORM_Q 64
 typedef enum { QGX_CODE_ELIAS_OMEGA = 0, QGX_CODE_TABLE = 1 } qgx_code; /* Psi, Appendix J */
 
 typedef struct {
@@ -89,7 +92,7 @@ typedef struct {
     uint32_t bucket;              /* coordinates per bucket, multiple of 4, <= QGX_MAX_BUCKET */
     uint32_t n_segments;          /* 0 or 1 => one segment of length d */
     const uint64_t* segment_len;  /* HOST, n_segments lengths summing to d; all but the last multiples of 4 */
-    int32_t norm;                 /* qgx_norm */
+    int32_t norm;                 /* qgx_norm, or another q in 1..QGX_MAX_NORM_Q */
     int32_t code;                 /* qgx_code */
     uint64_t seed;                /* key of the counter-based generator */
 } qgx_config;

@@ -137,8 +137,8 @@ void orc_layout_fill(uint64_t d, uint32_t bucket, uint32_t n_seg, const uint64_t
 }
 
 /* ------------------------------------------------------------------------ */
-/* Norm of one bucket (Section 3.2: the tuple (||v||_q, s, u)); q = 2 or the  */
-/* q -> infinity limit.  Returns the binary32 value that is stored/sent      */
+/* Norm of one bucket (Section 3.2: the tuple (||v||_q, s, u)); norm_kind is   */
+/* q in Z_+ (Definition 1), or 0 for the q -> infinity limit.  Returns the binary32 value that is stored/sent      */
 /* (C_b = 32 bits).  *finite is 0 when the bucket holds a non-finite value   */
 /* or the norm does not fit binary32.                                        */
 /* ------------------------------------------------------------------------ */
@@ -153,6 +153,21 @@ float orc_bucket_norm(const float* v, uint64_t len, int norm_kind, int* finite)
             acc += (double)v[i] * (double)v[i];
         }
         n = (float)sqrt(acc);
+    } else if (norm_kind != ORC_NORM_LINF) {
+        /* any other q in Z_+: (sum |v_i|^q)^(1/q), taken relative to the largest magnitude so    */
+        /* that no power leaves the range of binary64 */
+        const double q = (double)norm_kind;
+        double m = 0.0, acc = 0.0;
+        for (uint64_t i = 0; i < len; ++i) {
+            if (!isfinite(v[i])) ok = 0;
+            if (fabs((double)v[i]) > m) m = fabs((double)v[i]);
+        }
+        if (ok && m > 0.0) {
+            for (uint64_t i = 0; i < len; ++i) acc += pow(fabs((double)v[i]) / m, q);
+            n = (float)(m * pow(acc, 1.0 / q));
+        } else {
+            n = (float)m;
+        }
     } else {
         n = 0.0f;
         for (uint64_t i = 0; i < len; ++i) {

@@ -71,6 +71,29 @@ __device__ __forceinline__ uint32_t bcast_lane(uint32_t x, int src)
     return (uint32_t)__shfl((int)x, src, kWave);
 }
 
+// t^q for a small positive integer q (the same q in every lane).
+__device__ __forceinline__ double pow_int(double t, uint32_t q)
+{
+    double r = 1.0;
+    for (; q; q >>= 1) {
+        if (q & 1u) r *= t;
+        t *= t;
+    }
+    return r;
+}
+
+// s^(1/q) for s >= 1 in binary64: a single-precision guess, then Newton steps on x^q = s (each one
+// squares the error, so three reach the last bits from a guess good to 1e-6).
+__device__ __forceinline__ double root_int(double s, uint32_t q)
+{
+    double x = (double)__builtin_amdgcn_exp2f(__builtin_amdgcn_logf((float)s) / (float)q);   // v_exp_f32, v_log_f32: base 2
+    for (int it = 0; it < 3; ++it) {
+        const double xq1 = pow_int(x, q - 1u);
+        x -= (xq1 * x - s) / ((double)q * xq1);
+    }
+    return x;
+}
+
 // LDS accesses by byte address.  A pointer derived from the dynamic LDS array carries the array's
 // base as a late-bound addend that the compiler adds again on every access; an address computed once
 // as an integer does not.

@@ -227,7 +227,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
     unsigned char* s_lev = s_all + kCellsPad * sizeof(float2);
     uint16_t (*s_sub)[kSubs] = reinterpret_cast<uint16_t (*)[kSubs]>(s_lev + 2 * a.lev_stride);
     double* s_red = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(s_sub) + nwaves * kSubs * 2);
-    uint32_t* s_words = reinterpret_cast<uint32_t*>(s_red + nwaves);
+    uint32_t* s_words = reinterpret_cast<uint32_t*>(s_red + 2 * nwaves);      // second set: the general-q sum
     uint32_t* s_misc = s_words + (nwaves + 3) / 4 * 4;
     uint32_t* stage = reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(s_misc) + 32 + (size_t)w * a.stage_bytes);
     LdsPlan L;
@@ -310,6 +310,24 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                 else tot = (s_red[i] > tot || s_red[i] != s_red[i]) ? s_red[i] : tot;
             }
             n = (a.norm_kind == QGX_NORM_L2) ? (float)sqrt(tot) : (float)tot;
+            if (a.norm_kind != QGX_NORM_L2 && a.norm_kind != QGX_NORM_LINF && tot > 0.0 && tot <= 3.402823466e+38) {
+                // any other q of Definition 1: (sum |v_i|^q)^(1/q), relative to the largest magnitude
+                // found above so that no power leaves the range of binary64
+                const double inv_m = 1.0 / tot;
+                const uint32_t q = (uint32_t)a.norm_kind;
+                double acc = 0.0;
+                // (a rolled loop over memory: indexing the register copy by a run-time row would
+                // push it out of registers for the common norms as well)
+#pragma unroll 1
+                for (uint32_t i = g.clo + (uint32_t)lane; i < g.cend; i += kWave)
+                    acc += pow_int(fabs((double)Vk[i]) * inv_m, q);
+                acc = wave_sum(acc);
+                if (lane == 0) s_red[nwaves + w] = acc;
+                __syncthreads();
+                double sum = 0.0;
+                for (int i = 0; i < nwaves; ++i) sum += s_red[nwaves + i];
+                n = (float)(tot * root_int(sum, q));
+            }
             if (a.norms_in) {
                 const float forced = a.norms_in[(size_t)k * lay.NB + b];
                 u_le_1 = forced >= n;                                        // else |v| / norm may exceed 1
@@ -446,7 +464,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
 static size_t encode_lds_bytes(int waves, const EncodeArgs& a, bool with_stage)
 {
     size_t n = kCellsPad * sizeof(float2) + 2 * (size_t)a.lev_stride + (size_t)waves * kSubs * 2 +
-               (size_t)waves * sizeof(double) + (size_t)(waves + 3) / 4 * 4 * sizeof(uint32_t) + 32;
+               2 * (size_t)waves * sizeof(double) + (size_t)(waves + 3) / 4 * 4 * sizeof(uint32_t) + 32;
     if (with_stage) n += (size_t)waves * a.stage_bytes;
     return n;
 }

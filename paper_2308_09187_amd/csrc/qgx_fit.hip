@@ -92,7 +92,23 @@ __global__ __launch_bounds__(1024) void k_histogram(Layout lay, const float* __r
             else tot = fmax(tot, s_red[i]);
             anybad |= s_bad[i];
         }
-        const float n = (norm_kind == QGX_NORM_L2) ? (float)sqrt(tot) : (float)tot;
+        float n = (norm_kind == QGX_NORM_L2) ? (float)sqrt(tot) : (float)tot;
+        if (norm_kind != QGX_NORM_L2 && norm_kind != QGX_NORM_LINF && anybad == 0 && tot > 0.0) {
+            // general q: (sum |v_i|^q)^(1/q) relative to the largest magnitude, as in the encoder
+            const double inv_m = 1.0 / tot;
+            double sum = 0.0;
+#pragma unroll 1
+            for (uint32_t i = clo + (uint32_t)lane; i < cend; i += kWave) {      // rolled, from memory
+                sum += pow_int(fabs((double)Vk[i]) * inv_m, (uint32_t)norm_kind);
+            }
+            sum = wave_sum(sum);
+            __syncthreads();                         // everyone has read the first set of partial results
+            if (lane == 0) s_red[w] = sum;
+            __syncthreads();
+            double all = 0.0;
+            for (int i = 0; i < nwaves; ++i) all += s_red[i];
+            n = (float)(tot * root_int(all, (uint32_t)norm_kind));
+        }
         const bool usable = (anybad == 0) && (n > 0.0f) && (n <= 3.402823466e+38f);
         if (anybad != 0 && tid == 0) raise_error(sc, QGX_EBIT_NONFINITE);
         if (usable) {

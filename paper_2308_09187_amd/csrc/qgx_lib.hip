@@ -116,7 +116,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     *out = nullptr;
     if (cfg->d == 0 || cfg->d >= (1ull << 31) || cfg->K == 0 || cfg->K > 65535u) return QGX_ERR_ARG;
     if (cfg->bucket == 0 || (cfg->bucket & 3u) || cfg->bucket > QGX_MAX_BUCKET) return QGX_ERR_ARG;
-    if (cfg->norm != QGX_NORM_L2 && cfg->norm != QGX_NORM_LINF) return QGX_ERR_ARG;
+    if (cfg->norm < 0 || cfg->norm > QGX_MAX_NORM_Q) return QGX_ERR_ARG;
     if (cfg->code != QGX_CODE_ELIAS_OMEGA && cfg->code != QGX_CODE_TABLE) return QGX_ERR_ARG;
     qgx_ctx* c = new (std::nothrow) qgx_ctx;
     if (!c) return QGX_ERR_ARG;

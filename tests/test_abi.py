@@ -54,7 +54,8 @@ def test_create_rejects_bad_configurations_on_the_host():
     assert create(bucket=0) == -1
     assert create(bucket=250) == -1            # not a multiple of 4
     assert create(bucket=1 << 17) == -1        # above the largest bucket
-    assert create(norm=3) == -1
+    assert create(norm=65) == -1               # q of the norm: 0 (maximum) or 1..64
+    assert create(norm=-1) == -1
     assert create(code=7) == -1
     seg = (C.c_uint64 * 2)(1000, 25)           # does not sum to d
     assert create(n_segments=2, segment_len=seg) == -1

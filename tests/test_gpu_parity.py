@@ -76,6 +76,8 @@ CASES = [
     (1024, 4, 1024, oracle.NORM_L2, "exp8", None),                   # workload 1 shape
     (10 * 1024 + 64 + 128 + 4, 2, 2048, oracle.NORM_LINF, "exp16", [5 * 1024, 64, 128, 5 * 1024, 4]),
     (70000, 1, 65536, oracle.NORM_L2, "fine", None),                 # largest bucket, 127 symbols
+    (3 * 4096 + 77, 2, 8192, 3, "uni16", None),                      # another q of Definition 1: ||v||_3
+    (6000, 2, 4096, 1, "exp16", None),                               # and ||v||_1
 ]
 
 
@@ -513,7 +515,8 @@ def test_fit_levels_many_levels_and_sweeps(qgx):
     ctx.close()
 
 
-@pytest.mark.parametrize("norm,bucket,n_bins", [(oracle.NORM_L2, 16384, 4096), (oracle.NORM_LINF, 4096, 1024)])
+@pytest.mark.parametrize("norm,bucket,n_bins", [(oracle.NORM_L2, 16384, 4096), (oracle.NORM_LINF, 4096, 1024),
+                                                (4, 8192, 2048)])
 def test_fit_levels_parity(qgx, norm, bucket, n_bins):
     d, K, n_sym = (1 << 17) + 300, 3, 33
     start = synth.levels_exponential(n_sym - 1)

@@ -211,3 +211,40 @@ def test_layout_chunks():
     assert lay.d == 9855936 and lay.NB == 1207
     short = np.diff(lay.bucket_start.astype(np.int64))
     assert sorted(short[short < 8192].tolist()) == [64, 128, 256, 512]
+
+
+def test_general_q_norm_against_the_library_norm():
+    """||v||_q of Definition 1 for q in Z_+ other than 2: numpy's vector norm in binary64 is the
+    reference; q = 2 agrees with the dedicated route, a large q approaches the maximum, tiny and huge
+    magnitudes neither underflow nor overflow, and u = |v| / ||v||_q stays in [0, 1]."""
+    rng = np.random.default_rng(12)
+    v = (rng.standard_t(3, 3000) * 1e-2).astype(np.float32)
+    for q in (1, 3, 4, 7, 16):
+        n, fin = oracle.bucket_norm(v, q)
+        assert fin
+        want = np.linalg.norm(v.astype(np.float64), ord=q)
+        assert abs(float(n) - want) <= 1e-7 * want
+        assert (np.abs(v) / n <= 1.0).all()
+    n2, _ = oracle.bucket_norm(v, 2)
+    assert abs(float(n2) - np.linalg.norm(v.astype(np.float64))) <= 1e-7 * float(n2)
+    n64, _ = oracle.bucket_norm(v, 64)
+    ninf, _ = oracle.bucket_norm(v, oracle.NORM_LINF)
+    assert ninf <= n64 <= ninf * 3000 ** (1 / 64)
+    for scale in (1e-30, 1e30):
+        w = (v.astype(np.float64) * scale).astype(np.float32)
+        n, fin = oracle.bucket_norm(w, 8)
+        want = np.linalg.norm(w.astype(np.float64) / scale, ord=8) * scale
+        assert fin and abs(float(n) - want) <= 1e-6 * want
+    assert oracle.bucket_norm(np.zeros(10, np.float32), 3) == (0.0, True)
+    assert not oracle.bucket_norm(np.array([1, np.inf], np.float32), 3)[1]
+    # Q_l with q = 3: symbols follow u = |v| / ||v||_3
+    lay = oracle.layout(3000, 1024)
+    lv = synth.levels_uniform(8)
+    norms, idx, neg, bad = oracle.quantize(v[None, :], lay, 3, lv, 1, 0)
+    assert bad == 0
+    for b in range(lay.NB):
+        lo, hi = int(lay.bucket_start[b]), int(lay.bucket_start[b + 1])
+        assert norms[0, b] == oracle.bucket_norm(v[lo:hi], 3)[0]
+        u = np.abs(v[lo:hi]) * (np.float32(1) / norms[0, b])
+        j = np.minimum(np.floor(np.minimum(u, 1) * 8).astype(int), 7)
+        assert ((idx[0, lo:hi] == j) | (idx[0, lo:hi] == j + 1)).all()
