@@ -210,6 +210,15 @@ qgx_status qgx_state_export(qgx_ctx* ctx, float* Y, float* anchor, void* stream)
 qgx_status qgx_state_import(qgx_ctx* ctx, const float* Y, const float* anchor, double S, uint64_t t,
                             void* stream);
 
+/* Ergodic average of the half-step iterates, X_bar = (1/T) sum_t X_{t+1/2} (the point the
+ * convergence theorems bound; Section 2, Theorems 3 and 4).  qgx_average_reset(on = 1) clears a
+ * binary64 running sum in the context (allocated at the first such call; this is the one call
+ * besides qgx_create that allocates) and makes every later qgx_eg_step(half = 0) add its output to
+ * it, at 16 more bytes of traffic per coordinate; on = 0 switches that off.
+ * qgx_average_export: X_bar DEVICE [d] (or NULL) = sum / count, count = half-steps since the reset. */
+qgx_status qgx_average_reset(qgx_ctx* ctx, int on, void* stream);
+qgx_status qgx_average_export(qgx_ctx* ctx, float* X_bar, uint64_t* count, void* stream);
+
 /* Returns and clears the device error word (QGX_EBIT_*).  Synchronises `stream`. */
 uint32_t qgx_poll_error(qgx_ctx* ctx, void* stream);
 

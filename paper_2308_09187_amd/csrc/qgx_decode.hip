@@ -341,6 +341,12 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
                     x.z = (x.z + gam * y.z) - gam * m.z;
                     x.w = (x.w + gam * y.w) - gam * m.w;
                     *reinterpret_cast<float4*>(a.out + at) = x;
+                    if (a.x_sum) {                                   // ergodic average: sum of the half-step iterates
+                        double2* xs = reinterpret_cast<double2*>(a.x_sum + at);
+                        double2 s0 = xs[0], s1 = xs[1];
+                        s0.x += (double)x.x; s0.y += (double)x.y; s1.x += (double)x.z; s1.y += (double)x.w;
+                        xs[0] = s0; xs[1] = s1;
+                    }
                 } else {
                     float4 y = *reinterpret_cast<const float4*>(a.Y + at);
                     y.x -= m.x; y.y -= m.y; y.z -= m.z; y.w -= m.w;
@@ -357,7 +363,9 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
                 if (MODE == DecMode::Average) a.out[i0 + s] = m;
                 else if (MODE == DecMode::Half0) {
                     const float x = a.anchor ? a.anchor[i0 + s] : 0.0f;
-                    a.out[i0 + s] = (x + gam * a.Y[i0 + s]) - gam * m;
+                    const float xh = (x + gam * a.Y[i0 + s]) - gam * m;
+                    a.out[i0 + s] = xh;
+                    if (a.x_sum) a.x_sum[i0 + s] += (double)xh;
                 } else a.Y[i0 + s] -= m;
             }
         }
@@ -462,6 +470,20 @@ hipError_t launch_state_init(const Layout& lay, Scalars* sc, float* Y, float* an
 {
     const uint32_t grid = min((lay.d + 255u) / 256u, 4096u);
     hipLaunchKernelGGL(k_state_init, dim3(grid), dim3(256), 0, st, lay.d, lay.K, sc, Y, anchor, X1);
+    return hipGetLastError();
+}
+
+// Ergodic average of the half-step iterates: out = x_sum / count.
+__global__ __launch_bounds__(256) void k_average(uint32_t d, const double* __restrict__ x_sum, double count,
+                                                 float* __restrict__ out)
+{
+    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < d; i += gridDim.x * 256u) out[i] = (float)(x_sum[i] / count);
+}
+
+hipError_t launch_average(uint32_t d, const double* x_sum, double count, float* out, hipStream_t st)
+{
+    const uint32_t grid = min((d + 255u) / 256u, 4096u);
+    hipLaunchKernelGGL(k_average, dim3(grid), dim3(256), 0, st, d, x_sum, count, out);
     return hipGetLastError();
 }
 

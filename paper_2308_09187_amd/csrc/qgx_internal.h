@@ -126,6 +126,7 @@ struct DecodeArgs {
     float* Y;                   // [d] dual state (Half0 reads, Half1 updates)
     const float* anchor;        // [d] or null
     double* s_partial;          // [NC] per-chunk partial of S (Half1)
+    double* x_sum;              // [d] running sum of the X_{t+1/2} or null (Half0 adds its output)
     uint32_t stage_words;       // most words a chunk can take with the code in use (multiple of 4)
     uint32_t stage_stride;      // words of one LDS staging buffer (padded layout plus slack)
 };
@@ -140,6 +141,7 @@ hipError_t launch_finish_half1(const Layout& lay, Scalars* sc, const double* s_p
                                const float* anchor, float* X_out, hipStream_t st);
 hipError_t launch_state_init(const Layout& lay, Scalars* sc, float* Y, float* anchor, const float* X1,
                              hipStream_t st);
+hipError_t launch_average(uint32_t d, const double* x_sum, double count, float* out, hipStream_t st);
 hipError_t launch_state_set(Scalars* sc, double S, unsigned long long t, uint32_t K, hipStream_t st);
 hipError_t launch_sum_bits(const Layout& lay, const uint16_t* sub_end, Scalars* sc, hipStream_t st);
 hipError_t launch_histogram(const Layout& lay, const float* V, int norm_kind, uint32_t n_bins, double* partial,

@@ -27,6 +27,9 @@ struct qgx_ctx {
     double* d_hpartial = nullptr;
     double* d_hist = nullptr;
     double* d_prob = nullptr;       // [kSymMax] symbol probabilities of the last qgx_fit_code
+    double* d_xsum = nullptr;       // [d] sum of the X_{t+1/2} since qgx_average_reset (allocated there)
+    uint64_t xsum_count = 0;
+    bool xsum_on = false;
     uint32_t hist_bins = 0;         // bins of the histogram d_hist holds (0: none yet)
     uint32_t h_groups = 0;
     uint32_t epoch = 0;
@@ -102,7 +105,7 @@ qgx_status need_levels(qgx_ctx* ctx)
 
 void free_all(qgx_ctx* c)
 {
-    void* all[] = {c->d_layout, c->d_tab, c->d_sc, c->d_Y, c->d_anchor, c->d_scan, c->d_tickets, c->d_spartial, c->d_hpartial, c->d_hist, c->d_prob};
+    void* all[] = {c->d_layout, c->d_tab, c->d_sc, c->d_Y, c->d_anchor, c->d_scan, c->d_tickets, c->d_spartial, c->d_hpartial, c->d_hist, c->d_prob, c->d_xsum};
     for (void* p : all) (void)hipFree(p);
 }
 
@@ -509,13 +512,39 @@ qgx_status qgx_eg_step(qgx_ctx* ctx, int half, const qgx_stream* cur, const qgx_
         if (!X_out) return fail(ctx, QGX_ERR_ARG, "qgx_eg_step: X_out is required for half = 0");
         fill_decode_args(ctx, a, cur, nullptr);
         a.out = X_out;
+        a.x_sum = ctx->xsum_on ? ctx->d_xsum : nullptr;
         QGX_HIP(ctx, launch_decode(DecMode::Half0, ctx->lay, ctx->d_tab, ctx->d_sc, a, st));
+        if (ctx->xsum_on) ctx->xsum_count += 1;
         return QGX_OK;
     }
     fill_decode_args(ctx, a, cur, prev);
     a.s_partial = ctx->d_spartial;
     QGX_HIP(ctx, launch_decode(DecMode::Half1, ctx->lay, ctx->d_tab, ctx->d_sc, a, st));
     QGX_HIP(ctx, launch_finish_half1(ctx->lay, ctx->d_sc, ctx->d_spartial, ctx->d_Y, a.anchor, X_out, st));
+    return QGX_OK;
+}
+
+qgx_status qgx_average_reset(qgx_ctx* ctx, int on, void* stream)
+{
+    if (!ctx) return QGX_ERR_ARG;
+    ctx->xsum_on = on != 0;
+    ctx->xsum_count = 0;
+    if (!ctx->xsum_on) return QGX_OK;
+    if (!ctx->d_xsum && hipMalloc(&ctx->d_xsum, ctx->cfg.d * sizeof(double)) != hipSuccess)
+        return fail(ctx, QGX_ERR_HIP, "qgx_average_reset: no memory for the running sum");
+    QGX_HIP(ctx, hipMemsetAsync(ctx->d_xsum, 0, ctx->cfg.d * sizeof(double), (hipStream_t)stream));
+    return QGX_OK;
+}
+
+qgx_status qgx_average_export(qgx_ctx* ctx, float* X_bar, uint64_t* count, void* stream)
+{
+    if (!ctx || !aligned16(X_bar)) return fail(ctx, QGX_ERR_ARG, "qgx_average_export: null context or misaligned X_bar");
+    if (!ctx->xsum_on) return fail(ctx, QGX_ERR_STATE, "qgx_average_export: averaging is off (qgx_average_reset)");
+    if (count) *count = ctx->xsum_count;
+    if (X_bar) {
+        if (ctx->xsum_count == 0) return fail(ctx, QGX_ERR_STATE, "qgx_average_export: no half-step since the reset");
+        QGX_HIP(ctx, launch_average(ctx->lay.d, ctx->d_xsum, (double)ctx->xsum_count, X_bar, (hipStream_t)stream));
+    }
     return QGX_OK;
 }
 

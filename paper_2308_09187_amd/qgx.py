@@ -26,7 +26,7 @@ CHUNK, SUB, MAX_SYM, MAX_BINS = 4096, 64, 127, 4096
 EXPORTS = [
     "qgx_create", "qgx_destroy", "qgx_stream_sizes", "qgx_slot_words", "qgx_compact", "qgx_set_levels", "qgx_get_levels", "qgx_set_code_table",
     "qgx_quantize", "qgx_encode", "qgx_quantize_encode", "qgx_decode", "qgx_decode_average", "qgx_fit_levels", "qgx_fit_code",
-    "qgx_state_init", "qgx_eg_step", "qgx_get_scalars", "qgx_state_export", "qgx_state_import",
+    "qgx_state_init", "qgx_eg_step", "qgx_average_reset", "qgx_average_export", "qgx_get_scalars", "qgx_state_export", "qgx_state_import",
     "qgx_poll_error", "qgx_last_error",
 ]
 
@@ -226,6 +226,17 @@ class Context:
         self._check(self.lib.qgx_eg_step(self._h, C.c_int(half), C.byref(c), C.byref(p) if p is not None else None,
                                          _ptr(X_out), _stream_handle(stream)))
         return X_out
+
+    def average_reset(self, on=True, stream=None):
+        self._check(self.lib.qgx_average_reset(self._h, C.c_int(1 if on else 0), _stream_handle(stream)))
+
+    def average_export(self, out=None, stream=None):
+        """(X_bar [d], number of half-steps averaged)."""
+        if out is None:
+            out = torch.empty(self.d, dtype=torch.float32, device=self.device)
+        n = C.c_uint64()
+        self._check(self.lib.qgx_average_export(self._h, _ptr(out), C.byref(n), _stream_handle(stream)))
+        return out, n.value
 
     def scalars(self, want_bits=False, stream=None):
         S, g, t, b = C.c_double(), C.c_double(), C.c_uint64(), C.c_uint64()

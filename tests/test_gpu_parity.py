@@ -362,6 +362,8 @@ def run_lockstep(qgx, game, levels, norm, bucket, T, seed, anchor, refit=None, n
     ctx, lay = make_ctx(qgx, d, K, bucket, norm, levels, seed)
     x1 = game.x1() if anchor else None
     ctx.state_init(dev(x1) if anchor else None)
+    ctx.average_reset(True)                          # ergodic average of the half-step iterates alongside
+    xbar_o = np.zeros(d, np.float64)
     st = oracle.EGState(d, K, X1=x1)
     cur, prev = ctx.new_stream(slotted=True), ctx.new_stream(slotted=True)
     tmp = ctx.new_stream()
@@ -380,6 +382,7 @@ def run_lockstep(qgx, game, levels, norm, bucket, T, seed, anchor, refit=None, n
         assert_stream_equal(hp, so, lay)
         Vhat0, _, _ = oracle.decode(so, hp["norms"], lay, levels)
         Xh_o = st.half0(Vhat0)
+        xbar_o += Xh_o
         worst = max(worst, rel_err(Xh.cpu().numpy(), Xh_o))
         V1 = game.dual_vectors(Xh.cpu().numpy(), 2 * t + 1)
         ctx.quantize_encode(dev(V1), 2 * t + 1, cur)
@@ -397,6 +400,9 @@ def run_lockstep(qgx, game, levels, norm, bucket, T, seed, anchor, refit=None, n
         Y, _ = ctx.state_export()
         worst = max(worst, rel_err(Y.cpu().numpy(), st.Y))
         X = Xn.cpu().numpy()
+    xbar, n_avg = ctx.average_export()
+    assert n_avg == T
+    worst = max(worst, rel_err(xbar.cpu().numpy(), xbar_o / T))
     assert ctx.poll_error() == 0
     ctx.close()
     return worst, st
