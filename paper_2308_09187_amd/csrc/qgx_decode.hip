@@ -6,8 +6,8 @@
 // One wave per chunk position.  The wave copies a worker's chunk from the payload into LDS with
 // coalesced 16-byte loads (the next worker's chunk is already in flight in registers), then every
 // lane parses its own run of 64 coordinates, starting at the bit offset the sub-chunk table gives:
-// a 32-bit window from two LDS words, one 13-bit table lookup for (symbol, length), the sign bit,
-// one multiply by the bucket norm.  The K decoded values of a coordinate are summed in registers, so
+// a 64-bit window from three LDS words per three symbols, one 13-bit table lookup for (symbol,
+// length) each, the sign bit, one multiply by the bucket norm.  The K decoded values of a coordinate are summed in registers, so
 // decoded vectors never go to HBM in the fused modes.
 #include "qgx_device.h"
 
@@ -74,12 +74,12 @@ __device__ __forceinline__ void commit_chunk(uint32_t* stage, const uint4 (&pre)
 // LDS tables of the decoder in one array: level values first, then the decode table, so that the
 // level index of a reject entry (flag bit set) still lands inside the array.
 constexpr int kTabLvalBytes = kSymMax * 4;
-constexpr int kTabBytes = kTabLvalBytes + kDlutStore * 2;
+constexpr int kTabBytes = kTabLvalBytes + kDlut * 2;
 
 // Symbols are parsed in groups of up to three from one 64-bit window (three LDS words): a symbol
-// takes at most 14 bits, so the third one still starts inside the low word.  A table entry is
-// (length incl. sign) | 4 idx << 4 with bits 4 and 5 clear, so sums of entries carry the consumed
-// bits in their low six bits and an entry can be used as a shift count as it is.
+// takes at most 14 bits, so the third one still starts inside the first word.  A table entry is
+// (bits of the symbol incl. sign - 1) | 4 idx << 4 with bits 4 and 5 clear, so sums of entries carry
+// the consumed bits in their low six bits and an entry can be used as a shift count as it is.
 // The three steps are separate so that the caller can issue the next group's window reads before
 // it turns the current group's entries into values.
 struct Window { uint32_t w0, w1, w2; };
@@ -91,22 +91,24 @@ __device__ __forceinline__ Window read_window(const uint32_t* stage, uint32_t p)
 }
 
 // The dependent chain: window i needs the lengths of the symbols before it.  Advances the cursor.
+// The 64 bits are turned so that the first stream bit is on top: a window is then a funnel shift
+// away, its top 13 bits index the table, and a symbol's last bit (the sign) reaches bit 31 by a left
+// shift of (symbol bits - 1), which is what the entry's low bits hold.  `neg` counts the used bits
+// downwards (adding ~e takes off the entry's count plus one); only its low six bits mean anything.
 template <int N>
 __device__ __forceinline__ void parse_group(const Window& w, const unsigned char* tab, uint32_t& p,
                                             uint32_t (&win)[3], uint32_t (&e)[3])
 {
-    const uint32_t lo = __builtin_amdgcn_alignbit(w.w1, w.w0, p);             // shifts use p mod 32
-    const uint32_t hi = __builtin_amdgcn_alignbit(w.w2, w.w1, p);
-    uint32_t used = 0;
+    const uint32_t top = __brev(__builtin_amdgcn_alignbit(w.w1, w.w0, p));    // shifts use p mod 32
+    const uint32_t nxt = __brev(__builtin_amdgcn_alignbit(w.w2, w.w1, p));
+    uint32_t neg = 0;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-        win[i] = i == 0 ? lo : __builtin_amdgcn_alignbit(hi, lo, used);
-        const uint32_t t = win[i] & (uint32_t)(kDlut - 1);
-        const uint32_t h = (win[i] >> 6) & 0x7Fu;
-        e[i] = *reinterpret_cast<const uint16_t*>(tab + kTabLvalBytes + ((t + (h << 1)) << 1));
-        used += e[i];
+        win[i] = i == 0 ? top : __builtin_amdgcn_alignbit(top, nxt, neg);     // (top:nxt) << used, upper word
+        e[i] = *reinterpret_cast<const uint16_t*>(tab + kTabLvalBytes + ((win[i] >> 18) & 0x3FFEu));
+        neg += ~e[i];
     }
-    p += used & 63u;
+    p -= neg | 0xFFFFFFC0u;                                                   // minus (minus the bits used)
 }
 
 __device__ __forceinline__ float level_of(const unsigned char* tab, uint32_t e)
@@ -120,7 +122,7 @@ __device__ __forceinline__ float level_of(const unsigned char* tab, uint32_t e)
 template <bool EXACT_ZERO>
 __device__ __forceinline__ float symbol_value(float lv, uint32_t win, uint32_t e, float n)
 {
-    const uint32_t sg = __builtin_amdgcn_alignbit(win, win, e);                // last bit of the symbol -> bit 31
+    const uint32_t sg = win << (e & 31u);                                      // last bit of the symbol -> bit 31
     // norm and level are not negative: the sign goes in with one OR
     const float val = __uint_as_float((sg & 0x80000000u) | __float_as_uint(n * lv));
     if (EXACT_ZERO) return (e >> 4) == 0u ? 0.0f : val;
@@ -163,7 +165,7 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
     uint32_t* stage_p = stage + stage_stride;
 
     for (int i = tid; i < kSymMax; i += (int)blockDim.x) reinterpret_cast<float*>(s_tab)[i] = tab->lval[i];
-    for (int i = tid; i < kDlutStore / 2; i += (int)blockDim.x)
+    for (int i = tid; i < kDlut / 2; i += (int)blockDim.x)
         reinterpret_cast<uint32_t*>(s_tab + kTabLvalBytes)[i] = reinterpret_cast<const uint32_t*>(tab->dlut)[i];
     // words past a chunk's end are read by the window of its last symbols: keep them defined
     for (uint32_t q = (uint32_t)lane; q < kBufs * stage_stride; q += kWave) stage[q] = 0;

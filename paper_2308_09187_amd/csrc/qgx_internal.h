@@ -34,17 +34,10 @@ constexpr int kLevRegion = kSymMax * 16;                // bytes between the two
 constexpr int kDlutBits = kMaxCode;       // decode window
 constexpr int kDlut = 1 << kDlutBits;     // 8192 entries
 
-// Slot of a 13-bit window in the decode table.  The first bits of a window are the length prefix of
-// a code word and take few values, so consecutive 64-entry rows are skewed by two entries (one LDS
-// bank): the bank then follows window bits 6..12, which hold the digits of the symbol.
-constexpr int kDlutRow = 66;              // 64 entries + 2 of skew
-constexpr int kDlutStore = (kDlut / 64) * kDlutRow;   // 8448 entries
-__host__ __device__ inline uint32_t dlut_slot(uint32_t window)
-{
-    const uint32_t w = window & (uint32_t)(kDlut - 1);
-    return w + 2u * (w >> 6);
-}
-constexpr uint32_t kDlutReject = 0x8001u; // no code word starts this window: flag, one bit long, symbol 0
+// The decode table is indexed by the next 13 stream bits read as a number with the FIRST bit on top,
+// so the windows that start with one code word are neighbours: lanes that parse the same symbol read
+// the same or adjacent entries, whatever follows the word in their streams.
+constexpr uint32_t kDlutReject = 0x8000u; // no code word starts this window: flag, one bit long, symbol 0
 
 // Device-resident tables: rebuilt on the device whenever the level table or the code changes.
 struct Tables {
@@ -63,8 +56,9 @@ struct Tables {
     uint32_t code_kind;
     uint32_t cell_exact;
     uint32_t pad_;
-    // dlut[dlut_slot(next 13 stream bits)] = (length + 1 if idx != 0) | (4 * idx) << 4, or kDlutReject
-    uint16_t dlut[kDlutStore];
+    // dlut[next 13 stream bits, first bit on top] = (bits of the symbol incl. sign - 1) | (4 * idx) << 4,
+    // or kDlutReject
+    uint16_t dlut[kDlut];
 };
 
 // Scalars of the iteration; lives in device memory, read by kernels, copied out on request.

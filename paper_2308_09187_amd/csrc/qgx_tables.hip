@@ -44,7 +44,7 @@ static __device__ void build_tables_block(Tables* tab)
             tab->code[j] = bits | (len << 16);
         }
     }
-    for (int i = tid; i < kDlutStore; i += nt) tab->dlut[i] = (uint16_t)kDlutReject;
+    for (int i = tid; i < kDlut; i += nt) tab->dlut[i] = (uint16_t)kDlutReject;
     __syncthreads();
 
     for (int j = tid; j < kSymMax; j += nt) {
@@ -81,14 +81,16 @@ static __device__ void build_tables_block(Tables* tab)
         tab->cell[c] = make_float2(B, __uint_as_float((j << 4) | (a1 << 20)));
         if (crowded) tab->cell_exact = 0u;
     }
-    // every 13-bit window that starts with code word j decodes to j
+    // every 13-bit window that starts with code word j decodes to j: with the first stream bit on
+    // top these windows are one run of 2^(13 - len) entries
     for (uint32_t j = 0; j < n_sym; ++j) {
         const uint32_t cw = tab->code[j];
         const uint32_t len = cw >> 16, bits = cw & 0xFFFFu;
         if (len == 0 || len > (uint32_t)kMaxCode) continue;
+        const uint32_t first = (__brev(bits) >> (32u - len)) << (kDlutBits - len);   // the word, first bit on top
         const uint32_t reps = 1u << (kDlutBits - len);
-        for (uint32_t s = (uint32_t)tid; s < reps; s += (uint32_t)nt)
-            tab->dlut[dlut_slot(bits | (s << len))] = (uint16_t)((j << 6) | (len + (j != 0u ? 1u : 0u)));
+        const uint32_t entry = (j << 6) | (len - (j != 0u ? 0u : 1u));               // symbol bits - 1: sign for j != 0
+        for (uint32_t s = (uint32_t)tid; s < reps; s += (uint32_t)nt) tab->dlut[first + s] = (uint16_t)entry;
     }
     __syncthreads();
 }
