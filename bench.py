@@ -39,6 +39,10 @@ def parse_args():
     ap.add_argument("--full-iteration", action="store_true", help="also time encode + second half-step")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of the input (known size) to calibrate rocprofv3 HBM counters")
+    ap.add_argument("--workload", choices=["t3", "gan"], default="t3",
+                    help="t3: the headline batch of heavy-tailed vectors; gan: K vectors in a GAN-shaped layout of 14 "
+                         "tensors with per-tensor scale, buckets of 8192 per tensor, L-infinity norm, 16 exponential "
+                         "levels, full iteration (ignores --logd, --bucket, --n-sym)")
     ap.add_argument("--code", choices=["omega", "huffman"], default="omega",
                     help="Psi: Elias' recursive code of the level index (default) or the optimal prefix code "
                          "fitted to the estimated symbol probabilities")
@@ -93,15 +97,32 @@ def main():
         sys.exit(1)
     qgx.load()
     torch.cuda.set_device(0)
-    d, K, seed = 1 << args.logd, args.K, 2308
-    V = synth.student_t3_device(K, d, seed=20)
-    V1 = synth.student_t3_device(K, d, seed=21) if args.full_iteration else None
+    K, seed = args.K, 2308
     huffman = args.code == "huffman"
-    default_workload = (args.logd, args.K, args.bucket, args.n_sym, args.code, args.placement) == (24, 8, 16384, 33, "omega", "slotted")
-    ctx = qgx.Context(d, K, args.bucket, norm=qgx.NORM_L2, seed=seed,
-                      code=qgx.CODE_TABLE if huffman else qgx.CODE_ELIAS_OMEGA)
-    ctx.set_levels(synth.levels_exponential(args.n_sym - 1))
-    ctx.fit_levels(V, args.n_sym, 4096, sweeps=10)
+    code_kind = qgx.CODE_TABLE if huffman else qgx.CODE_ELIAS_OMEGA
+    if args.workload == "gan":
+        args.full_iteration = True
+        args.bucket, args.n_sym = 8192, 17
+        seg = [int(x) for x in synth.GAN_SEGMENTS]
+        d = sum(seg)
+        V = torch.from_numpy(synth.gan_dual_vectors(K, 0)).cuda()
+        V1 = torch.from_numpy(synth.gan_dual_vectors(K, 1)).cuda()
+        ctx = qgx.Context(d, K, args.bucket, norm=qgx.NORM_LINF, seed=seed, code=code_kind, segment_len=seg)
+        ctx.set_levels(synth.levels_exponential(16))
+        if huffman:
+            ctx.fit_levels(V, args.n_sym, 4096, sweeps=0)          # only measures: the table stays
+        what = "K=%d x d=%d in 14 tensors (GAN-shaped), N(0, sigma_t^2) with sigma_t log-uniform in [1e-5, 1e-2], " \
+               "buckets of 8192 per tensor, L-infinity, 16 exponential levels" % (K, d)
+    else:
+        d = 1 << args.logd
+        V = synth.student_t3_device(K, d, seed=20)
+        V1 = synth.student_t3_device(K, d, seed=21) if args.full_iteration else None
+        ctx = qgx.Context(d, K, args.bucket, norm=qgx.NORM_L2, seed=seed, code=code_kind)
+        ctx.set_levels(synth.levels_exponential(args.n_sym - 1))
+        ctx.fit_levels(V, args.n_sym, 4096, sweeps=10)
+        what = "K=%d x d=2^%d Student-t(3)*1e-2, bucket %d, L2, %d-symbol fitted table" % (K, args.logd, args.bucket, args.n_sym)
+    default_workload = (args.workload, args.logd, K, args.bucket, args.n_sym, args.code, args.placement) == \
+                       ("t3", 24, 8, 16384, 33, "omega", "slotted")
     levels = ctx.get_levels()
     code = ctx.fit_code()[1:] if huffman else (None, None)
     ctx.state_init(None)
@@ -158,10 +179,8 @@ def main():
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "K=%d x d=2^%d Student-t(3)*1e-2, bucket %d, L2, %d-symbol fitted table, %s; "
-                               "%s chunk placement; step = fused CODE.Q + fused decode/average/half-step%s"
-                               % (K, args.logd, args.bucket, args.n_sym,
-                                  "fitted optimal prefix code" if huffman else "Elias-omega", args.placement,
+        "config": {"workload": "%s, %s; %s chunk placement; step = fused CODE.Q + fused decode/average/half-step%s"
+                               % (what, "fitted optimal prefix code" if huffman else "Elias-omega", args.placement,
                                   " + CODE.Q + second half-step" if args.full_iteration else ""),
                    "K": K, "d": d, "bucket": args.bucket, "n_sym": args.n_sym,
                    "bits_per_coordinate": bits / float(K * d), "stream_bytes": stream_bytes},
@@ -177,7 +196,7 @@ def main():
         out["kernels_ms"]["encode_2"] = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
         out["kernels_ms"]["decode_avg_half1"] = float(np.mean([e[3].elapsed_time(e[4]) for e in events]))
     ctx.close()
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.workload == "t3":
         ds = min(d, 1 << args.cpu_sample_logd)
         args.cpu_sample_logd = ds.bit_length() - 1
         V_host = V[:, :ds].contiguous().cpu().numpy()

@@ -393,25 +393,39 @@ static hipError_t launch_one(const Layout& lay, const Tables* tab, Scalars* sc, 
     return hipGetLastError();
 }
 
-// Two launches cover the chunk positions: the full ones, then the ragged ones (if the layout has any).
+// Two launches cover the chunk positions: the full ones and, if the layout has any, the ragged ones.
+// The few ragged positions take about as long as the whole of the full ones (their parse is
+// predicated, and a wave still walks all K workers), so they go first and on the side queue, where
+// they run beside the full ones instead of after them.
 template <DecMode MODE, bool PREV>
-static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
+static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st,
+                              const SideQueue* side)
 {
-    hipError_t e = launch_one<MODE, true, PREV>(lay, tab, sc, a, st);
-    if (e != hipSuccess) return e;
-    return launch_one<MODE, false, PREV>(lay, tab, sc, a, st);
+    const bool both = lay.n_ragged != 0 && lay.n_ragged != lay.NC;
+    if (!both || side == nullptr) {
+        hipError_t e = launch_one<MODE, false, PREV>(lay, tab, sc, a, st);
+        if (e != hipSuccess) return e;
+        return launch_one<MODE, true, PREV>(lay, tab, sc, a, st);
+    }
+    hipError_t e = hipEventRecord(side->fork, st);
+    if (e == hipSuccess) e = hipStreamWaitEvent(side->stream, side->fork, 0);
+    if (e == hipSuccess) e = launch_one<MODE, false, PREV>(lay, tab, sc, a, side->stream);
+    if (e == hipSuccess) e = hipEventRecord(side->join, side->stream);
+    if (e == hipSuccess) e = launch_one<MODE, true, PREV>(lay, tab, sc, a, st);
+    if (e == hipSuccess) e = hipStreamWaitEvent(st, side->join, 0);
+    return e;
 }
 
 hipError_t launch_decode(DecMode mode, const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a,
-                         hipStream_t st)
+                         hipStream_t st, const SideQueue* side)
 {
     switch (mode) {
-        case DecMode::Decode: return launch_mode<DecMode::Decode, false>(lay, tab, sc, a, st);
-        case DecMode::Average: return launch_mode<DecMode::Average, false>(lay, tab, sc, a, st);
-        case DecMode::Half0: return launch_mode<DecMode::Half0, false>(lay, tab, sc, a, st);
+        case DecMode::Decode: return launch_mode<DecMode::Decode, false>(lay, tab, sc, a, st, side);
+        case DecMode::Average: return launch_mode<DecMode::Average, false>(lay, tab, sc, a, st, side);
+        case DecMode::Half0: return launch_mode<DecMode::Half0, false>(lay, tab, sc, a, st, side);
         default:
-            return a.payload_p ? launch_mode<DecMode::Half1, true>(lay, tab, sc, a, st)
-                               : launch_mode<DecMode::Half1, false>(lay, tab, sc, a, st);
+            return a.payload_p ? launch_mode<DecMode::Half1, true>(lay, tab, sc, a, st, side)
+                               : launch_mode<DecMode::Half1, false>(lay, tab, sc, a, st, side);
     }
 }
 

@@ -129,8 +129,14 @@ hipError_t launch_build_tables(Tables* tab, hipStream_t st);
 // tickets_per_worker: how far the launch advances every worker's ticket counter
 hipError_t launch_encode(EncMode mode, const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a,
                          hipStream_t st, uint32_t* tickets_per_worker);
+// A second queue for work that should overlap the caller's stream (fork: the side waits for what the
+// caller's stream holds so far; join: the caller's stream waits for the side).
+struct SideQueue {
+    hipStream_t stream;
+    hipEvent_t fork, join;
+};
 hipError_t launch_decode(DecMode mode, const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a,
-                         hipStream_t st);
+                         hipStream_t st, const SideQueue* side);
 hipError_t launch_finish_half1(const Layout& lay, Scalars* sc, const double* s_partial, const float* Y,
                                const float* anchor, float* X_out, hipStream_t st);
 hipError_t launch_state_init(const Layout& lay, Scalars* sc, float* Y, float* anchor, const float* X1,

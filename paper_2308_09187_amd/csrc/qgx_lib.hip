@@ -27,6 +27,8 @@ struct qgx_ctx {
     double* d_hpartial = nullptr;
     double* d_hist = nullptr;
     double* d_prob = nullptr;       // [kSymMax] symbol probabilities of the last qgx_fit_code
+    SideQueue side{};               // for the ragged chunk positions of the decoding kernels
+    bool side_ok = false;
     double* d_xsum = nullptr;       // [d] sum of the X_{t+1/2} since qgx_average_reset (allocated there)
     uint64_t xsum_count = 0;
     bool xsum_on = false;
@@ -107,6 +109,12 @@ void free_all(qgx_ctx* c)
 {
     void* all[] = {c->d_layout, c->d_tab, c->d_sc, c->d_Y, c->d_anchor, c->d_scan, c->d_tickets, c->d_spartial, c->d_hpartial, c->d_hist, c->d_prob, c->d_xsum};
     for (void* p : all) (void)hipFree(p);
+    if (c->side_ok) {
+        (void)hipEventDestroy(c->side.fork);
+        (void)hipEventDestroy(c->side.join);
+        (void)hipStreamDestroy(c->side.stream);
+        c->side_ok = false;
+    }
 }
 
 }  // namespace
@@ -205,6 +213,12 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     if (ok) {
         const uint32_t kind = (uint32_t)cfg->code;
         ok = hipMemcpy(&c->d_tab->code_kind, &kind, sizeof(kind), hipMemcpyHostToDevice) == hipSuccess;
+    }
+    if (ok && c->lay.n_ragged != 0 && c->lay.n_ragged != NC) {      // default priority, as every stream here
+        ok = hipStreamCreateWithFlags(&c->side.stream, hipStreamNonBlocking) == hipSuccess;
+        ok = ok && hipEventCreateWithFlags(&c->side.fork, hipEventDisableTiming) == hipSuccess;
+        ok = ok && hipEventCreateWithFlags(&c->side.join, hipEventDisableTiming) == hipSuccess;
+        c->side_ok = ok;
     }
     ok = ok && hipDeviceSynchronize() == hipSuccess;
     if (!ok) { free_all(c); delete c; return QGX_ERR_HIP; }
@@ -423,7 +437,7 @@ qgx_status qgx_decode(qgx_ctx* ctx, const qgx_stream* in, float* Vhat, void* str
     DecodeArgs a{};
     fill_decode_args(ctx, a, in, nullptr);
     a.out = Vhat;
-    QGX_HIP(ctx, launch_decode(DecMode::Decode, ctx->lay, ctx->d_tab, ctx->d_sc, a, (hipStream_t)stream));
+    QGX_HIP(ctx, launch_decode(DecMode::Decode, ctx->lay, ctx->d_tab, ctx->d_sc, a, (hipStream_t)stream, ctx->side_ok ? &ctx->side : nullptr));
     return QGX_OK;
 }
 
@@ -436,7 +450,8 @@ qgx_status qgx_decode_average(qgx_ctx* ctx, const qgx_stream* in, float* mean, v
     DecodeArgs a{};
     fill_decode_args(ctx, a, in, nullptr);
     a.out = mean;
-    QGX_HIP(ctx, launch_decode(DecMode::Average, ctx->lay, ctx->d_tab, ctx->d_sc, a, (hipStream_t)stream));
+    QGX_HIP(ctx, launch_decode(DecMode::Average, ctx->lay, ctx->d_tab, ctx->d_sc, a, (hipStream_t)stream,
+                               ctx->side_ok ? &ctx->side : nullptr));
     return QGX_OK;
 }
 
@@ -513,13 +528,13 @@ qgx_status qgx_eg_step(qgx_ctx* ctx, int half, const qgx_stream* cur, const qgx_
         fill_decode_args(ctx, a, cur, nullptr);
         a.out = X_out;
         a.x_sum = ctx->xsum_on ? ctx->d_xsum : nullptr;
-        QGX_HIP(ctx, launch_decode(DecMode::Half0, ctx->lay, ctx->d_tab, ctx->d_sc, a, st));
+        QGX_HIP(ctx, launch_decode(DecMode::Half0, ctx->lay, ctx->d_tab, ctx->d_sc, a, st, ctx->side_ok ? &ctx->side : nullptr));
         if (ctx->xsum_on) ctx->xsum_count += 1;
         return QGX_OK;
     }
     fill_decode_args(ctx, a, cur, prev);
     a.s_partial = ctx->d_spartial;
-    QGX_HIP(ctx, launch_decode(DecMode::Half1, ctx->lay, ctx->d_tab, ctx->d_sc, a, st));
+    QGX_HIP(ctx, launch_decode(DecMode::Half1, ctx->lay, ctx->d_tab, ctx->d_sc, a, st, ctx->side_ok ? &ctx->side : nullptr));
     QGX_HIP(ctx, launch_finish_half1(ctx->lay, ctx->d_sc, ctx->d_spartial, ctx->d_Y, a.anchor, X_out, st));
     return QGX_OK;
 }
