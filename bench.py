@@ -51,14 +51,19 @@ def parse_args():
     return ap.parse_args()
 
 
-def measured_traffic():
-    """HBM bytes per encoder launch from the committed rocprofv3 counter summary, if there is one."""
+def _profile_number(key):
+    """A figure from the committed rocprofv3 counter summary of the encoder, if there is one."""
     path = os.path.join(ROOT, "profiles", "encode_t3_K8_d2p24_pmc.txt")
     try:
-        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        m = re.search(r"^%s:\s*([0-9.eE+]+)" % key, open(path).read(), re.M)
         return float(m.group(1)) if m else None
     except OSError:
         return None
+
+
+def measured_traffic():
+    """HBM bytes per encoder launch (FETCH_SIZE + WRITE_SIZE, calibrated against a plain copy)."""
+    return _profile_number("traffic_bytes_per_launch")
 
 
 def cpu_baseline(args, levels, seed, V, code=(None, None)):
@@ -190,7 +195,9 @@ def main():
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      # the committed counter run covers the default workload only
                      "traffic": measured_traffic() if default_workload else None,
-                     "algorithmic_bytes": enc_bytes},
+                     "algorithmic_bytes": enc_bytes,
+                     # the kernel is bound by the vector ALUs before HBM: time they were busy in the counter run
+                     "valu_busy_us": _profile_number("valu_busy_us") if default_workload else None},
     }
     if args.full_iteration:
         out["kernels_ms"]["encode_2"] = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
