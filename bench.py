@@ -157,6 +157,20 @@ def main():
         probe = V.clone()          # plain copy kernel: reads and writes 4*K*d bytes
         torch.cuda.synchronize()
         del probe
+
+    def copy_bandwidth():
+        """What a plain device-to-device copy of the input reaches on this machine (read + written bytes per
+        second): the practical ceiling next to the published HBM peak."""
+        dst = torch.empty_like(V)
+        for _ in range(30):
+            dst.copy_(V)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            dst.copy_(V)
+        e1.record()
+        torch.cuda.synchronize()
+        return 2.0 * V.numel() * 4 * 20 / (e0.elapsed_time(e1) * 1e-3) / 1e9
     t_pre = time.perf_counter()
     while (time.perf_counter() - t_pre) * 1e3 < args.preroll_ms:
         for i in range(8):
@@ -176,6 +190,7 @@ def main():
     wall = time.perf_counter() - t0
     assert ctx.poll_error() == 0
 
+    copy_gbs = copy_bandwidth()
     ms_step = wall * 1e3 / args.steps
     enc_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
     upd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
@@ -207,6 +222,8 @@ def main():
                      # the committed counter run covers the default workload only
                      "traffic": measured_traffic() if default_workload else None,
                      "algorithmic_bytes": enc_bytes,
+                     # a plain copy of the same input on this machine, and the encoder's rate relative to it
+                     "copy_gbs": copy_gbs, "frac_of_copy": achieved / copy_gbs,
                      # the kernel is bound by the vector ALUs before HBM: time they were busy in the counter run
                      "valu_busy_us": _profile_number("valu_busy_us") if default_workload else None},
     }

@@ -276,19 +276,22 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
         float n = 0.0f;
         bool u_le_1 = true;
         if (MODE != EncMode::EncodeOnly) {
-            // A non-finite coordinate shows in the reduced value itself: the binary64 sum of squares
-            // cannot overflow from finite binary32 inputs, and the maximum is taken on magnitude bits.
+            // A non-finite coordinate shows in the reduced value itself (a sum of squares with a NaN
+            // or an infinity in it, a maximum taken on magnitude bits).
             double red;
             if (a.norm_kind == QGX_NORM_L2) {
-                double acc0 = 0.0, acc1 = 0.0;
+                // four binary32 runs of 16 fused multiply-adds per lane (error of a run at most
+                // 15 roundings, 1e-6 relative, half of that on the norm), everything after in
+                // binary64; sums outside the range where binary32 squares are safe are redone below
+                float p0 = 0.0f, p1 = 0.0f, p2 = 0.0f, p3 = 0.0f;
 #pragma unroll
                 for (int r = 0; r < kRows; ++r) {
-                    acc0 = fma((double)v[r].x, (double)v[r].x, acc0);
-                    acc1 = fma((double)v[r].y, (double)v[r].y, acc1);
-                    acc0 = fma((double)v[r].z, (double)v[r].z, acc0);
-                    acc1 = fma((double)v[r].w, (double)v[r].w, acc1);
+                    p0 = fmaf(v[r].x, v[r].x, p0);
+                    p1 = fmaf(v[r].y, v[r].y, p1);
+                    p2 = fmaf(v[r].z, v[r].z, p2);
+                    p3 = fmaf(v[r].w, v[r].w, p3);
                 }
-                red = wave_sum(acc0 + acc1);
+                red = wave_sum(((double)p0 + (double)p1) + ((double)p2 + (double)p3));
             } else {
                 uint32_t mx = 0;
 #pragma unroll
@@ -308,6 +311,18 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
             for (int i = 0; i < nwaves; ++i) {
                 if (a.norm_kind == QGX_NORM_L2) tot += s_red[i];
                 else tot = (s_red[i] > tot || s_red[i] != s_red[i]) ? s_red[i] : tot;
+            }
+            if (a.norm_kind == QGX_NORM_L2 && !(tot >= 0x1p-60 && tot <= 0x1p100)) {
+                // squares that overflow or go subnormal in binary32 (or a non-finite input): the sum
+                // again in binary64, from memory (the rolled loop keeps the register copy intact)
+                double acc = 0.0;
+#pragma unroll 1
+                for (uint32_t i = g.clo + (uint32_t)lane; i < g.cend; i += kWave) acc = fma((double)Vk[i], (double)Vk[i], acc);
+                acc = wave_sum(acc);
+                if (lane == 0) s_red[nwaves + w] = acc;
+                __syncthreads();
+                tot = 0.0;
+                for (int i = 0; i < nwaves; ++i) tot += s_red[nwaves + i];
             }
             n = (a.norm_kind == QGX_NORM_L2) ? (float)sqrt(tot) : (float)tot;
             if (a.norm_kind != QGX_NORM_L2 && a.norm_kind != QGX_NORM_LINF && tot > 0.0 && tot <= 3.402823466e+38) {
