@@ -194,10 +194,10 @@ def main():
     ms_step = wall * 1e3 / args.steps
     enc_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
     upd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
-    h_bits = a.sub_end.cpu().numpy().view(np.uint16)[:, :, 63].astype(np.int64)
+    h_bits = a.sub_end.cpu().numpy().view(np.uint16)[:, :, -1].astype(np.int64)
     words = int((((h_bits + 31) // 32 + 3) // 4 * 4).sum())
     bits = ctx.scalars(want_bits=True)["total_bits"]
-    side_bytes = K * ((ctx.NC + 1) * 4 + ctx.NC * 128 + ctx.NB * 4)
+    side_bytes = K * ((ctx.NC + 1) * 4 + ctx.NC * qgx.SUBS * 2 + ctx.NB * 4)
     stream_bytes = words * 4 + side_bytes
     enc_bytes = 4 * K * d + stream_bytes                 # read V once, write the coded streams
     upd_bytes = stream_bytes + 4 * d + 4 * d             # read streams and Y, write X_{t+1/2}

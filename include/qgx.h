@@ -31,7 +31,7 @@
  *   a multiple of 4 words; pad bits are 0.
  *     norms     [K][NB]       binary32 norm of every bucket (C_b = 32 bits), 0 for a rejected bucket
  *     chunk_off [K][NC+1]     word offset of chunk c inside worker k's payload; entry NC = words used
- *     sub_end   [K][NC][64]   bit offset, from the chunk start, one past the last bit of the j-th run
+ *     sub_end   [K][NC][128]  bit offset, from the chunk start, one past the last bit of the j-th run
  *                             of QGX_SUB coordinates (entries past the chunk's last run repeat the
  *                             chunk's bit length); makes the decode parallel
  *     payload   [K][payload_words_per_worker]
@@ -43,7 +43,7 @@
  *     slotted (slot_words > 0): chunk c starts at c * slot_words, slot_words = what qgx_slot_words
  *       reports; no workgroup waits for another, so coding is faster; the bits of every chunk are the
  *       same as in the compact form, and qgx_compact turns one into the other.
- *   A chunk's size in words is always ceil(sub_end[k][c][63] / 32) rounded up to a multiple of 4.
+ *   A chunk's size in words is always ceil(sub_end[k][c][127] / 32) rounded up to a multiple of 4.
  */
 #ifndef QGX_H
 #define QGX_H
@@ -55,7 +55,8 @@ extern "C" {
 #endif
 
 #define QGX_CHUNK 4096u      /* coordinates per chunk */
-#define QGX_SUB 64u          /* coordinates per sub-chunk table entry */
+#define QGX_SUB 32u          /* coordinates per sub-chunk table entry */
+#define QGX_SUBS 128u        /* sub-chunk table entries per chunk */
 #define QGX_MAX_BUCKET 65536u
 #define QGX_MAX_SYM 127u     /* largest level table (l_0 .. l_{s+1}) */
 #define QGX_MAX_BINS 4096u
@@ -101,7 +102,7 @@ typedef struct {
 typedef struct {
     float* norms;                       /* [K][NB] */
     uint32_t* chunk_off;                /* [K][NC+1] */
-    uint16_t* sub_end;                  /* [K][NC][64] */
+    uint16_t* sub_end;                  /* [K][NC][QGX_SUBS] */
     uint32_t* payload;                  /* [K][payload_words_per_worker] */
     uint64_t payload_words_per_worker;  /* multiple of 4 */
     uint64_t slot_words;                /* 0 = compact placement; else the fixed chunk slot (see above) */

@@ -74,6 +74,11 @@ def SUB():
     return int(lib().orc_sub_coords())
 
 
+def SUBS():
+    """Sub-chunk table entries per chunk."""
+    return CH() // SUB()
+
+
 def philox4x32_10(ctr, key):
     ctr = _c(ctr, np.uint32); key = _c(key, np.uint32)
     out = np.zeros(4, np.uint32)
@@ -155,7 +160,7 @@ class Stream:
     """CODE o Q output of K workers (the norms travel beside it)."""
     payload: np.ndarray     # uint32 [K][cap_words]
     chunk_off: np.ndarray   # uint32 [K][NC+1]
-    sub_end: np.ndarray     # uint16 [K][NC][64]
+    sub_end: np.ndarray     # uint16 [K][NC][SUBS()]
     total_bits: np.ndarray  # uint64 [K]   symbols + signs, no padding
     norms: np.ndarray = None
 
@@ -166,7 +171,7 @@ def encode(idx, neg, lay: Layout, cap_words: int, code_len=None, code_bits=None)
     code_len = _c(code_len, np.uint8); code_bits = _c(code_bits, np.uint32)
     payload = np.zeros((K, cap_words), np.uint32)
     chunk_off = np.zeros((K, lay.NC + 1), np.uint32)
-    sub_end = np.zeros((K, lay.NC, 64), np.uint16)
+    sub_end = np.zeros((K, lay.NC, SUBS()), np.uint16)
     total = np.zeros(K, np.uint64)
     rc = lib().orc_encode(_p(idx, C.c_uint8), _p(neg, C.c_uint8), C.c_uint32(K), C.c_uint64(d),
                           _p(lay.chunk_start, C.c_uint64), C.c_uint64(lay.NC),

@@ -48,8 +48,8 @@
 #include <string.h>
 
 #define ORC_CH 4096u        /* coordinates per chunk                       */
-#define ORC_SUB 64u         /* coordinates per sub-chunk                   */
-#define ORC_SUBS 64u        /* sub-chunk table entries per chunk           */
+#define ORC_SUB 32u         /* coordinates per sub-chunk                   */
+#define ORC_SUBS 128u       /* sub-chunk table entries per chunk           */
 #define ORC_ALIGN_WORDS 4u  /* chunk start alignment in 32-bit words       */
 
 enum { ORC_NORM_LINF = 0, ORC_NORM_L2 = 2 };

@@ -4,11 +4,14 @@
 // Theorem 3 for gamma_t.)
 //
 // One wave per chunk position.  The wave copies a worker's chunk from the payload into LDS with
-// coalesced 16-byte loads (the next worker's chunk is already in flight in registers), then every
-// lane parses its own run of 64 coordinates, starting at the bit offset the sub-chunk table gives:
-// a 64-bit window from three LDS words per three symbols, one 13-bit table lookup for (symbol,
-// length) each, the sign bit, one multiply by the bucket norm.  The K decoded values of a coordinate are summed in registers, so
-// decoded vectors never go to HBM in the fused modes.
+// coalesced 16-byte loads, then every lane parses its own 64 coordinates, that is two sub-chunks of
+// 32, each starting at the bit offset the sub-chunk table gives: a 64-bit window from three LDS words
+// per three symbols, one 13-bit table lookup for (symbol, length) each, the sign bit, one multiply by
+// the bucket norm.  A symbol's length decides where the next one starts, so a parse is one long
+// dependent chain of LDS look-ups; what a lane can do about that is to follow two chains at once:
+// its two sub-chunks when there is one stream, the two streams of the second half-step (each over
+// both sub-chunks in turn).  The K decoded values of a coordinate are summed in registers, so decoded
+// vectors never go to HBM in the fused modes.
 #include "qgx_device.h"
 
 namespace qgx {
@@ -131,6 +134,7 @@ __device__ __forceinline__ float symbol_value(float lv, uint32_t win, uint32_t e
 
 struct SubMeta {             // what a lane needs to parse its run of one worker's chunk
     uint32_t p0, p_end;      // bit cursor at the start and expected at the end
+    uint32_t p_mid;          // where the lane's second sub-chunk starts
     float n;                 // norm of the bucket
 };
 
@@ -139,8 +143,9 @@ __device__ __forceinline__ SubMeta load_meta(const uint16_t* sub_end, const floa
 {
     const uint16_t* se = sub_end + ((size_t)k * lay.NC + c) * kSubs;
     SubMeta m;
-    m.p_end = se[lane];
-    m.p0 = lane ? (uint32_t)se[lane - 1] : 0u;
+    m.p_end = se[2 * lane + 1];
+    m.p_mid = se[2 * lane];
+    m.p0 = lane ? (uint32_t)se[2 * lane - 1] : 0u;
     m.n = norms[(size_t)k * lay.NB + bkt];
     return m;
 }
@@ -198,39 +203,43 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
     // a cursor from a corrupt table is pulled back so that 64 symbols from it stay inside the buffer
     const uint32_t p_limit = stage_words * 32u - 64u * (uint32_t)kMaxSymBits - 64u;
 
-    float acc[kSub];
+    float acc[kLaneCoords];
 #pragma unroll
-    for (int s = 0; s < kSub; ++s) acc[s] = 0.0f;
+    for (int s = 0; s < kLaneCoords; ++s) acc[s] = 0.0f;
     double sdiff = 0.0;
     uint32_t flags = 0;
     bool malformed = false;
 
-    // worker k's chunk(s) and the per-lane cursors travel one iteration ahead, in registers
+    // Two streams: the next worker's chunks are already in flight in registers while these are parsed.
+    // One stream: the registers go to the second parse chain instead; the load of a chunk is covered
+    // by the other waves of the SIMD.  The lane's cursors and the norm travel ahead either way.
+    constexpr bool kAhead = PREV;
     uint4 pre[kPre];
     uint4 pre_p[PREV ? kPre : 1];
     ChunkRef cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, a.sub_end, k_first, c, lay.NC, stage_words, sc);
-    prefetch_chunk(cr, pre);
+    if constexpr (kAhead) prefetch_chunk(cr, pre);
     SubMeta nxt = load_meta(a.sub_end, a.norms, k_first, c, bkt, lay, lane);
-    SubMeta nxt_p{0u, 0u, 0.0f};
+    SubMeta nxt_p{0u, 0u, 0u, 0.0f};
     if constexpr (PREV) {
-        cr = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, a.sub_end_p, k_first, c, lay.NC, stage_words, sc);
-        prefetch_chunk(cr, pre_p);
+        const ChunkRef cp = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, a.sub_end_p, k_first, c, lay.NC, stage_words, sc);
+        prefetch_chunk(cp, pre_p);
         nxt_p = load_meta(a.sub_end_p, a.norms_p, k_first, c, bkt, lay, lane);
     }
 
     for (uint32_t kk = 0; kk < k_count; ++kk) {
         const uint32_t k = k_first + kk;
         const SubMeta cur = nxt, prv = nxt_p;
+        if constexpr (!kAhead) prefetch_chunk(cr, pre);
         commit_chunk(stage, pre, stage_words);
         if constexpr (PREV) commit_chunk(stage_p, pre_p, stage_words);
-        if (kk + 1 < k_count) {                      // next worker's chunks: in flight while these are parsed
+        if (kk + 1 < k_count) {
             cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, a.sub_end, k + 1, c, lay.NC, stage_words, sc);
             nxt = load_meta(a.sub_end, a.norms, k + 1, c, bkt, lay, lane);
-            prefetch_chunk(cr, pre);
+            if constexpr (kAhead) prefetch_chunk(cr, pre);
             if constexpr (PREV) {
-                cr = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, a.sub_end_p, k + 1, c, lay.NC, stage_words, sc);
+                const ChunkRef cp = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, a.sub_end_p, k + 1, c, lay.NC, stage_words, sc);
                 nxt_p = load_meta(a.sub_end_p, a.norms_p, k + 1, c, bkt, lay, lane);
-                prefetch_chunk(cr, pre_p);
+                prefetch_chunk(cp, pre_p);
             }
         }
         uint32_t p = cur.p0, pp = prv.p0;
@@ -240,46 +249,100 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
         float* vout = nullptr;
         if constexpr (MODE == DecMode::Decode) vout = a.out + (size_t)k * lay.d + clo + 64u * (uint32_t)lane;
         uint32_t win[3], e[3], win_p[3] = {0u, 0u, 0u}, e_p[3] = {0u, 0u, 0u};
-        if constexpr (FULL) {                        // 21 groups of three symbols and a last one
-            Window wn = read_window(stage, p), wn_p{0u, 0u, 0u};
-            if constexpr (PREV) wn_p = read_window(stage_p, pp);
+        if constexpr (FULL && !PREV) {
+            // the lane's two sub-chunks side by side: ten groups of three symbols and one of two each
+            constexpr int kHalf = kLaneCoords / 2;
+            uint32_t pb = cur.p_mid;
+            if (pb > p_limit) { pb = p_limit; malformed = true; }
+            uint32_t win_b[3], e_b[3];
+            Window wn = read_window(stage, p), wn_b = read_window(stage, pb);
 #pragma unroll
-            for (int s = 0; s < kSub; s += 3) {
-                if (s + 3 <= kSub) parse_group<3>(wn, s_tab, p, win, e);
-                else parse_group<1>(wn, s_tab, p, win, e);
-                if (s + 3 < kSub) wn = read_window(stage, p);        // the next group's words: issued before the values
-                if constexpr (PREV) {
-                    if (s + 3 <= kSub) parse_group<3>(wn_p, s_tab, pp, win_p, e_p);
-                    else parse_group<1>(wn_p, s_tab, pp, win_p, e_p);
-                    if (s + 3 < kSub) wn_p = read_window(stage_p, pp);
-                }
-                float lv[3], lv_p[3] = {0.0f, 0.0f, 0.0f};
+            for (int s = 0; s < kHalf; s += 3) {
+                if (s + 3 <= kHalf) parse_group<3>(wn, s_tab, p, win, e);
+                else parse_group<2>(wn, s_tab, p, win, e);
+                if (s + 3 < kHalf) wn = read_window(stage, p);
+                if (s + 3 <= kHalf) parse_group<3>(wn_b, s_tab, pb, win_b, e_b);
+                else parse_group<2>(wn_b, s_tab, pb, win_b, e_b);
+                if (s + 3 < kHalf) wn_b = read_window(stage, pb);
+                float lv[3], lv_b[3];
 #pragma unroll
                 for (int i = 0; i < 3; ++i) {
-                    if (s + i < kSub) {
+                    if (s + i < kHalf) {
                         lv[i] = level_of(s_tab, e[i]);
-                        flags |= e[i];
-                        if constexpr (PREV) { lv_p[i] = level_of(s_tab, e_p[i]); flags |= e_p[i]; }
+                        lv_b[i] = level_of(s_tab, e_b[i]);
+                        flags |= e[i] | e_b[i];
                     }
                 }
 #pragma unroll
                 for (int i = 0; i < 3; ++i) {
-                    if (s + i < kSub) {
+                    if (s + i < kHalf) {
                         const float val = symbol_value<kExact>(lv[i], win[i], e[i], n);
-                        if constexpr (MODE == DecMode::Decode) vout[s + i] = val;
-                        else acc[s + i] += val;
+                        const float val_b = symbol_value<kExact>(lv_b[i], win_b[i], e_b[i], n);
+                        if constexpr (MODE == DecMode::Decode) { vout[s + i] = val; vout[kHalf + s + i] = val_b; }
+                        else { acc[s + i] += val; acc[kHalf + s + i] += val_b; }
                         if constexpr (MODE == DecMode::Half1) {
-                            float pv = 0.0f;
-                            if constexpr (PREV) pv = symbol_value<true>(lv_p[i], win_p[i], e_p[i], np);
-                            const double df = (double)pv - (double)val;
-                            sdiff = fma(df, df, sdiff);
+                            sdiff = fma((double)val, (double)val, sdiff);
+                            sdiff = fma((double)val_b, (double)val_b, sdiff);
                         }
                     }
                 }
             }
+            if (p != cur.p_mid) malformed = true;
+            p = pb;
+        } else if constexpr (FULL) {
+            // two streams, two sub-chunks each: four chains, ten groups of three symbols and one of two
+            constexpr int kHalf = kLaneCoords / 2;
+            uint32_t pb = cur.p_mid, ppb = prv.p_mid;
+            if (pb > p_limit) { pb = p_limit; malformed = true; }
+            if (ppb > p_limit) { ppb = p_limit; malformed = true; }
+            uint32_t win_b[3], e_b[3], win_pb[3], e_pb[3];
+            Window wn = read_window(stage, p), wn_b = read_window(stage, pb);
+            Window wn_p = read_window(stage_p, pp), wn_pb = read_window(stage_p, ppb);
+#pragma unroll
+            for (int s = 0; s < kHalf; s += 3) {
+                if (s + 3 <= kHalf) parse_group<3>(wn, s_tab, p, win, e);
+                else parse_group<2>(wn, s_tab, p, win, e);
+                if (s + 3 < kHalf) wn = read_window(stage, p);
+                if (s + 3 <= kHalf) parse_group<3>(wn_p, s_tab, pp, win_p, e_p);
+                else parse_group<2>(wn_p, s_tab, pp, win_p, e_p);
+                if (s + 3 < kHalf) wn_p = read_window(stage_p, pp);
+                if (s + 3 <= kHalf) parse_group<3>(wn_b, s_tab, pb, win_b, e_b);
+                else parse_group<2>(wn_b, s_tab, pb, win_b, e_b);
+                if (s + 3 < kHalf) wn_b = read_window(stage, pb);
+                if (s + 3 <= kHalf) parse_group<3>(wn_pb, s_tab, ppb, win_pb, e_pb);
+                else parse_group<2>(wn_pb, s_tab, ppb, win_pb, e_pb);
+                if (s + 3 < kHalf) wn_pb = read_window(stage_p, ppb);
+                float lv[3], lv_p[3], lv_b[3], lv_pb[3];
+#pragma unroll
+                for (int i = 0; i < 3; ++i) {
+                    if (s + i < kHalf) {
+                        lv[i] = level_of(s_tab, e[i]);
+                        lv_p[i] = level_of(s_tab, e_p[i]);
+                        lv_b[i] = level_of(s_tab, e_b[i]);
+                        lv_pb[i] = level_of(s_tab, e_pb[i]);
+                        flags |= e[i] | e_p[i] | e_b[i] | e_pb[i];
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 3; ++i) {
+                    if (s + i < kHalf) {
+                        const float val = symbol_value<false>(lv[i], win[i], e[i], n);
+                        const float val_b = symbol_value<false>(lv_b[i], win_b[i], e_b[i], n);
+                        acc[s + i] += val;
+                        acc[kHalf + s + i] += val_b;
+                        const double df = (double)symbol_value<true>(lv_p[i], win_p[i], e_p[i], np) - (double)val;
+                        sdiff = fma(df, df, sdiff);
+                        const double df_b = (double)symbol_value<true>(lv_pb[i], win_pb[i], e_pb[i], np) - (double)val_b;
+                        sdiff = fma(df_b, df_b, sdiff);
+                    }
+                }
+            }
+            if (p != cur.p_mid || pp != prv.p_mid) malformed = true;
+            p = pb;
+            pp = ppb;
         } else {
 #pragma unroll
-            for (int s = 0; s < kSub; ++s) {
+            for (int s = 0; s < kLaneCoords; ++s) {
                 if (s < cnt) {
                     parse_group<1>(read_window(stage, p), s_tab, p, win, e);
                     flags |= e[0];
@@ -359,7 +422,7 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
     } else {
         const uint32_t i0 = clo + 64u * (uint32_t)lane;
 #pragma unroll
-        for (int s = 0; s < kSub; ++s) {
+        for (int s = 0; s < kLaneCoords; ++s) {
             if (s < cnt) {
                 const float m = acc[s] * invK;
                 if (MODE == DecMode::Average) a.out[i0 + s] = m;

@@ -156,7 +156,7 @@ __device__ __forceinline__ uint32_t pack_row(uint32_t* stage, uint16_t* sub_row,
     __hip_atomic_fetch_or(&stage[wi + 1], (uint32_t)(lo64 >> 32) | (uint32_t)hi64, __ATOMIC_RELAXED,
                           __HIP_MEMORY_SCOPE_WORKGROUP);
     __hip_atomic_fetch_or(&stage[wi + 2], (uint32_t)(hi64 >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    if ((lane & 15) == 15) sub_row[lane >> 4] = (uint16_t)(row_base + incl);
+    if ((lane & 7) == 7) sub_row[lane >> 3] = (uint16_t)(row_base + incl);      // a sub-chunk is eight lanes of a row
     return (uint32_t)__builtin_amdgcn_readlane((int)incl, kWave - 1);
 }
 
@@ -378,7 +378,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                     for (int q = 0; q < 4; ++q) pk |= (idx[q] | ((__float_as_uint(xs[q]) >> 31) << 7)) << (8 * q);
                     *reinterpret_cast<uint32_t*>(a.sym_out + kbase + i0) = pk;
                 } else {
-                    row_base += pack_row(stage, &s_sub[w][4 * r], row_base, e, lane);
+                    row_base += pack_row(stage, &s_sub[w][8 * r], row_base, e, lane);
                 }
             }
         } else {
@@ -425,7 +425,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                         const float4 t = *reinterpret_cast<const float4*>(s_lev + idx[q] * 16u + neg[q] * a.lev_stride);
                         e[q] = (i0 + (uint32_t)q < g.cend) ? __float_as_uint(t.z) : 0u;
                     }
-                    row_base += pack_row(stage, &s_sub[w][4 * r], row_base, e, lane);
+                    row_base += pack_row(stage, &s_sub[w][8 * r], row_base, e, lane);
                 }
             }
         }
@@ -435,7 +435,8 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
         uint32_t words = (total_bits + 31u) >> 5;
         words = (words + (kAlignWords - 1)) & ~(uint32_t)(kAlignWords - 1);
         if (MODE != EncMode::QuantOnly) {
-            if (lane >= 4 * g.nrows) s_sub[w][lane] = (uint16_t)total_bits;
+            for (int j = lane; j < kSubs; j += kWave)
+                if (j >= 8 * g.nrows) s_sub[w][j] = (uint16_t)total_bits;
             if (lane == 0 && ordered) s_words[w] = words;
         }
         if (MODE != EncMode::QuantOnly) {
@@ -461,9 +462,8 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                     a.chunk_off[(size_t)k * (lay.NC + 1) + g.c] = off;
                     if (g.c + 1 == lay.NC) a.chunk_off[(size_t)k * (lay.NC + 1) + lay.NC] = off + (ordered ? words : a.slot_words);
                 }
-                if (lane < 32)
-                    reinterpret_cast<uint32_t*>(a.sub_end + ((size_t)k * lay.NC + g.c) * kSubs)[lane] =
-                        reinterpret_cast<const uint32_t*>(s_sub[w])[lane];
+                reinterpret_cast<uint32_t*>(a.sub_end + ((size_t)k * lay.NC + g.c) * kSubs)[lane] =
+                    reinterpret_cast<const uint32_t*>(s_sub[w])[lane];      // 128 entries of 16 bits
                 if ((uint64_t)off + words > a.cap_words) {
                     if (lane == 0) raise_error(sc, QGX_EBIT_CAPACITY);
                 } else {

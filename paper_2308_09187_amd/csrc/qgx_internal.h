@@ -13,7 +13,8 @@ constexpr int kWave = 64;                 // CDNA wavefront
 constexpr int kChunk = QGX_CHUNK;         // coordinates per chunk = one wave's share
 constexpr int kRows = 16;                 // rows of 256 coordinates per chunk (4 per lane and row)
 constexpr int kSub = QGX_SUB;
-constexpr int kSubs = 64;                 // sub-chunk table entries per chunk
+constexpr int kSubs = QGX_SUBS;           // sub-chunk table entries per chunk
+constexpr int kLaneCoords = 64;           // coordinates one decoder lane parses: two sub-chunks
 constexpr int kMaxCode = QGX_MAX_CODE_BITS;             // longest code word
 constexpr int kMaxSymBits = kMaxCode + 1;               // plus the sign bit
 constexpr int kChunkWordsMax = kChunk * kMaxSymBits / 32;  // 1792
@@ -94,7 +95,7 @@ struct EncodeArgs {
     uint8_t* sym_out;           // [K][d]           (QuantOnly)
     const uint8_t* sym_in;      // [K][d]           (EncodeOnly)
     uint32_t* chunk_off;        // [K][NC+1]
-    uint16_t* sub_end;          // [K][NC][64]
+    uint16_t* sub_end;          // [K][NC][kSubs]
     uint32_t* payload;          // [K][cap]
     uint64_t cap_words;
     unsigned long long* scan_state;  // [K][NB] look-back words

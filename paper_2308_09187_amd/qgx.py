@@ -21,7 +21,7 @@ ERR_ARG, ERR_LEVELS, ERR_CAPACITY, ERR_STREAM, ERR_NONFINITE, ERR_HIP, ERR_STATE
 EBIT_CAPACITY, EBIT_STREAM, EBIT_NONFINITE, EBIT_STATE = 1, 2, 4, 8
 NORM_LINF, NORM_L2 = 0, 2
 CODE_ELIAS_OMEGA, CODE_TABLE = 0, 1
-CHUNK, SUB, MAX_SYM, MAX_BINS = 4096, 64, 127, 4096
+CHUNK, SUB, SUBS, MAX_SYM, MAX_BINS = 4096, 32, 128, 127, 4096
 
 EXPORTS = [
     "qgx_create", "qgx_destroy", "qgx_stream_sizes", "qgx_slot_words", "qgx_compact", "qgx_set_levels", "qgx_get_levels", "qgx_set_code_table",
@@ -86,7 +86,7 @@ class Stream:
         self.slot_words = int(slot_words)
         self.norms = torch.zeros((K, NB), dtype=torch.float32, device=device)
         self.chunk_off = torch.zeros((K, NC + 1), dtype=torch.int32, device=device)
-        self.sub_end = torch.zeros((K, NC, 64), dtype=torch.int16, device=device)
+        self.sub_end = torch.zeros((K, NC, SUBS), dtype=torch.int16, device=device)
         self.payload = torch.zeros((K, cap_words), dtype=torch.int32, device=device)
         self.cap_words = cap_words
 

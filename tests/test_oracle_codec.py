@@ -55,7 +55,7 @@ def _plain_stream(idx_row, neg_row):
 
 def _container_bits(st, k, c):
     base = int(st.chunk_off[k, c]) * 32
-    nbits = int(st.sub_end[k, c, 63])
+    nbits = int(st.sub_end[k, c, -1])
     w = st.payload[k]
     return "".join(str((int(w[(base + p) >> 5]) >> ((base + p) & 31)) & 1) for p in range(nbits))
 
@@ -102,10 +102,11 @@ def test_round_trip_and_strip_padding_invariant(kind):
             words = -(-len(plain) // 32)
             words = -(-words // 4) * 4
             assert int(st.chunk_off[k, c + 1]) - int(st.chunk_off[k, c]) == words
-            # sub-chunk table: ends of runs of 64 coordinates
-            pos = 0
-            for j in range(64):
-                a, b = lo + 64 * j, min(lo + 64 * (j + 1), hi)
+            # sub-chunk table: ends of runs of SUB coordinates
+            pos, S = 0, oracle.SUB()
+            assert st.sub_end.shape[2] == oracle.CH() // S
+            for j in range(oracle.CH() // S):
+                a, b = lo + S * j, min(lo + S * (j + 1), hi)
                 if a < hi:
                     pos += len(_plain_stream(idx[k, a:b], neg[k, a:b]))
                 assert int(st.sub_end[k, c, j]) == pos
