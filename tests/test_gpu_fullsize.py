@@ -1,6 +1,8 @@
-"""Parity at the headline size and in the benchmark's launch configuration (K = 8 vectors of
-d = 2^24 coordinates, buckets of 16384, L2, 33-symbol fitted table): properties that hold at any size
-over the whole output, and sampled buckets / chunks recomputed one by one by the oracle."""
+"""Parity at full size and in the benchmark's launch configurations: the headline workload (K = 8
+vectors of d = 2^24 coordinates, buckets of 16384, L2, 33-symbol fitted table; slotted chunk placement
+as timed, and compact) and the shape of the large quadratic game (K = 16 vectors of d = 2^26, buckets of
+65536, 65 fitted levels).  Properties that hold at any size are checked over the whole output; sampled
+buckets and chunks are recomputed one by one by the oracle."""
 import numpy as np
 import pytest
 
@@ -14,21 +16,30 @@ pytestmark = pytest.mark.gpu
 REL = 1e-6
 
 
+def chunk_words(h, k, c):
+    """The words of chunk c of worker k, whatever the placement: its size follows from its bit length."""
+    bits = int(h["sub_end"][k, c, -1])
+    n = ((bits + 31) // 32 + 3) // 4 * 4
+    off = int(h["chunk_off"][k, c])
+    return h["payload"][k, off:off + n]
+
+
 def mini_stream(h, k, c0, c1):
-    """The chunks c0..c1-1 of worker k as a stand-alone oracle Stream."""
-    off = h["chunk_off"][k, c0:c1 + 1].astype(np.int64)
-    words = h["payload"][k, off[0]:off[-1]].copy()
-    return oracle.Stream(words[None, :], (off - off[0]).astype(np.uint32)[None, :],
-                         h["sub_end"][k:k + 1, c0:c1], np.zeros(1, np.uint64))
+    """The chunks c0..c1-1 of worker k as a stand-alone compact oracle Stream."""
+    parts = [chunk_words(h, k, c) for c in range(c0, c1)]
+    off = np.concatenate([[0], np.cumsum([len(p) for p in parts])]).astype(np.uint32)
+    return oracle.Stream(np.concatenate(parts)[None, :], off[None, :], h["sub_end"][k:k + 1, c0:c1], np.zeros(1, np.uint64))
 
 
-def test_headline_configuration_sampled_against_oracle():
+@pytest.mark.parametrize("K,logd,bucket,n_sym,slotted", [(8, 24, 16384, 33, True), (8, 24, 16384, 33, False),
+                                                         (16, 26, 65536, 65, True)])
+def test_full_size_sampled_against_oracle(K, logd, bucket, n_sym, slotted):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     from paper_2308_09187_amd import qgx
     qgx.load()
-    K, d, bucket, n_sym, seed, call = 8, 1 << 24, 16384, 33, 2308, 6
-    print("generating", flush=True)
+    d, seed, call = 1 << logd, 2308, 6
+    print("generating", K, logd, bucket, n_sym, slotted, flush=True)
     V = synth.student_t3_device(K, d, seed=20)
     ctx = qgx.Context(d, K, bucket, norm=qgx.NORM_L2, seed=seed)
     ctx.set_levels(synth.levels_exponential(n_sym - 1))
@@ -37,7 +48,7 @@ def test_headline_configuration_sampled_against_oracle():
     assert (np.diff(levels) > 0).all()
     x1 = torch.randn(d, device="cuda", generator=torch.Generator(device="cuda").manual_seed(3))
     ctx.state_init(x1)
-    a = ctx.new_stream()
+    a = ctx.new_stream(slotted=slotted)
     Xh = torch.empty(d, device="cuda")
     print("encode + half-step", flush=True)
     ctx.quantize_encode(V, call, a)
@@ -53,10 +64,13 @@ def test_headline_configuration_sampled_against_oracle():
     assert (off[:, 0] == 0).all()
     words = (bits + 31) // 32
     words = (words + 3) // 4 * 4
-    np.testing.assert_array_equal(np.diff(off, axis=1), words)            # exclusive scan of chunk sizes
+    if slotted:
+        assert (np.diff(off, axis=1) == ctx.slot_words()).all() and (words <= ctx.slot_words()).all()
+    else:
+        np.testing.assert_array_equal(np.diff(off, axis=1), words)        # exclusive scan of chunk sizes
     assert (np.diff(h["sub_end"].astype(np.int64), axis=2) >= oracle.SUB()).all()    # >= 1 bit per coordinate
     assert (h["sub_end"][:, :, 0] >= oracle.SUB()).all()
-    assert (bits <= 4096 * 13).all()                                       # 33 symbols: <= 12 + 1 bits
+    assert (bits <= 4096 * (len(oracle.elias_omega(n_sym)) + 1)).all()     # longest word plus sign
     assert ctx.scalars(want_bits=True)["total_bits"] == int(bits.sum())
     assert np.isfinite(h["norms"]).all() and (h["norms"] > 0).all()
 
@@ -76,6 +90,7 @@ def test_headline_configuration_sampled_against_oracle():
         np.testing.assert_array_equal(ms.chunk_off, so.chunk_off)
         np.testing.assert_array_equal(ms.sub_end, so.sub_end)
         np.testing.assert_array_equal(ms.payload[0], so.payload[0, :ms.payload.shape[1]])
+        assert not so.payload[0, ms.payload.shape[1]:].any()
 
     # -- sampled chunks: decode all K workers, mean and first half-step --------------------------
     lay_c = oracle.layout(4096, 4096)
