@@ -144,7 +144,8 @@ qgx_status qgx_set_code_table(qgx_ctx* ctx, const uint8_t* code_len, const uint3
  *   call_id   distinguishes quantisation calls under one seed (e.g. 2t + half): coordinate i of
  *             worker k draws word (i mod 4) of Philox4x32-10(key = seed, counter = (i/4, 0, k, call_id)),
  *             top 24 bits as r in [0,1); rounds up iff r * (l_{j+1}-l_j) < u - l_j.
- *   norms_in  DEVICE [K][NB] or NULL: norms to use instead of computing them
+ *   norms_in  DEVICE [K][NB] or NULL: non-negative norms to use instead of computing them (a common
+ *             scale for several workers, say); coordinates that exceed it are clamped to u = 1
  *   norms_out DEVICE [K][NB]: the norm used (0 for a rejected bucket)
  *   sym       DEVICE [K][d] bytes: level index in bits 0..6, sign bit of v in bit 7 */
 qgx_status qgx_quantize(qgx_ctx* ctx, const float* V, uint32_t call_id, const float* norms_in,
@@ -159,7 +160,11 @@ qgx_status qgx_encode(qgx_ctx* ctx, const float* norms, const uint8_t* sym, qgx_
 qgx_status qgx_quantize_encode(qgx_ctx* ctx, const float* V, uint32_t call_id, const float* norms_in,
                                qgx_stream* out, void* stream);
 
-/* DEQ o CODE: Vhat DEVICE [K][d], vhat_i = +-(norm * l_idx). */
+/* DEQ o CODE: Vhat DEVICE [K][d], vhat_i = +-(norm * l_idx).
+ * The decoding calls (this one, qgx_decode_average, qgx_eg_step) work on `stream`; for layouts with
+ * chunks of fewer than QGX_CHUNK coordinates they also put a small kernel for those on a second queue
+ * of the context, forked from and joined back into `stream` with events, so that it runs beside the
+ * main kernel: callers see ordinary stream order. */
 qgx_status qgx_decode(qgx_ctx* ctx, const qgx_stream* in, float* Vhat, void* stream);
 
 /* Aggregate of Algorithm 1: mean DEVICE [d] = (1/K) sum_k DEQ(CODE_k), decoded on the fly. */
