@@ -71,6 +71,15 @@ __device__ __forceinline__ uint32_t bcast_lane(uint32_t x, int src)
     return (uint32_t)__shfl((int)x, src, kWave);
 }
 
+// A 16-byte load of data that is read once: marked non-temporal, so that it does not push what is
+// reused (the coded streams a later kernel reads back) out of the caches.
+typedef float nt_f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 nt_load4(const float* p)
+{
+    const nt_f32x4 r = __builtin_nontemporal_load(reinterpret_cast<const nt_f32x4*>(p));
+    return make_float4(r.x, r.y, r.z, r.w);
+}
+
 // t^q for a small positive integer q (the same q in every lane).
 __device__ __forceinline__ double pow_int(double t, uint32_t q)
 {

@@ -196,7 +196,7 @@ __device__ __forceinline__ void load_chunk(float4 (&v)[kRows], const float* __re
     if (g.full && vec_ok) {
 #pragma unroll
         for (int r = 0; r < kRows; ++r)
-            v[r] = *reinterpret_cast<const float4*>(Vk + g.clo + (uint32_t)r * 256u + (uint32_t)lane * 4u);
+            v[r] = nt_load4(Vk + g.clo + (uint32_t)r * 256u + (uint32_t)lane * 4u);
     } else {
 #pragma unroll
         for (int r = 0; r < kRows; ++r) {
