@@ -55,7 +55,7 @@ __device__ __forceinline__ void prefetch_chunk(const ChunkRef& cr, uint4 (&pre)[
 #pragma unroll
     for (int q = 0; q < kPre; ++q) {
         const uint32_t i = lane + (uint32_t)q * kWave;
-        pre[q] = (i < (cr.words >> 2)) ? cr.src[i] : make_uint4(0, 0, 0, 0);
+        pre[q] = (i < (cr.words >> 2)) ? nt_load4u(cr.src + i) : make_uint4(0, 0, 0, 0);
     }
 }
 

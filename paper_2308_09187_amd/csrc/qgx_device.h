@@ -80,6 +80,13 @@ __device__ __forceinline__ float4 nt_load4(const float* p)
     return make_float4(r.x, r.y, r.z, r.w);
 }
 
+typedef uint32_t nt_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 nt_load4u(const uint4* p)
+{
+    const nt_u32x4 r = __builtin_nontemporal_load(reinterpret_cast<const nt_u32x4*>(p));
+    return make_uint4(r.x, r.y, r.z, r.w);
+}
+
 // t^q for a small positive integer q (the same q in every lane).
 __device__ __forceinline__ double pow_int(double t, uint32_t q)
 {
