@@ -11,7 +11,9 @@
 // dependent chain of LDS look-ups; what a lane can do about that is to follow two chains at once:
 // its two sub-chunks when there is one stream, the two streams of the second half-step (each over
 // both sub-chunks in turn).  The K decoded values of a coordinate are summed in registers, so decoded
-// vectors never go to HBM in the fused modes.
+// vectors never go to HBM in the fused modes.  Chunk positions with fewer than 4096 coordinates are
+// few and go to a kernel of their own (k_decode_ragged), which spreads a position's workers over the
+// waves of a workgroup.
 #include "qgx_device.h"
 
 namespace qgx {
@@ -150,10 +152,25 @@ __device__ __forceinline__ SubMeta load_meta(const uint16_t* sub_end, const floa
     return m;
 }
 
-// FULL: the launch covers the chunk positions that hold 4096 coordinates (straight-line parse, output
-// turned through LDS); otherwise it covers the ragged positions listed in the layout.
+// First coordinate, length and bucket of chunk position c.
+__device__ __forceinline__ void chunk_geometry(const Layout& lay, uint32_t c, uint32_t& clo, uint32_t& clen, uint32_t& bkt)
+{
+    if (lay.uniform_bucket) {                             // one segment: chunk geometry is arithmetic
+        bkt = c / lay.waves_per_bucket;
+        const uint32_t lo = bkt * lay.uniform_bucket, hi = min(lo + lay.uniform_bucket, lay.d);
+        clo = lo + (c - bkt * lay.waves_per_bucket) * (uint32_t)kChunk;
+        clen = min((uint32_t)kChunk, hi - clo);
+    } else {
+        clo = lay.chunk_start[c];
+        clen = lay.chunk_start[c + 1] - clo;
+        bkt = lay.chunk_bucket[c];
+    }
+}
+
+// Covers the chunk positions that hold 4096 coordinates (straight-line parse, output turned through
+// LDS); the others are k_decode_ragged's.
 // PREV (Half1): the previous half-step's streams are there; without them the vectors count as zero.
-template <DecMode MODE, bool FULL, bool PREV>
+template <DecMode MODE, bool PREV>
 __global__ __launch_bounds__(kDecWaves * kWave) __attribute__((amdgpu_waves_per_eu(MODE == DecMode::Half1 ? 2 : 4)))
 void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArgs a)
 {
@@ -177,7 +194,7 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
     __syncthreads();
 
     const uint32_t g = (uint32_t)blockIdx.x * (blockDim.x >> 6) + (uint32_t)w;   // global wave number
-    const uint32_t n_pos = FULL ? lay.NC : lay.n_ragged;
+    const uint32_t n_pos = lay.NC;
     uint32_t c, k_first, k_count;
     if (MODE == DecMode::Decode) {
         if (g >= lay.K * n_pos) return;
@@ -186,20 +203,9 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
         if (g >= n_pos) return;
         c = g; k_first = 0; k_count = lay.K;
     }
-    if (!FULL) c = lay.ragged_chunk[c];
     uint32_t clo, clen, bkt;
-    if (lay.uniform_bucket) {                             // one segment: chunk geometry is arithmetic
-        bkt = c / lay.waves_per_bucket;
-        const uint32_t lo = bkt * lay.uniform_bucket, hi = min(lo + lay.uniform_bucket, lay.d);
-        clo = lo + (c - bkt * lay.waves_per_bucket) * (uint32_t)kChunk;
-        clen = min((uint32_t)kChunk, hi - clo);
-    } else {
-        clo = lay.chunk_start[c];
-        clen = lay.chunk_start[c + 1] - clo;
-        bkt = lay.chunk_bucket[c];
-    }
-    const int cnt = (int)min(64u, clen > 64u * (uint32_t)lane ? clen - 64u * (uint32_t)lane : 0u);
-    if ((clen == (uint32_t)kChunk) != FULL) return;      // wave-uniform: the other launch takes this position
+    chunk_geometry(lay, c, clo, clen, bkt);
+    if (clen != (uint32_t)kChunk) return;                // wave-uniform: the ragged launch takes this position
     // a cursor from a corrupt table is pulled back so that 64 symbols from it stay inside the buffer
     const uint32_t p_limit = stage_words * 32u - 64u * (uint32_t)kMaxSymBits - 64u;
 
@@ -249,7 +255,7 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
         float* vout = nullptr;
         if constexpr (MODE == DecMode::Decode) vout = a.out + (size_t)k * lay.d + clo + 64u * (uint32_t)lane;
         uint32_t win[3], e[3], win_p[3] = {0u, 0u, 0u}, e_p[3] = {0u, 0u, 0u};
-        if constexpr (FULL && !PREV) {
+        if constexpr (!PREV) {
             // the lane's two sub-chunks side by side: ten groups of three symbols and one of two each
             constexpr int kHalf = kLaneCoords / 2;
             uint32_t pb = cur.p_mid;
@@ -289,7 +295,7 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
             }
             if (p != cur.p_mid) malformed = true;
             p = pb;
-        } else if constexpr (FULL) {
+        } else {
             // two streams, two sub-chunks each: four chains, ten groups of three symbols and one of two
             constexpr int kHalf = kLaneCoords / 2;
             uint32_t pb = cur.p_mid, ppb = prv.p_mid;
@@ -340,31 +346,10 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
             if (p != cur.p_mid || pp != prv.p_mid) malformed = true;
             p = pb;
             pp = ppb;
-        } else {
-#pragma unroll
-            for (int s = 0; s < kLaneCoords; ++s) {
-                if (s < cnt) {
-                    parse_group<1>(read_window(stage, p), s_tab, p, win, e);
-                    flags |= e[0];
-                    const float val = symbol_value<kExact>(level_of(s_tab, e[0]), win[0], e[0], n);
-                    if constexpr (MODE == DecMode::Decode) vout[s] = val;
-                    else acc[s] += val;
-                    if constexpr (MODE == DecMode::Half1) {
-                        float pv = 0.0f;
-                        if constexpr (PREV) {
-                            parse_group<1>(read_window(stage_p, pp), s_tab, pp, win_p, e_p);
-                            flags |= e_p[0];
-                            pv = symbol_value<true>(level_of(s_tab, e_p[0]), win_p[0], e_p[0], np);
-                        }
-                        const double df = (double)pv - (double)val;
-                        sdiff = fma(df, df, sdiff);
-                    }
-                }
-            }
         }
-        if (cnt > 0 && p != cur.p_end) malformed = true;
+        if (p != cur.p_end) malformed = true;
         if constexpr (PREV) {
-            if (cnt > 0 && pp != prv.p_end) malformed = true;
+            if (pp != prv.p_end) malformed = true;
         }
     }
     malformed = malformed || (flags & 0x8000u) != 0u;
@@ -378,103 +363,249 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
         sdiff = wave_sum(sdiff);
         if (lane == 0) a.s_partial[c] = sdiff;
     }
-    if constexpr (FULL) {
-        // Lane L holds coordinates 64L..64L+63 of the chunk.  Through LDS, 16 symbols at a time, the
-        // wave turns them so that four consecutive lanes own 16 consecutive floats: global accesses
-        // then touch whole 64-byte pieces instead of 16 bytes per 256.
-        float* tr = reinterpret_cast<float*>(stage);          // 64 rows of 20 floats (16 + pad), 5120 bytes
+    // Lane L holds coordinates 64L..64L+63 of the chunk.  Through LDS, 16 symbols at a time, the
+    // wave turns them so that four consecutive lanes own 16 consecutive floats: global accesses
+    // then touch whole 64-byte pieces instead of 16 bytes per 256.
+    float* tr = reinterpret_cast<float*>(stage);          // 64 rows of 20 floats (16 + pad), 5120 bytes
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+    for (int q = 0; q < 4; ++q) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                *reinterpret_cast<float4*>(tr + lane * 20 + 4 * j) =
-                    make_float4(acc[16 * q + 4 * j] * invK, acc[16 * q + 4 * j + 1] * invK,
-                                acc[16 * q + 4 * j + 2] * invK, acc[16 * q + 4 * j + 3] * invK);
+        for (int j = 0; j < 4; ++j)
+            *reinterpret_cast<float4*>(tr + lane * 20 + 4 * j) =
+                make_float4(acc[16 * q + 4 * j] * invK, acc[16 * q + 4 * j + 1] * invK,
+                            acc[16 * q + 4 * j + 2] * invK, acc[16 * q + 4 * j + 3] * invK);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int row = (lane >> 2) + 16 * i;             // whose 16 symbols
-                const float4 m = *reinterpret_cast<const float4*>(tr + row * 20 + 4 * (lane & 3));
-                const uint32_t at = clo + 64u * (uint32_t)row + 16u * (uint32_t)q + 4u * (uint32_t)(lane & 3);
-                if (MODE == DecMode::Average) {
-                    *reinterpret_cast<float4*>(a.out + at) = m;
-                } else if (MODE == DecMode::Half0) {
-                    const float4 y = *reinterpret_cast<const float4*>(a.Y + at);
-                    float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (a.anchor) x = *reinterpret_cast<const float4*>(a.anchor + at);
-                    x.x = (x.x + gam * y.x) - gam * m.x;
-                    x.y = (x.y + gam * y.y) - gam * m.y;
-                    x.z = (x.z + gam * y.z) - gam * m.z;
-                    x.w = (x.w + gam * y.w) - gam * m.w;
-                    *reinterpret_cast<float4*>(a.out + at) = x;
-                    if (a.x_sum) {                                   // ergodic average: sum of the half-step iterates
-                        double2* xs = reinterpret_cast<double2*>(a.x_sum + at);
-                        double2 s0 = xs[0], s1 = xs[1];
-                        s0.x += (double)x.x; s0.y += (double)x.y; s1.x += (double)x.z; s1.y += (double)x.w;
-                        xs[0] = s0; xs[1] = s1;
-                    }
-                } else {
-                    float4 y = *reinterpret_cast<const float4*>(a.Y + at);
-                    y.x -= m.x; y.y -= m.y; y.z -= m.z; y.w -= m.w;
-                    *reinterpret_cast<float4*>(a.Y + at) = y;
+        for (int i = 0; i < 4; ++i) {
+            const int row = (lane >> 2) + 16 * i;             // whose 16 symbols
+            const float4 m = *reinterpret_cast<const float4*>(tr + row * 20 + 4 * (lane & 3));
+            const uint32_t at = clo + 64u * (uint32_t)row + 16u * (uint32_t)q + 4u * (uint32_t)(lane & 3);
+            if (MODE == DecMode::Average) {
+                *reinterpret_cast<float4*>(a.out + at) = m;
+            } else if (MODE == DecMode::Half0) {
+                const float4 y = *reinterpret_cast<const float4*>(a.Y + at);
+                float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (a.anchor) x = *reinterpret_cast<const float4*>(a.anchor + at);
+                x.x = (x.x + gam * y.x) - gam * m.x;
+                x.y = (x.y + gam * y.y) - gam * m.y;
+                x.z = (x.z + gam * y.z) - gam * m.z;
+                x.w = (x.w + gam * y.w) - gam * m.w;
+                *reinterpret_cast<float4*>(a.out + at) = x;
+                if (a.x_sum) {                                   // ergodic average: sum of the half-step iterates
+                    double2* xs = reinterpret_cast<double2*>(a.x_sum + at);
+                    double2 s0 = xs[0], s1 = xs[1];
+                    s0.x += (double)x.x; s0.y += (double)x.y; s1.x += (double)x.z; s1.y += (double)x.w;
+                    xs[0] = s0; xs[1] = s1;
                 }
-            }
-        }
-    } else {
-        const uint32_t i0 = clo + 64u * (uint32_t)lane;
-#pragma unroll
-        for (int s = 0; s < kLaneCoords; ++s) {
-            if (s < cnt) {
-                const float m = acc[s] * invK;
-                if (MODE == DecMode::Average) a.out[i0 + s] = m;
-                else if (MODE == DecMode::Half0) {
-                    const float x = a.anchor ? a.anchor[i0 + s] : 0.0f;
-                    const float xh = (x + gam * a.Y[i0 + s]) - gam * m;
-                    a.out[i0 + s] = xh;
-                    if (a.x_sum) a.x_sum[i0 + s] += (double)xh;
-                } else a.Y[i0 + s] -= m;
+            } else {
+                float4 y = *reinterpret_cast<const float4*>(a.Y + at);
+                y.x -= m.x; y.y -= m.y; y.z -= m.z; y.w -= m.w;
+                *reinterpret_cast<float4*>(a.Y + at) = y;
             }
         }
     }
 }
 
-template <DecMode MODE, bool FULL, bool PREV>
-static hipError_t launch_one(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
+// ---- chunk positions with fewer than 4096 coordinates --------------------------------------------
+// They are the tails of buckets and tensors: few, but a wave that walked all K workers of one, symbol
+// by symbol, would take as long as the whole launch of the full positions.  So a position gets a
+// workgroup of its own and its workers are spread over the waves: wave w stages and parses the chunk
+// of worker k0 + w (every lane its two sub-chunks side by side, as far as they go), then the waves
+// add their values to accumulators in LDS one after the other, so that a coordinate's K values are
+// summed in worker order like everywhere else.  The update itself is done by all threads, coalesced.
+constexpr int kAccPitch = 65;                         // s_acc[s][lane], padded: both access patterns spread over the banks
+
+template <bool PREV>
+constexpr int ragged_waves() { return PREV ? 4 : 8; } // two staging buffers per wave with two streams
+
+template <DecMode MODE, bool PREV>
+__global__ __launch_bounds__(ragged_waves<PREV>() * kWave)
+void k_decode_ragged(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArgs a)
 {
-    const uint64_t n_pos = FULL ? lay.NC : lay.n_ragged;
-    if (n_pos == 0 || (FULL && lay.n_ragged == lay.NC)) return hipSuccess;
+    static_assert(!PREV || MODE == DecMode::Half1, "only the second half-step reads two streams");
+    constexpr int W = ragged_waves<PREV>();
+    constexpr int kBufs = PREV ? 2 : 1;
+    constexpr bool kExact = MODE == DecMode::Decode;
+    constexpr int kHalf = kLaneCoords / 2;
+    extern __shared__ __align__(16) uint32_t s_dyn[];    // [waves][1 or 2][rag_stride]
+    __shared__ __align__(16) unsigned char s_tab[kTabBytes];
+    __shared__ float s_acc[kLaneCoords * kAccPitch];
+    __shared__ double s_sd[W];
+
+    const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
+    const uint32_t stage_words = a.rag_words, stage_stride = a.rag_stride;
+    uint32_t* stage = s_dyn + (size_t)w * kBufs * stage_stride;
+    uint32_t* stage_p = stage + stage_stride;
+
+    for (int i = tid; i < kSymMax; i += W * kWave) reinterpret_cast<float*>(s_tab)[i] = tab->lval[i];
+    for (int i = tid; i < kDlut / 2; i += W * kWave)
+        reinterpret_cast<uint32_t*>(s_tab + kTabLvalBytes)[i] = reinterpret_cast<const uint32_t*>(tab->dlut)[i];
+    for (int i = tid; i < kLaneCoords * kAccPitch; i += W * kWave) s_acc[i] = 0.0f;
+    for (uint32_t q = (uint32_t)lane; q < kBufs * stage_stride; q += kWave) stage[q] = 0;
+    __syncthreads();
+
+    const uint32_t c = lay.ragged_chunk[blockIdx.x];
+    uint32_t clo, clen, bkt;
+    chunk_geometry(lay, c, clo, clen, bkt);
+    const int cnt = (int)min(64u, clen > 64u * (uint32_t)lane ? clen - 64u * (uint32_t)lane : 0u);
+    const int cnt_a = min(cnt, kHalf), cnt_b = cnt - cnt_a;       // symbols of the lane's two sub-chunks
+    // a cursor from a corrupt table is pulled back so that 32 symbols from it stay inside the buffer
+    const uint32_t p_limit = stage_words * 32u - (uint32_t)(kHalf * kMaxSymBits) - 64u;
+
+    double sdiff = 0.0;
+    uint32_t flags = 0;
+    bool malformed = false;
+
+    for (uint32_t k0 = 0; k0 < lay.K; k0 += W) {
+        const uint32_t k = k0 + (uint32_t)w;
+        const bool active = k < lay.K;                    // wave-uniform
+        float val[kLaneCoords];
+#pragma unroll
+        for (int s = 0; s < kLaneCoords; ++s) val[s] = 0.0f;
+        if (active) {
+            uint4 pre[kPre];
+            const ChunkRef cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, a.sub_end, k, c, lay.NC, stage_words, sc);
+            prefetch_chunk(cr, pre);
+            const SubMeta cur = load_meta(a.sub_end, a.norms, k, c, bkt, lay, lane);
+            SubMeta prv{0u, 0u, 0u, 0.0f};
+            commit_chunk(stage, pre, stage_words);
+            if constexpr (PREV) {
+                const ChunkRef cp = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, a.sub_end_p, k, c, lay.NC, stage_words, sc);
+                prefetch_chunk(cp, pre);
+                prv = load_meta(a.sub_end_p, a.norms_p, k, c, bkt, lay, lane);
+                commit_chunk(stage_p, pre, stage_words);
+            }
+            uint32_t p = cur.p0, pb = cur.p_mid, pp = prv.p0, ppb = prv.p_mid;
+            if (p > p_limit) { p = p_limit; malformed = true; }
+            if (pb > p_limit) { pb = p_limit; malformed = true; }
+            if (pp > p_limit) { pp = p_limit; malformed = true; }
+            if (ppb > p_limit) { ppb = p_limit; malformed = true; }
+            const float n = cur.n, np = prv.n;
+            uint32_t win[3], e[3];
+#pragma unroll
+            for (int s = 0; s < kHalf; ++s) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {             // the two sub-chunks in turn: two independent chains
+                    if (s < (h ? cnt_b : cnt_a)) {
+                        parse_group<1>(read_window(stage, h ? pb : p), s_tab, h ? pb : p, win, e);
+                        flags |= e[0];
+                        const float v = symbol_value<kExact>(level_of(s_tab, e[0]), win[0], e[0], n);
+                        val[h * kHalf + s] = v;
+                        if constexpr (MODE == DecMode::Half1) {
+                            float pv = 0.0f;
+                            if constexpr (PREV) {
+                                parse_group<1>(read_window(stage_p, h ? ppb : pp), s_tab, h ? ppb : pp, win, e);
+                                flags |= e[0];
+                                pv = symbol_value<true>(level_of(s_tab, e[0]), win[0], e[0], np);
+                            }
+                            const double df = (double)pv - (double)v;
+                            sdiff = fma(df, df, sdiff);
+                        }
+                    }
+                }
+            }
+            if (cnt > 0 && (p != cur.p_mid || pb != cur.p_end)) malformed = true;
+            if constexpr (PREV) {
+                if (cnt > 0 && (pp != prv.p_mid || ppb != prv.p_end)) malformed = true;
+            }
+            if constexpr (MODE == DecMode::Decode) {
+                float* vout = a.out + (size_t)k * lay.d + clo + 64u * (uint32_t)lane;
+#pragma unroll
+                for (int s = 0; s < kLaneCoords; ++s)
+                    if (s < cnt) vout[s] = val[s];
+            }
+        }
+        if constexpr (MODE != DecMode::Decode) {
+            for (int turn = 0; turn < W; ++turn) {        // worker order: k0, k0 + 1, ...
+                if (turn == w && active) {
+#pragma unroll
+                    for (int s = 0; s < kLaneCoords; ++s)
+                        if (s < cnt) s_acc[s * kAccPitch + lane] += val[s];
+                }
+                __syncthreads();
+            }
+        }
+    }
+    malformed = malformed || (flags & 0x8000u) != 0u;
+    if (__any(malformed) && lane == 0) raise_error(sc, QGX_EBIT_STREAM);
+    if (MODE == DecMode::Decode) return;
+
+    if constexpr (MODE == DecMode::Half1) {
+        sdiff = wave_sum(sdiff);
+        if (lane == 0) s_sd[w] = sdiff;
+        __syncthreads();
+        if (tid == 0) {
+            double t = 0.0;
+            for (int i = 0; i < W; ++i) t += s_sd[i];
+            a.s_partial[c] = t;
+        }
+    }
+    const float invK = 1.0f / (float)lay.K;
+    const float gam = sc->gamma_f;
+    for (uint32_t i = (uint32_t)tid; i < clen; i += W * kWave) {
+        const float m = s_acc[(i & 63u) * kAccPitch + (i >> 6)] * invK;
+        const uint32_t at = clo + i;
+        if (MODE == DecMode::Average) a.out[at] = m;
+        else if (MODE == DecMode::Half0) {
+            const float x = a.anchor ? a.anchor[at] : 0.0f;
+            const float xh = (x + gam * a.Y[at]) - gam * m;
+            a.out[at] = xh;
+            if (a.x_sum) a.x_sum[at] += (double)xh;
+        } else a.Y[at] -= m;
+    }
+}
+
+template <DecMode MODE, bool PREV>
+static hipError_t launch_full(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
+{
+    if (lay.n_ragged == lay.NC) return hipSuccess;
     const size_t lds = (size_t)kDecWaves * (PREV ? 2 : 1) * a.stage_stride * sizeof(uint32_t);
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<MODE, FULL, PREV>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<MODE, PREV>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 140 * 1024);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    const uint64_t nwork = (MODE == DecMode::Decode) ? (uint64_t)lay.K * n_pos : n_pos;
+    const uint64_t nwork = (MODE == DecMode::Decode) ? (uint64_t)lay.K * lay.NC : lay.NC;
     const uint32_t grid = (uint32_t)((nwork + kDecWaves - 1) / kDecWaves);
-    hipLaunchKernelGGL((k_decode<MODE, FULL, PREV>), dim3(grid), dim3(kDecWaves * kWave), lds, st, lay, tab, sc, a);
+    hipLaunchKernelGGL((k_decode<MODE, PREV>), dim3(grid), dim3(kDecWaves * kWave), lds, st, lay, tab, sc, a);
     return hipGetLastError();
 }
 
-// Two launches cover the chunk positions: the full ones and, if the layout has any, the ragged ones.
-// The few ragged positions take about as long as the whole of the full ones (their parse is
-// predicated, and a wave still walks all K workers), so they go first and on the side queue, where
-// they run beside the full ones instead of after them.
+template <DecMode MODE, bool PREV>
+static hipError_t launch_ragged(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
+{
+    if (lay.n_ragged == 0) return hipSuccess;
+    constexpr int W = ragged_waves<PREV>();
+    const size_t lds = (size_t)W * (PREV ? 2 : 1) * a.rag_stride * sizeof(uint32_t);
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_ragged<MODE, PREV>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 100 * 1024);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((k_decode_ragged<MODE, PREV>), dim3(lay.n_ragged), dim3(W * kWave), lds, st, lay, tab, sc, a);
+    return hipGetLastError();
+}
+
+// Two launches cover the chunk positions: the full ones and, if the layout has any, the ragged ones,
+// which go first and on the side queue, where they run beside the full ones instead of after them.
 template <DecMode MODE, bool PREV>
 static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st,
                               const SideQueue* side)
 {
     const bool both = lay.n_ragged != 0 && lay.n_ragged != lay.NC;
     if (!both || side == nullptr) {
-        hipError_t e = launch_one<MODE, false, PREV>(lay, tab, sc, a, st);
+        hipError_t e = launch_ragged<MODE, PREV>(lay, tab, sc, a, st);
         if (e != hipSuccess) return e;
-        return launch_one<MODE, true, PREV>(lay, tab, sc, a, st);
+        return launch_full<MODE, PREV>(lay, tab, sc, a, st);
     }
     hipError_t e = hipEventRecord(side->fork, st);
     if (e == hipSuccess) e = hipStreamWaitEvent(side->stream, side->fork, 0);
-    if (e == hipSuccess) e = launch_one<MODE, false, PREV>(lay, tab, sc, a, side->stream);
+    if (e == hipSuccess) e = launch_ragged<MODE, PREV>(lay, tab, sc, a, side->stream);
     if (e == hipSuccess) e = hipEventRecord(side->join, side->stream);
-    if (e == hipSuccess) e = launch_one<MODE, true, PREV>(lay, tab, sc, a, st);
+    if (e == hipSuccess) e = launch_full<MODE, PREV>(lay, tab, sc, a, st);
     if (e == hipSuccess) e = hipStreamWaitEvent(st, side->join, 0);
     return e;
 }

@@ -81,6 +81,7 @@ struct Layout {                 // device pointers into one allocation
     const uint32_t* ragged_chunk;   // [n_ragged] chunk positions with fewer than kChunk coordinates, ascending
     uint32_t NB, NC, K, d;
     uint32_t n_ragged;
+    uint32_t max_ragged;            // coordinates of the longest of them
     uint32_t waves_per_bucket;      // ceil(bucket / kChunk)
     uint32_t uniform_bucket;        // bucket size if there is one segment (offsets are then arithmetic), else 0
 };
@@ -124,6 +125,8 @@ struct DecodeArgs {
     double* x_sum;              // [d] running sum of the X_{t+1/2} or null (Half0 adds its output)
     uint32_t stage_words;       // most words a chunk can take with the code in use (multiple of 4)
     uint32_t stage_stride;      // words of one LDS staging buffer (padded layout plus slack)
+    uint32_t rag_words;         // the same two for the layout's longest chunk of fewer than 4096 coordinates
+    uint32_t rag_stride;
 };
 
 hipError_t launch_build_tables(Tables* tab, hipStream_t st);

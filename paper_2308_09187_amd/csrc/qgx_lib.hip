@@ -149,6 +149,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     // buckets and chunks of one worker
     std::vector<uint32_t> bstart, bchunk0, cstart, cbucket, ragged;
     uint64_t pos = 0, worst = 0;
+    uint32_t max_ragged = 0;
     for (uint64_t len_s : c->seg) {
         uint64_t left = len_s;
         while (left) {
@@ -157,7 +158,10 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
             bchunk0.push_back((uint32_t)cstart.size());
             for (uint64_t o = 0; o < len; o += kChunk) {
                 const uint64_t cl = (len - o) < (uint64_t)kChunk ? (len - o) : (uint64_t)kChunk;
-                if (cl < (uint64_t)kChunk) ragged.push_back((uint32_t)cstart.size());
+                if (cl < (uint64_t)kChunk) {
+                    ragged.push_back((uint32_t)cstart.size());
+                    if (cl > max_ragged) max_ragged = (uint32_t)cl;
+                }
                 cstart.push_back((uint32_t)(pos + o));
                 cbucket.push_back((uint32_t)(bstart.size() - 1));
                 uint64_t wds = (cl * kMaxSymBits + 31) / 32;
@@ -187,6 +191,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
 
     c->lay.NB = NB; c->lay.NC = NC; c->lay.K = cfg->K; c->lay.d = (uint32_t)cfg->d;
     c->lay.n_ragged = (uint32_t)ragged.size();
+    c->lay.max_ragged = max_ragged;
     uint32_t max_len = 0;
     for (uint32_t b = 0; b < NB; ++b) max_len = bstart[b + 1] - bstart[b] > max_len ? bstart[b + 1] - bstart[b] : max_len;
     c->lay.waves_per_bucket = (max_len + kChunk - 1) / kChunk;
@@ -420,6 +425,9 @@ static void fill_decode_args(const qgx_ctx* ctx, DecodeArgs& a, const qgx_stream
     a.stage_words = chunk_slot_words(ctx);
     a.stage_stride = (a.stage_words + a.stage_words / 16 + 12 + 3) / 4 * 4;
     if (a.stage_stride < 1280u) a.stage_stride = 1280u;   // the buffer also turns the output (64 rows of 20 floats)
+    a.rag_words = ((ctx->lay.max_ragged * (ctx->max_code_len + 1) + 31) / 32 + 3) / 4 * 4;
+    if (a.rag_words < 64u) a.rag_words = 64u;             // room for a lane's run of 32 symbols from any cursor
+    a.rag_stride = (a.rag_words + a.rag_words / 16 + 12 + 3) / 4 * 4;
     a.norms = cur->norms; a.chunk_off = cur->chunk_off; a.sub_end = cur->sub_end; a.payload = cur->payload;
     a.cap_words = cur->payload_words_per_worker;
     if (prev) {

@@ -555,6 +555,42 @@ def test_fit_levels_parity(qgx, norm, bucket, n_bins):
     ctx.close()
 
 
+@pytest.mark.parametrize("K", [11, 5])
+def test_ragged_positions_many_workers(qgx, K):
+    """Chunk positions with fewer than 4096 coordinates, of several lengths (a lane with one run, with
+    two, with none), and a worker count that is no multiple of the waves that share a position:
+    plain decode, mean, both half-steps with and without the previous streams."""
+    segs = np.array([4096 + 3000, 700, 36, 4096, 64, 2049], np.uint64)
+    d = int(segs.sum())
+    levels = synth.levels_exponential(16)
+    ctx, lay = make_ctx(qgx, d, K, 4096, oracle.NORM_L2, levels, seed=77, segs=segs)
+    x1 = synth.gaussian_vector(d, seed=4)
+    V0, V1 = synth.student_t3(K, d, seed=5), synth.student_t3(K, d, seed=6)
+    a, b = ctx.new_stream(), ctx.new_stream()
+    ctx.quantize_encode(dev(V0), 0, a)
+    ctx.quantize_encode(dev(V1), 1, b)
+    ha, hb = a.to_host(), b.to_host()
+    _, _, _, sa = oracle_stream(V0, lay, oracle.NORM_L2, levels, 77, 0, ha["norms"], ctx.worst_words)
+    _, _, _, sb = oracle_stream(V1, lay, oracle.NORM_L2, levels, 77, 1, hb["norms"], ctx.worst_words)
+    assert_stream_equal(ha, sa, lay); assert_stream_equal(hb, sb, lay)
+    Va, _, _ = oracle.decode(sa, ha["norms"], lay, levels)
+    Vb, _, _ = oracle.decode(sb, hb["norms"], lay, levels)
+    np.testing.assert_array_equal(ctx.decode(a).cpu().numpy(), Va)              # one multiply: exact
+    assert rel_err(ctx.decode_average(a).cpu().numpy(), Va.astype(np.float64).mean(axis=0)) <= REL
+    for prev in (True, False):
+        ctx.state_init(dev(x1))
+        st = oracle.EGState(d, K, X1=x1)
+        Xh = torch.empty(d, device="cuda"); Xn = torch.empty(d, device="cuda")
+        ctx.eg_step(0, a, None, Xh)
+        assert rel_err(Xh.cpu().numpy(), st.half0(Va)) <= REL
+        ctx.eg_step(1, b, a if prev else None, Xn)
+        assert rel_err(Xn.cpu().numpy(), st.half1(Vb, Va if prev else None)) <= REL
+        sc = ctx.scalars()
+        assert abs(sc["S"] - st.S) <= REL * st.S and abs(sc["gamma"] - st.gamma) <= REL * st.gamma
+    assert ctx.poll_error() == 0
+    ctx.close()
+
+
 def test_gan_layout_full_iteration(qgx):
     """Workload 4 at a tenth of its size: 14 segments of very different scale, per-segment buckets of
     8192 with short ones, L-infinity norm, 16 exponential levels, K = 8, both half-steps."""
