@@ -227,9 +227,13 @@ def main():
                      # the kernel is bound by the vector ALUs before HBM: time they were busy in the counter run
                      "valu_busy_us": _profile_number("valu_busy_us") if default_workload else None},
     }
+    names = ["encode", "decode_avg_half0", "encode_2", "decode_avg_half1"][:n_ev - 1]
+    per_step = {n: np.array([e[j].elapsed_time(e[j + 1]) for e in events]) for j, n in enumerate(names)}
     if args.full_iteration:
-        out["kernels_ms"]["encode_2"] = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
-        out["kernels_ms"]["decode_avg_half1"] = float(np.mean([e[3].elapsed_time(e[4]) for e in events]))
+        out["kernels_ms"]["encode_2"] = float(per_step["encode_2"].mean())
+        out["kernels_ms"]["decode_avg_half1"] = float(per_step["decode_avg_half1"].mean())
+    out["kernels_ms_median"] = {n: float(np.median(v)) for n, v in per_step.items()}
+    out["kernels_ms_min"] = {n: float(v.min()) for n, v in per_step.items()}
     ctx.close()
     if not args.no_cpu_baseline and args.workload == "t3":
         ds = min(d, 1 << args.cpu_sample_logd)

@@ -61,6 +61,7 @@ extern "C" {
 #define QGX_MAX_SYM 127u     /* largest level table (l_0 .. l_{s+1}) */
 #define QGX_MAX_BINS 4096u
 #define QGX_MAX_CODE_BITS 13u
+#define QGX_TABLES 2         /* level tables (each with its code) a context holds */
 
 typedef struct qgx_ctx qgx_ctx;
 
@@ -125,6 +126,14 @@ qgx_status qgx_slot_words(const qgx_ctx* ctx, uint64_t* slot_words);
 /* Rewrites a slotted stream as a compact one (same bits per chunk, exclusive-scan offsets).
  * `out` must be compact (slot_words = 0) and may not alias `in`. */
 qgx_status qgx_compact(qgx_ctx* ctx, const qgx_stream* in, qgx_stream* out, void* stream);
+
+/* A context holds QGX_TABLES level tables, each with its own code: Section 3.3 notes that the dual
+ * vectors of the two half-steps, V_t and V_{t+1/2}, may be given level sequences of their own.
+ * `table` names the one that every call from here on sets, fits, reads, codes with and decodes with;
+ * `prev_table` the one the `prev` streams of qgx_eg_step(half = 1) were coded with.  Both are 0
+ * until this is called.  Slot sizes (qgx_slot_words) cover the longest code of the tables set, so
+ * streams of either table can share their buffers' geometry.  Host-side only; nothing is launched. */
+qgx_status qgx_select_table(qgx_ctx* ctx, uint32_t table, uint32_t prev_table);
 
 /* Level table l of Definition 1: levels_host HOST [n_sym], 2 <= n_sym <= QGX_MAX_SYM,
  * 0 = l[0] < ... < l[n_sym-1] = 1 (QGX_ERR_LEVELS otherwise).  Synchronises `stream`. */
@@ -201,7 +210,8 @@ qgx_status qgx_state_init(qgx_ctx* ctx, const float* X1, void* stream);
  *   half = 1: Y <- Y - (1/K) sum_k Vhat_{k,t+1/2};  S += sum_k ||Vhat_{k,t} - Vhat_{k,t+1/2}||^2;
  *             gamma_{t+1} = K / sqrt(1 + S);  t += 1;  X_out (may be NULL) <- X1 + gamma_{t+1} Y.
  *             `cur` holds the t+1/2 streams, `prev` the t streams (NULL: Vhat_{k,t} = 0, the
- *             dual-averaging case).  Both must have been coded with the context's current levels. */
+ *             dual-averaging case).  `cur` must have been coded with the selected table as it is
+ *             now, `prev` with the table qgx_select_table names for it. */
 qgx_status qgx_eg_step(qgx_ctx* ctx, int half, const qgx_stream* cur, const qgx_stream* prev,
                        float* X_out, void* stream);
 

@@ -152,6 +152,14 @@ __device__ __forceinline__ SubMeta load_meta(const uint16_t* sub_end, const floa
     return m;
 }
 
+// Level values and decode table of one Tables object into the decoder's LDS array.
+__device__ __forceinline__ void load_tables(unsigned char* s_tab, const Tables* __restrict__ tab, int tid, int nthreads)
+{
+    for (int i = tid; i < kSymMax; i += nthreads) reinterpret_cast<float*>(s_tab)[i] = tab->lval[i];
+    for (int i = tid; i < kDlut / 2; i += nthreads)
+        reinterpret_cast<uint32_t*>(s_tab + kTabLvalBytes)[i] = reinterpret_cast<const uint32_t*>(tab->dlut)[i];
+}
+
 // First coordinate, length and bucket of chunk position c.
 __device__ __forceinline__ void chunk_geometry(const Layout& lay, uint32_t c, uint32_t& clo, uint32_t& clen, uint32_t& bkt)
 {
@@ -170,13 +178,17 @@ __device__ __forceinline__ void chunk_geometry(const Layout& lay, uint32_t c, ui
 // Covers the chunk positions that hold 4096 coordinates (straight-line parse, output turned through
 // LDS); the others are k_decode_ragged's.
 // PREV (Half1): the previous half-step's streams are there; without them the vectors count as zero.
-template <DecMode MODE, bool PREV>
+// TWO: those were coded with another level table and code (a.tab_p) than the current ones.
+template <DecMode MODE, bool PREV, bool TWO>
 __global__ __launch_bounds__(kDecWaves * kWave) __attribute__((amdgpu_waves_per_eu(MODE == DecMode::Half1 ? 2 : 4)))
 void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArgs a)
 {
     static_assert(!PREV || MODE == DecMode::Half1, "only the second half-step reads two streams");
+    static_assert(!TWO || PREV, "a second table only comes with a second stream");
     extern __shared__ __align__(16) uint32_t s_dyn[];    // [waves][1 or 2][stage_stride]
     __shared__ __align__(16) unsigned char s_tab[kTabBytes];
+    __shared__ __align__(16) unsigned char s_tab2[TWO ? kTabBytes : 16];
+    const unsigned char* s_tab_p = TWO ? s_tab2 : s_tab;
 
     const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
     constexpr int kBufs = PREV ? 2 : 1;
@@ -186,9 +198,8 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
     uint32_t* stage = s_dyn + (size_t)w * kBufs * stage_stride;
     uint32_t* stage_p = stage + stage_stride;
 
-    for (int i = tid; i < kSymMax; i += (int)blockDim.x) reinterpret_cast<float*>(s_tab)[i] = tab->lval[i];
-    for (int i = tid; i < kDlut / 2; i += (int)blockDim.x)
-        reinterpret_cast<uint32_t*>(s_tab + kTabLvalBytes)[i] = reinterpret_cast<const uint32_t*>(tab->dlut)[i];
+    load_tables(s_tab, tab, tid, (int)blockDim.x);
+    if constexpr (TWO) load_tables(s_tab2, a.tab_p, tid, (int)blockDim.x);
     // words past a chunk's end are read by the window of its last symbols: keep them defined
     for (uint32_t q = (uint32_t)lane; q < kBufs * stage_stride; q += kWave) stage[q] = 0;
     __syncthreads();
@@ -309,23 +320,23 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
                 if (s + 3 <= kHalf) parse_group<3>(wn, s_tab, p, win, e);
                 else parse_group<2>(wn, s_tab, p, win, e);
                 if (s + 3 < kHalf) wn = read_window(stage, p);
-                if (s + 3 <= kHalf) parse_group<3>(wn_p, s_tab, pp, win_p, e_p);
-                else parse_group<2>(wn_p, s_tab, pp, win_p, e_p);
+                if (s + 3 <= kHalf) parse_group<3>(wn_p, s_tab_p, pp, win_p, e_p);
+                else parse_group<2>(wn_p, s_tab_p, pp, win_p, e_p);
                 if (s + 3 < kHalf) wn_p = read_window(stage_p, pp);
                 if (s + 3 <= kHalf) parse_group<3>(wn_b, s_tab, pb, win_b, e_b);
                 else parse_group<2>(wn_b, s_tab, pb, win_b, e_b);
                 if (s + 3 < kHalf) wn_b = read_window(stage, pb);
-                if (s + 3 <= kHalf) parse_group<3>(wn_pb, s_tab, ppb, win_pb, e_pb);
-                else parse_group<2>(wn_pb, s_tab, ppb, win_pb, e_pb);
+                if (s + 3 <= kHalf) parse_group<3>(wn_pb, s_tab_p, ppb, win_pb, e_pb);
+                else parse_group<2>(wn_pb, s_tab_p, ppb, win_pb, e_pb);
                 if (s + 3 < kHalf) wn_pb = read_window(stage_p, ppb);
                 float lv[3], lv_p[3], lv_b[3], lv_pb[3];
 #pragma unroll
                 for (int i = 0; i < 3; ++i) {
                     if (s + i < kHalf) {
                         lv[i] = level_of(s_tab, e[i]);
-                        lv_p[i] = level_of(s_tab, e_p[i]);
+                        lv_p[i] = level_of(s_tab_p, e_p[i]);
                         lv_b[i] = level_of(s_tab, e_b[i]);
-                        lv_pb[i] = level_of(s_tab, e_pb[i]);
+                        lv_pb[i] = level_of(s_tab_p, e_pb[i]);
                         flags |= e[i] | e_p[i] | e_b[i] | e_pb[i];
                     }
                 }
@@ -417,17 +428,20 @@ constexpr int kAccPitch = 65;                         // s_acc[s][lane], padded:
 template <bool PREV>
 constexpr int ragged_waves() { return PREV ? 4 : 8; } // two staging buffers per wave with two streams
 
-template <DecMode MODE, bool PREV>
+template <DecMode MODE, bool PREV, bool TWO>
 __global__ __launch_bounds__(ragged_waves<PREV>() * kWave)
 void k_decode_ragged(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArgs a)
 {
     static_assert(!PREV || MODE == DecMode::Half1, "only the second half-step reads two streams");
+    static_assert(!TWO || PREV, "a second table only comes with a second stream");
     constexpr int W = ragged_waves<PREV>();
     constexpr int kBufs = PREV ? 2 : 1;
     constexpr bool kExact = MODE == DecMode::Decode;
     constexpr int kHalf = kLaneCoords / 2;
     extern __shared__ __align__(16) uint32_t s_dyn[];    // [waves][1 or 2][rag_stride]
     __shared__ __align__(16) unsigned char s_tab[kTabBytes];
+    __shared__ __align__(16) unsigned char s_tab2[TWO ? kTabBytes : 16];
+    const unsigned char* s_tab_p = TWO ? s_tab2 : s_tab;
     __shared__ float s_acc[kLaneCoords * kAccPitch];
     __shared__ double s_sd[W];
 
@@ -436,9 +450,8 @@ void k_decode_ragged(Layout lay, const Tables* __restrict__ tab, Scalars* sc, De
     uint32_t* stage = s_dyn + (size_t)w * kBufs * stage_stride;
     uint32_t* stage_p = stage + stage_stride;
 
-    for (int i = tid; i < kSymMax; i += W * kWave) reinterpret_cast<float*>(s_tab)[i] = tab->lval[i];
-    for (int i = tid; i < kDlut / 2; i += W * kWave)
-        reinterpret_cast<uint32_t*>(s_tab + kTabLvalBytes)[i] = reinterpret_cast<const uint32_t*>(tab->dlut)[i];
+    load_tables(s_tab, tab, tid, W * kWave);
+    if constexpr (TWO) load_tables(s_tab2, a.tab_p, tid, W * kWave);
     for (int i = tid; i < kLaneCoords * kAccPitch; i += W * kWave) s_acc[i] = 0.0f;
     for (uint32_t q = (uint32_t)lane; q < kBufs * stage_stride; q += kWave) stage[q] = 0;
     __syncthreads();
@@ -493,9 +506,9 @@ void k_decode_ragged(Layout lay, const Tables* __restrict__ tab, Scalars* sc, De
                         if constexpr (MODE == DecMode::Half1) {
                             float pv = 0.0f;
                             if constexpr (PREV) {
-                                parse_group<1>(read_window(stage_p, h ? ppb : pp), s_tab, h ? ppb : pp, win, e);
+                                parse_group<1>(read_window(stage_p, h ? ppb : pp), s_tab_p, h ? ppb : pp, win, e);
                                 flags |= e[0];
-                                pv = symbol_value<true>(level_of(s_tab, e[0]), win[0], e[0], np);
+                                pv = symbol_value<true>(level_of(s_tab_p, e[0]), win[0], e[0], np);
                             }
                             const double df = (double)pv - (double)v;
                             sdiff = fma(df, df, sdiff);
@@ -554,58 +567,58 @@ void k_decode_ragged(Layout lay, const Tables* __restrict__ tab, Scalars* sc, De
     }
 }
 
-template <DecMode MODE, bool PREV>
+template <DecMode MODE, bool PREV, bool TWO>
 static hipError_t launch_full(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
 {
     if (lay.n_ragged == lay.NC) return hipSuccess;
     const size_t lds = (size_t)kDecWaves * (PREV ? 2 : 1) * a.stage_stride * sizeof(uint32_t);
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<MODE, PREV>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 140 * 1024);
+    static size_t lds_allowed = 0;                        // the limit is per kernel: raised when a launch needs more
+    if (lds > lds_allowed) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<MODE, PREV, TWO>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        attr_done = true;
+        lds_allowed = lds;
     }
     const uint64_t nwork = (MODE == DecMode::Decode) ? (uint64_t)lay.K * lay.NC : lay.NC;
     const uint32_t grid = (uint32_t)((nwork + kDecWaves - 1) / kDecWaves);
-    hipLaunchKernelGGL((k_decode<MODE, PREV>), dim3(grid), dim3(kDecWaves * kWave), lds, st, lay, tab, sc, a);
+    hipLaunchKernelGGL((k_decode<MODE, PREV, TWO>), dim3(grid), dim3(kDecWaves * kWave), lds, st, lay, tab, sc, a);
     return hipGetLastError();
 }
 
-template <DecMode MODE, bool PREV>
+template <DecMode MODE, bool PREV, bool TWO>
 static hipError_t launch_ragged(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
 {
     if (lay.n_ragged == 0) return hipSuccess;
     constexpr int W = ragged_waves<PREV>();
     const size_t lds = (size_t)W * (PREV ? 2 : 1) * a.rag_stride * sizeof(uint32_t);
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_ragged<MODE, PREV>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 100 * 1024);
+    static size_t lds_allowed = 0;
+    if (lds > lds_allowed) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_ragged<MODE, PREV, TWO>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        attr_done = true;
+        lds_allowed = lds;
     }
-    hipLaunchKernelGGL((k_decode_ragged<MODE, PREV>), dim3(lay.n_ragged), dim3(W * kWave), lds, st, lay, tab, sc, a);
+    hipLaunchKernelGGL((k_decode_ragged<MODE, PREV, TWO>), dim3(lay.n_ragged), dim3(W * kWave), lds, st, lay, tab, sc, a);
     return hipGetLastError();
 }
 
 // Two launches cover the chunk positions: the full ones and, if the layout has any, the ragged ones,
 // which go first and on the side queue, where they run beside the full ones instead of after them.
-template <DecMode MODE, bool PREV>
+template <DecMode MODE, bool PREV, bool TWO = false>
 static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st,
                               const SideQueue* side)
 {
     const bool both = lay.n_ragged != 0 && lay.n_ragged != lay.NC;
     if (!both || side == nullptr) {
-        hipError_t e = launch_ragged<MODE, PREV>(lay, tab, sc, a, st);
+        hipError_t e = launch_ragged<MODE, PREV, TWO>(lay, tab, sc, a, st);
         if (e != hipSuccess) return e;
-        return launch_full<MODE, PREV>(lay, tab, sc, a, st);
+        return launch_full<MODE, PREV, TWO>(lay, tab, sc, a, st);
     }
     hipError_t e = hipEventRecord(side->fork, st);
     if (e == hipSuccess) e = hipStreamWaitEvent(side->stream, side->fork, 0);
-    if (e == hipSuccess) e = launch_ragged<MODE, PREV>(lay, tab, sc, a, side->stream);
+    if (e == hipSuccess) e = launch_ragged<MODE, PREV, TWO>(lay, tab, sc, a, side->stream);
     if (e == hipSuccess) e = hipEventRecord(side->join, side->stream);
-    if (e == hipSuccess) e = launch_full<MODE, PREV>(lay, tab, sc, a, st);
+    if (e == hipSuccess) e = launch_full<MODE, PREV, TWO>(lay, tab, sc, a, st);
     if (e == hipSuccess) e = hipStreamWaitEvent(st, side->join, 0);
     return e;
 }
@@ -618,8 +631,9 @@ hipError_t launch_decode(DecMode mode, const Layout& lay, const Tables* tab, Sca
         case DecMode::Average: return launch_mode<DecMode::Average, false>(lay, tab, sc, a, st, side);
         case DecMode::Half0: return launch_mode<DecMode::Half0, false>(lay, tab, sc, a, st, side);
         default:
-            return a.payload_p ? launch_mode<DecMode::Half1, true>(lay, tab, sc, a, st, side)
-                               : launch_mode<DecMode::Half1, false>(lay, tab, sc, a, st, side);
+            if (a.payload_p == nullptr) return launch_mode<DecMode::Half1, false>(lay, tab, sc, a, st, side);
+            return a.tab_p ? launch_mode<DecMode::Half1, true, true>(lay, tab, sc, a, st, side)
+                           : launch_mode<DecMode::Half1, true>(lay, tab, sc, a, st, side);
     }
 }
 

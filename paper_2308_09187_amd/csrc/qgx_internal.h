@@ -118,6 +118,7 @@ struct DecodeArgs {
     // previous half-step's streams (Half1 only; payload_p null => all-zero vectors)
     const float* norms_p;  const uint32_t* chunk_off_p;  const uint16_t* sub_end_p;  const uint32_t* payload_p;
     uint64_t cap_words_p;
+    const Tables* tab_p;        // tables the previous streams were coded with, null when they are the current ones
     float* out;                 // Decode: Vhat [K][d]; Average: mean [d]; Half0: X_{t+1/2} [d]
     float* Y;                   // [d] dual state (Half0 reads, Half1 updates)
     const float* anchor;        // [d] or null

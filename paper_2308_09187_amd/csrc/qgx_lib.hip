@@ -11,13 +11,22 @@
 
 using namespace qgx;
 
+// What the host knows of one of the context's level tables (the table itself lives on the device).
+struct TableState {
+    uint32_t n_sym = 0;
+    uint32_t max_code_len = 0;      // longest code word of the code in use (without the sign bit)
+    bool levels_set = false, code_set = false;
+};
+
 struct qgx_ctx {
     qgx_config cfg{};
     std::vector<uint64_t> seg;
     int device = 0;
     Layout lay{};
     uint32_t* d_layout = nullptr;
-    Tables* d_tab = nullptr;
+    Tables* d_tabs = nullptr;        // [QGX_TABLES]
+    TableState ts[QGX_TABLES];
+    uint32_t sel = 0, sel_prev = 0;  // qgx_select_table
     Scalars* d_sc = nullptr;
     float* d_Y = nullptr;
     float* d_anchor = nullptr;
@@ -36,9 +45,7 @@ struct qgx_ctx {
     uint32_t h_groups = 0;
     uint32_t epoch = 0;
     uint32_t ticket_count = 0;
-    uint32_t n_sym = 0;
-    uint32_t max_code_len = 0;      // longest code word of the code in use (without the sign bit)
-    bool levels_set = false, code_set = false, state_ready = false, has_anchor = false;
+    bool state_ready = false, has_anchor = false;
     const uint16_t* last_sub_end = nullptr;
     uint64_t worst_words = 0;
     char err[256] = "";
@@ -76,6 +83,10 @@ uint32_t omega_length(uint32_t N)
     return len;
 }
 
+TableState& T(qgx_ctx* ctx) { return ctx->ts[ctx->sel]; }
+const TableState& T(const qgx_ctx* ctx) { return ctx->ts[ctx->sel]; }
+Tables* tab_of(const qgx_ctx* ctx) { return ctx->d_tabs + ctx->sel; }
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 qgx_status check_stream(qgx_ctx* ctx, const qgx_stream* s, const char* what)
@@ -91,23 +102,34 @@ qgx_status check_stream(qgx_ctx* ctx, const qgx_stream* s, const char* what)
     return QGX_OK;
 }
 
-// most words a full chunk can take with the code in use, multiple of 4
+// longest code word over the context's tables, so that streams of either share a slot size
+uint32_t longest_code(const qgx_ctx* ctx)
+{
+    uint32_t m = 0;
+    for (const TableState& t : ctx->ts) m = t.levels_set && t.max_code_len > m ? t.max_code_len : m;
+    return m;
+}
+
+// most words a full chunk can take with the codes in use, multiple of 4
 uint32_t chunk_slot_words(const qgx_ctx* ctx)
 {
-    const uint32_t words = (kChunk * (ctx->max_code_len + 1) + 31) / 32;
+    const uint32_t words = (kChunk * (longest_code(ctx) + 1) + 31) / 32;
     return (words + 3) / 4 * 4;
 }
 
-qgx_status need_levels(qgx_ctx* ctx)
+qgx_status need_levels(qgx_ctx* ctx, uint32_t which)
 {
-    if (!ctx->levels_set) return fail(ctx, QGX_ERR_STATE, "level table not set");
-    if (ctx->cfg.code == QGX_CODE_TABLE && !ctx->code_set) return fail(ctx, QGX_ERR_STATE, "code table not set");
+    const TableState& t = ctx->ts[which];
+    if (!t.levels_set) return fail(ctx, QGX_ERR_STATE, "level table %u not set", which);
+    if (ctx->cfg.code == QGX_CODE_TABLE && !t.code_set) return fail(ctx, QGX_ERR_STATE, "code table %u not set", which);
     return QGX_OK;
 }
 
+qgx_status need_levels(qgx_ctx* ctx) { return need_levels(ctx, ctx->sel); }
+
 void free_all(qgx_ctx* c)
 {
-    void* all[] = {c->d_layout, c->d_tab, c->d_sc, c->d_Y, c->d_anchor, c->d_scan, c->d_tickets, c->d_spartial, c->d_hpartial, c->d_hist, c->d_prob, c->d_xsum};
+    void* all[] = {c->d_layout, c->d_tabs, c->d_sc, c->d_Y, c->d_anchor, c->d_scan, c->d_tickets, c->d_spartial, c->d_hpartial, c->d_hist, c->d_prob, c->d_xsum};
     for (void* p : all) (void)hipFree(p);
     if (c->side_ok) {
         (void)hipEventDestroy(c->side.fork);
@@ -200,7 +222,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
 
     bool ok = true;
     ok = ok && hipMalloc(&c->d_layout, n_lay * sizeof(uint32_t)) == hipSuccess;
-    ok = ok && hipMalloc(&c->d_tab, sizeof(Tables)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_tabs, QGX_TABLES * sizeof(Tables)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_sc, sizeof(Scalars)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_Y, cfg->d * sizeof(float)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_anchor, cfg->d * sizeof(float)) == hipSuccess;
@@ -211,13 +233,14 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     ok = ok && hipMalloc(&c->d_hist, QGX_MAX_BINS * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_prob, kSymMax * sizeof(double)) == hipSuccess;
     ok = ok && hipMemcpy(c->d_layout, flat.data(), n_lay * sizeof(uint32_t), hipMemcpyHostToDevice) == hipSuccess;
-    ok = ok && hipMemset(c->d_tab, 0, sizeof(Tables)) == hipSuccess;
+    ok = ok && hipMemset(c->d_tabs, 0, QGX_TABLES * sizeof(Tables)) == hipSuccess;
     ok = ok && hipMemset(c->d_sc, 0, sizeof(Scalars)) == hipSuccess;
     ok = ok && hipMemset(c->d_scan, 0, (size_t)cfg->K * NB * sizeof(unsigned long long)) == hipSuccess;
     ok = ok && hipMemset(c->d_tickets, 0, (size_t)cfg->K * kTicketStride * sizeof(uint32_t)) == hipSuccess;
     if (ok) {
         const uint32_t kind = (uint32_t)cfg->code;
-        ok = hipMemcpy(&c->d_tab->code_kind, &kind, sizeof(kind), hipMemcpyHostToDevice) == hipSuccess;
+        for (int t = 0; ok && t < QGX_TABLES; ++t)
+            ok = hipMemcpy(&c->d_tabs[t].code_kind, &kind, sizeof(kind), hipMemcpyHostToDevice) == hipSuccess;
     }
     if (ok && c->lay.n_ragged != 0 && c->lay.n_ragged != NC) {      // default priority, as every stream here
         ok = hipStreamCreateWithFlags(&c->side.stream, hipStreamNonBlocking) == hipSuccess;
@@ -257,7 +280,7 @@ qgx_status qgx_stream_sizes(const qgx_ctx* ctx, uint64_t* n_buckets, uint64_t* n
 qgx_status qgx_slot_words(const qgx_ctx* ctx, uint64_t* slot_words)
 {
     if (!ctx || !slot_words) return QGX_ERR_ARG;
-    if (!ctx->levels_set || (ctx->cfg.code == QGX_CODE_TABLE && !ctx->code_set)) return QGX_ERR_STATE;
+    if (!T(ctx).levels_set || (ctx->cfg.code == QGX_CODE_TABLE && !T(ctx).code_set)) return QGX_ERR_STATE;
     *slot_words = chunk_slot_words(ctx);
     return QGX_OK;
 }
@@ -283,6 +306,16 @@ qgx_status qgx_compact(qgx_ctx* ctx, const qgx_stream* in, qgx_stream* out, void
     return QGX_OK;
 }
 
+qgx_status qgx_select_table(qgx_ctx* ctx, uint32_t table, uint32_t prev_table)
+{
+    if (!ctx) return QGX_ERR_ARG;
+    if (table >= QGX_TABLES || prev_table >= QGX_TABLES)
+        return fail(ctx, QGX_ERR_ARG, "qgx_select_table: a context has tables 0..%d", QGX_TABLES - 1);
+    ctx->sel = table;
+    ctx->sel_prev = prev_table;
+    return QGX_OK;
+}
+
 qgx_status qgx_set_levels(qgx_ctx* ctx, const float* levels_host, uint32_t n_sym, void* stream)
 {
     if (!ctx || !levels_host) return fail(ctx, QGX_ERR_ARG, "qgx_set_levels: null argument");
@@ -293,25 +326,25 @@ qgx_status qgx_set_levels(qgx_ctx* ctx, const float* levels_host, uint32_t n_sym
         if (!(levels_host[j] < levels_host[j + 1]))
             return fail(ctx, QGX_ERR_LEVELS, "level table not strictly increasing at %u", j);
     hipStream_t st = (hipStream_t)stream;
-    if (ctx->cfg.code == QGX_CODE_TABLE && ctx->code_set && n_sym != ctx->n_sym) ctx->code_set = false;
-    QGX_HIP(ctx, hipMemcpyAsync(ctx->d_tab->levels, levels_host, n_sym * sizeof(float), hipMemcpyHostToDevice, st));
-    QGX_HIP(ctx, hipMemcpyAsync(&ctx->d_tab->n_sym, &n_sym, sizeof(n_sym), hipMemcpyHostToDevice, st));
-    QGX_HIP(ctx, launch_build_tables(ctx->d_tab, st));
+    if (ctx->cfg.code == QGX_CODE_TABLE && T(ctx).code_set && n_sym != T(ctx).n_sym) T(ctx).code_set = false;
+    QGX_HIP(ctx, hipMemcpyAsync(tab_of(ctx)->levels, levels_host, n_sym * sizeof(float), hipMemcpyHostToDevice, st));
+    QGX_HIP(ctx, hipMemcpyAsync(&tab_of(ctx)->n_sym, &n_sym, sizeof(n_sym), hipMemcpyHostToDevice, st));
+    QGX_HIP(ctx, launch_build_tables(tab_of(ctx), st));
     QGX_HIP(ctx, hipStreamSynchronize(st));
-    ctx->n_sym = n_sym;
-    ctx->levels_set = true;
-    if (ctx->cfg.code == QGX_CODE_ELIAS_OMEGA) ctx->max_code_len = omega_length(n_sym);
+    T(ctx).n_sym = n_sym;
+    T(ctx).levels_set = true;
+    if (ctx->cfg.code == QGX_CODE_ELIAS_OMEGA) T(ctx).max_code_len = omega_length(n_sym);
     return QGX_OK;
 }
 
 qgx_status qgx_get_levels(qgx_ctx* ctx, float* levels_host, uint32_t* n_sym, void* stream)
 {
     if (!ctx || !levels_host || !n_sym) return fail(ctx, QGX_ERR_ARG, "qgx_get_levels: null argument");
-    if (!ctx->levels_set) return fail(ctx, QGX_ERR_STATE, "level table not set");
+    if (!T(ctx).levels_set) return fail(ctx, QGX_ERR_STATE, "level table not set");
     hipStream_t st = (hipStream_t)stream;
-    QGX_HIP(ctx, hipMemcpyAsync(levels_host, ctx->d_tab->levels, ctx->n_sym * sizeof(float), hipMemcpyDeviceToHost, st));
+    QGX_HIP(ctx, hipMemcpyAsync(levels_host, tab_of(ctx)->levels, T(ctx).n_sym * sizeof(float), hipMemcpyDeviceToHost, st));
     QGX_HIP(ctx, hipStreamSynchronize(st));
-    *n_sym = ctx->n_sym;
+    *n_sym = T(ctx).n_sym;
     return QGX_OK;
 }
 
@@ -320,7 +353,7 @@ qgx_status qgx_set_code_table(qgx_ctx* ctx, const uint8_t* code_len, const uint3
 {
     if (!ctx || !code_len || !code_bits) return fail(ctx, QGX_ERR_ARG, "qgx_set_code_table: null argument");
     if (ctx->cfg.code != QGX_CODE_TABLE) return fail(ctx, QGX_ERR_STATE, "context was not created with QGX_CODE_TABLE");
-    if (!ctx->levels_set || n_sym != ctx->n_sym)
+    if (!T(ctx).levels_set || n_sym != T(ctx).n_sym)
         return fail(ctx, QGX_ERR_STATE, "set the level table first; the code table must have as many entries");
     double kraft = 0.0;
     for (uint32_t j = 0; j < n_sym; ++j) {
@@ -337,12 +370,12 @@ qgx_status qgx_set_code_table(qgx_ctx* ctx, const uint8_t* code_len, const uint3
     uint32_t packed[kSymMax] = {0};
     for (uint32_t j = 0; j < n_sym; ++j) packed[j] = code_bits[j] | ((uint32_t)code_len[j] << 16);
     hipStream_t st = (hipStream_t)stream;
-    QGX_HIP(ctx, hipMemcpyAsync(ctx->d_tab->code, packed, sizeof(packed), hipMemcpyHostToDevice, st));
-    QGX_HIP(ctx, launch_build_tables(ctx->d_tab, st));
+    QGX_HIP(ctx, hipMemcpyAsync(tab_of(ctx)->code, packed, sizeof(packed), hipMemcpyHostToDevice, st));
+    QGX_HIP(ctx, launch_build_tables(tab_of(ctx), st));
     QGX_HIP(ctx, hipStreamSynchronize(st));
-    ctx->code_set = true;
-    ctx->max_code_len = 0;
-    for (uint32_t j = 0; j < n_sym; ++j) ctx->max_code_len = code_len[j] > ctx->max_code_len ? code_len[j] : ctx->max_code_len;
+    T(ctx).code_set = true;
+    T(ctx).max_code_len = 0;
+    for (uint32_t j = 0; j < n_sym; ++j) T(ctx).max_code_len = code_len[j] > T(ctx).max_code_len ? code_len[j] : T(ctx).max_code_len;
     return QGX_OK;
 }
 
@@ -356,11 +389,11 @@ static qgx_status run_encode(qgx_ctx* ctx, EncMode mode, const float* V, uint32_
     a.seed_lo = (uint32_t)ctx->cfg.seed; a.seed_hi = (uint32_t)(ctx->cfg.seed >> 32); a.call_id = call_id;
     a.norm_kind = ctx->cfg.norm;
     a.lev_stride = 16;
-    while (a.lev_stride < 16u * ctx->n_sym) a.lev_stride <<= 1;
+    while (a.lev_stride < 16u * T(ctx).n_sym) a.lev_stride <<= 1;
     a.sign_shift = 31;
     while ((1u << (31 - a.sign_shift)) < a.lev_stride) --a.sign_shift;
     {
-        const uint32_t words = (kChunk * (ctx->max_code_len + 1) + 31) / 32 + 4;
+        const uint32_t words = (kChunk * (T(ctx).max_code_len + 1) + 31) / 32 + 4;
         a.stage_bytes = (words + 3) / 4 * 16;
     }
     if (mode != EncMode::QuantOnly) {
@@ -382,7 +415,7 @@ static qgx_status run_encode(qgx_ctx* ctx, EncMode mode, const float* V, uint32_
     a.ticket_base = ctx->ticket_count;
     a.tickets = ctx->d_tickets;
     uint32_t groups = 0;
-    hipError_t le = launch_encode(mode, ctx->lay, ctx->d_tab, ctx->d_sc, a, (hipStream_t)stream, &groups);
+    hipError_t le = launch_encode(mode, ctx->lay, tab_of(ctx), ctx->d_sc, a, (hipStream_t)stream, &groups);
     if (le != hipSuccess) return fail(ctx, QGX_ERR_HIP, "encode launch: %s", hipGetErrorString(le));
     ctx->ticket_count += groups;
     if (mode != EncMode::QuantOnly) ctx->last_sub_end = out->sub_end;
@@ -425,7 +458,7 @@ static void fill_decode_args(const qgx_ctx* ctx, DecodeArgs& a, const qgx_stream
     a.stage_words = chunk_slot_words(ctx);
     a.stage_stride = (a.stage_words + a.stage_words / 16 + 12 + 3) / 4 * 4;
     if (a.stage_stride < 1280u) a.stage_stride = 1280u;   // the buffer also turns the output (64 rows of 20 floats)
-    a.rag_words = ((ctx->lay.max_ragged * (ctx->max_code_len + 1) + 31) / 32 + 3) / 4 * 4;
+    a.rag_words = ((ctx->lay.max_ragged * (longest_code(ctx) + 1) + 31) / 32 + 3) / 4 * 4;
     if (a.rag_words < 64u) a.rag_words = 64u;             // room for a lane's run of 32 symbols from any cursor
     a.rag_stride = (a.rag_words + a.rag_words / 16 + 12 + 3) / 4 * 4;
     a.norms = cur->norms; a.chunk_off = cur->chunk_off; a.sub_end = cur->sub_end; a.payload = cur->payload;
@@ -433,6 +466,7 @@ static void fill_decode_args(const qgx_ctx* ctx, DecodeArgs& a, const qgx_stream
     if (prev) {
         a.norms_p = prev->norms; a.chunk_off_p = prev->chunk_off; a.sub_end_p = prev->sub_end;
         a.payload_p = prev->payload; a.cap_words_p = prev->payload_words_per_worker;
+        a.tab_p = ctx->sel_prev != ctx->sel ? ctx->d_tabs + ctx->sel_prev : nullptr;
     }
 }
 
@@ -445,7 +479,7 @@ qgx_status qgx_decode(qgx_ctx* ctx, const qgx_stream* in, float* Vhat, void* str
     DecodeArgs a{};
     fill_decode_args(ctx, a, in, nullptr);
     a.out = Vhat;
-    QGX_HIP(ctx, launch_decode(DecMode::Decode, ctx->lay, ctx->d_tab, ctx->d_sc, a, (hipStream_t)stream, ctx->side_ok ? &ctx->side : nullptr));
+    QGX_HIP(ctx, launch_decode(DecMode::Decode, ctx->lay, tab_of(ctx), ctx->d_sc, a, (hipStream_t)stream, ctx->side_ok ? &ctx->side : nullptr));
     return QGX_OK;
 }
 
@@ -458,7 +492,7 @@ qgx_status qgx_decode_average(qgx_ctx* ctx, const qgx_stream* in, float* mean, v
     DecodeArgs a{};
     fill_decode_args(ctx, a, in, nullptr);
     a.out = mean;
-    QGX_HIP(ctx, launch_decode(DecMode::Average, ctx->lay, ctx->d_tab, ctx->d_sc, a, (hipStream_t)stream,
+    QGX_HIP(ctx, launch_decode(DecMode::Average, ctx->lay, tab_of(ctx), ctx->d_sc, a, (hipStream_t)stream,
                                ctx->side_ok ? &ctx->side : nullptr));
     return QGX_OK;
 }
@@ -467,8 +501,8 @@ qgx_status qgx_fit_levels(qgx_ctx* ctx, const float* V, uint32_t n_sym, uint32_t
                           double* hist_out, void* stream)
 {
     if (!ctx || !V || !aligned16(V)) return fail(ctx, QGX_ERR_ARG, "qgx_fit_levels: V null or misaligned");
-    if (!ctx->levels_set) return fail(ctx, QGX_ERR_STATE, "qgx_fit_levels starts from the current table: set one first");
-    if (n_sym != ctx->n_sym) return fail(ctx, QGX_ERR_ARG, "qgx_fit_levels: n_sym differs from the current table");
+    if (!T(ctx).levels_set) return fail(ctx, QGX_ERR_STATE, "qgx_fit_levels starts from the current table: set one first");
+    if (n_sym != T(ctx).n_sym) return fail(ctx, QGX_ERR_ARG, "qgx_fit_levels: n_sym differs from the current table");
     if (n_bins == 0 || (n_bins & 63u) || n_bins > QGX_MAX_BINS)
         return fail(ctx, QGX_ERR_ARG, "qgx_fit_levels: n_bins must be a multiple of 64, at most 4096");
     hipStream_t st = (hipStream_t)stream;
@@ -476,7 +510,7 @@ qgx_status qgx_fit_levels(qgx_ctx* ctx, const float* V, uint32_t n_sym, uint32_t
                                   ctx->d_sc, st));
     if (hist_out)
         QGX_HIP(ctx, hipMemcpyAsync(hist_out, ctx->d_hist, n_bins * sizeof(double), hipMemcpyDeviceToDevice, st));
-    QGX_HIP(ctx, launch_fit(ctx->d_tab, ctx->d_hist, n_bins, sweeps, st));
+    QGX_HIP(ctx, launch_fit(tab_of(ctx), ctx->d_hist, n_bins, sweeps, st));
     ctx->hist_bins = n_bins;
     return QGX_OK;
 }
@@ -485,25 +519,25 @@ qgx_status qgx_fit_code(qgx_ctx* ctx, double* p_host, uint8_t* code_len_host, ui
 {
     if (!ctx) return QGX_ERR_ARG;
     if (ctx->cfg.code != QGX_CODE_TABLE) return fail(ctx, QGX_ERR_STATE, "context was not created with QGX_CODE_TABLE");
-    if (!ctx->levels_set || ctx->hist_bins == 0)
+    if (!T(ctx).levels_set || ctx->hist_bins == 0)
         return fail(ctx, QGX_ERR_STATE, "qgx_fit_code needs the histogram of a qgx_fit_levels call (sweeps = 0 leaves the table as it is)");
     uint32_t need = 1;
-    while ((1u << need) < ctx->n_sym) ++need;
+    while ((1u << need) < T(ctx).n_sym) ++need;
     if (need > QGX_MAX_CODE_BITS) return fail(ctx, QGX_ERR_ARG, "too many symbols for the longest code word");
     hipStream_t st = (hipStream_t)stream;
-    QGX_HIP(ctx, launch_fit_code(ctx->d_tab, ctx->d_hist, ctx->hist_bins, QGX_MAX_CODE_BITS, ctx->d_prob, st));
+    QGX_HIP(ctx, launch_fit_code(tab_of(ctx), ctx->d_hist, ctx->hist_bins, QGX_MAX_CODE_BITS, ctx->d_prob, st));
     uint32_t packed[kSymMax];
-    QGX_HIP(ctx, hipMemcpyAsync(packed, ctx->d_tab->code, sizeof(packed), hipMemcpyDeviceToHost, st));
-    if (p_host) QGX_HIP(ctx, hipMemcpyAsync(p_host, ctx->d_prob, ctx->n_sym * sizeof(double), hipMemcpyDeviceToHost, st));
+    QGX_HIP(ctx, hipMemcpyAsync(packed, tab_of(ctx)->code, sizeof(packed), hipMemcpyDeviceToHost, st));
+    if (p_host) QGX_HIP(ctx, hipMemcpyAsync(p_host, ctx->d_prob, T(ctx).n_sym * sizeof(double), hipMemcpyDeviceToHost, st));
     QGX_HIP(ctx, hipStreamSynchronize(st));
-    ctx->max_code_len = 0;
-    for (uint32_t j = 0; j < ctx->n_sym; ++j) {
+    T(ctx).max_code_len = 0;
+    for (uint32_t j = 0; j < T(ctx).n_sym; ++j) {
         const uint32_t len = packed[j] >> 16;
-        ctx->max_code_len = len > ctx->max_code_len ? len : ctx->max_code_len;
+        T(ctx).max_code_len = len > T(ctx).max_code_len ? len : T(ctx).max_code_len;
         if (code_len_host) code_len_host[j] = (uint8_t)len;
         if (code_bits_host) code_bits_host[j] = packed[j] & 0xFFFFu;
     }
-    ctx->code_set = true;
+    T(ctx).code_set = true;
     return QGX_OK;
 }
 
@@ -524,6 +558,7 @@ qgx_status qgx_eg_step(qgx_ctx* ctx, int half, const qgx_stream* cur, const qgx_
     qgx_status s = check_stream(ctx, cur, "qgx_eg_step(cur)");
     if (s == QGX_OK && prev) s = check_stream(ctx, prev, "qgx_eg_step(prev)");
     if (s == QGX_OK) s = need_levels(ctx);
+    if (s == QGX_OK && prev) s = need_levels(ctx, ctx->sel_prev);
     if (s != QGX_OK) return s;
     if (!aligned16(X_out)) return fail(ctx, QGX_ERR_ARG, "qgx_eg_step: X_out misaligned");
     hipStream_t st = (hipStream_t)stream;
@@ -536,13 +571,13 @@ qgx_status qgx_eg_step(qgx_ctx* ctx, int half, const qgx_stream* cur, const qgx_
         fill_decode_args(ctx, a, cur, nullptr);
         a.out = X_out;
         a.x_sum = ctx->xsum_on ? ctx->d_xsum : nullptr;
-        QGX_HIP(ctx, launch_decode(DecMode::Half0, ctx->lay, ctx->d_tab, ctx->d_sc, a, st, ctx->side_ok ? &ctx->side : nullptr));
+        QGX_HIP(ctx, launch_decode(DecMode::Half0, ctx->lay, tab_of(ctx), ctx->d_sc, a, st, ctx->side_ok ? &ctx->side : nullptr));
         if (ctx->xsum_on) ctx->xsum_count += 1;
         return QGX_OK;
     }
     fill_decode_args(ctx, a, cur, prev);
     a.s_partial = ctx->d_spartial;
-    QGX_HIP(ctx, launch_decode(DecMode::Half1, ctx->lay, ctx->d_tab, ctx->d_sc, a, st, ctx->side_ok ? &ctx->side : nullptr));
+    QGX_HIP(ctx, launch_decode(DecMode::Half1, ctx->lay, tab_of(ctx), ctx->d_sc, a, st, ctx->side_ok ? &ctx->side : nullptr));
     QGX_HIP(ctx, launch_finish_half1(ctx->lay, ctx->d_sc, ctx->d_spartial, ctx->d_Y, a.anchor, X_out, st));
     return QGX_OK;
 }

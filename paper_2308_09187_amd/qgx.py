@@ -24,7 +24,7 @@ CODE_ELIAS_OMEGA, CODE_TABLE = 0, 1
 CHUNK, SUB, SUBS, MAX_SYM, MAX_BINS = 4096, 32, 128, 127, 4096
 
 EXPORTS = [
-    "qgx_create", "qgx_destroy", "qgx_stream_sizes", "qgx_slot_words", "qgx_compact", "qgx_set_levels", "qgx_get_levels", "qgx_set_code_table",
+    "qgx_create", "qgx_destroy", "qgx_stream_sizes", "qgx_slot_words", "qgx_compact", "qgx_select_table", "qgx_set_levels", "qgx_get_levels", "qgx_set_code_table",
     "qgx_quantize", "qgx_encode", "qgx_quantize_encode", "qgx_decode", "qgx_decode_average", "qgx_fit_levels", "qgx_fit_code",
     "qgx_state_init", "qgx_eg_step", "qgx_average_reset", "qgx_average_export", "qgx_get_scalars", "qgx_state_export", "qgx_state_import",
     "qgx_poll_error", "qgx_last_error",
@@ -226,6 +226,10 @@ class Context:
         self._check(self.lib.qgx_eg_step(self._h, C.c_int(half), C.byref(c), C.byref(p) if p is not None else None,
                                          _ptr(X_out), _stream_handle(stream)))
         return X_out
+
+    def select_table(self, table, prev_table=None):
+        self._check(self.lib.qgx_select_table(self._h, C.c_uint32(table),
+                                              C.c_uint32(table if prev_table is None else prev_table)))
 
     def average_reset(self, on=True, stream=None):
         self._check(self.lib.qgx_average_reset(self._h, C.c_int(1 if on else 0), _stream_handle(stream)))

@@ -591,6 +591,69 @@ def test_ragged_positions_many_workers(qgx, K):
     ctx.close()
 
 
+@pytest.mark.parametrize("fitted_code", [False, True])
+def test_two_level_tables_lockstep(qgx, fitted_code):
+    """Level sequences of their own for V_t and V_{t+1/2} (Section 3.3): table 0 (17 symbols) codes the
+    first half-step's vectors, table 1 (9 symbols) the second's; the second half-step decodes both
+    side by side.  Full and ragged chunk positions, Elias' code and fitted prefix codes."""
+    game = synth.QuadraticGame(d=3 * 4096 + 1500, K=5)
+    d, K, norm, seed, bucket = game.d, game.K, oracle.NORM_L2, 41, 4096
+    ctx = qgx.Context(d, K, bucket, norm=norm, code=qgx.CODE_TABLE if fitted_code else qgx.CODE_ELIAS_OMEGA, seed=seed)
+    lay = oracle.layout(d, bucket)
+    ctx.select_table(0); ctx.set_levels(synth.levels_exponential(16))
+    ctx.select_table(1, 0); ctx.set_levels(synth.levels_uniform(8))
+    x1 = synth.gaussian_vector(d, seed=8)
+    ctx.state_init(dev(x1))
+    st = oracle.EGState(d, K, X1=x1)
+    a, b = ctx.new_stream(), ctx.new_stream()
+    Xh = torch.empty(d, device="cuda"); Xn = torch.empty(d, device="cuda")
+    X = x1.astype(np.float32)
+    lev, code = [None, None], [(None, None), (None, None)]
+    worst = 0.0
+
+    def follow(which, V, call, stream_g):
+        """The oracle's stream and decoded vectors for what the GPU just coded with table `which`."""
+        h = stream_g.to_host()
+        _, idx, neg, _ = oracle.quantize(V, lay, norm, lev[which], seed, call, norms_in=h["norms"])
+        so = oracle.encode(idx, neg, lay, ctx.worst_words, code_len=code[which][0], code_bits=code[which][1])
+        assert_stream_equal(h, so, lay)
+        return oracle.decode(so, h["norms"], lay, lev[which], code_len=code[which][0], code_bits=code[which][1])[0]
+
+    for t in range(3):
+        V0 = game.dual_vectors(X, 2 * t)
+        ctx.select_table(0)
+        if t == 0:
+            ctx.fit_levels(dev(V0), 17, 4096, sweeps=4)
+            lev[0] = ctx.get_levels()                  # the oracle follows the GPU's tables (checked elsewhere)
+            if fitted_code:
+                code[0] = ctx.fit_code()[1:]
+        ctx.quantize_encode(dev(V0), 2 * t, a)
+        ctx.eg_step(0, a, None, Xh)
+        Vhat0 = follow(0, V0, 2 * t, a)
+        worst = max(worst, rel_err(Xh.cpu().numpy(), st.half0(Vhat0)))
+        V1 = game.dual_vectors(Xh.cpu().numpy(), 2 * t + 1)
+        ctx.select_table(1, 0)
+        if t == 0:
+            ctx.fit_levels(dev(V1), 9, 4096, sweeps=4)
+            lev[1] = ctx.get_levels()
+            assert len(lev[1]) == 9 and len(lev[0]) == 17
+            if fitted_code:
+                code[1] = ctx.fit_code()[1:]
+        ctx.quantize_encode(dev(V1), 2 * t + 1, b)
+        ctx.eg_step(1, b, a, Xn)
+        Vhat1 = follow(1, V1, 2 * t + 1, b)
+        Xn_o = st.half1(Vhat1, Vhat0)
+        sc = ctx.scalars()
+        assert abs(sc["S"] - st.S) <= REL * max(st.S, 1e-30) and abs(sc["gamma"] - st.gamma) <= REL * st.gamma
+        worst = max(worst, rel_err(Xn.cpu().numpy(), Xn_o))
+        X = Xn.cpu().numpy()
+    assert ctx.poll_error() == 0
+    assert worst <= REL
+    with pytest.raises(qgx.QgxError):
+        ctx.select_table(2)
+    ctx.close()
+
+
 def test_gan_layout_full_iteration(qgx):
     """Workload 4 at a tenth of its size: 14 segments of very different scale, per-segment buckets of
     8192 with short ones, L-infinity norm, 16 exponential levels, K = 8, both half-steps."""
