@@ -41,7 +41,7 @@ def parse_args():
     ap.add_argument("--bucket", type=int, default=16384)
     ap.add_argument("--n-sym", type=int, default=33)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-logd", type=int, default=23, help="log2 of coordinates per worker in the oracle sample")
+    ap.add_argument("--cpu-sample-logd", type=int, default=24, help="log2 of coordinates per worker in the oracle sample")
     ap.add_argument("--full-iteration", action="store_true", help="also time encode + second half-step")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of the input (known size) to calibrate rocprofv3 HBM counters")

@@ -2,7 +2,8 @@
 // bit packing through LDS, ordered placement of the chunks in the payload.
 // (Definition 1; Section 3.2; Appendix J "Encoding".)
 //
-// Work decomposition for 64-wide wavefronts: one workgroup per (worker, bucket); one wave per chunk of
+// Work decomposition for 64-wide wavefronts: one workgroup per (worker, bucket), or several per
+// bucket when it is longer than four chunks (see exchange_parts); one wave per chunk of
 // 4096 coordinates.  A wave holds its chunk in registers as 16 rows of 256 coordinates, lane L owning
 // the four consecutive coordinates 4L..4L+3 of every row, so that (a) every global load is a fully
 // coalesced 16-byte-per-lane access, (b) the bucket is read from HBM once and stays in registers
@@ -90,6 +91,54 @@ __device__ uint32_t lookback_exclusive(unsigned long long* state, uint32_t b, ui
     return excl;
 }
 
+// Buckets longer than four chunks are shared by several workgroups of four waves (parts), which a
+// compute unit holds five of at different points of their life, where one workgroup of sixteen waves
+// would have the unit to itself and leave the memory system idle while it computes and the ALUs idle
+// while it loads.  What the parts must agree on is the bucket's norm: every part publishes its
+// partial sum (or maximum) and reads the others'.  A published value is two words, each tagged with
+// the launch's epoch, so a reader knows a word is this launch's without any ordering between
+// stores.  The wait cannot deadlock: parts take their (bucket, part) from the worker's ticket
+// counter, so at most the bucket of the newest tickets is incomplete, and every other waiting
+// workgroup has all its partners running; the wait is bounded all the same.
+// Called by one whole wave; returns the parts' values combined in part order in every lane.
+__device__ double exchange_parts(unsigned long long* words /* [parts][2 phases][2] of this bucket */, uint32_t parts,
+                                 uint32_t part, uint32_t phase, double mine, bool take_max, uint32_t epoch, Scalars* sc)
+{
+    const int lane = lane_id();
+    const unsigned long long tag = (unsigned long long)epoch << 32;
+    const unsigned long long bits = (unsigned long long)__double_as_longlong(mine);
+    if (lane < 2)
+        __hip_atomic_store(&words[(part * 2u + phase) * 2u + (uint32_t)lane],
+                           tag | (lane ? (bits >> 32) : (bits & 0xFFFFFFFFull)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const bool reader = (uint32_t)lane < 2u * parts;
+    const uint32_t at = (((uint32_t)lane >> 1) * 2u + phase) * 2u + ((uint32_t)lane & 1u);
+    unsigned long long s = 0;
+    unsigned spins = 0;
+    for (;;) {
+        bool ready = true;
+        if (reader) {
+            s = __hip_atomic_load(&words[at], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ready = (uint32_t)(s >> 32) == epoch;
+        }
+        if (__all(ready)) break;
+        if (++spins > kSpinLimit) {               // never expected: see above
+            if (lane == 0) raise_error(sc, QGX_EBIT_STATE);
+            if (!ready) s = 0;
+            break;
+        }
+        __builtin_amdgcn_s_sleep(8);
+    }
+    double tot = 0.0;
+    for (uint32_t p = 0; p < parts; ++p) {
+        const uint32_t lo = (uint32_t)__shfl((int)(uint32_t)s, (int)(2u * p), kWave);
+        const uint32_t hi = (uint32_t)__shfl((int)(uint32_t)s, (int)(2u * p + 1u), kWave);
+        const double x = __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+        if (take_max) tot = (x > tot || x != x) ? x : tot;
+        else tot += x;
+    }
+    return tot;
+}
+
 struct LdsPlan {                 // where things live in the workgroup's LDS
     const float2* cell;          // cell table; an entry's second word is the LDS address of a level row
     const unsigned char* lev;    // level rows, two sign halves, lev_stride bytes apart
@@ -167,6 +216,7 @@ struct ChunkGeom {            // one wave's share of a bucket
     uint32_t clo, clen, cend; // first coordinate, length, one past the last
     int nrows;                // rows of 256 coordinates that hold data
     bool full;                // all 4096 coordinates present
+    uint32_t bparts;          // workgroups that share the bucket (groups of four chunks that hold data)
 };
 
 __device__ __forceinline__ ChunkGeom chunk_geom(const Layout& lay, uint32_t b, int w)
@@ -186,6 +236,7 @@ __device__ __forceinline__ ChunkGeom chunk_geom(const Layout& lay, uint32_t b, i
     g.cend = g.clo + g.clen;
     g.nrows = (int)((g.clen + 255u) >> 8);
     g.full = g.clen == (uint32_t)kChunk;
+    g.bparts = ((hi - lo + (uint32_t)kChunk - 1u) / (uint32_t)kChunk + 3u) >> 2;
     return g;
 }
 
@@ -229,7 +280,8 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
     unsigned char* s_lev = s_all + kCellsPad * sizeof(float2);
     uint16_t (*s_sub)[kSubs] = reinterpret_cast<uint16_t (*)[kSubs]>(s_lev + 2 * a.lev_stride);
     double* s_red = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(s_sub) + nwaves * kSubs * 2);
-    uint32_t* s_words = reinterpret_cast<uint32_t*>(s_red + 2 * nwaves);      // second set: the general-q sum
+    double* s_tot = s_red + 2 * nwaves;                                       // second set: the general-q sum
+    uint32_t* s_words = reinterpret_cast<uint32_t*>(s_tot + 2);               // bucket totals of a split bucket
     uint32_t* s_misc = s_words + (nwaves + 3) / 4 * 4;
     uint32_t* stage = reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(s_misc) + 32 + (size_t)w * a.stage_bytes);
     LdsPlan L;
@@ -244,8 +296,10 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
 
     // Compact placement: buckets by ticket (the ticket first: the table loads overlap its latency).
     // Slotted placement and plain quantisation have no order to keep: the bucket is the block's own.
+    // Split buckets: (bucket, part) by ticket as well, whatever the placement (see exchange_parts).
     const bool ordered = MODE != EncMode::QuantOnly && a.slot_words == 0u;
-    if (ordered) {
+    const bool ticketed = ordered || a.parts > 1u;
+    if (ticketed) {
         if (tid == 0) s_misc[2] = atomicAdd(a.tickets + k * kTicketStride, 1u) - a.ticket_base;
     }
     for (int i = tid; i < (int)n_sym; i += (int)blockDim.x) {
@@ -267,9 +321,21 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
     const size_t kbase = (size_t)k * lay.d;
     const bool vec_ok = (kbase & 3u) == 0;             // 16-byte aligned rows for this worker
     const float* __restrict__ Vk = (MODE != EncMode::EncodeOnly) ? a.V + kbase : nullptr;
-    const uint32_t b = ordered ? s_misc[2] : (uint32_t)blockIdx.x / lay.K;
-    if (b >= lay.NB) return;                           // cannot happen: one workgroup per bucket and worker
-    const ChunkGeom g = chunk_geom(lay, b, w);
+    const uint32_t unit = ticketed ? s_misc[2] : (uint32_t)blockIdx.x / lay.K;
+    const uint32_t b = a.parts > 1u ? unit / a.parts : unit;
+    const uint32_t part = unit - b * a.parts;
+    if (b >= lay.NB) return;                           // cannot happen: one workgroup per unit and worker
+    const ChunkGeom g = chunk_geom(lay, b, (int)part * 4 + w);
+    if (part >= g.bparts) {
+        // a short bucket has nothing for this part; no partner waits for it, but in compact placement
+        // the units after it look back over its (empty) aggregate
+        if (ordered && tid == 0)
+            __hip_atomic_store(a.scan_state + (size_t)k * lay.NB * a.parts + unit,
+                               (unsigned long long)((a.epoch << 2) | 1u) << 32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+    const bool split = a.parts > 1u && g.bparts > 1u;
+    unsigned long long* xch = a.xch + ((size_t)k * lay.NB + b) * a.parts * 4u;
     float4 v[kRows];
     if (MODE != EncMode::EncodeOnly) load_chunk(v, Vk, g, vec_ok, lane);
     {
@@ -314,6 +380,14 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                 if (a.norm_kind == QGX_NORM_L2) tot += s_red[i];
                 else tot = (s_red[i] > tot || s_red[i] != s_red[i]) ? s_red[i] : tot;
             }
+            if (split) {
+                if (w == 0) {
+                    const double t = exchange_parts(xch, g.bparts, part, 0u, tot, a.norm_kind != QGX_NORM_L2, a.epoch, sc);
+                    if (lane == 0) s_tot[0] = t;
+                }
+                __syncthreads();
+                tot = s_tot[0];
+            }
             if (a.norm_kind == QGX_NORM_L2 && !(tot >= 0x1p-60 && tot <= 0x1p100)) {
                 // squares that overflow or go subnormal in binary32 (or a non-finite input): the sum
                 // again in binary64, from memory (the rolled loop keeps the register copy intact)
@@ -325,6 +399,14 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                 __syncthreads();
                 tot = 0.0;
                 for (int i = 0; i < nwaves; ++i) tot += s_red[nwaves + i];
+                if (split) {
+                    if (w == 0) {
+                        const double t = exchange_parts(xch, g.bparts, part, 1u, tot, false, a.epoch, sc);
+                        if (lane == 0) s_tot[1] = t;
+                    }
+                    __syncthreads();
+                    tot = s_tot[1];
+                }
             }
             n = (a.norm_kind == QGX_NORM_L2) ? (float)sqrt(tot) : (float)tot;
             if (a.norm_kind != QGX_NORM_L2 && a.norm_kind != QGX_NORM_LINF && tot > 0.0 && tot <= 3.402823466e+38) {
@@ -343,6 +425,14 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                 __syncthreads();
                 double sum = 0.0;
                 for (int i = 0; i < nwaves; ++i) sum += s_red[nwaves + i];
+                if (split) {
+                    if (w == 0) {
+                        const double t = exchange_parts(xch, g.bparts, part, 1u, sum, false, a.epoch, sc);
+                        if (lane == 0) s_tot[1] = t;
+                    }
+                    __syncthreads();
+                    sum = s_tot[1];
+                }
                 n = (float)(tot * root_int(sum, q));
             }
             if (a.norms_in) {
@@ -354,7 +444,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
             if (bucket_bad) n = 0.0f;
             if (tid == 0) {
                 if (bucket_bad) raise_error(sc, QGX_EBIT_NONFINITE);
-                if (a.norms_out) a.norms_out[(size_t)k * lay.NB + b] = n;
+                if (a.norms_out && part == 0u) a.norms_out[(size_t)k * lay.NB + b] = n;
             }
         }
         const float rinv = 1.0f / n;                   // one IEEE division per bucket
@@ -451,7 +541,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                     bucket_words += s_words[i];
                 }
                 if (w == 0) {
-                    const uint32_t excl = lookback_exclusive(a.scan_state + (size_t)k * lay.NB, b, bucket_words, a.epoch, sc);
+                    const uint32_t excl = lookback_exclusive(a.scan_state + (size_t)k * lay.NB * a.parts, unit, bucket_words, a.epoch, sc);
                     if (lane == 0) s_misc[1] = excl;
                 }
                 __syncthreads();
@@ -481,7 +571,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
 static size_t encode_lds_bytes(int waves, const EncodeArgs& a, bool with_stage)
 {
     size_t n = kCellsPad * sizeof(float2) + 2 * (size_t)a.lev_stride + (size_t)waves * kSubs * 2 +
-               2 * (size_t)waves * sizeof(double) + (size_t)(waves + 3) / 4 * 4 * sizeof(uint32_t) + 32;
+               (2 * (size_t)waves + 2) * sizeof(double) + (size_t)(waves + 3) / 4 * 4 * sizeof(uint32_t) + 32;
     if (with_stage) n += (size_t)waves * a.stage_bytes;
     return n;
 }
@@ -490,7 +580,7 @@ template <EncMode MODE>
 static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a, hipStream_t st,
                               uint32_t* tickets_per_worker)
 {
-    const int waves = (int)lay.waves_per_bucket;
+    const int waves = a.parts > 1u ? 4 : (int)lay.waves_per_bucket;
     const size_t lds = encode_lds_bytes(waves, a, MODE != EncMode::QuantOnly);
     static bool attr_done = false;
     if (!attr_done) {
@@ -499,9 +589,11 @@ static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc,
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    // one workgroup per bucket; in compact placement each takes one ticket of its worker
-    *tickets_per_worker = (MODE != EncMode::QuantOnly && a.slot_words == 0u) ? lay.NB : 0u;
-    hipLaunchKernelGGL(k_encode<MODE>, dim3(lay.K * lay.NB), dim3(waves * kWave), lds, st, lay, tab, sc, a);
+    // one workgroup per bucket, or per part of a bucket; in compact placement and with split buckets
+    // each takes one ticket of its worker
+    const uint32_t units = lay.NB * a.parts;
+    *tickets_per_worker = ((MODE != EncMode::QuantOnly && a.slot_words == 0u) || a.parts > 1u) ? units : 0u;
+    hipLaunchKernelGGL(k_encode<MODE>, dim3(lay.K * units), dim3(waves * kWave), lds, st, lay, tab, sc, a);
     return hipGetLastError();
 }
 

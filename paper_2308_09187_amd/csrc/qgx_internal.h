@@ -99,7 +99,9 @@ struct EncodeArgs {
     uint16_t* sub_end;          // [K][NC][kSubs]
     uint32_t* payload;          // [K][cap]
     uint64_t cap_words;
-    unsigned long long* scan_state;  // [K][NB] look-back words
+    unsigned long long* scan_state;  // [K][NB * parts] look-back words
+    unsigned long long* xch;         // [K][NB][parts][2][2] partial norms of split buckets, epoch-tagged
+    uint32_t parts;             // workgroups per bucket: 1, or ceil(waves_per_bucket / 4) when that exceeds 4
     uint32_t* tickets;          // [K] ever-increasing bucket tickets, kTicketStride words apart
     uint32_t epoch;             // tags scan_state entries of this launch
     uint32_t ticket_base;       // value of every ticket counter before this launch

@@ -31,6 +31,8 @@ struct qgx_ctx {
     float* d_Y = nullptr;
     float* d_anchor = nullptr;
     unsigned long long* d_scan = nullptr;
+    unsigned long long* d_xch = nullptr;   // partial norms of buckets shared by several workgroups
+    uint32_t parts = 1;                    // workgroups per bucket in the encoder
     uint32_t* d_tickets = nullptr;
     double* d_spartial = nullptr;
     double* d_hpartial = nullptr;
@@ -129,7 +131,7 @@ qgx_status need_levels(qgx_ctx* ctx) { return need_levels(ctx, ctx->sel); }
 
 void free_all(qgx_ctx* c)
 {
-    void* all[] = {c->d_layout, c->d_tabs, c->d_sc, c->d_Y, c->d_anchor, c->d_scan, c->d_tickets, c->d_spartial, c->d_hpartial, c->d_hist, c->d_prob, c->d_xsum};
+    void* all[] = {c->d_layout, c->d_tabs, c->d_sc, c->d_Y, c->d_anchor, c->d_scan, c->d_xch, c->d_tickets, c->d_spartial, c->d_hpartial, c->d_hist, c->d_prob, c->d_xsum};
     for (void* p : all) (void)hipFree(p);
     if (c->side_ok) {
         (void)hipEventDestroy(c->side.fork);
@@ -226,7 +228,16 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     ok = ok && hipMalloc(&c->d_sc, sizeof(Scalars)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_Y, cfg->d * sizeof(float)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_anchor, cfg->d * sizeof(float)) == hipSuccess;
-    ok = ok && hipMalloc(&c->d_scan, (size_t)cfg->K * NB * sizeof(unsigned long long)) == hipSuccess;
+    // A bucket of more than four chunks is shared by workgroups of four waves.  Per worker, the parts
+    // of one bucket (the newest tickets) can be waiting for partners that have not started yet: up
+    // to 3 K workgroups, which must stay below what the GPU holds at once, so only for K <= 64.
+    c->parts = (c->lay.waves_per_bucket > 4u && cfg->K <= 64u) ? (c->lay.waves_per_bucket + 3u) / 4u : 1u;
+    const size_t n_units = (size_t)cfg->K * NB * c->parts;
+    ok = ok && hipMalloc(&c->d_scan, n_units * sizeof(unsigned long long)) == hipSuccess;
+    if (c->parts > 1u) {
+        ok = ok && hipMalloc(&c->d_xch, n_units * 4 * sizeof(unsigned long long)) == hipSuccess;
+        ok = ok && hipMemset(c->d_xch, 0, n_units * 4 * sizeof(unsigned long long)) == hipSuccess;
+    }
     ok = ok && hipMalloc(&c->d_tickets, (size_t)cfg->K * kTicketStride * sizeof(uint32_t)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_spartial, (size_t)NC * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_hpartial, (size_t)c->h_groups * QGX_MAX_BINS * sizeof(double)) == hipSuccess;
@@ -235,7 +246,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     ok = ok && hipMemcpy(c->d_layout, flat.data(), n_lay * sizeof(uint32_t), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemset(c->d_tabs, 0, QGX_TABLES * sizeof(Tables)) == hipSuccess;
     ok = ok && hipMemset(c->d_sc, 0, sizeof(Scalars)) == hipSuccess;
-    ok = ok && hipMemset(c->d_scan, 0, (size_t)cfg->K * NB * sizeof(unsigned long long)) == hipSuccess;
+    ok = ok && hipMemset(c->d_scan, 0, n_units * sizeof(unsigned long long)) == hipSuccess;
     ok = ok && hipMemset(c->d_tickets, 0, (size_t)cfg->K * kTicketStride * sizeof(uint32_t)) == hipSuccess;
     if (ok) {
         const uint32_t kind = (uint32_t)cfg->code;
@@ -408,10 +419,12 @@ static qgx_status run_encode(qgx_ctx* ctx, EncMode mode, const float* V, uint32_
         a.chunk_off = out->chunk_off; a.sub_end = out->sub_end; a.payload = out->payload;
         a.cap_words = out->payload_words_per_worker;
         a.scan_state = ctx->d_scan;
-        ctx->epoch = (ctx->epoch + 1u) & 0x3FFFFFFFu;
-        if (ctx->epoch == 0) ctx->epoch = 1;
-        a.epoch = ctx->epoch;
     }
+    ctx->epoch = (ctx->epoch + 1u) & 0x3FFFFFFFu;      // tags what workgroups of this launch publish to each other
+    if (ctx->epoch == 0) ctx->epoch = 1;
+    a.epoch = ctx->epoch;
+    a.parts = ctx->parts;
+    a.xch = ctx->d_xch;
     a.ticket_base = ctx->ticket_count;
     a.tickets = ctx->d_tickets;
     uint32_t groups = 0;

@@ -78,6 +78,9 @@ CASES = [
     (70000, 1, 65536, oracle.NORM_L2, "fine", None),                 # largest bucket, 127 symbols
     (3 * 4096 + 77, 2, 8192, 3, "uni16", None),                      # another q of Definition 1: ||v||_3
     (6000, 2, 4096, 1, "exp16", None),                               # and ||v||_1
+    (3 * 32768 + 5000, 3, 32768, oracle.NORM_LINF, "uni16", None),   # buckets shared by two workgroups
+    (2 * 65536 + 20000, 2, 65536, 3, "exp16", None),                 # by four, two exchanges (maximum, then powers)
+    (65536 + 40000, 2, 65536, oracle.NORM_L2, "exp16", [65536, 24576, 15424]),   # full, 6-chunk and 4-chunk buckets
 ]
 
 
@@ -247,6 +250,26 @@ def test_degenerate_inputs_and_error_word(qgx):
         c2.quantize_encode(dev(V), 0, c2.new_stream())
     assert e.value.status == qgx.ERR_STATE         # no level table yet
     c2.close()
+
+
+@pytest.mark.parametrize("scale", [1e25, 1e-30])
+def test_split_bucket_extreme_scale(qgx, scale):
+    """Squares that overflow or vanish in binary32: the bucket's sum is redone in binary64, across the
+    workgroups that share a bucket as well."""
+    d, K, bucket = 65536 + 30000, 2, 65536
+    levels = synth.levels_exponential(16)
+    ctx, lay = make_ctx(qgx, d, K, bucket, oracle.NORM_L2, levels, seed=9)
+    V = (synth.student_t3(K, d, seed=12).astype(np.float64) * 1e2 * scale).astype(np.float32)
+    assert np.isfinite(V).all() and V.any()
+    out = ctx.new_stream()
+    ctx.quantize_encode(dev(V), 3, out)
+    h = out.to_host()
+    n_o, _, _, bad = oracle.quantize(V, lay, oracle.NORM_L2, levels, 9, 3)
+    assert bad == 0 and np.max(np.abs(h["norms"] - n_o) / n_o) <= REL
+    _, _, _, st_o = oracle_stream(V, lay, oracle.NORM_L2, levels, 9, 3, h["norms"], ctx.worst_words)
+    assert_stream_equal(h, st_o, lay)
+    assert ctx.poll_error() == 0
+    ctx.close()
 
 
 def test_malformed_stream_sets_error_bit(qgx):
