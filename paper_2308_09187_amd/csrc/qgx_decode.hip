@@ -493,38 +493,65 @@ void k_decode_ragged(Layout lay, const Tables* __restrict__ tab, Scalars* sc, De
             if (pp > p_limit) { pp = p_limit; malformed = true; }
             if (ppb > p_limit) { ppb = p_limit; malformed = true; }
             const float n = cur.n, np = prv.n;
-            uint32_t win[3], e[3];
+            // Every lane parses 32 symbols per chain whatever its count (from a cursor below p_limit they
+            // stay inside the buffer, and any window finds a table entry), and what lies past its count
+            // is masked out: without branches the chains of a lane advance side by side, in groups of
+            // three symbols per window as in the kernel for the full positions.
+            float* vout = nullptr;
+            if constexpr (MODE == DecMode::Decode) vout = a.out + (size_t)k * lay.d + clo + 64u * (uint32_t)lane;
+            const uint32_t start_a = p, start_b = pb, start_pa = pp, start_pb = ppb;
+            uint32_t used_a = 0, used_b = 0, used_pa = 0, used_pb = 0;     // bits of the symbols that count
+            uint32_t win[3], e[3], win_b[3], e_b[3];
+            uint32_t win_p[3] = {0u, 0u, 0u}, e_p[3] = {0u, 0u, 0u}, win_pb[3] = {0u, 0u, 0u}, e_pb[3] = {0u, 0u, 0u};
+            Window wn = read_window(stage, p), wn_b = read_window(stage, pb);
+            Window wn_p{0u, 0u, 0u}, wn_pb{0u, 0u, 0u};
+            if constexpr (PREV) { wn_p = read_window(stage_p, pp); wn_pb = read_window(stage_p, ppb); }
 #pragma unroll
-            for (int s = 0; s < kHalf; ++s) {
+            for (int s = 0; s < kHalf; s += 3) {
+                if (s + 3 <= kHalf) { parse_group<3>(wn, s_tab, p, win, e); parse_group<3>(wn_b, s_tab, pb, win_b, e_b); }
+                else { parse_group<2>(wn, s_tab, p, win, e); parse_group<2>(wn_b, s_tab, pb, win_b, e_b); }
+                if (s + 3 < kHalf) { wn = read_window(stage, p); wn_b = read_window(stage, pb); }
+                if constexpr (PREV) {
+                    if (s + 3 <= kHalf) { parse_group<3>(wn_p, s_tab_p, pp, win_p, e_p); parse_group<3>(wn_pb, s_tab_p, ppb, win_pb, e_pb); }
+                    else { parse_group<2>(wn_p, s_tab_p, pp, win_p, e_p); parse_group<2>(wn_pb, s_tab_p, ppb, win_pb, e_pb); }
+                    if (s + 3 < kHalf) { wn_p = read_window(stage_p, pp); wn_pb = read_window(stage_p, ppb); }
+                }
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {             // the two sub-chunks in turn: two independent chains
-                    if (s < (h ? cnt_b : cnt_a)) {
-                        parse_group<1>(read_window(stage, h ? pb : p), s_tab, h ? pb : p, win, e);
-                        flags |= e[0];
-                        const float v = symbol_value<kExact>(level_of(s_tab, e[0]), win[0], e[0], n);
-                        val[h * kHalf + s] = v;
+                for (int i = 0; i < 3; ++i) {
+                    if (s + i < kHalf) {
+                        const bool ok_a = s + i < cnt_a, ok_b = s + i < cnt_b;
+                        const float v = symbol_value<kExact>(level_of(s_tab, e[i]), win[i], e[i], n);
+                        const float v_b = symbol_value<kExact>(level_of(s_tab, e_b[i]), win_b[i], e_b[i], n);
+                        if constexpr (MODE == DecMode::Decode) {
+                            if (ok_a) vout[s + i] = v;
+                            if (ok_b) vout[kHalf + s + i] = v_b;
+                        } else {
+                            val[s + i] = ok_a ? v : 0.0f;
+                            val[kHalf + s + i] = ok_b ? v_b : 0.0f;
+                        }
+                        flags |= (ok_a ? e[i] : 0u) | (ok_b ? e_b[i] : 0u);
+                        used_a += ok_a ? (e[i] & 15u) + 1u : 0u;
+                        used_b += ok_b ? (e_b[i] & 15u) + 1u : 0u;
                         if constexpr (MODE == DecMode::Half1) {
-                            float pv = 0.0f;
+                            float pv = 0.0f, pv_b = 0.0f;
                             if constexpr (PREV) {
-                                parse_group<1>(read_window(stage_p, h ? ppb : pp), s_tab_p, h ? ppb : pp, win, e);
-                                flags |= e[0];
-                                pv = symbol_value<true>(level_of(s_tab_p, e[0]), win[0], e[0], np);
+                                pv = symbol_value<true>(level_of(s_tab_p, e_p[i]), win_p[i], e_p[i], np);
+                                pv_b = symbol_value<true>(level_of(s_tab_p, e_pb[i]), win_pb[i], e_pb[i], np);
+                                flags |= (ok_a ? e_p[i] : 0u) | (ok_b ? e_pb[i] : 0u);
+                                used_pa += ok_a ? (e_p[i] & 15u) + 1u : 0u;
+                                used_pb += ok_b ? (e_pb[i] & 15u) + 1u : 0u;
                             }
-                            const double df = (double)pv - (double)v;
+                            const double df = ok_a ? (double)pv - (double)v : 0.0;
+                            const double df_b = ok_b ? (double)pv_b - (double)v_b : 0.0;
                             sdiff = fma(df, df, sdiff);
+                            sdiff = fma(df_b, df_b, sdiff);
                         }
                     }
                 }
             }
-            if (cnt > 0 && (p != cur.p_mid || pb != cur.p_end)) malformed = true;
+            if (cnt > 0 && (start_a + used_a != cur.p_mid || start_b + used_b != cur.p_end)) malformed = true;
             if constexpr (PREV) {
-                if (cnt > 0 && (pp != prv.p_mid || ppb != prv.p_end)) malformed = true;
-            }
-            if constexpr (MODE == DecMode::Decode) {
-                float* vout = a.out + (size_t)k * lay.d + clo + 64u * (uint32_t)lane;
-#pragma unroll
-                for (int s = 0; s < kLaneCoords; ++s)
-                    if (s < cnt) vout[s] = val[s];
+                if (cnt > 0 && (start_pa + used_pa != prv.p_mid || start_pb + used_pb != prv.p_end)) malformed = true;
             }
         }
         if constexpr (MODE != DecMode::Decode) {
