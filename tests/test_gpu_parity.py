@@ -81,6 +81,7 @@ CASES = [
     (3 * 32768 + 5000, 3, 32768, oracle.NORM_LINF, "uni16", None),   # buckets shared by two workgroups
     (2 * 65536 + 20000, 2, 65536, 3, "exp16", None),                 # by four, two exchanges (maximum, then powers)
     (65536 + 40000, 2, 65536, oracle.NORM_L2, "exp16", [65536, 24576, 15424]),   # full, 6-chunk and 4-chunk buckets
+    (65536 + 500, 65, 65536, oracle.NORM_L2, "exp8", None),          # many workers: one 16-wave workgroup per bucket
 ]
 
 
