@@ -100,9 +100,9 @@ __device__ __forceinline__ Window read_window(const uint32_t* stage, uint32_t p)
 // away, its top 13 bits index the table, and a symbol's last bit (the sign) reaches bit 31 by a left
 // shift of (symbol bits - 1), which is what the entry's low bits hold.  `neg` counts the used bits
 // downwards (adding ~e takes off the entry's count plus one); only its low six bits mean anything.
-template <int N>
+template <int N, bool WIDE = false>
 __device__ __forceinline__ void parse_group(const Window& w, const unsigned char* tab, uint32_t& p,
-                                            uint32_t (&win)[3], uint32_t (&e)[3])
+                                            uint32_t (&win)[3], uint32_t (&e)[3], float (&lv)[3])
 {
     const uint32_t top = __brev(__builtin_amdgcn_alignbit(w.w1, w.w0, p));    // shifts use p mod 32
     const uint32_t nxt = __brev(__builtin_amdgcn_alignbit(w.w2, w.w1, p));
@@ -110,10 +110,24 @@ __device__ __forceinline__ void parse_group(const Window& w, const unsigned char
 #pragma unroll
     for (int i = 0; i < N; ++i) {
         win[i] = i == 0 ? top : __builtin_amdgcn_alignbit(top, nxt, neg);     // (top:nxt) << used, upper word
-        e[i] = *reinterpret_cast<const uint16_t*>(tab + kTabLvalBytes + ((win[i] >> 18) & 0x3FFEu));
+        if constexpr (WIDE) {                                                 // entry and level in one look-up
+            const uint2 t = *reinterpret_cast<const uint2*>(tab + kTabLvalBytes + ((win[i] >> 18) & 0x3FF8u));
+            e[i] = t.x;
+            lv[i] = __uint_as_float(t.y);
+        } else {
+            e[i] = *reinterpret_cast<const uint16_t*>(tab + kTabLvalBytes + ((win[i] >> 18) & 0x3FFEu));
+        }
         neg += ~e[i];
     }
     p -= neg | 0xFFFFFFC0u;                                                   // minus (minus the bits used)
+}
+
+template <int N>
+__device__ __forceinline__ void parse_group(const Window& w, const unsigned char* tab, uint32_t& p,
+                                            uint32_t (&win)[3], uint32_t (&e)[3])
+{
+    float unused[3];
+    parse_group<N, false>(w, tab, p, win, e, unused);
 }
 
 __device__ __forceinline__ float level_of(const unsigned char* tab, uint32_t e)
@@ -152,12 +166,15 @@ __device__ __forceinline__ SubMeta load_meta(const uint16_t* sub_end, const floa
     return m;
 }
 
-// Level values and decode table of one Tables object into the decoder's LDS array.
+// Level values and decode table of one Tables object into the decoder's LDS array (WIDE: the table of
+// 8-byte entries, which has the same size).
+template <bool WIDE = false>
 __device__ __forceinline__ void load_tables(unsigned char* s_tab, const Tables* __restrict__ tab, int tid, int nthreads)
 {
+    static_assert(kWide * sizeof(uint2) == kDlut * sizeof(uint16_t), "the two decode tables share one LDS area");
     for (int i = tid; i < kSymMax; i += nthreads) reinterpret_cast<float*>(s_tab)[i] = tab->lval[i];
-    for (int i = tid; i < kDlut / 2; i += nthreads)
-        reinterpret_cast<uint32_t*>(s_tab + kTabLvalBytes)[i] = reinterpret_cast<const uint32_t*>(tab->dlut)[i];
+    const uint32_t* src = WIDE ? reinterpret_cast<const uint32_t*>(tab->dlutw) : reinterpret_cast<const uint32_t*>(tab->dlut);
+    for (int i = tid; i < kDlut / 2; i += nthreads) reinterpret_cast<uint32_t*>(s_tab + kTabLvalBytes)[i] = src[i];
 }
 
 // First coordinate, length and bucket of chunk position c.
@@ -179,7 +196,8 @@ __device__ __forceinline__ void chunk_geometry(const Layout& lay, uint32_t c, ui
 // LDS); the others are k_decode_ragged's.
 // PREV (Half1): the previous half-step's streams are there; without them the vectors count as zero.
 // TWO: those were coded with another level table and code (a.tab_p) than the current ones.
-template <DecMode MODE, bool PREV, bool TWO>
+// WIDE: no code word has more than kWideBits bits, so the 8-byte decode table is there (one stream).
+template <DecMode MODE, bool PREV, bool TWO, bool WIDE>
 __global__ __launch_bounds__(kDecWaves * kWave) __attribute__((amdgpu_waves_per_eu(MODE == DecMode::Half1 ? 2 : 4)))
 void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArgs a)
 {
@@ -198,8 +216,16 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
     uint32_t* stage = s_dyn + (size_t)w * kBufs * stage_stride;
     uint32_t* stage_p = stage + stage_stride;
 
-    load_tables(s_tab, tab, tid, (int)blockDim.x);
-    if constexpr (TWO) load_tables(s_tab2, a.tab_p, tid, (int)blockDim.x);
+    if constexpr (WIDE) {
+        bool ok = tab->wide_ok != 0u;
+        if constexpr (TWO) ok = ok && a.tab_p->wide_ok != 0u;
+        if (!ok) {                                        // the host chose this variant for another code
+            if (tid == 0) raise_error(sc, QGX_EBIT_STATE);
+            return;
+        }
+    }
+    load_tables<WIDE>(s_tab, tab, tid, (int)blockDim.x);
+    if constexpr (TWO) load_tables<WIDE>(s_tab2, a.tab_p, tid, (int)blockDim.x);
     // words past a chunk's end are read by the window of its last symbols: keep them defined
     for (uint32_t q = (uint32_t)lane; q < kBufs * stage_stride; q += kWave) stage[q] = 0;
     __syncthreads();
@@ -275,18 +301,20 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
             Window wn = read_window(stage, p), wn_b = read_window(stage, pb);
 #pragma unroll
             for (int s = 0; s < kHalf; s += 3) {
-                if (s + 3 <= kHalf) parse_group<3>(wn, s_tab, p, win, e);
-                else parse_group<2>(wn, s_tab, p, win, e);
-                if (s + 3 < kHalf) wn = read_window(stage, p);
-                if (s + 3 <= kHalf) parse_group<3>(wn_b, s_tab, pb, win_b, e_b);
-                else parse_group<2>(wn_b, s_tab, pb, win_b, e_b);
-                if (s + 3 < kHalf) wn_b = read_window(stage, pb);
                 float lv[3], lv_b[3];
+                if (s + 3 <= kHalf) parse_group<3, WIDE>(wn, s_tab, p, win, e, lv);
+                else parse_group<2, WIDE>(wn, s_tab, p, win, e, lv);
+                if (s + 3 < kHalf) wn = read_window(stage, p);
+                if (s + 3 <= kHalf) parse_group<3, WIDE>(wn_b, s_tab, pb, win_b, e_b, lv_b);
+                else parse_group<2, WIDE>(wn_b, s_tab, pb, win_b, e_b, lv_b);
+                if (s + 3 < kHalf) wn_b = read_window(stage, pb);
 #pragma unroll
                 for (int i = 0; i < 3; ++i) {
                     if (s + i < kHalf) {
-                        lv[i] = level_of(s_tab, e[i]);
-                        lv_b[i] = level_of(s_tab, e_b[i]);
+                        if constexpr (!WIDE) {
+                            lv[i] = level_of(s_tab, e[i]);
+                            lv_b[i] = level_of(s_tab, e_b[i]);
+                        }
                         flags |= e[i] | e_b[i];
                     }
                 }
@@ -317,26 +345,28 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
             Window wn_p = read_window(stage_p, pp), wn_pb = read_window(stage_p, ppb);
 #pragma unroll
             for (int s = 0; s < kHalf; s += 3) {
-                if (s + 3 <= kHalf) parse_group<3>(wn, s_tab, p, win, e);
-                else parse_group<2>(wn, s_tab, p, win, e);
-                if (s + 3 < kHalf) wn = read_window(stage, p);
-                if (s + 3 <= kHalf) parse_group<3>(wn_p, s_tab_p, pp, win_p, e_p);
-                else parse_group<2>(wn_p, s_tab_p, pp, win_p, e_p);
-                if (s + 3 < kHalf) wn_p = read_window(stage_p, pp);
-                if (s + 3 <= kHalf) parse_group<3>(wn_b, s_tab, pb, win_b, e_b);
-                else parse_group<2>(wn_b, s_tab, pb, win_b, e_b);
-                if (s + 3 < kHalf) wn_b = read_window(stage, pb);
-                if (s + 3 <= kHalf) parse_group<3>(wn_pb, s_tab_p, ppb, win_pb, e_pb);
-                else parse_group<2>(wn_pb, s_tab_p, ppb, win_pb, e_pb);
-                if (s + 3 < kHalf) wn_pb = read_window(stage_p, ppb);
                 float lv[3], lv_p[3], lv_b[3], lv_pb[3];
+                if (s + 3 <= kHalf) parse_group<3, WIDE>(wn, s_tab, p, win, e, lv);
+                else parse_group<2, WIDE>(wn, s_tab, p, win, e, lv);
+                if (s + 3 < kHalf) wn = read_window(stage, p);
+                if (s + 3 <= kHalf) parse_group<3, WIDE>(wn_p, s_tab_p, pp, win_p, e_p, lv_p);
+                else parse_group<2, WIDE>(wn_p, s_tab_p, pp, win_p, e_p, lv_p);
+                if (s + 3 < kHalf) wn_p = read_window(stage_p, pp);
+                if (s + 3 <= kHalf) parse_group<3, WIDE>(wn_b, s_tab, pb, win_b, e_b, lv_b);
+                else parse_group<2, WIDE>(wn_b, s_tab, pb, win_b, e_b, lv_b);
+                if (s + 3 < kHalf) wn_b = read_window(stage, pb);
+                if (s + 3 <= kHalf) parse_group<3, WIDE>(wn_pb, s_tab_p, ppb, win_pb, e_pb, lv_pb);
+                else parse_group<2, WIDE>(wn_pb, s_tab_p, ppb, win_pb, e_pb, lv_pb);
+                if (s + 3 < kHalf) wn_pb = read_window(stage_p, ppb);
 #pragma unroll
                 for (int i = 0; i < 3; ++i) {
                     if (s + i < kHalf) {
-                        lv[i] = level_of(s_tab, e[i]);
-                        lv_p[i] = level_of(s_tab_p, e_p[i]);
-                        lv_b[i] = level_of(s_tab, e_b[i]);
-                        lv_pb[i] = level_of(s_tab_p, e_pb[i]);
+                        if constexpr (!WIDE) {
+                            lv[i] = level_of(s_tab, e[i]);
+                            lv_p[i] = level_of(s_tab_p, e_p[i]);
+                            lv_b[i] = level_of(s_tab, e_b[i]);
+                            lv_pb[i] = level_of(s_tab_p, e_pb[i]);
+                        }
                         flags |= e[i] | e_p[i] | e_b[i] | e_pb[i];
                     }
                 }
@@ -594,22 +624,29 @@ void k_decode_ragged(Layout lay, const Tables* __restrict__ tab, Scalars* sc, De
     }
 }
 
-template <DecMode MODE, bool PREV, bool TWO>
-static hipError_t launch_full(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
+template <DecMode MODE, bool PREV, bool TWO, bool WIDE>
+static hipError_t launch_full_as(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
 {
     if (lay.n_ragged == lay.NC) return hipSuccess;
     const size_t lds = (size_t)kDecWaves * (PREV ? 2 : 1) * a.stage_stride * sizeof(uint32_t);
     static size_t lds_allowed = 0;                        // the limit is per kernel: raised when a launch needs more
     if (lds > lds_allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<MODE, PREV, TWO>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<MODE, PREV, TWO, WIDE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         lds_allowed = lds;
     }
     const uint64_t nwork = (MODE == DecMode::Decode) ? (uint64_t)lay.K * lay.NC : lay.NC;
     const uint32_t grid = (uint32_t)((nwork + kDecWaves - 1) / kDecWaves);
-    hipLaunchKernelGGL((k_decode<MODE, PREV, TWO>), dim3(grid), dim3(kDecWaves * kWave), lds, st, lay, tab, sc, a);
+    hipLaunchKernelGGL((k_decode<MODE, PREV, TWO, WIDE>), dim3(grid), dim3(kDecWaves * kWave), lds, st, lay, tab, sc, a);
     return hipGetLastError();
+}
+
+template <DecMode MODE, bool PREV, bool TWO>
+static hipError_t launch_full(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
+{
+    if (a.wide) return launch_full_as<MODE, PREV, TWO, true>(lay, tab, sc, a, st);
+    return launch_full_as<MODE, PREV, TWO, false>(lay, tab, sc, a, st);
 }
 
 template <DecMode MODE, bool PREV, bool TWO>

@@ -39,6 +39,13 @@ constexpr int kDlut = 1 << kDlutBits;     // 8192 entries
 // so the windows that start with one code word are neighbours: lanes that parse the same symbol read
 // the same or adjacent entries, whatever follows the word in their streams.
 constexpr uint32_t kDlutReject = 0x8000u; // no code word starts this window: flag, one bit long, symbol 0
+// When the first kWideBits bits of a code word always tell which word it is (every word at most that
+// long, or longer ones that differ from each other earlier: Elias' code up to 63 symbols), a second
+// table indexed by the next kWideBits stream bits holds the same entry together with the level value,
+// so that one 8-byte look-up per symbol replaces the entry look-up and the level look-up (same
+// footprint: 2^11 entries of 8 bytes).
+constexpr int kWideBits = 11;
+constexpr int kWide = 1 << kWideBits;
 
 // Device-resident tables: rebuilt on the device whenever the level table or the code changes.
 struct Tables {
@@ -60,6 +67,11 @@ struct Tables {
     // dlut[next 13 stream bits, first bit on top] = (bits of the symbol incl. sign - 1) | (4 * idx) << 4,
     // or kDlutReject
     uint16_t dlut[kDlut];
+    // dlutw[next 11 stream bits, first bit on top] = {the dlut entry, bits of l_idx}; wide_ok tells
+    // whether 11 bits identify every code word
+    uint2 dlutw[kWide];
+    uint32_t wide_ok;
+    uint32_t pad2_[3];
 };
 
 // Scalars of the iteration; lives in device memory, read by kernels, copied out on request.
@@ -130,6 +142,7 @@ struct DecodeArgs {
     uint32_t stage_stride;      // words of one LDS staging buffer (padded layout plus slack)
     uint32_t rag_words;         // the same two for the layout's longest chunk of fewer than 4096 coordinates
     uint32_t rag_stride;
+    uint32_t wide;              // the 8-byte decode table of the current streams' code is valid (Tables::wide_ok)
 };
 
 hipError_t launch_build_tables(Tables* tab, hipStream_t st);

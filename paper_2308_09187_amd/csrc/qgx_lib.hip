@@ -16,6 +16,7 @@ struct TableState {
     uint32_t n_sym = 0;
     uint32_t max_code_len = 0;      // longest code word of the code in use (without the sign bit)
     bool levels_set = false, code_set = false;
+    bool wide = false;              // 11 bits identify every code word: the decoders may use the 8-byte table
 };
 
 struct qgx_ctx {
@@ -88,6 +89,19 @@ uint32_t omega_length(uint32_t N)
 TableState& T(qgx_ctx* ctx) { return ctx->ts[ctx->sel]; }
 const TableState& T(const qgx_ctx* ctx) { return ctx->ts[ctx->sel]; }
 Tables* tab_of(const qgx_ctx* ctx) { return ctx->d_tabs + ctx->sel; }
+
+// Do the first kWideBits bits of a code word always tell which one it is?  packed[j] = bits | length << 16,
+// first-written bit in bit 0.  In a prefix-free code only two words that are both longer can agree there.
+bool wide_table_ok(const uint32_t* packed, uint32_t n_sym)
+{
+    const uint32_t mask = (1u << kWideBits) - 1u;
+    for (uint32_t i = 0; i < n_sym; ++i)
+        for (uint32_t j = i + 1; j < n_sym; ++j)
+            if ((packed[i] >> 16) > (uint32_t)kWideBits && (packed[j] >> 16) > (uint32_t)kWideBits &&
+                ((packed[i] ^ packed[j]) & mask) == 0u)
+                return false;
+    return true;
+}
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -344,7 +358,10 @@ qgx_status qgx_set_levels(qgx_ctx* ctx, const float* levels_host, uint32_t n_sym
     QGX_HIP(ctx, hipStreamSynchronize(st));
     T(ctx).n_sym = n_sym;
     T(ctx).levels_set = true;
-    if (ctx->cfg.code == QGX_CODE_ELIAS_OMEGA) T(ctx).max_code_len = omega_length(n_sym);
+    if (ctx->cfg.code == QGX_CODE_ELIAS_OMEGA) {
+        T(ctx).max_code_len = omega_length(n_sym);
+        T(ctx).wide = n_sym <= 63u;     // the words of 1..63 differ within their first 11 bits, those of 64 and 65 do not
+    }
     return QGX_OK;
 }
 
@@ -387,6 +404,7 @@ qgx_status qgx_set_code_table(qgx_ctx* ctx, const uint8_t* code_len, const uint3
     T(ctx).code_set = true;
     T(ctx).max_code_len = 0;
     for (uint32_t j = 0; j < n_sym; ++j) T(ctx).max_code_len = code_len[j] > T(ctx).max_code_len ? code_len[j] : T(ctx).max_code_len;
+    T(ctx).wide = wide_table_ok(packed, n_sym);
     return QGX_OK;
 }
 
@@ -474,6 +492,7 @@ static void fill_decode_args(const qgx_ctx* ctx, DecodeArgs& a, const qgx_stream
     a.rag_words = ((ctx->lay.max_ragged * (longest_code(ctx) + 1) + 31) / 32 + 3) / 4 * 4;
     if (a.rag_words < 64u) a.rag_words = 64u;             // room for a lane's run of 32 symbols from any cursor
     a.rag_stride = (a.rag_words + a.rag_words / 16 + 12 + 3) / 4 * 4;
+    a.wide = (T(ctx).wide && (!prev || ctx->ts[ctx->sel_prev].wide)) ? 1u : 0u;   // one kernel variant reads both streams
     a.norms = cur->norms; a.chunk_off = cur->chunk_off; a.sub_end = cur->sub_end; a.payload = cur->payload;
     a.cap_words = cur->payload_words_per_worker;
     if (prev) {
@@ -551,6 +570,7 @@ qgx_status qgx_fit_code(qgx_ctx* ctx, double* p_host, uint8_t* code_len_host, ui
         if (code_bits_host) code_bits_host[j] = packed[j] & 0xFFFFu;
     }
     T(ctx).code_set = true;
+    T(ctx).wide = wide_table_ok(packed, T(ctx).n_sym);
     return QGX_OK;
 }
 

@@ -1,5 +1,5 @@
 // Derived device tables: level pairs for the rounding step, the tau lookup cells, the code words of
-// Psi and the 13-bit decode table.  Rebuilt on the device whenever the level table or the code
+// Psi and the decode tables.  Rebuilt on the device whenever the level table or the code
 // changes, so that a refit never goes through the host.
 #include "qgx_device.h"
 
@@ -45,6 +45,7 @@ static __device__ void build_tables_block(Tables* tab)
         }
     }
     for (int i = tid; i < kDlut; i += nt) tab->dlut[i] = (uint16_t)kDlutReject;
+    for (int i = tid; i < kWide; i += nt) tab->dlutw[i] = make_uint2(kDlutReject, 0u);
     __syncthreads();
 
     for (int j = tid; j < kSymMax; j += nt) {
@@ -60,7 +61,7 @@ static __device__ void build_tables_block(Tables* tab)
         tab->lval[j] = l;
     }
     // cells: lower level, the level inside (if any), and whether a second one makes the cell inexact
-    if (tid == 0) tab->cell_exact = 1u;
+    if (tid == 0) { tab->cell_exact = 1u; tab->wide_ok = 1u; }
     __syncthreads();
     for (int c = tid; c < kCellsPad; c += nt) {
         uint32_t j = 0;
@@ -91,6 +92,15 @@ static __device__ void build_tables_block(Tables* tab)
         const uint32_t reps = 1u << (kDlutBits - len);
         const uint32_t entry = (j << 6) | (len - (j != 0u ? 0u : 1u));               // symbol bits - 1: sign for j != 0
         for (uint32_t s = (uint32_t)tid; s < reps; s += (uint32_t)nt) tab->dlut[first + s] = (uint16_t)entry;
+        // the same run in the 11-bit table, with the level beside the entry; a longer word takes the one
+        // slot of its first 11 bits, and the table is no use if two such words meet there
+        const uint32_t first_w = first >> (kDlutBits - kWideBits);
+        const uint32_t reps_w = len <= (uint32_t)kWideBits ? 1u << (kWideBits - len) : 1u;
+        __syncthreads();                             // the words before this one are in the table
+        if (tid == 0 && tab->dlutw[first_w].x != kDlutReject) tab->wide_ok = 0u;
+        __syncthreads();
+        for (uint32_t s = (uint32_t)tid; s < reps_w; s += (uint32_t)nt)
+            tab->dlutw[first_w + s] = make_uint2(entry, __float_as_uint(lv[j]));
     }
     __syncthreads();
 }
