@@ -43,6 +43,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-logd", type=int, default=24, help="log2 of coordinates per worker in the oracle sample")
     ap.add_argument("--full-iteration", action="store_true", help="also time encode + second half-step")
+    ap.add_argument("--rotate", action="store_true",
+                    help="alternate between two input batches and two stream buffers from step to step")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of the input (known size) to calibrate rocprofv3 HBM counters")
     ap.add_argument("--workload", choices=["t3", "gan"], default="t3",
@@ -128,6 +130,7 @@ def main():
         d = 1 << args.logd
         V = synth.student_t3_device(K, d, seed=20)
         V1 = synth.student_t3_device(K, d, seed=21) if args.full_iteration else None
+        Vr = synth.student_t3_device(K, d, seed=21) if args.rotate and not args.full_iteration else None
         ctx = qgx.Context(d, K, args.bucket, norm=qgx.NORM_L2, seed=seed, code=code_kind)
         ctx.set_levels(synth.levels_exponential(args.n_sym - 1))
         ctx.fit_levels(V, args.n_sym, 4096, sweeps=10)
@@ -142,6 +145,14 @@ def main():
     Xh = torch.empty(d, dtype=torch.float32, device="cuda")
 
     def step(i, ev=None):
+        if args.rotate and not args.full_iteration:
+            Vi, si = ((V, a), (Vr, b))[i & 1]
+            if ev: ev[0].record()
+            ctx.quantize_encode(Vi, 2 * i, si)
+            if ev: ev[1].record()
+            ctx.eg_step(0, si, None, Xh)
+            if ev: ev[2].record()
+            return
         if ev: ev[0].record()
         ctx.quantize_encode(V, 2 * i, a)
         if ev: ev[1].record()

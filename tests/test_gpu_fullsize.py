@@ -31,21 +31,25 @@ def mini_stream(h, k, c0, c1):
     return oracle.Stream(np.concatenate(parts)[None, :], off[None, :], h["sub_end"][k:k + 1, c0:c1], np.zeros(1, np.uint64))
 
 
-@pytest.mark.parametrize("K,logd,bucket,n_sym,slotted", [(8, 24, 16384, 33, True), (8, 24, 16384, 33, False),
-                                                         (16, 26, 65536, 65, True)])
-def test_full_size_sampled_against_oracle(K, logd, bucket, n_sym, slotted):
+@pytest.mark.parametrize("K,logd,bucket,n_sym,slotted,fitted_code",
+                         [(8, 24, 16384, 33, True, False), (8, 24, 16384, 33, False, False), (8, 24, 16384, 33, True, True),
+                          (16, 26, 65536, 65, True, False), (16, 24, 65536, 65, False, False)])
+def test_full_size_sampled_against_oracle(K, logd, bucket, n_sym, slotted, fitted_code):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     from paper_2308_09187_amd import qgx
     qgx.load()
     d, seed, call = 1 << logd, 2308, 6
-    print("generating", K, logd, bucket, n_sym, slotted, flush=True)
+    print("generating", K, logd, bucket, n_sym, slotted, fitted_code, flush=True)
     V = synth.student_t3_device(K, d, seed=20)
-    ctx = qgx.Context(d, K, bucket, norm=qgx.NORM_L2, seed=seed)
+    ctx = qgx.Context(d, K, bucket, norm=qgx.NORM_L2, seed=seed, code=qgx.CODE_TABLE if fitted_code else qgx.CODE_ELIAS_OMEGA)
     ctx.set_levels(synth.levels_exponential(n_sym - 1))
     ctx.fit_levels(V, n_sym, 4096, sweeps=10)
     levels = ctx.get_levels()
     assert (np.diff(levels) > 0).all()
+    # the fitted prefix code, if any, is taken from the library (its parity is checked elsewhere)
+    code_len, code_bits = ctx.fit_code()[1:] if fitted_code else (None, None)
+    longest = int(code_len.max()) if fitted_code else len(oracle.elias_omega(n_sym))
     x1 = torch.randn(d, device="cuda", generator=torch.Generator(device="cuda").manual_seed(3))
     ctx.state_init(x1)
     a = ctx.new_stream(slotted=slotted)
@@ -70,7 +74,7 @@ def test_full_size_sampled_against_oracle(K, logd, bucket, n_sym, slotted):
         np.testing.assert_array_equal(np.diff(off, axis=1), words)        # exclusive scan of chunk sizes
     assert (np.diff(h["sub_end"].astype(np.int64), axis=2) >= oracle.SUB()).all()    # >= 1 bit per coordinate
     assert (h["sub_end"][:, :, 0] >= oracle.SUB()).all()
-    assert (bits <= 4096 * (len(oracle.elias_omega(n_sym)) + 1)).all()     # longest word plus sign
+    assert (bits <= 4096 * (longest + 1)).all()                            # longest word plus sign
     assert ctx.scalars(want_bits=True)["total_bits"] == int(bits.sum())
     assert np.isfinite(h["norms"]).all() and (h["norms"] > 0).all()
 
@@ -85,7 +89,7 @@ def test_full_size_sampled_against_oracle(K, logd, bucket, n_sym, slotted):
         assert abs(h["norms"][k, b] - n_o[0, 0]) <= REL * n_o[0, 0]
         _, idx, neg, _ = oracle.quantize(vb, lay_b, oracle.NORM_L2, levels, seed, call,
                                          norms_in=h["norms"][k:k + 1, b:b + 1], k0=k, i0=b * bucket)
-        so = oracle.encode(idx, neg, lay_b, cap_words=bucket)
+        so = oracle.encode(idx, neg, lay_b, cap_words=bucket, code_len=code_len, code_bits=code_bits)
         ms = mini_stream(h, k, b * CPB, (b + 1) * CPB)
         np.testing.assert_array_equal(ms.chunk_off, so.chunk_off)
         np.testing.assert_array_equal(ms.sub_end, so.sub_end)
@@ -101,7 +105,8 @@ def test_full_size_sampled_against_oracle(K, logd, bucket, n_sym, slotted):
         dec = []
         for k in range(K):
             ms = mini_stream(h, k, c, c + 1)
-            dec.append(oracle.decode(ms, h["norms"][k:k + 1, c // CPB:c // CPB + 1], lay_c, levels)[0][0])
+            dec.append(oracle.decode(ms, h["norms"][k:k + 1, c // CPB:c // CPB + 1], lay_c, levels,
+                                     code_len=code_len, code_bits=code_bits)[0][0])
         st = oracle.EGState(4096, K, X1=x1[c * 4096:(c + 1) * 4096].cpu().numpy())
         want = st.half0(np.stack(dec))
         got = Xh[c * 4096:(c + 1) * 4096].cpu().numpy()
