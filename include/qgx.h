@@ -21,6 +21,10 @@
  *   - Errors found on the device (non-finite bucket, stream capacity, malformed stream) set bits in
  *     a device error word that qgx_poll_error returns and clears.
  *   - Determinism: the same (config, levels, V, call_id) gives a byte-identical qgx_stream.
+ *   - A context serves one caller at a time: its calls are issued from one thread, in order.  The
+ *     coding calls pass per-launch counters (tickets, an epoch) to their kernels, so a captured HIP
+ *     graph of them cannot be replayed; the second-half-step and decoding calls of a layout with
+ *     short chunks use a side queue of the library's own beside `stream`.
  *
  * Stream container (the paper fixes only the bit string {0,1}*; the container is this library's):
  *   Coordinates of one worker are cut into segments (tensors), segments into buckets of at most
@@ -41,8 +45,10 @@
  *     compact (slot_words = 0): chunk_off is the exclusive scan of the chunk sizes in chunk order, the
  *       payload has no gaps and chunk_off[k][NC] is the number of words used: the form to ship;
  *     slotted (slot_words > 0): chunk c starts at c * slot_words, slot_words = what qgx_slot_words
- *       reports; no workgroup waits for another, so coding is faster; the bits of every chunk are the
- *       same as in the compact form, and qgx_compact turns one into the other.
+ *       reports; no workgroup waits for another's output, so coding is faster; the bits of every
+ *       chunk are the same as in the compact form, and qgx_compact turns one into the other.
+ *   Buckets of more than 16384 coordinates are coded by several workgroups that exchange their
+ *   partial norms (for K <= 64; one large workgroup per bucket beyond that).
  *   A chunk's size in words is always ceil(sub_end[k][c][127] / 32) rounded up to a multiple of 4.
  */
 #ifndef QGX_H
