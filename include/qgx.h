@@ -67,6 +67,7 @@ extern "C" {
 #define QGX_MAX_SYM 127u     /* largest level table (l_0 .. l_{s+1}) */
 #define QGX_MAX_BINS 4096u
 #define QGX_MAX_CODE_BITS 13u
+#define QGX_FIT_CODE_BITS 11u  /* longest word of a code made by qgx_fit_code */
 #define QGX_TABLES 2         /* level tables (each with its code) a context holds */
 
 typedef struct qgx_ctx qgx_ctx;
@@ -198,8 +199,9 @@ qgx_status qgx_fit_levels(qgx_ctx* ctx, const float* V, uint32_t n_sym, uint32_t
  * symbols can be estimated), only with QGX_CODE_TABLE.  p_j of Proposition 1 is taken from the
  * histogram of the last qgx_fit_levels call (with sweeps = 0 that call only measures: a table whose
  * gaps are at least 2^-24 stays as it is) and the current level table; the code is the optimal prefix code for the weights
- * round(p_j 2^32), at least 1, with no word longer than QGX_MAX_CODE_BITS (Huffman's code whenever
- * that limit is slack), words numbered canonically by (length, index).  It replaces the context's
+ * round(p_j 2^32), at least 1, with no word longer than QGX_FIT_CODE_BITS (Huffman's code whenever
+ * that limit is slack; 11 bits and not the 13 a caller's table may have, so that the decoders can
+ * always take their one-look-up table), words numbered canonically by (length, index).  It replaces the context's
  * code table; the slot size of slotted streams follows its longest word (qgx_slot_words).
  * p_host HOST [n_sym] doubles, code_len_host HOST [n_sym], code_bits_host HOST [n_sym] (layout as in
  * qgx_set_code_table), each may be NULL.  Synchronises `stream`.

@@ -555,9 +555,9 @@ qgx_status qgx_fit_code(qgx_ctx* ctx, double* p_host, uint8_t* code_len_host, ui
         return fail(ctx, QGX_ERR_STATE, "qgx_fit_code needs the histogram of a qgx_fit_levels call (sweeps = 0 leaves the table as it is)");
     uint32_t need = 1;
     while ((1u << need) < T(ctx).n_sym) ++need;
-    if (need > QGX_MAX_CODE_BITS) return fail(ctx, QGX_ERR_ARG, "too many symbols for the longest code word");
+    if (need > QGX_FIT_CODE_BITS) return fail(ctx, QGX_ERR_ARG, "too many symbols for the longest code word");
     hipStream_t st = (hipStream_t)stream;
-    QGX_HIP(ctx, launch_fit_code(tab_of(ctx), ctx->d_hist, ctx->hist_bins, QGX_MAX_CODE_BITS, ctx->d_prob, st));
+    QGX_HIP(ctx, launch_fit_code(tab_of(ctx), ctx->d_hist, ctx->hist_bins, QGX_FIT_CODE_BITS, ctx->d_prob, st));
     uint32_t packed[kSymMax];
     QGX_HIP(ctx, hipMemcpyAsync(packed, tab_of(ctx)->code, sizeof(packed), hipMemcpyDeviceToHost, st));
     if (p_host) QGX_HIP(ctx, hipMemcpyAsync(p_host, ctx->d_prob, T(ctx).n_sym * sizeof(double), hipMemcpyDeviceToHost, st));
