@@ -275,11 +275,10 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
     const uint32_t n_sym = tab->n_sym;
     const uint32_t k = (uint32_t)blockIdx.x % lay.K;    // worker fixed by the block, buckets by ticket
 
-    // LDS plan: [cell][lev + / lev -][sub-chunk ends][reduction scratch][one staging buffer per wave]
+    // LDS plan: [cell][lev + / lev -][reduction scratch][one staging buffer per wave]
     float2* s_cell = reinterpret_cast<float2*>(s_all);
     unsigned char* s_lev = s_all + kCellsPad * sizeof(float2);
-    uint16_t (*s_sub)[kSubs] = reinterpret_cast<uint16_t (*)[kSubs]>(s_lev + 2 * a.lev_stride);
-    double* s_red = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(s_sub) + nwaves * kSubs * 2);
+    double* s_red = reinterpret_cast<double*>(s_lev + a.lev_bytes);
     double* s_tot = s_red + 2 * nwaves;                                       // second set: the general-q sum
     uint32_t* s_words = reinterpret_cast<uint32_t*>(s_tot + 2);               // bucket totals of a split bucket
     uint32_t* s_misc = s_words + (nwaves + 3) / 4 * 4;
@@ -336,6 +335,10 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
     }
     const bool split = a.parts > 1u && g.bparts > 1u;
     unsigned long long* xch = a.xch + ((size_t)k * lay.NB + b) * a.parts * 4u;
+    // The sub-chunk ends go straight to the table in global memory (eight lanes of a row write one
+    // 16-byte piece): staging them in LDS would cost the fifth workgroup of a compute unit.
+    uint16_t* __restrict__ sub_g =
+        MODE != EncMode::QuantOnly ? a.sub_end + ((size_t)k * lay.NC + g.c) * kSubs : nullptr;
     float4 v[kRows];
     if (MODE != EncMode::EncodeOnly) load_chunk(v, Vk, g, vec_ok, lane);
     {
@@ -470,7 +473,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                     for (int q = 0; q < 4; ++q) pk |= (idx[q] | ((__float_as_uint(xs[q]) >> 31) << 7)) << (8 * q);
                     *reinterpret_cast<uint32_t*>(a.sym_out + kbase + i0) = pk;
                 } else {
-                    row_base += pack_row(stage, &s_sub[w][8 * r], row_base, e, lane);
+                    row_base += pack_row(stage, sub_g + 8 * r, row_base, e, lane);
                 }
             }
         } else {
@@ -517,7 +520,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                         const float4 t = *reinterpret_cast<const float4*>(s_lev + idx[q] * 16u + neg[q] * a.lev_stride);
                         e[q] = (i0 + (uint32_t)q < g.cend) ? __float_as_uint(t.z) : 0u;
                     }
-                    row_base += pack_row(stage, &s_sub[w][8 * r], row_base, e, lane);
+                    row_base += pack_row(stage, sub_g + 8 * r, row_base, e, lane);
                 }
             }
         }
@@ -527,8 +530,10 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
         uint32_t words = (total_bits + 31u) >> 5;
         words = (words + (kAlignWords - 1)) & ~(uint32_t)(kAlignWords - 1);
         if (MODE != EncMode::QuantOnly) {
-            for (int j = lane; j < kSubs; j += kWave)
-                if (j >= 8 * g.nrows) s_sub[w][j] = (uint16_t)total_bits;
+            if (g.clen != 0) {
+                for (int j = lane; j < kSubs; j += kWave)
+                    if (j >= 8 * g.nrows) sub_g[j] = (uint16_t)total_bits;
+            }
             if (lane == 0 && ordered) s_words[w] = words;
         }
         if (MODE != EncMode::QuantOnly) {
@@ -554,8 +559,6 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                     a.chunk_off[(size_t)k * (lay.NC + 1) + g.c] = off;
                     if (g.c + 1 == lay.NC) a.chunk_off[(size_t)k * (lay.NC + 1) + lay.NC] = off + (ordered ? words : a.slot_words);
                 }
-                reinterpret_cast<uint32_t*>(a.sub_end + ((size_t)k * lay.NC + g.c) * kSubs)[lane] =
-                    reinterpret_cast<const uint32_t*>(s_sub[w])[lane];      // 128 entries of 16 bits
                 if ((uint64_t)off + words > a.cap_words) {
                     if (lane == 0) raise_error(sc, QGX_EBIT_CAPACITY);
                 } else {
@@ -570,7 +573,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
 
 static size_t encode_lds_bytes(int waves, const EncodeArgs& a, bool with_stage)
 {
-    size_t n = kCellsPad * sizeof(float2) + 2 * (size_t)a.lev_stride + (size_t)waves * kSubs * 2 +
+    size_t n = kCellsPad * sizeof(float2) + (size_t)a.lev_bytes +
                (2 * (size_t)waves + 2) * sizeof(double) + (size_t)(waves + 3) / 4 * 4 * sizeof(uint32_t) + 32;
     if (with_stage) n += (size_t)waves * a.stage_bytes;
     return n;

@@ -119,8 +119,9 @@ struct EncodeArgs {
     uint32_t ticket_base;       // value of every ticket counter before this launch
     uint32_t seed_lo, seed_hi, call_id;
     int norm_kind;
-    // LDS plan of the launch (bytes): [cell][lev: two sign halves lev_stride apart][sub][misc][stage x waves]
+    // LDS plan of the launch (bytes): [cell][lev: two sign halves lev_stride apart][misc][stage x waves]
     uint32_t lev_stride;        // power of two >= 16 * n_sym
+    uint32_t lev_bytes;         // lev_stride + 16 * n_sym: the second half ends with its last row
     uint32_t sign_shift;        // (bits of v) >> sign_shift puts the sign bit on lev_stride
     uint32_t stage_bytes;       // per wave, multiple of 16, covers 4096 symbols of the longest code + sign
     uint32_t slot_words;        // 0: compact placement (ordered scan); else chunk c goes to c * slot_words
