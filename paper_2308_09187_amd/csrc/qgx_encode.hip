@@ -190,8 +190,10 @@ __device__ __forceinline__ uint32_t quantize_one(float x, float rinv, uint32_t r
 }
 
 // Appends one row (four entries per lane) to the wave's staging buffer; returns the row's bit count.
-__device__ __forceinline__ uint32_t pack_row(uint32_t* stage, uint16_t* sub_row, uint32_t row_base,
-                                             const uint32_t (&e)[4], int lane)
+// sub_mine: where the lane's run of this row ends in the sub-chunk table, written by the run's last
+// lane (ends_run); both are the caller's so that they are worked out once per chunk, not per row.
+__device__ __forceinline__ uint32_t pack_row(uint32_t* stage, uint16_t* sub_mine, bool ends_run, uint32_t row_base,
+                                             const uint32_t (&e)[4])
 {
     const uint32_t l0 = e[0] >> 16, l1 = e[1] >> 16, l2 = e[2] >> 16, l3 = e[3] >> 16;
     const uint32_t c01 = (e[0] & 0xFFFFu) | ((e[1] & 0xFFFFu) << l0);     // <= 28 bits
@@ -207,7 +209,7 @@ __device__ __forceinline__ uint32_t pack_row(uint32_t* stage, uint16_t* sub_row,
     __hip_atomic_fetch_or(&stage[wi + 1], (uint32_t)(lo64 >> 32) | (uint32_t)hi64, __ATOMIC_RELAXED,
                           __HIP_MEMORY_SCOPE_WORKGROUP);
     __hip_atomic_fetch_or(&stage[wi + 2], (uint32_t)(hi64 >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    if ((lane & 7) == 7) sub_row[lane >> 3] = (uint16_t)(row_base + incl);      // a sub-chunk is eight lanes of a row
+    if (ends_run) *sub_mine = (uint16_t)(row_base + incl);                      // a sub-chunk is eight lanes of a row
     return (uint32_t)__builtin_amdgcn_readlane((int)incl, kWave - 1);
 }
 
@@ -339,6 +341,8 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
     // 16-byte piece): staging them in LDS would cost the fifth workgroup of a compute unit.
     uint16_t* __restrict__ sub_g =
         MODE != EncMode::QuantOnly ? a.sub_end + ((size_t)k * lay.NC + g.c) * kSubs : nullptr;
+    uint16_t* __restrict__ sub_mine = sub_g + (lane >> 3);
+    const bool ends_run = (lane & 7) == 7;
     float4 v[kRows];
     if (MODE != EncMode::EncodeOnly) load_chunk(v, Vk, g, vec_ok, lane);
     {
@@ -473,7 +477,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                     for (int q = 0; q < 4; ++q) pk |= (idx[q] | ((__float_as_uint(xs[q]) >> 31) << 7)) << (8 * q);
                     *reinterpret_cast<uint32_t*>(a.sym_out + kbase + i0) = pk;
                 } else {
-                    row_base += pack_row(stage, sub_g + 8 * r, row_base, e, lane);
+                    row_base += pack_row(stage, sub_mine + 8 * r, ends_run, row_base, e);
                 }
             }
         } else {
@@ -520,7 +524,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                         const float4 t = *reinterpret_cast<const float4*>(s_lev + idx[q] * 16u + neg[q] * a.lev_stride);
                         e[q] = (i0 + (uint32_t)q < g.cend) ? __float_as_uint(t.z) : 0u;
                     }
-                    row_base += pack_row(stage, sub_g + 8 * r, row_base, e, lane);
+                    row_base += pack_row(stage, sub_mine + 8 * r, ends_run, row_base, e);
                 }
             }
         }
