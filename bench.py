@@ -235,7 +235,8 @@ def main():
                      "algorithmic_bytes": enc_bytes,
                      # a plain copy of the same input on this machine, and the encoder's rate relative to it
                      "copy_gbs": copy_gbs, "frac_of_copy": achieved / copy_gbs,
-                     # the kernel is bound by the vector ALUs before HBM: time they were busy in the counter run
+                     # upper bound on the vector-ALU time of a launch from the counter run: instructions issued
+                     # per SIMD x 4 clocks (simple instructions take fewer: the ALUs are the second ceiling)
                      "valu_busy_us": _profile_number("valu_busy_us") if default_workload else None},
     }
     names = ["encode", "decode_avg_half0", "encode_2", "decode_avg_half1"][:n_ev - 1]

@@ -10,8 +10,8 @@
 // between the norm reduction and the rounding pass, (c) one Philox4x32 block (four words) serves
 // exactly the four coordinates of a lane and row.
 //
-// The kernel runs close to what the memory system gives (about 93 % of a plain copy of its input) with
-// the vector ALUs busy about 90 % of the time, so the per-coordinate path is kept to a straight
+// The kernel runs close to what the memory system gives (about 93 % of a plain copy of its input) and
+// at about two thirds of what the vector ALUs could issue, so the per-coordinate path is kept to a straight
 // line: u -> 1/16-octave cell -> (boundary level, address of the lower candidate table row) -> one
 // 16-byte LDS row holding the level, the scaled gap and the two candidate code words with the sign
 // already appended -> compare against the Philox draw -> select.  Chunks that are not full, buckets
