@@ -93,14 +93,20 @@ static __device__ void build_tables_block(Tables* tab)
         const uint32_t entry = (j << 6) | (len - (j != 0u ? 0u : 1u));               // symbol bits - 1: sign for j != 0
         for (uint32_t s = (uint32_t)tid; s < reps; s += (uint32_t)nt) tab->dlut[first + s] = (uint16_t)entry;
         // the same run in the 11-bit table, with the level beside the entry; a longer word takes the one
-        // slot of its first 11 bits, and the table is no use if two such words meet there
+        // slot of its first 11 bits (no shorter word's run reaches it: the code is prefix-free)
         const uint32_t first_w = first >> (kDlutBits - kWideBits);
         const uint32_t reps_w = len <= (uint32_t)kWideBits ? 1u << (kWideBits - len) : 1u;
-        __syncthreads();                             // the words before this one are in the table
-        if (tid == 0 && tab->dlutw[first_w].x != kDlutReject) tab->wide_ok = 0u;
-        __syncthreads();
         for (uint32_t s = (uint32_t)tid; s < reps_w; s += (uint32_t)nt)
             tab->dlutw[first_w + s] = make_uint2(entry, __float_as_uint(lv[j]));
+    }
+    __syncthreads();
+    // the 11-bit table is no use if two of the longer words met in one slot: one of them no longer finds itself
+    for (uint32_t j = (uint32_t)tid; j < n_sym; j += (uint32_t)nt) {
+        const uint32_t cw = tab->code[j];
+        const uint32_t len = cw >> 16, bits = cw & 0xFFFFu;
+        if (len <= (uint32_t)kWideBits || len > (uint32_t)kMaxCode) continue;
+        const uint32_t first_w = (__brev(bits) >> (32u - len)) >> (len - kWideBits);
+        if ((tab->dlutw[first_w].x >> 6) != j) tab->wide_ok = 0u;
     }
     __syncthreads();
 }

@@ -288,12 +288,22 @@ def test_malformed_stream_sets_error_bit(qgx):
     ctx.close()
 
 
-def test_table_code(qgx):
-    """A caller-supplied prefix code (fixed 4-bit words) through the same kernels."""
+@pytest.mark.parametrize("kind", ["fixed4", "unary"])
+def test_table_code(qgx, kind):
+    """A caller-supplied prefix code through the same kernels: fixed 4-bit words, and a unary code
+    whose three longest words (12, 13 and 13 bits) agree in their first 11 bits, so that the decoders
+    must keep to the 13-bit table."""
     d, K = 3 * 4096 + 5, 2
-    levels = synth.levels_uniform(15)               # 16 symbols
-    code_len = np.full(16, 4, np.uint8)
-    code_bits = np.array([int(format(j, "04b")[::-1], 2) for j in range(16)], np.uint32)
+    if kind == "fixed4":
+        levels = synth.levels_uniform(15)           # 16 symbols
+        code_len = np.full(16, 4, np.uint8)
+        code_bits = np.array([int(format(j, "04b")[::-1], 2) for j in range(16)], np.uint32)
+    else:
+        levels = synth.levels_uniform(13)           # 14 symbols: l - 1 ones and a zero, the last one all ones
+        code_len = np.array(list(range(1, 13)) + [13, 13], np.uint8)
+        code_bits = np.array([(1 << (l - 1)) - 1 for l in range(1, 13)] + [0xFFF, 0x1FFF], np.uint32)
+        code_len, code_bits = code_len[::-1].copy(), code_bits[::-1].copy()   # the frequent low symbols get the long words
+    n_sym = len(levels)
     ctx = qgx.Context(d, K, 8192, norm=oracle.NORM_LINF, code=qgx.CODE_TABLE, seed=5)
     ctx.set_levels(levels)
     ctx.set_code_table(code_len, code_bits)
@@ -307,8 +317,9 @@ def test_table_code(qgx):
     assert_stream_equal(h, st_o, lay)
     Vhat_o, _, _ = oracle.decode(st_o, h["norms"], lay, levels, code_len=code_len, code_bits=code_bits)
     np.testing.assert_array_equal(ctx.decode(out).cpu().numpy(), Vhat_o)
+    assert rel_err(ctx.decode_average(out).cpu().numpy(), Vhat_o.astype(np.float64).mean(axis=0)) <= REL
     with pytest.raises(qgx.QgxError):               # not prefix-free
-        ctx.set_code_table(np.array([1] + [4] * 15, np.uint8), code_bits)
+        ctx.set_code_table(np.array([1] + [4] * (n_sym - 1), np.uint8), np.arange(n_sym, dtype=np.uint32))
     assert ctx.poll_error() == 0
     ctx.close()
 
