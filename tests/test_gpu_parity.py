@@ -463,6 +463,15 @@ def test_quadratic_game_lockstep_with_refit(qgx):
     assert worst <= REL
 
 
+def test_lockstep_with_65_levels(qgx):
+    """Elias' words of 64 and 65 agree in their first 11 bits, so with 65 symbols every decoder takes the
+    13-bit table and the separate level look-up: the same iterations through those variants."""
+    game = synth.QuadraticGame(d=3 * 8192 + 2000, K=3)
+    game.x1 = lambda: np.zeros(game.d, np.float32)
+    worst, st = run_lockstep(qgx, game, synth.levels_uniform(64), oracle.NORM_L2, 8192, 4, seed=6, anchor=False, refit=2)
+    assert worst <= REL
+
+
 def test_optimistic_dual_averaging_lockstep(qgx):
     """The optimistic dual averaging case of eq. (Q-GenX): the first half-step reuses the previous
     iteration's coded feedback g_{k,t-1/2} (nothing at t = 1), so every iteration codes once; the step
@@ -626,16 +635,17 @@ def test_ragged_positions_many_workers(qgx, K):
     ctx.close()
 
 
-@pytest.mark.parametrize("fitted_code", [False, True])
-def test_two_level_tables_lockstep(qgx, fitted_code):
+@pytest.mark.parametrize("fitted_code,n0", [(False, 17), (True, 17), (False, 65)])
+def test_two_level_tables_lockstep(qgx, fitted_code, n0):
     """Level sequences of their own for V_t and V_{t+1/2} (Section 3.3): table 0 (17 symbols) codes the
     first half-step's vectors, table 1 (9 symbols) the second's; the second half-step decodes both
-    side by side.  Full and ragged chunk positions, Elias' code and fitted prefix codes."""
+    side by side.  Full and ragged chunk positions, Elias' code and fitted prefix codes; with 65 symbols
+    in table 0 the decoders cannot use the 11-bit decode table."""
     game = synth.QuadraticGame(d=3 * 4096 + 1500, K=5)
     d, K, norm, seed, bucket = game.d, game.K, oracle.NORM_L2, 41, 4096
     ctx = qgx.Context(d, K, bucket, norm=norm, code=qgx.CODE_TABLE if fitted_code else qgx.CODE_ELIAS_OMEGA, seed=seed)
     lay = oracle.layout(d, bucket)
-    ctx.select_table(0); ctx.set_levels(synth.levels_exponential(16))
+    ctx.select_table(0); ctx.set_levels(synth.levels_exponential(16) if n0 == 17 else synth.levels_uniform(n0 - 1))
     ctx.select_table(1, 0); ctx.set_levels(synth.levels_uniform(8))
     x1 = synth.gaussian_vector(d, seed=8)
     ctx.state_init(dev(x1))
@@ -658,7 +668,7 @@ def test_two_level_tables_lockstep(qgx, fitted_code):
         V0 = game.dual_vectors(X, 2 * t)
         ctx.select_table(0)
         if t == 0:
-            ctx.fit_levels(dev(V0), 17, 4096, sweeps=4)
+            ctx.fit_levels(dev(V0), n0, 4096, sweeps=4)
             lev[0] = ctx.get_levels()                  # the oracle follows the GPU's tables (checked elsewhere)
             if fitted_code:
                 code[0] = ctx.fit_code()[1:]
@@ -671,7 +681,7 @@ def test_two_level_tables_lockstep(qgx, fitted_code):
         if t == 0:
             ctx.fit_levels(dev(V1), 9, 4096, sweeps=4)
             lev[1] = ctx.get_levels()
-            assert len(lev[1]) == 9 and len(lev[0]) == 17
+            assert len(lev[1]) == 9 and len(lev[0]) == n0
             if fitted_code:
                 code[1] = ctx.fit_code()[1:]
         ctx.quantize_encode(dev(V1), 2 * t + 1, b)
