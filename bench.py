@@ -89,9 +89,29 @@ def cpu_baseline(args, levels, seed, V, code=(None, None)):
     Vhat, _, _ = oracle.decode(s, norms, lay, levels, code_len=code[0], code_bits=code[1])
     st.half0(Vhat)
     dt = time.perf_counter() - t0
-    return {"value": 4.0 * K * d / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
-            "sample": "first 2^%d coordinates of each of the %d workers, one pass quantise+encode+decode+half-step, %.2f s"
-                      % (args.cpu_sample_logd, K, dt)}
+    out = {"value": 4.0 * K * d / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+           "sample": "first 2^%d coordinates of each of the %d workers, one pass quantise+encode+decode+half-step, %.2f s"
+                     % (args.cpu_sample_logd, K, dt)}
+    # the same on one thread, on an eighth of the sample (the oracle's loops are OpenMP over workers and buckets)
+    try:
+        import ctypes
+        gomp = ctypes.CDLL("libgomp.so.1")
+        d1 = max(d // 8, args.bucket)
+        lay1 = oracle.layout(d1, args.bucket)
+        V1 = np.ascontiguousarray(V[:, :d1])
+        gomp.omp_set_num_threads(1)
+        t0 = time.perf_counter()
+        norms, idx, neg, _ = oracle.quantize(V1, lay1, oracle.NORM_L2, levels, seed, 0)
+        s = oracle.encode(idx, neg, lay1, cap_words=d1 // 2, code_len=code[0], code_bits=code[1])
+        Vhat, _, _ = oracle.decode(s, norms, lay1, levels, code_len=code[0], code_bits=code[1])
+        oracle.EGState(d1, K).half0(Vhat)
+        dt1 = time.perf_counter() - t0
+        gomp.omp_set_num_threads(threads)
+        out["single_thread"] = {"value": 4.0 * K * d1 / dt1 / 1e9, "unit": "GB/s",
+                                "sample": "first %d coordinates of each worker, %.2f s" % (d1, dt1)}
+    except OSError:
+        pass
+    return out
 
 
 def main():
