@@ -103,7 +103,7 @@ class Layout:
     bucket: int
     bucket_start: np.ndarray   # uint64 [NB+1]
     chunk_start: np.ndarray    # uint64 [NC+1]
-    chunk_bucket: np.ndarray   # uint64 [NC]
+    chunk_bucket: np.ndarray   # uint64 [NC]: bucket of the chunk's first coordinate
 
     @property
     def NB(self):
@@ -195,7 +195,8 @@ def decode(st: Stream, norms, lay: Layout, levels, code_len=None, code_bits=None
     rc = lib().orc_decode(_p(payload, C.c_uint32), C.c_uint64(cap), _p(chunk_off, C.c_uint32),
                           _p(sub_end, C.c_uint16), _p(norms, C.c_float),
                           C.c_uint32(K), C.c_uint64(lay.d), _p(lay.chunk_start, C.c_uint64),
-                          _p(lay.chunk_bucket, C.c_uint64), C.c_uint64(lay.NC), C.c_uint64(lay.NB),
+                          _p(lay.chunk_bucket, C.c_uint64), _p(lay.bucket_start, C.c_uint64),
+                          C.c_uint64(lay.NC), C.c_uint64(lay.NB),
                           _p(levels, C.c_float), C.c_uint32(len(levels)),
                           _p(code_len, C.c_uint8), _p(code_bits, C.c_uint32),
                           _p(Vhat, C.c_float), _p(idx, C.c_uint8), _p(neg, C.c_uint8))

@@ -91,9 +91,20 @@ float orc_uniform24(uint64_t seed, uint32_t k, uint32_t call_id, uint64_t i)
 
 /* ------------------------------------------------------------------------ */
 /* Layout: segments (tensors) are cut into buckets of at most `bucket`       */
-/* coordinates (the last bucket of a segment may be short); every bucket is  */
-/* cut into chunks of at most ORC_CH coordinates.                            */
+/* coordinates (the last bucket of a segment may be short).  Chunks, the     */
+/* container's unit, hold at most ORC_CH coordinates: every bucket is cut    */
+/* into chunks of its own, except that buckets of 256, 512, 1024 or 2048     */
+/* coordinates share chunks: there a segment is cut into runs of ORC_CH      */
+/* coordinates, each holding whole buckets (the paper's experiment uses      */
+/* buckets of 1024; a chunk per bucket would leave three quarters of every   */
+/* chunk's tables empty).  chunk_bucket[c] is the bucket of the chunk's      */
+/* first coordinate.                                                         */
 /* ------------------------------------------------------------------------ */
+static int orc_shared_chunks(uint32_t bucket)
+{
+    return bucket == 256 || bucket == 512 || bucket == 1024 || bucket == 2048;
+}
+
 void orc_layout_counts(uint64_t d, uint32_t bucket, uint32_t n_seg, const uint64_t* seg_len,
                        uint64_t* n_buckets, uint64_t* n_chunks)
 {
@@ -101,10 +112,11 @@ void orc_layout_counts(uint64_t d, uint32_t bucket, uint32_t n_seg, const uint64
     if (seg_len == NULL) { seg_len = &one; n_seg = 1; }
     for (uint32_t s = 0; s < n_seg; ++s) {
         uint64_t left = seg_len[s];
+        if (orc_shared_chunks(bucket)) nc += (left + ORC_CH - 1) / ORC_CH;
         while (left > 0) {
             uint64_t len = left < bucket ? left : bucket;
             nb += 1;
-            nc += (len + ORC_CH - 1) / ORC_CH;
+            if (!orc_shared_chunks(bucket)) nc += (len + ORC_CH - 1) / ORC_CH;
             left -= len;
         }
     }
@@ -119,13 +131,22 @@ void orc_layout_fill(uint64_t d, uint32_t bucket, uint32_t n_seg, const uint64_t
     if (seg_len == NULL) { seg_len = &one; n_seg = 1; }
     for (uint32_t s = 0; s < n_seg; ++s) {
         uint64_t left = seg_len[s];
+        if (orc_shared_chunks(bucket)) {
+            for (uint64_t o = 0; o < left; o += ORC_CH) {
+                chunk_start[nc] = pos + o;
+                chunk_bucket[nc] = nb + o / bucket;
+                nc += 1;
+            }
+        }
         while (left > 0) {
             uint64_t len = left < bucket ? left : bucket;
             bucket_start[nb] = pos;
-            for (uint64_t o = 0; o < len; o += ORC_CH) {
-                chunk_start[nc] = pos + o;
-                chunk_bucket[nc] = nb;
-                nc += 1;
+            if (!orc_shared_chunks(bucket)) {
+                for (uint64_t o = 0; o < len; o += ORC_CH) {
+                    chunk_start[nc] = pos + o;
+                    chunk_bucket[nc] = nb;
+                    nc += 1;
+                }
             }
             nb += 1;
             pos += len;
@@ -392,7 +413,7 @@ static int read_symbol(const uint32_t* words, uint64_t* pos, uint64_t end,
 int orc_decode(const uint32_t* payload, uint64_t cap_words, const uint32_t* chunk_off,
                const uint16_t* sub_end, const float* norms,
                uint32_t K, uint64_t d, const uint64_t* chunk_start, const uint64_t* chunk_bucket,
-               uint64_t NC, uint64_t NB, const float* levels, uint32_t n_sym,
+               const uint64_t* bucket_start, uint64_t NC, uint64_t NB, const float* levels, uint32_t n_sym,
                const uint8_t* code_len, const uint32_t* code_bits,
                float* Vhat, uint8_t* idx_out, uint8_t* neg_out)
 {
@@ -405,11 +426,13 @@ int orc_decode(const uint32_t* payload, uint64_t cap_words, const uint32_t* chun
             const uint64_t base = (uint64_t)chunk_off[(uint64_t)k * (NC + 1) + c] * 32;
             const uint64_t end = (uint64_t)chunk_off[(uint64_t)k * (NC + 1) + c + 1] * 32;
             const uint16_t* se = sub_end + ((uint64_t)k * NC + c) * ORC_SUBS;
-            const float n = norms[(uint64_t)k * NB + chunk_bucket[c]];
+            uint64_t b = chunk_bucket[c];                 /* bucket of coordinate i: a chunk may hold several */
             uint64_t pos = base;
             int bad = 0;
             for (uint64_t i = lo; i < hi && !bad; ++i) {
                 uint32_t sym = 0, sg = 0;
+                while (i >= bucket_start[b + 1]) ++b;
+                const float n = norms[(uint64_t)k * NB + b];
                 if (read_symbol(words, &pos, end, code_len, code_bits, n_sym, &sym)) { bad = 1; break; }
                 if (sym != 0) {
                     if (pos >= end) { bad = 1; break; }

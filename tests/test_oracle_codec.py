@@ -60,10 +60,13 @@ def _container_bits(st, k, c):
     return "".join(str((int(w[(base + p) >> 5]) >> ((base + p) & 31)) & 1) for p in range(nbits))
 
 
-@pytest.mark.parametrize("kind", ["random", "zeros", "max", "alternating", "ramp"])
-def test_round_trip_and_strip_padding_invariant(kind):
+@pytest.mark.parametrize("kind,bucket", [("random", 8192), ("zeros", 8192), ("max", 8192), ("alternating", 8192), ("ramp", 8192),
+                                         ("random", 1024), ("ramp", 256)])
+def test_round_trip_and_strip_padding_invariant(kind, bucket):
     K, n_sym = 3, 33
-    lay = oracle.layout(2 * 4096 + 777, 8192)              # chunks 4096, 4096, 777: ragged tail
+    # chunks of 4096, 4096 and 777 coordinates (ragged tail); with small buckets a chunk holds several of them
+    lay = oracle.layout(2 * 4096 + 777, bucket)
+    assert lay.NC == 3 and lay.NB == -(-lay.d // bucket)
     d = lay.d
     rng = np.random.default_rng(5)
     if kind == "random":
@@ -85,8 +88,7 @@ def test_round_trip_and_strip_padding_invariant(kind):
     np.testing.assert_array_equal(neg2[idx != 0], neg[idx != 0])
     assert not neg2[idx == 0].any()
     # vhat = +-(norm * level), one binary32 product
-    nb = norms[:, lay.chunk_bucket.astype(int)]
-    per_coord_norm = np.repeat(nb, np.diff(lay.chunk_start).astype(int), axis=1)
+    per_coord_norm = np.repeat(norms, np.diff(lay.bucket_start).astype(int), axis=1)
     want = per_coord_norm * levels[idx] * np.where((neg == 1) & (idx != 0), np.float32(-1), np.float32(1))
     np.testing.assert_array_equal(Vhat, want.astype(np.float32))
     # container minus padding == the paper's plain symbol stream, chunk by chunk

@@ -207,6 +207,13 @@ def test_layout_chunks():
     assert lay.NB == 2 and lay.NC == 4
     assert lay.chunk_start.tolist() == [0, CH, 2 * CH, 3 * CH, 3 * CH + 100]
     assert lay.chunk_bucket.tolist() == [0, 0, 1, 1]
+    # buckets of 256..2048 share chunks: a segment is cut into runs of CH coordinates holding whole buckets
+    lay = oracle.layout(2 * CH + 1500, 1024, [CH + 1024, CH + 476])
+    assert lay.bucket_start.tolist() == [0, 1024, 2048, 3072, 4096, 5120, 6144, 7168, 8192, 9216, 9692]
+    assert lay.chunk_start.tolist() == [0, CH, CH + 1024, 2 * CH + 1024, 2 * CH + 1500]
+    assert lay.chunk_bucket.tolist() == [0, 4, 5, 9]
+    lay = oracle.layout(3000, 1000)                    # other small sizes keep a chunk per bucket
+    assert lay.chunk_start.tolist() == [0, 1000, 2000, 3000] and lay.chunk_bucket.tolist() == [0, 1, 2]
     lay = oracle.layout(int(synth.GAN_SEGMENTS.sum()), 8192, synth.GAN_SEGMENTS)
     assert lay.d == 9855936 and lay.NB == 1207
     short = np.diff(lay.bucket_start.astype(np.int64))
