@@ -29,7 +29,9 @@
  * Stream container (the paper fixes only the bit string {0,1}*; the container is this library's):
  *   Coordinates of one worker are cut into segments (tensors), segments into buckets of at most
  *   `bucket` coordinates (own norm each; the last bucket of a segment may be short), buckets into
- *   chunks of at most QGX_CHUNK coordinates.  A chunk's bits are: for every coordinate in index
+ *   chunks of at most QGX_CHUNK coordinates; buckets of 256, 512, 1024 or 2048 coordinates share
+ *   chunks instead (a segment is cut into runs of QGX_CHUNK coordinates, each holding whole buckets),
+ *   so that a chunk's tables and the kernels' lanes are not left mostly empty.  A chunk's bits are: for every coordinate in index
  *   order the code word Psi(idx), first-written bit first, then one sign bit (1 = negative) iff
  *   idx != 0.  Stream bit p of a chunk lives in 32-bit word p>>5, bit p&31.  Every chunk starts at
  *   a multiple of 4 words; pad bits are 0.

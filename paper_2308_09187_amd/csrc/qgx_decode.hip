@@ -162,7 +162,8 @@ __device__ __forceinline__ SubMeta load_meta(const uint16_t* sub_end, const floa
     m.p_end = se[2 * lane + 1];
     m.p_mid = se[2 * lane];
     m.p0 = lane ? (uint32_t)se[2 * lane - 1] : 0u;
-    m.n = norms[(size_t)k * lay.NB + bkt];
+    // the lane's 64 coordinates lie in one bucket: the chunk's own, or with shared chunks one further on
+    m.n = norms[(size_t)k * lay.NB + bkt + (((uint32_t)lane * (uint32_t)kLaneCoords) >> lay.bucket_shift)];
     return m;
 }
 

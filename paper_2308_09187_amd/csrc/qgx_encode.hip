@@ -264,11 +264,93 @@ __device__ __forceinline__ void load_chunk(float4 (&v)[kRows], const float* __re
     }
 }
 
+// Shared chunks (buckets of 256..2048 coordinates): a wave's chunk holds up to 16 buckets, each a run
+// of whole rows, so the wave works out their norms by itself, one wave reduction at the last row of
+// every bucket, and leaves 1 / norm (0 for a bucket that is all zero or rejected) in LDS for the
+// rounding pass.  Returns whether the straight-line rounding path applies to the whole chunk: every
+// bucket live and no coordinate above its norm.
+template <EncMode MODE>
+__device__ __forceinline__ bool shared_chunk_norms(const float4 (&v)[kRows], const float* __restrict__ Vk,
+                                                   const ChunkGeom& g, const Layout& lay, const EncodeArgs& a,
+                                                   Scalars* sc, uint32_t k, uint32_t bucket0, float* rinv_out, int lane)
+{
+    const uint32_t bshift = lay.bucket_shift, rshift = bshift - 8u;
+    const uint32_t rows_mask = (1u << rshift) - 1u;
+    const bool l2 = a.norm_kind == QGX_NORM_L2;
+    bool plain = true;
+    float p0 = 0.0f, p1 = 0.0f, p2 = 0.0f, p3 = 0.0f;
+    uint32_t mx = 0;
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        if (l2) {
+            p0 = fmaf(v[r].x, v[r].x, p0);
+            p1 = fmaf(v[r].y, v[r].y, p1);
+            p2 = fmaf(v[r].z, v[r].z, p2);
+            p3 = fmaf(v[r].w, v[r].w, p3);
+        } else {
+            mx = max(mx, __float_as_uint(v[r].x) & 0x7FFFFFFFu);
+            mx = max(mx, __float_as_uint(v[r].y) & 0x7FFFFFFFu);
+            mx = max(mx, __float_as_uint(v[r].z) & 0x7FFFFFFFu);
+            mx = max(mx, __float_as_uint(v[r].w) & 0x7FFFFFFFu);
+        }
+        if ((((uint32_t)r + 1u) & rows_mask) != 0u) continue;             // wave-uniform: the bucket goes on
+        const uint32_t gb = (uint32_t)r >> rshift;
+        const uint32_t lo = g.clo + (gb << bshift);
+        if (lo < g.cend) {
+            const uint32_t hi = min(lo + (1u << bshift), g.cend);
+            double tot;
+            if (l2) {
+                tot = wave_sum(((double)p0 + (double)p1) + ((double)p2 + (double)p3));
+                if (!(tot >= 0x1p-60 && tot <= 0x1p100)) {                // as in the kernel: redo in binary64
+                    double acc = 0.0;
+#pragma unroll 1
+                    for (uint32_t i = lo + (uint32_t)lane; i < hi; i += kWave) acc = fma((double)Vk[i], (double)Vk[i], acc);
+                    tot = wave_sum(acc);
+                }
+            } else {
+                uint32_t m = mx;
+#pragma unroll
+                for (int off = kWave / 2; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off, kWave));
+                tot = (double)__uint_as_float(m);
+            }
+            float n = l2 ? (float)sqrt(tot) : (float)tot;
+            if (!l2 && a.norm_kind != QGX_NORM_LINF && tot > 0.0 && tot <= 3.402823466e+38) {
+                const double inv_m = 1.0 / tot;
+                double acc = 0.0;
+#pragma unroll 1
+                for (uint32_t i = lo + (uint32_t)lane; i < hi; i += kWave)
+                    acc += pow_int(fabs((double)Vk[i]) * inv_m, (uint32_t)a.norm_kind);
+                n = (float)(tot * root_int(wave_sum(acc), (uint32_t)a.norm_kind));
+            }
+            bool u_le_1 = true;
+            if (a.norms_in) {
+                const float forced = a.norms_in[(size_t)k * lay.NB + bucket0 + gb];
+                u_le_1 = forced >= n;
+                n = (n == n && fabsf(n) <= 3.402823466e+38f) ? forced : n;
+            }
+            const bool bucket_bad = !(fabsf(n) <= 3.402823466e+38f);
+            if (bucket_bad) n = 0.0f;
+            const bool live = n > 0.0f;
+            if (lane == 0) {
+                if (bucket_bad) raise_error(sc, QGX_EBIT_NONFINITE);
+                if (a.norms_out) a.norms_out[(size_t)k * lay.NB + bucket0 + gb] = n;
+                rinv_out[gb] = live ? 1.0f / n : 0.0f;                    // one IEEE division per bucket
+            }
+            plain = plain && live && u_le_1;
+        }
+        p0 = p1 = p2 = p3 = 0.0f;
+        mx = 0;
+    }
+    return plain;
+}
+
 // One workgroup per (worker, bucket).  Workgroups are short-lived on purpose: with five of them per
 // compute unit at different points of their life, the load, ticket and look-back latencies of one
 // overlap the arithmetic of the others (a persistent, lock-stepped variant measured slower).
-template <EncMode MODE>
-__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5)))
+// GROUPED: the layout has shared chunks; a workgroup is four waves with a chunk each, and every wave
+// finds the norms of its chunk's buckets by itself.
+template <EncMode MODE, bool GROUPED>
+__global__ __launch_bounds__(GROUPED ? 256 : 1024) __attribute__((amdgpu_waves_per_eu(5)))
 void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArgs a)
 {
     extern __shared__ __align__(16) unsigned char s_all[];
@@ -284,7 +366,9 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
     double* s_tot = s_red + 2 * nwaves;                                       // second set: the general-q sum
     uint32_t* s_words = reinterpret_cast<uint32_t*>(s_tot + 2);               // bucket totals of a split bucket
     uint32_t* s_misc = s_words + (nwaves + 3) / 4 * 4;
-    uint32_t* stage = reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(s_misc) + 32 + (size_t)w * a.stage_bytes);
+    float* s_rinv = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(s_misc) + 32);      // GROUPED: [waves][16]
+    uint32_t* stage = reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(s_misc) + 32 +
+                                                  (GROUPED ? (size_t)nwaves * 64 : 0) + (size_t)w * a.stage_bytes);
     LdsPlan L;
     L.cell = s_cell; L.lev = s_lev; L.lev_stride = a.lev_stride; L.sign_shift = a.sign_shift;
     L.lev_addr = lds_address(s_lev);
@@ -323,10 +407,24 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
     const bool vec_ok = (kbase & 3u) == 0;             // 16-byte aligned rows for this worker
     const float* __restrict__ Vk = (MODE != EncMode::EncodeOnly) ? a.V + kbase : nullptr;
     const uint32_t unit = ticketed ? s_misc[2] : (uint32_t)blockIdx.x / lay.K;
-    const uint32_t b = a.parts > 1u ? unit / a.parts : unit;
-    const uint32_t part = unit - b * a.parts;
-    if (b >= lay.NB) return;                           // cannot happen: one workgroup per unit and worker
-    const ChunkGeom g = chunk_geom(lay, b, (int)part * 4 + w);
+    uint32_t b = a.parts > 1u ? unit / a.parts : unit;  // the bucket; with shared chunks the first of the wave's chunk
+    const uint32_t part = GROUPED ? 0u : unit - b * a.parts;
+    ChunkGeom g;
+    if constexpr (GROUPED) {
+        if (unit * 4u >= lay.NC) return;               // cannot happen: one workgroup per four chunks and worker
+        g.c = unit * 4u + (uint32_t)w;
+        const bool there = g.c < lay.NC;
+        g.clo = there ? lay.chunk_start[g.c] : 0u;
+        g.clen = there ? lay.chunk_start[g.c + 1] - g.clo : 0u;
+        g.cend = g.clo + g.clen;
+        g.nrows = (int)((g.clen + 255u) >> 8);
+        g.full = g.clen == (uint32_t)kChunk;
+        g.bparts = 1u;
+        b = there ? lay.chunk_bucket[g.c] : 0u;
+    } else {
+        if (b >= lay.NB) return;                       // cannot happen: one workgroup per unit and worker
+        g = chunk_geom(lay, b, (int)part * 4 + w);
+    }
     if (part >= g.bparts) {
         // a short bucket has nothing for this part; no partner waits for it, but in compact placement
         // the units after it look back over its (empty) aggregate
@@ -350,7 +448,11 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
         // ---- norm of the bucket from the rows in registers ---------------------------------------
         float n = 0.0f;
         bool u_le_1 = true;
-        if (MODE != EncMode::EncodeOnly) {
+        bool plain = true;                             // GROUPED: every bucket of the chunk live, no u above 1
+        if constexpr (GROUPED) {
+            if (MODE != EncMode::EncodeOnly && g.clen != 0u)
+                plain = shared_chunk_norms<MODE>(v, Vk, g, lay, a, sc, k, b, s_rinv + w * 16, lane);
+        } else if (MODE != EncMode::EncodeOnly) {
             // A non-finite coordinate shows in the reduced value itself (a sum of squares with a NaN
             // or an infinity in it, a maximum taken on magnitude bits).
             double red;
@@ -454,9 +556,10 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                 if (a.norms_out && part == 0u) a.norms_out[(size_t)k * lay.NB + b] = n;
             }
         }
-        const float rinv = 1.0f / n;                   // one IEEE division per bucket
-        const bool live = n > 0.0f;
+        const float rinv = GROUPED ? 0.0f : 1.0f / n;  // one IEEE division per bucket
+        const bool live = GROUPED ? plain : n > 0.0f;
         const bool fast = g.full && live && vec_ok && u_le_1 && (cell_exact != 0u) && MODE != EncMode::EncodeOnly;
+        const uint32_t rshift = GROUPED ? lay.bucket_shift - 8u : 0u;         // rows per bucket, as a shift
 
         // ---- per row: quantise, code, pack -------------------------------------------------------
         uint32_t row_base = 0;                         // bits of this chunk written so far (wave-uniform)
@@ -466,10 +569,11 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                 const uint32_t i0 = g.clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
                 uint32_t rnd[4], e[4], idx[4];
                 philox4x32_10(i0 >> 2, 0u, k, a.call_id, a.seed_lo, a.seed_hi, rnd);
-                e[0] = quantize_one<true>(v[r].x, rinv, rnd[0], L, n_sym, idx[0]);
-                e[1] = quantize_one<true>(v[r].y, rinv, rnd[1], L, n_sym, idx[1]);
-                e[2] = quantize_one<true>(v[r].z, rinv, rnd[2], L, n_sym, idx[2]);
-                e[3] = quantize_one<true>(v[r].w, rinv, rnd[3], L, n_sym, idx[3]);
+                const float rinv_r = GROUPED ? s_rinv[w * 16 + (int)((uint32_t)r >> rshift)] : rinv;
+                e[0] = quantize_one<true>(v[r].x, rinv_r, rnd[0], L, n_sym, idx[0]);
+                e[1] = quantize_one<true>(v[r].y, rinv_r, rnd[1], L, n_sym, idx[1]);
+                e[2] = quantize_one<true>(v[r].z, rinv_r, rnd[2], L, n_sym, idx[2]);
+                e[3] = quantize_one<true>(v[r].w, rinv_r, rnd[3], L, n_sym, idx[3]);
                 if (MODE == EncMode::QuantOnly) {
                     uint32_t pk = 0;
                     const float xs[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
@@ -506,11 +610,13 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                     if (i0 + 2 < g.cend) x.z = Vk[i0 + 2];
                     if (i0 + 3 < g.cend) x.w = Vk[i0 + 3];
                     const float xs[4] = {x.x, x.y, x.z, x.w};
+                    const float rinv_r = GROUPED ? s_rinv[w * 16 + (int)((uint32_t)r >> rshift)] : rinv;
+                    const bool live_r = GROUPED ? rinv_r != 0.0f : live;
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         idx[q] = 0;
                         neg[q] = __float_as_uint(xs[q]) >> 31;
-                        if (live) (void)quantize_one<false>(xs[q], rinv, rnd[q], L, n_sym, idx[q]);
+                        if (live_r) (void)quantize_one<false>(xs[q], rinv_r, rnd[q], L, n_sym, idx[q]);
                     }
                 }
                 if (MODE == EncMode::QuantOnly) {
@@ -575,42 +681,50 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
     }
 }
 
-static size_t encode_lds_bytes(int waves, const EncodeArgs& a, bool with_stage)
+static size_t encode_lds_bytes(int waves, const EncodeArgs& a, bool with_stage, bool grouped)
 {
-    size_t n = kCellsPad * sizeof(float2) + (size_t)a.lev_bytes +
+    size_t n = kCellsPad * sizeof(float2) + (size_t)a.lev_bytes + (grouped ? (size_t)waves * 64 : 0) +
                (2 * (size_t)waves + 2) * sizeof(double) + (size_t)(waves + 3) / 4 * 4 * sizeof(uint32_t) + 32;
     if (with_stage) n += (size_t)waves * a.stage_bytes;
     return n;
 }
 
-template <EncMode MODE>
+template <EncMode MODE, bool GROUPED>
 static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a, hipStream_t st,
                               uint32_t* tickets_per_worker)
 {
-    const int waves = a.parts > 1u ? 4 : (int)lay.waves_per_bucket;
-    const size_t lds = encode_lds_bytes(waves, a, MODE != EncMode::QuantOnly);
+    const int waves = (GROUPED || a.parts > 1u) ? 4 : (int)lay.waves_per_bucket;
+    const size_t lds = encode_lds_bytes(waves, a, MODE != EncMode::QuantOnly, GROUPED);
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_encode<MODE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_encode<MODE, GROUPED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    // one workgroup per bucket, or per part of a bucket; in compact placement and with split buckets
-    // each takes one ticket of its worker
-    const uint32_t units = lay.NB * a.parts;
+    // one workgroup per bucket, per part of a bucket, or (shared chunks) per four chunks; in compact
+    // placement and with split buckets each takes one ticket of its worker
+    const uint32_t units = GROUPED ? (lay.NC + 3u) / 4u : lay.NB * a.parts;
     *tickets_per_worker = ((MODE != EncMode::QuantOnly && a.slot_words == 0u) || a.parts > 1u) ? units : 0u;
-    hipLaunchKernelGGL(k_encode<MODE>, dim3(lay.K * units), dim3(waves * kWave), lds, st, lay, tab, sc, a);
+    hipLaunchKernelGGL((k_encode<MODE, GROUPED>), dim3(lay.K * units), dim3(waves * kWave), lds, st, lay, tab, sc, a);
     return hipGetLastError();
+}
+
+template <EncMode MODE>
+static hipError_t launch_kind(const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a, hipStream_t st,
+                              uint32_t* tickets_per_worker)
+{
+    return lay.shared_chunks ? launch_mode<MODE, true>(lay, tab, sc, a, st, tickets_per_worker)
+                             : launch_mode<MODE, false>(lay, tab, sc, a, st, tickets_per_worker);
 }
 
 hipError_t launch_encode(EncMode mode, const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a,
                          hipStream_t st, uint32_t* tickets_per_worker)
 {
     switch (mode) {
-        case EncMode::Fused: return launch_mode<EncMode::Fused>(lay, tab, sc, a, st, tickets_per_worker);
-        case EncMode::QuantOnly: return launch_mode<EncMode::QuantOnly>(lay, tab, sc, a, st, tickets_per_worker);
-        default: return launch_mode<EncMode::EncodeOnly>(lay, tab, sc, a, st, tickets_per_worker);
+        case EncMode::Fused: return launch_kind<EncMode::Fused>(lay, tab, sc, a, st, tickets_per_worker);
+        case EncMode::QuantOnly: return launch_kind<EncMode::QuantOnly>(lay, tab, sc, a, st, tickets_per_worker);
+        default: return launch_kind<EncMode::EncodeOnly>(lay, tab, sc, a, st, tickets_per_worker);
     }
 }
 

@@ -89,14 +89,21 @@ struct Layout {                 // device pointers into one allocation
     const uint32_t* bucket_start;   // [NB+1]
     const uint32_t* bucket_chunk0;  // [NB+1] first chunk of each bucket
     const uint32_t* chunk_start;    // [NC+1]
-    const uint32_t* chunk_bucket;   // [NC]
+    const uint32_t* chunk_bucket;   // [NC] bucket of the chunk's first coordinate
     const uint32_t* ragged_chunk;   // [n_ragged] chunk positions with fewer than kChunk coordinates, ascending
     uint32_t NB, NC, K, d;
     uint32_t n_ragged;
     uint32_t max_ragged;            // coordinates of the longest of them
     uint32_t waves_per_bucket;      // ceil(bucket / kChunk)
     uint32_t uniform_bucket;        // bucket size if there is one segment (offsets are then arithmetic), else 0
+    // Buckets of 256, 512, 1024 or 2048 coordinates share chunks: a segment is cut into runs of kChunk
+    // coordinates that hold whole buckets.  bucket_shift = log2(bucket) there and 31 otherwise, so that
+    // coordinate i of chunk c lies in bucket chunk_bucket[c] + (i >> bucket_shift) with either kind.
+    uint32_t shared_chunks;
+    uint32_t bucket_shift;
 };
+
+inline bool shares_chunks(uint32_t bucket) { return bucket == 256u || bucket == 512u || bucket == 1024u || bucket == 2048u; }
 
 enum class EncMode { Fused, QuantOnly, EncodeOnly };
 enum class DecMode { Decode, Average, Half0, Half1 };

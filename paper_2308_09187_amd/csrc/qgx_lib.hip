@@ -188,22 +188,32 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     std::vector<uint32_t> bstart, bchunk0, cstart, cbucket, ragged;
     uint64_t pos = 0, worst = 0;
     uint32_t max_ragged = 0;
+    const bool shared = shares_chunks(cfg->bucket);
+    auto add_chunk = [&](uint64_t start, uint64_t cl, uint32_t first_bucket) {
+        if (cl < (uint64_t)kChunk) {
+            ragged.push_back((uint32_t)cstart.size());
+            if (cl > max_ragged) max_ragged = (uint32_t)cl;
+        }
+        cstart.push_back((uint32_t)start);
+        cbucket.push_back(first_bucket);
+        const uint64_t wds = (cl * kMaxSymBits + 31) / 32;
+        worst += (wds + kAlignWords - 1) / kAlignWords * kAlignWords;
+    };
     for (uint64_t len_s : c->seg) {
         uint64_t left = len_s;
+        if (shared) {                                   // chunks are runs of the segment, each holding whole buckets
+            for (uint64_t o = 0; o < len_s; o += kChunk)
+                add_chunk(pos + o, (len_s - o) < (uint64_t)kChunk ? (len_s - o) : (uint64_t)kChunk,
+                          (uint32_t)(bstart.size() + o / cfg->bucket));
+        }
         while (left) {
             const uint64_t len = left < cfg->bucket ? left : cfg->bucket;
             bstart.push_back((uint32_t)pos);
-            bchunk0.push_back((uint32_t)cstart.size());
-            for (uint64_t o = 0; o < len; o += kChunk) {
-                const uint64_t cl = (len - o) < (uint64_t)kChunk ? (len - o) : (uint64_t)kChunk;
-                if (cl < (uint64_t)kChunk) {
-                    ragged.push_back((uint32_t)cstart.size());
-                    if (cl > max_ragged) max_ragged = (uint32_t)cl;
-                }
-                cstart.push_back((uint32_t)(pos + o));
-                cbucket.push_back((uint32_t)(bstart.size() - 1));
-                uint64_t wds = (cl * kMaxSymBits + 31) / 32;
-                worst += (wds + kAlignWords - 1) / kAlignWords * kAlignWords;
+            bchunk0.push_back((uint32_t)cstart.size());     // (not meaningful with shared chunks)
+            if (!shared) {
+                for (uint64_t o = 0; o < len; o += kChunk)
+                    add_chunk(pos + o, (len - o) < (uint64_t)kChunk ? (len - o) : (uint64_t)kChunk,
+                              (uint32_t)(bstart.size() - 1));
             }
             pos += len;
             left -= len;
@@ -233,7 +243,11 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     uint32_t max_len = 0;
     for (uint32_t b = 0; b < NB; ++b) max_len = bstart[b + 1] - bstart[b] > max_len ? bstart[b + 1] - bstart[b] : max_len;
     c->lay.waves_per_bucket = (max_len + kChunk - 1) / kChunk;
-    c->lay.uniform_bucket = c->seg.size() == 1 ? cfg->bucket : 0u;
+    c->lay.uniform_bucket = (c->seg.size() == 1 && !shared) ? cfg->bucket : 0u;
+    c->lay.shared_chunks = shared ? 1u : 0u;
+    c->lay.bucket_shift = 31u;
+    if (shared)
+        for (c->lay.bucket_shift = 0; (1u << c->lay.bucket_shift) < cfg->bucket;) ++c->lay.bucket_shift;
     c->h_groups = histogram_groups(c->lay);
 
     bool ok = true;

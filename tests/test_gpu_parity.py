@@ -82,6 +82,10 @@ CASES = [
     (2 * 65536 + 20000, 2, 65536, 3, "exp16", None),                 # by four, two exchanges (maximum, then powers)
     (65536 + 40000, 2, 65536, oracle.NORM_L2, "exp16", [65536, 24576, 15424]),   # full, 6-chunk and 4-chunk buckets
     (65536 + 500, 65, 65536, oracle.NORM_L2, "exp8", None),          # many workers: one 16-wave workgroup per bucket
+    (3 * 4096 + 1024 + 300, 3, 1024, oracle.NORM_L2, "exp16", None), # the paper's bucket size: chunks shared by four buckets
+    (2 * 4096 + 3 * 256 + 12, 2, 256, oracle.NORM_LINF, "uni16", None),        # by sixteen
+    (4096 + 512 + 2048 + 2344, 2, 512, 3, "exp16", [4096 + 512, 2048, 2344]),  # by eight, several tensors, ||v||_3
+    (5 * 4096, 5, 2048, oracle.NORM_L2, "exp8", None),               # by two; a workgroup's last wave has no chunk
 ]
 
 
@@ -268,6 +272,41 @@ def test_split_bucket_extreme_scale(qgx, scale):
     n_o, _, _, bad = oracle.quantize(V, lay, oracle.NORM_L2, levels, 9, 3)
     assert bad == 0 and np.max(np.abs(h["norms"] - n_o) / n_o) <= REL
     _, _, _, st_o = oracle_stream(V, lay, oracle.NORM_L2, levels, 9, 3, h["norms"], ctx.worst_words)
+    assert_stream_equal(h, st_o, lay)
+    assert ctx.poll_error() == 0
+    ctx.close()
+
+
+def test_shared_chunks_with_dead_and_forced_buckets(qgx):
+    """Buckets of 1024 share chunks of 4096: a chunk whose buckets are not all live (one all zero,
+    one with a NaN) or whose norms are forced below the largest magnitude leaves the straight-line
+    path as a whole, and every bucket still gets its own treatment."""
+    d, K, bucket = 3 * 4096, 2, 1024
+    levels = synth.levels_exponential(8)
+    ctx, lay = make_ctx(qgx, d, K, bucket, oracle.NORM_L2, levels, seed=3)
+    V = synth.student_t3(K, d, seed=14)
+    V[0, 1024:2048] = 0.0                           # a dead bucket inside the first chunk of worker 0
+    V[1, 5000] = np.nan                             # a rejected bucket inside the second chunk of worker 1
+    out = ctx.new_stream()
+    ctx.quantize_encode(dev(V), 7, out)
+    assert ctx.poll_error() == qgx.EBIT_NONFINITE
+    h = out.to_host()
+    n_o, _, _, bad = oracle.quantize(V, lay, oracle.NORM_L2, levels, 3, 7)
+    assert bad == 1 and h["norms"][0, 1] == 0.0 and h["norms"][1, 4] == 0.0
+    live = n_o > 0
+    assert np.max(np.abs(h["norms"][live] - n_o[live]) / n_o[live]) <= REL and not h["norms"][~live].any()
+    _, _, _, st_o = oracle_stream(V, lay, oracle.NORM_L2, levels, 3, 7, h["norms"], ctx.worst_words)
+    assert_stream_equal(h, st_o, lay)
+    Vhat_o, _, _ = oracle.decode(st_o, h["norms"], lay, levels)
+    np.testing.assert_array_equal(ctx.decode(out).cpu().numpy(), Vhat_o)
+    # forced norms: half the true ones for one chunk's buckets (coordinates above them clamp to u = 1)
+    V2 = synth.student_t3(K, d, seed=15)
+    forced = oracle.quantize(V2, lay, oracle.NORM_L2, levels, 3, 8)[0].copy()
+    forced[:, 4:8] *= np.float32(0.01)
+    ctx.quantize_encode(dev(V2), 8, out, norms_in=dev(forced))
+    h = out.to_host()
+    np.testing.assert_array_equal(h["norms"], forced)
+    _, _, _, st_o = oracle_stream(V2, lay, oracle.NORM_L2, levels, 3, 8, forced, ctx.worst_words)
     assert_stream_equal(h, st_o, lay)
     assert ctx.poll_error() == 0
     ctx.close()
