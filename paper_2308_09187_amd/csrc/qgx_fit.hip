@@ -140,6 +140,121 @@ __global__ __launch_bounds__(1024) void k_histogram(Layout lay, const float* __r
         partial[(size_t)blockIdx.x * n_bins + i] = s_acc[i];
 }
 
+// Buckets of 256..2048 coordinates (one to eight rows of 256): a workgroup of one wave per bucket
+// would leave the chip nearly empty and spend its time folding 4096 counters per bucket.  Here a
+// workgroup is four waves with a bucket each.  A wave counts into 16-bit counters of its own (two to
+// a word; a count is at most 2048), and the lane that takes a counter from zero remembers it: after
+// the count exactly those lanes fold their counters into the workgroup's binary64 sums, weighted by
+// the squared norm, and clear them, so a fold costs what the bucket touched, not the whole table.
+// The waves fold one after the other, in wave order, so every sum still receives its terms in a
+// fixed order and the histogram is reproducible bit for bit.
+template <int RPB>
+__global__ __launch_bounds__(256) void k_histogram_small(Layout lay, const float* __restrict__ V, int norm_kind,
+                                                         uint32_t n_bins, double* __restrict__ partial, Scalars* sc)
+{
+    extern __shared__ __align__(16) unsigned char s_raw[];
+    constexpr int kW = 4;
+    const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
+    double* s_acc = reinterpret_cast<double*>(s_raw);                                   // [n_bins]
+    uint32_t* s_cnt = reinterpret_cast<uint32_t*>(s_acc + n_bins) + (size_t)w * (n_bins / 2);   // [n_bins / 2] per wave
+    for (uint32_t i = (uint32_t)tid; i < n_bins; i += kW * kWave) s_acc[i] = 0.0;
+    for (uint32_t i = (uint32_t)lane; i < n_bins / 2; i += kWave) s_cnt[i] = 0u;
+    __syncthreads();
+
+    const uint32_t n_work = lay.K * lay.NB;
+    for (uint32_t t0 = (uint32_t)blockIdx.x * kW; t0 < n_work; t0 += gridDim.x * kW) {
+        const uint32_t t = t0 + (uint32_t)w;
+        const bool have = t < n_work;                     // wave-uniform
+        const uint32_t b = have ? t / lay.K : 0u, k = have ? t - b * lay.K : 0u;
+        const uint32_t lo = lay.bucket_start[b], hi = have ? lay.bucket_start[b + 1] : lo;
+        const size_t kbase = (size_t)k * lay.d;
+        const bool vec_ok = (kbase & 3u) == 0;
+        const float* __restrict__ Vk = V + kbase;
+        float4 v[RPB];
+#pragma unroll
+        for (int r = 0; r < RPB; ++r) {
+            const uint32_t i0 = lo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i0 + 4u <= hi) {
+                if (vec_ok) x = *reinterpret_cast<const float4*>(Vk + i0);
+                else x = make_float4(Vk[i0], Vk[i0 + 1], Vk[i0 + 2], Vk[i0 + 3]);
+            } else if (i0 < hi) {
+                x.x = Vk[i0];
+                if (i0 + 1 < hi) x.y = Vk[i0 + 1];
+                if (i0 + 2 < hi) x.z = Vk[i0 + 2];
+            }
+            v[r] = x;
+        }
+        // the norm, with the arithmetic of k_histogram for a bucket of one wave
+        double acc = 0.0;
+        float mx = 0.0f;
+        uint32_t bad = 0;
+#pragma unroll
+        for (int r = 0; r < RPB; ++r) {
+            const float e[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float ax = fabsf(e[q]);
+                bad |= !(ax <= 3.402823466e+38f);
+                if (norm_kind == QGX_NORM_L2) acc = fma((double)e[q], (double)e[q], acc);
+                else mx = fmaxf(mx, ax);
+            }
+        }
+        double tot = (norm_kind == QGX_NORM_L2) ? wave_sum(acc) : (double)wave_max(mx);
+        bad = wave_or(bad);
+        float n = (norm_kind == QGX_NORM_L2) ? (float)sqrt(tot) : (float)tot;
+        if (norm_kind != QGX_NORM_L2 && norm_kind != QGX_NORM_LINF && bad == 0 && tot > 0.0) {
+            const double inv_m = 1.0 / tot;
+            double sum = 0.0;
+#pragma unroll 1
+            for (uint32_t i = lo + (uint32_t)lane; i < hi; i += kWave)
+                sum += pow_int(fabs((double)Vk[i]) * inv_m, (uint32_t)norm_kind);
+            n = (float)(tot * root_int(wave_sum(sum), (uint32_t)norm_kind));
+        }
+        const bool usable = have && (bad == 0) && (n > 0.0f) && (n <= 3.402823466e+38f);
+        if (have && bad != 0 && lane == 0) raise_error(sc, QGX_EBIT_NONFINITE);
+
+        uint32_t bins[4 * RPB];
+        uint32_t mine = 0;                                // slots whose counter this lane took from zero
+        if (usable) {
+            const float rinv = 1.0f / n;
+#pragma unroll
+            for (int r = 0; r < RPB; ++r) {
+                const uint32_t i0 = lo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
+                const float e[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    bins[4 * r + q] = 0;
+                    if (i0 + (uint32_t)q < hi) {
+                        const float u = fminf(fabsf(e[q]) * rinv, 1.0f);
+                        const uint32_t bin = bin_of(u, n_bins), sh = (bin & 1u) * 16u;
+                        bins[4 * r + q] = bin;
+                        const uint32_t old = atomicAdd(&s_cnt[bin >> 1], 1u << sh);
+                        if (((old >> sh) & 0xFFFFu) == 0u) mine |= 1u << (4 * r + q);
+                    }
+                }
+            }
+        }
+        const double wgt = (double)n * (double)n;         // lambda of Section 3.3, unnormalised
+        for (int turn = 0; turn < kW; ++turn) {
+            if (turn == w && usable) {
+#pragma unroll
+                for (int s = 0; s < 4 * RPB; ++s) {
+                    if (mine & (1u << s)) {
+                        const uint32_t bin = bins[s], sh = (bin & 1u) * 16u;
+                        const uint32_t cnt = (s_cnt[bin >> 1] >> sh) & 0xFFFFu;
+                        s_acc[bin] += (double)cnt * wgt;
+                        atomicAnd(&s_cnt[bin >> 1], ~(0xFFFFu << sh));
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    for (uint32_t i = (uint32_t)tid; i < n_bins; i += kW * kWave)
+        partial[(size_t)blockIdx.x * n_bins + i] = s_acc[i];
+}
+
 // Workgroup sums -> histogram, in an order that does not depend on timing: a thread adds a run of
 // kRedRun consecutive workgroups' values of one bin, then the runs of a bin are added in order.
 constexpr uint32_t kRedRun = 32;
@@ -175,9 +290,19 @@ uint32_t histogram_groups(const Layout& lay)
 hipError_t launch_histogram(const Layout& lay, const float* V, int norm_kind, uint32_t n_bins, double* partial,
                             uint32_t n_partial, double* hist, Scalars* sc, hipStream_t st)
 {
-    const size_t lds = (size_t)n_bins * (sizeof(double) + sizeof(uint32_t));
-    hipLaunchKernelGGL(k_histogram, dim3(n_partial), dim3(lay.waves_per_bucket * kWave), lds, st, lay, V, norm_kind,
-                       n_bins, partial, sc);
+    if (lay.shared_chunks) {                              // buckets of 256 << s coordinates, s = 0..3
+        const size_t lds = (size_t)n_bins * (sizeof(double) + 4 * sizeof(uint16_t));
+        switch (lay.bucket_shift) {
+            case 8: hipLaunchKernelGGL(k_histogram_small<1>, dim3(n_partial), dim3(256), lds, st, lay, V, norm_kind, n_bins, partial, sc); break;
+            case 9: hipLaunchKernelGGL(k_histogram_small<2>, dim3(n_partial), dim3(256), lds, st, lay, V, norm_kind, n_bins, partial, sc); break;
+            case 10: hipLaunchKernelGGL(k_histogram_small<4>, dim3(n_partial), dim3(256), lds, st, lay, V, norm_kind, n_bins, partial, sc); break;
+            default: hipLaunchKernelGGL(k_histogram_small<8>, dim3(n_partial), dim3(256), lds, st, lay, V, norm_kind, n_bins, partial, sc); break;
+        }
+    } else {
+        const size_t lds = (size_t)n_bins * (sizeof(double) + sizeof(uint32_t));
+        hipLaunchKernelGGL(k_histogram, dim3(n_partial), dim3(lay.waves_per_bucket * kWave), lds, st, lay, V, norm_kind,
+                           n_bins, partial, sc);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_hist_reduce, dim3((n_bins + kRedBins - 1u) / kRedBins), dim3(256), 0, st, n_bins, n_partial,

@@ -605,7 +605,8 @@ def test_fit_levels_many_levels_and_sweeps(qgx):
 
 
 @pytest.mark.parametrize("norm,bucket,n_bins", [(oracle.NORM_L2, 16384, 4096), (oracle.NORM_LINF, 4096, 1024),
-                                                (4, 8192, 2048)])
+                                                (4, 8192, 2048), (oracle.NORM_L2, 1024, 4096),
+                                                (oracle.NORM_LINF, 256, 1024), (3, 2048, 2048)])
 def test_fit_levels_parity(qgx, norm, bucket, n_bins):
     d, K, n_sym = (1 << 17) + 300, 3, 33
     start = synth.levels_exponential(n_sym - 1)
