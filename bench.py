@@ -51,9 +51,11 @@ def parse_args():
                     help="t3: the headline batch of heavy-tailed vectors; gan: K vectors in a GAN-shaped layout of 14 "
                          "tensors with per-tensor scale, buckets of 8192 per tensor, L-infinity norm, 16 exponential "
                          "levels, full iteration (ignores --logd, --bucket, --n-sym)")
-    ap.add_argument("--code", choices=["omega", "huffman"], default="omega",
-                    help="Psi: Elias' recursive code of the level index (default) or the optimal prefix code "
-                         "fitted to the estimated symbol probabilities")
+    ap.add_argument("--code", choices=["omega", "huffman", "fixed"], default="omega",
+                    help="Psi: Elias' recursive code of the level index (default), the optimal prefix code "
+                         "fitted to the estimated symbol probabilities, or words of one width (with uniform levels: "
+                         "the fixed-width setting of the paper's experiment, e.g. --workload gan --bucket 1024 "
+                         "--n-sym 8 --code fixed for 3 bits + sign)")
     ap.add_argument("--placement", choices=["slotted", "compact"], default="slotted",
                     help="chunk placement of the coded streams handed from the encoder to the update kernel")
     return ap.parse_args()
@@ -131,34 +133,47 @@ def main():
     qgx.load()
     torch.cuda.set_device(0)
     K, seed = args.K, 2308
-    huffman = args.code == "huffman"
-    code_kind = qgx.CODE_TABLE if huffman else qgx.CODE_ELIAS_OMEGA
+    huffman, fixed = args.code == "huffman", args.code == "fixed"
+    code_kind = qgx.CODE_TABLE if (huffman or fixed) else qgx.CODE_ELIAS_OMEGA
     if args.workload == "gan":
         args.full_iteration = True
-        args.bucket, args.n_sym = 8192, 17
+        if not fixed:
+            args.n_sym = 17
+        if args.bucket == 16384:                                   # the option's default: this workload's own
+            args.bucket = 8192
         seg = [int(x) for x in synth.GAN_SEGMENTS]
         d = sum(seg)
         V = torch.from_numpy(synth.gan_dual_vectors(K, 0)).cuda()
         V1 = torch.from_numpy(synth.gan_dual_vectors(K, 1)).cuda()
         ctx = qgx.Context(d, K, args.bucket, norm=qgx.NORM_LINF, seed=seed, code=code_kind, segment_len=seg)
-        ctx.set_levels(synth.levels_exponential(16))
+        ctx.set_levels(synth.levels_uniform(args.n_sym - 1) if fixed else synth.levels_exponential(16))
         if huffman:
             ctx.fit_levels(V, args.n_sym, 4096, sweeps=0)          # only measures: the table stays
         what = "K=%d x d=%d in 14 tensors (GAN-shaped), N(0, sigma_t^2) with sigma_t log-uniform in [1e-5, 1e-2], " \
-               "buckets of 8192 per tensor, L-infinity, 16 exponential levels" % (K, d)
+               "buckets of %d per tensor, L-infinity, %s levels" % (K, d, args.bucket, "%d uniform" % (args.n_sym - 1) if fixed
+                                                                    else "16 exponential")
     else:
         d = 1 << args.logd
         V = synth.student_t3_device(K, d, seed=20)
         V1 = synth.student_t3_device(K, d, seed=21) if args.full_iteration else None
         Vr = synth.student_t3_device(K, d, seed=21) if args.rotate and not args.full_iteration else None
         ctx = qgx.Context(d, K, args.bucket, norm=qgx.NORM_L2, seed=seed, code=code_kind)
-        ctx.set_levels(synth.levels_exponential(args.n_sym - 1))
-        ctx.fit_levels(V, args.n_sym, 4096, sweeps=10)
-        what = "K=%d x d=2^%d Student-t(3)*1e-2, bucket %d, L2, %d-symbol fitted table" % (K, args.logd, args.bucket, args.n_sym)
+        if fixed:
+            ctx.set_levels(synth.levels_uniform(args.n_sym - 1))
+            what = "K=%d x d=2^%d Student-t(3)*1e-2, bucket %d, L2, %d uniform levels" % (K, args.logd, args.bucket, args.n_sym - 1)
+        else:
+            ctx.set_levels(synth.levels_exponential(args.n_sym - 1))
+            ctx.fit_levels(V, args.n_sym, 4096, sweeps=10)
+            what = "K=%d x d=2^%d Student-t(3)*1e-2, bucket %d, L2, %d-symbol fitted table" % (K, args.logd, args.bucket, args.n_sym)
     default_workload = (args.workload, args.logd, K, args.bucket, args.n_sym, args.code, args.placement) == \
                        ("t3", 24, 8, 16384, 33, "omega", "slotted")
     levels = ctx.get_levels()
-    code = ctx.fit_code()[1:] if huffman else (None, None)
+    if fixed:                                                      # words of ceil(log2 n_sym) bits, symbol j as the number j
+        width = max(1, (args.n_sym - 1).bit_length())
+        code = (np.full(args.n_sym, width, np.uint8), np.arange(args.n_sym, dtype=np.uint32))
+        ctx.set_code_table(*code)
+    else:
+        code = ctx.fit_code()[1:] if huffman else (None, None)
     ctx.state_init(None)
     slotted = args.placement == "slotted"
     a, b = ctx.new_stream(slotted=slotted), ctx.new_stream(slotted=slotted)
@@ -242,7 +257,7 @@ def main():
         "ms_per_step": ms_step, "preroll_ms": args.preroll_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s, %s; %s chunk placement; step = fused CODE.Q + fused decode/average/half-step%s"
-                               % (what, "fitted optimal prefix code" if huffman else "Elias-omega", args.placement,
+                               % (what, "fitted optimal prefix code" if huffman else "fixed-width code" if fixed else "Elias-omega", args.placement,
                                   " + CODE.Q + second half-step" if args.full_iteration else ""),
                    "K": K, "d": d, "bucket": args.bucket, "n_sym": args.n_sym,
                    "bits_per_coordinate": bits / float(K * d), "stream_bytes": stream_bytes},

@@ -163,7 +163,8 @@ __device__ __forceinline__ SubMeta load_meta(const uint16_t* sub_end, const floa
     m.p_mid = se[2 * lane];
     m.p0 = lane ? (uint32_t)se[2 * lane - 1] : 0u;
     // the lane's 64 coordinates lie in one bucket: the chunk's own, or with shared chunks one further on
-    m.n = norms[(size_t)k * lay.NB + bkt + (((uint32_t)lane * (uint32_t)kLaneCoords) >> lay.bucket_shift)];
+    // (a lane past the end of a short chunk has nothing to decode: its index is kept inside the table)
+    m.n = norms[(size_t)k * lay.NB + min(bkt + (((uint32_t)lane * (uint32_t)kLaneCoords) >> lay.bucket_shift), lay.NB - 1u)];
     return m;
 }
 
@@ -244,8 +245,10 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
     uint32_t clo, clen, bkt;
     chunk_geometry(lay, c, clo, clen, bkt);
     if (clen != (uint32_t)kChunk) return;                // wave-uniform: the ragged launch takes this position
-    // a cursor from a corrupt table is pulled back so that 64 symbols from it stay inside the buffer
-    const uint32_t p_limit = stage_words * 32u - 64u * (uint32_t)kMaxSymBits - 64u;
+    // A cursor from a corrupt table is pulled back so that a chain of 32 symbols from it stays inside
+    // the buffer.  No valid cursor is beyond that: the last chain of a chunk starts after 4064 symbols
+    // of at most sym_bits each, and the buffer holds 4096 of them.
+    const uint32_t p_limit = stage_words * 32u - 32u * a.sym_bits;
 
     float acc[kLaneCoords];
 #pragma unroll
@@ -492,8 +495,9 @@ void k_decode_ragged(Layout lay, const Tables* __restrict__ tab, Scalars* sc, De
     chunk_geometry(lay, c, clo, clen, bkt);
     const int cnt = (int)min(64u, clen > 64u * (uint32_t)lane ? clen - 64u * (uint32_t)lane : 0u);
     const int cnt_a = min(cnt, kHalf), cnt_b = cnt - cnt_a;       // symbols of the lane's two sub-chunks
-    // a cursor from a corrupt table is pulled back so that 32 symbols from it stay inside the buffer
-    const uint32_t p_limit = stage_words * 32u - (uint32_t)(kHalf * kMaxSymBits) - 64u;
+    // Every chain parses 32 symbols whatever its count, so the buffer has room for that beyond the
+    // longest chunk (rag_words); a cursor from a corrupt table is pulled back to where that room starts.
+    const uint32_t p_limit = stage_words * 32u - (uint32_t)kHalf * a.sym_bits - 64u;
 
     double sdiff = 0.0;
     uint32_t flags = 0;

@@ -148,7 +148,9 @@ struct DecodeArgs {
     double* x_sum;              // [d] running sum of the X_{t+1/2} or null (Half0 adds its output)
     uint32_t stage_words;       // most words a chunk can take with the code in use (multiple of 4)
     uint32_t stage_stride;      // words of one LDS staging buffer (padded layout plus slack)
-    uint32_t rag_words;         // the same two for the layout's longest chunk of fewer than 4096 coordinates
+    uint32_t sym_bits;          // most bits a symbol can take with the codes in use (longest word + sign)
+    uint32_t rag_words;         // the same two for the layout's longest chunk of fewer than 4096 coordinates,
+                                // plus room for 32 symbols and a window past its end
     uint32_t rag_stride;
     uint32_t wide;              // the 8-byte decode table of the current streams' code is valid (Tables::wide_ok)
 };

@@ -504,8 +504,8 @@ static void fill_decode_args(const qgx_ctx* ctx, DecodeArgs& a, const qgx_stream
     a.stage_words = chunk_slot_words(ctx);
     a.stage_stride = (a.stage_words + a.stage_words / 16 + 12 + 3) / 4 * 4;
     if (a.stage_stride < 1280u) a.stage_stride = 1280u;   // the buffer also turns the output (64 rows of 20 floats)
-    a.rag_words = ((ctx->lay.max_ragged * (longest_code(ctx) + 1) + 31) / 32 + 3) / 4 * 4;
-    if (a.rag_words < 64u) a.rag_words = 64u;             // room for a lane's run of 32 symbols from any cursor
+    a.sym_bits = longest_code(ctx) + 1;
+    a.rag_words = ((ctx->lay.max_ragged * a.sym_bits + 31) / 32 + a.sym_bits + 2 + 3) / 4 * 4;
     a.rag_stride = (a.rag_words + a.rag_words / 16 + 12 + 3) / 4 * 4;
     a.wide = (T(ctx).wide && (!prev || ctx->ts[ctx->sel_prev].wide)) ? 1u : 0u;   // one kernel variant reads both streams
     a.norms = cur->norms; a.chunk_off = cur->chunk_off; a.sub_end = cur->sub_end; a.payload = cur->payload;

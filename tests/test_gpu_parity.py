@@ -312,6 +312,44 @@ def test_shared_chunks_with_dead_and_forced_buckets(qgx):
     ctx.close()
 
 
+@pytest.mark.parametrize("n_sym,bucket,fixed", [(33, 8192, False), (65, 8192, False), (8, 1024, True), (127, 4096, True)])
+def test_every_symbol_at_the_longest_word(qgx, n_sym, bucket, fixed):
+    """Chunks that fill their staging buffers to the last bit (every symbol the longest word, with a
+    sign): nothing of a valid stream may look malformed to the decoders, in any mode, for full and
+    ragged chunk positions."""
+    d, K = 2 * 4096 + 1000, 3
+    levels = synth.levels_uniform(n_sym - 1)
+    code = qgx.CODE_TABLE if fixed else qgx.CODE_ELIAS_OMEGA
+    ctx, lay = make_ctx(qgx, d, K, bucket, oracle.NORM_LINF, levels, seed=2, code=code)
+    cl = cb = None
+    if fixed:
+        width = (n_sym - 1).bit_length()
+        cl, cb = np.full(n_sym, width, np.uint8), np.arange(n_sym, dtype=np.uint32)
+        ctx.set_code_table(cl, cb)
+    idx = np.full((K, d), n_sym - 1, np.uint8)
+    neg = np.ones((K, d), np.uint8)
+    norms = np.random.default_rng(1).uniform(0.5, 2.0, (K, lay.NB)).astype(np.float32)
+    a, b = ctx.new_stream(), ctx.new_stream(slotted=True)
+    sym = dev(idx | (neg << 7))
+    ctx.encode(dev(norms), sym, a)
+    ctx.encode(dev(norms), sym, b)
+    st_o = oracle.encode(idx, neg, lay, ctx.worst_words, code_len=cl, code_bits=cb)
+    assert_stream_equal(a.to_host(), st_o, lay)
+    Vhat_o, _, _ = oracle.decode(st_o, norms, lay, levels, code_len=cl, code_bits=cb)
+    np.testing.assert_array_equal(ctx.decode(a).cpu().numpy(), Vhat_o)
+    np.testing.assert_array_equal(ctx.decode(b).cpu().numpy(), Vhat_o)
+    assert rel_err(ctx.decode_average(b).cpu().numpy(), Vhat_o.astype(np.float64).mean(axis=0)) <= REL
+    ctx.state_init(None)
+    st = oracle.EGState(d, K)
+    Xh = torch.empty(d, device="cuda"); Xn = torch.empty(d, device="cuda")
+    ctx.eg_step(0, a, None, Xh)
+    assert rel_err(Xh.cpu().numpy(), st.half0(Vhat_o)) <= REL
+    ctx.eg_step(1, b, a, Xn)
+    assert rel_err(Xn.cpu().numpy(), st.half1(Vhat_o, Vhat_o)) <= REL
+    assert ctx.poll_error() == 0
+    ctx.close()
+
+
 def test_malformed_stream_sets_error_bit(qgx):
     d, K = 8192, 1
     levels = synth.levels_exponential(8)            # 9 symbols: many 13-bit windows are not code words
