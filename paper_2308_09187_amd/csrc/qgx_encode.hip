@@ -12,7 +12,7 @@
 //
 // The kernel runs close to what the memory system gives (about 93 % of a plain copy of its input) and
 // at about two thirds of what the vector ALUs could issue, so the per-coordinate path is kept to a straight
-// line: u -> 1/16-octave cell -> (boundary level, address of the lower candidate table row) -> one
+// line: u -> cell (1/16, 1/32 or 1/64 of an octave, by the table's size) -> (boundary level, address of the lower candidate table row) -> one
 // 16-byte LDS row holding the level, the scaled gap and the two candidate code words with the sign
 // already appended -> compare against the Philox draw -> select.  Chunks that are not full, buckets
 // with a zero norm and level tables too fine for the cell table take a general path.
@@ -144,14 +144,16 @@ struct LdsPlan {                 // where things live in the workgroup's LDS
     const unsigned char* lev;    // level rows, two sign halves, lev_stride bytes apart
     uint32_t lev_addr;           // LDS byte address of the level rows (the cell table sits at address 0)
     uint32_t lev_stride, sign_shift;
+    uint32_t cell_shift;         // bits of u >> cell_shift = cell number + cell_key0
+    uint32_t cell_key0;          // key of the first cell (everything below goes there too)
 };
 
 // tau(u) by the general route: start at the cell's lower level and walk up; returns the byte offset
 // of row j in the level table.
 __device__ __forceinline__ uint32_t level_row_general(const LdsPlan& L, float u, uint32_t n_sym)
 {
-    const float um = fminf(fmaxf(u, __uint_as_float((uint32_t)kCellKey0 << kCellShift)), 1.0f);
-    const float2 c = L.cell[(__float_as_uint(um) >> kCellShift) - kCellKey0];
+    const float um = fminf(fmaxf(u, __uint_as_float(L.cell_key0 << L.cell_shift)), 1.0f);
+    const float2 c = L.cell[(__float_as_uint(um) >> L.cell_shift) - L.cell_key0];
     uint32_t j = (__float_as_uint(c.y) - L.lev_addr) >> 4;
     while (j + 2 < n_sym && reinterpret_cast<const float4*>(L.lev)[j + 1].x <= u) ++j;
     return j << 4;
@@ -160,7 +162,8 @@ __device__ __forceinline__ uint32_t level_row_general(const LdsPlan& L, float u,
 // One coordinate: the packed code entry E(idx, sign) = bits | length << 16 of q_l(u) with sign.
 // FAST: straight-line cell route, valid when u <= 1 up to rounding (so the clamp of u to 1 can be
 // left out: at u >= 1 the coordinate rounds up whatever the draw) and no cell holds two levels.
-template <bool FAST>
+// CM: the cell size as a compile-time constant (mantissa bits per octave), 0 = whatever L says.
+template <bool FAST, int CM = 0>
 __device__ __forceinline__ uint32_t quantize_one(float x, float rinv, uint32_t rnd, const LdsPlan& L, uint32_t n_sym,
                                                  uint32_t& idx_out)
 {
@@ -170,8 +173,14 @@ __device__ __forceinline__ uint32_t quantize_one(float x, float rinv, uint32_t r
     uint32_t row;                                       // byte offset of the level row in its half
     if (FAST) {
         // cell number times eight; a saturating subtraction sends everything below the first cell there
-        const uint32_t key8 = (__builtin_elementwise_sub_sat(__float_as_uint(u), (uint32_t)kCellKey0 << kCellShift)
-                               >> (kCellShift - 3)) & 0xFFF8u;
+        uint32_t key8;
+        if constexpr (CM != 0) {
+            constexpr uint32_t shift = 23u - CM, key0 = (uint32_t)(127 - kCellOct) << CM;
+            key8 = (__builtin_elementwise_sub_sat(__float_as_uint(u), key0 << shift) >> (shift - 3u)) & 0xFFF8u;
+            static_assert(((uint32_t)((kCellOct << CM) + 1) * 8u) <= 0x10000u, "cell numbers times eight fit 16 bits");
+        } else {
+            key8 = (__builtin_elementwise_sub_sat(__float_as_uint(u), L.cell_key0 << L.cell_shift) >> (L.cell_shift - 3u)) & ~7u;
+        }
         const uint2 c = lds_load_u2(key8);          // the cell table starts at LDS address 0 (checked at entry)
         // the cell's lower row, or the next one from the boundary level on (one level per cell at most)
         const uint32_t at = sg + c.y + (u >= __uint_as_float(c.x) ? 16u : 0u);
@@ -349,7 +358,9 @@ __device__ __forceinline__ bool shared_chunk_norms(const float4 (&v)[kRows], con
 // overlap the arithmetic of the others (a persistent, lock-stepped variant measured slower).
 // GROUPED: the layout has shared chunks; a workgroup is four waves with a chunk each, and every wave
 // finds the norms of its chunk's buckets by itself.
-template <EncMode MODE, bool GROUPED>
+// CM4: the level table has at most 33 entries, so the cells are 1/16 octaves: the common case keeps
+// its constants.
+template <EncMode MODE, bool GROUPED, bool CM4>
 __global__ __launch_bounds__(GROUPED ? 256 : 1024) __attribute__((amdgpu_waves_per_eu(5)))
 void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArgs a)
 {
@@ -361,7 +372,8 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
 
     // LDS plan: [cell][lev + / lev -][reduction scratch][one staging buffer per wave]
     float2* s_cell = reinterpret_cast<float2*>(s_all);
-    unsigned char* s_lev = s_all + kCellsPad * sizeof(float2);
+    const int n_cells = cell_count((int)a.cell_mant);
+    unsigned char* s_lev = s_all + cell_count_padded((int)a.cell_mant) * sizeof(float2);
     double* s_red = reinterpret_cast<double*>(s_lev + a.lev_bytes);
     double* s_tot = s_red + 2 * nwaves;                                       // second set: the general-q sum
     uint32_t* s_words = reinterpret_cast<uint32_t*>(s_tot + 2);               // bucket totals of a split bucket
@@ -372,6 +384,8 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
     LdsPlan L;
     L.cell = s_cell; L.lev = s_lev; L.lev_stride = a.lev_stride; L.sign_shift = a.sign_shift;
     L.lev_addr = lds_address(s_lev);
+    L.cell_shift = 23u - a.cell_mant;
+    L.cell_key0 = (uint32_t)(127 - kCellOct) << a.cell_mant;
     // The straight-line lookup addresses the cell table by number: the kernel has no static LDS, so
     // the dynamic array (and with it the table) starts at address 0.
     if (lds_address(s_all) != 0u) {
@@ -391,7 +405,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
         reinterpret_cast<float4*>(s_lev)[i] = tab->lev2[0][i];
         reinterpret_cast<float4*>(s_lev + a.lev_stride)[i] = tab->lev2[1][i];
     }
-    for (int i = tid; i < kCells; i += (int)blockDim.x) {
+    for (int i = tid; i < n_cells; i += (int)blockDim.x) {
         float2 c = tab->cell[i];                       // row offset -> LDS address of the row
         c.y = __uint_as_float((__float_as_uint(c.y) & 0xFFFFu) + L.lev_addr);
         s_cell[i] = c;
@@ -400,7 +414,8 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
         for (uint32_t q = (uint32_t)lane; q < a.stage_bytes / 16; q += kWave)
             reinterpret_cast<uint4*>(stage)[q] = make_uint4(0, 0, 0, 0);
     }
-    const uint32_t cell_exact = tab->cell_exact;
+    // (the table builder and the host take the cell size from the table's length by the same rule)
+    const uint32_t cell_exact = (tab->cell_exact != 0u && (uint32_t)cell_mant(n_sym) == a.cell_mant) ? 1u : 0u;
     __syncthreads();
 
     const size_t kbase = (size_t)k * lay.d;
@@ -570,10 +585,10 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                 uint32_t rnd[4], e[4], idx[4];
                 philox4x32_10(i0 >> 2, 0u, k, a.call_id, a.seed_lo, a.seed_hi, rnd);
                 const float rinv_r = GROUPED ? s_rinv[w * 16 + (int)((uint32_t)r >> rshift)] : rinv;
-                e[0] = quantize_one<true>(v[r].x, rinv_r, rnd[0], L, n_sym, idx[0]);
-                e[1] = quantize_one<true>(v[r].y, rinv_r, rnd[1], L, n_sym, idx[1]);
-                e[2] = quantize_one<true>(v[r].z, rinv_r, rnd[2], L, n_sym, idx[2]);
-                e[3] = quantize_one<true>(v[r].w, rinv_r, rnd[3], L, n_sym, idx[3]);
+                e[0] = quantize_one<true, CM4 ? 4 : 0>(v[r].x, rinv_r, rnd[0], L, n_sym, idx[0]);
+                e[1] = quantize_one<true, CM4 ? 4 : 0>(v[r].y, rinv_r, rnd[1], L, n_sym, idx[1]);
+                e[2] = quantize_one<true, CM4 ? 4 : 0>(v[r].z, rinv_r, rnd[2], L, n_sym, idx[2]);
+                e[3] = quantize_one<true, CM4 ? 4 : 0>(v[r].w, rinv_r, rnd[3], L, n_sym, idx[3]);
                 if (MODE == EncMode::QuantOnly) {
                     uint32_t pk = 0;
                     const float xs[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
@@ -683,13 +698,13 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
 
 static size_t encode_lds_bytes(int waves, const EncodeArgs& a, bool with_stage, bool grouped)
 {
-    size_t n = kCellsPad * sizeof(float2) + (size_t)a.lev_bytes + (grouped ? (size_t)waves * 64 : 0) +
+    size_t n = cell_count_padded((int)a.cell_mant) * sizeof(float2) + (size_t)a.lev_bytes + (grouped ? (size_t)waves * 64 : 0) +
                (2 * (size_t)waves + 2) * sizeof(double) + (size_t)(waves + 3) / 4 * 4 * sizeof(uint32_t) + 32;
     if (with_stage) n += (size_t)waves * a.stage_bytes;
     return n;
 }
 
-template <EncMode MODE, bool GROUPED>
+template <EncMode MODE, bool GROUPED, bool CM4>
 static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a, hipStream_t st,
                               uint32_t* tickets_per_worker)
 {
@@ -697,7 +712,7 @@ static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc,
     const size_t lds = encode_lds_bytes(waves, a, MODE != EncMode::QuantOnly, GROUPED);
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_encode<MODE, GROUPED>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_encode<MODE, GROUPED, CM4>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_done = true;
@@ -706,7 +721,7 @@ static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc,
     // placement and with split buckets each takes one ticket of its worker
     const uint32_t units = GROUPED ? (lay.NC + 3u) / 4u : lay.NB * a.parts;
     *tickets_per_worker = ((MODE != EncMode::QuantOnly && a.slot_words == 0u) || a.parts > 1u) ? units : 0u;
-    hipLaunchKernelGGL((k_encode<MODE, GROUPED>), dim3(lay.K * units), dim3(waves * kWave), lds, st, lay, tab, sc, a);
+    hipLaunchKernelGGL((k_encode<MODE, GROUPED, CM4>), dim3(lay.K * units), dim3(waves * kWave), lds, st, lay, tab, sc, a);
     return hipGetLastError();
 }
 
@@ -714,8 +729,11 @@ template <EncMode MODE>
 static hipError_t launch_kind(const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a, hipStream_t st,
                               uint32_t* tickets_per_worker)
 {
-    return lay.shared_chunks ? launch_mode<MODE, true>(lay, tab, sc, a, st, tickets_per_worker)
-                             : launch_mode<MODE, false>(lay, tab, sc, a, st, tickets_per_worker);
+    if (a.cell_mant == 4u)
+        return lay.shared_chunks ? launch_mode<MODE, true, true>(lay, tab, sc, a, st, tickets_per_worker)
+                                 : launch_mode<MODE, false, true>(lay, tab, sc, a, st, tickets_per_worker);
+    return lay.shared_chunks ? launch_mode<MODE, true, false>(lay, tab, sc, a, st, tickets_per_worker)
+                             : launch_mode<MODE, false, false>(lay, tab, sc, a, st, tickets_per_worker);
 }
 
 hipError_t launch_encode(EncMode mode, const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a,

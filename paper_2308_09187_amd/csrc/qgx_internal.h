@@ -23,13 +23,15 @@ constexpr int kMaxWaves = QGX_MAX_BUCKET / kChunk;      // 16 waves = 1024 threa
 constexpr int kTicketStride = 32;           // one 128-byte line per worker's counter
 constexpr int kSymMax = 128;              // table storage (QGX_MAX_SYM = 127 entries used at most)
 
-// tau lookup: one cell per 1/16 octave over 24 octaves below 1, plus the cell of u = 1.
-constexpr int kCellMant = 4;
+// tau lookup: one cell per 1/16, 1/32 or 1/64 octave (by the size of the level table: a cell must not
+// hold two levels) over 24 octaves below 1, plus the cell of u = 1.
 constexpr int kCellOct = 24;
-constexpr int kCellShift = 23 - kCellMant;
-constexpr int kCellKey0 = (127 - kCellOct) << kCellMant;
-constexpr int kCells = (kCellOct << kCellMant) + 1;     // 385
-constexpr int kCellsPad = 388;
+constexpr int kCellMantMax = 6;
+constexpr int kCellsMax = (kCellOct << kCellMantMax) + 1;    // 1537
+constexpr int kCellsPadMax = 1540;
+inline __host__ __device__ int cell_mant(uint32_t n_sym) { return n_sym <= 33u ? 4 : n_sym <= 65u ? 5 : 6; }
+inline __host__ __device__ int cell_count(int mant) { return (kCellOct << mant) + 1; }
+inline __host__ __device__ int cell_count_padded(int mant) { return (cell_count(mant) + 3) / 4 * 4; }
 constexpr int kLevRegion = kSymMax * 16;                // bytes between the two sign halves of lev2
 
 constexpr int kDlutBits = kMaxCode;       // decode window
@@ -53,10 +55,10 @@ struct Tables {
     // coordinate with sign sg between levels j and j+1 needs.  E(idx, sg) = code word of idx with the
     // sign bit appended (idx != 0), first-written bit in bit 0, total length << 16.
     float4 lev2[2][kSymMax];
-    // cell[c] = {B, a0 | a1 << 16} for the c-th 1/16-octave of u: a0 = byte offset in lev2 of the row of
+    // cell[c] = {B, a0 | a1 << 16} for the c-th cell of u (cell_mant(n_sym) mantissa bits per octave): a0 = byte offset in lev2 of the row of
     // the last level <= the cell's lower edge; B = the level inside the cell (+inf if none), a1 = the
     // row to use when u >= B.  Exact only if no cell holds two levels (cell_exact).
-    float2 cell[kCellsPad];
+    float2 cell[kCellsPadMax];
     float lval[kSymMax];        // l_j
     float levels[kSymMax];      // the table as set or fitted (source of the ones above)
     uint32_t code[kSymMax];     // code word (first-written bit in bit 0) | length << 16, no sign
@@ -127,6 +129,7 @@ struct EncodeArgs {
     uint32_t seed_lo, seed_hi, call_id;
     int norm_kind;
     // LDS plan of the launch (bytes): [cell][lev: two sign halves lev_stride apart][misc][stage x waves]
+    uint32_t cell_mant;         // cell_mant(n_sym) of the table in use
     uint32_t lev_stride;        // power of two >= 16 * n_sym
     uint32_t lev_bytes;         // lev_stride + 16 * n_sym: the second half ends with its last row
     uint32_t sign_shift;        // (bits of v) >> sign_shift puts the sign bit on lev_stride

@@ -434,6 +434,7 @@ static qgx_status run_encode(qgx_ctx* ctx, EncMode mode, const float* V, uint32_
     a.lev_stride = 16;
     while (a.lev_stride < 16u * T(ctx).n_sym) a.lev_stride <<= 1;
     a.lev_bytes = a.lev_stride + 16u * T(ctx).n_sym;
+    a.cell_mant = (uint32_t)cell_mant(T(ctx).n_sym);
     a.sign_shift = 31;
     while ((1u << (31 - a.sign_shift)) < a.lev_stride) --a.sign_shift;
     {

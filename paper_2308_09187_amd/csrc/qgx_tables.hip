@@ -63,14 +63,16 @@ static __device__ void build_tables_block(Tables* tab)
     // cells: lower level, the level inside (if any), and whether a second one makes the cell inexact
     if (tid == 0) { tab->cell_exact = 1u; tab->wide_ok = 1u; }
     __syncthreads();
-    for (int c = tid; c < kCellsPad; c += nt) {
+    const int mant = cell_mant(n_sym), cells = cell_count(mant), cell_shift = 23 - mant;
+    const int key0 = (127 - kCellOct) << mant;
+    for (int c = tid; c < cell_count_padded(mant); c += nt) {
         uint32_t j = 0;
         float B = inf;
         uint32_t a1 = 0;
         bool crowded = false;
-        if (c < kCells) {
-            const float edge = c == 0 ? 0.0f : __uint_as_float((uint32_t)(c + kCellKey0) << kCellShift);
-            const float next = c + 1 < kCells ? __uint_as_float((uint32_t)(c + 1 + kCellKey0) << kCellShift) : inf;
+        if (c < cells) {
+            const float edge = c == 0 ? 0.0f : __uint_as_float((uint32_t)(c + key0) << cell_shift);
+            const float next = c + 1 < cells ? __uint_as_float((uint32_t)(c + 1 + key0) << cell_shift) : inf;
             while (j + 2 < n_sym && lv[j + 1] <= edge) ++j;
             a1 = j;
             if (j + 2 < n_sym && lv[j + 1] < next) {      // a level strictly inside the cell
