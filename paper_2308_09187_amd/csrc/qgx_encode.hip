@@ -358,9 +358,8 @@ __device__ __forceinline__ bool shared_chunk_norms(const float4 (&v)[kRows], con
 // overlap the arithmetic of the others (a persistent, lock-stepped variant measured slower).
 // GROUPED: the layout has shared chunks; a workgroup is four waves with a chunk each, and every wave
 // finds the norms of its chunk's buckets by itself.
-// CM4: the level table has at most 33 entries, so the cells are 1/16 octaves: the common case keeps
-// its constants.
-template <EncMode MODE, bool GROUPED, bool CM4>
+// CM: cell_mant of the level table, so that the rounding pass has the cell size as a constant.
+template <EncMode MODE, bool GROUPED, int CM>
 __global__ __launch_bounds__(GROUPED ? 256 : 1024) __attribute__((amdgpu_waves_per_eu(5)))
 void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArgs a)
 {
@@ -585,10 +584,10 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                 uint32_t rnd[4], e[4], idx[4];
                 philox4x32_10(i0 >> 2, 0u, k, a.call_id, a.seed_lo, a.seed_hi, rnd);
                 const float rinv_r = GROUPED ? s_rinv[w * 16 + (int)((uint32_t)r >> rshift)] : rinv;
-                e[0] = quantize_one<true, CM4 ? 4 : 0>(v[r].x, rinv_r, rnd[0], L, n_sym, idx[0]);
-                e[1] = quantize_one<true, CM4 ? 4 : 0>(v[r].y, rinv_r, rnd[1], L, n_sym, idx[1]);
-                e[2] = quantize_one<true, CM4 ? 4 : 0>(v[r].z, rinv_r, rnd[2], L, n_sym, idx[2]);
-                e[3] = quantize_one<true, CM4 ? 4 : 0>(v[r].w, rinv_r, rnd[3], L, n_sym, idx[3]);
+                e[0] = quantize_one<true, CM>(v[r].x, rinv_r, rnd[0], L, n_sym, idx[0]);
+                e[1] = quantize_one<true, CM>(v[r].y, rinv_r, rnd[1], L, n_sym, idx[1]);
+                e[2] = quantize_one<true, CM>(v[r].z, rinv_r, rnd[2], L, n_sym, idx[2]);
+                e[3] = quantize_one<true, CM>(v[r].w, rinv_r, rnd[3], L, n_sym, idx[3]);
                 if (MODE == EncMode::QuantOnly) {
                     uint32_t pk = 0;
                     const float xs[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
@@ -704,7 +703,7 @@ static size_t encode_lds_bytes(int waves, const EncodeArgs& a, bool with_stage, 
     return n;
 }
 
-template <EncMode MODE, bool GROUPED, bool CM4>
+template <EncMode MODE, bool GROUPED, int CM>
 static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a, hipStream_t st,
                               uint32_t* tickets_per_worker)
 {
@@ -712,7 +711,7 @@ static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc,
     const size_t lds = encode_lds_bytes(waves, a, MODE != EncMode::QuantOnly, GROUPED);
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_encode<MODE, GROUPED, CM4>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_encode<MODE, GROUPED, CM>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_done = true;
@@ -721,7 +720,7 @@ static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc,
     // placement and with split buckets each takes one ticket of its worker
     const uint32_t units = GROUPED ? (lay.NC + 3u) / 4u : lay.NB * a.parts;
     *tickets_per_worker = ((MODE != EncMode::QuantOnly && a.slot_words == 0u) || a.parts > 1u) ? units : 0u;
-    hipLaunchKernelGGL((k_encode<MODE, GROUPED, CM4>), dim3(lay.K * units), dim3(waves * kWave), lds, st, lay, tab, sc, a);
+    hipLaunchKernelGGL((k_encode<MODE, GROUPED, CM>), dim3(lay.K * units), dim3(waves * kWave), lds, st, lay, tab, sc, a);
     return hipGetLastError();
 }
 
@@ -729,11 +728,14 @@ template <EncMode MODE>
 static hipError_t launch_kind(const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a, hipStream_t st,
                               uint32_t* tickets_per_worker)
 {
-    if (a.cell_mant == 4u)
-        return lay.shared_chunks ? launch_mode<MODE, true, true>(lay, tab, sc, a, st, tickets_per_worker)
-                                 : launch_mode<MODE, false, true>(lay, tab, sc, a, st, tickets_per_worker);
-    return lay.shared_chunks ? launch_mode<MODE, true, false>(lay, tab, sc, a, st, tickets_per_worker)
-                             : launch_mode<MODE, false, false>(lay, tab, sc, a, st, tickets_per_worker);
+    switch (a.cell_mant) {
+        case 4: return lay.shared_chunks ? launch_mode<MODE, true, 4>(lay, tab, sc, a, st, tickets_per_worker)
+                                         : launch_mode<MODE, false, 4>(lay, tab, sc, a, st, tickets_per_worker);
+        case 5: return lay.shared_chunks ? launch_mode<MODE, true, 5>(lay, tab, sc, a, st, tickets_per_worker)
+                                         : launch_mode<MODE, false, 5>(lay, tab, sc, a, st, tickets_per_worker);
+        default: return lay.shared_chunks ? launch_mode<MODE, true, 6>(lay, tab, sc, a, st, tickets_per_worker)
+                                          : launch_mode<MODE, false, 6>(lay, tab, sc, a, st, tickets_per_worker);
+    }
 }
 
 hipError_t launch_encode(EncMode mode, const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a,
