@@ -182,10 +182,11 @@ def test_norms_in_override_and_unaligned_worker_stride(qgx):
     ctx.close()
 
 
-@pytest.mark.parametrize("d", [1, 3, 4, 7, 63, 64, 65, 255, 257])
-def test_tiny_vectors(qgx, d):
+@pytest.mark.parametrize("d,bucket", [(1, 64), (3, 64), (4, 64), (7, 64), (63, 64), (64, 64), (65, 64), (255, 64), (257, 64),
+                                      (1, 256), (255, 256), (256, 256), (257, 256), (513, 512), (4097, 1024)])
+def test_tiny_vectors(qgx, d, bucket):
     levels = synth.levels_uniform(4)
-    ctx, lay = make_ctx(qgx, d, 2, 64, oracle.NORM_LINF, levels, seed=11)
+    ctx, lay = make_ctx(qgx, d, 2, bucket, oracle.NORM_LINF, levels, seed=11)
     V = synth.student_t3(2, d, seed=d)
     out = ctx.new_stream()
     ctx.quantize_encode(dev(V), 1, out)
