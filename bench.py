@@ -263,7 +263,9 @@ def main():
                    "bits_per_coordinate": bits / float(K * d), "stream_bytes": stream_bytes},
         "hbm_frac_step": (enc_bytes + upd_bytes) / ((enc_ms + upd_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernels_ms": {"encode": enc_ms, "decode_avg_half0": upd_ms},
-        "roofline": {"kernel": "k_encode<Fused>", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"kernel": "k_encode<Fused, %s, %d>" % ("true" if args.bucket in (256, 512, 1024, 2048) else "false",
+                                                            4 if args.n_sym <= 33 else 5 if args.n_sym <= 65 else 6),
+                     "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      # the committed counter run covers the default workload only
                      "traffic": measured_traffic() if default_workload else None,
