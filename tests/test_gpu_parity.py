@@ -778,6 +778,79 @@ def test_two_level_tables_lockstep(qgx, fitted_code, n0):
     ctx.close()
 
 
+@pytest.mark.parametrize("sweep", [1, 2])
+def test_random_configurations(qgx, sweep):
+    """Seeded random layouts (bucket sizes of every kind, several tensors with ragged ends), worker
+    counts, norms, level tables, codes and placements: streams bit for bit, decoded vectors exactly,
+    mean, both half-steps and S to 1e-6, no error bit."""
+    rng = np.random.default_rng(sweep)
+    done = 0
+    while done < 20:
+        bucket = int(rng.choice([64, 128, 256, 512, 1000, 1024, 2048, 3000, 4096, 6000, 8192, 12288, 16384, 20000, 32768, 65536]))
+        nseg = int(rng.integers(1, 5))
+        segs = [int(rng.integers(1, 6 * max(bucket, 2048)) // 4 * 4 + 4) for _ in range(nseg)]
+        segs[-1] += int(rng.integers(0, 4))
+        d = sum(segs)
+        if d > 300000:
+            continue
+        done += 1
+        K = int(rng.choice([1, 2, 3, 5, 8, 9]))
+        norm = int(rng.choice([oracle.NORM_L2, oracle.NORM_LINF, 1, 3]))
+        n_sym = int(rng.choice([2, 3, 9, 17, 33, 34, 65, 66, 127]))
+        kind = str(rng.choice(["uni", "exp", "rand"]))
+        levels = synth.levels_uniform(n_sym - 1)
+        if kind == "exp" and n_sym <= 25:
+            levels = synth.levels_exponential(n_sym - 1)
+        elif kind == "rand":
+            x = np.sort(rng.uniform(0, 1, n_sym - 2)).astype(np.float32)
+            cand = np.concatenate([[0], x, [1]]).astype(np.float32)
+            if (np.diff(cand) > 1e-6).all():
+                levels = cand
+        fixed, slotted = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+        seed, call = int(rng.integers(1, 1 << 30)), int(rng.integers(0, 100))
+        print("config", bucket, segs, K, norm, n_sym, kind, fixed, slotted, flush=True)
+        seg_arr = np.array(segs, np.uint64) if nseg > 1 else None
+        ctx, lay = make_ctx(qgx, d, K, bucket, norm, levels, seed, seg_arr, code=qgx.CODE_TABLE if fixed else qgx.CODE_ELIAS_OMEGA)
+        cl = cb = None
+        if fixed:
+            cl = np.full(n_sym, max(1, (n_sym - 1).bit_length()), np.uint8)
+            cb = np.arange(n_sym, dtype=np.uint32)
+            ctx.set_code_table(cl, cb)
+        V0 = synth.student_t3(K, d, seed=int(rng.integers(1, 1000)))
+        V1 = synth.student_t3(K, d, seed=int(rng.integers(1, 1000)))
+        if rng.integers(0, 4) == 0:
+            V0[0, :min(d, bucket)] = 0                    # a dead bucket
+        a, b, tmp = ctx.new_stream(slotted=slotted), ctx.new_stream(slotted=slotted), ctx.new_stream()
+        ctx.quantize_encode(dev(V0), call, a)
+        ctx.quantize_encode(dev(V1), call + 1, b)
+
+        def follow(V, c, s):
+            h = (ctx.compact(s, tmp) if slotted else s).to_host()
+            n_o = oracle.quantize(V, lay, norm, levels, seed, c)[0]
+            live = n_o > 0
+            assert (np.abs(h["norms"][live] - n_o[live]) / n_o[live]).max(initial=0) <= REL
+            _, idx, neg, _ = oracle.quantize(V, lay, norm, levels, seed, c, norms_in=h["norms"])
+            so = oracle.encode(idx, neg, lay, ctx.worst_words, code_len=cl, code_bits=cb)
+            assert_stream_equal(h, so, lay)
+            return oracle.decode(so, h["norms"], lay, levels, code_len=cl, code_bits=cb)[0]
+
+        Va, Vb = follow(V0, call, a), follow(V1, call + 1, b)
+        np.testing.assert_array_equal(ctx.decode(a).cpu().numpy(), Va)
+        assert rel_err(ctx.decode_average(b).cpu().numpy(), Vb.astype(np.float64).mean(axis=0)) <= REL
+        x1 = synth.gaussian_vector(d, seed=3)
+        ctx.state_init(dev(x1))
+        st = oracle.EGState(d, K, X1=x1)
+        Xh = torch.empty(d, device="cuda"); Xn = torch.empty(d, device="cuda")
+        ctx.eg_step(0, a, None, Xh)
+        assert rel_err(Xh.cpu().numpy(), st.half0(Va)) <= REL
+        prev = bool(rng.integers(0, 2))
+        ctx.eg_step(1, b, a if prev else None, Xn)
+        assert rel_err(Xn.cpu().numpy(), st.half1(Vb, Va if prev else None)) <= REL
+        assert abs(ctx.scalars()["S"] - st.S) <= REL * max(st.S, 1e-30)
+        assert ctx.poll_error() == 0
+        ctx.close()
+
+
 def test_gan_layout_full_iteration(qgx):
     """Workload 4 at a tenth of its size: 14 segments of very different scale, per-segment buckets of
     8192 with short ones, L-infinity norm, 16 exponential levels, K = 8, both half-steps."""
