@@ -436,12 +436,19 @@ __global__ __launch_bounds__(256) void k_fit(Tables* tab, const double* __restri
         M0[n_bins] = r0; M1[n_bins] = r1;
     }
     __syncthreads();
-    a0 = s_part0[tid]; a1 = s_part1[tid];
-    for (uint32_t b = b0; b < b1; ++b) {
-        M0[b] = a0; M1[b] = a1;
-        const double h = H[b];
-        a0 += h;
-        a1 += h * 0.5 * (bin_edge(b, n_bins) + bin_edge(b + 1, n_bins));
+    // Prefix at a bin = the thread's base plus the running sum inside its run of bins, the same running
+    // sum whose end gave the next thread's base: so the prefix never steps where the histogram is
+    // empty, also not from one thread's bins to the next's (a step of one rounding there would look
+    // like mass to the search below when a target sits at the top of the data's support).
+    {
+        const double base0 = s_part0[tid], base1 = s_part1[tid];
+        a0 = 0.0; a1 = 0.0;
+        for (uint32_t b = b0; b < b1; ++b) {
+            M0[b] = base0 + a0; M1[b] = base1 + a1;
+            const double h = H[b];
+            a0 += h;
+            a1 += h * 0.5 * (bin_edge(b, n_bins) + bin_edge(b + 1, n_bins));
+        }
     }
     __syncthreads();
 

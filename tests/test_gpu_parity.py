@@ -851,6 +851,26 @@ def test_random_configurations(qgx, sweep):
         ctx.close()
 
 
+def test_fit_levels_at_the_top_of_the_support(qgx):
+    """Uniform coordinates under L2 leave no mass above u = 0.04: levels that start above it come to
+    rest exactly at the top of the support, where the solver's prefix sums must be flat (a step of one
+    rounding between two threads' bins once sent a level a bin too far)."""
+    segs = np.array([42868, 22580], np.uint64)
+    d, K, bucket, n_bins, n_sym = int(segs.sum()), 3, 8192, 1024, 17
+    start = synth.levels_exponential(n_sym - 1)
+    ctx, lay = make_ctx(qgx, d, K, bucket, oracle.NORM_L2, start, seed=5, segs=segs)
+    V = synth.uniform_vectors(K, d, seed=58)
+    H_o = oracle.histogram(V, lay, oracle.NORM_L2, n_bins)
+    assert not H_o[oracle.bin_of(np.float32(0.0401), n_bins):].any()
+    for sweeps in (1, 10):
+        ctx.set_levels(start)
+        ctx.fit_levels(dev(V), n_sym, n_bins, sweeps=sweeps)
+        lv_g, lv_o = ctx.get_levels(), oracle.fit_levels(H_o, start, sweeps=sweeps)
+        np.testing.assert_allclose(lv_g, lv_o, rtol=REL, atol=1e-9)
+    assert ctx.poll_error() == 0
+    ctx.close()
+
+
 def test_gan_layout_full_iteration(qgx):
     """Workload 4 at a tenth of its size: 14 segments of very different scale, per-segment buckets of
     8192 with short ones, L-infinity norm, 16 exponential levels, K = 8, both half-steps."""
