@@ -319,7 +319,9 @@ qgx_status qgx_stream_sizes(const qgx_ctx* ctx, uint64_t* n_buckets, uint64_t* n
 qgx_status qgx_slot_words(const qgx_ctx* ctx, uint64_t* slot_words)
 {
     if (!ctx || !slot_words) return QGX_ERR_ARG;
-    if (!T(ctx).levels_set || (ctx->cfg.code == QGX_CODE_TABLE && !T(ctx).code_set)) return QGX_ERR_STATE;
+    if (!T(ctx).levels_set || (ctx->cfg.code == QGX_CODE_TABLE && !T(ctx).code_set))
+        return fail(const_cast<qgx_ctx*>(ctx), QGX_ERR_STATE,
+                    "qgx_slot_words: the slot follows the longest code word: set the level table (and the code table) first");
     *slot_words = chunk_slot_words(ctx);
     return QGX_OK;
 }
