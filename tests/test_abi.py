@@ -64,3 +64,11 @@ def test_create_rejects_bad_configurations_on_the_host():
     assert lib.qgx_create(None, None) == -1
     lib.qgx_last_error.restype = C.c_char_p
     assert lib.qgx_last_error(None) == b"null context"
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
