@@ -347,6 +347,15 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
             uint32_t win_b[3], e_b[3], win_pb[3], e_pb[3];
             Window wn = read_window(stage, p), wn_b = read_window(stage, pb);
             Window wn_p = read_window(stage_p, pp), wn_pb = read_window(stage_p, ppb);
+            // Squared differences: six at a time in binary32 (at most six roundings on a sum of
+            // non-negative terms), the groups in binary64.  The differences are scaled by a power of two
+            // taken from the larger of the lane's two norms, so that no square leaves the range of
+            // binary32 whatever the scale of the vectors; the sum is scaled back in binary64.
+            const uint32_t ex = min((__float_as_uint(fmaxf(n, np)) >> 23) & 0xFFu, 253u);   // (254 - ex = 0 would be no power of two)
+            const float down = __uint_as_float((254u - ex) << 23);                       // 2^(127 - ex)
+            const double up2 = __longlong_as_double((long long)(2 * (int)ex - 254 + 1023) << 52);   // 2^(2 ex - 254)
+            float sd32 = 0.0f;
+            double sw = 0.0;
 #pragma unroll
             for (int s = 0; s < kHalf; s += 3) {
                 float lv[3], lv_p[3], lv_b[3], lv_pb[3];
@@ -381,13 +390,16 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
                         const float val_b = symbol_value<false>(lv_b[i], win_b[i], e_b[i], n);
                         acc[s + i] += val;
                         acc[kHalf + s + i] += val_b;
-                        const double df = (double)symbol_value<true>(lv_p[i], win_p[i], e_p[i], np) - (double)val;
-                        sdiff = fma(df, df, sdiff);
-                        const double df_b = (double)symbol_value<true>(lv_pb[i], win_pb[i], e_pb[i], np) - (double)val_b;
-                        sdiff = fma(df_b, df_b, sdiff);
+                        const float df = (symbol_value<false>(lv_p[i], win_p[i], e_p[i], np) - val) * down;   // (a stray sign on a zero does not show in a difference)
+                        sd32 = fmaf(df, df, sd32);
+                        const float df_b = (symbol_value<false>(lv_pb[i], win_pb[i], e_pb[i], np) - val_b) * down;
+                        sd32 = fmaf(df_b, df_b, sd32);
                     }
                 }
+                sw += (double)sd32;
+                sd32 = 0.0f;
             }
+            sdiff = fma(sw, up2, sdiff);
             if (p != cur.p_mid || pp != prv.p_mid) malformed = true;
             p = pb;
             pp = ppb;

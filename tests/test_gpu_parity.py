@@ -521,6 +521,41 @@ def run_lockstep(qgx, game, levels, norm, bucket, T, seed, anchor, refit=None, n
     return worst, st
 
 
+@pytest.mark.parametrize("scale,bucket", [(1e25, 8192), (1e-30, 8192), (1e-30, 1024), (3e37, 4096)])
+def test_step_size_sum_at_extreme_scales(qgx, scale, bucket):
+    """S = sum of squared differences of the two half-steps' decoded vectors, whose squares overflow or
+    vanish in binary32 at these scales: the kernel's scaled partial sums still match the binary64 sum."""
+    d, K = 5 * 4096 + 1000, 3
+    levels = synth.levels_exponential(16)
+    ctx, lay = make_ctx(qgx, d, K, bucket, oracle.NORM_L2, levels, seed=21)
+    ctx.state_init(None)
+    st = oracle.EGState(d, K)
+    Va = (synth.student_t3(K, d, seed=31).astype(np.float64) * scale).astype(np.float32)
+    Vb = (synth.student_t3(K, d, seed=32).astype(np.float64) * scale).astype(np.float32)
+    assert np.isfinite(Va).all() and np.isfinite(Vb).all()
+    prev, cur = ctx.new_stream(slotted=True), ctx.new_stream(slotted=True)
+    Xh = torch.empty(d, device="cuda"); Xn = torch.empty(d, device="cuda")
+    ctx.quantize_encode(dev(Va), 0, prev)
+    ctx.eg_step(0, prev, None, Xh)
+    ctx.quantize_encode(dev(Vb), 1, cur)
+    ctx.eg_step(1, cur, prev, Xn)
+    tmp = ctx.new_stream()
+    hp = ctx.compact(prev, tmp).to_host()
+    _, _, _, so = oracle_stream(Va, lay, oracle.NORM_L2, levels, 21, 0, hp["norms"], ctx.worst_words)
+    Vhat0, _, _ = oracle.decode(so, hp["norms"], lay, levels)
+    hc = ctx.compact(cur, tmp).to_host()
+    _, _, _, so1 = oracle_stream(Vb, lay, oracle.NORM_L2, levels, 21, 1, hc["norms"], ctx.worst_words)
+    Vhat1, _, _ = oracle.decode(so1, hc["norms"], lay, levels)
+    st.half0(Vhat0)
+    st.half1(Vhat1, Vhat0)
+    sc = ctx.scalars()
+    assert st.S > 0 and np.isfinite(st.S)
+    assert abs(sc["S"] - st.S) <= REL * st.S
+    assert abs(sc["gamma"] - st.gamma) <= REL * st.gamma
+    assert ctx.poll_error() == 0
+    ctx.close()
+
+
 def test_bilinear_game_100_iterations_lockstep(qgx):
     """Workload 1: x, y in R^512, K = 4, L2, bucket = whole vector, 8 exponential levels, 100 iterations."""
     game = synth.BilinearGame(n=512, K=4, noise=0.1)
