@@ -185,7 +185,13 @@ qgx_status qgx_quantize_encode(qgx_ctx* ctx, const float* V, uint32_t call_id, c
  * main kernel: callers see ordinary stream order. */
 qgx_status qgx_decode(qgx_ctx* ctx, const qgx_stream* in, float* Vhat, void* stream);
 
-/* Aggregate of Algorithm 1: mean DEVICE [d] = (1/K) sum_k DEQ(CODE_k), decoded on the fly. */
+/* Aggregate of Algorithm 1: mean DEVICE [d] = (1/K) sum_k DEQ(CODE_k), decoded on the fly.
+ * The K values of a coordinate are added in binary32, in worker order; on layouts with too few
+ * chunks to fill the GPU the workers are split in two or four runs (as equal as K allows, the
+ * longer ones first), each added in order, and the runs' sums added in order (the same in
+ * qgx_eg_step).  The number of runs follows from the layout, K and the device, so results repeat bit
+ * for bit; QGX_KSPLIT=1, 2 or 4 in the environment when the context is created overrides the choice
+ * (for tests and timing; ignored when above K). */
 qgx_status qgx_decode_average(qgx_ctx* ctx, const qgx_stream* in, float* mean, void* stream);
 
 /* Adaptive levels, eq. (QAda): weighted histogram of the normalised coordinates of V (each bucket

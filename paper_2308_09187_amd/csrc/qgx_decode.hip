@@ -199,18 +199,25 @@ __device__ __forceinline__ void chunk_geometry(const Layout& lay, uint32_t c, ui
 // PREV (Half1): the previous half-step's streams are there; without them the vectors count as zero.
 // TWO: those were coded with another level table and code (a.tab_p) than the current ones.
 // WIDE: no code word has more than kWideBits bits, so the 8-byte decode table is there (one stream).
-template <DecMode MODE, bool PREV, bool TWO, bool WIDE>
+// KSPLIT = 2 or 4: that many neighbouring waves share a position, each takes a run of the workers (as
+// equal as K allows, the longer runs first), and they add their sums through LDS before the update
+// (for layouts with too few positions to fill the GPU's wave slots).
+template <DecMode MODE, bool PREV, bool TWO, bool WIDE, int KSPLIT = 1>
 __global__ __launch_bounds__(kDecWaves * kWave) __attribute__((amdgpu_waves_per_eu(MODE == DecMode::Half1 ? 2 : 4)))
 void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArgs a)
 {
     static_assert(!PREV || MODE == DecMode::Half1, "only the second half-step reads two streams");
     static_assert(!TWO || PREV, "a second table only comes with a second stream");
+    static_assert(KSPLIT == 1 || KSPLIT == 2 || KSPLIT == 4, "the waves of a workgroup in groups of 1, 2 or 4");
+    static_assert(KSPLIT == 1 || MODE != DecMode::Decode, "plain decoding has nothing to add up");
+    __shared__ double s_sd[KSPLIT > 1 ? kDecWaves : 1];
     extern __shared__ __align__(16) uint32_t s_dyn[];    // [waves][1 or 2][stage_stride]
     __shared__ __align__(16) unsigned char s_tab[kTabBytes];
     __shared__ __align__(16) unsigned char s_tab2[TWO ? kTabBytes : 16];
     const unsigned char* s_tab_p = TWO ? s_tab2 : s_tab;
 
     const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
+    const int part = w & (KSPLIT - 1);                   // this wave's place in its group
     constexpr int kBufs = PREV ? 2 : 1;
     constexpr bool kExact = MODE == DecMode::Decode;
     const uint32_t stage_words = a.stage_words;          // words a chunk of this code can take
@@ -235,16 +242,30 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
     const uint32_t g = (uint32_t)blockIdx.x * (blockDim.x >> 6) + (uint32_t)w;   // global wave number
     const uint32_t n_pos = lay.NC;
     uint32_t c, k_first, k_count;
+    bool mine;                                           // wave-uniform: a full position that this launch covers
     if (MODE == DecMode::Decode) {
-        if (g >= lay.K * n_pos) return;
+        mine = g < lay.K * n_pos;
         k_first = g / n_pos; c = g - k_first * n_pos; k_count = 1;
+    } else if (KSPLIT > 1) {
+        const uint32_t each = lay.K / KSPLIT, more = lay.K % KSPLIT;   // `more` runs of each + 1, then runs of each
+        c = g / KSPLIT;
+        mine = c < n_pos;
+        k_first = (uint32_t)part * each + min((uint32_t)part, more);
+        k_count = each + ((uint32_t)part < more ? 1u : 0u);
     } else {
-        if (g >= n_pos) return;
+        mine = g < n_pos;
         c = g; k_first = 0; k_count = lay.K;
     }
-    uint32_t clo, clen, bkt;
-    chunk_geometry(lay, c, clo, clen, bkt);
-    if (clen != (uint32_t)kChunk) return;                // wave-uniform: the ragged launch takes this position
+    uint32_t clo = 0, clen = 0, bkt = 0;
+    if (mine) chunk_geometry(lay, c, clo, clen, bkt);
+    mine = mine && clen == (uint32_t)kChunk;             // the ragged launch takes the other positions
+    if constexpr (KSPLIT == 1) {
+        if (!mine) return;
+    } else {
+        // the waves of a group meet at workgroup barriers below, so every wave of the workgroup
+        // goes there, the ones without a position with nothing to do on the way
+        if (!mine) k_count = 0;
+    }
     // A cursor from a corrupt table is pulled back so that a chain of 32 symbols from it stays inside
     // the buffer.  No valid cursor is beyond that: the last chain of a chunk starts after 4064 symbols
     // of at most sym_bits each, and the buffer holds 4096 of them.
@@ -263,14 +284,17 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
     constexpr bool kAhead = PREV;
     uint4 pre[kPre];
     uint4 pre_p[PREV ? kPre : 1];
-    ChunkRef cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, a.sub_end, k_first, c, lay.NC, stage_words, sc);
-    if constexpr (kAhead) prefetch_chunk(cr, pre);
-    SubMeta nxt = load_meta(a.sub_end, a.norms, k_first, c, bkt, lay, lane);
-    SubMeta nxt_p{0u, 0u, 0u, 0.0f};
-    if constexpr (PREV) {
-        const ChunkRef cp = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, a.sub_end_p, k_first, c, lay.NC, stage_words, sc);
-        prefetch_chunk(cp, pre_p);
-        nxt_p = load_meta(a.sub_end_p, a.norms_p, k_first, c, bkt, lay, lane);
+    ChunkRef cr{nullptr, 0u};
+    SubMeta nxt{0u, 0u, 0u, 0.0f}, nxt_p{0u, 0u, 0u, 0.0f};
+    if (k_count != 0u) {                                  // (always, unless KSPLIT left this wave without work)
+        cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, a.sub_end, k_first, c, lay.NC, stage_words, sc);
+        if constexpr (kAhead) prefetch_chunk(cr, pre);
+        nxt = load_meta(a.sub_end, a.norms, k_first, c, bkt, lay, lane);
+        if constexpr (PREV) {
+            const ChunkRef cp = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, a.sub_end_p, k_first, c, lay.NC, stage_words, sc);
+            prefetch_chunk(cp, pre_p);
+            nxt_p = load_meta(a.sub_end_p, a.norms_p, k_first, c, bkt, lay, lane);
+        }
     }
 
     for (uint32_t kk = 0; kk < k_count; ++kk) {
@@ -418,23 +442,52 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
     const float gam = sc->gamma_f;
     if constexpr (MODE == DecMode::Half1) {
         sdiff = wave_sum(sdiff);
-        if (lane == 0) a.s_partial[c] = sdiff;
+        if constexpr (KSPLIT > 1) {
+            if (lane == 0) s_sd[w] = sdiff;               // joined below, after the first barrier
+        } else {
+            if (lane == 0) a.s_partial[c] = sdiff;
+        }
     }
     // Lane L holds coordinates 64L..64L+63 of the chunk.  Through LDS, 16 symbols at a time, the
     // wave turns them so that four consecutive lanes own 16 consecutive floats: global accesses
     // then touch whole 64-byte pieces instead of 16 bytes per 256.
+    // KSPLIT: all waves of the group put their sums there, and after a barrier each of them adds them
+    // up (in the order of the workers' runs) for its share of the rows and does the update for those.
     float* tr = reinterpret_cast<float*>(stage);          // 64 rows of 20 floats (16 + pad), 5120 bytes
+    const float* tr0 = KSPLIT > 1 ? reinterpret_cast<const float*>(s_dyn + (size_t)(w - part) * kBufs * stage_stride) : tr;
+    const size_t tr_step = (size_t)kBufs * stage_stride;  // from one wave's buffer to the next, in words
+    const float scale = KSPLIT > 1 ? 1.0f : invK;         // KSPLIT: the division comes after the group's sum
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
+        if (mine) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            *reinterpret_cast<float4*>(tr + lane * 20 + 4 * j) =
-                make_float4(acc[16 * q + 4 * j] * invK, acc[16 * q + 4 * j + 1] * invK,
-                            acc[16 * q + 4 * j + 2] * invK, acc[16 * q + 4 * j + 3] * invK);
+            for (int j = 0; j < 4; ++j)
+                *reinterpret_cast<float4*>(tr + lane * 20 + 4 * j) =
+                    make_float4(acc[16 * q + 4 * j] * scale, acc[16 * q + 4 * j + 1] * scale,
+                                acc[16 * q + 4 * j + 2] * scale, acc[16 * q + 4 * j + 3] * scale);
+        }
+        if constexpr (KSPLIT > 1) {
+            __syncthreads();
+            if (MODE == DecMode::Half1 && q == 0 && mine && part == 0 && lane == 0) {
+                double sd = s_sd[w];
+                for (int j = 1; j < KSPLIT; ++j) sd += s_sd[w + j];
+                a.s_partial[c] = sd;
+            }
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
+            if (KSPLIT > 1 && i * KSPLIT / 4 != part) continue;   // 64 / KSPLIT rows for each wave of the group
+            if (!mine) continue;
             const int row = (lane >> 2) + 16 * i;             // whose 16 symbols
-            const float4 m = *reinterpret_cast<const float4*>(tr + row * 20 + 4 * (lane & 3));
+            float4 m = *reinterpret_cast<const float4*>(tr0 + row * 20 + 4 * (lane & 3));
+            if constexpr (KSPLIT > 1) {
+#pragma unroll
+                for (int j = 1; j < KSPLIT; ++j) {
+                    const float4 h = *reinterpret_cast<const float4*>(tr0 + j * tr_step + row * 20 + 4 * (lane & 3));
+                    m.x += h.x; m.y += h.y; m.z += h.z; m.w += h.w;
+                }
+                m.x *= invK; m.y *= invK; m.z *= invK; m.w *= invK;
+            }
             const uint32_t at = clo + 64u * (uint32_t)row + 16u * (uint32_t)q + 4u * (uint32_t)(lane & 3);
             if (MODE == DecMode::Average) {
                 *reinterpret_cast<float4*>(a.out + at) = m;
@@ -458,6 +511,9 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
                 y.x -= m.x; y.y -= m.y; y.z -= m.z; y.w -= m.w;
                 *reinterpret_cast<float4*>(a.Y + at) = y;
             }
+        }
+        if constexpr (KSPLIT > 1) {
+            if (q < 3) __syncthreads();                       // the partners have read this quarter
         }
     }
 }
@@ -641,29 +697,39 @@ void k_decode_ragged(Layout lay, const Tables* __restrict__ tab, Scalars* sc, De
     }
 }
 
-template <DecMode MODE, bool PREV, bool TWO, bool WIDE>
+template <DecMode MODE, bool PREV, bool TWO, bool WIDE, int KSPLIT>
 static hipError_t launch_full_as(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
 {
     if (lay.n_ragged == lay.NC) return hipSuccess;
     const size_t lds = (size_t)kDecWaves * (PREV ? 2 : 1) * a.stage_stride * sizeof(uint32_t);
     static size_t lds_allowed = 0;                        // the limit is per kernel: raised when a launch needs more
     if (lds > lds_allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<MODE, PREV, TWO, WIDE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<MODE, PREV, TWO, WIDE, KSPLIT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         lds_allowed = lds;
     }
-    const uint64_t nwork = (MODE == DecMode::Decode) ? (uint64_t)lay.K * lay.NC : lay.NC;
+    const uint64_t nwork = (MODE == DecMode::Decode) ? (uint64_t)lay.K * lay.NC : (uint64_t)lay.NC * (uint32_t)KSPLIT;
     const uint32_t grid = (uint32_t)((nwork + kDecWaves - 1) / kDecWaves);
-    hipLaunchKernelGGL((k_decode<MODE, PREV, TWO, WIDE>), dim3(grid), dim3(kDecWaves * kWave), lds, st, lay, tab, sc, a);
+    hipLaunchKernelGGL((k_decode<MODE, PREV, TWO, WIDE, KSPLIT>), dim3(grid), dim3(kDecWaves * kWave), lds, st, lay, tab, sc, a);
     return hipGetLastError();
 }
 
 template <DecMode MODE, bool PREV, bool TWO>
 static hipError_t launch_full(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
 {
-    if (a.wide) return launch_full_as<MODE, PREV, TWO, true>(lay, tab, sc, a, st);
-    return launch_full_as<MODE, PREV, TWO, false>(lay, tab, sc, a, st);
+    if constexpr (MODE != DecMode::Decode) {
+        if (a.ksplit == 2u) {
+            if (a.wide) return launch_full_as<MODE, PREV, TWO, true, 2>(lay, tab, sc, a, st);
+            return launch_full_as<MODE, PREV, TWO, false, 2>(lay, tab, sc, a, st);
+        }
+        if (a.ksplit == 4u) {
+            if (a.wide) return launch_full_as<MODE, PREV, TWO, true, 4>(lay, tab, sc, a, st);
+            return launch_full_as<MODE, PREV, TWO, false, 4>(lay, tab, sc, a, st);
+        }
+    }
+    if (a.wide) return launch_full_as<MODE, PREV, TWO, true, 1>(lay, tab, sc, a, st);
+    return launch_full_as<MODE, PREV, TWO, false, 1>(lay, tab, sc, a, st);
 }
 
 template <DecMode MODE, bool PREV, bool TWO>

@@ -156,6 +156,7 @@ struct DecodeArgs {
                                 // plus room for 32 symbols and a window past its end
     uint32_t rag_stride;
     uint32_t wide;              // the 8-byte decode table of the current streams' code is valid (Tables::wide_ok)
+    uint32_t ksplit;            // fused modes: 1, 2 or 4 waves per full position, a run of the workers each
 };
 
 hipError_t launch_build_tables(Tables* tab, hipStream_t st);

@@ -3,6 +3,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -23,6 +24,8 @@ struct qgx_ctx {
     qgx_config cfg{};
     std::vector<uint64_t> seg;
     int device = 0;
+    uint32_t n_simd = 1024;          // SIMDs of the device (four per compute unit)
+    int ksplit_forced = -1;          // QGX_KSPLIT=1|2|4 in the environment at qgx_create, else -1: by the rule
     Layout lay{};
     uint32_t* d_layout = nullptr;
     Tables* d_tabs = nullptr;        // [QGX_TABLES]
@@ -227,6 +230,13 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     c->worst_words = worst;
 
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return QGX_ERR_HIP; }
+    {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess && cus > 0)
+            c->n_simd = 4u * (uint32_t)cus;
+        const char* f = getenv("QGX_KSPLIT");
+        if (f && (f[0] == '1' || f[0] == '2' || f[0] == '4') && f[1] == 0) c->ksplit_forced = f[0] - '0';
+    }
     const size_t n_lay = (size_t)(NB + 1) * 2 + (NC + 1) + NC + ragged.size() + 1;
     std::vector<uint32_t> flat;
     flat.reserve(n_lay);
@@ -511,6 +521,20 @@ static void fill_decode_args(const qgx_ctx* ctx, DecodeArgs& a, const qgx_stream
     a.rag_words = ((ctx->lay.max_ragged * a.sym_bits + 31) / 32 + a.sym_bits + 2 + 3) / 4 * 4;
     a.rag_stride = (a.rag_words + a.rag_words / 16 + 12 + 3) / 4 * 4;
     a.wide = (T(ctx).wide && (!prev || ctx->ts[ctx->sel_prev].wide)) ? 1u : 0u;   // one kernel variant reads both streams
+    // Full positions against the wave slots the kernel can hold (4 per SIMD with one stream, 2 with two):
+    // a launch takes about as long as its rounds of waves, counted whole; with a position given to f
+    // waves, a run of the workers each, the rounds are 1/f as long and the last one is rounded up to
+    // 1/f of one.  Taken (f = 2 or 4) when that saves more than the joining costs.
+    a.ksplit = 1u;
+    {
+        const double r = (double)(ctx->lay.NC - ctx->lay.n_ragged) / ((double)ctx->n_simd * (prev ? 2.0 : 4.0));
+        double best = std::ceil(r);
+        for (uint32_t f = 2; f <= 4u && f <= ctx->lay.K; f *= 2) {
+            const double cost = std::ceil(f * r) / f * (f == 2 ? 1.05 : 1.10);
+            if (cost < best) { best = cost; a.ksplit = f; }
+        }
+        if (ctx->ksplit_forced >= 0 && (uint32_t)ctx->ksplit_forced <= ctx->lay.K) a.ksplit = (uint32_t)ctx->ksplit_forced;
+    }
     a.norms = cur->norms; a.chunk_off = cur->chunk_off; a.sub_end = cur->sub_end; a.payload = cur->payload;
     a.cap_words = cur->payload_words_per_worker;
     if (prev) {

@@ -585,6 +585,32 @@ def test_lockstep_with_65_levels(qgx):
     assert worst <= REL
 
 
+@pytest.mark.parametrize("K,bucket,n_levels,waves", [(2, 4096, 16, 2), (5, 8192, 16, 2), (8, 1024, 16, 4), (3, 8192, 64, 2),
+                                                     (7, 4096, 16, 4), (4, 8192, 64, 4)])
+def test_positions_shared_by_several_waves(qgx, monkeypatch, K, bucket, n_levels, waves):
+    """Layouts with few chunk positions give every full position to two or four waves, a run of the
+    workers each, which join their sums before the update; here that is forced (the library reads
+    QGX_KSPLIT when a context is made), for K that does and does not divide evenly, both decode tables,
+    buckets sharing chunks, and with ragged positions beside the full ones.  The same lock-step
+    comparison as everywhere else; the mean over the workers goes through decode_average as well."""
+    monkeypatch.setenv("QGX_KSPLIT", str(waves))
+    d = 5 * 8192 + 1500
+    game = synth.QuadraticGame(d=d, K=K)
+    game.x1 = lambda: np.zeros(game.d, np.float32)
+    levels = synth.levels_uniform(n_levels) if n_levels == 64 else synth.levels_exponential(n_levels)
+    worst, st = run_lockstep(qgx, game, levels, oracle.NORM_L2, bucket, 3, seed=8, anchor=False, refit=2)
+    assert worst <= REL
+    ctx, lay = make_ctx(qgx, d, K, bucket, oracle.NORM_L2, levels, seed=8)
+    V = game.dual_vectors(np.zeros(d, np.float32), 0)
+    out = ctx.new_stream()
+    ctx.quantize_encode(dev(V), 0, out)
+    Vhat = ctx.decode(out).cpu().numpy().astype(np.float64)
+    mean = ctx.decode_average(out).cpu().numpy()
+    assert rel_err(mean, Vhat.mean(axis=0)) <= REL
+    assert ctx.poll_error() == 0
+    ctx.close()
+
+
 def test_optimistic_dual_averaging_lockstep(qgx):
     """The optimistic dual averaging case of eq. (Q-GenX): the first half-step reuses the previous
     iteration's coded feedback g_{k,t-1/2} (nothing at t = 1), so every iteration codes once; the step
