@@ -586,7 +586,7 @@ def test_lockstep_with_65_levels(qgx):
 
 
 @pytest.mark.parametrize("K,bucket,n_levels,waves", [(2, 4096, 16, 2), (5, 8192, 16, 2), (8, 1024, 16, 4), (3, 8192, 64, 2),
-                                                     (7, 4096, 16, 4), (4, 8192, 64, 4)])
+                                                     (7, 4096, 16, 4), (4, 8192, 64, 4), (8, 1024, 16, 1), (3, 8192, 64, 1)])
 def test_positions_shared_by_several_waves(qgx, monkeypatch, K, bucket, n_levels, waves):
     """Layouts with few chunk positions give every full position to two or four waves, a run of the
     workers each, which join their sums before the update; here that is forced (the library reads
@@ -839,11 +839,14 @@ def test_two_level_tables_lockstep(qgx, fitted_code, n0):
     ctx.close()
 
 
-@pytest.mark.parametrize("sweep", [1, 2])
-def test_random_configurations(qgx, sweep):
+@pytest.mark.parametrize("sweep,waves", [(1, None), (2, None), (1, 1), (2, 1), (3, 2)])
+def test_random_configurations(qgx, monkeypatch, sweep, waves):
     """Seeded random layouts (bucket sizes of every kind, several tensors with ragged ends), worker
     counts, norms, level tables, codes and placements: streams bit for bit, decoded vectors exactly,
-    mean, both half-steps and S to 1e-6, no error bit."""
+    mean, both half-steps and S to 1e-6, no error bit.  Layouts this small give a chunk position to
+    several waves; `waves` = 1 makes the library take the one-wave kernels of large layouts instead."""
+    if waves is not None:
+        monkeypatch.setenv("QGX_KSPLIT", str(waves))
     rng = np.random.default_rng(sweep)
     done = 0
     while done < 20:
