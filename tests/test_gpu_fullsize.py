@@ -1,8 +1,8 @@
 """Parity at full size and in the benchmark's launch configurations: the headline workload (K = 8
 vectors of d = 2^24 coordinates, buckets of 16384, L2, 33-symbol fitted table; slotted chunk placement
 as timed, and compact) and the shape of the large quadratic game (K = 16 vectors of d = 2^26, buckets of
-65536, 65 fitted levels).  Properties that hold at any size are checked over the whole output; sampled
-buckets and chunks are recomputed one by one by the oracle."""
+65536, 65 fitted levels), the latter also as 50 iterations with refits.  Properties that hold at any
+size are checked over the whole output; sampled buckets and chunks are recomputed one by one by the oracle."""
 import numpy as np
 import pytest
 
@@ -111,4 +111,103 @@ def test_full_size_sampled_against_oracle(K, logd, bucket, n_sym, slotted, fitte
         want = st.half0(np.stack(dec))
         got = Xh[c * 4096:(c + 1) * 4096].cpu().numpy()
         assert np.linalg.norm(got - want) <= REL * np.linalg.norm(want)
+    ctx.close()
+
+
+def test_large_quadratic_game_50_iterations_on_device():
+    """The large strongly monotone game at its real shape: z in R^(2^26), F(z) = Mz + b with 2x2 blocks
+    [[mu, a], [-a, mu]], K = 16 workers with N(0, 0.05^2) noise, buckets of 65536, L2, 65 levels refitted
+    every 10 iterations, 50 iterations of eq. (Q-GenX) with X_1 = 0.  The operator and the noise are
+    torch device code outside the library (the caller's part); every iterate stays on the device.
+    Whole-run properties (S grows, gamma shrinks, t counts, no error bit, the refits move the table),
+    and at iteration 11, right after a refit, sampled buckets of the coded stream and a sampled chunk of
+    the second half-step are recomputed by the oracle."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2308_09187_amd import qgx
+    qgx.load()
+    K, d, bucket, n_sym, seed, T = 16, 1 << 26, 65536, 65, 77, 50
+    game = synth.QuadraticGame(d, K)
+    a_d, b_d = torch.from_numpy(game.a).cuda(), torch.from_numpy(game.b).cuda()
+    mu, noise = game.mu, game.noise
+
+    def operator(z):
+        z2 = z.view(-1, 2)
+        f = torch.empty_like(z2)
+        f[:, 0] = mu * z2[:, 0] + a_d * z2[:, 1]
+        f[:, 1] = mu * z2[:, 1] - a_d * z2[:, 0]
+        return f.view(-1) + b_d
+
+    V = torch.empty(K, d, device="cuda")
+    gen = torch.Generator(device="cuda")
+
+    def dual_vectors(z, call):
+        gen.manual_seed(4200 + call)
+        V.normal_(0.0, noise, generator=gen)
+        V.add_(operator(z))
+        return V
+
+    ctx = qgx.Context(d, K, bucket, norm=qgx.NORM_L2, seed=seed)
+    ctx.set_levels(synth.levels_exponential(n_sym - 1))
+    ctx.state_init(None)
+    prev, cur = ctx.new_stream(slotted=True), ctx.new_stream(slotted=True)
+    X = torch.zeros(d, device="cuda")
+    Xh, Xn = torch.empty(d, device="cuda"), torch.empty(d, device="cuda")
+    res0 = float(torch.linalg.vector_norm(operator(X).double()))
+    S_last, gamma_last, tables = 0.0, float(K), []
+    lay_b, lay_c, CPB = oracle.layout(bucket, bucket), oracle.layout(4096, 4096), bucket // 4096
+    rng = np.random.default_rng(1)
+    for t in range(T):
+        V0 = dual_vectors(X, 2 * t)
+        if t % 10 == 0:
+            ctx.fit_levels(V0, n_sym, 4096, sweeps=8)
+            tables.append(ctx.get_levels())
+            assert (np.diff(tables[-1]) > 0).all() and tables[-1][0] == 0 and tables[-1][-1] == 1
+        ctx.quantize_encode(V0, 2 * t, prev)
+        if t == 10:                                  # sampled buckets of the stream, bit for bit
+            levels = tables[-1]
+            h = prev.to_host()
+            for k, b in [(0, 0), (K - 1, ctx.NB - 1), (int(rng.integers(K)), int(rng.integers(ctx.NB)))]:
+                print("bucket", k, b, flush=True)
+                vb = V0[k, b * bucket:(b + 1) * bucket].cpu().numpy()[None, :]
+                n_o, _, _, _ = oracle.quantize(vb, lay_b, oracle.NORM_L2, levels, seed, 2 * t, k0=k, i0=b * bucket)
+                assert abs(h["norms"][k, b] - n_o[0, 0]) <= REL * n_o[0, 0]
+                _, idx, neg, _ = oracle.quantize(vb, lay_b, oracle.NORM_L2, levels, seed, 2 * t,
+                                                 norms_in=h["norms"][k:k + 1, b:b + 1], k0=k, i0=b * bucket)
+                so = oracle.encode(idx, neg, lay_b, cap_words=bucket)
+                ms = mini_stream(h, k, b * CPB, (b + 1) * CPB)
+                np.testing.assert_array_equal(ms.sub_end, so.sub_end)
+                np.testing.assert_array_equal(ms.payload[0], so.payload[0, :ms.payload.shape[1]])
+        ctx.eg_step(0, prev, None, Xh)
+        V1 = dual_vectors(Xh, 2 * t + 1)
+        ctx.quantize_encode(V1, 2 * t + 1, cur)
+        if t == 10:
+            Y_before, _ = ctx.state_export()
+        ctx.eg_step(1, cur, prev, Xn)
+        if t == 10:                                  # a sampled chunk of the second half-step
+            Y_after, _ = ctx.state_export()
+            hc = cur.to_host()
+            c = int(rng.integers(ctx.NC))
+            print("chunk", c, flush=True)
+            dec_c, dec_p = [], []
+            for k in range(K):
+                nb = slice(c // CPB, c // CPB + 1)
+                dec_c.append(oracle.decode(mini_stream(hc, k, c, c + 1), hc["norms"][k:k + 1, nb], lay_c, levels)[0][0])
+                dec_p.append(oracle.decode(mini_stream(h, k, c, c + 1), h["norms"][k:k + 1, nb], lay_c, levels)[0][0])
+            sl = slice(c * 4096, (c + 1) * 4096)
+            want = Y_before[sl].cpu().numpy().astype(np.float64) - np.mean(np.stack(dec_c), axis=0)
+            got = Y_after[sl].cpu().numpy()
+            assert np.linalg.norm(got - want) <= REL * np.linalg.norm(want)
+            del Y_before, Y_after
+        sc = ctx.scalars()
+        assert sc["S"] > S_last and sc["gamma"] < gamma_last and sc["t"] == t + 2
+        assert abs(sc["gamma"] - K / np.sqrt(1.0 + sc["S"])) <= 1e-12 * sc["gamma"]
+        S_last, gamma_last = sc["S"], sc["gamma"]
+        X, Xn = Xn, X
+    assert ctx.poll_error() == 0
+    assert len(tables) == 5 and all(np.abs(tables[i] - tables[0]).max() > 0 for i in range(1, 5))
+    res = float(torch.linalg.vector_norm(operator(X).double()))
+    print("residual |F(X)|: %.6e at X_1, %.6e after %d iterations; gamma_T = %.3e" % (res0, res, T, gamma_last), flush=True)
+    # the drift of the iterates is along -b and lowers |F| by about gamma_T T mu (the noise is orthogonal to it to first order)
+    assert np.isfinite(res) and res < res0
     ctx.close()
