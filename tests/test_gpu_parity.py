@@ -963,3 +963,37 @@ def test_gan_layout_full_iteration(qgx):
     assert abs(sc["S"] - st.S) <= REL * st.S
     assert ctx.poll_error() == 0
     ctx.close()
+
+
+def test_gan_layout_full_size(qgx):
+    """Workload 4 at its full size and in the configuration the benchmark times (9 855 936 coordinates in
+    14 tensors, 1207 buckets per worker with four short ones, K = 8, L-infinity, 16 exponential levels,
+    slotted placement): the whole iteration against the oracle, every stream bit and both half-steps."""
+    segs = synth.GAN_SEGMENTS.astype(np.uint64)
+    d, K = int(segs.sum()), 8
+    levels = synth.levels_exponential(16)
+    ctx, lay = make_ctx(qgx, d, K, 8192, oracle.NORM_LINF, levels, seed=31, segs=segs)
+    assert ctx.NB == 1207
+    ctx.state_init(None)
+    st = oracle.EGState(d, K)
+    V0 = synth.gan_dual_vectors(K, 0)
+    V1 = synth.gan_dual_vectors(K, 1)
+    a, b, tmp = ctx.new_stream(slotted=True), ctx.new_stream(slotted=True), ctx.new_stream()
+    Xh = torch.empty(d, device="cuda"); Xn = torch.empty(d, device="cuda")
+    ctx.quantize_encode(dev(V0), 0, a); ctx.eg_step(0, a, None, Xh)
+    ctx.quantize_encode(dev(V1), 1, b); ctx.eg_step(1, b, a, Xn)
+    ha = ctx.compact(a, tmp).to_host()
+    hb = ctx.compact(b, tmp).to_host()
+    print("oracle", flush=True)
+    _, _, _, sa = oracle_stream(V0, lay, oracle.NORM_LINF, levels, 31, 0, ha["norms"], ctx.worst_words)
+    _, _, _, sb = oracle_stream(V1, lay, oracle.NORM_LINF, levels, 31, 1, hb["norms"], ctx.worst_words)
+    np.testing.assert_array_equal(ha["norms"], oracle.quantize(V0, lay, oracle.NORM_LINF, levels, 31, 0)[0])
+    assert_stream_equal(ha, sa, lay); assert_stream_equal(hb, sb, lay)
+    Va, _, _ = oracle.decode(sa, ha["norms"], lay, levels)
+    Vb, _, _ = oracle.decode(sb, hb["norms"], lay, levels)
+    assert rel_err(Xh.cpu().numpy(), st.half0(Va)) <= REL
+    assert rel_err(Xn.cpu().numpy(), st.half1(Vb, Va)) <= REL
+    sc = ctx.scalars()
+    assert abs(sc["S"] - st.S) <= REL * st.S and abs(sc["gamma"] - st.gamma) <= REL * st.gamma
+    assert ctx.poll_error() == 0
+    ctx.close()
