@@ -997,3 +997,41 @@ def test_gan_layout_full_size(qgx):
     assert abs(sc["S"] - st.S) <= REL * st.S and abs(sc["gamma"] - st.gamma) <= REL * st.gamma
     assert ctx.poll_error() == 0
     ctx.close()
+
+
+def test_headline_workload_whole_output(qgx):
+    """The benchmark's own configuration in full (K = 8 vectors of 2^24 Student-t(3) coordinates, buckets
+    of 16384, L2, 33 fitted levels, slotted placement): every norm to 1e-6, every bit of the coded streams,
+    and the whole first and second half-step against the oracle (the oracle takes a few seconds)."""
+    K, d, bucket, n_sym, seed = 8, 1 << 24, 16384, 33, 2308
+    V0d = synth.student_t3_device(K, d, seed=20)
+    V1d = synth.student_t3_device(K, d, seed=21)
+    ctx, lay = make_ctx(qgx, d, K, bucket, oracle.NORM_L2, synth.levels_exponential(n_sym - 1), seed=seed)
+    ctx.fit_levels(V0d, n_sym, 4096, sweeps=10)
+    levels = ctx.get_levels()
+    ctx.state_init(None)
+    st = oracle.EGState(d, K)
+    a, b, tmp = ctx.new_stream(slotted=True), ctx.new_stream(slotted=True), ctx.new_stream()
+    Xh = torch.empty(d, device="cuda"); Xn = torch.empty(d, device="cuda")
+    ctx.quantize_encode(V0d, 0, a); ctx.eg_step(0, a, None, Xh)
+    ctx.quantize_encode(V1d, 1, b); ctx.eg_step(1, b, a, Xn)
+    ha = ctx.compact(a, tmp).to_host()
+    hb = ctx.compact(b, tmp).to_host()
+    V0, V1 = V0d.cpu().numpy(), V1d.cpu().numpy()
+    del V0d, V1d
+    print("oracle", flush=True)
+    n_o = oracle.quantize(V0, lay, oracle.NORM_L2, levels, seed, 0)[0]
+    assert np.max(np.abs(ha["norms"] - n_o) / n_o) <= REL
+    _, _, _, sa = oracle_stream(V0, lay, oracle.NORM_L2, levels, seed, 0, ha["norms"], ctx.worst_words)
+    assert_stream_equal(ha, sa, lay)
+    Va, _, _ = oracle.decode(sa, ha["norms"], lay, levels)
+    assert rel_err(Xh.cpu().numpy(), st.half0(Va)) <= REL
+    del V0, sa
+    _, _, _, sb = oracle_stream(V1, lay, oracle.NORM_L2, levels, seed, 1, hb["norms"], ctx.worst_words)
+    assert_stream_equal(hb, sb, lay)
+    Vb, _, _ = oracle.decode(sb, hb["norms"], lay, levels)
+    assert rel_err(Xn.cpu().numpy(), st.half1(Vb, Va)) <= REL
+    sc = ctx.scalars()
+    assert abs(sc["S"] - st.S) <= REL * st.S and abs(sc["gamma"] - st.gamma) <= REL * st.gamma
+    assert ctx.poll_error() == 0
+    ctx.close()
