@@ -99,7 +99,7 @@ typedef enum { QGX_CODE_ELIAS_OMEGA = 0, QGX_CODE_TABLE = 1 } qgx_code; /* Psi, 
 
 typedef struct {
     uint64_t d;                   /* coordinates per worker, 1 <= d < 2^31 */
-    uint32_t K;                   /* workers, 1 <= K <= 65535 */
+    uint32_t K;                   /* workers, 1 <= K <= 65535; K * buckets and K * chunks per worker below 2^31 */
     uint32_t bucket;              /* coordinates per bucket, multiple of 4, <= QGX_MAX_BUCKET */
     uint32_t n_segments;          /* 0 or 1 => one segment of length d */
     const uint64_t* segment_len;  /* HOST, n_segments lengths summing to d; all but the last multiples of 4 */

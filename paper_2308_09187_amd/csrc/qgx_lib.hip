@@ -226,7 +226,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     bchunk0.push_back((uint32_t)cstart.size());
     cstart.push_back((uint32_t)pos);
     const uint32_t NB = (uint32_t)bstart.size() - 1, NC = (uint32_t)cbucket.size();
-    if ((uint64_t)NB * cfg->K >= (1ull << 31)) { delete c; return QGX_ERR_ARG; }
+    if ((uint64_t)NB * cfg->K >= (1ull << 31) || (uint64_t)NC * cfg->K >= (1ull << 31)) { delete c; return QGX_ERR_ARG; }
     c->worst_words = worst;
 
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return QGX_ERR_HIP; }

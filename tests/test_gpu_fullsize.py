@@ -211,3 +211,57 @@ def test_large_quadratic_game_50_iterations_on_device():
     # the drift of the iterates is along -b and lowers |F| by about gamma_T T mu (the noise is orthogonal to it to first order)
     assert np.isfinite(res) and res < res0
     ctx.close()
+
+
+def test_longest_vector():
+    """The largest d the boundary takes (2^31 - 4 coordinates, here with K = 1, buckets of 65536, the last
+    one short and ending in a chunk of 4092): coordinate indices, Philox counters and byte offsets near the
+    top of their ranges.  Sampled buckets of the stream (the first, one in the middle, the last two) and the
+    chunks of the first half-step under them are recomputed by the oracle; sizes and totals over the whole."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2308_09187_amd import qgx
+    qgx.load()
+    K, d, bucket, seed, call = 1, (1 << 31) - 4, 65536, 99, 3
+    V = torch.empty(K, d, device="cuda")
+    V.normal_(0.0, 1e-3, generator=torch.Generator(device="cuda").manual_seed(5))
+    levels = synth.levels_exponential(16)
+    ctx = qgx.Context(d, K, bucket, norm=qgx.NORM_L2, seed=seed)
+    ctx.set_levels(levels)
+    NB, NC, CPB = ctx.NB, ctx.NC, bucket // 4096
+    assert NB == 32768 and NC == 524288
+    x1 = torch.empty(d, device="cuda")
+    x1.normal_(0.0, 1.0, generator=torch.Generator(device="cuda").manual_seed(6))
+    ctx.state_init(x1)
+    a = ctx.new_stream(slotted=True)
+    Xh = torch.empty(d, device="cuda")
+    print("encode + half-step", flush=True)
+    ctx.quantize_encode(V, call, a)
+    ctx.eg_step(0, a, None, Xh)
+    torch.cuda.synchronize()
+    assert ctx.poll_error() == 0
+    h = a.to_host()
+    bits = h["sub_end"][:, :, -1].astype(np.int64)
+    assert ctx.scalars(want_bits=True)["total_bits"] == int(bits.sum())
+    assert (np.diff(h["chunk_off"].astype(np.int64), axis=1) == ctx.slot_words()).all()
+    assert np.isfinite(h["norms"]).all() and (h["norms"] > 0).all()
+    lay_c = oracle.layout(4096, 4096)
+    for b in [0, NB // 2 + 1, NB - 2, NB - 1]:
+        print("bucket", b, flush=True)
+        lo, hi = b * bucket, min((b + 1) * bucket, d)
+        vb = V[0, lo:hi].cpu().numpy()[None, :]
+        lay_b = oracle.layout(hi - lo, bucket)
+        n_o, _, _, _ = oracle.quantize(vb, lay_b, oracle.NORM_L2, levels, seed, call, k0=0, i0=lo)
+        assert abs(h["norms"][0, b] - n_o[0, 0]) <= REL * n_o[0, 0]
+        _, idx, neg, _ = oracle.quantize(vb, lay_b, oracle.NORM_L2, levels, seed, call,
+                                         norms_in=h["norms"][0:1, b:b + 1], k0=0, i0=lo)
+        so = oracle.encode(idx, neg, lay_b, cap_words=bucket)
+        ms = mini_stream(h, 0, b * CPB, b * CPB + lay_b.NC)
+        np.testing.assert_array_equal(ms.sub_end, so.sub_end)
+        np.testing.assert_array_equal(ms.payload[0], so.payload[0, :ms.payload.shape[1]])
+        Vhat, _, _ = oracle.decode(so, h["norms"][0:1, b:b + 1], lay_b, levels)
+        st = oracle.EGState(hi - lo, K, X1=x1[lo:hi].cpu().numpy())
+        want = st.half0(Vhat)
+        got = Xh[lo:hi].cpu().numpy()
+        assert np.linalg.norm(got - want) <= REL * np.linalg.norm(want)
+    ctx.close()
