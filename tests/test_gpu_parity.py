@@ -1035,3 +1035,39 @@ def test_headline_workload_whole_output(qgx):
     assert abs(sc["S"] - st.S) <= REL * st.S and abs(sc["gamma"] - st.gamma) <= REL * st.gamma
     assert ctx.poll_error() == 0
     ctx.close()
+
+
+@pytest.mark.parametrize("slotted", [True, False])
+def test_most_workers(qgx, slotted):
+    """K = 65535, the most the boundary takes, on a layout of one full chunk position and a ragged one
+    of four coordinates: every stream bit for bit; the mean and the half-steps to 1e-6 sqrt(K/16), the
+    growth of a binary32 sum over K terms (the oracle adds in binary64)."""
+    K, d, bucket, seed = 65535, 4100, 4096, 12
+    tol = REL * np.sqrt(K / 16.0)
+    levels = synth.levels_exponential(16)
+    ctx, lay = make_ctx(qgx, d, K, bucket, oracle.NORM_L2, levels, seed=seed)
+    rng = np.random.default_rng(77)
+    V0 = (rng.standard_normal((K, d)) * 1e-2).astype(np.float32)
+    V1 = (rng.standard_normal((K, d)) * 1e-2).astype(np.float32)
+    x1 = rng.standard_normal(d).astype(np.float32)
+    ctx.state_init(dev(x1))
+    st = oracle.EGState(d, K, X1=x1)
+    a, b, tmp = ctx.new_stream(slotted=slotted), ctx.new_stream(slotted=slotted), ctx.new_stream()
+    Xh = torch.empty(d, device="cuda"); Xn = torch.empty(d, device="cuda")
+    ctx.quantize_encode(dev(V0), 0, a); ctx.eg_step(0, a, None, Xh)
+    ctx.quantize_encode(dev(V1), 1, b); ctx.eg_step(1, b, a, Xn)
+    ha = (ctx.compact(a, tmp) if slotted else a).to_host()
+    _, _, _, sa = oracle_stream(V0, lay, oracle.NORM_L2, levels, seed, 0, ha["norms"], ctx.worst_words)
+    assert_stream_equal(ha, sa, lay)
+    hb = (ctx.compact(b, tmp) if slotted else b).to_host()
+    _, _, _, sb = oracle_stream(V1, lay, oracle.NORM_L2, levels, seed, 1, hb["norms"], ctx.worst_words)
+    assert_stream_equal(hb, sb, lay)
+    Va, _, _ = oracle.decode(sa, ha["norms"], lay, levels)
+    Vb, _, _ = oracle.decode(sb, hb["norms"], lay, levels)
+    assert rel_err(ctx.decode_average(a).cpu().numpy(), Va.mean(axis=0)) <= tol
+    assert rel_err(Xh.cpu().numpy(), st.half0(Va)) <= tol
+    assert rel_err(Xn.cpu().numpy(), st.half1(Vb, Va)) <= tol
+    sc = ctx.scalars()
+    assert abs(sc["S"] - st.S) <= REL * st.S and abs(sc["gamma"] - st.gamma) <= REL * st.gamma
+    assert ctx.poll_error() == 0
+    ctx.close()
