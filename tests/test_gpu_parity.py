@@ -86,6 +86,8 @@ CASES = [
     (2 * 4096 + 3 * 256 + 12, 2, 256, oracle.NORM_LINF, "uni16", None),        # by sixteen
     (4096 + 512 + 2048 + 2344, 2, 512, 3, "exp16", [4096 + 512, 2048, 2344]),  # by eight, several tensors, ||v||_3
     (5 * 4096, 5, 2048, oracle.NORM_L2, "exp8", None),               # by two; a workgroup's last wave has no chunk
+    (403, 3, 4, oracle.NORM_L2, "exp16", None),                      # the smallest bucket: four coordinates, one chunk each
+    (1000, 2, 12, oracle.NORM_LINF, "uni16", [500, 500]),            # buckets of 12 in two tensors, short ones at their ends
 ]
 
 
