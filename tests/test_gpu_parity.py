@@ -706,6 +706,32 @@ def test_fit_levels_many_levels_and_sweeps(qgx):
     ctx.close()
 
 
+@pytest.mark.parametrize("n_sym,n_bins", [(2, 64), (3, 64), (3, 4096), (127, 64), (127, 4096)])
+def test_fit_levels_smallest_and_largest_tables(qgx, n_sym, n_bins):
+    """Tables of 2 symbols (nothing to move), 3 (one free level) and 127 (the most), histograms of 64 bins
+    (the fewest) and 4096, on a density without empty bins so that every root is unique."""
+    d, K = (1 << 15) + 24, 2
+    start = np.linspace(0, 1, n_sym).astype(np.float32) ** (2 if n_sym > 2 else 1)
+    ctx, lay = make_ctx(qgx, d, K, 4096, oracle.NORM_LINF, start, seed=0)
+    V = synth.uniform_vectors(K, d, seed=50)
+    hist = torch.zeros(n_bins, dtype=torch.float64, device="cuda")
+    ctx.fit_levels(dev(V), n_sym, n_bins, sweeps=6, hist_out=hist)
+    H_o = oracle.histogram(V, lay, oracle.NORM_LINF, n_bins)
+    np.testing.assert_allclose(hist.cpu().numpy(), H_o, rtol=1e-12, atol=0)
+    lv_g, lv_o = ctx.get_levels(), oracle.fit_levels(H_o, start, sweeps=6)
+    assert len(lv_g) == n_sym and lv_g[0] == 0 and lv_g[-1] == 1 and (np.diff(lv_g) > 0).all()
+    np.testing.assert_allclose(lv_g, lv_o, rtol=REL, atol=1e-9)
+    if n_sym == 2:
+        np.testing.assert_array_equal(lv_g, start)
+    out = ctx.new_stream()
+    ctx.quantize_encode(dev(V), 1, out)
+    h = out.to_host()
+    _, _, _, so = oracle_stream(V, lay, oracle.NORM_LINF, lv_g, 0, 1, h["norms"], ctx.worst_words)
+    assert_stream_equal(h, so, lay)
+    assert ctx.poll_error() == 0
+    ctx.close()
+
+
 @pytest.mark.parametrize("norm,bucket,n_bins", [(oracle.NORM_L2, 16384, 4096), (oracle.NORM_LINF, 4096, 1024),
                                                 (4, 8192, 2048), (oracle.NORM_L2, 1024, 4096),
                                                 (oracle.NORM_LINF, 256, 1024), (3, 2048, 2048)])
