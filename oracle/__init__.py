@@ -15,8 +15,10 @@ from dataclasses import dataclass
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "qgx_oracle.c")
-_LIB = os.path.join(_HERE, "libqgx_oracle.so")
+# QGX_ORACLE_SRC names another C source to build (next to itself) and load instead: the test that plants
+# mistakes in a copy of the oracle, to see that the pins catch them, runs the pins that way.
+_SRC = os.environ.get("QGX_ORACLE_SRC") or os.path.join(_HERE, "qgx_oracle.c")
+_LIB = os.path.join(os.path.dirname(os.path.abspath(_SRC)), "libqgx_oracle.so")
 
 NORM_LINF = 0
 NORM_L2 = 2

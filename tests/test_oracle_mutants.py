@@ -1,0 +1,62 @@
+"""Do the pins have teeth?  Each case plants one plausible mistake (a dropped term, a wrong sign or index,
+a swapped operand, a missing root) in a copy of the oracle's C source, builds it, and runs the pin tests
+of that part against the copy in a child process: at least one of them has to fail.  The mistakes live
+on the CPU and in a temporary directory only."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "qgx_oracle.c")
+
+Q, C, E, F, H, R = ("tests/test_oracle_quantize.py", "tests/test_oracle_codec.py", "tests/test_oracle_eg.py",
+                    "tests/test_oracle_fit.py", "tests/test_oracle_huffman.py", "tests/test_oracle_rng.py")
+
+MUTANTS = [
+    ("nine Philox rounds", "round < 10; ++round", "round < 9; ++round", [R]),
+    ("23 random bits instead of 24", "(out[i & 3] >> 8) * 0x1p-24f", "(out[i & 3] >> 9) * 0x1p-24f", [Q]),
+    ("rounds down where it should round up", "sym = j + ((r * g < t) ? 1u : 0u);", "sym = j + ((r * g < t) ? 0u : 1u);", [Q]),
+    ("signs dropped", "neg[(uint64_t)k * d + i] = (uint8_t)(signbit(x) ? 1 : 0);", "neg[(uint64_t)k * d + i] = 0;", [Q]),
+    ("L2 norm without the root", "n = (float)sqrt(acc);", "n = (float)acc;", [Q]),
+    ("level index one too high", "while (j + 2 < n_sym && levels[j + 1] <= u) ++j;",
+     "while (j + 2 < n_sym && levels[j] <= u) ++j;", [Q]),
+    ("gap without its lower end", "const float g = levels[j + 1] - levels[j];", "const float g = levels[j + 1];", [Q]),
+    ("Elias groups least significant bit first", "tmp[len++] = (uint8_t)((N >> i) & 1u);",
+     "tmp[len++] = (uint8_t)((N >> (nb - 1 - i)) & 1u);", [C]),
+    ("a sign bit for zeros too", "if (sym != 0) put_bit(words, word_pos * 32 + p++,", "put_bit(words, word_pos * 32 + p++,", [C]),
+    ("decoded sign inverted", "Vhat[(uint64_t)k * d + i] = sg ? -mag : mag;", "Vhat[(uint64_t)k * d + i] = sg ? mag : -mag;", [C]),
+    ("half-step towards the dual vector", "X_half[i] = x_t - gamma * (acc / (double)K);",
+     "X_half[i] = x_t + gamma * (acc / (double)K);", [E]),
+    ("mean not divided by K", "Y[i] = Y[i] - acc / (double)K;", "Y[i] = Y[i] - acc;", [E]),
+    ("step size without the root", "*gamma = (double)K / sqrt(1.0 + *S);", "*gamma = (double)K / (1.0 + *S);", [E]),
+    ("S from sums instead of differences", "s_add += (prev - cur) * (prev - cur);", "s_add += (prev + cur) * (prev + cur);", [E]),
+    ("histogram weighted by the norm, not its square", "const double w = (double)n * (double)n;", "const double w = (double)n;", [F]),
+    ("stationarity with a wrong sign", "const double left = (m1x - m1a) - a * (m0x - m0a);",
+     "const double left = (m1x - m1a) + a * (m0x - m0a);", [F]),
+    ("symbol probabilities mirrored", "p[j] += mass * (1.0 - up);\n            p[j + 1] += mass * up;",
+     "p[j] += mass * up;\n            p[j + 1] += mass * (1.0 - up);", [H]),
+    ("a package counted as one item of the level below", "take = 2 * packages;", "take = packages;", [H]),
+    ("canonical words not advanced", "            ++code;\n", "", [H]),
+    ("largest magnitude taken as the smallest", "if (a > n) n = a;", "if (a < n || n == 0.0f) n = a;", [Q]),
+    ("q-norm raised to q instead of 1/q", "n = (float)(m * pow(acc, 1.0 / q));", "n = (float)(m * pow(acc, q));", [Q]),
+    ("mean over K - 1", "mean[i] = acc / (double)K;", "mean[i] = acc / (double)(K - 1);", [E, C]),
+    ("bins half an octave off", "const int64_t key = (int64_t)(bits >> 17) - ((int64_t)127 * 64 - (int64_t)n_bins);",
+     "const int64_t key = (int64_t)(bits >> 17) - ((int64_t)127 * 64 - (int64_t)n_bins) - 32;", [F]),
+    ("objective without the cubic term", "const double P_hi = -hi * hi * hi / 3.0 + (a + c) * hi * hi / 2.0 - a * c * hi;",
+     "const double P_hi = (a + c) * hi * hi / 2.0 - a * c * hi;", [F]),
+    ("one item too many bought at the top level", "uint32_t take = 2 * (n - 1);", "uint32_t take = 2 * n - 1;", [H]),
+]
+
+
+@pytest.mark.parametrize("name,old,new,files", MUTANTS, ids=[m[0].replace(" ", "_") for m in MUTANTS])
+def test_a_pin_fails_for_the_planted_mistake(tmp_path, name, old, new, files):
+    src = open(SRC).read()
+    assert src.count(old) == 1, "the text to change must occur exactly once"
+    mutant = tmp_path / "qgx_oracle.c"
+    mutant.write_text(src.replace(old, new))
+    env = dict(os.environ, QGX_ORACLE_SRC=str(mutant))
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider", *files],
+                       cwd=ROOT, env=env, capture_output=True, text=True, timeout=900)
+    assert r.returncode == 1 and " failed" in r.stdout, "no pin caught: %s\n%s" % (name, r.stdout[-2000:] + r.stderr[-2000:])
