@@ -44,6 +44,19 @@ MUTANTS = [
     ("mean over K - 1", "mean[i] = acc / (double)K;", "mean[i] = acc / (double)(K - 1);", [E, C]),
     ("bins half an octave off", "const int64_t key = (int64_t)(bits >> 17) - ((int64_t)127 * 64 - (int64_t)n_bins);",
      "const int64_t key = (int64_t)(bits >> 17) - ((int64_t)127 * 64 - (int64_t)n_bins) - 32;", [F]),
+    ("the next word of the Philox block", "out[i & 3]", "out[(i + 1) & 3]", [Q, R]),
+    ("draws that ignore the call", "ctr[3] = call_id;", "ctr[3] = 0;", [Q, R]),
+    ("draws that ignore the worker", "ctr[2] = k;", "ctr[2] = 0;", [Q, R]),
+    ("first moment of a bin taken at its lower edge", "M1[b + 1] = M1[b] + H[b] * 0.5 * (e0 + e1);",
+     "M1[b + 1] = M1[b] + H[b] * e0;", [F]),
+    ("stationarity without its right-hand term", "return left - right;", "return left;", [F]),
+    ("every bucket decoded with the first norm", "const float n = norms[(uint64_t)k * NB + b];",
+     "const float n = norms[(uint64_t)k * NB];", [C]),
+    ("symbol probabilities not normalised", "for (uint32_t j = 0; j < n_sym; ++j) p[j] /= total;", "", [H]),
+    ("next iterate without the anchor", "X_next[i] = (anchor ? anchor[i] : 0.0) + (*gamma) * Y[i];",
+     "X_next[i] = (*gamma) * Y[i];", [E]),
+    ("current iterate without the step size", "const double x_t = (anchor ? anchor[i] : 0.0) + gamma * Y[i];",
+     "const double x_t = (anchor ? anchor[i] : 0.0) + Y[i];", [E]),
     ("objective without the cubic term", "const double P_hi = -hi * hi * hi / 3.0 + (a + c) * hi * hi / 2.0 - a * c * hi;",
      "const double P_hi = (a + c) * hi * hi / 2.0 - a * c * hi;", [F]),
     ("one item too many bought at the top level", "uint32_t take = 2 * (n - 1);", "uint32_t take = 2 * n - 1;", [H]),
