@@ -276,6 +276,9 @@ def main():
                      # per SIMD x 4 clocks (simple instructions take fewer: the ALUs are the second ceiling)
                      "valu_busy_us": _profile_number("valu_busy_us") if default_workload else None},
     }
+    if out["roofline"]["valu_busy_us"]:
+        # the same bound as a share of this run's launch time: near 1 means the ALUs, not HBM, are the nearer ceiling
+        out["roofline"]["valu_busy_frac"] = out["roofline"]["valu_busy_us"] / (enc_ms * 1e3)
     names = ["encode", "decode_avg_half0", "encode_2", "decode_avg_half1"][:n_ev - 1]
     per_step = {n: np.array([e[j].elapsed_time(e[j + 1]) for e in events]) for j, n in enumerate(names)}
     if args.full_iteration:
