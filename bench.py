@@ -56,6 +56,9 @@ def parse_args():
                          "fitted to the estimated symbol probabilities, or words of one width (with uniform levels: "
                          "the fixed-width setting of the paper's experiment, e.g. --workload gan --bucket 1024 "
                          "--n-sym 8 --code fixed for 3 bits + sign)")
+    ap.add_argument("--graph", action="store_true",
+                    help="with --full-iteration: also capture the iteration as one HIP graph and time its replays "
+                         "(reported as an extra object; matters for small vectors, where launches dominate)")
     ap.add_argument("--placement", choices=["slotted", "compact"], default="slotted",
                     help="chunk placement of the coded streams handed from the encoder to the update kernel")
     return ap.parse_args()
@@ -236,6 +239,27 @@ def main():
     wall = time.perf_counter() - t0
     assert ctx.poll_error() == 0
 
+    graph_ms = None
+    if args.graph and args.full_iteration and slotted and args.bucket <= 16384:
+        # every kernel of the iteration takes what changes from device memory, the call numbers included
+        def iteration():
+            ctx.quantize_encode(V, qgx.CALL_FIRST_HALF, a)
+            ctx.eg_step(0, a, None, Xh)
+            ctx.quantize_encode(V1, qgx.CALL_SECOND_HALF, b)
+            ctx.eg_step(1, b, a, None)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            iteration()
+        for _ in range(args.warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        assert ctx.poll_error() == 0
+
     copy_gbs = copy_bandwidth()
     ms_step = wall * 1e3 / args.steps
     enc_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
@@ -279,6 +303,9 @@ def main():
     if out["roofline"]["valu_busy_us"]:
         # the same bound as a share of this run's launch time: near 1 means the ALUs, not HBM, are the nearer ceiling
         out["roofline"]["valu_busy_frac"] = out["roofline"]["valu_busy_us"] / (enc_ms * 1e3)
+    if graph_ms is not None:
+        out["graph"] = {"ms_per_step": graph_ms, "value": 4.0 * K * d * passes / (graph_ms * 1e-3) / 1e9, "unit": "GB/s",
+                        "what": "the same iteration captured once as a HIP graph and replayed"}
     names = ["encode", "decode_avg_half0", "encode_2", "decode_avg_half1"][:n_ev - 1]
     per_step = {n: np.array([e[j].elapsed_time(e[j + 1]) for e in events]) for j, n in enumerate(names)}
     if args.full_iteration:

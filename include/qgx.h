@@ -21,10 +21,16 @@
  *   - Errors found on the device (non-finite bucket, stream capacity, malformed stream) set bits in
  *     a device error word that qgx_poll_error returns and clears.
  *   - Determinism: the same (config, levels, V, call_id) gives a byte-identical qgx_stream.
- *   - A context serves one caller at a time: its calls are issued from one thread, in order.  The
- *     coding calls pass per-launch counters (tickets, an epoch) to their kernels, so a captured HIP
- *     graph of them cannot be replayed; the second-half-step and decoding calls of a layout with
- *     short chunks use a side queue of the library's own beside `stream`.
+ *   - A context serves one caller at a time: its calls are issued from one thread, in order.
+ *   - HIP graphs: qgx_quantize_encode into a slotted stream (layouts whose buckets have at most
+ *     16384 coordinates), qgx_decode_average and qgx_eg_step may be captured and the graph replayed:
+ *     their kernels take everything that changes between iterations (Y, S, gamma, t, and with
+ *     QGX_CALL_FIRST_HALF / QGX_CALL_SECOND_HALF the call number) from device memory.  Run them once
+ *     before capturing (the first launch of a kernel sets its attributes).  Not for replay: coding
+ *     into a compact stream or with larger buckets (their kernels get per-launch counters, tickets
+ *     and an epoch, as arguments), and the running average (its count is kept on the host).  The
+ *     second-half-step and decoding calls of a layout with short chunks use a side queue of the
+ *     library's own beside `stream`, forked and joined with events, which a capture takes along.
  *
  * Stream container (the paper fixes only the bit string {0,1}*; the container is this library's):
  *   Coordinates of one worker are cut into segments (tensors), segments into buckets of at most
@@ -96,6 +102,9 @@ typedef enum {
 typedef enum { QGX_NORM_LINF = 0, QGX_NORM_L2 = 2 } qgx_norm;
 #define QGX_MAX_NORM_Q 64
 typedef enum { QGX_CODE_ELIAS_OMEGA = 0, QGX_CODE_TABLE = 1 } qgx_code; /* Psi, Appendix J */
+/* call_id values that stand for "from the iteration counter on the device" (see qgx_quantize) */
+#define QGX_CALL_FIRST_HALF 0xFFFFFFFEu
+#define QGX_CALL_SECOND_HALF 0xFFFFFFFFu
 
 typedef struct {
     uint64_t d;                   /* coordinates per worker, 1 <= d < 2^31 */
@@ -162,6 +171,11 @@ qgx_status qgx_set_code_table(qgx_ctx* ctx, const uint8_t* code_len, const uint3
  *   call_id   distinguishes quantisation calls under one seed (e.g. 2t + half): coordinate i of
  *             worker k draws word (i mod 4) of Philox4x32-10(key = seed, counter = (i/4, 0, k, call_id)),
  *             top 24 bits as r in [0,1); rounds up iff r * (l_{j+1}-l_j) < u - l_j.
+ *             QGX_CALL_FIRST_HALF / QGX_CALL_SECOND_HALF instead of a number: the kernel takes
+ *             2(t-1) resp. 2(t-1)+1 (mod 2^32) with t the iteration counter of the context's state
+ *             as it is on the device when the kernel runs (1 after qgx_state_init, advanced by every
+ *             second half-step), so that a captured HIP graph of an iteration draws fresh numbers
+ *             at every replay.
  *   norms_in  DEVICE [K][NB] or NULL: non-negative norms to use instead of computing them (a common
  *             scale for several workers, say); coordinates that exceed it are clamped to u = 1
  *   norms_out DEVICE [K][NB]: the norm used (0 for a rejected bucket)

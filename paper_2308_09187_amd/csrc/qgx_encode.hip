@@ -419,6 +419,8 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
 
     const size_t kbase = (size_t)k * lay.d;
     const bool vec_ok = (kbase & 3u) == 0;             // 16-byte aligned rows for this worker
+    // the number of this quantisation call: given, or taken from the iteration counter (replayed graphs)
+    const uint32_t call_id = a.call_mode ? 2u * (uint32_t)(sc->t - 1ull) + (a.call_mode - 1u) : a.call_id;
     const float* __restrict__ Vk = (MODE != EncMode::EncodeOnly) ? a.V + kbase : nullptr;
     const uint32_t unit = ticketed ? s_misc[2] : (uint32_t)blockIdx.x / lay.K;
     uint32_t b = a.parts > 1u ? unit / a.parts : unit;  // the bucket; with shared chunks the first of the wave's chunk
@@ -582,7 +584,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
             for (int r = 0; r < kRows; ++r) {
                 const uint32_t i0 = g.clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
                 uint32_t rnd[4], e[4], idx[4];
-                philox4x32_10(i0 >> 2, 0u, k, a.call_id, a.seed_lo, a.seed_hi, rnd);
+                philox4x32_10(i0 >> 2, 0u, k, call_id, a.seed_lo, a.seed_hi, rnd);
                 const float rinv_r = GROUPED ? s_rinv[w * 16 + (int)((uint32_t)r >> rshift)] : rinv;
                 e[0] = quantize_one<true, CM>(v[r].x, rinv_r, rnd[0], L, n_sym, idx[0]);
                 e[1] = quantize_one<true, CM>(v[r].y, rinv_r, rnd[1], L, n_sym, idx[1]);
@@ -616,7 +618,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                     if (__any(unknown) && lane == 0) raise_error(sc, QGX_EBIT_STREAM);
                 } else {
                     uint32_t rnd[4];
-                    philox4x32_10(i0 >> 2, 0u, k, a.call_id, a.seed_lo, a.seed_hi, rnd);
+                    philox4x32_10(i0 >> 2, 0u, k, call_id, a.seed_lo, a.seed_hi, rnd);
                     // the register copy is indexed by compile-time row numbers only: this path reads the row again
                     float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
                     if (i0 < g.cend) x.x = Vk[i0];

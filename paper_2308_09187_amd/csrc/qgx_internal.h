@@ -127,6 +127,7 @@ struct EncodeArgs {
     uint32_t epoch;             // tags scan_state entries of this launch
     uint32_t ticket_base;       // value of every ticket counter before this launch
     uint32_t seed_lo, seed_hi, call_id;
+    uint32_t call_mode;         // 0: call_id as given; 1, 2: 2(t-1), 2(t-1)+1 from the iteration counter on the device
     int norm_kind;
     // LDS plan of the launch (bytes): [cell][lev: two sign halves lev_stride apart][misc][stage x waves]
     uint32_t cell_mant;         // cell_mant(n_sym) of the table in use

@@ -442,6 +442,7 @@ static qgx_status run_encode(qgx_ctx* ctx, EncMode mode, const float* V, uint32_
     EncodeArgs a{};
     a.V = V; a.norms_in = norms_in; a.norms_out = norms_out; a.sym_out = sym_out; a.sym_in = sym_in;
     a.seed_lo = (uint32_t)ctx->cfg.seed; a.seed_hi = (uint32_t)(ctx->cfg.seed >> 32); a.call_id = call_id;
+    a.call_mode = call_id == QGX_CALL_FIRST_HALF ? 1u : call_id == QGX_CALL_SECOND_HALF ? 2u : 0u;
     a.norm_kind = ctx->cfg.norm;
     a.lev_stride = 16;
     while (a.lev_stride < 16u * T(ctx).n_sym) a.lev_stride <<= 1;

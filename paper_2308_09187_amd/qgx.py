@@ -19,6 +19,7 @@ LIB_PATH = os.environ.get("QGX_LIB") or os.path.join(_HERE, "libqgx.so")
 OK = 0
 ERR_ARG, ERR_LEVELS, ERR_CAPACITY, ERR_STREAM, ERR_NONFINITE, ERR_HIP, ERR_STATE = -1, -2, -3, -4, -5, -6, -7
 EBIT_CAPACITY, EBIT_STREAM, EBIT_NONFINITE, EBIT_STATE = 1, 2, 4, 8
+CALL_FIRST_HALF, CALL_SECOND_HALF = 0xFFFFFFFE, 0xFFFFFFFF   # call numbers taken from the iteration counter on the device
 NORM_LINF, NORM_L2 = 0, 2
 CODE_ELIAS_OMEGA, CODE_TABLE = 0, 1
 CHUNK, SUB, SUBS, MAX_SYM, MAX_BINS = 4096, 32, 128, 127, 4096

@@ -1099,3 +1099,78 @@ def test_most_workers(qgx, slotted):
     assert abs(sc["S"] - st.S) <= REL * st.S and abs(sc["gamma"] - st.gamma) <= REL * st.gamma
     assert ctx.poll_error() == 0
     ctx.close()
+
+
+@pytest.mark.parametrize("d", [6 * 4096, 6 * 4096 + 700])
+def test_iteration_as_a_replayed_hip_graph(qgx, d):
+    """One iteration of Algorithm 1 -- operator (torch device code), CODE o Q, first half-step, operator,
+    CODE o Q, second half-step -- captured once as a HIP graph and replayed: Y, S, gamma, t and, with
+    QGX_CALL_FIRST_HALF / QGX_CALL_SECOND_HALF, the number of the quantisation call live on the device, so
+    every replay is the next iteration with fresh draws.  Between replays the test does eager work (new
+    noise, compaction, copies) and synchronises; every iteration is compared with the oracle, which is
+    given call numbers 2(t-1) and 2(t-1)+1.  The second layout has a ragged chunk position, whose kernel
+    runs on the library's side queue inside the capture."""
+    K, bucket, seed, T = 3, 4096, 41, 5
+    levels = synth.levels_exponential(16)
+    game = synth.QuadraticGame(d=d, K=K)
+    a_d, b_d = dev(game.a), dev(game.b)
+    ctx, lay = make_ctx(qgx, d, K, bucket, oracle.NORM_L2, levels, seed=seed)
+    ctx.state_init(None)
+    st = oracle.EGState(d, K)
+    sa, sb, tmp = ctx.new_stream(slotted=True), ctx.new_stream(slotted=True), ctx.new_stream()
+    X = torch.zeros(d, device="cuda")
+    Xh = torch.empty(d, device="cuda")
+    V0, V1 = torch.empty(K, d, device="cuda"), torch.empty(K, d, device="cuda")
+    N0, N1 = torch.empty(K, d, device="cuda"), torch.empty(K, d, device="cuda")
+    F = torch.empty(d, device="cuda")
+
+    def dual_vectors(z, noise, out):
+        z2, f2 = z.view(-1, 2), F.view(-1, 2)
+        torch.mul(z2[:, 0], game.mu, out=f2[:, 0]); f2[:, 0].addcmul_(a_d, z2[:, 1])
+        torch.mul(z2[:, 1], game.mu, out=f2[:, 1]); f2[:, 1].addcmul_(a_d, z2[:, 0], value=-1.0)
+        F.add_(b_d)
+        torch.add(noise, F, out=out)
+
+    def iteration():
+        dual_vectors(X, N0, V0)
+        ctx.quantize_encode(V0, qgx.CALL_FIRST_HALF, sa)
+        ctx.eg_step(0, sa, None, Xh)
+        dual_vectors(Xh, N1, V1)
+        ctx.quantize_encode(V1, qgx.CALL_SECOND_HALF, sb)
+        ctx.eg_step(1, sb, sa, X)
+
+    def fresh_noise(t):
+        g = torch.Generator(device="cuda").manual_seed(1000 + t)
+        N0.normal_(0.0, game.noise, generator=g); N1.normal_(0.0, game.noise, generator=g)
+
+    def check(t):
+        torch.cuda.synchronize()
+        ha = ctx.compact(sa, tmp).to_host()
+        hb = ctx.compact(sb, tmp).to_host()
+        v0, v1 = V0.cpu().numpy(), V1.cpu().numpy()
+        _, _, _, oa = oracle_stream(v0, lay, oracle.NORM_L2, levels, seed, 2 * (t - 1), ha["norms"], ctx.worst_words)
+        _, _, _, ob = oracle_stream(v1, lay, oracle.NORM_L2, levels, seed, 2 * (t - 1) + 1, hb["norms"], ctx.worst_words)
+        assert_stream_equal(ha, oa, lay); assert_stream_equal(hb, ob, lay)
+        Va, _, _ = oracle.decode(oa, ha["norms"], lay, levels)
+        Vb, _, _ = oracle.decode(ob, hb["norms"], lay, levels)
+        assert rel_err(Xh.cpu().numpy(), st.half0(Va)) <= REL
+        assert rel_err(X.cpu().numpy(), st.half1(Vb, Va)) <= REL
+        sc = ctx.scalars()
+        assert sc["t"] == t + 1 == st.t
+        assert abs(sc["S"] - st.S) <= REL * st.S and abs(sc["gamma"] - st.gamma) <= REL * st.gamma
+
+    fresh_noise(1)
+    iteration()                      # eagerly once: the first launch of a kernel sets its attributes
+    check(1)
+    graph = torch.cuda.CUDAGraph()
+    fresh_noise(2)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        iteration()                  # recorded, not run
+    for t in range(2, T + 1):
+        if t > 2:
+            fresh_noise(t)
+        graph.replay()
+        check(t)
+    assert ctx.poll_error() == 0
+    ctx.close()
