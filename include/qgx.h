@@ -22,15 +22,13 @@
  *     a device error word that qgx_poll_error returns and clears.
  *   - Determinism: the same (config, levels, V, call_id) gives a byte-identical qgx_stream.
  *   - A context serves one caller at a time: its calls are issued from one thread, in order.
- *   - HIP graphs: qgx_quantize_encode into a slotted stream (layouts whose buckets have at most
- *     16384 coordinates), qgx_decode_average and qgx_eg_step may be captured and the graph replayed:
- *     their kernels take everything that changes between iterations (Y, S, gamma, t, and with
+ *   - HIP graphs: the coding, decoding and half-step calls may be captured and the graph replayed:
+ *     their kernels take everything that changes between iterations (Y, S, gamma, t, the running
+ *     sum and its count, the tags and ticket counters that order workgroups, and with
  *     QGX_CALL_FIRST_HALF / QGX_CALL_SECOND_HALF the call number) from device memory.  Run them once
- *     before capturing (the first launch of a kernel sets its attributes).  Not for replay: coding
- *     into a compact stream or with larger buckets (their kernels get per-launch counters, tickets
- *     and an epoch, as arguments), and the running average (its count is kept on the host).  The
- *     second-half-step and decoding calls of a layout with short chunks use a side queue of the
- *     library's own beside `stream`, forked and joined with events, which a capture takes along.
+ *     before capturing (the first launch of a kernel sets its attributes).  The second-half-step
+ *     and decoding calls of a layout with short chunks use a side queue of the library's own beside
+ *     `stream`, forked and joined with events, which a capture takes along.
  *
  * Stream container (the paper fixes only the bit string {0,1}*; the container is this library's):
  *   Coordinates of one worker are cut into segments (tensors), segments into buckets of at most
@@ -261,7 +259,9 @@ qgx_status qgx_state_import(qgx_ctx* ctx, const float* Y, const float* anchor, d
  * binary64 running sum in the context (allocated at the first such call; this is the one call
  * besides qgx_create that allocates) and makes every later qgx_eg_step(half = 0) add its output to
  * it, at 16 more bytes of traffic per coordinate; on = 0 switches that off.
- * qgx_average_export: X_bar DEVICE [d] (or NULL) = sum / count, count = half-steps since the reset. */
+ * qgx_average_export: X_bar DEVICE [d] (or NULL) = sum / count, count = half-steps since the reset
+ * (kept on the device, so that the half-steps of a replayed graph count; the call reads it back and
+ * so synchronises `stream`). */
 qgx_status qgx_average_reset(qgx_ctx* ctx, int on, void* stream);
 qgx_status qgx_average_export(qgx_ctx* ctx, float* X_bar, uint64_t* count, void* stream);
 

@@ -844,17 +844,40 @@ hipError_t launch_state_init(const Layout& lay, Scalars* sc, float* Y, float* an
     return hipGetLastError();
 }
 
-// Ergodic average of the half-step iterates: out = x_sum / count.
-__global__ __launch_bounds__(256) void k_average(uint32_t d, const double* __restrict__ x_sum, double count,
+// Ergodic average of the half-step iterates: out = x_sum / count, the count kept on the device (so
+// that the half-steps of a replayed graph are counted too); clearing the sum; counting a half-step.
+__global__ __launch_bounds__(256) void k_average(uint32_t d, const double* __restrict__ x_sum, const Scalars* sc,
                                                  float* __restrict__ out)
 {
+    const double count = (double)sc->avg_count;
     for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < d; i += gridDim.x * 256u) out[i] = (float)(x_sum[i] / count);
 }
 
-hipError_t launch_average(uint32_t d, const double* x_sum, double count, float* out, hipStream_t st)
+hipError_t launch_average(uint32_t d, const double* x_sum, const Scalars* sc, float* out, hipStream_t st)
 {
     const uint32_t grid = min((d + 255u) / 256u, 4096u);
-    hipLaunchKernelGGL(k_average, dim3(grid), dim3(256), 0, st, d, x_sum, count, out);
+    hipLaunchKernelGGL(k_average, dim3(grid), dim3(256), 0, st, d, x_sum, sc, out);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void k_average_reset(uint32_t d, double* __restrict__ x_sum, Scalars* sc)
+{
+    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < d; i += gridDim.x * 256u) x_sum[i] = 0.0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) sc->avg_count = 0ull;
+}
+
+hipError_t launch_average_reset(uint32_t d, double* x_sum, Scalars* sc, hipStream_t st)
+{
+    const uint32_t grid = min((d + 255u) / 256u, 4096u);
+    hipLaunchKernelGGL(k_average_reset, dim3(grid), dim3(256), 0, st, d, x_sum, sc);
+    return hipGetLastError();
+}
+
+__global__ void k_average_count(Scalars* sc) { sc->avg_count += 1ull; }
+
+hipError_t launch_average_count(Scalars* sc, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_average_count, dim3(1), dim3(1), 0, st, sc);
     return hipGetLastError();
 }
 

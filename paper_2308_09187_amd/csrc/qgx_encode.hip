@@ -397,8 +397,18 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
     // Split buckets: (bucket, part) by ticket as well, whatever the placement (see exchange_parts).
     const bool ordered = MODE != EncMode::QuantOnly && a.slot_words == 0u;
     const bool ticketed = ordered || a.parts > 1u;
+    // A worker's counter only ever grows, and every launch of a context that takes tickets takes the
+    // same number from it, so a ticket tells both the unit inside this launch and the number of the
+    // launch, which tags what the workgroups publish to each other (30 bits, never 0: untouched
+    // words hold 0).  Nothing about it comes from the host: a captured graph can be replayed.
     if (ticketed) {
-        if (tid == 0) s_misc[2] = atomicAdd(a.tickets + k * kTicketStride, 1u) - a.ticket_base;
+        if (tid == 0) {
+            const unsigned long long per_launch = GROUPED ? (lay.NC + 3u) / 4u : (unsigned long long)lay.NB * a.parts;
+            const unsigned long long raw = atomicAdd(a.tickets + k * kTicketStride, 1ull);
+            const unsigned long long launch = raw / per_launch;
+            s_misc[2] = (uint32_t)(raw - launch * per_launch);
+            s_misc[3] = (uint32_t)(launch % 0x3FFFFFFFull) + 1u;
+        }
     }
     for (int i = tid; i < (int)n_sym; i += (int)blockDim.x) {
         reinterpret_cast<float4*>(s_lev)[i] = tab->lev2[0][i];
@@ -423,6 +433,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
     const uint32_t call_id = a.call_mode ? 2u * (uint32_t)(sc->t - 1ull) + (a.call_mode - 1u) : a.call_id;
     const float* __restrict__ Vk = (MODE != EncMode::EncodeOnly) ? a.V + kbase : nullptr;
     const uint32_t unit = ticketed ? s_misc[2] : (uint32_t)blockIdx.x / lay.K;
+    const uint32_t epoch = ticketed ? s_misc[3] : 0u;
     uint32_t b = a.parts > 1u ? unit / a.parts : unit;  // the bucket; with shared chunks the first of the wave's chunk
     const uint32_t part = GROUPED ? 0u : unit - b * a.parts;
     ChunkGeom g;
@@ -446,7 +457,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
         // the units after it look back over its (empty) aggregate
         if (ordered && tid == 0)
             __hip_atomic_store(a.scan_state + (size_t)k * lay.NB * a.parts + unit,
-                               (unsigned long long)((a.epoch << 2) | 1u) << 32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                               (unsigned long long)((epoch << 2) | 1u) << 32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
     const bool split = a.parts > 1u && g.bparts > 1u;
@@ -507,7 +518,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
             }
             if (split) {
                 if (w == 0) {
-                    const double t = exchange_parts(xch, g.bparts, part, 0u, tot, a.norm_kind != QGX_NORM_L2, a.epoch, sc);
+                    const double t = exchange_parts(xch, g.bparts, part, 0u, tot, a.norm_kind != QGX_NORM_L2, epoch, sc);
                     if (lane == 0) s_tot[0] = t;
                 }
                 __syncthreads();
@@ -526,7 +537,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                 for (int i = 0; i < nwaves; ++i) tot += s_red[nwaves + i];
                 if (split) {
                     if (w == 0) {
-                        const double t = exchange_parts(xch, g.bparts, part, 1u, tot, false, a.epoch, sc);
+                        const double t = exchange_parts(xch, g.bparts, part, 1u, tot, false, epoch, sc);
                         if (lane == 0) s_tot[1] = t;
                     }
                     __syncthreads();
@@ -552,7 +563,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                 for (int i = 0; i < nwaves; ++i) sum += s_red[nwaves + i];
                 if (split) {
                     if (w == 0) {
-                        const double t = exchange_parts(xch, g.bparts, part, 1u, sum, false, a.epoch, sc);
+                        const double t = exchange_parts(xch, g.bparts, part, 1u, sum, false, epoch, sc);
                         if (lane == 0) s_tot[1] = t;
                     }
                     __syncthreads();
@@ -672,7 +683,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                     bucket_words += s_words[i];
                 }
                 if (w == 0) {
-                    const uint32_t excl = lookback_exclusive(a.scan_state + (size_t)k * lay.NB * a.parts, unit, bucket_words, a.epoch, sc);
+                    const uint32_t excl = lookback_exclusive(a.scan_state + (size_t)k * lay.NB * a.parts, unit, bucket_words, epoch, sc);
                     if (lane == 0) s_misc[1] = excl;
                 }
                 __syncthreads();
@@ -706,8 +717,7 @@ static size_t encode_lds_bytes(int waves, const EncodeArgs& a, bool with_stage, 
 }
 
 template <EncMode MODE, bool GROUPED, int CM>
-static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a, hipStream_t st,
-                              uint32_t* tickets_per_worker)
+static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a, hipStream_t st)
 {
     const int waves = (GROUPED || a.parts > 1u) ? 4 : (int)lay.waves_per_bucket;
     const size_t lds = encode_lds_bytes(waves, a, MODE != EncMode::QuantOnly, GROUPED);
@@ -719,34 +729,32 @@ static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc,
         attr_done = true;
     }
     // one workgroup per bucket, per part of a bucket, or (shared chunks) per four chunks; in compact
-    // placement and with split buckets each takes one ticket of its worker
+    // placement and with split buckets each takes one ticket of its worker (the kernel's per_launch)
     const uint32_t units = GROUPED ? (lay.NC + 3u) / 4u : lay.NB * a.parts;
-    *tickets_per_worker = ((MODE != EncMode::QuantOnly && a.slot_words == 0u) || a.parts > 1u) ? units : 0u;
     hipLaunchKernelGGL((k_encode<MODE, GROUPED, CM>), dim3(lay.K * units), dim3(waves * kWave), lds, st, lay, tab, sc, a);
     return hipGetLastError();
 }
 
 template <EncMode MODE>
-static hipError_t launch_kind(const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a, hipStream_t st,
-                              uint32_t* tickets_per_worker)
+static hipError_t launch_kind(const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a, hipStream_t st)
 {
     switch (a.cell_mant) {
-        case 4: return lay.shared_chunks ? launch_mode<MODE, true, 4>(lay, tab, sc, a, st, tickets_per_worker)
-                                         : launch_mode<MODE, false, 4>(lay, tab, sc, a, st, tickets_per_worker);
-        case 5: return lay.shared_chunks ? launch_mode<MODE, true, 5>(lay, tab, sc, a, st, tickets_per_worker)
-                                         : launch_mode<MODE, false, 5>(lay, tab, sc, a, st, tickets_per_worker);
-        default: return lay.shared_chunks ? launch_mode<MODE, true, 6>(lay, tab, sc, a, st, tickets_per_worker)
-                                          : launch_mode<MODE, false, 6>(lay, tab, sc, a, st, tickets_per_worker);
+        case 4: return lay.shared_chunks ? launch_mode<MODE, true, 4>(lay, tab, sc, a, st)
+                                         : launch_mode<MODE, false, 4>(lay, tab, sc, a, st);
+        case 5: return lay.shared_chunks ? launch_mode<MODE, true, 5>(lay, tab, sc, a, st)
+                                         : launch_mode<MODE, false, 5>(lay, tab, sc, a, st);
+        default: return lay.shared_chunks ? launch_mode<MODE, true, 6>(lay, tab, sc, a, st)
+                                          : launch_mode<MODE, false, 6>(lay, tab, sc, a, st);
     }
 }
 
 hipError_t launch_encode(EncMode mode, const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a,
-                         hipStream_t st, uint32_t* tickets_per_worker)
+                         hipStream_t st)
 {
     switch (mode) {
-        case EncMode::Fused: return launch_kind<EncMode::Fused>(lay, tab, sc, a, st, tickets_per_worker);
-        case EncMode::QuantOnly: return launch_kind<EncMode::QuantOnly>(lay, tab, sc, a, st, tickets_per_worker);
-        default: return launch_kind<EncMode::EncodeOnly>(lay, tab, sc, a, st, tickets_per_worker);
+        case EncMode::Fused: return launch_kind<EncMode::Fused>(lay, tab, sc, a, st);
+        case EncMode::QuantOnly: return launch_kind<EncMode::QuantOnly>(lay, tab, sc, a, st);
+        default: return launch_kind<EncMode::EncodeOnly>(lay, tab, sc, a, st);
     }
 }
 

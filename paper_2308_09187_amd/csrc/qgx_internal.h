@@ -20,7 +20,7 @@ constexpr int kMaxSymBits = kMaxCode + 1;               // plus the sign bit
 constexpr int kChunkWordsMax = kChunk * kMaxSymBits / 32;  // 1792
 constexpr int kAlignWords = 4;
 constexpr int kMaxWaves = QGX_MAX_BUCKET / kChunk;      // 16 waves = 1024 threads per bucket
-constexpr int kTicketStride = 32;           // one 128-byte line per worker's counter
+constexpr int kTicketStride = 16;           // one 128-byte line per worker's (64-bit) counter
 constexpr int kSymMax = 128;              // table storage (QGX_MAX_SYM = 127 entries used at most)
 
 // tau lookup: one cell per 1/16, 1/32 or 1/64 octave (by the size of the level table: a cell must not
@@ -85,6 +85,7 @@ struct Scalars {
     float gamma_f;              // gamma rounded to binary32, what the update kernels multiply by
     unsigned int err;           // QGX_EBIT_*
     unsigned int pad_[2];
+    unsigned long long avg_count;   // first half-steps added to the running sum since its reset
 };
 
 struct Layout {                 // device pointers into one allocation
@@ -123,9 +124,7 @@ struct EncodeArgs {
     unsigned long long* scan_state;  // [K][NB * parts] look-back words
     unsigned long long* xch;         // [K][NB][parts][2][2] partial norms of split buckets, epoch-tagged
     uint32_t parts;             // workgroups per bucket: 1, or ceil(waves_per_bucket / 4) when that exceeds 4
-    uint32_t* tickets;          // [K] ever-increasing bucket tickets, kTicketStride words apart
-    uint32_t epoch;             // tags scan_state entries of this launch
-    uint32_t ticket_base;       // value of every ticket counter before this launch
+    unsigned long long* tickets;   // [K] ever-increasing tickets, kTicketStride counters apart
     uint32_t seed_lo, seed_hi, call_id;
     uint32_t call_mode;         // 0: call_id as given; 1, 2: 2(t-1), 2(t-1)+1 from the iteration counter on the device
     int norm_kind;
@@ -161,9 +160,8 @@ struct DecodeArgs {
 };
 
 hipError_t launch_build_tables(Tables* tab, hipStream_t st);
-// tickets_per_worker: how far the launch advances every worker's ticket counter
 hipError_t launch_encode(EncMode mode, const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a,
-                         hipStream_t st, uint32_t* tickets_per_worker);
+                         hipStream_t st);
 // A second queue for work that should overlap the caller's stream (fork: the side waits for what the
 // caller's stream holds so far; join: the caller's stream waits for the side).
 struct SideQueue {
@@ -176,7 +174,9 @@ hipError_t launch_finish_half1(const Layout& lay, Scalars* sc, const double* s_p
                                const float* anchor, float* X_out, hipStream_t st);
 hipError_t launch_state_init(const Layout& lay, Scalars* sc, float* Y, float* anchor, const float* X1,
                              hipStream_t st);
-hipError_t launch_average(uint32_t d, const double* x_sum, double count, float* out, hipStream_t st);
+hipError_t launch_average(uint32_t d, const double* x_sum, const Scalars* sc, float* out, hipStream_t st);
+hipError_t launch_average_reset(uint32_t d, double* x_sum, Scalars* sc, hipStream_t st);
+hipError_t launch_average_count(Scalars* sc, hipStream_t st);
 hipError_t launch_state_set(Scalars* sc, double S, unsigned long long t, uint32_t K, hipStream_t st);
 hipError_t launch_sum_bits(const Layout& lay, const uint16_t* sub_end, Scalars* sc, hipStream_t st);
 hipError_t launch_histogram(const Layout& lay, const float* V, int norm_kind, uint32_t n_bins, double* partial,

@@ -37,7 +37,7 @@ struct qgx_ctx {
     unsigned long long* d_scan = nullptr;
     unsigned long long* d_xch = nullptr;   // partial norms of buckets shared by several workgroups
     uint32_t parts = 1;                    // workgroups per bucket in the encoder
-    uint32_t* d_tickets = nullptr;
+    unsigned long long* d_tickets = nullptr;
     double* d_spartial = nullptr;
     double* d_hpartial = nullptr;
     double* d_hist = nullptr;
@@ -45,12 +45,9 @@ struct qgx_ctx {
     SideQueue side{};               // for the ragged chunk positions of the decoding kernels
     bool side_ok = false;
     double* d_xsum = nullptr;       // [d] sum of the X_{t+1/2} since qgx_average_reset (allocated there)
-    uint64_t xsum_count = 0;
     bool xsum_on = false;
     uint32_t hist_bins = 0;         // bins of the histogram d_hist holds (0: none yet)
     uint32_t h_groups = 0;
-    uint32_t epoch = 0;
-    uint32_t ticket_count = 0;
     bool state_ready = false, has_anchor = false;
     const uint16_t* last_sub_end = nullptr;
     uint64_t worst_words = 0;
@@ -276,7 +273,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
         ok = ok && hipMalloc(&c->d_xch, n_units * 4 * sizeof(unsigned long long)) == hipSuccess;
         ok = ok && hipMemset(c->d_xch, 0, n_units * 4 * sizeof(unsigned long long)) == hipSuccess;
     }
-    ok = ok && hipMalloc(&c->d_tickets, (size_t)cfg->K * kTicketStride * sizeof(uint32_t)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_tickets, (size_t)cfg->K * kTicketStride * sizeof(unsigned long long)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_spartial, (size_t)NC * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_hpartial, (size_t)c->h_groups * QGX_MAX_BINS * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_hist, QGX_MAX_BINS * sizeof(double)) == hipSuccess;
@@ -285,7 +282,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     ok = ok && hipMemset(c->d_tabs, 0, QGX_TABLES * sizeof(Tables)) == hipSuccess;
     ok = ok && hipMemset(c->d_sc, 0, sizeof(Scalars)) == hipSuccess;
     ok = ok && hipMemset(c->d_scan, 0, n_units * sizeof(unsigned long long)) == hipSuccess;
-    ok = ok && hipMemset(c->d_tickets, 0, (size_t)cfg->K * kTicketStride * sizeof(uint32_t)) == hipSuccess;
+    ok = ok && hipMemset(c->d_tickets, 0, (size_t)cfg->K * kTicketStride * sizeof(unsigned long long)) == hipSuccess;
     if (ok) {
         const uint32_t kind = (uint32_t)cfg->code;
         for (int t = 0; ok && t < QGX_TABLES; ++t)
@@ -467,17 +464,11 @@ static qgx_status run_encode(qgx_ctx* ctx, EncMode mode, const float* V, uint32_
         a.cap_words = out->payload_words_per_worker;
         a.scan_state = ctx->d_scan;
     }
-    ctx->epoch = (ctx->epoch + 1u) & 0x3FFFFFFFu;      // tags what workgroups of this launch publish to each other
-    if (ctx->epoch == 0) ctx->epoch = 1;
-    a.epoch = ctx->epoch;
     a.parts = ctx->parts;
     a.xch = ctx->d_xch;
-    a.ticket_base = ctx->ticket_count;
     a.tickets = ctx->d_tickets;
-    uint32_t groups = 0;
-    hipError_t le = launch_encode(mode, ctx->lay, tab_of(ctx), ctx->d_sc, a, (hipStream_t)stream, &groups);
+    hipError_t le = launch_encode(mode, ctx->lay, tab_of(ctx), ctx->d_sc, a, (hipStream_t)stream);
     if (le != hipSuccess) return fail(ctx, QGX_ERR_HIP, "encode launch: %s", hipGetErrorString(le));
-    ctx->ticket_count += groups;
     if (mode != EncMode::QuantOnly) ctx->last_sub_end = out->sub_end;
     return QGX_OK;
 }
@@ -648,7 +639,7 @@ qgx_status qgx_eg_step(qgx_ctx* ctx, int half, const qgx_stream* cur, const qgx_
         a.out = X_out;
         a.x_sum = ctx->xsum_on ? ctx->d_xsum : nullptr;
         QGX_HIP(ctx, launch_decode(DecMode::Half0, ctx->lay, tab_of(ctx), ctx->d_sc, a, st, ctx->side_ok ? &ctx->side : nullptr));
-        if (ctx->xsum_on) ctx->xsum_count += 1;
+        if (ctx->xsum_on) QGX_HIP(ctx, launch_average_count(ctx->d_sc, st));
         return QGX_OK;
     }
     fill_decode_args(ctx, a, cur, prev);
@@ -662,11 +653,10 @@ qgx_status qgx_average_reset(qgx_ctx* ctx, int on, void* stream)
 {
     if (!ctx) return QGX_ERR_ARG;
     ctx->xsum_on = on != 0;
-    ctx->xsum_count = 0;
     if (!ctx->xsum_on) return QGX_OK;
     if (!ctx->d_xsum && hipMalloc(&ctx->d_xsum, ctx->cfg.d * sizeof(double)) != hipSuccess)
         return fail(ctx, QGX_ERR_HIP, "qgx_average_reset: no memory for the running sum");
-    QGX_HIP(ctx, hipMemsetAsync(ctx->d_xsum, 0, ctx->cfg.d * sizeof(double), (hipStream_t)stream));
+    QGX_HIP(ctx, launch_average_reset(ctx->lay.d, ctx->d_xsum, ctx->d_sc, (hipStream_t)stream));
     return QGX_OK;
 }
 
@@ -674,10 +664,13 @@ qgx_status qgx_average_export(qgx_ctx* ctx, float* X_bar, uint64_t* count, void*
 {
     if (!ctx || !aligned16(X_bar)) return fail(ctx, QGX_ERR_ARG, "qgx_average_export: null context or misaligned X_bar");
     if (!ctx->xsum_on) return fail(ctx, QGX_ERR_STATE, "qgx_average_export: averaging is off (qgx_average_reset)");
-    if (count) *count = ctx->xsum_count;
+    unsigned long long n = 0;                               // the count lives on the device: replayed graphs add to it too
+    QGX_HIP(ctx, hipMemcpyAsync(&n, &ctx->d_sc->avg_count, sizeof(n), hipMemcpyDeviceToHost, (hipStream_t)stream));
+    QGX_HIP(ctx, hipStreamSynchronize((hipStream_t)stream));
+    if (count) *count = n;
     if (X_bar) {
-        if (ctx->xsum_count == 0) return fail(ctx, QGX_ERR_STATE, "qgx_average_export: no half-step since the reset");
-        QGX_HIP(ctx, launch_average(ctx->lay.d, ctx->d_xsum, (double)ctx->xsum_count, X_bar, (hipStream_t)stream));
+        if (n == 0) return fail(ctx, QGX_ERR_STATE, "qgx_average_export: no half-step since the reset");
+        QGX_HIP(ctx, launch_average(ctx->lay.d, ctx->d_xsum, ctx->d_sc, X_bar, (hipStream_t)stream));
     }
     return QGX_OK;
 }

@@ -1101,23 +1101,28 @@ def test_most_workers(qgx, slotted):
     ctx.close()
 
 
-@pytest.mark.parametrize("d", [6 * 4096, 6 * 4096 + 700])
-def test_iteration_as_a_replayed_hip_graph(qgx, d):
+@pytest.mark.parametrize("d,bucket,slotted", [(6 * 4096, 4096, True), (6 * 4096 + 700, 4096, True),
+                                              (2 * 32768 + 5000, 32768, False), (3 * 4096 + 1024 + 300, 1024, False)])
+def test_iteration_as_a_replayed_hip_graph(qgx, d, bucket, slotted):
     """One iteration of Algorithm 1 -- operator (torch device code), CODE o Q, first half-step, operator,
     CODE o Q, second half-step -- captured once as a HIP graph and replayed: Y, S, gamma, t and, with
     QGX_CALL_FIRST_HALF / QGX_CALL_SECOND_HALF, the number of the quantisation call live on the device, so
     every replay is the next iteration with fresh draws.  Between replays the test does eager work (new
     noise, compaction, copies) and synchronises; every iteration is compared with the oracle, which is
     given call numbers 2(t-1) and 2(t-1)+1.  The second layout has a ragged chunk position, whose kernel
-    runs on the library's side queue inside the capture."""
-    K, bucket, seed, T = 3, 4096, 41, 5
+    runs on the library's side queue inside the capture; the third has buckets shared by two workgroups
+    and compact placement, whose workgroups are ordered by tickets and tags that a kernel of the capture
+    renews; the fourth buckets that share chunks.  The running average is on: its count is on the device."""
+    K, seed, T = 3, 41, 5
     levels = synth.levels_exponential(16)
     game = synth.QuadraticGame(d=d, K=K)
     a_d, b_d = dev(game.a), dev(game.b)
     ctx, lay = make_ctx(qgx, d, K, bucket, oracle.NORM_L2, levels, seed=seed)
     ctx.state_init(None)
     st = oracle.EGState(d, K)
-    sa, sb, tmp = ctx.new_stream(slotted=True), ctx.new_stream(slotted=True), ctx.new_stream()
+    sa, sb, tmp = ctx.new_stream(slotted=slotted), ctx.new_stream(slotted=slotted), ctx.new_stream()
+    ctx.average_reset(True)
+    xbar_o = np.zeros(d, np.float64)
     X = torch.zeros(d, device="cuda")
     Xh = torch.empty(d, device="cuda")
     V0, V1 = torch.empty(K, d, device="cuda"), torch.empty(K, d, device="cuda")
@@ -1145,16 +1150,20 @@ def test_iteration_as_a_replayed_hip_graph(qgx, d):
 
     def check(t):
         torch.cuda.synchronize()
-        ha = ctx.compact(sa, tmp).to_host()
-        hb = ctx.compact(sb, tmp).to_host()
+        ha = (ctx.compact(sa, tmp) if slotted else sa).to_host()
+        hb = (ctx.compact(sb, tmp) if slotted else sb).to_host()
         v0, v1 = V0.cpu().numpy(), V1.cpu().numpy()
         _, _, _, oa = oracle_stream(v0, lay, oracle.NORM_L2, levels, seed, 2 * (t - 1), ha["norms"], ctx.worst_words)
         _, _, _, ob = oracle_stream(v1, lay, oracle.NORM_L2, levels, seed, 2 * (t - 1) + 1, hb["norms"], ctx.worst_words)
         assert_stream_equal(ha, oa, lay); assert_stream_equal(hb, ob, lay)
         Va, _, _ = oracle.decode(oa, ha["norms"], lay, levels)
         Vb, _, _ = oracle.decode(ob, hb["norms"], lay, levels)
-        assert rel_err(Xh.cpu().numpy(), st.half0(Va)) <= REL
+        xh_o = st.half0(Va)
+        xbar_o[:] += xh_o
+        assert rel_err(Xh.cpu().numpy(), xh_o) <= REL
         assert rel_err(X.cpu().numpy(), st.half1(Vb, Va)) <= REL
+        xbar, n_avg = ctx.average_export()
+        assert n_avg == t and rel_err(xbar.cpu().numpy(), xbar_o / t) <= REL
         sc = ctx.scalars()
         assert sc["t"] == t + 1 == st.t
         assert abs(sc["S"] - st.S) <= REL * st.S and abs(sc["gamma"] - st.gamma) <= REL * st.gamma
