@@ -240,7 +240,7 @@ def main():
     assert ctx.poll_error() == 0
 
     graph_ms = None
-    if args.graph and args.full_iteration and slotted and args.bucket <= 16384:
+    if args.graph and args.full_iteration:
         # every kernel of the iteration takes what changes from device memory, the call numbers included
         def iteration():
             ctx.quantize_encode(V, qgx.CALL_FIRST_HALF, a)
