@@ -72,3 +72,16 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode == 2
     assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_binding_constants_match_the_header():
+    """The numbers the binding repeats (status codes, error bits, limits, the call numbers that stand for
+    'from the iteration counter') are the header's."""
+    from paper_2308_09187_amd import qgx
+    text = open(HEADER).read()
+    defs = {m.group(1): int(m.group(2).rstrip("uU"), 0) for m in re.finditer(r"#define\s+(QGX_[A-Z0-9_]+)\s+(0x[0-9A-Fa-f]+[uU]?|\d+[uU]?)\s", text)}
+    assert defs["QGX_CALL_FIRST_HALF"] == qgx.CALL_FIRST_HALF and defs["QGX_CALL_SECOND_HALF"] == qgx.CALL_SECOND_HALF
+    assert defs["QGX_CHUNK"] == qgx.CHUNK and defs["QGX_SUB"] == qgx.SUB and defs["QGX_SUBS"] == qgx.SUBS
+    assert defs["QGX_MAX_BINS"] == qgx.MAX_BINS
+    for bit in ("CAPACITY", "STREAM", "NONFINITE", "STATE"):
+        assert defs["QGX_EBIT_" + bit] == getattr(qgx, "EBIT_" + bit)
