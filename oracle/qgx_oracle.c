@@ -569,72 +569,79 @@ void orc_histogram(const float* V, uint32_t K, uint64_t d,
     }
 }
 
-/* Cumulative mass and first moment of the piecewise-uniform density at x. */
-typedef struct { uint32_t n_bins; const double* H; const double* M0; const double* M1; } orc_cdf;
-
-static uint32_t bin_containing(const orc_cdf* F, double x)
+/* The bin with edge(b) <= x < edge(b+1) (the last bin for x = 1): start from the bin of x rounded to
+ * binary32, then walk to the exact answer for the binary64 x. */
+static uint32_t bin_containing(uint32_t n_bins, double x)
 {
-    /* the bin with edge(b) <= x < edge(b+1): start from the bin of x rounded to binary32,
-     * then walk to the exact answer for the binary64 x */
-    uint32_t b = orc_bin_of((float)x, F->n_bins);
-    while (b + 1 < F->n_bins && orc_bin_edge(b + 1, F->n_bins) <= x) ++b;
-    while (b > 0 && orc_bin_edge(b, F->n_bins) > x) --b;
+    uint32_t b = orc_bin_of((float)x, n_bins);
+    while (b + 1 < n_bins && orc_bin_edge(b + 1, n_bins) <= x) ++b;
+    while (b > 0 && orc_bin_edge(b, n_bins) > x) --b;
     return b;
 }
-static double cum_mass(const orc_cdf* F, double x)
+
+/* int_from^to w(u) dF~(u) for the weight w(u) = u - pivot (rising = 1) or pivot - u (rising = 0),
+ * summed piece by piece: a piece is the part of one bin inside [from, to], the density is uniform
+ * on it, so its integral of a linear weight is its mass times the weight at its midpoint.  On
+ * [pivot, to] resp. [from, pivot] every term is non-negative, so a small mass next to the pivot is
+ * not lost against the total mass, as it would be in a difference of cumulative sums. */
+static double linear_moment(const double* H, uint32_t n_bins, double from, double to, double pivot, int rising)
 {
-    const uint32_t b = bin_containing(F, x);
-    const double e0 = orc_bin_edge(b, F->n_bins), e1 = orc_bin_edge(b + 1, F->n_bins);
-    return F->M0[b] + F->H[b] * (x - e0) / (e1 - e0);
-}
-static double cum_moment(const orc_cdf* F, double x)
-{
-    const uint32_t b = bin_containing(F, x);
-    const double e0 = orc_bin_edge(b, F->n_bins), e1 = orc_bin_edge(b + 1, F->n_bins);
-    return F->M1[b] + F->H[b] / (e1 - e0) * 0.5 * (x * x - e0 * e0);
+    double sum = 0.0;
+    if (!(to > from)) return 0.0;
+    for (uint32_t b = bin_containing(n_bins, from); b < n_bins; ++b) {
+        const double e0 = orc_bin_edge(b, n_bins), e1 = orc_bin_edge(b + 1, n_bins);
+        if (e0 >= to) break;
+        const double lo = from > e0 ? from : e0, hi = to < e1 ? to : e1;
+        if (!(hi > lo) || H[b] == 0.0) continue;
+        const double piece_mass = H[b] * (hi - lo) / (e1 - e0);
+        const double piece_mid = 0.5 * (lo + hi);
+        sum += piece_mass * (rising ? piece_mid - pivot : pivot - piece_mid);
+    }
+    return sum;
 }
 
 /* G(x) = int_a^x (u-a) dF~ - int_x^c (c-u) dF~ : derivative in l_j = x of the
- * two terms of (QAda) that contain l_j, with neighbours a = l_{j-1}, c = l_{j+1}. */
-static double stationarity(const orc_cdf* F, double a, double x, double c)
+ * two terms of (QAda) that contain l_j, with neighbours a = l_{j-1}, c = l_{j+1}.
+ * Non-decreasing in x, G(a) <= 0 <= G(c). */
+static double stationarity(const double* H, uint32_t n_bins, double a, double x, double c)
 {
-    const double m0a = cum_mass(F, a), m0x = cum_mass(F, x), m0c = cum_mass(F, c);
-    const double m1a = cum_moment(F, a), m1x = cum_moment(F, x), m1c = cum_moment(F, c);
-    const double left = (m1x - m1a) - a * (m0x - m0a);
-    const double right = c * (m0c - m0x) - (m1c - m1x);
+    const double left = linear_moment(H, n_bins, a, x, a, 1);
+    const double right = linear_moment(H, n_bins, x, c, c, 0);
     return left - right;
 }
 
 /* ------------------------------------------------------------------------ */
 /* (QAda) by updating one level at a time (Section 3.3, last sentence):      */
 /* each interior level moves to the root of the stationarity condition       */
-/* between its neighbours (bisection), in index order, `sweeps` times.       */
+/* between its neighbours, in index order, `sweeps` times.  G is continuous   */
+/* and non-decreasing, and it is zero on a whole interval where that interval */
+/* holds no mass (every point of it minimises the update); the level goes to */
+/* the smallest root, inf{x in [a,c] : G(x) >= 0}, found by bisection (with   */
+/* no mass at all between the neighbours that is a itself).  Every update is */
+/* rounded to binary32, the precision of the table, at once, so that whether */
+/* any mass lies between two levels never hangs on the last bits of a        */
+/* binary64 intermediate (a level at the edge of the data's support sits on   */
+/* the bin edge itself).                                                     */
 /* levels[n_sym] in/out (binary32 table); work in binary64; finally round to */
 /* binary32 and keep the table strictly increasing with gaps >= 2^-24.       */
 /* ------------------------------------------------------------------------ */
 void orc_fit_levels(const double* H, uint32_t n_bins, float* levels, uint32_t n_sym, uint32_t sweeps)
 {
-    double* M0 = (double*)malloc(sizeof(double) * (n_bins + 1));
-    double* M1 = (double*)malloc(sizeof(double) * (n_bins + 1));
     double* l = (double*)malloc(sizeof(double) * n_sym);
-    orc_cdf F = { n_bins, H, M0, M1 };
-    M0[0] = 0.0; M1[0] = 0.0;
-    for (uint32_t b = 0; b < n_bins; ++b) {
-        const double e0 = orc_bin_edge(b, n_bins), e1 = orc_bin_edge(b + 1, n_bins);
-        M0[b + 1] = M0[b] + H[b];
-        M1[b + 1] = M1[b] + H[b] * 0.5 * (e0 + e1);
-    }
+    double total = 0.0;
+    for (uint32_t b = 0; b < n_bins; ++b) total += H[b];
     for (uint32_t j = 0; j < n_sym; ++j) l[j] = (double)levels[j];
-    if (M0[n_bins] > 0.0) {
+    if (total > 0.0) {
         for (uint32_t s = 0; s < sweeps; ++s) {
             for (uint32_t j = 1; j + 1 < n_sym; ++j) {
+                /* the smallest x in [a, c] with G(x) >= 0: G(lo) < 0 <= G(hi) throughout (or lo = a) */
                 const double a = l[j - 1], c = l[j + 1];
                 double lo = a, hi = c;
                 for (int it = 0; it < 48; ++it) {
                     const double mid = 0.5 * (lo + hi);
-                    if (stationarity(&F, a, mid, c) < 0.0) lo = mid; else hi = mid;
+                    if (stationarity(H, n_bins, a, mid, c) < 0.0) lo = mid; else hi = mid;
                 }
-                l[j] = 0.5 * (lo + hi);
+                l[j] = (double)(float)(0.5 * (lo + hi));     /* the table is binary32: rounded at once */
             }
         }
     }
@@ -649,7 +656,7 @@ void orc_fit_levels(const double* H, uint32_t n_bins, float* levels, uint32_t n_
         const float ceil_ = levels[j + 1] - 0x1p-24f;
         if (levels[j] > ceil_) levels[j] = ceil_;
     }
-    free(M0); free(M1); free(l);
+    free(l);
 }
 
 /* The objective of (QAda) for a level table, on the same piecewise-uniform

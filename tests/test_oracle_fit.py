@@ -128,3 +128,88 @@ def test_empty_histogram_and_collapsed_levels_stay_valid():
     H = np.zeros(4096); H[3000] = 1.0
     lv = oracle.fit_levels(H, lv0, sweeps=50)
     assert lv[0] == 0 and lv[-1] == 1 and (np.diff(lv) >= 2.0 ** -24).all()
+
+
+def test_flat_stationarity_takes_the_smallest_root():
+    """Histograms with empty bins, answers by hand (64 bins: one octave, bins of width 1/128 above 0.5).
+    (i) One free level between 0 and 1, mass m1 in bin 16 and m2 in bin 48 with m1 * mid1 = m2 * (1 - mid2):
+    the stationarity condition holds on the whole empty stretch between the two bins, and the level goes
+    to its left end, the top edge of bin 16.  (ii) No mass between the neighbours: the level goes to the
+    lower neighbour; the first level with mass above it goes where the mass below it reaches
+    int (1 - u) dF: a fraction (1 - mid) of the bin's mass, that far into the bin."""
+    e = oracle.bin_edges(64)
+    assert e[16] == 0.625 and e[17] == 0.6328125 and e[48] == 0.875
+    mid1, mid2 = 0.5 * (e[16] + e[17]), 0.5 * (e[48] + e[49])
+    H = np.zeros(64); H[16] = 1.0 - mid2; H[48] = mid1                    # both products are exact in binary64
+    for start in (0.55, 0.7, 0.95):
+        lv = oracle.fit_levels(H, np.array([0, start, 1], np.float32), sweeps=1)
+        assert lv[1] == np.float32(e[17])
+    # a little more mass on the right moves the root into bin 48, a little less into bin 16
+    H2 = H.copy(); H2[48] *= 1.01
+    assert e[48] < oracle.fit_levels(H2, np.array([0, 0.7, 1], np.float32), sweeps=1)[1] < e[49]
+    H2[48] = H[48] * 0.99
+    assert e[16] < oracle.fit_levels(H2, np.array([0, 0.7, 1], np.float32), sweeps=1)[1] < e[17]
+    # (ii)
+    H = np.zeros(64); H[60] = 3.0
+    lv = oracle.fit_levels(H, np.array([0, 0.6, 0.7, 0.9, 1], np.float32), sweeps=1)
+    mid = 0.5 * (e[60] + e[61])
+    want3 = e[60] + (1.0 - mid) * (e[61] - e[60])
+    assert want3 == 0.968963623046875
+    np.testing.assert_array_equal(lv, np.array([0, 2.0 ** -24, 2.0 ** -23, want3, 1], np.float32))
+
+
+def _exact_G(H, edges, a, x, c):
+    """The stationarity function of a level update in exact rational arithmetic, from its definition:
+    int_a^x (u - a) dF - int_x^c (c - u) dF for the piecewise-uniform density of the histogram."""
+    from fractions import Fraction as Fr
+    a, x, c = Fr(float(a)), Fr(float(x)), Fr(float(c))
+    tot = Fr(0)
+    for b in np.nonzero(H)[0]:
+        e0, e1 = Fr(float(edges[b])), Fr(float(edges[b + 1]))
+        dens = Fr(float(H[b])) / (e1 - e0)
+        lo, hi = max(a, e0), min(x, e1)
+        if hi > lo:                                    # int (u - a) du = [(u - a)^2 / 2]
+            tot += dens * ((hi - a) ** 2 - (lo - a) ** 2) / 2
+        lo, hi = max(x, e0), min(c, e1)
+        if hi > lo:                                    # int (c - u) du = [-(c - u)^2 / 2]
+            tot -= dens * ((c - lo) ** 2 - (c - hi) ** 2) / 2
+    return tot
+
+
+def test_every_update_is_the_smallest_root_in_exact_arithmetic():
+    """One sweep over histograms with many empty bins and masses of very different sizes; every level
+    must be, to the rounding of the binary32 table, the smallest root of its stationarity function,
+    evaluated here from the definition in rational arithmetic: negative one binary32 step below the level
+    (unless that is the lower neighbour), not negative one step above.  A sliver of mass next to a
+    neighbour decides such a sign against a total mass 10^15 times larger."""
+    rng = np.random.default_rng(11)
+    checked = slivers = 0
+    for case in range(30):
+        n_bins = int(rng.choice([64, 256]))
+        edges = oracle.bin_edges(n_bins)
+        H = rng.random(n_bins) * 10.0 ** rng.integers(-12, 3, n_bins)
+        H[rng.random(n_bins) < 0.6] = 0.0
+        H[n_bins - 1 - int(rng.integers(0, 8))] = 1.0
+        n_sym = int(rng.choice([4, 6, 9]))
+        start = np.concatenate([[0], np.sort(rng.uniform(0.3, 0.999, n_sym - 2)), [1]]).astype(np.float32)
+        if case % 3 == 0:                              # a level just below the top edge of a bin that ends a run of mass
+            b = int(rng.choice([i for i in range(8, n_bins - 1) if H[i] > 0 and H[i + 1] == 0] or [0]))
+            if b and edges[b] > start[1] + 1e-3:
+                start[2] = np.nextafter(np.float32(edges[b + 1]), np.float32(0))
+                start[2:] = np.maximum.accumulate(np.maximum(start[2:], start[2]))
+                start[-1] = 1
+                if not (np.diff(start) > 0).all():
+                    continue
+                slivers += 1
+        new = oracle.fit_levels(H, start, sweeps=1)
+        if not (np.diff(new) > 2.0 ** -20).all():
+            continue                                   # levels pushed apart at the end: covered by the test above
+        for j in range(1, n_sym - 1):
+            a, c, x = new[j - 1], start[j + 1], new[j]
+            assert a <= x <= c
+            up, dn = np.nextafter(x, np.float32(2)), np.nextafter(x, np.float32(-1))
+            assert _exact_G(H, edges, a, min(up, c), c) >= 0
+            if dn >= a and x > a:
+                assert _exact_G(H, edges, a, dn, c) < 0, (case, j)
+            checked += 1
+    assert checked > 60 and slivers > 3
