@@ -55,6 +55,7 @@ def lib():
         _lib.orc_bin_edge.restype = C.c_double
         _lib.orc_bin_edge.argtypes = [C.c_uint32, C.c_uint32]
         _lib.orc_qada_objective.restype = C.c_double
+        _lib.orc_stationary_point.restype = C.c_double
         for f in ("orc_chunk_coords", "orc_sub_coords", "orc_align_words"):
             getattr(_lib, f).restype = C.c_uint32
     return _lib
@@ -275,6 +276,12 @@ def fit_levels(H, levels, sweeps):
     lib().orc_fit_levels(_p(H, C.c_double), C.c_uint32(len(H)), _p(lv, C.c_float),
                          C.c_uint32(len(lv)), C.c_uint32(sweeps))
     return lv
+
+
+def stationary_point(H, a, c):
+    """One level update: the smallest root of the stationarity condition between the neighbours a < c."""
+    H = _c(H, np.float64)
+    return float(lib().orc_stationary_point(_p(H, C.c_double), C.c_uint32(len(H)), C.c_double(a), C.c_double(c)))
 
 
 def symbol_probabilities(H, levels):

@@ -579,71 +579,91 @@ static uint32_t bin_containing(uint32_t n_bins, double x)
     return b;
 }
 
-/* int_from^to w(u) dF~(u) for the weight w(u) = u - pivot (rising = 1) or pivot - u (rising = 0),
- * summed piece by piece: a piece is the part of one bin inside [from, to], the density is uniform
- * on it, so its integral of a linear weight is its mass times the weight at its midpoint.  On
- * [pivot, to] resp. [from, pivot] every term is non-negative, so a small mass next to the pivot is
- * not lost against the total mass, as it would be in a difference of cumulative sums. */
-static double linear_moment(const double* H, uint32_t n_bins, double from, double to, double pivot, int rising)
-{
-    double sum = 0.0;
-    if (!(to > from)) return 0.0;
-    for (uint32_t b = bin_containing(n_bins, from); b < n_bins; ++b) {
-        const double e0 = orc_bin_edge(b, n_bins), e1 = orc_bin_edge(b + 1, n_bins);
-        if (e0 >= to) break;
-        const double lo = from > e0 ? from : e0, hi = to < e1 ? to : e1;
-        if (!(hi > lo) || H[b] == 0.0) continue;
-        const double piece_mass = H[b] * (hi - lo) / (e1 - e0);
-        const double piece_mid = 0.5 * (lo + hi);
-        sum += piece_mass * (rising ? piece_mid - pivot : pivot - piece_mid);
-    }
-    return sum;
-}
-
-/* G(x) = int_a^x (u-a) dF~ - int_x^c (c-u) dF~ : derivative in l_j = x of the
- * two terms of (QAda) that contain l_j, with neighbours a = l_{j-1}, c = l_{j+1}.
- * Non-decreasing in x, G(a) <= 0 <= G(c). */
-static double stationarity(const double* H, uint32_t n_bins, double a, double x, double c)
-{
-    const double left = linear_moment(H, n_bins, a, x, a, 1);
-    const double right = linear_moment(H, n_bins, x, c, c, 0);
-    return left - right;
-}
-
 /* ------------------------------------------------------------------------ */
 /* (QAda) by updating one level at a time (Section 3.3, last sentence):      */
 /* each interior level moves to the root of the stationarity condition       */
-/* between its neighbours, in index order, `sweeps` times.  G is continuous   */
-/* and non-decreasing, and it is zero on a whole interval where that interval */
-/* holds no mass (every point of it minimises the update); the level goes to */
-/* the smallest root, inf{x in [a,c] : G(x) >= 0}, found by bisection (with   */
-/* no mass at all between the neighbours that is a itself).  Every update is */
-/* rounded to binary32, the precision of the table, at once, so that whether */
-/* any mass lies between two levels never hangs on the last bits of a        */
-/* binary64 intermediate (a level at the edge of the data's support sits on   */
-/* the bin edge itself).                                                     */
+/* between its neighbours a = l_{j-1} and c = l_{j+1}, in index order,        */
+/* `sweeps` times.  The condition: the derivative in l_j = x of the two terms */
+/* of (QAda) that contain l_j,                                               */
+/*     G(x) = int_a^x (u - a) dF~(u) - int_x^c (c - u) dF~(u) ,               */
+/* vanishes.  On the piecewise-uniform density of the histogram G is          */
+/* continuous, non-decreasing and linear on every piece (a piece is the part  */
+/* of one bin inside [a, c]; dG/dx = (c - a) * density), with G(a) <= 0 <=    */
+/* G(c).  It is zero on a whole interval where that interval holds no mass    */
+/* (every point of it minimises the update; the paper leaves the choice       */
+/* open): the level goes to the smallest root, inf{x in [a,c] : G(x) >= 0};   */
+/* with no mass at all between the neighbours that is a itself.               */
+/* G at the piece ends comes from two running sums of non-negative terms,     */
+/* the left integral summed upwards from a and the right one downwards from   */
+/* c (the integral of a linear weight over a piece is the piece's mass times  */
+/* the weight at its midpoint), so that a sliver of mass next to a neighbour  */
+/* is not lost against the total mass, as it would be in a difference of      */
+/* cumulative sums taken from 0.  The root is read off the first piece at     */
+/* whose upper end G is no longer negative.                                   */
 /* levels[n_sym] in/out (binary32 table); work in binary64; finally round to */
 /* binary32 and keep the table strictly increasing with gaps >= 2^-24.       */
 /* ------------------------------------------------------------------------ */
+static double smallest_stationary_point(const double* H, uint32_t n_bins, double a, double c,
+                                        double* lo, double* hi, double* mass, double* left, double* right)
+{
+    /* the pieces of [a, c] */
+    uint32_t n = 0;
+    if (!(c > a)) return a;
+    for (uint32_t b = bin_containing(n_bins, a); b < n_bins; ++b) {
+        const double e0 = orc_bin_edge(b, n_bins), e1 = orc_bin_edge(b + 1, n_bins);
+        if (e0 >= c) break;
+        lo[n] = a > e0 ? a : e0;
+        hi[n] = c < e1 ? c : e1;
+        if (!(hi[n] > lo[n])) continue;
+        mass[n] = H[b] * (hi[n] - lo[n]) / (e1 - e0);
+        n += 1;
+    }
+    /* left[p] = int_a^{lo_p} (u - a) dF~,  right[p] = int_{lo_p}^c (c - u) dF~ ; entry n stands for x = c */
+    left[0] = 0.0;
+    for (uint32_t p = 0; p < n; ++p) {
+        const double piece_mid = 0.5 * (lo[p] + hi[p]);
+        left[p + 1] = left[p] + mass[p] * (piece_mid - a);
+    }
+    right[n] = 0.0;
+    for (uint32_t p = n; p > 0; --p) {
+        const double piece_mid = 0.5 * (lo[p - 1] + hi[p - 1]);
+        right[p - 1] = right[p] + mass[p - 1] * (c - piece_mid);
+    }
+    if (!(right[0] > 0.0)) return a;                      /* no mass between the neighbours */
+    for (uint32_t p = 0; p < n; ++p) {
+        const double G_lo = left[p] - right[p], G_hi = left[p + 1] - right[p + 1];
+        if (G_lo < 0.0 && G_hi >= 0.0) {
+            const double slope = (c - a) * mass[p] / (hi[p] - lo[p]);
+            double x = lo[p] - G_lo / slope;
+            if (x > hi[p]) x = hi[p];
+            return x;
+        }
+    }
+    return c;                                             /* not reached: G(c) >= 0 */
+}
+
+/* One update on its own (for the pins): the smallest root for the neighbours a < c. */
+double orc_stationary_point(const double* H, uint32_t n_bins, double a, double c)
+{
+    double* work = (double*)malloc(sizeof(double) * 5 * ((size_t)n_bins + 2));
+    const size_t m = (size_t)n_bins + 2;
+    const double x = smallest_stationary_point(H, n_bins, a, c, work, work + m, work + 2 * m, work + 3 * m, work + 4 * m);
+    free(work);
+    return x;
+}
+
 void orc_fit_levels(const double* H, uint32_t n_bins, float* levels, uint32_t n_sym, uint32_t sweeps)
 {
     double* l = (double*)malloc(sizeof(double) * n_sym);
+    double* work = (double*)malloc(sizeof(double) * 5 * ((size_t)n_bins + 2));
+    double* lo = work, *hi = lo + n_bins + 2, *mass = hi + n_bins + 2, *left = mass + n_bins + 2, *right = left + n_bins + 2;
     double total = 0.0;
     for (uint32_t b = 0; b < n_bins; ++b) total += H[b];
     for (uint32_t j = 0; j < n_sym; ++j) l[j] = (double)levels[j];
     if (total > 0.0) {
-        for (uint32_t s = 0; s < sweeps; ++s) {
-            for (uint32_t j = 1; j + 1 < n_sym; ++j) {
-                /* the smallest x in [a, c] with G(x) >= 0: G(lo) < 0 <= G(hi) throughout (or lo = a) */
-                const double a = l[j - 1], c = l[j + 1];
-                double lo = a, hi = c;
-                for (int it = 0; it < 48; ++it) {
-                    const double mid = 0.5 * (lo + hi);
-                    if (stationarity(H, n_bins, a, mid, c) < 0.0) lo = mid; else hi = mid;
-                }
-                l[j] = (double)(float)(0.5 * (lo + hi));     /* the table is binary32: rounded at once */
-            }
-        }
+        for (uint32_t s = 0; s < sweeps; ++s)
+            for (uint32_t j = 1; j + 1 < n_sym; ++j)
+                l[j] = smallest_stationary_point(H, n_bins, l[j - 1], l[j + 1], lo, hi, mass, left, right);
     }
     levels[0] = 0.0f; levels[n_sym - 1] = 1.0f;
     for (uint32_t j = 1; j + 1 < n_sym; ++j) {
@@ -656,7 +676,7 @@ void orc_fit_levels(const double* H, uint32_t n_bins, float* levels, uint32_t n_
         const float ceil_ = levels[j + 1] - 0x1p-24f;
         if (levels[j] > ceil_) levels[j] = ceil_;
     }
-    free(l);
+    free(l); free(work);
 }
 
 /* The objective of (QAda) for a level table, on the same piecewise-uniform

@@ -33,10 +33,12 @@ MUTANTS = [
     ("step size without the root", "*gamma = (double)K / sqrt(1.0 + *S);", "*gamma = (double)K / (1.0 + *S);", [E]),
     ("S from sums instead of differences", "s_add += (prev - cur) * (prev - cur);", "s_add += (prev + cur) * (prev + cur);", [E]),
     ("histogram weighted by the norm, not its square", "const double w = (double)n * (double)n;", "const double w = (double)n;", [F]),
-    ("stationarity with a wrong sign", "sum += piece_mass * (rising ? piece_mid - pivot : pivot - piece_mid);",
-     "sum += piece_mass * (rising ? piece_mid + pivot : pivot - piece_mid);", [F]),
-    ("the largest root where the condition holds on an interval", "if (stationarity(H, n_bins, a, mid, c) < 0.0) lo = mid; else hi = mid;",
-     "if (stationarity(H, n_bins, a, mid, c) <= 0.0) lo = mid; else hi = mid;", [F]),
+    ("stationarity with a wrong sign", "left[p + 1] = left[p] + mass[p] * (piece_mid - a);",
+     "left[p + 1] = left[p] + mass[p] * (piece_mid + a);", [F]),
+    ("the largest root where the condition holds on an interval", "if (G_lo < 0.0 && G_hi >= 0.0) {",
+     "if (G_lo <= 0.0 && G_hi > 0.0) {", [F]),
+    ("slope of the stationarity function without the distance between the neighbours",
+     "const double slope = (c - a) * mass[p] / (hi[p] - lo[p]);", "const double slope = mass[p] / (hi[p] - lo[p]);", [F]),
     ("symbol probabilities mirrored", "p[j] += mass * (1.0 - up);\n            p[j + 1] += mass * up;",
      "p[j] += mass * up;\n            p[j + 1] += mass * (1.0 - up);", [H]),
     ("a package counted as one item of the level below", "take = 2 * packages;", "take = packages;", [H]),
@@ -49,9 +51,10 @@ MUTANTS = [
     ("the next word of the Philox block", "out[i & 3]", "out[(i + 1) & 3]", [Q, R]),
     ("draws that ignore the call", "ctr[3] = call_id;", "ctr[3] = 0;", [Q, R]),
     ("draws that ignore the worker", "ctr[2] = k;", "ctr[2] = 0;", [Q, R]),
-    ("moment of a piece taken at its lower end", "const double piece_mid = 0.5 * (lo + hi);",
-     "const double piece_mid = lo;", [F]),
-    ("stationarity without its right-hand term", "return left - right;", "return left;", [F]),
+    ("moment of a piece taken at its lower end", "const double piece_mid = 0.5 * (lo[p] + hi[p]);",
+     "const double piece_mid = lo[p];", [F]),
+    ("stationarity without its right-hand term", "const double G_lo = left[p] - right[p], G_hi = left[p + 1] - right[p + 1];",
+     "const double G_lo = left[p], G_hi = left[p + 1];", [F]),
     ("every bucket decoded with the first norm", "const float n = norms[(uint64_t)k * NB + b];",
      "const float n = norms[(uint64_t)k * NB];", [C]),
     ("symbol probabilities not normalised", "for (uint32_t j = 0; j < n_sym; ++j) p[j] /= total;", "", [H]),
