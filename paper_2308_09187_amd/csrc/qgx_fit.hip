@@ -311,92 +311,119 @@ hipError_t launch_histogram(const Layout& lay, const float* V, int norm_kind, ui
 }
 
 // ---- solver ---------------------------------------------------------------------------------------
-// With F~ piecewise uniform inside bins, the stationarity condition of (QAda) in l_j between its
+// With F~ piecewise uniform inside bins, the stationarity condition of (QAda) in l_j = x between its
 // neighbours a = l_{j-1}, c = l_{j+1},
-//     int_a^x (u - a) dF~ = int_x^c (c - u) dF~ ,
-// is linear in the mass M0(x) = F~ mass below x:  M0(x) = M0(a) + int_a^c (c - u) dF~ / (c - a).
-// So each update is an inverse-CDF lookup: prefix sums of mass and first moment, one binary search.
+//     G(x) = int_a^x (u - a) dF~ - int_x^c (c - u) dF~ = 0 ,
+// has dG/dx = (c - a) * density(x), so G(x) = (c - a) * mass(a, x) - int_a^c (c - u) dF~: the level goes
+// where the mass between a and x reaches  t = int_a^c (c - u) dF~ / (c - a).  Where that holds on a
+// whole interval (no mass there) the smallest such x is taken; with no mass at all between the
+// neighbours that is a.  Every update is rounded to binary32, the precision of the table, at once:
+// a level next to the edge of the data's support then sits on the bin edge itself, and whether any
+// mass lies between two levels does not hang on the last bits of a binary64 intermediate.
+//
+// Everything is summed from a onwards, non-negative terms only (a difference of cumulative sums taken
+// from 0 would lose a sliver of mass next to a level against the total).  A two-level tree over the bins
+// keeps that short: nodes of 16 and 256 bins hold their mass and their moment about their own right
+// edge, rho = sum H_b (edge - mid_b), so that int (c - u) dF~ over a node is (c - edge) * mass + rho.
 
-struct Cdf {
+struct Tree {
     const double* H;      // LDS [n_bins]
-    const double* M0;     // LDS [n_bins+1]
-    const double* M1;     // LDS [n_bins+1]
+    const double* m1;     // [n_bins / 16] mass of a node of 16 bins
+    const double* r1;     // its moment about its right edge
+    const double* m2;     // [n_bins / 256] the same for the complete nodes of 256 bins
+    const double* r2;
     uint32_t n_bins;
 };
 
-__device__ uint32_t bin_containing(const Cdf& F, double x)
+__device__ uint32_t bin_containing(uint32_t n_bins, double x)
 {
-    uint32_t b = bin_of((float)x, F.n_bins);
-    while (b + 1 < F.n_bins && bin_edge(b + 1, F.n_bins) <= x) ++b;
-    while (b > 0 && bin_edge(b, F.n_bins) > x) --b;
+    uint32_t b = bin_of((float)x, n_bins);
+    while (b + 1 < n_bins && bin_edge(b + 1, n_bins) <= x) ++b;
+    while (b > 0 && bin_edge(b, n_bins) > x) --b;
     return b;
 }
 
-// 1 / w for the width w of a bin other than the first: widths on the binary32 grid are powers of
-// two, so the reciprocal is an exponent flip and multiplying by it is the division, exactly.
-// (Bin 0 reaches from 0 to the second bin's edge, which is no power of two.)
-__device__ __forceinline__ double inv_pow2(double w)
+// The largest aligned node that starts at bin p, ends at or before bin q and is at most of level cap
+// (0: a bin, 1: 16 bins, 2: 256 bins).
+__device__ __forceinline__ uint32_t node_level(uint32_t p, uint32_t q, uint32_t cap)
 {
-    return __longlong_as_double(0x7FE0000000000000ll - __double_as_longlong(w));
+    if (cap >= 2u && (p & 255u) == 0u && p + 256u <= q) return 2u;
+    if (cap >= 1u && (p & 15u) == 0u && p + 16u <= q) return 1u;
+    return 0u;
 }
 
-struct Cum { double m0, m1; };      // mass and first moment of F~ below a point
-
-__device__ Cum cum_at(const Cdf& F, double x)
+// Right edge of the last bin with mass in [first, last], or `fallback` if none has any.
+__device__ double last_mass_edge(const Tree& T, uint32_t first, uint32_t last_plus_1, double fallback)
 {
-    const uint32_t b = bin_containing(F, x);
-    const double e0 = bin_edge(b, F.n_bins), e1 = bin_edge(b + 1, F.n_bins);
-    const double h = F.H[b];
-    Cum c;
-    if (b == 0) {
-        c.m0 = F.M0[b] + h * (x - e0) / (e1 - e0);
-        c.m1 = F.M1[b] + h / (e1 - e0) * 0.5 * (x * x - e0 * e0);
-    } else {
-        const double iw = inv_pow2(e1 - e0);
-        c.m0 = F.M0[b] + h * (x - e0) * iw;
-        c.m1 = F.M1[b] + h * iw * 0.5 * (x * x - e0 * e0);
+    for (uint32_t b = last_plus_1; b > first; --b)
+        if (T.H[b - 1u] > 0.0) return bin_edge(b, T.n_bins);
+    return fallback;
+}
+
+__device__ double stationary_point(const Tree& T, double a, double c)
+{
+    if (!(c > a)) return a;
+    const uint32_t nb = T.n_bins;
+    const uint32_t ba = bin_containing(nb, a), bc = bin_containing(nb, c);
+    // the pieces of the bins that hold a and c, and the whole bins ba + 1 .. bc - 1 between them
+    const double a_e0 = bin_edge(ba, nb), a_e1 = bin_edge(ba + 1u, nb);
+    const double a_hi = c < a_e1 ? c : a_e1;
+    const double m_a = T.H[ba] * (a_hi - a) / (a_e1 - a_e0);
+    double m_c = 0.0, c_e0 = c;
+    if (bc > ba) {
+        c_e0 = bin_edge(bc, nb);
+        m_c = T.H[bc] * (c - c_e0) / (bin_edge(bc + 1u, nb) - c_e0);
     }
-    return c;
-}
-
-// Smallest i in [1, n_bins] with M0[i] >= target, for 0 = M0[0] < target (M0 is non-decreasing; a
-// target a rounding above the total gives n_bins).  Sixteen-way: the 15 probes of a round do not
-// depend on each other.
-__device__ uint32_t first_at_least(const Cdf& F, double target)
-{
-    uint32_t lo = 0, hi = F.n_bins;                 // M0[lo] < target, and the answer is at most hi
-    while (hi - lo > 1u) {
-        const uint32_t span = hi - lo;
-        uint32_t below = 0;                         // probes whose value is still under the target
-#pragma unroll
-        for (uint32_t q = 1; q < 16u; ++q) below += F.M0[lo + ((span * q) >> 4)] < target ? 1u : 0u;
-        const uint32_t nlo = lo + ((span * below) >> 4);
-        hi = below == 15u ? hi : lo + ((span * (below + 1u)) >> 4);
-        lo = nlo;
+    // int_a^c (c - u) dF~
+    double right_all = m_a * (c - 0.5 * (a + a_hi));
+    for (uint32_t p = ba + 1u; p < bc;) {
+        const uint32_t lvl = node_level(p, bc, 2u);
+        if (lvl == 2u) { right_all += (c - bin_edge(p + 256u, nb)) * T.m2[p >> 8] + T.r2[p >> 8]; p += 256u; }
+        else if (lvl == 1u) { right_all += (c - bin_edge(p + 16u, nb)) * T.m1[p >> 4] + T.r1[p >> 4]; p += 16u; }
+        else { const double e1 = bin_edge(p + 1u, nb); right_all += T.H[p] * (c - 0.5 * (bin_edge(p, nb) + e1)); p += 1u; }
     }
-    return hi;
-}
-
-// ca, cc: cumulatives at the neighbours a and c.
-__device__ double stationary_point(const Cdf& F, double a, double c, const Cum& ca, const Cum& cc)
-{
-    const double right_all = c * (cc.m0 - ca.m0) - (cc.m1 - ca.m1);   // int_a^c (c - u) dF~
+    right_all += m_c * (c - 0.5 * (c_e0 + c));
     if (!(right_all > 0.0)) return a;                                  // no mass between the neighbours
-    const double target = ca.m0 + right_all / (c - a);
-    const uint32_t b = first_at_least(F, target) - 1u;                 // the root lies in bin b
-    const double e0 = bin_edge(b, F.n_bins), e1 = bin_edge(b + 1, F.n_bins);
-    const double h = F.H[b];
-    double x = e0;
-    if (h > 0.0) x = e0 + (target - F.M0[b]) / h * (e1 - e0);
-    return fmin(fmax(x, a), c);
-}
-
-__device__ __forceinline__ Cum shfl_up1(const Cum& c)
-{
-    Cum r;
-    r.m0 = __shfl_up(c.m0, 1, kWave);
-    r.m1 = __shfl_up(c.m1, 1, kWave);
-    return r;
+    const double t = right_all / (c - a);
+    // the smallest x with mass(a, x) >= t
+    double acc = 0.0, x;
+    if (acc + m_a >= t) {
+        x = a + (t - acc) / m_a * (a_hi - a);
+    } else {
+        acc += m_a;
+        bool found = false, inside = false;
+        uint32_t cap = 2u, q = bc;
+        uint32_t p = ba + 1u;
+        while (p < q) {
+            const uint32_t lvl = node_level(p, q, cap);
+            const double m = lvl == 2u ? T.m2[p >> 8] : lvl == 1u ? T.m1[p >> 4] : T.H[p];
+            if (acc + m >= t) {                                        // it is reached inside this node
+                if (lvl == 0u) {
+                    const double e0 = bin_edge(p, nb);
+                    x = e0 + (t - acc) / m * (bin_edge(p + 1u, nb) - e0);
+                    found = true;
+                    break;
+                }
+                q = p + (lvl == 2u ? 256u : 16u);
+                cap = lvl - 1u;
+                inside = true;
+            } else {
+                acc += m;
+                p += lvl == 2u ? 256u : lvl == 1u ? 16u : 1u;
+            }
+        }
+        if (!found) {
+            if (!inside && m_c > 0.0) {
+                x = c_e0 + (t - acc) / m_c * (c - c_e0);
+            } else {
+                // a node's mass reached t and the sum of its parts, rounded otherwise, did not (or t is a
+                // rounding above all the mass): the answer is where the mass seen so far ends
+                x = last_mass_edge(T, ba + 1u, q, m_a > 0.0 ? a_hi : a);
+            }
+        }
+    }
+    x = fmin(fmax(x, a), c);
+    return x;
 }
 
 // The sweeps update level j from the new l_{j-1} and the old l_{j+1}, one level after the other.
@@ -408,88 +435,65 @@ __global__ __launch_bounds__(256) void k_fit(Tables* tab, const double* __restri
                                              uint32_t sweeps)
 {
     extern __shared__ __align__(16) unsigned char s_raw[];
-    double* M0 = reinterpret_cast<double*>(s_raw);               // [n_bins+1]
-    double* M1 = M0 + (n_bins + 1);                              // [n_bins+1]
-    double* H = M1 + (n_bins + 1);                               // [n_bins]
-    __shared__ double s_part0[256], s_part1[256];
-    __shared__ double s_lev[kSymMax + 1], s_c0[kSymMax + 1], s_c1[kSymMax + 1];   // table between passes
+    double* H = reinterpret_cast<double*>(s_raw);                // [n_bins]
+    __shared__ double s_m1[QGX_MAX_BINS / 16], s_r1[QGX_MAX_BINS / 16];
+    __shared__ double s_m2[QGX_MAX_BINS / 256], s_r2[QGX_MAX_BINS / 256];
+    __shared__ double s_lev[kSymMax + 1];                         // the table between passes
 
     const uint32_t tid = threadIdx.x;
-    const uint32_t per = (n_bins + 255u) / 256u;
-    const uint32_t b0 = tid * per, b1 = min(b0 + per, n_bins);
-    double a0 = 0.0, a1 = 0.0;
-    for (uint32_t b = b0; b < b1; ++b) {
-        const double h = hist[b];
-        H[b] = h;
-        a0 += h;
-        a1 += h * 0.5 * (bin_edge(b, n_bins) + bin_edge(b + 1, n_bins));
-    }
-    s_part0[tid] = a0; s_part1[tid] = a1;
+    for (uint32_t b = tid; b < n_bins; b += 256u) H[b] = hist[b];
     __syncthreads();
-    if (tid == 0) {
-        double r0 = 0.0, r1 = 0.0;
-        for (int i = 0; i < 256; ++i) {
-            const double t0 = s_part0[i], t1 = s_part1[i];
-            s_part0[i] = r0; s_part1[i] = r1;
-            r0 += t0; r1 += t1;
+    const uint32_t n1 = n_bins >> 4, n2 = n_bins >> 8;            // n_bins is a multiple of 64
+    if (tid < n1) {
+        const double edge = bin_edge(16u * tid + 16u, n_bins);
+        double m = 0.0, r = 0.0;
+        for (uint32_t b = 16u * tid; b < 16u * tid + 16u; ++b) {
+            m += H[b];
+            r += H[b] * (edge - 0.5 * (bin_edge(b, n_bins) + bin_edge(b + 1u, n_bins)));
         }
-        M0[n_bins] = r0; M1[n_bins] = r1;
+        s_m1[tid] = m; s_r1[tid] = r;
     }
     __syncthreads();
-    // Prefix at a bin = the thread's base plus the running sum inside its run of bins, the same running
-    // sum whose end gave the next thread's base: so the prefix never steps where the histogram is
-    // empty, also not from one thread's bins to the next's (a step of one rounding there would look
-    // like mass to the search below when a target sits at the top of the data's support).
-    {
-        const double base0 = s_part0[tid], base1 = s_part1[tid];
-        a0 = 0.0; a1 = 0.0;
-        for (uint32_t b = b0; b < b1; ++b) {
-            M0[b] = base0 + a0; M1[b] = base1 + a1;
-            const double h = H[b];
-            a0 += h;
-            a1 += h * 0.5 * (bin_edge(b, n_bins) + bin_edge(b + 1, n_bins));
+    if (tid < n2) {
+        const double edge = bin_edge(256u * tid + 256u, n_bins);
+        double m = 0.0, r = 0.0;
+        for (uint32_t i = 16u * tid; i < 16u * tid + 16u; ++i) {
+            m += s_m1[i];
+            r += (edge - bin_edge(16u * i + 16u, n_bins)) * s_m1[i] + s_r1[i];
         }
+        s_m2[tid] = m; s_r2[tid] = r;
     }
-    __syncthreads();
-
-    const Cdf F = {H, M0, M1, n_bins};
     const uint32_t n_sym = tab->n_sym;
-    if (tid < n_sym) {
-        const double l = (double)tab->levels[tid];
-        const Cum c = cum_at(F, l);
-        s_lev[tid] = l; s_c0[tid] = c.m0; s_c1[tid] = c.m1;
-    }
+    if (tid < n_sym) s_lev[tid] = (double)tab->levels[tid];
     __syncthreads();
     if (tid >= (uint32_t)kWave) return;
 
+    const Tree T = {H, s_m1, s_r1, s_m2, s_r2, n_bins};
     const uint32_t lane = tid, top = n_sym - 1u;
-    const Cum c_top = {M0[n_bins], M1[n_bins]};                  // cumulatives at l_s = 1
-    if (M0[n_bins] > 0.0 && n_sym > 2u) {
+    double total = 0.0;
+    for (uint32_t i = 0; i < n1; ++i) total += s_m1[i];
+    if (total > 0.0 && n_sym > 2u) {
         for (uint32_t first = 0; first < sweeps; first += (uint32_t)kWave) {
             const uint32_t ns = min((uint32_t)kWave, sweeps - first);    // sweeps of this pass, one per lane
             double mine = 0.0;                      // the level this lane moved in its last step
-            Cum mine_c = {0.0, 0.0};
             const uint32_t steps = 2u * (ns - 1u) + (top - 1u);
             for (uint32_t t = 1; t <= steps; ++t) {
                 // the lane below moved level j + 1 one step ago
                 double above = __shfl_up(mine, 1, kWave);
-                Cum above_c = shfl_up1(mine_c);
                 const int j = (int)t - 2 * (int)lane;
                 const bool active = lane < ns && j >= 1 && j < (int)top;
                 if (active) {
-                    if (lane == 0) { above = s_lev[j + 1]; above_c.m0 = s_c0[j + 1]; above_c.m1 = s_c1[j + 1]; }
-                    if (j + 1 == (int)top) { above = 1.0; above_c = c_top; }
+                    if (lane == 0) above = s_lev[j + 1];
+                    if (j + 1 == (int)top) above = 1.0;
                     const double below = j == 1 ? 0.0 : mine;
-                    const Cum below_c = j == 1 ? Cum{0.0, 0.0} : mine_c;
-                    mine = stationary_point(F, below, above, below_c, above_c);
-                    mine_c = cum_at(F, mine);
-                    if (lane == ns - 1u) { s_lev[j] = mine; s_c0[j] = mine_c.m0; s_c1[j] = mine_c.m1; }
+                    mine = stationary_point(T, below, above);
+                    if (lane == ns - 1u) s_lev[j] = mine;
                 }
             }
         }
     }
-    // back to binary32, strictly increasing with gaps of at least 2^-24: up from l_0 = 0, then down
-    // from l_s = 1; one lane, the table is short
+    // strictly increasing with gaps of at least 2^-24: up from l_0 = 0, then down from l_s = 1; one
+    // lane, the table is short
     if (lane == 0) {
         float* lv = tab->levels;
         lv[0] = 0.0f; lv[top] = 1.0f;
@@ -507,15 +511,7 @@ __global__ __launch_bounds__(256) void k_fit(Tables* tab, const double* __restri
 
 hipError_t launch_fit(Tables* tab, const double* hist, uint32_t n_bins, uint32_t sweeps, hipStream_t st)
 {
-    const size_t lds = (3 * (size_t)n_bins + 2) * sizeof(double);
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fit),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (3 * QGX_MAX_BINS + 2) * (int)sizeof(double));
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    const size_t lds = (size_t)n_bins * sizeof(double);
     hipLaunchKernelGGL(k_fit, dim3(1), dim3(256), lds, st, tab, hist, n_bins, sweeps);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

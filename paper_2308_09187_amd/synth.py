@@ -82,6 +82,25 @@ def uniform_vectors(K: int, d: int, seed: int = 50) -> np.ndarray:
     return out
 
 
+def vectors_on_intervals(K: int, d: int, bucket: int, lo, hi, seed: int = 60) -> np.ndarray:
+    """[K][d] float32 with random signs whose magnitudes lie in the union of the intervals
+    [lo_i, hi_i) of (0, 1): an interval at random, weighted by its index to give masses of unequal size,
+    then a uniform point of it, and one coordinate of magnitude exactly 1 in every bucket of `bucket`
+    coordinates.  Under the L-infinity norm the normalised magnitudes are then the magnitudes
+    themselves, so the caller decides which stretches of (0, 1) stay empty."""
+    lo, hi = np.asarray(lo, np.float64), np.asarray(hi, np.float64)
+    w = 1.0 + np.arange(len(lo)) % 7
+    out = np.empty((K, d), np.float32)
+    for k in range(K):
+        g = _rng(seed, k)
+        which = g.choice(len(lo), size=d, p=w / w.sum())
+        mag = (lo[which] + g.random(d) * (hi[which] - lo[which])).astype(np.float32)
+        mag = np.minimum(np.maximum(mag, lo[which].astype(np.float32)), np.nextafter(hi[which].astype(np.float32), np.float32(0)))
+        mag[::bucket] = 1.0
+        out[k] = mag * np.where(g.random(d) < 0.5, np.float32(-1), np.float32(1))
+    return out
+
+
 def student_t3(K: int, d: int, seed: int = 20, scale: float = 1e-2) -> np.ndarray:
     out = np.empty((K, d), np.float32)
     for k in range(K):

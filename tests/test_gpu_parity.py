@@ -939,8 +939,45 @@ def test_random_configurations(qgx, monkeypatch, sweep, waves):
         ctx.eg_step(1, b, a if prev else None, Xn)
         assert rel_err(Xn.cpu().numpy(), st.half1(Vb, Va if prev else None)) <= REL
         assert abs(ctx.scalars()["S"] - st.S) <= REL * max(st.S, 1e-30)
+        # the level fit on the same batch, from the table in use: histogram and table against the oracle's
+        n_bins, sweeps = int(rng.choice([64, 256, 1024, 4096])), int(rng.choice([1, 4, 10]))
+        hist = torch.zeros(n_bins, dtype=torch.float64, device="cuda")
+        ctx.fit_levels(dev(V0), n_sym, n_bins, sweeps=sweeps, hist_out=hist)
+        H_o = oracle.histogram(V0, lay, norm, n_bins)
+        np.testing.assert_allclose(hist.cpu().numpy(), H_o, rtol=1e-10, atol=0)
+        np.testing.assert_allclose(ctx.get_levels(), oracle.fit_levels(H_o, levels, sweeps=sweeps), rtol=REL, atol=1e-9)
         assert ctx.poll_error() == 0
         ctx.close()
+
+
+@pytest.mark.parametrize("n_sym,n_bins,sweeps", [(65, 256, 10), (33, 64, 30), (127, 1024, 10), (9, 256, 3)])
+def test_fit_levels_on_a_histogram_with_empty_bins(qgx, n_sym, n_bins, sweeps):
+    """A fifth of the bins (and a whole stretch at the bottom) hold no mass: levels meet empty stretches,
+    where the stationarity condition of an update holds on a whole interval or no mass lies between the
+    neighbours at all.  The level goes to the smallest root; table against the oracle's to 1e-6."""
+    d, K, bucket = (1 << 17) + 520, 2, 4096
+    edges = oracle.bin_edges(n_bins)
+    rng = np.random.default_rng(n_sym)
+    keep = rng.random(n_bins) >= 0.2
+    keep[:n_bins // 8] = False
+    keep[n_bins - 1] = False                      # only the coordinate of magnitude 1 falls there
+    V = synth.vectors_on_intervals(K, d, bucket, edges[:-1][keep], edges[1:][keep], seed=60)
+    start = synth.levels_uniform(n_sym - 1)
+    ctx, lay = make_ctx(qgx, d, K, bucket, oracle.NORM_LINF, start, seed=0)
+    hist = torch.zeros(n_bins, dtype=torch.float64, device="cuda")
+    H_o = oracle.histogram(V, lay, oracle.NORM_LINF, n_bins)
+    assert not H_o[~keep][:-1].any() and (H_o[keep] > 0).all() and H_o[-1] > 0
+    for sw in (1, sweeps):
+        ctx.set_levels(start)
+        ctx.fit_levels(dev(V), n_sym, n_bins, sweeps=sw, hist_out=hist)
+        np.testing.assert_allclose(hist.cpu().numpy(), H_o, rtol=1e-12, atol=0)
+        lv_g, lv_o = ctx.get_levels(), oracle.fit_levels(H_o, start, sweeps=sw)
+        assert lv_g[0] == 0 and lv_g[-1] == 1 and (np.diff(lv_g) > 0).all()
+        np.testing.assert_allclose(lv_g, lv_o, rtol=REL, atol=1e-9)
+        if sw == 1 and n_sym > 9 and n_bins <= 256:   # levels without mass between their neighbours went to the lower one
+            assert (np.diff(lv_o) < 1e-6).any()
+    assert ctx.poll_error() == 0
+    ctx.close()
 
 
 def test_fit_levels_at_the_top_of_the_support(qgx):
