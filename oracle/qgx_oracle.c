@@ -735,97 +735,99 @@ void orc_symbol_probabilities(const double* H, uint32_t n_bins, const float* lev
 /* ------------------------------------------------------------------------ */
 /* Psi as an optimal prefix code for given symbol weights (Appendix J: Huffman*/
 /* coding when the symbol distribution is known or estimated), with no word   */
-/* longer than max_len bits.  Without the limit this is Huffman's code; with  */
-/* it, the optimal length-limited code, by the package-merge construction     */
-/* (Larmore and Hirschberg 1990): symbol i may buy one "coin" per level       */
-/* 1..max_len at price w_i; level by level, from the deepest up, the sorted   */
-/* coins are paired into packages that compete with the next level's coins;   */
-/* the cheapest 2(n-1) items of the top level are bought, and len_i is the    */
-/* number of coins of symbol i among them.  Weights are integers (exact       */
-/* sums); among equal weights a single coin goes before a package and a       */
-/* lower symbol index before a higher one.  n >= 2, 2^max_len >= n.           */
-/* Returns 0, or -1 if no such code exists.                                   */
+/* longer than max_len bits, straight from the definition of optimality:      */
+/*     minimise  sum_i w_i len_i   over  1 <= len_i <= max_len                */
+/*     subject to Kraft's inequality  sum_i 2^-len_i <= 1                     */
+/* (a prefix code with these lengths exists exactly when it holds).  Without  */
+/* the limit being active the minimum is the cost of Huffman's code.          */
+/* Exhaustive dynamic programme over (symbol, code space left): in units of   */
+/* 2^-max_len the whole code space is B = 2^max_len and a word of len bits    */
+/* takes 2^(max_len - len); best[i][k] is the least cost of words for the     */
+/* symbols i .. n-1 out of k units.  Among optimal assignments the one whose  */
+/* length vector is smallest in dictionary order is returned.  Weights are    */
+/* integers (exact sums).  n >= 2, max_len <= 16.                             */
+/* Returns 0, or -1 if no such code exists (2^max_len < n) or max_len > 16.   */
 /* ------------------------------------------------------------------------ */
 int orc_limited_prefix_lengths(const uint64_t* w, uint32_t n, uint32_t max_len, uint8_t* len)
 {
-    if (n < 2 || max_len < 1 || max_len > 32 || (max_len < 32 && (1ull << max_len) < n)) return -1;
-    uint32_t* order = (uint32_t*)malloc(sizeof(uint32_t) * n);          /* symbols by weight, then index */
-    for (uint32_t i = 0; i < n; ++i) order[i] = i;
-    for (uint32_t i = 1; i < n; ++i) {                                   /* insertion sort: stable */
-        const uint32_t x = order[i];
-        uint32_t q = i;
-        while (q > 0 && w[order[q - 1]] > w[x]) { order[q] = order[q - 1]; --q; }
-        order[q] = x;
-    }
-    const uint32_t cap = 2 * n;
-    uint64_t* cur = (uint64_t*)malloc(sizeof(uint64_t) * cap);          /* weights of the list of the level */
-    uint64_t* nxt = (uint64_t*)malloc(sizeof(uint64_t) * cap);
-    uint8_t* is_pkg = (uint8_t*)calloc((size_t)max_len * cap, 1);        /* per level: 1 where the item is a package */
-    uint32_t* count = (uint32_t*)malloc(sizeof(uint32_t) * max_len);     /* items in the list of each level */
-    /* deepest level: the coins alone */
-    uint32_t m = n;
-    for (uint32_t i = 0; i < n; ++i) cur[i] = w[order[i]];
-    count[max_len - 1] = m;
-    for (int l = (int)max_len - 2; l >= 0; --l) {
-        /* packages of the level below, merged with this level's coins */
-        const uint32_t n_pk = m / 2;
-        uint32_t a = 0, b = 0, o = 0;
-        uint8_t* flag = is_pkg + (size_t)l * cap;
-        while (a < n || b < n_pk) {
-            const uint64_t wa = a < n ? w[order[a]] : 0, wb = b < n_pk ? cur[2 * b] + cur[2 * b + 1] : 0;
-            if (b >= n_pk || (a < n && wa <= wb)) { nxt[o] = wa; flag[o] = 0; ++a; }
-            else { nxt[o] = wb; flag[o] = 1; ++b; }
-            ++o;
+    if (n < 2 || max_len < 1 || max_len > 16 || (1u << max_len) < n) return -1;
+    const uint64_t none = UINT64_MAX;
+    const uint32_t B = 1u << max_len;
+    uint64_t* best = (uint64_t*)malloc(sizeof(uint64_t) * (size_t)(n + 1) * (B + 1));
+    if (!best) return -1;
+#define BEST(i, k) best[(size_t)(i) * (B + 1) + (k)]
+    for (uint32_t k = 0; k <= B; ++k) BEST(n, k) = 0;              /* nothing left to code */
+    for (uint32_t i = n; i-- > 0;) {
+        for (uint32_t k = 0; k <= B; ++k) {
+            uint64_t least = none;
+            for (uint32_t l = 1; l <= max_len; ++l) {
+                const uint32_t space = 1u << (max_len - l);
+                if (space > k || BEST(i + 1, k - space) == none) continue;
+                const uint64_t cost = w[i] * l + BEST(i + 1, k - space);
+                if (cost < least) least = cost;
+            }
+            BEST(i, k) = least;
         }
-        m = o;
-        count[l] = m;
-        uint64_t* t = cur; cur = nxt; nxt = t;
     }
-    /* buy the cheapest 2(n-1) items of the top level; a package stands for two items of the level below */
-    for (uint32_t i = 0; i < n; ++i) len[i] = 0;
-    uint32_t take = 2 * (n - 1);
-    for (uint32_t l = 0; l < max_len && take > 0; ++l) {
-        if (take > count[l]) take = count[l];
-        const uint8_t* flag = is_pkg + (size_t)l * cap;
-        uint32_t singles = 0, packages = 0;
-        for (uint32_t i = 0; i < take; ++i) { if (flag[i]) ++packages; else ++singles; }
-        for (uint32_t i = 0; i < singles; ++i) len[order[i]] += 1;       /* the coins of a level come in weight order */
-        take = 2 * packages;
+    int rc = BEST(0, B) == none ? -1 : 0;
+    uint32_t k = B;
+    for (uint32_t i = 0; i < n && rc == 0; ++i) {                    /* read one optimal assignment back */
+        len[i] = 0;
+        for (uint32_t l = 1; l <= max_len; ++l) {
+            const uint32_t space = 1u << (max_len - l);
+            if (space > k || BEST(i + 1, k - space) == none) continue;
+            if (w[i] * l + BEST(i + 1, k - space) == BEST(i, k)) { len[i] = (uint8_t)l; k -= space; break; }
+        }
+        if (len[i] == 0) rc = -1;
     }
-    free(order); free(cur); free(nxt); free(is_pkg); free(count);
-    return 0;
+#undef BEST
+    free(best);
+    return rc;
 }
 
-/* Integer weights for the code construction from probabilities: round(p * 2^32), at least 1 so   */
-/* that a symbol never seen in the fitted sample still gets a word.                                 */
+/* Integer weights for the code construction from probabilities: p * 2^32 rounded to the nearest  */
+/* integer, at least 1 so that a symbol never seen in the fitted sample still gets a word.          */
 void orc_code_weights(const double* p, uint32_t n, uint64_t* w)
 {
     for (uint32_t i = 0; i < n; ++i) {
-        const double x = floor(p[i] * 4294967296.0 + 0.5);
-        w[i] = x >= 1.0 ? (uint64_t)x : 1ull;
+        const long long x = llround(ldexp(p[i], 32));
+        w[i] = x >= 1 ? (uint64_t)x : 1ull;
     }
 }
 
-/* Canonical words for given lengths: symbols in order of (length, index) take consecutive binary  */
-/* numbers, read most significant bit first; bits[i] holds word i with its first bit in bit 0 (the */
-/* container's bit order).  Returns 0, or -1 if the lengths overfill the code space.               */
+/* Canonical words for given lengths: list the symbols by (length, index); the first takes the word  */
+/* of all zeros, every next one the previous word plus one, extended by zeros on the right to its   */
+/* own length (words read most significant bit first).  bits[i] holds word i with its first bit in  */
+/* bit 0 (the container's bit order).  Returns 0, or -1 if the lengths overfill the code space.     */
+typedef struct { uint32_t len, index; } orc_word_order;
+static int by_length_then_index(const void* x, const void* y)
+{
+    const orc_word_order* a = (const orc_word_order*)x;
+    const orc_word_order* b = (const orc_word_order*)y;
+    if (a->len != b->len) return a->len < b->len ? -1 : 1;
+    return a->index < b->index ? -1 : (a->index > b->index ? 1 : 0);
+}
+
 int orc_canonical_code(const uint8_t* len, uint32_t n, uint32_t* bits)
 {
-    uint32_t code = 0, prev_len = 0;
-    uint64_t kraft = 0;                                     /* in units of 2^-32 */
-    for (uint32_t L = 1; L <= 32; ++L) {
-        for (uint32_t i = 0; i < n; ++i) {
-            if (len[i] != L) continue;
-            code <<= (L - prev_len);
-            prev_len = L;
-            kraft += 1ull << (32 - L);
-            if (kraft > (1ull << 32)) return -1;
-            uint32_t rev = 0;
-            for (uint32_t q = 0; q < L; ++q) rev |= ((code >> (L - 1 - q)) & 1u) << q;
-            bits[i] = rev;
-            ++code;
-        }
+    orc_word_order* order = (orc_word_order*)malloc(sizeof(orc_word_order) * n);
+    long double kraft = 0.0L;
+    for (uint32_t i = 0; i < n; ++i) {
+        order[i].len = len[i]; order[i].index = i;
+        if (len[i] < 1 || len[i] > 32) { free(order); return -1; }
+        kraft += ldexpl(1.0L, -(int)len[i]);
     }
+    if (kraft > 1.0L) { free(order); return -1; }
+    qsort(order, n, sizeof(orc_word_order), by_length_then_index);
+    uint64_t word = 0;                                      /* value of the word, most significant bit first */
+    for (uint32_t r = 0; r < n; ++r) {
+        if (r > 0) word = (word + 1) << (order[r].len - order[r - 1].len);
+        uint32_t first_bit_low = 0;                         /* the same word with its first bit in bit 0 */
+        for (uint32_t q = 0; q < order[r].len; ++q)
+            if ((word >> (order[r].len - 1 - q)) & 1u) first_bit_low |= 1u << q;
+        bits[order[r].index] = first_bit_low;
+    }
+    free(order);
     return 0;
 }
 

@@ -431,8 +431,11 @@ def test_fit_code_parity(qgx, norm, table, limit_active):
     assert int((w * cl_g.astype(np.uint64)).sum()) == int((w * cl_o.astype(np.uint64)).sum())
     assert cl_g.max() <= 11 and sum(2.0 ** -int(x) for x in cl_g) <= 1.0
     assert (cl_g.max() == 11) == limit_active or not limit_active
-    np.testing.assert_array_equal(cl_g, cl_o)       # and on these inputs no tie falls differently
-    np.testing.assert_array_equal(cb_g, cb_o)
+    # (the oracle minimises the cost over all length assignments by dynamic programming, the kernel builds
+    # its code by package-merge: where several assignments are optimal they may differ, the cost may not)
+    if limit_active:
+        np.testing.assert_array_equal(cl_g, cl_o)   # on this input the optimum is unique
+    np.testing.assert_array_equal(cb_g, oracle.canonical_code(cl_g))     # canonical words for the lengths chosen
     # coding with it, both placements
     out = ctx.new_stream()
     ctx.quantize_encode(dev(V), 4, out)
@@ -945,7 +948,26 @@ def test_random_configurations(qgx, monkeypatch, sweep, waves):
         ctx.fit_levels(dev(V0), n_sym, n_bins, sweeps=sweeps, hist_out=hist)
         H_o = oracle.histogram(V0, lay, norm, n_bins)
         np.testing.assert_allclose(hist.cpu().numpy(), H_o, rtol=1e-10, atol=0)
-        np.testing.assert_allclose(ctx.get_levels(), oracle.fit_levels(H_o, levels, sweeps=sweeps), rtol=REL, atol=1e-9)
+        lv_fit = ctx.get_levels()
+        np.testing.assert_allclose(lv_fit, oracle.fit_levels(H_o, levels, sweeps=sweeps), rtol=REL, atol=1e-9)
+        if fixed:
+            # Psi fitted to the symbol probabilities of the new table: p_j, the cost of the code (the one thing
+            # about an optimal code that is unique), canonical words; then a stream coded with it
+            p_g, cl_g, cb_g = ctx.fit_code()
+            p_o = oracle.symbol_probabilities(hist.cpu().numpy(), lv_fit)
+            np.testing.assert_allclose(p_g, p_o, rtol=1e-10, atol=1e-14)
+            w = oracle.code_weights(p_o)
+            cl_o = oracle.limited_prefix_lengths(w, 11)
+            assert int((w * cl_g.astype(np.uint64)).sum()) == int((w * cl_o.astype(np.uint64)).sum())
+            assert 1 <= cl_g.min() and cl_g.max() <= 11 and sum(2.0 ** -int(x) for x in cl_g) <= 1.0
+            np.testing.assert_array_equal(cb_g, oracle.canonical_code(cl_g))
+            ctx.quantize_encode(dev(V0), call + 2, tmp)
+            h = tmp.to_host()
+            _, idx, neg, _ = oracle.quantize(V0, lay, norm, lv_fit, seed, call + 2, norms_in=h["norms"])
+            so = oracle.encode(idx, neg, lay, ctx.worst_words, code_len=cl_g, code_bits=cb_g)
+            assert_stream_equal(h, so, lay)
+            np.testing.assert_array_equal(ctx.decode(tmp).cpu().numpy(),
+                                          oracle.decode(so, h["norms"], lay, lv_fit, code_len=cl_g, code_bits=cb_g)[0])
         assert ctx.poll_error() == 0
         ctx.close()
 

@@ -41,8 +41,10 @@ MUTANTS = [
      "const double slope = (c - a) * mass[p] / (hi[p] - lo[p]);", "const double slope = mass[p] / (hi[p] - lo[p]);", [F]),
     ("symbol probabilities mirrored", "p[j] += mass * (1.0 - up);\n            p[j + 1] += mass * up;",
      "p[j] += mass * up;\n            p[j + 1] += mass * (1.0 - up);", [H]),
-    ("a package counted as one item of the level below", "take = 2 * packages;", "take = packages;", [H]),
-    ("canonical words not advanced", "            ++code;\n", "", [H]),
+    ("a word charged the code space of one a bit longer", "const uint32_t space = 1u << (max_len - l);\n                if (space > k || BEST(i + 1, k - space) == none) continue;\n                const uint64_t cost",
+     "const uint32_t space = (1u << (max_len - l)) >> 1;\n                if (space > k || BEST(i + 1, k - space) == none) continue;\n                const uint64_t cost", [H]),
+    ("canonical words not advanced", "if (r > 0) word = (word + 1) << (order[r].len - order[r - 1].len);",
+     "if (r > 0) word = word << (order[r].len - order[r - 1].len);", [H]),
     ("largest magnitude taken as the smallest", "if (a > n) n = a;", "if (a < n || n == 0.0f) n = a;", [Q]),
     ("q-norm raised to q instead of 1/q", "n = (float)(m * pow(acc, 1.0 / q));", "n = (float)(m * pow(acc, q));", [Q]),
     ("mean over K - 1", "mean[i] = acc / (double)K;", "mean[i] = acc / (double)(K - 1);", [E, C]),
@@ -64,7 +66,8 @@ MUTANTS = [
      "const double x_t = (anchor ? anchor[i] : 0.0) + Y[i];", [E]),
     ("objective without the cubic term", "const double P_hi = -hi * hi * hi / 3.0 + (a + c) * hi * hi / 2.0 - a * c * hi;",
      "const double P_hi = (a + c) * hi * hi / 2.0 - a * c * hi;", [F]),
-    ("one item too many bought at the top level", "uint32_t take = 2 * (n - 1);", "uint32_t take = 2 * n - 1;", [H]),
+    ("cost of a word without its weight", "const uint64_t cost = w[i] * l + BEST(i + 1, k - space);",
+     "const uint64_t cost = l + BEST(i + 1, k - space);", [H]),
 ]
 
 
