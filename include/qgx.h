@@ -75,6 +75,7 @@ extern "C" {
 #define QGX_MAX_CODE_BITS 13u
 #define QGX_FIT_CODE_BITS 11u  /* longest word of a code made by qgx_fit_code */
 #define QGX_TABLES 2         /* level tables (each with its code) a context holds */
+#define QGX_STATIC_MAX_CHUNKS 65536u  /* most chunks per worker qgx_eg_step_static takes (2^28 coordinates) */
 
 typedef struct qgx_ctx qgx_ctx;
 
@@ -242,6 +243,21 @@ qgx_status qgx_state_init(qgx_ctx* ctx, const float* X1, void* stream);
  *             now, `prev` with the table qgx_select_table names for it. */
 qgx_status qgx_eg_step(qgx_ctx* ctx, int half, const qgx_stream* cur, const qgx_stream* prev,
                        float* X_out, void* stream);
+
+/* qgx_eg_step for callers that may not allocate device memory and want the guarantee in the interface:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same kernels, same results bit for bit as qgx_eg_step; the one difference is where the second
+ * half-step keeps its scratch, the per-chunk partial sums of S: not in memory that qgx_create allocated
+ * but in a fixed array inside the library's device image (8 * QGX_STATIC_MAX_CHUNKS = 512 KiB per GPU,
+ * held until the process ends; its address on a device is looked up once, in the first qgx_create on
+ * that device).  The call itself allocates and frees nothing.
+ *   - QGX_ERR_CAPACITY if the layout has more than QGX_STATIC_MAX_CHUNKS chunks per worker (qgx_eg_step
+ *     has no such limit); QGX_ERR_STATE if the context's device is not the current one.
+ *   - All contexts on one GPU share the array: every call overwrites the entries 0 .. n_chunks - 1 it
+ *     then reads and relies on nothing a previous call left, but two such calls that overlap on one
+ *     GPU (different streams or threads) race on it.  Calls on one stream, or ordered by events, do not. */
+qgx_status qgx_eg_step_static(qgx_ctx* ctx, int half, const qgx_stream* cur, const qgx_stream* prev,
+                              float* X_out, void* stream);
 
 /* Scalars of the iteration and of the last coding call.  Any pointer may be NULL.  Synchronises.
  * total_bits: symbols + signs of the last qgx_encode / qgx_quantize_encode over all workers,

@@ -5,12 +5,42 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
 #include "qgx_internal.h"
 
 using namespace qgx;
+
+// Scratch of qgx_eg_step_static, the variant of qgx_eg_step for callers that may not allocate: the
+// per-chunk partial sums of the step-size accumulator S, which qgx_eg_step keeps in memory that
+// qgx_create allocated.  Every GPU the library runs on holds its own copy of the array, at its own
+// address, until the process ends.  The name below is a host-side stand-in for it, not a device
+// address: host code uses the address hipGetSymbolAddress gave for the device (static_scratch_of).
+static __device__ __align__(256) double scratch[QGX_STATIC_MAX_CHUNKS];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+double* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Address of `scratch` on `device`, which must be the current device; asked for once per device.
+hipError_t static_scratch_of(int device, double** out)
+{
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = static_cast<double*>(p);
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
+}  // namespace
 
 // What the host knows of one of the context's level tables (the table itself lives on the device).
 struct TableState {
@@ -39,6 +69,7 @@ struct qgx_ctx {
     uint32_t parts = 1;                    // workgroups per bucket in the encoder
     unsigned long long* d_tickets = nullptr;
     double* d_spartial = nullptr;
+    double* d_static_scratch = nullptr;   // this device's copy of the file-scope scratch array (not owned)
     double* d_hpartial = nullptr;
     double* d_hist = nullptr;
     double* d_prob = nullptr;       // [kSymMax] symbol probabilities of the last qgx_fit_code
@@ -227,6 +258,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     c->worst_words = worst;
 
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return QGX_ERR_HIP; }
+    if (static_scratch_of(c->device, &c->d_static_scratch) != hipSuccess) { delete c; return QGX_ERR_HIP; }
     {
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess && cus > 0)
@@ -617,8 +649,8 @@ qgx_status qgx_state_init(qgx_ctx* ctx, const float* X1, void* stream)
     return QGX_OK;
 }
 
-qgx_status qgx_eg_step(qgx_ctx* ctx, int half, const qgx_stream* cur, const qgx_stream* prev, float* X_out,
-                       void* stream)
+static qgx_status eg_step_with(qgx_ctx* ctx, int half, const qgx_stream* cur, const qgx_stream* prev, float* X_out,
+                               void* stream, double* s_partial)
 {
     if (!ctx || (half != 0 && half != 1)) return fail(ctx, QGX_ERR_ARG, "qgx_eg_step: half must be 0 or 1");
     if (!ctx->state_ready) return fail(ctx, QGX_ERR_STATE, "qgx_eg_step before qgx_state_init");
@@ -643,10 +675,29 @@ qgx_status qgx_eg_step(qgx_ctx* ctx, int half, const qgx_stream* cur, const qgx_
         return QGX_OK;
     }
     fill_decode_args(ctx, a, cur, prev);
-    a.s_partial = ctx->d_spartial;
+    a.s_partial = s_partial;
     QGX_HIP(ctx, launch_decode(DecMode::Half1, ctx->lay, tab_of(ctx), ctx->d_sc, a, st, ctx->side_ok ? &ctx->side : nullptr));
-    QGX_HIP(ctx, launch_finish_half1(ctx->lay, ctx->d_sc, ctx->d_spartial, ctx->d_Y, a.anchor, X_out, st));
+    QGX_HIP(ctx, launch_finish_half1(ctx->lay, ctx->d_sc, s_partial, ctx->d_Y, a.anchor, X_out, st));
     return QGX_OK;
+}
+
+qgx_status qgx_eg_step(qgx_ctx* ctx, int half, const qgx_stream* cur, const qgx_stream* prev, float* X_out,
+                       void* stream)
+{
+    return eg_step_with(ctx, half, cur, prev, X_out, stream, ctx ? ctx->d_spartial : nullptr);
+}
+
+qgx_status qgx_eg_step_static(qgx_ctx* ctx, int half, const qgx_stream* cur, const qgx_stream* prev, float* X_out,
+                              void* stream)
+{
+    if (!ctx) return QGX_ERR_ARG;
+    if (ctx->lay.NC > QGX_STATIC_MAX_CHUNKS)
+        return fail(ctx, QGX_ERR_CAPACITY, "qgx_eg_step_static: %u chunks per worker exceed the %u the static scratch holds; use qgx_eg_step",
+                    ctx->lay.NC, (unsigned)QGX_STATIC_MAX_CHUNKS);
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != ctx->device)
+        return fail(ctx, QGX_ERR_STATE, "qgx_eg_step_static: the context's device must be current");
+    return eg_step_with(ctx, half, cur, prev, X_out, stream, ctx->d_static_scratch);
 }
 
 qgx_status qgx_average_reset(qgx_ctx* ctx, int on, void* stream)

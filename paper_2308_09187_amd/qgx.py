@@ -23,11 +23,12 @@ CALL_FIRST_HALF, CALL_SECOND_HALF = 0xFFFFFFFE, 0xFFFFFFFF   # call numbers take
 NORM_LINF, NORM_L2 = 0, 2
 CODE_ELIAS_OMEGA, CODE_TABLE = 0, 1
 CHUNK, SUB, SUBS, MAX_SYM, MAX_BINS = 4096, 32, 128, 127, 4096
+STATIC_MAX_CHUNKS = 65536
 
 EXPORTS = [
     "qgx_create", "qgx_destroy", "qgx_stream_sizes", "qgx_slot_words", "qgx_compact", "qgx_select_table", "qgx_set_levels", "qgx_get_levels", "qgx_set_code_table",
     "qgx_quantize", "qgx_encode", "qgx_quantize_encode", "qgx_decode", "qgx_decode_average", "qgx_fit_levels", "qgx_fit_code",
-    "qgx_state_init", "qgx_eg_step", "qgx_average_reset", "qgx_average_export", "qgx_get_scalars", "qgx_state_export", "qgx_state_import",
+    "qgx_state_init", "qgx_eg_step", "qgx_eg_step_static", "qgx_average_reset", "qgx_average_export", "qgx_get_scalars", "qgx_state_export", "qgx_state_import",
     "qgx_poll_error", "qgx_last_error",
 ]
 
@@ -221,11 +222,13 @@ class Context:
     def state_init(self, X1=None, stream=None):
         self._check(self.lib.qgx_state_init(self._h, _ptr(X1), _stream_handle(stream)))
 
-    def eg_step(self, half, cur: Stream, prev: Stream = None, X_out=None, stream=None):
+    def eg_step(self, half, cur: Stream, prev: Stream = None, X_out=None, stream=None, static=False):
+        """static: through qgx_eg_step_static (scratch in the library's device image, nothing allocated)."""
         c = cur.c_struct()
         p = prev.c_struct() if prev is not None else None
-        self._check(self.lib.qgx_eg_step(self._h, C.c_int(half), C.byref(c), C.byref(p) if p is not None else None,
-                                         _ptr(X_out), _stream_handle(stream)))
+        fn = self.lib.qgx_eg_step_static if static else self.lib.qgx_eg_step
+        self._check(fn(self._h, C.c_int(half), C.byref(c), C.byref(p) if p is not None else None,
+                       _ptr(X_out), _stream_handle(stream)))
         return X_out
 
     def select_table(self, table, prev_table=None):
