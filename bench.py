@@ -266,7 +266,7 @@ def main():
     upd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
     h_bits = a.sub_end.cpu().numpy().view(np.uint16)[:, :, -1].astype(np.int64)
     words = int((((h_bits + 31) // 32 + 3) // 4 * 4).sum())
-    bits = ctx.scalars(want_bits=True)["total_bits"]
+    bits = ctx.stream_bits(a)
     side_bytes = K * ((ctx.NC + 1) * 4 + ctx.NC * qgx.SUBS * 2 + ctx.NB * 4)
     stream_bytes = words * 4 + side_bytes
     enc_bytes = 4 * K * d + stream_bytes                 # read V once, write the coded streams

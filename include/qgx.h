@@ -203,8 +203,7 @@ qgx_status qgx_decode(qgx_ctx* ctx, const qgx_stream* in, float* Vhat, void* str
  * chunks to fill the GPU the workers are split in two or four runs (as equal as K allows, the
  * longer ones first), each added in order, and the runs' sums added in order (the same in
  * qgx_eg_step).  The number of runs follows from the layout, K and the device, so results repeat bit
- * for bit; QGX_KSPLIT=1, 2 or 4 in the environment when the context is created overrides the choice
- * (for tests and timing; ignored when above K). */
+ * for bit (qgx_debug_set_waves_per_position overrides the choice, for tests and timing). */
 qgx_status qgx_decode_average(qgx_ctx* ctx, const qgx_stream* in, float* mean, void* stream);
 
 /* Adaptive levels, eq. (QAda): weighted histogram of the normalised coordinates of V (each bucket
@@ -259,11 +258,16 @@ qgx_status qgx_eg_step(qgx_ctx* ctx, int half, const qgx_stream* cur, const qgx_
 qgx_status qgx_eg_step_static(qgx_ctx* ctx, int half, const qgx_stream* cur, const qgx_stream* prev,
                               float* X_out, void* stream);
 
-/* Scalars of the iteration and of the last coding call.  Any pointer may be NULL.  Synchronises.
- * total_bits: symbols + signs of the last qgx_encode / qgx_quantize_encode over all workers,
- * without padding and without the 32 bits per bucket for the norm. */
-qgx_status qgx_get_scalars(qgx_ctx* ctx, double* S, double* gamma, uint64_t* t, uint64_t* total_bits,
-                           void* stream);
+/* Scalars of the iteration.  Any pointer may be NULL.  Synchronises `stream`. */
+qgx_status qgx_get_scalars(qgx_ctx* ctx, double* S, double* gamma, uint64_t* t, void* stream);
+
+/* Bits of a coded stream over all workers: code words and signs, without padding and without the
+ * 32 bits per bucket for the norm (the quantity Theorem 2 bounds, less C_b per bucket).  Synchronises. */
+qgx_status qgx_stream_bits(qgx_ctx* ctx, const qgx_stream* coded, uint64_t* total_bits, void* stream);
+
+/* Test and timing hook: the number of waves that share a full chunk position in the decoding calls
+ * (1, 2 or 4; ignored when above K), or 0 to go back to the library's own rule.  Host-side only. */
+qgx_status qgx_debug_set_waves_per_position(qgx_ctx* ctx, int waves);
 
 /* Copies the dual state out (checkpoint) or in (resume).  Y, anchor DEVICE [d]; NULL skips. */
 qgx_status qgx_state_export(qgx_ctx* ctx, float* Y, float* anchor, void* stream);

@@ -29,8 +29,10 @@ def build(force: bool = False) -> str:
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
     if force or stale:
         tmp = _LIB + ".tmp%d" % os.getpid()
+        # QGX_ORACLE_CFLAGS: extra compiler flags for a build named by QGX_ORACLE_SRC (the sanitizer test)
+        extra = os.environ.get("QGX_ORACLE_CFLAGS", "").split() if os.environ.get("QGX_ORACLE_SRC") else []
         subprocess.check_call(
-            ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC",
+            ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", *extra,
              "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB

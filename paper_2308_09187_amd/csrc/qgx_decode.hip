@@ -702,13 +702,9 @@ static hipError_t launch_full_as(const Layout& lay, const Tables* tab, Scalars* 
 {
     if (lay.n_ragged == lay.NC) return hipSuccess;
     const size_t lds = (size_t)kDecWaves * (PREV ? 2 : 1) * a.stage_stride * sizeof(uint32_t);
-    static size_t lds_allowed = 0;                        // the limit is per kernel: raised when a launch needs more
-    if (lds > lds_allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<MODE, PREV, TWO, WIDE, KSPLIT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        lds_allowed = lds;
-    }
+    static LdsLimit limit;
+    hipError_t e = limit.ensure(reinterpret_cast<const void*>(&k_decode<MODE, PREV, TWO, WIDE, KSPLIT>), lds);
+    if (e != hipSuccess) return e;
     const uint64_t nwork = (MODE == DecMode::Decode) ? (uint64_t)lay.K * lay.NC : (uint64_t)lay.NC * (uint32_t)KSPLIT;
     const uint32_t grid = (uint32_t)((nwork + kDecWaves - 1) / kDecWaves);
     hipLaunchKernelGGL((k_decode<MODE, PREV, TWO, WIDE, KSPLIT>), dim3(grid), dim3(kDecWaves * kWave), lds, st, lay, tab, sc, a);
@@ -738,13 +734,9 @@ static hipError_t launch_ragged(const Layout& lay, const Tables* tab, Scalars* s
     if (lay.n_ragged == 0) return hipSuccess;
     constexpr int W = ragged_waves<PREV>();
     const size_t lds = (size_t)W * (PREV ? 2 : 1) * a.rag_stride * sizeof(uint32_t);
-    static size_t lds_allowed = 0;
-    if (lds > lds_allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_ragged<MODE, PREV, TWO>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        lds_allowed = lds;
-    }
+    static LdsLimit limit;
+    hipError_t e = limit.ensure(reinterpret_cast<const void*>(&k_decode_ragged<MODE, PREV, TWO>), lds);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((k_decode_ragged<MODE, PREV, TWO>), dim3(lay.n_ragged), dim3(W * kWave), lds, st, lay, tab, sc, a);
     return hipGetLastError();
 }

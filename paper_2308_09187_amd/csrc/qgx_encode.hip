@@ -721,13 +721,9 @@ static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc,
 {
     const int waves = (GROUPED || a.parts > 1u) ? 4 : (int)lay.waves_per_bucket;
     const size_t lds = encode_lds_bytes(waves, a, MODE != EncMode::QuantOnly, GROUPED);
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_encode<MODE, GROUPED, CM>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static LdsLimit limit;
+    hipError_t e = limit.ensure(reinterpret_cast<const void*>(&k_encode<MODE, GROUPED, CM>), 160 * 1024);
+    if (e != hipSuccess) return e;
     // one workgroup per bucket, per part of a bucket, or (shared chunks) per four chunks; in compact
     // placement and with split buckets each takes one ticket of its worker (the kernel's per_launch)
     const uint32_t units = GROUPED ? (lay.NC + 3u) / 4u : lay.NB * a.parts;

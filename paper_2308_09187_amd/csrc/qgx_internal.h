@@ -5,6 +5,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+#include <mutex>
+
 #include "../../include/qgx.h"
 
 namespace qgx {
@@ -157,6 +160,29 @@ struct DecodeArgs {
     uint32_t rag_stride;
     uint32_t wide;              // the 8-byte decode table of the current streams' code is valid (Tables::wide_ok)
     uint32_t ksplit;            // fused modes: 1, 2 or 4 waves per full position, a run of the workers each
+};
+
+// The dynamic LDS a kernel may be launched with is an attribute of the kernel on a device, raised with
+// hipFuncSetAttribute.  One object per kernel (a function-local static of its launcher) remembers, per
+// device, what was last granted, and asks again only when a launch needs more; contexts on several
+// threads and devices share it, hence the lock.
+struct LdsLimit {
+    static constexpr int kDevices = 64;
+    std::atomic<size_t> granted[kDevices];
+    std::mutex lock;
+    hipError_t ensure(const void* kernel, size_t bytes)
+    {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= kDevices) return hipErrorInvalidDevice;
+        if (bytes <= granted[dev].load(std::memory_order_acquire)) return hipSuccess;
+        std::lock_guard<std::mutex> hold(lock);
+        if (bytes <= granted[dev].load(std::memory_order_relaxed)) return hipSuccess;
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e == hipSuccess) granted[dev].store(bytes, std::memory_order_release);
+        return e;
+    }
 };
 
 hipError_t launch_build_tables(Tables* tab, hipStream_t st);

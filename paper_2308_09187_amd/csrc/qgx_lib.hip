@@ -55,7 +55,7 @@ struct qgx_ctx {
     std::vector<uint64_t> seg;
     int device = 0;
     uint32_t n_simd = 1024;          // SIMDs of the device (four per compute unit)
-    int ksplit_forced = -1;          // QGX_KSPLIT=1|2|4 in the environment at qgx_create, else -1: by the rule
+    int ksplit_forced = -1;          // qgx_debug_set_waves_per_position: 1, 2 or 4, else -1: by the rule
     Layout lay{};
     uint32_t* d_layout = nullptr;
     Tables* d_tabs = nullptr;        // [QGX_TABLES]
@@ -80,7 +80,6 @@ struct qgx_ctx {
     uint32_t hist_bins = 0;         // bins of the histogram d_hist holds (0: none yet)
     uint32_t h_groups = 0;
     bool state_ready = false, has_anchor = false;
-    const uint16_t* last_sub_end = nullptr;
     uint64_t worst_words = 0;
     char err[256] = "";
 };
@@ -102,6 +101,17 @@ qgx_status fail(qgx_ctx* ctx, qgx_status st, const char* fmt, ...)
     do {                                                                                               \
         hipError_t e_ = (call);                                                                        \
         if (e_ != hipSuccess) return fail((ctx), QGX_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+// The same after an asynchronous copy into a local variable has been queued on `st`: the function may
+// not return, and so end the variable's life, before the queue has drained.
+#define QGX_HIP_DRAIN(ctx, st, call)                                                                   \
+    do {                                                                                               \
+        hipError_t e_ = (call);                                                                        \
+        if (e_ != hipSuccess) {                                                                        \
+            (void)hipStreamSynchronize(st);                                                            \
+            return fail((ctx), QGX_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_));                   \
+        }                                                                                              \
     } while (0)
 
 // Length of Elias' recursive (omega) code of N >= 1: one terminating bit plus every prefixed group.
@@ -263,8 +273,6 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess && cus > 0)
             c->n_simd = 4u * (uint32_t)cus;
-        const char* f = getenv("QGX_KSPLIT");
-        if (f && (f[0] == '1' || f[0] == '2' || f[0] == '4') && f[1] == 0) c->ksplit_forced = f[0] - '0';
     }
     const size_t n_lay = (size_t)(NB + 1) * 2 + (NC + 1) + NC + ragged.size() + 1;
     std::vector<uint32_t> flat;
@@ -501,7 +509,6 @@ static qgx_status run_encode(qgx_ctx* ctx, EncMode mode, const float* V, uint32_
     a.tickets = ctx->d_tickets;
     hipError_t le = launch_encode(mode, ctx->lay, tab_of(ctx), ctx->d_sc, a, (hipStream_t)stream);
     if (le != hipSuccess) return fail(ctx, QGX_ERR_HIP, "encode launch: %s", hipGetErrorString(le));
-    if (mode != EncMode::QuantOnly) ctx->last_sub_end = out->sub_end;
     return QGX_OK;
 }
 
@@ -626,7 +633,7 @@ qgx_status qgx_fit_code(qgx_ctx* ctx, double* p_host, uint8_t* code_len_host, ui
     QGX_HIP(ctx, launch_fit_code(tab_of(ctx), ctx->d_hist, ctx->hist_bins, QGX_FIT_CODE_BITS, ctx->d_prob, st));
     uint32_t packed[kSymMax];
     QGX_HIP(ctx, hipMemcpyAsync(packed, tab_of(ctx)->code, sizeof(packed), hipMemcpyDeviceToHost, st));
-    if (p_host) QGX_HIP(ctx, hipMemcpyAsync(p_host, ctx->d_prob, T(ctx).n_sym * sizeof(double), hipMemcpyDeviceToHost, st));
+    if (p_host) QGX_HIP_DRAIN(ctx, st, hipMemcpyAsync(p_host, ctx->d_prob, T(ctx).n_sym * sizeof(double), hipMemcpyDeviceToHost, st));
     QGX_HIP(ctx, hipStreamSynchronize(st));
     T(ctx).max_code_len = 0;
     for (uint32_t j = 0; j < T(ctx).n_sym; ++j) {
@@ -726,21 +733,39 @@ qgx_status qgx_average_export(qgx_ctx* ctx, float* X_bar, uint64_t* count, void*
     return QGX_OK;
 }
 
-qgx_status qgx_get_scalars(qgx_ctx* ctx, double* S, double* gamma, uint64_t* t, uint64_t* total_bits, void* stream)
+qgx_status qgx_get_scalars(qgx_ctx* ctx, double* S, double* gamma, uint64_t* t, void* stream)
 {
     if (!ctx) return QGX_ERR_ARG;
     hipStream_t st = (hipStream_t)stream;
-    if (total_bits) {
-        if (!ctx->last_sub_end) return fail(ctx, QGX_ERR_STATE, "no coding call yet");
-        QGX_HIP(ctx, launch_sum_bits(ctx->lay, ctx->last_sub_end, ctx->d_sc, st));
-    }
     Scalars h;
     QGX_HIP(ctx, hipMemcpyAsync(&h, ctx->d_sc, sizeof(h), hipMemcpyDeviceToHost, st));
     QGX_HIP(ctx, hipStreamSynchronize(st));
     if (S) *S = h.S;
     if (gamma) *gamma = h.gamma;
     if (t) *t = h.t;
-    if (total_bits) *total_bits = h.total_bits;
+    return QGX_OK;
+}
+
+qgx_status qgx_stream_bits(qgx_ctx* ctx, const qgx_stream* coded, uint64_t* total_bits, void* stream)
+{
+    if (!ctx || !total_bits) return fail(ctx, QGX_ERR_ARG, "qgx_stream_bits: null argument");
+    qgx_status s = check_stream(ctx, coded, "qgx_stream_bits");
+    if (s != QGX_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+    QGX_HIP(ctx, launch_sum_bits(ctx->lay, coded->sub_end, ctx->d_sc, st));
+    unsigned long long bits = 0;
+    QGX_HIP(ctx, hipMemcpyAsync(&bits, &ctx->d_sc->total_bits, sizeof(bits), hipMemcpyDeviceToHost, st));
+    QGX_HIP(ctx, hipStreamSynchronize(st));
+    *total_bits = bits;
+    return QGX_OK;
+}
+
+qgx_status qgx_debug_set_waves_per_position(qgx_ctx* ctx, int waves)
+{
+    if (!ctx) return QGX_ERR_ARG;
+    if (waves != 0 && waves != 1 && waves != 2 && waves != 4)
+        return fail(ctx, QGX_ERR_ARG, "qgx_debug_set_waves_per_position: 0 (by the rule), 1, 2 or 4");
+    ctx->ksplit_forced = waves == 0 ? -1 : waves;
     return QGX_OK;
 }
 

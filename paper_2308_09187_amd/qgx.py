@@ -13,8 +13,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# QGX_LIB names another build of the same library (to time two builds side by side)
-LIB_PATH = os.environ.get("QGX_LIB") or os.path.join(_HERE, "libqgx.so")
+LIB_PATH = os.path.join(_HERE, "libqgx.so")
 
 OK = 0
 ERR_ARG, ERR_LEVELS, ERR_CAPACITY, ERR_STREAM, ERR_NONFINITE, ERR_HIP, ERR_STATE = -1, -2, -3, -4, -5, -6, -7
@@ -28,7 +27,7 @@ STATIC_MAX_CHUNKS = 65536
 EXPORTS = [
     "qgx_create", "qgx_destroy", "qgx_stream_sizes", "qgx_slot_words", "qgx_compact", "qgx_select_table", "qgx_set_levels", "qgx_get_levels", "qgx_set_code_table",
     "qgx_quantize", "qgx_encode", "qgx_quantize_encode", "qgx_decode", "qgx_decode_average", "qgx_fit_levels", "qgx_fit_code",
-    "qgx_state_init", "qgx_eg_step", "qgx_eg_step_static", "qgx_average_reset", "qgx_average_export", "qgx_get_scalars", "qgx_state_export", "qgx_state_import",
+    "qgx_state_init", "qgx_eg_step", "qgx_eg_step_static", "qgx_average_reset", "qgx_average_export", "qgx_get_scalars", "qgx_stream_bits", "qgx_debug_set_waves_per_position", "qgx_state_export", "qgx_state_import",
     "qgx_poll_error", "qgx_last_error",
 ]
 
@@ -246,11 +245,19 @@ class Context:
         self._check(self.lib.qgx_average_export(self._h, _ptr(out), C.byref(n), _stream_handle(stream)))
         return out, n.value
 
-    def scalars(self, want_bits=False, stream=None):
-        S, g, t, b = C.c_double(), C.c_double(), C.c_uint64(), C.c_uint64()
-        self._check(self.lib.qgx_get_scalars(self._h, C.byref(S), C.byref(g), C.byref(t),
-                                             C.byref(b) if want_bits else None, _stream_handle(stream)))
-        return dict(S=S.value, gamma=g.value, t=t.value, total_bits=b.value if want_bits else None)
+    def scalars(self, stream=None):
+        S, g, t = C.c_double(), C.c_double(), C.c_uint64()
+        self._check(self.lib.qgx_get_scalars(self._h, C.byref(S), C.byref(g), C.byref(t), _stream_handle(stream)))
+        return dict(S=S.value, gamma=g.value, t=t.value)
+
+    def stream_bits(self, coded: Stream, stream=None):
+        """Code-word and sign bits of a coded stream over all workers (no padding, no norms)."""
+        c, b = coded.c_struct(), C.c_uint64()
+        self._check(self.lib.qgx_stream_bits(self._h, C.byref(c), C.byref(b), _stream_handle(stream)))
+        return b.value
+
+    def debug_set_waves_per_position(self, waves):
+        self._check(self.lib.qgx_debug_set_waves_per_position(self._h, C.c_int(waves)))
 
     def state_export(self, stream=None):
         Y = torch.empty(self.d, dtype=torch.float32, device=self.device)

@@ -75,7 +75,7 @@ def test_full_size_sampled_against_oracle(K, logd, bucket, n_sym, slotted, fitte
     assert (np.diff(h["sub_end"].astype(np.int64), axis=2) >= oracle.SUB()).all()    # >= 1 bit per coordinate
     assert (h["sub_end"][:, :, 0] >= oracle.SUB()).all()
     assert (bits <= 4096 * (longest + 1)).all()                            # longest word plus sign
-    assert ctx.scalars(want_bits=True)["total_bits"] == int(bits.sum())
+    assert ctx.stream_bits(a) == int(bits.sum())
     assert np.isfinite(h["norms"]).all() and (h["norms"] > 0).all()
 
     # -- sampled buckets: norm, symbols -> stream bits, exactly --------------------------------
@@ -242,7 +242,7 @@ def test_longest_vector():
     assert ctx.poll_error() == 0
     h = a.to_host()
     bits = h["sub_end"][:, :, -1].astype(np.int64)
-    assert ctx.scalars(want_bits=True)["total_bits"] == int(bits.sum())
+    assert ctx.stream_bits(a) == int(bits.sum())
     assert (np.diff(h["chunk_off"].astype(np.int64), axis=1) == ctx.slot_words()).all()
     assert np.isfinite(h["norms"]).all() and (h["norms"] > 0).all()
     lay_c = oracle.layout(4096, 4096)

@@ -29,12 +29,35 @@ def rel_err(a, b):
     return np.linalg.norm(a - b) / (nb if nb > 0 else 1.0)
 
 
+def mean_abs(Vhat):
+    """(1/K) sum_k |vhat_k,i|: the scale of a coordinate of the aggregate."""
+    acc = np.zeros(Vhat.shape[1], np.float64)
+    for row in Vhat:
+        acc += np.abs(row)
+    return acc / Vhat.shape[0]
+
+
+def assert_elementwise(got, want, scale, what=""):
+    """Coordinate by coordinate: |got - want| <= 1e-6 * scale_i, with scale_i the sum of the magnitudes
+    that enter coordinate i (the decoded vectors are exact, so an aggregate or an iterate is off by a
+    handful of binary32 roundings of those magnitudes: (K + 1) 2^-24 for a mean over K <= 8 workers,
+    four more for an update).  A 2-norm over 2^24 coordinates would hide one wrong coordinate."""
+    err = np.abs(np.asarray(got, np.float64) - np.asarray(want, np.float64))
+    bad = err > REL * np.asarray(scale, np.float64) + 1e-37
+    assert not bad.any(), "%s: %d coordinates off, first at %d: %r vs %r" % (
+        what, int(bad.sum()), int(np.argmax(bad)), got[int(np.argmax(bad))], want[int(np.argmax(bad))])
+
+
 def dev(x):
     return torch.from_numpy(np.ascontiguousarray(x)).cuda()
 
 
+WAVES_PER_POSITION = {"waves": 0}      # forced through the library's test hook for every context made here (0: its own rule)
+
+
 def make_ctx(qgx, d, K, bucket, norm, levels, seed=7, segs=None, code=0):
     ctx = qgx.Context(d, K, bucket, norm=norm, code=code, seed=seed, segment_len=segs)
+    ctx.debug_set_waves_per_position(WAVES_PER_POSITION["waves"])
     ctx.set_levels(levels)
     lay = oracle.layout(d, bucket, segs)
     assert (ctx.NB, ctx.NC) == (lay.NB, lay.NC)
@@ -123,7 +146,7 @@ def test_quantize_encode_decode_parity(qgx, d, K, bucket, norm, tab, segs):
     h = out.to_host()
     np.testing.assert_array_equal(h["norms"], norms_g)
     assert_stream_equal(h, st_o, lay)
-    assert ctx.scalars(want_bits=True)["total_bits"] == int(st_o.total_bits.sum())
+    assert ctx.stream_bits(out) == int(st_o.total_bits.sum())
 
     # slotted placement: the same bits chunk by chunk at fixed slots; decodes alike; compacts to the same bytes
     slot = ctx.slot_words()
@@ -162,6 +185,59 @@ def test_quantize_encode_decode_parity(qgx, d, K, bucket, norm, tab, segs):
     # and another call_id gives another draw
     ctx.quantize_encode(Vd, call + 1, out3)
     assert not np.array_equal(out3.to_host()["payload"], h["payload"])
+    ctx.close()
+
+
+@pytest.mark.parametrize("tab", ["uni16", "exp16"])
+def test_single_vector_operator_over_32_calls(qgx, tab):
+    """Workload 2: one vector of 2^20 iid N(0,1) coordinates, buckets of 8192, L2 norm, 16 uniform or 16
+    exponential levels, one quantise + encode + decode round trip for each call number 0..31 (the 32 seeds).
+    Every stream bit for bit against the oracle; and on the GPU's own decoded vectors: the mean over the
+    32 draws is within 5 sigma of unbiased (||mean - v||^2 against Var / 32), the realised variance is
+    within 1 % of eq. (var), and bucket by bucket it respects eps_Q ||v||^2 of Theorem 1 with d the
+    bucket length (the worked values 4.782 and 0.125002)."""
+    d, K, bucket, seed, R = 1 << 20, 1, 8192, 10, 32
+    v = synth.gaussian_vector(d, seed=10)
+    V = v[None, :]
+    levels = table(tab)
+    ctx, lay = make_ctx(qgx, d, K, bucket, oracle.NORM_L2, levels, seed=seed)
+    Vd = dev(V)
+    out = ctx.new_stream()
+    v64 = v.astype(np.float64)
+    acc, sq = np.zeros(d), np.zeros(lay.NB)
+    for call in range(R):
+        ctx.quantize_encode(Vd, call, out)
+        Vh = ctx.decode(out).cpu().numpy()
+        h = out.to_host()
+        if call == 0:
+            n_o = oracle.quantize(V, lay, oracle.NORM_L2, levels, seed, 0)[0]
+            assert np.max(np.abs(h["norms"] - n_o) / n_o) <= REL
+        _, _, _, so = oracle_stream(V, lay, oracle.NORM_L2, levels, seed, call, h["norms"], ctx.worst_words)
+        assert_stream_equal(h, so, lay)
+        np.testing.assert_array_equal(Vh, oracle.decode(so, h["norms"], lay, levels)[0])
+        acc += Vh[0]
+        sq += ((Vh[0].astype(np.float64) - v64) ** 2).reshape(lay.NB, bucket).sum(1)
+    # eq. (var), bucket by bucket, in binary64 from Definition 1
+    lv = levels.astype(np.float64)
+    vb = v64.reshape(lay.NB, bucket)
+    n = np.sqrt((vb * vb).sum(1))
+    u = np.abs(vb) / n[:, None]
+    tau = np.minimum(np.searchsorted(lv, u, side="right") - 1, len(lv) - 2)
+    var_i = n[:, None] ** 2 * (lv[tau + 1] - u) * (u - lv[tau])        # variance of every coordinate's draw
+    var_b = var_i.sum(1)
+    assert abs(sq.sum() / R - var_b.sum()) <= 0.01 * var_b.sum()
+    # unbiasedness: E ||mean - v||^2 = Var / R; the statistic is a sum over 2^20 independent coordinates whose
+    # variance is about 2 sum sigma_i^4 / R^2
+    stat = ((acc / R - v64) ** 2).sum()
+    sigma = np.sqrt(2.0 * (var_i ** 2).sum()) / R
+    assert abs(stat - var_b.sum() / R) <= 5 * sigma
+    # Theorem 1 with d = 8192 = bucket length
+    l1, lbar = lv[1], (lv[2:] / lv[1:-1]).max()
+    dth = (2 / l1) ** 2
+    eps = (lbar + 1 / lbar) / 4 - 0.5 + (0.25 * l1 * l1 * bucket if bucket < dth else l1 * np.sqrt(bucket) - 1)
+    assert abs(eps - (4.78185425 if tab == "uni16" else 0.12500191)) < 1e-6
+    assert (var_b <= eps * n * n).all() and (sq / R <= eps * n * n).all()
+    assert ctx.poll_error() == 0
     ctx.close()
 
 
@@ -594,11 +670,11 @@ def test_lockstep_with_65_levels(qgx):
                                                      (7, 4096, 16, 4), (4, 8192, 64, 4), (8, 1024, 16, 1), (3, 8192, 64, 1)])
 def test_positions_shared_by_several_waves(qgx, monkeypatch, K, bucket, n_levels, waves):
     """Layouts with few chunk positions give every full position to two or four waves, a run of the
-    workers each, which join their sums before the update; here that is forced (the library reads
-    QGX_KSPLIT when a context is made), for K that does and does not divide evenly, both decode tables,
+    workers each, which join their sums before the update; here that is forced (through the library's
+    test hook, for every context made), for K that does and does not divide evenly, both decode tables,
     buckets sharing chunks, and with ragged positions beside the full ones.  The same lock-step
     comparison as everywhere else; the mean over the workers goes through decode_average as well."""
-    monkeypatch.setenv("QGX_KSPLIT", str(waves))
+    monkeypatch.setitem(WAVES_PER_POSITION, "waves", waves)
     d = 5 * 8192 + 1500
     game = synth.QuadraticGame(d=d, K=K)
     game.x1 = lambda: np.zeros(game.d, np.float32)
@@ -877,7 +953,7 @@ def test_random_configurations(qgx, monkeypatch, sweep, waves):
     mean, both half-steps and S to 1e-6, no error bit.  Layouts this small give a chunk position to
     several waves; `waves` = 1 makes the library take the one-wave kernels of large layouts instead."""
     if waves is not None:
-        monkeypatch.setenv("QGX_KSPLIT", str(waves))
+        monkeypatch.setitem(WAVES_PER_POSITION, "waves", waves)
     rng = np.random.default_rng(sweep)
     done = 0
     while done < 20:
@@ -1078,8 +1154,14 @@ def test_gan_layout_full_size(qgx):
     assert_stream_equal(ha, sa, lay); assert_stream_equal(hb, sb, lay)
     Va, _, _ = oracle.decode(sa, ha["norms"], lay, levels)
     Vb, _, _ = oracle.decode(sb, hb["norms"], lay, levels)
-    assert rel_err(Xh.cpu().numpy(), st.half0(Va)) <= REL
-    assert rel_err(Xn.cpu().numpy(), st.half1(Vb, Va)) <= REL
+    g1 = st.gamma
+    Xh_o = st.half0(Va)
+    assert rel_err(Xh.cpu().numpy(), Xh_o) <= REL
+    assert_elementwise(Xh.cpu().numpy(), Xh_o, g1 * mean_abs(Va), "X_{t+1/2}")       # X_1 = 0, Y_1 = 0
+    Xn_o = st.half1(Vb, Va)
+    assert rel_err(Xn.cpu().numpy(), Xn_o) <= REL
+    assert_elementwise(Xn.cpu().numpy(), Xn_o, st.gamma * mean_abs(Vb), "X_{t+1}")
+    assert_elementwise(ctx.state_export()[0].cpu().numpy(), st.Y, mean_abs(Vb), "Y_{t+1}")
     sc = ctx.scalars()
     assert abs(sc["S"] - st.S) <= REL * st.S and abs(sc["gamma"] - st.gamma) <= REL * st.gamma
     assert ctx.poll_error() == 0
@@ -1112,12 +1194,19 @@ def test_headline_workload_whole_output(qgx):
     _, _, _, sa = oracle_stream(V0, lay, oracle.NORM_L2, levels, seed, 0, ha["norms"], ctx.worst_words)
     assert_stream_equal(ha, sa, lay)
     Va, _, _ = oracle.decode(sa, ha["norms"], lay, levels)
-    assert rel_err(Xh.cpu().numpy(), st.half0(Va)) <= REL
+    g1 = st.gamma
+    Xh_o = st.half0(Va)
+    assert rel_err(Xh.cpu().numpy(), Xh_o) <= REL
+    assert_elementwise(Xh.cpu().numpy(), Xh_o, g1 * mean_abs(Va), "X_{t+1/2}")       # X_1 = 0, Y_1 = 0
+    assert_elementwise(ctx.decode_average(a).cpu().numpy(), oracle.mean(Va), mean_abs(Va), "mean")
     del V0, sa
     _, _, _, sb = oracle_stream(V1, lay, oracle.NORM_L2, levels, seed, 1, hb["norms"], ctx.worst_words)
     assert_stream_equal(hb, sb, lay)
     Vb, _, _ = oracle.decode(sb, hb["norms"], lay, levels)
-    assert rel_err(Xn.cpu().numpy(), st.half1(Vb, Va)) <= REL
+    Xn_o = st.half1(Vb, Va)
+    assert rel_err(Xn.cpu().numpy(), Xn_o) <= REL
+    assert_elementwise(Xn.cpu().numpy(), Xn_o, st.gamma * mean_abs(Vb), "X_{t+1}")
+    assert_elementwise(ctx.state_export()[0].cpu().numpy(), st.Y, mean_abs(Vb), "Y_{t+1}")
     sc = ctx.scalars()
     assert abs(sc["S"] - st.S) <= REL * st.S and abs(sc["gamma"] - st.gamma) <= REL * st.gamma
     assert ctx.poll_error() == 0
