@@ -20,6 +20,7 @@ namespace qgx {
 
 constexpr int kPre = kChunkWordsMax / (kWave * 4);   // 7 x uint4 per lane cover a worst-case chunk
 constexpr int kDecWaves = 8;                          // waves per workgroup: they share the decode table
+constexpr int kLead = 4;                              // zero words in front of a staged chunk (full positions)
 
 // Staged chunk layout in LDS.  Lane j parses the j-th run of 64 coordinates, whose bits start roughly
 // 64 * (bits per coordinate) / 32 words after lane j-1's: a power-of-two stride that would put all
@@ -61,17 +62,22 @@ __device__ __forceinline__ void prefetch_chunk(const ChunkRef& cr, uint4 (&pre)[
     }
 }
 
+// LEAD: words of zeros kept in front of the chunk (0 or kLead), so that a cursor may point one bit
+// before the chunk's first bit.
+template <int LEAD = 0>
 __device__ __forceinline__ void commit_chunk(uint32_t* stage, const uint4 (&pre)[kPre], uint32_t stage_words)
 {
+    static_assert(LEAD % 4 == 0, "16-byte pieces stay aligned");
     const uint32_t lane = (uint32_t)lane_id();
 #pragma unroll
     for (int q = 0; q < kPre; ++q) {
         const uint32_t i0 = (lane + (uint32_t)q * kWave) * 4u;
         if (i0 < stage_words) {
-            uint2* at = reinterpret_cast<uint2*>(stage + staged(i0));          // even slot: 8-byte aligned
+            const uint32_t j0 = i0 + (uint32_t)LEAD;
+            uint2* at = reinterpret_cast<uint2*>(stage + staged(j0));          // even slot: 8-byte aligned
             at[0] = make_uint2(pre[q].x, pre[q].y);
             at[1] = make_uint2(pre[q].z, pre[q].w);
-            if ((i0 & 31u) == 0u && i0 != 0u) at[-1] = make_uint2(pre[q].x, pre[q].y);   // pads repeat their successors
+            if ((j0 & 31u) == 0u && j0 != 0u) at[-1] = make_uint2(pre[q].x, pre[q].y);   // pads repeat their successors
         }
     }
 }
@@ -128,6 +134,54 @@ __device__ __forceinline__ void parse_group(const Window& w, const unsigned char
 {
     float unused[3];
     parse_group<N, false>(w, tab, p, win, e, unused);
+}
+
+// The same chain for the kernel of the full positions, with the windows taken one bit early: the cursor
+// q points at the bit BEFORE the next symbol, so bit 31 of a symbol's window is the last bit of the
+// symbol before it, which is that symbol's sign if it has one.  The sign of a symbol is thus read off
+// the window of the next one with a single AND-OR, no shift by its length: W[i + 1] for symbol i, the
+// next group's W[0] for a group's last symbol, and for the last group of a run (LAST, two symbols) the
+// window after its second symbol, W[2].  The table index sits one bit lower (bits 30..20 resp. 30..18).
+// `all_neg` gathers the AND of the groups' (negative) bit counts: a reject entry (bit 15) leaves a zero
+// among its bits 15..31, valid entries (below 0x2000 each) never do, so no per-symbol flag is kept.
+template <int N, bool WIDE, bool LAST>
+__device__ __forceinline__ void parse_group_early(const Window& w, const unsigned char* tab, uint32_t& q,
+                                                  uint32_t (&W)[4], uint32_t (&e)[3], float (&lv)[3], uint32_t& all_neg)
+{
+    static_assert(!LAST || N == 2, "a run of 32 symbols ends with a group of two");
+    const uint32_t top = __brev(__builtin_amdgcn_alignbit(w.w1, w.w0, q));    // shifts use q mod 32
+    const uint32_t nxt = __brev(__builtin_amdgcn_alignbit(w.w2, w.w1, q));
+    uint32_t neg = 0;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        W[i] = i == 0 ? top : __builtin_amdgcn_alignbit(top, nxt, neg);       // (top:nxt) << used, upper word
+        if constexpr (WIDE) {
+            const uint2 t = *reinterpret_cast<const uint2*>(tab + kTabLvalBytes + ((W[i] >> 17) & 0x3FF8u));
+            e[i] = t.x;
+            lv[i] = __uint_as_float(t.y);
+        } else {
+            e[i] = *reinterpret_cast<const uint16_t*>(tab + kTabLvalBytes + ((W[i] >> 17) & 0x3FFEu));
+        }
+        neg += ~e[i];
+    }
+    if constexpr (LAST) W[N] = __builtin_amdgcn_alignbit(top, nxt, neg);     // at least two bits used: never a shift by 0
+    all_neg &= neg;
+    q -= neg | 0xFFFFFFC0u;
+}
+
+// norm with the sign of the symbol whose last bit is bit 31 of `w_next` (norms are not negative)
+__device__ __forceinline__ float signed_norm(uint32_t w_next, float n)
+{
+    return __uint_as_float((w_next & 0x80000000u) | __float_as_uint(n));
+}
+
+// +-(norm * level), one binary32 product, sign from the window of the next symbol
+template <bool EXACT_ZERO>
+__device__ __forceinline__ float value_early(uint32_t w_next, float lv, uint32_t e, float n)
+{
+    const float val = __uint_as_float((w_next & 0x80000000u) | __float_as_uint(n * lv));
+    if (EXACT_ZERO) return (e >> 4) == 0u ? 0.0f : val;
+    return val;
 }
 
 __device__ __forceinline__ float level_of(const unsigned char* tab, uint32_t e)
@@ -219,7 +273,6 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
     const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
     const int part = w & (KSPLIT - 1);                   // this wave's place in its group
     constexpr int kBufs = PREV ? 2 : 1;
-    constexpr bool kExact = MODE == DecMode::Decode;
     const uint32_t stage_words = a.stage_words;          // words a chunk of this code can take
     const uint32_t stage_stride = a.stage_stride;        // padded size of one staging buffer, words
     uint32_t* stage = s_dyn + (size_t)w * kBufs * stage_stride;
@@ -275,7 +328,7 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
 #pragma unroll
     for (int s = 0; s < kLaneCoords; ++s) acc[s] = 0.0f;
     double sdiff = 0.0;
-    uint32_t flags = 0;
+    uint32_t all_neg = 0xFFFFFFFFu;
     bool malformed = false;
 
     // Two streams: the next worker's chunks are already in flight in registers while these are parsed.
@@ -301,8 +354,8 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
         const uint32_t k = k_first + kk;
         const SubMeta cur = nxt, prv = nxt_p;
         if constexpr (!kAhead) prefetch_chunk(cr, pre);
-        commit_chunk(stage, pre, stage_words);
-        if constexpr (PREV) commit_chunk(stage_p, pre_p, stage_words);
+        commit_chunk<kLead>(stage, pre, stage_words);
+        if constexpr (PREV) commit_chunk<kLead>(stage_p, pre_p, stage_words);
         if (kk + 1 < k_count) {
             cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, a.sub_end, k + 1, c, lay.NC, stage_words, sc);
             nxt = load_meta(a.sub_end, a.norms, k + 1, c, bkt, lay, lane);
@@ -319,58 +372,68 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
         const float n = cur.n, np = prv.n;
         float* vout = nullptr;
         if constexpr (MODE == DecMode::Decode) vout = a.out + (size_t)k * lay.d + clo + 64u * (uint32_t)lane;
-        uint32_t win[3], e[3], win_p[3] = {0u, 0u, 0u}, e_p[3] = {0u, 0u, 0u};
+        // From stream bit p to the staged chunk's bit before it: the chunk has kLead zero words in front.
+        constexpr uint32_t kEarly = 32u * (uint32_t)kLead - 1u;
+        constexpr int kHalf = kLaneCoords / 2;
         if constexpr (!PREV) {
-            // the lane's two sub-chunks side by side: ten groups of three symbols and one of two each
-            constexpr int kHalf = kLaneCoords / 2;
+            // the lane's two sub-chunks side by side: ten groups of three symbols and one of two each;
+            // a group's last symbol is finished when the next group's first window (its sign on top) is there
             uint32_t pb = cur.p_mid;
             if (pb > p_limit) { pb = p_limit; malformed = true; }
-            uint32_t win_b[3], e_b[3];
-            Window wn = read_window(stage, p), wn_b = read_window(stage, pb);
+            uint32_t q = p + kEarly, qb = pb + kEarly;
+            uint32_t W[4], e[3], W_b[4], e_b[3];
+            float lv_held = 0.0f, lv_held_b = 0.0f;
+            uint32_t e_held = 0u, e_held_b = 0u;
+            Window wn = read_window(stage, q), wn_b = read_window(stage, qb);
+            auto emit = [&](int at, uint32_t w_next, float lv, uint32_t en) {
+                if constexpr (MODE == DecMode::Decode) {
+                    vout[at] = value_early<true>(w_next, lv, en, n);
+                } else if constexpr (MODE == DecMode::Half1) {           // no previous streams: the vectors of t count as zero
+                    const float val = value_early<false>(w_next, lv, en, n);
+                    acc[at] += val;
+                    sdiff = fma((double)val, (double)val, sdiff);
+                } else {
+                    acc[at] = fmaf(signed_norm(w_next, n), lv, acc[at]);    // (a stray sign on a zero adds nothing)
+                }
+            };
 #pragma unroll
             for (int s = 0; s < kHalf; s += 3) {
                 float lv[3], lv_b[3];
-                if (s + 3 <= kHalf) parse_group<3, WIDE>(wn, s_tab, p, win, e, lv);
-                else parse_group<2, WIDE>(wn, s_tab, p, win, e, lv);
-                if (s + 3 < kHalf) wn = read_window(stage, p);
-                if (s + 3 <= kHalf) parse_group<3, WIDE>(wn_b, s_tab, pb, win_b, e_b, lv_b);
-                else parse_group<2, WIDE>(wn_b, s_tab, pb, win_b, e_b, lv_b);
-                if (s + 3 < kHalf) wn_b = read_window(stage, pb);
+                if (s + 3 <= kHalf) {
+                    parse_group_early<3, WIDE, false>(wn, s_tab, q, W, e, lv, all_neg);
+                    wn = read_window(stage, q);
+                    parse_group_early<3, WIDE, false>(wn_b, s_tab, qb, W_b, e_b, lv_b, all_neg);
+                    wn_b = read_window(stage, qb);
+                } else {
+                    parse_group_early<2, WIDE, true>(wn, s_tab, q, W, e, lv, all_neg);
+                    parse_group_early<2, WIDE, true>(wn_b, s_tab, qb, W_b, e_b, lv_b, all_neg);
+                }
+                const int cnt = s + 3 <= kHalf ? 3 : 2;
+                if constexpr (!WIDE) {
 #pragma unroll
-                for (int i = 0; i < 3; ++i) {
-                    if (s + i < kHalf) {
-                        if constexpr (!WIDE) {
-                            lv[i] = level_of(s_tab, e[i]);
-                            lv_b[i] = level_of(s_tab, e_b[i]);
-                        }
-                        flags |= e[i] | e_b[i];
+                    for (int i = 0; i < 3; ++i) {
+                        if (i < cnt) { lv[i] = level_of(s_tab, e[i]); lv_b[i] = level_of(s_tab, e_b[i]); }
                     }
                 }
+                if (s > 0) { emit(s - 1, W[0], lv_held, e_held); emit(kHalf + s - 1, W_b[0], lv_held_b, e_held_b); }
 #pragma unroll
-                for (int i = 0; i < 3; ++i) {
-                    if (s + i < kHalf) {
-                        const float val = symbol_value<kExact>(lv[i], win[i], e[i], n);
-                        const float val_b = symbol_value<kExact>(lv_b[i], win_b[i], e_b[i], n);
-                        if constexpr (MODE == DecMode::Decode) { vout[s + i] = val; vout[kHalf + s + i] = val_b; }
-                        else { acc[s + i] += val; acc[kHalf + s + i] += val_b; }
-                        if constexpr (MODE == DecMode::Half1) {
-                            sdiff = fma((double)val, (double)val, sdiff);
-                            sdiff = fma((double)val_b, (double)val_b, sdiff);
-                        }
-                    }
+                for (int i = 0; i < 2; ++i) {
+                    if (i + 1 < cnt || cnt == 2) { emit(s + i, W[i + 1], lv[i], e[i]); emit(kHalf + s + i, W_b[i + 1], lv_b[i], e_b[i]); }
                 }
+                if (cnt == 3) { lv_held = lv[2]; e_held = e[2]; lv_held_b = lv_b[2]; e_held_b = e_b[2]; }
             }
-            if (p != cur.p_mid) malformed = true;
-            p = pb;
+            if (q - kEarly != cur.p_mid) malformed = true;
+            p = qb - kEarly;
         } else {
             // two streams, two sub-chunks each: four chains, ten groups of three symbols and one of two
-            constexpr int kHalf = kLaneCoords / 2;
             uint32_t pb = cur.p_mid, ppb = prv.p_mid;
             if (pb > p_limit) { pb = p_limit; malformed = true; }
             if (ppb > p_limit) { ppb = p_limit; malformed = true; }
-            uint32_t win_b[3], e_b[3], win_pb[3], e_pb[3];
-            Window wn = read_window(stage, p), wn_b = read_window(stage, pb);
-            Window wn_p = read_window(stage_p, pp), wn_pb = read_window(stage_p, ppb);
+            uint32_t q = p + kEarly, qb = pb + kEarly, qp = pp + kEarly, qpb = ppb + kEarly;
+            uint32_t W[4], e[3], W_b[4], e_b[3], W_p[4], e_p[3], W_pb[4], e_pb[3];
+            float lv_held = 0.0f, lv_held_b = 0.0f, lv_held_p = 0.0f, lv_held_pb = 0.0f;
+            Window wn = read_window(stage, q), wn_b = read_window(stage, qb);
+            Window wn_p = read_window(stage_p, qp), wn_pb = read_window(stage_p, qpb);
             // Squared differences: six at a time in binary32 (at most six roundings on a sum of
             // non-negative terms), the groups in binary64.  The differences are scaled by a power of two
             // taken from the larger of the lane's two norms, so that no square leaves the range of
@@ -380,60 +443,69 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
             const double up2 = __longlong_as_double((long long)(2 * (int)ex - 254 + 1023) << 52);   // 2^(2 ex - 254)
             float sd32 = 0.0f;
             double sw = 0.0;
+            auto emit2 = [&](int at, uint32_t w_next, float lv, uint32_t w_next_p, float lv_p) {
+                const float val = value_early<false>(w_next, lv, 0u, n);
+                acc[at] += val;
+                const float df = (value_early<false>(w_next_p, lv_p, 0u, np) - val) * down;   // (a stray sign on a zero does not show in a difference)
+                sd32 = fmaf(df, df, sd32);
+            };
 #pragma unroll
             for (int s = 0; s < kHalf; s += 3) {
                 float lv[3], lv_p[3], lv_b[3], lv_pb[3];
-                if (s + 3 <= kHalf) parse_group<3, WIDE>(wn, s_tab, p, win, e, lv);
-                else parse_group<2, WIDE>(wn, s_tab, p, win, e, lv);
-                if (s + 3 < kHalf) wn = read_window(stage, p);
-                if (s + 3 <= kHalf) parse_group<3, WIDE>(wn_p, s_tab_p, pp, win_p, e_p, lv_p);
-                else parse_group<2, WIDE>(wn_p, s_tab_p, pp, win_p, e_p, lv_p);
-                if (s + 3 < kHalf) wn_p = read_window(stage_p, pp);
-                if (s + 3 <= kHalf) parse_group<3, WIDE>(wn_b, s_tab, pb, win_b, e_b, lv_b);
-                else parse_group<2, WIDE>(wn_b, s_tab, pb, win_b, e_b, lv_b);
-                if (s + 3 < kHalf) wn_b = read_window(stage, pb);
-                if (s + 3 <= kHalf) parse_group<3, WIDE>(wn_pb, s_tab_p, ppb, win_pb, e_pb, lv_pb);
-                else parse_group<2, WIDE>(wn_pb, s_tab_p, ppb, win_pb, e_pb, lv_pb);
-                if (s + 3 < kHalf) wn_pb = read_window(stage_p, ppb);
+                if (s + 3 <= kHalf) {
+                    parse_group_early<3, WIDE, false>(wn, s_tab, q, W, e, lv, all_neg);
+                    wn = read_window(stage, q);
+                    parse_group_early<3, WIDE, false>(wn_p, s_tab_p, qp, W_p, e_p, lv_p, all_neg);
+                    wn_p = read_window(stage_p, qp);
+                    parse_group_early<3, WIDE, false>(wn_b, s_tab, qb, W_b, e_b, lv_b, all_neg);
+                    wn_b = read_window(stage, qb);
+                    parse_group_early<3, WIDE, false>(wn_pb, s_tab_p, qpb, W_pb, e_pb, lv_pb, all_neg);
+                    wn_pb = read_window(stage_p, qpb);
+                } else {
+                    parse_group_early<2, WIDE, true>(wn, s_tab, q, W, e, lv, all_neg);
+                    parse_group_early<2, WIDE, true>(wn_p, s_tab_p, qp, W_p, e_p, lv_p, all_neg);
+                    parse_group_early<2, WIDE, true>(wn_b, s_tab, qb, W_b, e_b, lv_b, all_neg);
+                    parse_group_early<2, WIDE, true>(wn_pb, s_tab_p, qpb, W_pb, e_pb, lv_pb, all_neg);
+                }
+                const int cnt = s + 3 <= kHalf ? 3 : 2;
+                if constexpr (!WIDE) {
 #pragma unroll
-                for (int i = 0; i < 3; ++i) {
-                    if (s + i < kHalf) {
-                        if constexpr (!WIDE) {
+                    for (int i = 0; i < 3; ++i) {
+                        if (i < cnt) {
                             lv[i] = level_of(s_tab, e[i]);
                             lv_p[i] = level_of(s_tab_p, e_p[i]);
                             lv_b[i] = level_of(s_tab, e_b[i]);
                             lv_pb[i] = level_of(s_tab_p, e_pb[i]);
                         }
-                        flags |= e[i] | e_p[i] | e_b[i] | e_pb[i];
                     }
+                }
+                if (s > 0) {
+                    emit2(s - 1, W[0], lv_held, W_p[0], lv_held_p);
+                    emit2(kHalf + s - 1, W_b[0], lv_held_b, W_pb[0], lv_held_pb);
                 }
 #pragma unroll
-                for (int i = 0; i < 3; ++i) {
-                    if (s + i < kHalf) {
-                        const float val = symbol_value<false>(lv[i], win[i], e[i], n);
-                        const float val_b = symbol_value<false>(lv_b[i], win_b[i], e_b[i], n);
-                        acc[s + i] += val;
-                        acc[kHalf + s + i] += val_b;
-                        const float df = (symbol_value<false>(lv_p[i], win_p[i], e_p[i], np) - val) * down;   // (a stray sign on a zero does not show in a difference)
-                        sd32 = fmaf(df, df, sd32);
-                        const float df_b = (symbol_value<false>(lv_pb[i], win_pb[i], e_pb[i], np) - val_b) * down;
-                        sd32 = fmaf(df_b, df_b, sd32);
+                for (int i = 0; i < 2; ++i) {
+                    if (i + 1 < cnt || cnt == 2) {
+                        emit2(s + i, W[i + 1], lv[i], W_p[i + 1], lv_p[i]);
+                        emit2(kHalf + s + i, W_b[i + 1], lv_b[i], W_pb[i + 1], lv_pb[i]);
                     }
                 }
+                if (cnt == 3) { lv_held = lv[2]; lv_held_b = lv_b[2]; lv_held_p = lv_p[2]; lv_held_pb = lv_pb[2]; }
                 sw += (double)sd32;
                 sd32 = 0.0f;
             }
             sdiff = fma(sw, up2, sdiff);
-            if (p != cur.p_mid || pp != prv.p_mid) malformed = true;
-            p = pb;
-            pp = ppb;
+            if (q - kEarly != cur.p_mid || qp - kEarly != prv.p_mid) malformed = true;
+            p = qb - kEarly;
+            pp = qpb - kEarly;
         }
         if (p != cur.p_end) malformed = true;
         if constexpr (PREV) {
             if (pp != prv.p_end) malformed = true;
         }
     }
-    malformed = malformed || (flags & 0x8000u) != 0u;
+    // a reject entry (bit 15 set) leaves a zero among bits 15..31 of its group's negative bit count
+    malformed = malformed || (all_neg >> 15) != 0x1FFFFu;
     if (__any(malformed) && lane == 0) raise_error(sc, QGX_EBIT_STREAM);
     if (MODE == DecMode::Decode) return;
 
