@@ -59,6 +59,8 @@ def parse_args():
     ap.add_argument("--graph", action="store_true",
                     help="with --full-iteration: also capture the iteration as one HIP graph and time its replays "
                          "(reported as an extra object; matters for small vectors, where launches dominate)")
+    ap.add_argument("--no-huffman", action="store_true",
+                    help="skip the second leg of the default run (the same step with Psi fitted to the symbol probabilities)")
     ap.add_argument("--placement", choices=["slotted", "compact"], default="slotted",
                     help="chunk placement of the coded streams handed from the encoder to the update kernel")
     return ap.parse_args()
@@ -117,6 +119,49 @@ def cpu_baseline(args, levels, seed, V, code=(None, None)):
     except OSError:
         pass
     return out
+
+
+def fitted_code_leg(args, V, seed, Xh):
+    """The default step once more with the paper's other choice of Psi (Appendix J: Huffman coding once the
+    symbol probabilities can be estimated, which a fitted level table implies): the optimal prefix code on the
+    p_j of Proposition 1.  Fewer bytes move (about 4.5 instead of 11.9 bits per coordinate) in nearly the same
+    time, so the fraction of the HBM peak is lower: it is on record beside the headline."""
+    import numpy as np
+    import torch
+
+    from paper_2308_09187_amd import qgx, synth
+    K, d = V.shape
+    ctx = qgx.Context(d, K, args.bucket, norm=qgx.NORM_L2, seed=seed, code=qgx.CODE_TABLE)
+    ctx.set_levels(synth.levels_exponential(args.n_sym - 1))
+    ctx.fit_levels(V, args.n_sym, 4096, sweeps=10)
+    ctx.fit_code()
+    ctx.state_init(None)
+    a = ctx.new_stream(slotted=True)
+    for i in range(args.warmup):
+        ctx.quantize_encode(V, 2 * i, a); ctx.eg_step(0, a, None, Xh)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        ev[i][0].record(); ctx.quantize_encode(V, 2 * i, a)
+        ev[i][1].record(); ctx.eg_step(0, a, None, Xh)
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    assert ctx.poll_error() == 0
+    enc_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    upd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+    h_bits = a.sub_end.cpu().numpy().view(np.uint16)[:, :, -1].astype(np.int64)
+    words = int((((h_bits + 31) // 32 + 3) // 4 * 4).sum())
+    stream_bytes = words * 4 + K * ((ctx.NC + 1) * 4 + ctx.NC * qgx.SUBS * 2 + ctx.NB * 4)
+    enc_bytes, upd_bytes = 4 * K * d + stream_bytes, stream_bytes + 8 * d
+    bits = ctx.stream_bits(a)
+    ctx.close()
+    return {"config": {"workload": "the same batch and level table, Psi = optimal prefix code fitted to the symbol probabilities",
+                       "bits_per_coordinate": bits / float(K * d), "stream_bytes": stream_bytes},
+            "value": 4.0 * K * d / ((enc_ms + upd_ms) * 1e-3) / 1e9, "unit": "GB/s",
+            "kernels_ms": {"encode": enc_ms, "decode_avg_half0": upd_ms},
+            "hbm_frac_step": (enc_bytes + upd_bytes) / ((enc_ms + upd_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "roofline": {"kernel": "k_encode<Fused, false, 4>", "bound": "hbm", "achieved": enc_bytes / (enc_ms * 1e-3) / 1e9,
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": enc_bytes / (enc_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "traffic": None, "algorithmic_bytes": enc_bytes}}
 
 
 def main():
@@ -239,6 +284,28 @@ def main():
     wall = time.perf_counter() - t0
     assert ctx.poll_error() == 0
 
+    # The same two kernels with the half-step reading a stream that is NOT fresh in the 256 MB infinity cache:
+    # the encoder fills one of two stream buffers while the half-step decodes the other, coded one step (and
+    # about 1 GB of traffic) earlier.  On one GPU the default loop's flow (decode what was just coded) is the
+    # method's own; over a network the streams arrive from elsewhere, which is what this loop stands for.
+    cold = None
+    if not args.full_iteration and not args.rotate:
+        b_cold = ctx.new_stream(slotted=slotted)
+        ctx.quantize_encode(V, 1, b_cold)
+        bufs = (a, b_cold)
+        ev_c = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+        for i in range(args.warmup + args.steps):
+            e = ev_c[i - args.warmup] if i >= args.warmup else None
+            if e: e[0].record()
+            ctx.quantize_encode(V, 2 * i, bufs[i & 1])
+            if e: e[1].record()
+            ctx.eg_step(0, bufs[(i + 1) & 1], None, Xh)
+            if e: e[2].record()
+        torch.cuda.synchronize()
+        assert ctx.poll_error() == 0
+        cold = (float(np.mean([e[0].elapsed_time(e[1]) for e in ev_c])), float(np.mean([e[1].elapsed_time(e[2]) for e in ev_c])))
+        del b_cold
+
     graph_ms = None
     if args.graph and args.full_iteration:
         # every kernel of the iteration takes what changes from device memory, the call numbers included
@@ -291,15 +358,22 @@ def main():
                                                             4 if args.n_sym <= 33 else 5 if args.n_sym <= 65 else 6),
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     # the committed counter run covers the default workload only
+                     # HBM bytes per launch from the committed rocprofv3 counter run of this command (FETCH_SIZE and
+                     # WRITE_SIZE, calibrated on a plain copy), not measured in this run; default workload only
                      "traffic": measured_traffic() if default_workload else None,
+                     "traffic_source": "profiles/encode_t3_K8_d2p24_pmc.txt" if default_workload else None,
                      "algorithmic_bytes": enc_bytes,
                      # a plain copy of the same input on this machine, and the encoder's rate relative to it
                      "copy_gbs": copy_gbs, "frac_of_copy": achieved / copy_gbs,
                      # upper bound on the vector-ALU time of a launch from the counter run: instructions issued
                      # per SIMD x 4 clocks (simple instructions take fewer: the ALUs are the second ceiling)
+                     # (from the same committed counter run)
                      "valu_busy_us": _profile_number("valu_busy_us") if default_workload else None},
     }
+    if cold is not None:
+        out["kernels_ms_cold_stream"] = {"encode": cold[0], "decode_avg_half0": cold[1],
+                                         "what": "the half-step decodes a stream coded one step earlier (not fresh in the infinity cache)"}
+        out["hbm_frac_step_cold_stream"] = (enc_bytes + upd_bytes) / ((cold[0] + cold[1]) * 1e-3) / 1e9 / HBM_PEAK_GBS
     if out["roofline"]["valu_busy_us"]:
         # the same bound as a share of this run's launch time: near 1 means the ALUs, not HBM, are the nearer ceiling
         out["roofline"]["valu_busy_frac"] = out["roofline"]["valu_busy_us"] / (enc_ms * 1e3)
@@ -314,6 +388,8 @@ def main():
     out["kernels_ms_median"] = {n: float(np.median(v)) for n, v in per_step.items()}
     out["kernels_ms_min"] = {n: float(v.min()) for n, v in per_step.items()}
     ctx.close()
+    if default_workload and not args.full_iteration and not args.no_huffman:
+        out["fitted_code"] = fitted_code_leg(args, V, seed, Xh)
     if not args.no_cpu_baseline and args.workload == "t3":
         ds = min(d, 1 << args.cpu_sample_logd)
         args.cpu_sample_logd = ds.bit_length() - 1
