@@ -58,6 +58,9 @@ def lib():
         _lib.orc_bin_edge.argtypes = [C.c_uint32, C.c_uint32]
         _lib.orc_qada_objective.restype = C.c_double
         _lib.orc_stationary_point.restype = C.c_double
+        _lib.orc_normal.restype = C.c_double
+        _lib.orc_normal.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64]
+        _lib.orc_norm2.restype = C.c_double
         for f in ("orc_chunk_coords", "orc_sub_coords", "orc_align_words"):
             getattr(_lib, f).restype = C.c_uint32
     return _lib
@@ -332,3 +335,29 @@ def qada_objective(H, levels):
     H = _c(H, np.float64); lv = _c(levels, np.float32)
     return float(lib().orc_qada_objective(_p(H, C.c_double), C.c_uint32(len(H)),
                                           _p(lv, C.c_float), C.c_uint32(len(lv))))
+
+
+def game_operator(z, a, b, mu):
+    """F(z) = M z + b for the block-diagonal M of the large quadratic game, binary64."""
+    z = _c(z, np.float32); a = _c(a, np.float32); b = _c(b, np.float32)
+    F = np.zeros(len(z), np.float64)
+    lib().orc_game_operator(_p(z, C.c_float), _p(a, C.c_float), _p(b, C.c_float), C.c_double(mu), C.c_uint64(len(z)), _p(F, C.c_double))
+    return F
+
+
+def normal(noise_seed, k, call_id, i):
+    return float(lib().orc_normal(noise_seed, k, call_id, i))
+
+
+def game_dual_vectors(z, a, b, mu, sigma, noise_seed, call_id, K):
+    """[K][d] float32: F(z) + sigma N(0, 1), the reproducible draws of the game's stochastic oracle."""
+    z = _c(z, np.float32); a = _c(a, np.float32); b = _c(b, np.float32)
+    V = np.zeros((K, len(z)), np.float32)
+    lib().orc_game_dual_vectors(_p(z, C.c_float), _p(a, C.c_float), _p(b, C.c_float), C.c_double(mu), C.c_double(sigma),
+                                C.c_uint64(noise_seed), C.c_uint32(call_id), C.c_uint32(K), C.c_uint64(len(z)), _p(V, C.c_float))
+    return V
+
+
+def norm2(x):
+    x = _c(x, np.float32)
+    return float(lib().orc_norm2(_p(x, C.c_float), C.c_uint64(x.size)))

@@ -831,6 +831,68 @@ int orc_canonical_code(const uint8_t* len, uint32_t n, uint32_t* bits)
     return 0;
 }
 
+/* ------------------------------------------------------------------------ */
+/* The synthetic stochastic oracle of the large quadratic game (Section 2:    */
+/* a dual vector is g(z; omega) = A(z) + U(z; omega) with E U = 0 and bounded */
+/* variance, the absolute-noise model).  The operator is strongly monotone:   */
+/* F(z) = M z + b with M block diagonal, 2x2 blocks [[mu, a_j], [-a_j, mu]]   */
+/* acting on the coordinate pairs (2j, 2j+1).  Worker k's dual vector in      */
+/* quantisation call `call_id` is F(z) + sigma * N, N standard normal and     */
+/* independent over workers, calls and coordinates.  The draws are this       */
+/* project's own choice, made reproducible like the rounding draws: the four  */
+/* coordinates 4g..4g+3 take the Philox4x32-10 block with key noise_seed and  */
+/* counter (g, 1, k, call_id) (the rounding draws have 0 in the second word), */
+/* words (w0, w1) give coordinates 4g, 4g+1 and (w2, w3) give 4g+2, 4g+3 by   */
+/* the Box-Muller transform: u1 = (2 (w >> 9) + 1) 2^-24 in (0, 1),           */
+/* u2 = (w' >> 8) 2^-24 in [0, 1), r = sqrt(-2 ln u1),                        */
+/* n = r cos(2 pi u2), n' = r sin(2 pi u2).  Binary64 throughout; the dual    */
+/* vector is rounded to binary32 once.                                       */
+/* ------------------------------------------------------------------------ */
+void orc_game_operator(const float* z, const float* a, const float* b, double mu, uint64_t d, double* F)
+{
+    for (uint64_t j = 0; j + 1 < d; j += 2) {
+        const double z0 = z[j], z1 = z[j + 1], aj = a[j / 2];
+        F[j] = mu * z0 + aj * z1 + (double)b[j];
+        F[j + 1] = -aj * z0 + mu * z1 + (double)b[j + 1];
+    }
+}
+
+double orc_normal(uint64_t noise_seed, uint32_t k, uint32_t call_id, uint64_t i)
+{
+    const double two_pi = 6.283185307179586476925286766559;
+    uint32_t ctr[4], key[2], out[4];
+    const uint64_t g = i >> 2;
+    ctr[0] = (uint32_t)g; ctr[1] = 1u; ctr[2] = k; ctr[3] = call_id;
+    key[0] = (uint32_t)noise_seed; key[1] = (uint32_t)(noise_seed >> 32);
+    orc_philox4x32_10(ctr, key, out);
+    const uint32_t wr = out[(i & 2)], wt = out[(i & 2) + 1];       /* the pair this coordinate belongs to */
+    const double u1 = (2.0 * (double)(wr >> 9) + 1.0) * 0x1p-24;
+    const double u2 = (double)(wt >> 8) * 0x1p-24;
+    const double r = sqrt(-2.0 * log(u1));
+    return (i & 1) ? r * sin(two_pi * u2) : r * cos(two_pi * u2);
+}
+
+/* V [K][d]: worker k's dual vector F(z) + sigma N_k, rounded to binary32. */
+void orc_game_dual_vectors(const float* z, const float* a, const float* b, double mu, double sigma,
+                           uint64_t noise_seed, uint32_t call_id, uint32_t K, uint64_t d, float* V)
+{
+    double* F = (double*)malloc(sizeof(double) * d);
+    orc_game_operator(z, a, b, mu, d, F);
+#pragma omp parallel for schedule(static)
+    for (uint32_t k = 0; k < K; ++k)
+        for (uint64_t i = 0; i < d; ++i)
+            V[(uint64_t)k * d + i] = (float)(F[i] + sigma * orc_normal(noise_seed, k, call_id, i));
+    free(F);
+}
+
+/* ||x||_2 in binary64 (the residual ||F(x)|| of Section 2 once x = F(.) has been formed). */
+double orc_norm2(const float* x, uint64_t n)
+{
+    double acc = 0.0;
+    for (uint64_t i = 0; i < n; ++i) acc += (double)x[i] * (double)x[i];
+    return sqrt(acc);
+}
+
 uint32_t orc_chunk_coords(void) { return ORC_CH; }
 uint32_t orc_sub_coords(void) { return ORC_SUB; }
 uint32_t orc_align_words(void) { return ORC_ALIGN_WORDS; }

@@ -13,6 +13,7 @@ SRC = os.path.join(ROOT, "oracle", "qgx_oracle.c")
 
 Q, C, E, F, H, R = ("tests/test_oracle_quantize.py", "tests/test_oracle_codec.py", "tests/test_oracle_eg.py",
                     "tests/test_oracle_fit.py", "tests/test_oracle_huffman.py", "tests/test_oracle_rng.py")
+G = "tests/test_oracle_game.py"
 
 MUTANTS = [
     ("nine Philox rounds", "round < 10; ++round", "round < 9; ++round", [R]),
@@ -66,6 +67,13 @@ MUTANTS = [
      "const double x_t = (anchor ? anchor[i] : 0.0) + Y[i];", [E]),
     ("objective without the cubic term", "const double P_hi = -hi * hi * hi / 3.0 + (a + c) * hi * hi / 2.0 - a * c * hi;",
      "const double P_hi = (a + c) * hi * hi / 2.0 - a * c * hi;", [F]),
+    ("noise radius without the root", "const double r = sqrt(-2.0 * log(u1));", "const double r = -2.0 * log(u1);", [G]),
+    ("both halves of a noise pair from the cosine", "return (i & 1) ? r * sin(two_pi * u2) : r * cos(two_pi * u2);",
+     "return r * cos(two_pi * u2);", [G]),
+    ("noise that ignores the worker", "ctr[0] = (uint32_t)g; ctr[1] = 1u; ctr[2] = k; ctr[3] = call_id;",
+     "ctr[0] = (uint32_t)g; ctr[1] = 1u; ctr[2] = 0; ctr[3] = call_id;", [G]),
+    ("operator with a symmetric coupling", "F[j + 1] = -aj * z0 + mu * z1 + (double)b[j + 1];",
+     "F[j + 1] = aj * z0 + mu * z1 + (double)b[j + 1];", [G]),
     ("cost of a word without its weight", "const uint64_t cost = w[i] * l + BEST(i + 1, k - space);",
      "const uint64_t cost = l + BEST(i + 1, k - space);", [H]),
 ]

@@ -9,7 +9,7 @@ import sys
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-PINS = ["tests/test_oracle_rng.py", "tests/test_oracle_quantize.py", "tests/test_oracle_codec.py",
+PINS = ["tests/test_oracle_rng.py", "tests/test_oracle_quantize.py", "tests/test_oracle_codec.py", "tests/test_oracle_game.py",
         "tests/test_oracle_eg.py", "tests/test_oracle_fit.py", "tests/test_oracle_huffman.py"]
 
 
