@@ -47,10 +47,12 @@ def parse_args():
                     help="alternate between two input batches and two stream buffers from step to step")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of the input (known size) to calibrate rocprofv3 HBM counters")
-    ap.add_argument("--workload", choices=["t3", "gan"], default="t3",
+    ap.add_argument("--workload", choices=["t3", "gan", "game"], default="t3",
                     help="t3: the headline batch of heavy-tailed vectors; gan: K vectors in a GAN-shaped layout of 14 "
                          "tensors with per-tensor scale, buckets of 8192 per tensor, L-infinity norm, 16 exponential "
-                         "levels, full iteration (ignores --logd, --bucket, --n-sym)")
+                         "levels, full iteration (ignores --logd, --bucket, --n-sym); game: the large quadratic game, "
+                         "K = 16 workers, z in R^(2^26), buckets of 65536, 65 levels, whole iterations on the device with "
+                         "the dual vectors formed inside the coding kernel and, for comparison, written out and coded from memory")
     ap.add_argument("--code", choices=["omega", "huffman", "fixed"], default="omega",
                     help="Psi: Elias' recursive code of the level index (default), the optimal prefix code "
                          "fitted to the estimated symbol probabilities, or words of one width (with uniform levels: "
@@ -164,8 +166,105 @@ def fitted_code_leg(args, V, seed, Xh):
                          "traffic": None, "algorithmic_bytes": enc_bytes}}
 
 
+def game_bench(args):
+    """Whole iterations of eq. (Q-GenX) on the large strongly monotone quadratic game with nothing but scalars
+    leaving the device: per iteration two rounds of (K dual vectors at the current point -> CODE o Q -> fused
+    half-step).  Timed twice: with the dual vectors formed inside the coding kernel (qgx_quantize_encode_game),
+    and with them written to memory by qgx_game_dual_vectors and coded from there (generator included)."""
+    import numpy as np
+    import torch
+
+    from paper_2308_09187_amd import qgx, synth
+    qgx.load()
+    torch.cuda.set_device(0)
+    K = 16 if args.K == 8 else args.K
+    logd = 26 if args.logd == 24 else args.logd
+    bucket = 65536 if args.bucket == 16384 else args.bucket
+    n_sym = 65 if args.n_sym == 33 else args.n_sym
+    d, seed = 1 << logd, 2308
+    game = synth.QuadraticGame(d, K)
+    a_d, b_d = torch.from_numpy(game.a).cuda(), torch.from_numpy(game.b).cuda()
+    ctx = qgx.Context(d, K, bucket, norm=qgx.NORM_L2, seed=seed)
+    ctx.set_levels(synth.levels_exponential(n_sym - 1))
+    X = torch.zeros(d, device="cuda")
+    Xh, Xn = torch.empty(d, device="cuda"), torch.empty(d, device="cuda")
+    V = torch.empty((K, d), device="cuda")
+    ctx.game_dual_vectors(X, a_d, b_d, game.mu, game.noise, 42, 0, out=V)
+    ctx.fit_levels(V, n_sym, 4096, sweeps=8)
+    sa, sb = ctx.new_stream(slotted=True), ctx.new_stream(slotted=True)
+    names = ["generate", "encode", "decode_avg_half0", "generate_2", "encode_2", "decode_avg_half1"]
+
+    def iteration(fused, ev=None):
+        nonlocal X, Xn
+        def mark(j):
+            if ev: ev[j].record()
+        mark(0)
+        if not fused: ctx.game_dual_vectors(X, a_d, b_d, game.mu, game.noise, 42, qgx.CALL_FIRST_HALF, out=V)
+        mark(1)
+        if fused: ctx.quantize_encode_game(X, a_d, b_d, game.mu, game.noise, 42, qgx.CALL_FIRST_HALF, sa)
+        else: ctx.quantize_encode(V, qgx.CALL_FIRST_HALF, sa)
+        mark(2)
+        ctx.eg_step(0, sa, None, Xh)
+        mark(3)
+        if not fused: ctx.game_dual_vectors(Xh, a_d, b_d, game.mu, game.noise, 42, qgx.CALL_SECOND_HALF, out=V)
+        mark(4)
+        if fused: ctx.quantize_encode_game(Xh, a_d, b_d, game.mu, game.noise, 42, qgx.CALL_SECOND_HALF, sb)
+        else: ctx.quantize_encode(V, qgx.CALL_SECOND_HALF, sb)
+        mark(5)
+        ctx.eg_step(1, sb, sa, Xn)
+        mark(6)
+        X, Xn = Xn, X
+
+    def timed(fused):
+        nonlocal X
+        X.zero_()
+        ctx.state_init(None)
+        for _ in range(args.warmup):
+            iteration(fused)
+        torch.cuda.synchronize()
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            iteration(fused, events[i])
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) / args.steps
+        assert ctx.poll_error() == 0
+        per = {n: float(np.mean([e[j].elapsed_time(e[j + 1]) for e in events])) for j, n in enumerate(names)}
+        return wall, per
+
+    wall_f, per_f = timed(True)
+    wall_m, per_m = timed(False)
+    res = ctx.norm2(ctx.game_operator(X, a_d, b_d, game.mu))
+    bits = ctx.stream_bits(sa)
+    h_bits = sa.sub_end.cpu().numpy().view(np.uint16)[:, :, -1].astype(np.int64)
+    stream_bytes = int((((h_bits + 31) // 32 + 3) // 4 * 4).sum()) * 4 + K * ((ctx.NC + 1) * 4 + ctx.NC * qgx.SUBS * 2 + ctx.NB * 4)
+    # algorithmic bytes of the fused coding kernel: z, a and b once (10 bytes per coordinate; the K workers' reads of
+    # one piece meet in the cache) and the streams out.  The kernel is bound by instruction issue, not by these.
+    enc_bytes_f = d * 10 + stream_bytes
+    out = {
+        "metric": "GB/s of fp32 dual vectors through quantize->encode->decode->avg->EG step; % HBM peak",
+        "value": 2 * 4.0 * K * d / wall_f / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall_f * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "large quadratic game, K=%d x d=2^%d, F(z) = Mz + b with 2x2 blocks, N(0, %.2f^2) noise, bucket %d, L2, "
+                               "%d-symbol fitted table, Elias-omega, slotted; step = one whole iteration on the device, dual vectors "
+                               "formed inside the coding kernel" % (K, logd, game.noise, bucket, n_sym),
+                   "K": K, "d": d, "bucket": bucket, "n_sym": n_sym, "bits_per_coordinate": bits / float(K * d), "stream_bytes": stream_bytes},
+        "kernels_ms": per_f,
+        "materialised": {"what": "the same iterations with the dual vectors written to memory by qgx_game_dual_vectors and coded from there",
+                         "ms_per_step": wall_m * 1e3, "value": 2 * 4.0 * K * d / wall_m / 1e9, "unit": "GB/s", "kernels_ms": per_m},
+        "roofline": {"kernel": "k_encode<Generate, false, %d>" % (4 if n_sym <= 33 else 5 if n_sym <= 65 else 6), "bound": "hbm",
+                     "achieved": enc_bytes_f / (per_f["encode"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": enc_bytes_f / (per_f["encode"] * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes": enc_bytes_f},
+        "residual_norm_at_the_last_iterate": res,
+    }
+    ctx.close()
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
+    if args.gpus == 1 and args.workload == "game":
+        return game_bench(args)
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the K workers are a batch on it); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)

@@ -228,6 +228,40 @@ qgx_status qgx_fit_levels(qgx_ctx* ctx, const float* V, uint32_t n_sym, uint32_t
  * QGX_ERR_STATE without a histogram, a level table, or QGX_CODE_TABLE. */
 qgx_status qgx_fit_code(qgx_ctx* ctx, double* p_host, uint8_t* code_len_host, uint32_t* code_bits_host, void* stream);
 
+/* The caller's side of an iteration for the large quadratic game, as calls of the library, so that a whole
+ * iteration can stay on the device (Section 2: the stochastic oracle g(z; omega) = A(z) + U(z; omega) with
+ * E U = 0 and bounded variance; the residual ||A(x)|| the convergence theorems are read against).
+ * The operator is F(z) = M z + b, M block diagonal with 2x2 blocks [[mu, a_j], [-a_j, mu]] on the coordinate
+ * pairs (2j, 2j+1): strongly monotone with modulus mu.  Worker k's dual vector in call `call_id` is
+ * F(z) + sigma N with N standard normal, independent over workers, calls and coordinates: coordinates
+ * 4g..4g+3 take Philox4x32-10(key = noise_seed, counter = (g, 1, k, call_id)), words (w0, w1) and (w2, w3)
+ * each give two draws by Box-Muller with u1 = (2 (w >> 9) + 1) 2^-24, u2 = (w' >> 8) 2^-24.  All pointers
+ * DEVICE; z and b 16-byte aligned, a 8-byte aligned; d a multiple of 4. */
+typedef struct {
+    const float* z;       /* [d] the point */
+    const float* a;       /* [d / 2] couplings of the 2x2 blocks */
+    const float* b;       /* [d] */
+    float mu;             /* modulus of strong monotonicity (diagonal of every block) */
+    float sigma;          /* standard deviation of the noise, >= 0 */
+    uint64_t noise_seed;  /* key of the noise draws */
+} qgx_game;
+
+/* F_out DEVICE [d] = F(z). */
+qgx_status qgx_game_operator(qgx_ctx* ctx, const qgx_game* game, float* F_out, void* stream);
+/* V_out DEVICE [K][d]: the K workers' dual vectors.  call_id as in qgx_quantize (the two special values too). */
+qgx_status qgx_game_dual_vectors(qgx_ctx* ctx, const qgx_game* game, uint32_t call_id, float* V_out, void* stream);
+/* CODE o Q of those same dual vectors without writing them to memory and reading them back: the coding
+ * kernel forms each coordinate where qgx_quantize_encode would load it (the rounding draws use the context's
+ * seed and the same call_id; the noise draws differ from them in key and counter).  The stream equals, bit
+ * for bit, that of qgx_quantize_encode on the output of qgx_game_dual_vectors.  V_out DEVICE [K][d] or NULL:
+ * the dual vectors as formed, for checking.  One segment, buckets that do not share chunks, L2 or
+ * L-infinity norm (QGX_ERR_ARG otherwise). */
+qgx_status qgx_quantize_encode_game(qgx_ctx* ctx, const qgx_game* game, uint32_t call_id, qgx_stream* out,
+                                    float* V_out, void* stream);
+/* result_host HOST <- ||x||_2 of x DEVICE [n], squares summed in binary64 in a fixed order (the residual
+ * ||F(x)|| once F(x) has been formed with qgx_game_operator, say at the ergodic average).  Synchronises. */
+qgx_status qgx_norm2(qgx_ctx* ctx, const float* x, uint64_t n, double* result_host, void* stream);
+
 /* State of eq. (Q-GenX): Y_1 = 0, S = 0, t = 1, gamma_1 = K, anchor = X1 (DEVICE [d] or NULL = 0).
  * The paper's X_{t+1} = gamma_{t+1} Y_{t+1} is the X1 = 0 case of X_{t+1} = X1 + gamma_{t+1} Y_{t+1}. */
 qgx_status qgx_state_init(qgx_ctx* ctx, const float* X1, void* stream);

@@ -31,6 +31,47 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
+// Two standard normal draws from two words of a Philox block (Box-Muller): u1 = (2 (w >> 9) + 1) 2^-24 in
+// (0, 1), u2 = (w' >> 8) 2^-24 in [0, 1), r = sqrt(-2 ln u1), (r cos 2 pi u2, r sin 2 pi u2).  Both
+// uniforms are exact in binary32; logarithm, root, sine and cosine are the hardware's (v_log_f32 in base
+// 2, v_sin_f32 and v_cos_f32 take their argument in turns), good to about 1e-6, which is ample for noise.
+__device__ __forceinline__ float2 box_muller(uint32_t w_radius, uint32_t w_angle)
+{
+    const float u1 = (float)(2u * (w_radius >> 9) + 1u) * 0x1p-24f;
+    const float u2 = (float)(w_angle >> 8) * 0x1p-24f;
+    const float r = __builtin_amdgcn_sqrtf(-1.3862943611198906f * __builtin_amdgcn_logf(u1));   // -2 ln 2 * log2 u1
+    return make_float2(r * __builtin_amdgcn_cosf(u2), r * __builtin_amdgcn_sinf(u2));
+}
+
+// Coordinates i0 .. i0 + 3 (i0 a multiple of 4) of F(z) = M z + b.
+__device__ __forceinline__ float4 game_operator_row(const GameArgs& G, uint32_t i0)
+{
+    const float4 z = *reinterpret_cast<const float4*>(G.z + i0);
+    const float4 b = *reinterpret_cast<const float4*>(G.b + i0);
+    const float2 a = *reinterpret_cast<const float2*>(G.a + (i0 >> 1));
+    float4 f;
+    f.x = (G.mu * z.x + a.x * z.y) + b.x;
+    f.y = (G.mu * z.y - a.x * z.x) + b.y;
+    f.z = (G.mu * z.z + a.y * z.w) + b.z;
+    f.w = (G.mu * z.w - a.y * z.z) + b.w;
+    return f;
+}
+
+// The same four coordinates of worker k's dual vector in call `call_id`: F(z) + sigma N, the noise from the
+// Philox block with key (seed_lo, seed_hi) and counter (i0 / 4, 1, k, call_id).
+__device__ __forceinline__ float4 game_dual_row(const GameArgs& G, uint32_t i0, uint32_t k, uint32_t call_id)
+{
+    uint32_t w[4];
+    philox4x32_10(i0 >> 2, 1u, k, call_id, G.seed_lo, G.seed_hi, w);
+    const float2 n01 = box_muller(w[0], w[1]), n23 = box_muller(w[2], w[3]);
+    float4 v = game_operator_row(G, i0);
+    v.x += G.sigma * n01.x;
+    v.y += G.sigma * n01.y;
+    v.z += G.sigma * n23.x;
+    v.w += G.sigma * n23.y;
+    return v;
+}
+
 // Inclusive prefix sum over the 64 lanes of a wave with DPP row shifts and row broadcasts: four
 // shifted adds inside each row of 16 lanes, then lane 15 of a row into the next row, then lane 31
 // into the upper half.

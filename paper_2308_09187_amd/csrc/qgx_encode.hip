@@ -428,10 +428,20 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
     __syncthreads();
 
     const size_t kbase = (size_t)k * lay.d;
-    const bool vec_ok = (kbase & 3u) == 0;             // 16-byte aligned rows for this worker
+    const bool vec_ok = MODE == EncMode::Generate || (kbase & 3u) == 0;    // 16-byte aligned rows for this worker
     // the number of this quantisation call: given, or taken from the iteration counter (replayed graphs)
     const uint32_t call_id = a.call_mode ? 2u * (uint32_t)(sc->t - 1ull) + (a.call_mode - 1u) : a.call_id;
-    const float* __restrict__ Vk = (MODE != EncMode::EncodeOnly) ? a.V + kbase : nullptr;
+    const float* __restrict__ Vk = (MODE == EncMode::Fused || MODE == EncMode::QuantOnly) ? a.V + kbase : nullptr;
+    // one coordinate of the worker's vector again, for the rolled paths: from memory, or (Generate) formed again
+    auto value_at = [&](uint32_t i) -> float {
+        if constexpr (MODE == EncMode::Generate) {
+            const float4 row = game_dual_row(a.game, i & ~3u, k, call_id);
+            const uint32_t q = i & 3u;
+            return q == 0u ? row.x : q == 1u ? row.y : q == 2u ? row.z : row.w;
+        } else {
+            return Vk[i];
+        }
+    };
     const uint32_t unit = ticketed ? s_misc[2] : (uint32_t)blockIdx.x / lay.K;
     const uint32_t epoch = ticketed ? s_misc[3] : 0u;
     uint32_t b = a.parts > 1u ? unit / a.parts : unit;  // the bucket; with shared chunks the first of the wave's chunk
@@ -469,7 +479,22 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
     uint16_t* __restrict__ sub_mine = sub_g + (lane >> 3);
     const bool ends_run = (lane & 7) == 7;
     float4 v[kRows];
-    if (MODE != EncMode::EncodeOnly) load_chunk(v, Vk, g, vec_ok, lane);
+    if constexpr (MODE == EncMode::Generate) {
+        // the dual vector is formed here instead of read: operator and noise for four coordinates per lane and row
+        // (every bucket and vector length is a multiple of four in this mode)
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) {
+            const uint32_t i0 = g.clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i0 < g.cend) {
+                x = game_dual_row(a.game, i0, k, call_id);
+                if (a.game.V_out) *reinterpret_cast<float4*>(a.game.V_out + kbase + i0) = x;
+            }
+            v[r] = x;
+        }
+    } else if (MODE != EncMode::EncodeOnly) {
+        load_chunk(v, Vk, g, vec_ok, lane);
+    }
     {
 
         // ---- norm of the bucket from the rows in registers ---------------------------------------
@@ -529,7 +554,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                 // again in binary64, from memory (the rolled loop keeps the register copy intact)
                 double acc = 0.0;
 #pragma unroll 1
-                for (uint32_t i = g.clo + (uint32_t)lane; i < g.cend; i += kWave) acc = fma((double)Vk[i], (double)Vk[i], acc);
+                for (uint32_t i = g.clo + (uint32_t)lane; i < g.cend; i += kWave) { const double x = (double)value_at(i); acc = fma(x, x, acc); }
                 acc = wave_sum(acc);
                 if (lane == 0) s_red[nwaves + w] = acc;
                 __syncthreads();
@@ -555,7 +580,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                 // push it out of registers for the common norms as well)
 #pragma unroll 1
                 for (uint32_t i = g.clo + (uint32_t)lane; i < g.cend; i += kWave)
-                    acc += pow_int(fabs((double)Vk[i]) * inv_m, q);
+                    acc += pow_int(fabs((double)value_at(i)) * inv_m, q);
                 acc = wave_sum(acc);
                 if (lane == 0) s_red[nwaves + w] = acc;
                 __syncthreads();
@@ -632,10 +657,14 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                     philox4x32_10(i0 >> 2, 0u, k, call_id, a.seed_lo, a.seed_hi, rnd);
                     // the register copy is indexed by compile-time row numbers only: this path reads the row again
                     float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (i0 < g.cend) x.x = Vk[i0];
-                    if (i0 + 1 < g.cend) x.y = Vk[i0 + 1];
-                    if (i0 + 2 < g.cend) x.z = Vk[i0 + 2];
-                    if (i0 + 3 < g.cend) x.w = Vk[i0 + 3];
+                    if constexpr (MODE == EncMode::Generate) {
+                        if (i0 < g.cend) x = game_dual_row(a.game, i0, k, call_id);
+                    } else {
+                        if (i0 < g.cend) x.x = Vk[i0];
+                        if (i0 + 1 < g.cend) x.y = Vk[i0 + 1];
+                        if (i0 + 2 < g.cend) x.z = Vk[i0 + 2];
+                        if (i0 + 3 < g.cend) x.w = Vk[i0 + 3];
+                    }
                     const float xs[4] = {x.x, x.y, x.z, x.w};
                     const float rinv_r = GROUPED ? s_rinv[w * 16 + (int)((uint32_t)r >> rshift)] : rinv;
                     const bool live_r = GROUPED ? rinv_r != 0.0f : live;
@@ -749,6 +778,13 @@ hipError_t launch_encode(EncMode mode, const Layout& lay, const Tables* tab, Sca
 {
     switch (mode) {
         case EncMode::Fused: return launch_kind<EncMode::Fused>(lay, tab, sc, a, st);
+        case EncMode::Generate:
+            if (lay.shared_chunks) return hipErrorInvalidValue;          // (the host side has refused this layout)
+            switch (a.cell_mant) {
+                case 4: return launch_mode<EncMode::Generate, false, 4>(lay, tab, sc, a, st);
+                case 5: return launch_mode<EncMode::Generate, false, 5>(lay, tab, sc, a, st);
+                default: return launch_mode<EncMode::Generate, false, 6>(lay, tab, sc, a, st);
+            }
         case EncMode::QuantOnly: return launch_kind<EncMode::QuantOnly>(lay, tab, sc, a, st);
         default: return launch_kind<EncMode::EncodeOnly>(lay, tab, sc, a, st);
     }

@@ -111,8 +111,21 @@ struct Layout {                 // device pointers into one allocation
 
 inline bool shares_chunks(uint32_t bucket) { return bucket == 256u || bucket == 512u || bucket == 1024u || bucket == 2048u; }
 
-enum class EncMode { Fused, QuantOnly, EncodeOnly };
+// Fused: V from memory; Generate: V formed on the fly from the game's operator and noise (GameArgs)
+enum class EncMode { Fused, QuantOnly, EncodeOnly, Generate };
 enum class DecMode { Decode, Average, Half0, Half1 };
+
+// The synthetic stochastic oracle of the large quadratic game (Section 2: g(z; omega) = A(z) + U(z; omega)):
+// F(z) = M z + b, M block diagonal with 2x2 blocks [[mu, a_j], [-a_j, mu]] on the pairs (2j, 2j+1), plus
+// sigma times standard normal noise drawn per (worker, call, coordinate).
+struct GameArgs {
+    const float* z;             // [d]
+    const float* a;             // [d / 2]
+    const float* b;             // [d]
+    float mu, sigma;
+    uint32_t seed_lo, seed_hi;  // key of the noise draws
+    float* V_out;               // [K][d] or null: the dual vectors as the fused coding kernel formed them (for tests)
+};
 
 struct EncodeArgs {
     const float* V;             // [K][d]           (Fused, QuantOnly)
@@ -138,6 +151,7 @@ struct EncodeArgs {
     uint32_t sign_shift;        // (bits of v) >> sign_shift puts the sign bit on lev_stride
     uint32_t stage_bytes;       // per wave, multiple of 16, covers 4096 symbols of the longest code + sign
     uint32_t slot_words;        // 0: compact placement (ordered scan); else chunk c goes to c * slot_words
+    GameArgs game;              // EncMode::Generate
 };
 
 struct DecodeArgs {
@@ -214,5 +228,10 @@ hipError_t launch_fit(Tables* tab, const double* hist, uint32_t n_bins, uint32_t
 hipError_t launch_fit_code(Tables* tab, const double* hist, uint32_t n_bins, uint32_t max_len, double* p_out,
                            hipStream_t st);
 uint32_t histogram_groups(const Layout& lay);
+hipError_t launch_game_operator(const GameArgs& g, uint32_t d, float* F_out, hipStream_t st);
+hipError_t launch_game_dual_vectors(const GameArgs& g, uint32_t d, uint32_t K, uint32_t call_id, uint32_t call_mode,
+                                    const Scalars* sc, float* V_out, hipStream_t st);
+constexpr uint32_t kNormBlocks = 1024;     // partial sums of qgx_norm2
+hipError_t launch_norm2(const float* x, uint64_t n, double* partial /*[kNormBlocks + 1]*/, hipStream_t st);
 
 }  // namespace qgx

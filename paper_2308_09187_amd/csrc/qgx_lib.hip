@@ -73,6 +73,7 @@ struct qgx_ctx {
     double* d_hpartial = nullptr;
     double* d_hist = nullptr;
     double* d_prob = nullptr;       // [kSymMax] symbol probabilities of the last qgx_fit_code
+    double* d_norm = nullptr;       // [kNormBlocks + 1] partial sums and result of qgx_norm2
     SideQueue side{};               // for the ragged chunk positions of the decoding kernels
     bool side_ok = false;
     double* d_xsum = nullptr;       // [d] sum of the X_{t+1/2} since qgx_average_reset (allocated there)
@@ -186,7 +187,7 @@ qgx_status need_levels(qgx_ctx* ctx) { return need_levels(ctx, ctx->sel); }
 
 void free_all(qgx_ctx* c)
 {
-    void* all[] = {c->d_layout, c->d_tabs, c->d_sc, c->d_Y, c->d_anchor, c->d_scan, c->d_xch, c->d_tickets, c->d_spartial, c->d_hpartial, c->d_hist, c->d_prob, c->d_xsum};
+    void* all[] = {c->d_layout, c->d_tabs, c->d_sc, c->d_Y, c->d_anchor, c->d_scan, c->d_xch, c->d_tickets, c->d_spartial, c->d_hpartial, c->d_hist, c->d_prob, c->d_norm, c->d_xsum};
     for (void* p : all) (void)hipFree(p);
     if (c->side_ok) {
         (void)hipEventDestroy(c->side.fork);
@@ -318,6 +319,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     ok = ok && hipMalloc(&c->d_hpartial, (size_t)c->h_groups * QGX_MAX_BINS * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_hist, QGX_MAX_BINS * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_prob, kSymMax * sizeof(double)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_norm, (kNormBlocks + 1) * sizeof(double)) == hipSuccess;
     ok = ok && hipMemcpy(c->d_layout, flat.data(), n_lay * sizeof(uint32_t), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemset(c->d_tabs, 0, QGX_TABLES * sizeof(Tables)) == hipSuccess;
     ok = ok && hipMemset(c->d_sc, 0, sizeof(Scalars)) == hipSuccess;
@@ -472,7 +474,8 @@ qgx_status qgx_set_code_table(qgx_ctx* ctx, const uint8_t* code_len, const uint3
 }
 
 static qgx_status run_encode(qgx_ctx* ctx, EncMode mode, const float* V, uint32_t call_id, const float* norms_in,
-                             float* norms_out, uint8_t* sym_out, const uint8_t* sym_in, qgx_stream* out, void* stream)
+                             float* norms_out, uint8_t* sym_out, const uint8_t* sym_in, qgx_stream* out, void* stream,
+                             const GameArgs* game = nullptr)
 {
     qgx_status s = need_levels(ctx);
     if (s != QGX_OK) return s;
@@ -504,6 +507,7 @@ static qgx_status run_encode(qgx_ctx* ctx, EncMode mode, const float* V, uint32_
         a.cap_words = out->payload_words_per_worker;
         a.scan_state = ctx->d_scan;
     }
+    if (game) a.game = *game;
     a.parts = ctx->parts;
     a.xch = ctx->d_xch;
     a.tickets = ctx->d_tickets;
@@ -541,6 +545,70 @@ qgx_status qgx_quantize_encode(qgx_ctx* ctx, const float* V, uint32_t call_id, c
     if (s != QGX_OK) return s;
     if (!aligned16(V) || !aligned16(norms_in)) return fail(ctx, QGX_ERR_ARG, "qgx_quantize_encode: V must be 16-byte aligned");
     return run_encode(ctx, EncMode::Fused, V, call_id, norms_in, out->norms, nullptr, nullptr, out, stream);
+}
+
+// qgx_game -> kernel arguments, with the checks the kernels rely on (four coordinates at a time)
+static qgx_status game_args(qgx_ctx* ctx, const qgx_game* game, GameArgs& g, const char* what)
+{
+    if (!game || !game->z || !game->a || !game->b) return fail(ctx, QGX_ERR_ARG, "%s: null game pointer", what);
+    if (!aligned16(game->z) || !aligned16(game->b) || (reinterpret_cast<uintptr_t>(game->a) & 7u))
+        return fail(ctx, QGX_ERR_ARG, "%s: z and b must be 16-byte aligned, a 8-byte aligned", what);
+    if (ctx->cfg.d & 3u) return fail(ctx, QGX_ERR_ARG, "%s: the vector length must be a multiple of 4", what);
+    if (!(game->sigma >= 0.0f) || !(std::fabs(game->mu) <= 3.402823466e+38f))
+        return fail(ctx, QGX_ERR_ARG, "%s: sigma must be >= 0 and mu finite", what);
+    g.z = game->z; g.a = game->a; g.b = game->b; g.mu = game->mu; g.sigma = game->sigma;
+    g.seed_lo = (uint32_t)game->noise_seed; g.seed_hi = (uint32_t)(game->noise_seed >> 32);
+    g.V_out = nullptr;
+    return QGX_OK;
+}
+
+qgx_status qgx_game_operator(qgx_ctx* ctx, const qgx_game* game, float* F_out, void* stream)
+{
+    if (!ctx || !F_out || !aligned16(F_out)) return fail(ctx, QGX_ERR_ARG, "qgx_game_operator: F_out null or misaligned");
+    GameArgs g{};
+    qgx_status s = game_args(ctx, game, g, "qgx_game_operator");
+    if (s != QGX_OK) return s;
+    QGX_HIP(ctx, launch_game_operator(g, ctx->lay.d, F_out, (hipStream_t)stream));
+    return QGX_OK;
+}
+
+qgx_status qgx_game_dual_vectors(qgx_ctx* ctx, const qgx_game* game, uint32_t call_id, float* V_out, void* stream)
+{
+    if (!ctx || !V_out || !aligned16(V_out)) return fail(ctx, QGX_ERR_ARG, "qgx_game_dual_vectors: V_out null or misaligned");
+    GameArgs g{};
+    qgx_status s = game_args(ctx, game, g, "qgx_game_dual_vectors");
+    if (s != QGX_OK) return s;
+    const uint32_t mode = call_id == QGX_CALL_FIRST_HALF ? 1u : call_id == QGX_CALL_SECOND_HALF ? 2u : 0u;
+    QGX_HIP(ctx, launch_game_dual_vectors(g, ctx->lay.d, ctx->lay.K, call_id, mode, ctx->d_sc, V_out, (hipStream_t)stream));
+    return QGX_OK;
+}
+
+qgx_status qgx_quantize_encode_game(qgx_ctx* ctx, const qgx_game* game, uint32_t call_id, qgx_stream* out, float* V_out,
+                                    void* stream)
+{
+    if (!ctx) return QGX_ERR_ARG;
+    qgx_status s = check_stream(ctx, out, "qgx_quantize_encode_game");
+    if (s != QGX_OK) return s;
+    GameArgs g{};
+    s = game_args(ctx, game, g, "qgx_quantize_encode_game");
+    if (s != QGX_OK) return s;
+    if (!aligned16(V_out)) return fail(ctx, QGX_ERR_ARG, "qgx_quantize_encode_game: V_out misaligned");
+    if (ctx->lay.shared_chunks || ctx->seg.size() != 1)
+        return fail(ctx, QGX_ERR_ARG, "qgx_quantize_encode_game: one segment, and buckets that do not share chunks (not 256..2048)");
+    if (ctx->cfg.norm != QGX_NORM_L2 && ctx->cfg.norm != QGX_NORM_LINF)
+        return fail(ctx, QGX_ERR_ARG, "qgx_quantize_encode_game: L2 or L-infinity norm");
+    g.V_out = V_out;
+    return run_encode(ctx, EncMode::Generate, nullptr, call_id, nullptr, out->norms, nullptr, nullptr, out, stream, &g);
+}
+
+qgx_status qgx_norm2(qgx_ctx* ctx, const float* x, uint64_t n, double* result_host, void* stream)
+{
+    if (!ctx || !x || !result_host || n == 0) return fail(ctx, QGX_ERR_ARG, "qgx_norm2: null argument or empty vector");
+    hipStream_t st = (hipStream_t)stream;
+    QGX_HIP(ctx, launch_norm2(x, n, ctx->d_norm, st));
+    QGX_HIP(ctx, hipMemcpyAsync(result_host, ctx->d_norm + kNormBlocks, sizeof(double), hipMemcpyDeviceToHost, st));
+    QGX_HIP(ctx, hipStreamSynchronize(st));
+    return QGX_OK;
 }
 
 static void fill_decode_args(const qgx_ctx* ctx, DecodeArgs& a, const qgx_stream* cur, const qgx_stream* prev)

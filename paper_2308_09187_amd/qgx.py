@@ -29,6 +29,7 @@ EXPORTS = [
     "qgx_quantize", "qgx_encode", "qgx_quantize_encode", "qgx_decode", "qgx_decode_average", "qgx_fit_levels", "qgx_fit_code",
     "qgx_state_init", "qgx_eg_step", "qgx_eg_step_static", "qgx_average_reset", "qgx_average_export", "qgx_get_scalars", "qgx_stream_bits", "qgx_debug_set_waves_per_position", "qgx_state_export", "qgx_state_import",
     "qgx_poll_error", "qgx_last_error",
+    "qgx_game_operator", "qgx_game_dual_vectors", "qgx_quantize_encode_game", "qgx_norm2",
 ]
 
 
@@ -42,6 +43,11 @@ class _Config(C.Structure):
     _fields_ = [("d", C.c_uint64), ("K", C.c_uint32), ("bucket", C.c_uint32), ("n_segments", C.c_uint32),
                 ("segment_len", C.POINTER(C.c_uint64)), ("norm", C.c_int32), ("code", C.c_int32),
                 ("seed", C.c_uint64)]
+
+
+class _Game(C.Structure):
+    _fields_ = [("z", C.c_void_p), ("a", C.c_void_p), ("b", C.c_void_p), ("mu", C.c_float), ("sigma", C.c_float),
+                ("noise_seed", C.c_uint64)]
 
 
 class _Stream(C.Structure):
@@ -190,6 +196,36 @@ class Context:
         self._check(self.lib.qgx_quantize_encode(self._h, _ptr(V), C.c_uint32(call_id), _ptr(norms_in), C.byref(s),
                                                  _stream_handle(stream)))
         return out
+
+    # -- the large quadratic game's operator, dual vectors and residual norm on the device -------------
+    @staticmethod
+    def _game(z, a, b, mu, sigma, noise_seed):
+        return _Game(z.data_ptr(), a.data_ptr(), b.data_ptr(), mu, sigma, noise_seed)
+
+    def game_operator(self, z, a, b, mu, out=None, stream=None):
+        if out is None:
+            out = torch.empty(self.d, dtype=torch.float32, device=z.device)
+        g = self._game(z, a, b, mu, 0.0, 0)
+        self._check(self.lib.qgx_game_operator(self._h, C.byref(g), _ptr(out), _stream_handle(stream)))
+        return out
+
+    def game_dual_vectors(self, z, a, b, mu, sigma, noise_seed, call_id, out=None, stream=None):
+        if out is None:
+            out = torch.empty((self.K, self.d), dtype=torch.float32, device=z.device)
+        g = self._game(z, a, b, mu, sigma, noise_seed)
+        self._check(self.lib.qgx_game_dual_vectors(self._h, C.byref(g), C.c_uint32(call_id), _ptr(out), _stream_handle(stream)))
+        return out
+
+    def quantize_encode_game(self, z, a, b, mu, sigma, noise_seed, call_id, out: Stream, V_out=None, stream=None):
+        g, s = self._game(z, a, b, mu, sigma, noise_seed), out.c_struct()
+        self._check(self.lib.qgx_quantize_encode_game(self._h, C.byref(g), C.c_uint32(call_id), C.byref(s), _ptr(V_out),
+                                                      _stream_handle(stream)))
+        return out
+
+    def norm2(self, x, stream=None):
+        r = C.c_double()
+        self._check(self.lib.qgx_norm2(self._h, _ptr(x), C.c_uint64(x.numel()), C.byref(r), _stream_handle(stream)))
+        return r.value
 
     # -- DEQ o CODE and the fused updates ---------------------------------------------------------
     def decode(self, st: Stream, out=None, stream=None):
