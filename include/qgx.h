@@ -262,6 +262,14 @@ qgx_status qgx_quantize_encode_game(qgx_ctx* ctx, const qgx_game* game, uint32_t
  * ||F(x)|| once F(x) has been formed with qgx_game_operator, say at the ergodic average).  Synchronises. */
 qgx_status qgx_norm2(qgx_ctx* ctx, const float* x, uint64_t n, double* result_host, void* stream);
 
+/* What one call of Q did, per worker (Section 3.1; a diagnostic beside the hot path).  V DEVICE [K][d] the vectors
+ * given to qgx_quantize / qgx_quantize_encode, Vhat DEVICE [K][d] their decoded images (qgx_decode).  HOST
+ * arrays of K, each optional (NULL): nonzeros = ||Q(v_k)||_0, whose expectation is (1 - p_0) d (Lemma 2);
+ * sq_error = ||Q(v_k) - v_k||^2, whose expectation is eq. (var) and which Theorem 1 bounds by
+ * epsilon_Q ||v_k||^2 on average; sq_norm = ||v_k||^2.  Sums in binary64 in a fixed order.  Synchronises. */
+qgx_status qgx_quantization_metrics(qgx_ctx* ctx, const float* V, const float* Vhat, uint64_t* nonzeros_host,
+                                    double* sq_error_host, double* sq_norm_host, void* stream);
+
 /* State of eq. (Q-GenX): Y_1 = 0, S = 0, t = 1, gamma_1 = K, anchor = X1 (DEVICE [d] or NULL = 0).
  * The paper's X_{t+1} = gamma_{t+1} Y_{t+1} is the X1 = 0 case of X_{t+1} = X1 + gamma_{t+1} Y_{t+1}. */
 qgx_status qgx_state_init(qgx_ctx* ctx, const float* X1, void* stream);

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqgx.so")
-SOURCES = ["qgx_lib.hip", "qgx_tables.hip", "qgx_encode.hip", "qgx_decode.hip", "qgx_fit.hip", "qgx_game.hip"]
+SOURCES = ["qgx_lib.hip", "qgx_tables.hip", "qgx_encode.hip", "qgx_decode.hip", "qgx_fit.hip", "qgx_game.hip", "qgx_metrics.hip"]
 
 # -ffp-contract=off: the rounding decisions are specified as separately rounded binary32 operations.
 # packed-fp32 ops are switched off for the device pass (the host pass warns that it ignores the flag).

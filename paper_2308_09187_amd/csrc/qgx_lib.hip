@@ -74,6 +74,7 @@ struct qgx_ctx {
     double* d_hist = nullptr;
     double* d_prob = nullptr;       // [kSymMax] symbol probabilities of the last qgx_fit_code
     double* d_norm = nullptr;       // [kNormBlocks + 1] partial sums and result of qgx_norm2
+    double* d_metrics = nullptr;    // [K][3][kMetricBlocks] partial sums, then [K][3] results of qgx_quantization_metrics
     SideQueue side{};               // for the ragged chunk positions of the decoding kernels
     bool side_ok = false;
     double* d_xsum = nullptr;       // [d] sum of the X_{t+1/2} since qgx_average_reset (allocated there)
@@ -187,7 +188,7 @@ qgx_status need_levels(qgx_ctx* ctx) { return need_levels(ctx, ctx->sel); }
 
 void free_all(qgx_ctx* c)
 {
-    void* all[] = {c->d_layout, c->d_tabs, c->d_sc, c->d_Y, c->d_anchor, c->d_scan, c->d_xch, c->d_tickets, c->d_spartial, c->d_hpartial, c->d_hist, c->d_prob, c->d_norm, c->d_xsum};
+    void* all[] = {c->d_layout, c->d_tabs, c->d_sc, c->d_Y, c->d_anchor, c->d_scan, c->d_xch, c->d_tickets, c->d_spartial, c->d_hpartial, c->d_hist, c->d_prob, c->d_norm, c->d_metrics, c->d_xsum};
     for (void* p : all) (void)hipFree(p);
     if (c->side_ok) {
         (void)hipEventDestroy(c->side.fork);
@@ -320,6 +321,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     ok = ok && hipMalloc(&c->d_hist, QGX_MAX_BINS * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_prob, kSymMax * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_norm, (kNormBlocks + 1) * sizeof(double)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_metrics, (size_t)cfg->K * 3 * (kMetricBlocks + 1) * sizeof(double)) == hipSuccess;
     ok = ok && hipMemcpy(c->d_layout, flat.data(), n_lay * sizeof(uint32_t), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemset(c->d_tabs, 0, QGX_TABLES * sizeof(Tables)) == hipSuccess;
     ok = ok && hipMemset(c->d_sc, 0, sizeof(Scalars)) == hipSuccess;
@@ -608,6 +610,25 @@ qgx_status qgx_norm2(qgx_ctx* ctx, const float* x, uint64_t n, double* result_ho
     QGX_HIP(ctx, launch_norm2(x, n, ctx->d_norm, st));
     QGX_HIP(ctx, hipMemcpyAsync(result_host, ctx->d_norm + kNormBlocks, sizeof(double), hipMemcpyDeviceToHost, st));
     QGX_HIP(ctx, hipStreamSynchronize(st));
+    return QGX_OK;
+}
+
+qgx_status qgx_quantization_metrics(qgx_ctx* ctx, const float* V, const float* Vhat, uint64_t* nonzeros_host,
+                                    double* sq_error_host, double* sq_norm_host, void* stream)
+{
+    if (!ctx || !V || !Vhat) return fail(ctx, QGX_ERR_ARG, "qgx_quantization_metrics: null argument");
+    hipStream_t st = (hipStream_t)stream;
+    const uint32_t K = ctx->lay.K;
+    double* result = ctx->d_metrics + (size_t)K * 3 * kMetricBlocks;
+    QGX_HIP(ctx, launch_metrics(V, Vhat, ctx->lay.d, K, ctx->d_metrics, result, st));
+    std::vector<double> h((size_t)K * 3);
+    QGX_HIP_DRAIN(ctx, st, hipMemcpyAsync(h.data(), result, h.size() * sizeof(double), hipMemcpyDeviceToHost, st));
+    QGX_HIP(ctx, hipStreamSynchronize(st));
+    for (uint32_t k = 0; k < K; ++k) {
+        if (nonzeros_host) nonzeros_host[k] = (uint64_t)h[(size_t)k * 3];
+        if (sq_error_host) sq_error_host[k] = h[(size_t)k * 3 + 1];
+        if (sq_norm_host) sq_norm_host[k] = h[(size_t)k * 3 + 2];
+    }
     return QGX_OK;
 }
 

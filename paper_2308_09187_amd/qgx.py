@@ -29,7 +29,7 @@ EXPORTS = [
     "qgx_quantize", "qgx_encode", "qgx_quantize_encode", "qgx_decode", "qgx_decode_average", "qgx_fit_levels", "qgx_fit_code",
     "qgx_state_init", "qgx_eg_step", "qgx_eg_step_static", "qgx_average_reset", "qgx_average_export", "qgx_get_scalars", "qgx_stream_bits", "qgx_debug_set_waves_per_position", "qgx_state_export", "qgx_state_import",
     "qgx_poll_error", "qgx_last_error",
-    "qgx_game_operator", "qgx_game_dual_vectors", "qgx_quantize_encode_game", "qgx_norm2",
+    "qgx_game_operator", "qgx_game_dual_vectors", "qgx_quantize_encode_game", "qgx_norm2", "qgx_quantization_metrics",
 ]
 
 
@@ -226,6 +226,17 @@ class Context:
         r = C.c_double()
         self._check(self.lib.qgx_norm2(self._h, _ptr(x), C.c_uint64(x.numel()), C.byref(r), _stream_handle(stream)))
         return r.value
+
+    def quantization_metrics(self, V, Vhat, stream=None):
+        """Per worker: (number of nonzeros of Q(v), ||Q(v) - v||^2, ||v||^2) as three numpy arrays of K."""
+        import numpy as np
+        nnz = np.zeros(self.K, np.uint64)
+        err = np.zeros(self.K, np.float64)
+        nrm = np.zeros(self.K, np.float64)
+        self._check(self.lib.qgx_quantization_metrics(self._h, _ptr(V), _ptr(Vhat), C.c_void_p(nnz.ctypes.data),
+                                                      C.c_void_p(err.ctypes.data), C.c_void_p(nrm.ctypes.data),
+                                                      _stream_handle(stream)))
+        return nnz, err, nrm
 
     # -- DEQ o CODE and the fused updates ---------------------------------------------------------
     def decode(self, st: Stream, out=None, stream=None):

@@ -195,7 +195,8 @@ def test_single_vector_operator_over_32_calls(qgx, tab):
     Every stream bit for bit against the oracle; and on the GPU's own decoded vectors: the mean over the
     32 draws is within 5 sigma of unbiased (||mean - v||^2 against Var / 32), the realised variance is
     within 1 % of eq. (var), and bucket by bucket it respects eps_Q ||v||^2 of Theorem 1 with d the
-    bucket length (the worked values 4.782 and 0.125002)."""
+    bucket length (the worked values 4.782 and 0.125002).  The device's own per-call figures
+    (qgx_quantization_metrics) equal the same sums taken here, and their means meet Lemma 2 and eq. (var)."""
     d, K, bucket, seed, R = 1 << 20, 1, 8192, 10, 32
     v = synth.gaussian_vector(d, seed=10)
     V = v[None, :]
@@ -205,9 +206,17 @@ def test_single_vector_operator_over_32_calls(qgx, tab):
     out = ctx.new_stream()
     v64 = v.astype(np.float64)
     acc, sq = np.zeros(d), np.zeros(lay.NB)
+    nnz_dev, err_dev = [], []
     for call in range(R):
         ctx.quantize_encode(Vd, call, out)
-        Vh = ctx.decode(out).cpu().numpy()
+        Vh_d = ctx.decode(out)
+        Vh = Vh_d.cpu().numpy()
+        nnz, err, nrm = ctx.quantization_metrics(Vd, Vh_d)
+        assert nnz[0] == np.count_nonzero(Vh[0])
+        assert abs(err[0] - ((Vh[0].astype(np.float64) - v64) ** 2).sum()) <= 1e-12 * err[0]
+        assert abs(nrm[0] - (v64 * v64).sum()) <= 1e-12 * nrm[0]
+        nnz_dev.append(float(nnz[0]))
+        err_dev.append(err[0])
         h = out.to_host()
         if call == 0:
             n_o = oracle.quantize(V, lay, oracle.NORM_L2, levels, seed, 0)[0]
@@ -226,6 +235,11 @@ def test_single_vector_operator_over_32_calls(qgx, tab):
     var_i = n[:, None] ** 2 * (lv[tau + 1] - u) * (u - lv[tau])        # variance of every coordinate's draw
     var_b = var_i.sum(1)
     assert abs(sq.sum() / R - var_b.sum()) <= 0.01 * var_b.sum()
+    assert abs(np.mean(err_dev) - var_b.sum()) <= 0.01 * var_b.sum()
+    # Lemma 2: a coordinate below l_1 survives with probability u / l_1, one above it always; the count is a
+    # sum of independent Bernoulli draws
+    p_nz = np.where(tau == 0, u / lv[1], 1.0)
+    assert abs(np.mean(nnz_dev) - p_nz.sum()) <= 5 * np.sqrt((p_nz * (1 - p_nz)).sum() / R) + 1e-9
     # unbiasedness: E ||mean - v||^2 = Var / R; the statistic is a sum over 2^20 independent coordinates whose
     # variance is about 2 sum sigma_i^4 / R^2
     stat = ((acc / R - v64) ** 2).sum()
@@ -237,6 +251,26 @@ def test_single_vector_operator_over_32_calls(qgx, tab):
     eps = (lbar + 1 / lbar) / 4 - 0.5 + (0.25 * l1 * l1 * bucket if bucket < dth else l1 * np.sqrt(bucket) - 1)
     assert abs(eps - (4.78185425 if tab == "uni16" else 0.12500191)) < 1e-6
     assert (var_b <= eps * n * n).all() and (sq / R <= eps * n * n).all()
+    assert ctx.poll_error() == 0
+    ctx.close()
+
+
+def test_quantization_metrics_per_worker(qgx):
+    """The per-worker figures on several workers, a ragged d and an all-zero worker, against plain sums here."""
+    d, K, bucket = 3 * 4096 + 77, 4, 512
+    levels = synth.levels_exponential(8)
+    ctx, lay = make_ctx(qgx, d, K, bucket, oracle.NORM_LINF, levels, seed=5)
+    V = synth.student_t3(K, d, seed=21)
+    V[2] = 0.0
+    Vd, out = dev(V), ctx.new_stream()
+    ctx.quantize_encode(Vd, 3, out)
+    Vh_d = ctx.decode(out)
+    Vh, V64 = Vh_d.cpu().numpy().astype(np.float64), V.astype(np.float64)
+    nnz, err, nrm = ctx.quantization_metrics(Vd, Vh_d)
+    np.testing.assert_array_equal(nnz, np.count_nonzero(Vh, axis=1))
+    np.testing.assert_allclose(err, ((Vh - V64) ** 2).sum(1), rtol=1e-12, atol=0)
+    np.testing.assert_allclose(nrm, (V64 * V64).sum(1), rtol=1e-12, atol=0)
+    assert nnz[2] == 0 and err[2] == 0.0 and nrm[2] == 0.0 and nnz[0] > 0
     assert ctx.poll_error() == 0
     ctx.close()
 
