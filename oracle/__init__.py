@@ -61,6 +61,7 @@ def lib():
         _lib.orc_normal.restype = C.c_double
         _lib.orc_normal.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64]
         _lib.orc_norm2.restype = C.c_double
+        _lib.orc_game_gap.restype = C.c_double
         for f in ("orc_chunk_coords", "orc_sub_coords", "orc_align_words"):
             getattr(_lib, f).restype = C.c_uint32
     return _lib
@@ -356,6 +357,16 @@ def game_dual_vectors(z, a, b, mu, sigma, noise_seed, call_id, K):
     lib().orc_game_dual_vectors(_p(z, C.c_float), _p(a, C.c_float), _p(b, C.c_float), C.c_double(mu), C.c_double(sigma),
                                 C.c_uint64(noise_seed), C.c_uint32(call_id), C.c_uint32(K), C.c_uint64(len(z)), _p(V, C.c_float))
     return V
+
+
+def game_gap(xhat, a, b, mu, center, R, want_maximiser=False):
+    """Restricted gap sup_{x in C} <A(x), xhat - x> over the ball C of radius R around center (None = origin)."""
+    xhat = _c(xhat, np.float32); a = _c(a, np.float32); b = _c(b, np.float32)
+    c = None if center is None else _c(center, np.float32)
+    x = np.zeros(len(xhat), np.float64)
+    g = lib().orc_game_gap(_p(xhat, C.c_float), _p(a, C.c_float), _p(b, C.c_float), C.c_double(mu), None if c is None else _p(c, C.c_float),
+          C.c_double(R), C.c_uint64(len(xhat)), _p(x, C.c_double))
+    return (float(g), x) if want_maximiser else float(g)
 
 
 def norm2(x):

@@ -893,6 +893,50 @@ double orc_norm2(const float* x, uint64_t n)
     return sqrt(acc);
 }
 
+/* ------------------------------------------------------------------------ */
+/* Restricted gap (eq. (Gap), Section 2) of the game's operator over the      */
+/* closed ball C of radius R around `center` (NULL = the origin):             */
+/*   Gap_C(xhat) = sup_{x in C} <A(x), xhat - x>,  A(x) = M x + b.            */
+/* M is mu I plus a skew part, so <M x, x> = mu ||x||^2 and                   */
+/*   <A(x), xhat - x> = -mu ||x||^2 + <M^T xhat - b, x> + <b, xhat>,          */
+/* a concave quadratic with the same curvature in every direction (mu > 0):   */
+/* its maximiser over the ball is the point of the ball nearest to the free   */
+/* maximiser x0 = (M^T xhat - b) / (2 mu).  The supremum is then taken from   */
+/* the definition at that point.  Binary64.                                   */
+/* ------------------------------------------------------------------------ */
+double orc_game_gap(const float* xhat, const float* a, const float* b, double mu, const float* center, double R,
+                    uint64_t d, double* maximiser /* [d] or NULL */)
+{
+    double* x = (double*)malloc(sizeof(double) * d);
+    double dist2 = 0.0;
+    for (uint64_t j = 0; j + 1 < d; j += 2) {
+        const double h0 = xhat[j], h1 = xhat[j + 1], aj = a[j / 2];
+        /* M^T = [[mu, -a], [a, mu]] on the block */
+        x[j] = (mu * h0 - aj * h1 - (double)b[j]) / (2.0 * mu);
+        x[j + 1] = (aj * h0 + mu * h1 - (double)b[j + 1]) / (2.0 * mu);
+        for (int q = 0; q < 2; ++q) {
+            const double c = center ? (double)center[j + q] : 0.0;
+            dist2 += (x[j + q] - c) * (x[j + q] - c);
+        }
+    }
+    const double dist = sqrt(dist2);
+    if (dist > R) {
+        for (uint64_t i = 0; i < d; ++i) {
+            const double c = center ? (double)center[i] : 0.0;
+            x[i] = c + (R / dist) * (x[i] - c);
+        }
+    }
+    double gap = 0.0;
+    for (uint64_t j = 0; j + 1 < d; j += 2) {
+        const double x0 = x[j], x1 = x[j + 1], aj = a[j / 2];
+        const double A0 = mu * x0 + aj * x1 + (double)b[j], A1 = -aj * x0 + mu * x1 + (double)b[j + 1];
+        gap += A0 * ((double)xhat[j] - x0) + A1 * ((double)xhat[j + 1] - x1);
+    }
+    if (maximiser) memcpy(maximiser, x, sizeof(double) * d);
+    free(x);
+    return gap;
+}
+
 uint32_t orc_chunk_coords(void) { return ORC_CH; }
 uint32_t orc_sub_coords(void) { return ORC_SUB; }
 uint32_t orc_align_words(void) { return ORC_ALIGN_WORDS; }

@@ -74,6 +74,11 @@ MUTANTS = [
      "ctr[0] = (uint32_t)g; ctr[1] = 1u; ctr[2] = 0; ctr[3] = call_id;", [G]),
     ("operator with a symmetric coupling", "F[j + 1] = -aj * z0 + mu * z1 + (double)b[j + 1];",
      "F[j + 1] = aj * z0 + mu * z1 + (double)b[j + 1];", [G]),
+    ("free maximiser of the gap without the factor two", "x[j] = (mu * h0 - aj * h1 - (double)b[j]) / (2.0 * mu);",
+     "x[j] = (mu * h0 - aj * h1 - (double)b[j]) / mu;", [G]),
+    ("gap's maximiser from the operator instead of its transpose", "x[j + 1] = (aj * h0 + mu * h1 - (double)b[j + 1]) / (2.0 * mu);",
+     "x[j + 1] = (-aj * h0 + mu * h1 - (double)b[j + 1]) / (2.0 * mu);", [G]),
+    ("gap's ball taken around the origin", "x[i] = c + (R / dist) * (x[i] - c);", "x[i] = (R / dist) * x[i];", [G]),
     ("cost of a word without its weight", "const uint64_t cost = w[i] * l + BEST(i + 1, k - space);",
      "const uint64_t cost = l + BEST(i + 1, k - space);", [H]),
 ]
