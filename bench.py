@@ -238,9 +238,15 @@ def game_bench(args):
     bits = ctx.stream_bits(sa)
     h_bits = sa.sub_end.cpu().numpy().view(np.uint16)[:, :, -1].astype(np.int64)
     stream_bytes = int((((h_bits + 31) // 32 + 3) // 4 * 4).sum()) * 4 + K * ((ctx.NC + 1) * 4 + ctx.NC * qgx.SUBS * 2 + ctx.NB * 4)
-    # algorithmic bytes of the fused coding kernel: z, a and b once (10 bytes per coordinate; the K workers' reads of
-    # one piece meet in the cache) and the streams out.  The kernel is bound by instruction issue, not by these.
+    # The coding kernel that forms its own input is bound by vector-ALU issue, not by memory (it reads z, a and b
+    # once, 10 bytes per coordinate, and writes the streams: 13 % of the memory roof).  Its row loop holds 256
+    # vector instructions per four coordinates in the compiled kernel (140 of the plain coding kernel, of which
+    # Philox4x32-10 is 56, plus a second Philox block, two Box-Muller pairs and the operator): 64 per coordinate.
+    # Roof: one vector instruction per SIMD every four clocks, 256 CUs x 4 SIMDs x 64 lanes x 2.4 GHz / 4.
+    VALU_PER_COORD, ALU_PEAK = 64.0, 256 * 4 * 64 * 2.4e9 / 4 / 1e12
+    alu_rate = VALU_PER_COORD * K * d / (per_f["encode"] * 1e-3) / 1e12
     enc_bytes_f = d * 10 + stream_bytes
+    gap = ctx.game_gap(X, a_d, b_d, game.mu, torch.from_numpy(game.solution().astype(np.float32)).cuda(), 1.0)
     out = {
         "metric": "GB/s of fp32 dual vectors through quantize->encode->decode->avg->EG step; % HBM peak",
         "value": 2 * 4.0 * K * d / wall_f / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -252,10 +258,12 @@ def game_bench(args):
         "kernels_ms": per_f,
         "materialised": {"what": "the same iterations with the dual vectors written to memory by qgx_game_dual_vectors and coded from there",
                          "ms_per_step": wall_m * 1e3, "value": 2 * 4.0 * K * d / wall_m / 1e9, "unit": "GB/s", "kernels_ms": per_m},
-        "roofline": {"kernel": "k_encode<Generate, false, %d>" % (4 if n_sym <= 33 else 5 if n_sym <= 65 else 6), "bound": "hbm",
-                     "achieved": enc_bytes_f / (per_f["encode"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": enc_bytes_f / (per_f["encode"] * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes": enc_bytes_f},
+        "roofline": {"kernel": "k_encode<Generate, false, %d>" % (4 if n_sym <= 33 else 5 if n_sym <= 65 else 6), "bound": "alu",
+                     "achieved": alu_rate, "peak": ALU_PEAK, "unit": "T lane-instructions/s", "frac": alu_rate / ALU_PEAK, "traffic": None,
+                     "valu_instructions_per_coordinate": VALU_PER_COORD, "algorithmic_bytes": enc_bytes_f,
+                     "hbm_frac": enc_bytes_f / (per_f["encode"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "residual_norm_at_the_last_iterate": res,
+        "restricted_gap_at_the_last_iterate_unit_ball_around_the_solution": gap,
     }
     ctx.close()
     print(json.dumps(out))

@@ -262,6 +262,15 @@ qgx_status qgx_quantize_encode_game(qgx_ctx* ctx, const qgx_game* game, uint32_t
  * ||F(x)|| once F(x) has been formed with qgx_game_operator, say at the ergodic average).  Synchronises. */
 qgx_status qgx_norm2(qgx_ctx* ctx, const float* x, uint64_t n, double* result_host, void* stream);
 
+/* result_host HOST <- the restricted gap of eq. (Gap), Section 2, for the game's operator and the candidate
+ * game->z over the closed ball of `radius` around centre (DEVICE [d], or NULL = the origin):
+ * sup_{x in ball} <F(x), z - x>, the quantity the convergence theorems bound at the ergodic average.  For this
+ * operator the supremum has a closed form (a concave quadratic of equal curvature mu in all directions: the
+ * maximiser is the point of the ball nearest to (M^T z - b) / (2 mu)); binary64 sums in a fixed order.
+ * mu > 0 (QGX_ERR_ARG otherwise); sigma and noise_seed are not used.  Synchronises. */
+qgx_status qgx_game_gap(qgx_ctx* ctx, const qgx_game* game, const float* centre, double radius, double* result_host,
+                        void* stream);
+
 /* What one call of Q did, per worker (Section 3.1; a diagnostic beside the hot path).  V DEVICE [K][d] the vectors
  * given to qgx_quantize / qgx_quantize_encode, Vhat DEVICE [K][d] their decoded images (qgx_decode).  HOST
  * arrays of K, each optional (NULL): nonzeros = ||Q(v_k)||_0, whose expectation is (1 - p_0) d (Lemma 2);

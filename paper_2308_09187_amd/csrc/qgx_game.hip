@@ -83,4 +83,88 @@ hipError_t launch_norm2(const float* x, uint64_t n, double* partial, hipStream_t
     return hipGetLastError();
 }
 
+// Restricted gap (eq. (Gap), Section 2) of F over the closed ball of radius R around `centre` (NULL: the
+// origin): sup_x <F(x), xhat - x>.  <M x, x> = mu ||x||^2 (the coupling is skew), so the objective is a concave
+// quadratic of the same curvature in every direction and its maximiser over the ball is the point of the ball
+// nearest to the free maximiser x0 = (M^T xhat - b) / (2 mu).  Two passes over the blocks in binary64, each
+// with the fixed-order sums of the norm above: the distance of x0 from the centre, then the objective at the
+// maximiser.  G.z holds xhat.
+__device__ __forceinline__ void gap_free_maximiser(const GameArgs& G, const float* __restrict__ centre, uint64_t j,
+                                                   double& x0, double& x1, double& c0, double& c1)
+{
+    const double h0 = (double)G.z[j], h1 = (double)G.z[j + 1], a = (double)G.a[j >> 1], mu = (double)G.mu;
+    x0 = (mu * h0 - a * h1 - (double)G.b[j]) / (2.0 * mu);
+    x1 = (a * h0 + mu * h1 - (double)G.b[j + 1]) / (2.0 * mu);
+    c0 = centre ? (double)centre[j] : 0.0;
+    c1 = centre ? (double)centre[j + 1] : 0.0;
+}
+
+__device__ __forceinline__ void block_sum_to(double acc, double* __restrict__ out)
+{
+    __shared__ double s_red[256];
+    s_red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) s_red[threadIdx.x] += s_red[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *out = s_red[0];
+}
+
+// PASS 0: partial[block] = sum of ||x0 - c||^2 over the block's run of 2x2 blocks.
+// PASS 1: with shrink = partial[kNormBlocks] (1 inside the ball, R / distance outside), the objective's sum.
+template <int PASS>
+__global__ __launch_bounds__(256) void k_gap_partial(GameArgs G, const float* __restrict__ centre, uint64_t d,
+                                                     double* __restrict__ partial)
+{
+    const uint64_t pairs = d / 2, per = (pairs + kNormBlocks - 1) / kNormBlocks;
+    const uint64_t lo = (uint64_t)blockIdx.x * per, hi = lo + per < pairs ? lo + per : pairs;
+    const double shrink = PASS == 1 ? partial[kNormBlocks] : 1.0;
+    double* out = partial + (PASS == 1 ? kNormBlocks + 1 : 0) + blockIdx.x;
+    double acc = 0.0;
+    for (uint64_t p = lo + threadIdx.x; p < hi; p += 256u) {
+        double x0, x1, c0, c1;
+        gap_free_maximiser(G, centre, 2 * p, x0, x1, c0, c1);
+        if (PASS == 0) {
+            acc += (x0 - c0) * (x0 - c0) + (x1 - c1) * (x1 - c1);
+        } else {
+            x0 = c0 + shrink * (x0 - c0);
+            x1 = c1 + shrink * (x1 - c1);
+            const double a = (double)G.a[p], mu = (double)G.mu;
+            const double F0 = mu * x0 + a * x1 + (double)G.b[2 * p], F1 = -a * x0 + mu * x1 + (double)G.b[2 * p + 1];
+            acc += F0 * ((double)G.z[2 * p] - x0) + F1 * ((double)G.z[2 * p + 1] - x1);
+        }
+    }
+    block_sum_to(acc, out);
+}
+
+// PASS 0: partial[kNormBlocks] = the factor that brings x0 into the ball; PASS 1: partial[2 kNormBlocks + 1] = the gap.
+template <int PASS>
+__global__ __launch_bounds__(256) void k_gap_finish(double* __restrict__ partial, double R)
+{
+    const double* in = partial + (PASS == 1 ? kNormBlocks + 1 : 0);
+    double acc = 0.0;
+    for (uint32_t i = threadIdx.x; i < kNormBlocks; i += 256u) acc += in[i];
+    __shared__ double s_total;
+    block_sum_to(acc, &s_total);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        if (PASS == 0) {
+            const double dist = sqrt(s_total);
+            partial[kNormBlocks] = dist > R ? R / dist : 1.0;
+        } else {
+            partial[2 * kNormBlocks + 1] = s_total;
+        }
+    }
+}
+
+hipError_t launch_game_gap(const GameArgs& g, const float* centre, double R, uint64_t d, double* partial, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_gap_partial<0>, dim3(kNormBlocks), dim3(256), 0, st, g, centre, d, partial);
+    hipLaunchKernelGGL(k_gap_finish<0>, dim3(1), dim3(256), 0, st, partial, R);
+    hipLaunchKernelGGL(k_gap_partial<1>, dim3(kNormBlocks), dim3(256), 0, st, g, centre, d, partial);
+    hipLaunchKernelGGL(k_gap_finish<1>, dim3(1), dim3(256), 0, st, partial, R);
+    return hipGetLastError();
+}
+
 }  // namespace qgx

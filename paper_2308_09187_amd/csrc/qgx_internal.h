@@ -233,6 +233,8 @@ hipError_t launch_game_dual_vectors(const GameArgs& g, uint32_t d, uint32_t K, u
                                     const Scalars* sc, float* V_out, hipStream_t st);
 constexpr uint32_t kNormBlocks = 1024;     // partial sums of qgx_norm2
 hipError_t launch_norm2(const float* x, uint64_t n, double* partial /*[kNormBlocks + 1]*/, hipStream_t st);
+hipError_t launch_game_gap(const GameArgs& g, const float* centre, double R, uint64_t d,
+                           double* partial /*[2 kNormBlocks + 2]: the result in the last*/, hipStream_t st);
 constexpr uint32_t kMetricBlocks = 256;    // partial sums per worker and figure of qgx_quantization_metrics
 hipError_t launch_metrics(const float* V, const float* Vhat, uint64_t d, uint32_t K, double* partial /*[K][3][kMetricBlocks]*/,
                           double* result /*[K][3]*/, hipStream_t st);

@@ -73,7 +73,7 @@ struct qgx_ctx {
     double* d_hpartial = nullptr;
     double* d_hist = nullptr;
     double* d_prob = nullptr;       // [kSymMax] symbol probabilities of the last qgx_fit_code
-    double* d_norm = nullptr;       // [kNormBlocks + 1] partial sums and result of qgx_norm2
+    double* d_norm = nullptr;       // [2 kNormBlocks + 2] partial sums and results of qgx_norm2 and qgx_game_gap
     double* d_metrics = nullptr;    // [K][3][kMetricBlocks] partial sums, then [K][3] results of qgx_quantization_metrics
     SideQueue side{};               // for the ragged chunk positions of the decoding kernels
     bool side_ok = false;
@@ -320,7 +320,7 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
     ok = ok && hipMalloc(&c->d_hpartial, (size_t)c->h_groups * QGX_MAX_BINS * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_hist, QGX_MAX_BINS * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_prob, kSymMax * sizeof(double)) == hipSuccess;
-    ok = ok && hipMalloc(&c->d_norm, (kNormBlocks + 1) * sizeof(double)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_norm, (2 * kNormBlocks + 2) * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_metrics, (size_t)cfg->K * 3 * (kMetricBlocks + 1) * sizeof(double)) == hipSuccess;
     ok = ok && hipMemcpy(c->d_layout, flat.data(), n_lay * sizeof(uint32_t), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemset(c->d_tabs, 0, QGX_TABLES * sizeof(Tables)) == hipSuccess;
@@ -609,6 +609,22 @@ qgx_status qgx_norm2(qgx_ctx* ctx, const float* x, uint64_t n, double* result_ho
     hipStream_t st = (hipStream_t)stream;
     QGX_HIP(ctx, launch_norm2(x, n, ctx->d_norm, st));
     QGX_HIP(ctx, hipMemcpyAsync(result_host, ctx->d_norm + kNormBlocks, sizeof(double), hipMemcpyDeviceToHost, st));
+    QGX_HIP(ctx, hipStreamSynchronize(st));
+    return QGX_OK;
+}
+
+qgx_status qgx_game_gap(qgx_ctx* ctx, const qgx_game* game, const float* centre, double radius, double* result_host,
+                        void* stream)
+{
+    if (!ctx || !result_host) return fail(ctx, QGX_ERR_ARG, "qgx_game_gap: null argument");
+    GameArgs g;
+    qgx_status s = game_args(ctx, game, g, "qgx_game_gap");
+    if (s != QGX_OK) return s;
+    if (!(game->mu > 0.0f) || !(radius >= 0.0) || !(radius <= 1.7976931348623157e308))
+        return fail(ctx, QGX_ERR_ARG, "qgx_game_gap: mu must be positive and the radius finite and >= 0");
+    hipStream_t st = (hipStream_t)stream;
+    QGX_HIP(ctx, launch_game_gap(g, centre, radius, ctx->lay.d, ctx->d_norm, st));
+    QGX_HIP(ctx, hipMemcpyAsync(result_host, ctx->d_norm + 2 * kNormBlocks + 1, sizeof(double), hipMemcpyDeviceToHost, st));
     QGX_HIP(ctx, hipStreamSynchronize(st));
     return QGX_OK;
 }

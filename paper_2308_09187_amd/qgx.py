@@ -29,7 +29,7 @@ EXPORTS = [
     "qgx_quantize", "qgx_encode", "qgx_quantize_encode", "qgx_decode", "qgx_decode_average", "qgx_fit_levels", "qgx_fit_code",
     "qgx_state_init", "qgx_eg_step", "qgx_eg_step_static", "qgx_average_reset", "qgx_average_export", "qgx_get_scalars", "qgx_stream_bits", "qgx_debug_set_waves_per_position", "qgx_state_export", "qgx_state_import",
     "qgx_poll_error", "qgx_last_error",
-    "qgx_game_operator", "qgx_game_dual_vectors", "qgx_quantize_encode_game", "qgx_norm2", "qgx_quantization_metrics",
+    "qgx_game_operator", "qgx_game_dual_vectors", "qgx_quantize_encode_game", "qgx_norm2", "qgx_game_gap", "qgx_quantization_metrics",
 ]
 
 
@@ -208,6 +208,12 @@ class Context:
         g = self._game(z, a, b, mu, 0.0, 0)
         self._check(self.lib.qgx_game_operator(self._h, C.byref(g), _ptr(out), _stream_handle(stream)))
         return out
+
+    def game_gap(self, z, a, b, mu, centre, radius, stream=None):
+        r = C.c_double()
+        g = self._game(z, a, b, mu, 0.0, 0)
+        self._check(self.lib.qgx_game_gap(self._h, C.byref(g), _ptr(centre), C.c_double(radius), C.byref(r), _stream_handle(stream)))
+        return r.value
 
     def game_dual_vectors(self, z, a, b, mu, sigma, noise_seed, call_id, out=None, stream=None):
         if out is None:

@@ -103,6 +103,7 @@ def test_iterations_on_the_device_and_the_residual_of_the_ergodic_average(qgx):
     d, K, bucket, T = 6 * 8192, 4, 8192, 12
     game, ctx, _ = setup(qgx, d, K, bucket)
     ad, bd = dev(game.a), dev(game.b)
+    sol = dev(game.solution().astype(np.float32))
 
     def run(fused):
         ctx.state_init(None)
@@ -125,15 +126,43 @@ def test_iterations_on_the_device_and_the_residual_of_the_ergodic_average(qgx):
             xbar, n = ctx.average_export()
             assert n == t + 1
             res.append(ctx.norm2(ctx.game_operator(xbar, ad, bd, game.mu)))
-        return X.clone(), xbar.clone(), res, ctx.scalars()
+        gap = ctx.game_gap(xbar, ad, bd, game.mu, sol, 1.0)
+        return X.clone(), xbar.clone(), res, ctx.scalars(), gap
 
-    X_f, xbar_f, res_f, sc_f = run(True)
-    X_m, xbar_m, res_m, sc_m = run(False)
-    assert torch.equal(X_f, X_m) and torch.equal(xbar_f, xbar_m) and res_f == res_m and sc_f == sc_m
+    X_f, xbar_f, res_f, sc_f, gap_f = run(True)
+    X_m, xbar_m, res_m, sc_m, gap_m = run(False)
+    assert torch.equal(X_f, X_m) and torch.equal(xbar_f, xbar_m) and res_f == res_m and sc_f == sc_m and gap_f == gap_m
+    # the restricted gap over the unit ball around the solution: positive, and the oracle's on the same average
+    want_gap = oracle.game_gap(xbar_f.cpu().numpy(), game.a, game.b, float(np.float32(game.mu)), game.solution().astype(np.float32), 1.0)
+    assert gap_f > 0 and abs(gap_f - want_gap) <= 1e-9 * want_gap
     want = np.linalg.norm(oracle.game_operator(xbar_f.cpu().numpy(), game.a, game.b, game.mu))
     assert abs(res_f[-1] - want) <= REL * want
     assert res_f[-1] < res_f[0] and sc_f["t"] == T + 1
     assert ctx.poll_error() == 0
+    ctx.close()
+
+
+@pytest.mark.parametrize("d,K,bucket", [(5 * 4096 + 512, 3, 8192), (4096, 2, 4096), (1 << 20, 2, 16384)])
+def test_restricted_gap_against_the_oracle(qgx, d, K, bucket):
+    """eq. (Gap) over balls that hold the free maximiser and balls that do not, around the origin, a random centre
+    and the solution; at the solution itself the gap is zero up to the rounding of the solution to binary32."""
+    game, ctx, z = setup(qgx, d, K, bucket)
+    ad, bd = dev(game.a), dev(game.b)
+    zs = game.solution().astype(np.float32)
+    rng = np.random.default_rng(17)
+    centre = rng.standard_normal(d).astype(np.float32)
+    near = (zs + 0.01 * rng.standard_normal(d)).astype(np.float32)
+    mu32 = float(np.float32(game.mu))           # the modulus as the struct carries it: the free maximum goes like 1 / mu
+    for xhat, c, R in ((z, None, 1.0), (z, None, 1e6), (z, centre, 3.0 * np.sqrt(d)), (near, zs, 1.0), (near, zs, 1e-3), (zs, zs, 1.0)):
+        want = oracle.game_gap(xhat, game.a, game.b, mu32, c, R)
+        got = ctx.game_gap(dev(xhat), ad, bd, game.mu, None if c is None else dev(c), R)
+        # both sides add 2^20 products in binary64, in different orders
+        scale = np.abs(oracle.game_operator(xhat, game.a, game.b, game.mu)).sum() * (np.abs(xhat).max() + 1.0)
+        assert abs(got - want) <= 1e-12 * scale + 1e-12 * abs(want), (R, got, want)
+        assert got == ctx.game_gap(dev(xhat), ad, bd, game.mu, None if c is None else dev(c), R)
+    assert abs(ctx.game_gap(dev(zs), ad, bd, game.mu, dev(zs), 1.0)) <= 1e-6 * d * 1e-3
+    with pytest.raises(qgx.QgxError):
+        ctx.game_gap(dev(z), ad, bd, 0.0, None, 1.0)
     ctx.close()
 
 
