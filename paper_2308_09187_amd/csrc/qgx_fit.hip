@@ -317,23 +317,29 @@ hipError_t launch_histogram(const Layout& lay, const float* V, int norm_kind, ui
 // has dG/dx = (c - a) * density(x), so G(x) = (c - a) * mass(a, x) - int_a^c (c - u) dF~: the level goes
 // where the mass between a and x reaches  t = int_a^c (c - u) dF~ / (c - a).  Where that holds on a
 // whole interval (no mass there) the smallest such x is taken; with no mass at all between the
-// neighbours that is a.  Every update is rounded to binary32, the precision of the table, at once:
-// a level next to the edge of the data's support then sits on the bin edge itself, and whether any
-// mass lies between two levels does not hang on the last bits of a binary64 intermediate.
+// neighbours that is a.  Levels stay in binary64 between the sweeps and are rounded to the table's
+// binary32 once, at the end.
 //
 // Everything is summed from a onwards, non-negative terms only (a difference of cumulative sums taken
 // from 0 would lose a sliver of mass next to a level against the total).  A two-level tree over the bins
 // keeps that short: nodes of 16 and 256 bins hold their mass and their moment about their own right
 // edge, rho = sum H_b (edge - mid_b), so that int (c - u) dF~ over a node is (c - edge) * mass + rho.
+// The whole bins between a and c are then at most five runs of at most 16 items: bins up to a multiple
+// of 16, nodes of 16 up to a multiple of 256, nodes of 256, and down again.  One update is the work of a
+// row of 16 lanes, a lane per item of a run: the integral is one sum across the row, and the place where
+// the mass reaches t is found with a prefix sum across the row per run, then inside the node that holds
+// it, a level of the tree at a time.
 
 struct Tree {
     const double* H;      // LDS [n_bins]
     const double* m1;     // [n_bins / 16] mass of a node of 16 bins
     const double* r1;     // its moment about its right edge
-    const double* m2;     // [n_bins / 256] the same for the complete nodes of 256 bins
+    const double* m2;     // [n_bins / 256] the same for the nodes of 256 bins
     const double* r2;
     uint32_t n_bins;
 };
+
+constexpr uint32_t kRow = 16;     // lanes per update
 
 __device__ uint32_t bin_containing(uint32_t n_bins, double x)
 {
@@ -343,16 +349,51 @@ __device__ uint32_t bin_containing(uint32_t n_bins, double x)
     return b;
 }
 
-// The largest aligned node that starts at bin p, ends at or before bin q and is at most of level cap
-// (0: a bin, 1: 16 bins, 2: 256 bins).
-__device__ __forceinline__ uint32_t node_level(uint32_t p, uint32_t q, uint32_t cap)
+// x of another lane of the row, by a DPP control word; lanes without a source read 0
+template <int CTRL>
+__device__ __forceinline__ double row_dpp(double x)
 {
-    if (cap >= 2u && (p & 255u) == 0u && p + 256u <= q) return 2u;
-    if (cap >= 1u && (p & 15u) == 0u && p + 16u <= q) return 1u;
-    return 0u;
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), CTRL, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), CTRL, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
 }
 
-// Right edge of the last bin with mass in [first, last], or `fallback` if none has any.
+// The sum over the row, the same bits in all its lanes: mirror, mirror within eight, swap pairs, swap
+// neighbours; at every step the two lanes of a pair add the same two numbers.
+__device__ __forceinline__ double row_sum(double x)
+{
+    x += row_dpp<0x140>(x);      // row_mirror
+    x += row_dpp<0x141>(x);      // row_half_mirror
+    x += row_dpp<0x4E>(x);       // quad_perm [2,3,0,1]
+    x += row_dpp<0xB1>(x);       // quad_perm [1,0,3,2]
+    return x;
+}
+
+// inclusive prefix sum over the lanes of the row (row_shr by 1, 2, 4, 8; nothing is shifted in from outside)
+__device__ __forceinline__ double row_scan(double x, uint32_t)
+{
+    x += row_dpp<0x111>(x);
+    x += row_dpp<0x112>(x);
+    x += row_dpp<0x114>(x);
+    x += row_dpp<0x118>(x);
+    return x;
+}
+
+// first lane of this row with the predicate set, kRow if none
+__device__ __forceinline__ uint32_t row_first(bool pred)
+{
+    const unsigned long long b = __ballot(pred);
+    const uint32_t mine = (uint32_t)(b >> (threadIdx.x & 48u)) & 0xFFFFu;
+    return mine ? (uint32_t)__ffs((int)mine) - 1u : kRow;
+}
+
+// mass of item idx of a level of the tree (0: a bin, 1: 16 bins, 2: 256 bins)
+__device__ __forceinline__ double item_mass(const Tree& T, uint32_t lvl, uint32_t idx)
+{
+    return lvl == 2u ? T.m2[idx] : lvl == 1u ? T.m1[idx] : T.H[idx];
+}
+
+// Right edge of the last bin with mass in [first, last_plus_1), or `fallback` if none has any.
 __device__ double last_mass_edge(const Tree& T, uint32_t first, uint32_t last_plus_1, double fallback)
 {
     for (uint32_t b = last_plus_1; b > first; --b)
@@ -360,12 +401,13 @@ __device__ double last_mass_edge(const Tree& T, uint32_t first, uint32_t last_pl
     return fallback;
 }
 
+// All 16 lanes of a row call this with the same a and c and get the same x.
 __device__ double stationary_point(const Tree& T, double a, double c)
 {
     if (!(c > a)) return a;
-    const uint32_t nb = T.n_bins;
+    const uint32_t nb = T.n_bins, li = threadIdx.x & (kRow - 1u);
     const uint32_t ba = bin_containing(nb, a), bc = bin_containing(nb, c);
-    // the pieces of the bins that hold a and c, and the whole bins ba + 1 .. bc - 1 between them
+    // the pieces of the bins that hold a and c, and the whole bins P .. Q - 1 between them
     const double a_e0 = bin_edge(ba, nb), a_e1 = bin_edge(ba + 1u, nb);
     const double a_hi = c < a_e1 ? c : a_e1;
     const double m_a = T.H[ba] * (a_hi - a) / (a_e1 - a_e0);
@@ -374,63 +416,99 @@ __device__ double stationary_point(const Tree& T, double a, double c)
         c_e0 = bin_edge(bc, nb);
         m_c = T.H[bc] * (c - c_e0) / (bin_edge(bc + 1u, nb) - c_e0);
     }
-    // int_a^c (c - u) dF~
-    double right_all = m_a * (c - 0.5 * (a + a_hi));
-    for (uint32_t p = ba + 1u; p < bc;) {
-        const uint32_t lvl = node_level(p, bc, 2u);
-        if (lvl == 2u) { right_all += (c - bin_edge(p + 256u, nb)) * T.m2[p >> 8] + T.r2[p >> 8]; p += 256u; }
-        else if (lvl == 1u) { right_all += (c - bin_edge(p + 16u, nb)) * T.m1[p >> 4] + T.r1[p >> 4]; p += 16u; }
-        else { const double e1 = bin_edge(p + 1u, nb); right_all += T.H[p] * (c - 0.5 * (bin_edge(p, nb) + e1)); p += 1u; }
+    const uint32_t P = ba + 1u, Q = bc > P ? bc : P;
+    // runs: bins [P, P1), nodes of 16 [p1, p2), nodes of 256 [p2 / 16, q2 / 16), nodes of 16 [q2, q1), bins [Q1, Q)
+    const uint32_t up = (P + 15u) & ~15u;
+    const uint32_t P1 = Q < up ? Q : up;
+    const uint32_t dn = Q & ~15u;
+    const uint32_t Q1 = dn > P1 ? dn : P1;
+    const uint32_t p1 = P1 >> 4, q1 = Q1 >> 4;                 // equal when no whole node of 16 lies between
+    const uint32_t up1 = (p1 + 15u) & ~15u;
+    const uint32_t p2 = q1 < up1 ? q1 : up1;
+    const uint32_t dn1 = q1 & ~15u;
+    const uint32_t q2 = dn1 > p2 ? dn1 : p2;
+    const uint32_t lo[5] = {P, p1, p2 >> 4, q2, Q1}, hi[5] = {P1, p2, p2 < q2 ? q2 >> 4 : p2 >> 4, q1, Q};
+    const uint32_t lvl[5] = {0u, 1u, 2u, 1u, 0u};
+    double m[5], rho = 0.0;
+#pragma unroll
+    for (int s = 0; s < 5; ++s) {
+        const uint32_t idx = lo[s] + li;
+        m[s] = 0.0;
+        if (idx < hi[s]) {
+            m[s] = item_mass(T, lvl[s], idx);
+            if (lvl[s] == 0u) rho += m[s] * (c - 0.5 * (bin_edge(idx, nb) + bin_edge(idx + 1u, nb)));
+            else if (lvl[s] == 1u) rho += (c - bin_edge(16u * idx + 16u, nb)) * m[s] + T.r1[idx];
+            else rho += (c - bin_edge(256u * idx + 256u, nb)) * m[s] + T.r2[idx];
+        }
     }
-    right_all += m_c * (c - 0.5 * (c_e0 + c));
+    // int_a^c (c - u) dF~
+    const double right_all = m_a * (c - 0.5 * (a + a_hi)) + row_sum(rho) + m_c * (c - 0.5 * (c_e0 + c));
     if (!(right_all > 0.0)) return a;                                  // no mass between the neighbours
     const double t = right_all / (c - a);
     // the smallest x with mass(a, x) >= t
-    double acc = 0.0, x;
-    if (acc + m_a >= t) {
-        x = a + (t - acc) / m_a * (a_hi - a);
-    } else {
-        acc += m_a;
-        bool found = false, inside = false;
-        uint32_t cap = 2u, q = bc;
-        uint32_t p = ba + 1u;
-        while (p < q) {
-            const uint32_t lvl = node_level(p, q, cap);
-            const double m = lvl == 2u ? T.m2[p >> 8] : lvl == 1u ? T.m1[p >> 4] : T.H[p];
-            if (acc + m >= t) {                                        // it is reached inside this node
-                if (lvl == 0u) {
-                    const double e0 = bin_edge(p, nb);
-                    x = e0 + (t - acc) / m * (bin_edge(p + 1u, nb) - e0);
-                    found = true;
-                    break;
-                }
-                q = p + (lvl == 2u ? 256u : 16u);
-                cap = lvl - 1u;
-                inside = true;
-            } else {
-                acc += m;
-                p += lvl == 2u ? 256u : lvl == 1u ? 16u : 1u;
-            }
-        }
-        if (!found) {
-            if (!inside && m_c > 0.0) {
-                x = c_e0 + (t - acc) / m_c * (c - c_e0);
-            } else {
-                // a node's mass reached t and the sum of its parts, rounded otherwise, did not (or t is a
-                // rounding above all the mass): the answer is where the mass seen so far ends
-                x = last_mass_edge(T, ba + 1u, q, m_a > 0.0 ? a_hi : a);
-            }
+    if (m_a >= t) return fmin(fmax(a + t / m_a * (a_hi - a), a), c);
+    // the runs' prefix sums side by side, then each run's mass on top of the runs before it
+    double cum[5], base[6];
+#pragma unroll
+    for (int s = 0; s < 5; ++s) cum[s] = row_scan(m[s], li);
+    base[0] = m_a;
+#pragma unroll
+    for (int s = 0; s < 5; ++s) {
+        cum[s] += base[s];
+        base[s + 1] = __shfl(cum[s], (int)kRow - 1, (int)kRow);
+    }
+    double acc = base[5], prev = 0.0;
+    uint32_t at_lvl = 0u, at_idx = 0u;
+    bool found = false;
+#pragma unroll
+    for (int s = 0; s < 5; ++s) {
+        const uint32_t first = row_first(lo[s] + li < hi[s] && cum[s] >= t);
+        if (!found && first < kRow) {
+            found = true;
+            at_lvl = lvl[s];
+            at_idx = lo[s] + first;
+            const double before = __shfl(cum[s], (int)(first > 0u ? first - 1u : 0u), (int)kRow);
+            prev = first > 0u ? before : base[s];
         }
     }
-    x = fmin(fmax(x, a), c);
-    return x;
+    double x;
+    if (!found) {
+        // the mass reaches t in the piece of c's bin, or t is a rounding above all the mass: then the answer
+        // is where the mass ends
+        x = m_c > 0.0 ? c_e0 + (t - acc) / m_c * (c - c_e0) : last_mass_edge(T, P, Q, m_a > 0.0 ? a_hi : a);
+    } else {
+        const uint32_t node_end = at_lvl == 2u ? 256u * at_idx + 256u : at_lvl == 1u ? 16u * at_idx + 16u : at_idx + 1u;
+        bool lost = false;
+        while (at_lvl > 0u && !lost) {                                 // into the node that holds it
+            const uint32_t child = 16u * at_idx + li;
+            const double cum = prev + row_scan(item_mass(T, at_lvl - 1u, child), li);
+            const uint32_t first = row_first(cum >= t);
+            if (first < kRow) {
+                const double before = __shfl(cum, (int)(first > 0u ? first - 1u : 0u), (int)kRow);
+                prev = first > 0u ? before : prev;
+                at_idx = 16u * at_idx + first;
+                at_lvl -= 1u;
+            } else {
+                lost = true;       // the node's mass reached t and the sum of its parts, rounded otherwise, did not
+            }
+        }
+        if (lost) {
+            x = last_mass_edge(T, P, node_end, m_a > 0.0 ? a_hi : a);
+        } else {
+            const double e0 = bin_edge(at_idx, nb);
+            x = e0 + (t - prev) / T.H[at_idx] * (bin_edge(at_idx + 1u, nb) - e0);
+            x = fmax(x, e0);
+        }
+    }
+    return fmin(fmax(x, a), c);
 }
 
 // The sweeps update level j from the new l_{j-1} and the old l_{j+1}, one level after the other.
 // Update (sweep s, level j) therefore only waits for (s, j-1) and (s-1, j+1), and all updates with
-// the same 2s + j can run together: lane s of one wave carries sweep s, two levels behind lane s-1,
-// and takes its upper neighbour from that lane's previous step.  Same arithmetic, same order, same
-// result as the plain double loop, in 2 sweeps + n_sym steps instead of sweeps * n_sym.
+// the same 2s + j can run together: row s of the workgroup's 16 rows of 16 lanes carries sweep s, two
+// levels behind row s-1, and takes its upper neighbour from what that row left in LDS one step ago.
+// Same updates in the same order as the plain double loop, in 2 sweeps + n_sym steps instead of
+// sweeps * n_sym.
 __global__ __launch_bounds__(256) void k_fit(Tables* tab, const double* __restrict__ hist, uint32_t n_bins,
                                              uint32_t sweeps)
 {
@@ -439,6 +517,8 @@ __global__ __launch_bounds__(256) void k_fit(Tables* tab, const double* __restri
     __shared__ double s_m1[QGX_MAX_BINS / 16], s_r1[QGX_MAX_BINS / 16];
     __shared__ double s_m2[QGX_MAX_BINS / 256], s_r2[QGX_MAX_BINS / 256];
     __shared__ double s_lev[kSymMax + 1];                         // the table between passes
+    __shared__ double s_moved[2][kRow];                           // what each row moved in the last two steps
+    __shared__ double s_total;
 
     const uint32_t tid = threadIdx.x;
     for (uint32_t b = tid; b < n_bins; b += 256u) H[b] = hist[b];
@@ -454,10 +534,13 @@ __global__ __launch_bounds__(256) void k_fit(Tables* tab, const double* __restri
         s_m1[tid] = m; s_r1[tid] = r;
     }
     __syncthreads();
-    if (tid < n2) {
-        const double edge = bin_edge(256u * tid + 256u, n_bins);
+    // the last node of 256 is short when n_bins is not a multiple of 256: nothing reads it then (a run of
+    // nodes of 256 only holds whole ones), but its slot is written all the same
+    if (tid < (n_bins + 255u) >> 8) {
+        const uint32_t last = min(16u * tid + 16u, n1);
+        const double edge = bin_edge(16u * last, n_bins);
         double m = 0.0, r = 0.0;
-        for (uint32_t i = 16u * tid; i < 16u * tid + 16u; ++i) {
+        for (uint32_t i = 16u * tid; i < last; ++i) {
             m += s_m1[i];
             r += (edge - bin_edge(16u * i + 16u, n_bins)) * s_m1[i] + s_r1[i];
         }
@@ -465,36 +548,42 @@ __global__ __launch_bounds__(256) void k_fit(Tables* tab, const double* __restri
     }
     const uint32_t n_sym = tab->n_sym;
     if (tid < n_sym) s_lev[tid] = (double)tab->levels[tid];
+    if (tid == 0) {
+        double total = 0.0;
+        for (uint32_t i = 0; i < n1; ++i) total += s_m1[i];
+        s_total = total;
+    }
     __syncthreads();
-    if (tid >= (uint32_t)kWave) return;
+    (void)n2;
 
     const Tree T = {H, s_m1, s_r1, s_m2, s_r2, n_bins};
-    const uint32_t lane = tid, top = n_sym - 1u;
-    double total = 0.0;
-    for (uint32_t i = 0; i < n1; ++i) total += s_m1[i];
-    if (total > 0.0 && n_sym > 2u) {
-        for (uint32_t first = 0; first < sweeps; first += (uint32_t)kWave) {
-            const uint32_t ns = min((uint32_t)kWave, sweeps - first);    // sweeps of this pass, one per lane
-            double mine = 0.0;                      // the level this lane moved in its last step
+    const uint32_t row = tid >> 4, top = n_sym - 1u;
+    if (s_total > 0.0 && n_sym > 2u) {
+        for (uint32_t first = 0; first < sweeps; first += kRow) {
+            const uint32_t ns = min(kRow, sweeps - first);               // sweeps of this pass, one per row
+            double mine = 0.0;                      // the level this row moved in its last step
             const uint32_t steps = 2u * (ns - 1u) + (top - 1u);
             for (uint32_t t = 1; t <= steps; ++t) {
-                // the lane below moved level j + 1 one step ago
-                double above = __shfl_up(mine, 1, kWave);
-                const int j = (int)t - 2 * (int)lane;
-                const bool active = lane < ns && j >= 1 && j < (int)top;
+                const int j = (int)t - 2 * (int)row;
+                const bool active = row < ns && j >= 1 && j < (int)top;
                 if (active) {
-                    if (lane == 0) above = s_lev[j + 1];
+                    // the row below moved level j + 1 one step ago; the first row reads the table of the last pass
+                    double above = row == 0u ? s_lev[j + 1] : s_moved[(t - 1u) & 1u][row - 1u];
                     if (j + 1 == (int)top) above = 1.0;
                     const double below = j == 1 ? 0.0 : mine;
                     mine = stationary_point(T, below, above);
-                    if (lane == ns - 1u) s_lev[j] = mine;
+                    if ((tid & (kRow - 1u)) == 0u) {
+                        s_moved[t & 1u][row] = mine;
+                        if (row == ns - 1u) s_lev[j] = mine;
+                    }
                 }
+                __syncthreads();
             }
         }
     }
     // strictly increasing with gaps of at least 2^-24: up from l_0 = 0, then down from l_s = 1; one
     // lane, the table is short
-    if (lane == 0) {
+    if (tid == 0) {
         float* lv = tab->levels;
         lv[0] = 0.0f; lv[top] = 1.0f;
         for (uint32_t j = 1; j < top; ++j) {
