@@ -644,15 +644,17 @@ __global__ __launch_bounds__(256) void k_fit_code(Tables* tab, const double* __r
     }
     const double total = s_part[0];
 
-    if (tid < n) {
+    // p_j: a row of 16 lanes per level, every lane each 16th bin under the two gaps next to the level
+    for (uint32_t j = tid >> 4; j < ((n + 15u) & ~15u); j += 16u) {        // whole rows walk together
+        const uint32_t li = tid & 15u;
         double acc = 0.0;
-        if (total > 0.0) {
+        if (j < n && total > 0.0) {
             for (int side = 0; side < 2; ++side) {                         // 0: gap below (rising), 1: gap above (falling)
-                if ((side == 0 && tid == 0) || (side == 1 && tid + 1 >= n)) continue;
-                const double a = side == 0 ? s_lev[tid - 1] : s_lev[tid], c = side == 0 ? s_lev[tid] : s_lev[tid + 1];
+                if ((side == 0 && j == 0) || (side == 1 && j + 1 >= n)) continue;
+                const double a = side == 0 ? s_lev[j - 1] : s_lev[j], c = side == 0 ? s_lev[j] : s_lev[j + 1];
                 uint32_t b = bin_of((float)a, n_bins);
                 while (b > 0 && bin_edge(b, n_bins) > a) --b;
-                for (; b < n_bins; ++b) {
+                for (b += li; b < n_bins; b += 16u) {
                     const double e0 = bin_edge(b, n_bins), e1 = bin_edge(b + 1, n_bins);
                     if (e0 >= c) break;
                     const double lo = a > e0 ? a : e0, hi = c < e1 ? c : e1;
@@ -662,11 +664,14 @@ __global__ __launch_bounds__(256) void k_fit_code(Tables* tab, const double* __r
                     acc += side == 0 ? mass * up : mass * (1.0 - up);
                 }
             }
-            acc /= total;
         }
-        p_out[tid] = acc;
-        const double x = floor(acc * 4294967296.0 + 0.5);
-        s_w[tid] = x >= 1.0 ? (unsigned long long)x : 1ull;
+        acc = row_sum(acc);
+        if (j < n && li == 0u) {
+            if (total > 0.0) acc /= total;
+            p_out[j] = acc;
+            const double x = floor(acc * 4294967296.0 + 0.5);
+            s_w[j] = x >= 1.0 ? (unsigned long long)x : 1ull;
+        }
     }
     __syncthreads();
     if (tid != 0) return;
