@@ -354,8 +354,10 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
         const uint32_t k = k_first + kk;
         const SubMeta cur = nxt, prv = nxt_p;
         if constexpr (!kAhead) prefetch_chunk(cr, pre);
+        wave_lds_fence();                                     // the last worker's windows have been read
         commit_chunk<kLead>(stage, pre, stage_words);
         if constexpr (PREV) commit_chunk<kLead>(stage_p, pre_p, stage_words);
+        wave_lds_fence();                                     // a lane parses words that other lanes stored
         if (kk + 1 < k_count) {
             cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, a.sub_end, k + 1, c, lay.NC, stage_words, sc);
             nxt = load_meta(a.sub_end, a.norms, k + 1, c, bkt, lay, lane);
@@ -520,24 +522,36 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
             if (lane == 0) a.s_partial[c] = sdiff;
         }
     }
-    // Lane L holds coordinates 64L..64L+63 of the chunk.  Through LDS, 16 symbols at a time, the
-    // wave turns them so that four consecutive lanes own 16 consecutive floats: global accesses
-    // then touch whole 64-byte pieces instead of 16 bytes per 256.
+    // Lane L holds coordinates 64L..64L+63 of the chunk.  Through LDS the wave turns them, a quarter of them
+    // at a time, so that neighbouring lanes own consecutive floats and global accesses touch whole pieces
+    // of kPiece floats instead of 16 bytes per 256.  Where the output is another array than the one read
+    // (the first half-step, the plain average) a piece is a whole 128-byte line, from the 32 lanes of one
+    // half of the wave and 32 of their symbols: with pieces of 64 bytes the cache fetched the other half of
+    // every output line that it did not hold, a sixth more traffic for the launch.  The second half-step
+    // updates Y in place, the line is there when it is written, and pieces of 64 bytes from all 64 lanes
+    // and 16 of their symbols are the quicker turn.
     // KSPLIT: all waves of the group put their sums there, and after a barrier each of them adds them
     // up (in the order of the workers' runs) for its share of the rows and does the update for those.
-    float* tr = reinterpret_cast<float*>(stage);          // 64 rows of 20 floats (16 + pad), 5120 bytes
+    constexpr int kPiece = MODE == DecMode::Half1 ? 16 : 32;   // floats of a row per pass
+    constexpr int kPitch = kPiece + 4;                          // 64 rows of 20 floats or 32 rows of 36: at most 5120 bytes
+    constexpr int kRowLanes = kPiece / 4;                       // lanes that read a row, a float4 each
+    constexpr int kRowsPerRead = kWave / kRowLanes;
+    float* tr = reinterpret_cast<float*>(stage);
     const float* tr0 = KSPLIT > 1 ? reinterpret_cast<const float*>(s_dyn + (size_t)(w - part) * kBufs * stage_stride) : tr;
     const size_t tr_step = (size_t)kBufs * stage_stride;  // from one wave's buffer to the next, in words
     const float scale = KSPLIT > 1 ? 1.0f : invK;         // KSPLIT: the division comes after the group's sum
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        if (mine) {
+        const int first_lane = kPiece == 32 ? 32 * (q >> 1) : 0;    // the lanes whose symbols this pass turns
+        const int first_sym = kPiece == 32 ? 32 * (q & 1) : 16 * q;  // ... and which of their symbols
+        if (mine && (kPiece == 16 || (lane >> 5) == (q >> 1))) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                *reinterpret_cast<float4*>(tr + lane * 20 + 4 * j) =
-                    make_float4(acc[16 * q + 4 * j] * scale, acc[16 * q + 4 * j + 1] * scale,
-                                acc[16 * q + 4 * j + 2] * scale, acc[16 * q + 4 * j + 3] * scale);
+            for (int j = 0; j < kRowLanes; ++j)
+                *reinterpret_cast<float4*>(tr + (lane - first_lane) * kPitch + 4 * j) =
+                    make_float4(acc[first_sym + 4 * j] * scale, acc[first_sym + 4 * j + 1] * scale,
+                                acc[first_sym + 4 * j + 2] * scale, acc[first_sym + 4 * j + 3] * scale);
         }
+        wave_lds_fence();                                     // the rows are read by other lanes than wrote them
         if constexpr (KSPLIT > 1) {
             __syncthreads();
             if (MODE == DecMode::Half1 && q == 0 && mine && part == 0 && lane == 0) {
@@ -548,19 +562,19 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            if (KSPLIT > 1 && i * KSPLIT / 4 != part) continue;   // 64 / KSPLIT rows for each wave of the group
+            if (KSPLIT > 1 && i * KSPLIT / 4 != part) continue;   // a share of the rows for each wave of the group
             if (!mine) continue;
-            const int row = (lane >> 2) + 16 * i;             // whose 16 symbols
-            float4 m = *reinterpret_cast<const float4*>(tr0 + row * 20 + 4 * (lane & 3));
+            const int row = lane / kRowLanes + kRowsPerRead * i, col = lane % kRowLanes;
+            float4 m = *reinterpret_cast<const float4*>(tr0 + row * kPitch + 4 * col);
             if constexpr (KSPLIT > 1) {
 #pragma unroll
                 for (int j = 1; j < KSPLIT; ++j) {
-                    const float4 h = *reinterpret_cast<const float4*>(tr0 + j * tr_step + row * 20 + 4 * (lane & 3));
-                    m.x += h.x; m.y += h.y; m.z += h.z; m.w += h.w;
+                    const float4 h4 = *reinterpret_cast<const float4*>(tr0 + j * tr_step + row * kPitch + 4 * col);
+                    m.x += h4.x; m.y += h4.y; m.z += h4.z; m.w += h4.w;
                 }
                 m.x *= invK; m.y *= invK; m.z *= invK; m.w *= invK;
             }
-            const uint32_t at = clo + 64u * (uint32_t)row + 16u * (uint32_t)q + 4u * (uint32_t)(lane & 3);
+            const uint32_t at = clo + 64u * (uint32_t)(first_lane + row) + (uint32_t)first_sym + 4u * (uint32_t)col;
             if (MODE == DecMode::Average) {
                 *reinterpret_cast<float4*>(a.out + at) = m;
             } else if (MODE == DecMode::Half0) {
@@ -584,6 +598,7 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
                 *reinterpret_cast<float4*>(a.Y + at) = y;
             }
         }
+        wave_lds_fence();                                     // ... and written again in the next pass
         if constexpr (KSPLIT > 1) {
             if (q < 3) __syncthreads();                       // the partners have read this quarter
         }
@@ -662,6 +677,7 @@ void k_decode_ragged(Layout lay, const Tables* __restrict__ tab, Scalars* sc, De
                 prv = load_meta(a.sub_end_p, a.norms_p, k, c, bkt, lay, lane);
                 commit_chunk(stage_p, pre, stage_words);
             }
+            wave_lds_fence();                                 // a lane parses words that other lanes stored
             uint32_t p = cur.p0, pb = cur.p_mid, pp = prv.p0, ppb = prv.p_mid;
             if (p > p_limit) { p = p_limit; malformed = true; }
             if (pb > p_limit) { pb = p_limit; malformed = true; }

@@ -72,6 +72,17 @@ __device__ __forceinline__ float4 game_dual_row(const GameArgs& G, uint32_t i0, 
     return v;
 }
 
+// Between two phases in which the lanes of a wave exchange data through LDS without a workgroup barrier.
+// The hardware runs a wave's LDS instructions in the order they were issued; this keeps the compiler from
+// moving them across the boundary, or from making one side of the exchange part of a branch that only
+// some lanes take.  No instruction is emitted.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // Inclusive prefix sum over the 64 lanes of a wave with DPP row shifts and row broadcasts: four
 // shifted adds inside each row of 16 lanes, then lane 15 of a row into the next row, then lane 31
 // into the upper half.

@@ -730,6 +730,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
                 } else {
                     uint4* __restrict__ dst = reinterpret_cast<uint4*>(a.payload + (size_t)k * a.cap_words + off);
                     uint4* src = reinterpret_cast<uint4*>(stage);
+                    wave_lds_fence();                          // a lane stores words that all lanes' codes went into
                     for (uint32_t q = (uint32_t)lane; q < (words >> 2); q += kWave) dst[q] = src[q];
                 }
             }
