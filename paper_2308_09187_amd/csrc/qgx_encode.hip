@@ -504,6 +504,7 @@ void k_encode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, EncodeArg
         if constexpr (GROUPED) {
             if (MODE != EncMode::EncodeOnly && g.clen != 0u)
                 plain = shared_chunk_norms<MODE>(v, Vk, g, lay, a, sc, k, b, s_rinv + w * 16, lane);
+            wave_lds_fence();                              // lane 0 left the buckets' 1 / norm for all lanes
         } else if (MODE != EncMode::EncodeOnly) {
             // A non-finite coordinate shows in the reduced value itself (a sum of squares with a NaN
             // or an infinity in it, a maximum taken on magnitude bits).

@@ -236,6 +236,7 @@ __global__ __launch_bounds__(256) void k_histogram_small(Layout lay, const float
             }
         }
         const double wgt = (double)n * (double)n;         // lambda of Section 3.3, unnormalised
+        wave_lds_fence();                                 // the counts a lane folds hold other lanes' additions
         for (int turn = 0; turn < kW; ++turn) {
             if (turn == w && usable) {
 #pragma unroll
