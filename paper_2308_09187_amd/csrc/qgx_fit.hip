@@ -27,9 +27,15 @@ __device__ __forceinline__ double bin_edge(uint32_t b, uint32_t n_bins)
     return (double)__uint_as_float((uint32_t)((int)b + (127 * 64 - (int)n_bins)) << 17);
 }
 
-__global__ __launch_bounds__(1024) void k_histogram(Layout lay, const float* __restrict__ V, int norm_kind,
-                                                    uint32_t n_bins, double* __restrict__ partial, Scalars* sc)
+// A workgroup walks its buckets one after the other, each in three phases divided by barriers (norm, count,
+// fold), and a compute unit holds only two or three such workgroups (LDS): nothing hides a phase's
+// latency but the next bucket's rows, so with buckets of at most four chunks those are loaded into a
+// second set of registers before the current bucket is worked on.
+template <int MAXW>
+__global__ __launch_bounds__(MAXW * kWave) void k_histogram(Layout lay, const float* __restrict__ V, int norm_kind,
+                                                            uint32_t n_bins, double* __restrict__ partial, Scalars* sc)
 {
+    constexpr bool kAhead = MAXW <= 4;                                   // registers for a second bucket's rows
     extern __shared__ __align__(16) unsigned char s_raw[];
     double* s_acc = reinterpret_cast<double*>(s_raw);                    // [n_bins]
     uint32_t* s_cnt = reinterpret_cast<uint32_t*>(s_acc + n_bins);       // [n_bins]
@@ -42,16 +48,15 @@ __global__ __launch_bounds__(1024) void k_histogram(Layout lay, const float* __r
     __syncthreads();
 
     const uint32_t n_work = lay.K * lay.NB;
-    for (uint32_t t = blockIdx.x; t < n_work; t += gridDim.x) {
+    // the rows of this wave's chunk of unit t (bucket t / K of worker t % K), zeros past the bucket's end
+    auto load_rows = [&](uint32_t t, float4 (&v)[kRows]) {
         const uint32_t b = t / lay.K, k = t - b * lay.K;
         const uint32_t lo = lay.bucket_start[b], hi = lay.bucket_start[b + 1];
         const uint32_t clo = lo + (uint32_t)w * kChunk;
-        const uint32_t clen = clo < hi ? min((uint32_t)kChunk, hi - clo) : 0u;
-        const uint32_t cend = clo + clen;
+        const uint32_t cend = clo < hi ? clo + min((uint32_t)kChunk, hi - clo) : clo;
         const size_t kbase = (size_t)k * lay.d;
         const bool vec_ok = (kbase & 3u) == 0;
         const float* __restrict__ Vk = V + kbase;
-        float4 v[kRows];
 #pragma unroll
         for (int r = 0; r < kRows; ++r) {
             const uint32_t i0 = clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
@@ -65,6 +70,24 @@ __global__ __launch_bounds__(1024) void k_histogram(Layout lay, const float* __r
                 if (i0 + 2 < cend) x.z = Vk[i0 + 2];
             }
             v[r] = x;
+        }
+    };
+    float4 v[kRows], v_next[kAhead ? kRows : 1];
+    if constexpr (kAhead) {
+        if (blockIdx.x < n_work) load_rows(blockIdx.x, v);
+    }
+    for (uint32_t t = blockIdx.x; t < n_work; t += gridDim.x) {
+        const uint32_t b = t / lay.K, k = t - b * lay.K;
+        const uint32_t lo = lay.bucket_start[b], hi = lay.bucket_start[b + 1];
+        const uint32_t clo = lo + (uint32_t)w * kChunk;
+        const uint32_t clen = clo < hi ? min((uint32_t)kChunk, hi - clo) : 0u;
+        const uint32_t cend = clo + clen;
+        const size_t kbase = (size_t)k * lay.d;
+        const float* __restrict__ Vk = V + kbase;
+        if constexpr (kAhead) {
+            if (t + gridDim.x < n_work) load_rows(t + gridDim.x, v_next);
+        } else {
+            load_rows(t, v);
         }
         double acc = 0.0;
         float mx = 0.0f;
@@ -135,6 +158,10 @@ __global__ __launch_bounds__(1024) void k_histogram(Layout lay, const float* __r
             }
         }
         __syncthreads();
+        if constexpr (kAhead) {
+#pragma unroll
+            for (int r = 0; r < kRows; ++r) v[r] = v_next[r];
+        }
     }
     for (uint32_t i = (uint32_t)tid; i < n_bins; i += blockDim.x)
         partial[(size_t)blockIdx.x * n_bins + i] = s_acc[i];
@@ -284,8 +311,10 @@ __global__ __launch_bounds__(256) void k_hist_reduce(uint32_t n_bins, uint32_t n
 
 uint32_t histogram_groups(const Layout& lay)
 {
+    // two workgroups per compute unit; three (what its LDS holds with 4096 bins) where a workgroup is a single wave
     const uint32_t n_work = lay.K * lay.NB;
-    return n_work < 512u ? n_work : 512u;
+    const uint32_t groups = (!lay.shared_chunks && lay.waves_per_bucket == 1u) ? 768u : 512u;
+    return n_work < groups ? n_work : groups;
 }
 
 hipError_t launch_histogram(const Layout& lay, const float* V, int norm_kind, uint32_t n_bins, double* partial,
@@ -301,8 +330,12 @@ hipError_t launch_histogram(const Layout& lay, const float* V, int norm_kind, ui
         }
     } else {
         const size_t lds = (size_t)n_bins * (sizeof(double) + sizeof(uint32_t));
-        hipLaunchKernelGGL(k_histogram, dim3(n_partial), dim3(lay.waves_per_bucket * kWave), lds, st, lay, V, norm_kind,
-                           n_bins, partial, sc);
+        if (lay.waves_per_bucket <= 4u)
+            hipLaunchKernelGGL(k_histogram<4>, dim3(n_partial), dim3(lay.waves_per_bucket * kWave), lds, st, lay, V, norm_kind,
+                               n_bins, partial, sc);
+        else
+            hipLaunchKernelGGL(k_histogram<kMaxWaves>, dim3(n_partial), dim3(lay.waves_per_bucket * kWave), lds, st, lay, V,
+                               norm_kind, n_bins, partial, sc);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
