@@ -52,8 +52,10 @@ MUTANTS = [
     ("bins half an octave off", "const int64_t key = (int64_t)(bits >> 17) - ((int64_t)127 * 64 - (int64_t)n_bins);",
      "const int64_t key = (int64_t)(bits >> 17) - ((int64_t)127 * 64 - (int64_t)n_bins) - 32;", [F]),
     ("the next word of the Philox block", "out[i & 3]", "out[(i + 1) & 3]", [Q, R]),
-    ("draws that ignore the call", "ctr[3] = call_id;", "ctr[3] = 0;", [Q, R]),
-    ("draws that ignore the worker", "ctr[2] = k;", "ctr[2] = 0;", [Q, R]),
+    ("draws that ignore the call", "ctr[1] = (uint32_t)(blk >> 32); ctr[2] = k; ctr[3] = call_id;",
+     "ctr[1] = (uint32_t)(blk >> 32); ctr[2] = k; ctr[3] = 0;", [Q, R]),
+    ("draws that ignore the worker", "ctr[1] = (uint32_t)(blk >> 32); ctr[2] = k; ctr[3] = call_id;",
+     "ctr[1] = (uint32_t)(blk >> 32); ctr[2] = 0; ctr[3] = call_id;", [Q, R]),
     ("moment of a piece taken at its lower end", "const double piece_mid = 0.5 * (lo[p] + hi[p]);",
      "const double piece_mid = lo[p];", [F]),
     ("stationarity without its right-hand term", "const double G_lo = left[p] - right[p], G_hi = left[p + 1] - right[p + 1];",
