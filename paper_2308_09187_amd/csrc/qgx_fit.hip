@@ -661,7 +661,7 @@ __global__ __launch_bounds__(256) void k_fit_code(Tables* tab, const double* __r
     double* H = reinterpret_cast<double*>(s_raw);                      // [n_bins]
     __shared__ double s_part[256];
     __shared__ double s_lev[kSymMax];
-    __shared__ unsigned long long s_w[kSymMax], s_cur[2 * kSymMax], s_nxt[2 * kSymMax];
+    __shared__ unsigned long long s_w[kSymMax], s_sw[kSymMax], s_cur[2 * kSymMax], s_nxt[2 * kSymMax];
     __shared__ uint8_t s_pkg[kMaxCode][2 * kSymMax];
     __shared__ uint32_t s_count[kMaxCode];
     __shared__ uint8_t s_order[kSymMax], s_len[kSymMax];
@@ -708,54 +708,81 @@ __global__ __launch_bounds__(256) void k_fit_code(Tables* tab, const double* __r
         }
     }
     __syncthreads();
-    if (tid != 0) return;
 
-    // symbols by weight, then index (stable insertion sort)
-    for (uint32_t i = 0; i < n; ++i) s_order[i] = (uint8_t)i;
-    for (uint32_t i = 1; i < n; ++i) {
-        const uint8_t x = s_order[i];
-        uint32_t q = i;
-        while (q > 0 && s_w[s_order[q - 1]] > s_w[x]) { s_order[q] = s_order[q - 1]; --q; }
-        s_order[q] = x;
+    // Symbols by weight, then index: a symbol's place is the number of symbols that come before it.
+    if (tid < n) {
+        const unsigned long long wi = s_w[tid];
+        uint32_t rank = 0;
+        for (uint32_t k = 0; k < n; ++k) {
+            const unsigned long long wk = s_w[k];
+            rank += (wk < wi || (wk == wi && k < tid)) ? 1u : 0u;
+        }
+        s_order[rank] = (uint8_t)tid;
     }
+    __syncthreads();
+    if (tid < n) s_sw[tid] = s_w[s_order[tid]];
+    __syncthreads();
+    // Package-merge, a level per round: the list of a level is the merge of the n single symbols with the
+    // packages (pairs, in order) of the level above; at equal weight the single comes first.  Both lists are
+    // sorted, so an item's place is its own index plus the number of items of the other list before it
+    // (a binary search): a thread per item.
     unsigned long long* cur = s_cur;
     unsigned long long* nxt = s_nxt;
     uint32_t m = n;
-    for (uint32_t i = 0; i < n; ++i) { cur[i] = s_w[s_order[i]]; s_pkg[max_len - 1][i] = 0; }
-    s_count[max_len - 1] = m;
+    if (tid < n) { cur[tid] = s_sw[tid]; s_pkg[max_len - 1][tid] = 0; }
+    if (tid == 0) s_count[max_len - 1] = m;
+    __syncthreads();
     for (int l = (int)max_len - 2; l >= 0; --l) {
         const uint32_t n_pk = m >> 1;
-        uint32_t ia = 0, ib = 0, o = 0;
-        while (ia < n || ib < n_pk) {
-            const unsigned long long wa = ia < n ? s_w[s_order[ia]] : 0ull;
-            const unsigned long long wb = ib < n_pk ? cur[2 * ib] + cur[2 * ib + 1] : 0ull;
-            if (ib >= n_pk || (ia < n && wa <= wb)) { nxt[o] = wa; s_pkg[l][o] = 0; ++ia; }
-            else { nxt[o] = wb; s_pkg[l][o] = 1; ++ib; }
-            ++o;
+        if (tid < n) {                                   // single tid: after the packages that weigh less
+            const unsigned long long wa = s_sw[tid];
+            uint32_t lo = 0, hi = n_pk;                  // first package with weight >= wa
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (cur[2 * mid] + cur[2 * mid + 1] < wa) lo = mid + 1; else hi = mid;
+            }
+            nxt[tid + lo] = wa;
+            s_pkg[l][tid + lo] = 0;
+        } else if (tid - n < n_pk) {                     // package tid - n: after the singles that weigh no more
+            const uint32_t ib = tid - n;
+            const unsigned long long wb = cur[2 * ib] + cur[2 * ib + 1];
+            uint32_t lo = 0, hi = n;                     // first single with weight > wb
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (s_sw[mid] <= wb) lo = mid + 1; else hi = mid;
+            }
+            nxt[ib + lo] = wb;
+            s_pkg[l][ib + lo] = 1;
         }
-        m = o;
-        s_count[l] = m;
+        m = n + n_pk;
+        if (tid == 0) s_count[l] = m;
+        __syncthreads();
         unsigned long long* t = cur; cur = nxt; nxt = t;
     }
-    for (uint32_t i = 0; i < n; ++i) s_len[i] = 0;
+    // The 2 (n - 1) lightest items of the lowest level are taken; every single among the items taken at a
+    // level adds a bit to its symbol (the singles are the lightest symbols in order), every package sends
+    // its two parts of the level above.
+    if (tid < n) s_len[tid] = 0;
+    __syncthreads();
     uint32_t take = 2u * (n - 1u);
-    for (uint32_t l = 0; l < max_len && take > 0; ++l) {
+    for (uint32_t l = 0; l < max_len; ++l) {                           // (take falls to 0 and stays there)
         take = min(take, s_count[l]);
-        uint32_t singles = 0, packages = 0;
-        for (uint32_t i = 0; i < take; ++i) { if (s_pkg[l][i]) ++packages; else ++singles; }
-        for (uint32_t i = 0; i < singles; ++i) s_len[s_order[i]] += 1;
+        const uint32_t packages = (uint32_t)__syncthreads_count(tid < take && s_pkg[l][tid] != 0);
+        const uint32_t singles = take - packages;
+        if (tid < singles) s_len[s_order[tid]] += 1;
         take = 2u * packages;
     }
-    // canonical words; the table wants the first-written bit in bit 0
-    uint32_t code = 0, prev_len = 0;
-    for (uint32_t L = 1; L <= max_len; ++L) {
-        for (uint32_t i = 0; i < n; ++i) {
-            if (s_len[i] != L) continue;
-            code <<= (L - prev_len);
-            prev_len = L;
-            tab->code[i] = (__brev(code) >> (32u - L)) | (L << 16);
-            ++code;
+    __syncthreads();
+    // canonical words: the symbols in the order (length, index), each word the count of the words before it at
+    // its own length's scale; the table wants the first-written bit in bit 0
+    if (tid < n) {
+        const uint32_t L = s_len[tid];
+        uint32_t code = 0;
+        for (uint32_t k = 0; k < n; ++k) {
+            const uint32_t lk = s_len[k];
+            if (lk < L || (lk == L && k < tid)) code += 1u << (L - lk);
         }
+        tab->code[tid] = (__brev(code) >> (32u - L)) | (L << 16);
     }
 }
 
