@@ -319,7 +319,19 @@ def main():
         else:
             ctx.set_levels(synth.levels_exponential(args.n_sym - 1))
             ctx.fit_levels(V, args.n_sym, 4096, sweeps=10)
+            # what an update step of Algorithm 1 adds to its iteration (the fit is not part of the timed step):
+            # histogram, reduction, 10 sweeps from the table just fitted and the rebuild of the device tables
+            fitted = ctx.get_levels()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(5):
+                ctx.fit_levels(V, args.n_sym, 4096, sweeps=10)
+            torch.cuda.synchronize()
+            level_fit_ms = (time.perf_counter() - t0) * 1e3 / 5
+            ctx.set_levels(fitted)                                 # the workload's table is the one of the first fit
             what = "K=%d x d=2^%d Student-t(3)*1e-2, bucket %d, L2, %d-symbol fitted table" % (K, args.logd, args.bucket, args.n_sym)
+    if "level_fit_ms" not in locals():
+        level_fit_ms = None
     default_workload = (args.workload, args.logd, K, args.bucket, args.n_sym, args.code, args.placement) == \
                        ("t3", 24, 8, 16384, 33, "omega", "slotted")
     levels = ctx.get_levels()
@@ -461,6 +473,7 @@ def main():
                    "bits_per_coordinate": bits / float(K * d), "stream_bytes": stream_bytes},
         "hbm_frac_step": (enc_bytes + upd_bytes) / ((enc_ms + upd_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernels_ms": {"encode": enc_ms, "decode_avg_half0": upd_ms},
+        "level_fit_ms": level_fit_ms,      # per update step of Algorithm 1, outside the timed step (histogram, reduction, 10 sweeps, tables)
         "roofline": {"kernel": "k_encode<Fused, %s, %d>" % ("true" if args.bucket in (256, 512, 1024, 2048) else "false",
                                                             4 if args.n_sym <= 33 else 5 if args.n_sym <= 65 else 6),
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
