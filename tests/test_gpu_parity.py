@@ -980,7 +980,7 @@ def test_two_level_tables_lockstep(qgx, fitted_code, n0):
     ctx.close()
 
 
-@pytest.mark.parametrize("sweep,waves", [(1, None), (2, None), (1, 1), (2, 1), (3, 2)])
+@pytest.mark.parametrize("sweep,waves", [(1, None), (2, None), (1, 1), (2, 1), (3, 2), (4, None), (5, 4), (6, 1)])
 def test_random_configurations(qgx, monkeypatch, sweep, waves):
     """Seeded random layouts (bucket sizes of every kind, several tensors with ragged ends), worker
     counts, norms, level tables, codes and placements: streams bit for bit, decoded vectors exactly,
