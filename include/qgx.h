@@ -26,9 +26,8 @@
  *     their kernels take everything that changes between iterations (Y, S, gamma, t, the running
  *     sum and its count, the tags and ticket counters that order workgroups, and with
  *     QGX_CALL_FIRST_HALF / QGX_CALL_SECOND_HALF the call number) from device memory.  Run them once
- *     before capturing (the first launch of a kernel sets its attributes).  The second-half-step
- *     and decoding calls of a layout with short chunks use a side queue of the library's own beside
- *     `stream`, forked and joined with events, which a capture takes along.
+ *     before capturing (the first launch of a kernel sets its attributes).  Every call works on
+ *     `stream` alone.
  *
  * Stream container (the paper fixes only the bit string {0,1}*; the container is this library's):
  *   Coordinates of one worker are cut into segments (tensors), segments into buckets of at most
@@ -191,11 +190,7 @@ qgx_status qgx_encode(qgx_ctx* ctx, const float* norms, const uint8_t* sym, qgx_
 qgx_status qgx_quantize_encode(qgx_ctx* ctx, const float* V, uint32_t call_id, const float* norms_in,
                                qgx_stream* out, void* stream);
 
-/* DEQ o CODE: Vhat DEVICE [K][d], vhat_i = +-(norm * l_idx).
- * The decoding calls (this one, qgx_decode_average, qgx_eg_step) work on `stream`; for layouts with
- * chunks of fewer than QGX_CHUNK coordinates they also put a small kernel for those on a second queue
- * of the context, forked from and joined back into `stream` with events, so that it runs beside the
- * main kernel: callers see ordinary stream order. */
+/* DEQ o CODE: Vhat DEVICE [K][d], vhat_i = +-(norm * l_idx). */
 qgx_status qgx_decode(qgx_ctx* ctx, const qgx_stream* in, float* Vhat, void* stream);
 
 /* Aggregate of Algorithm 1: mean DEVICE [d] = (1/K) sum_k DEQ(CODE_k), decoded on the fly.

@@ -256,18 +256,17 @@ __device__ __forceinline__ void chunk_geometry(const Layout& lay, uint32_t c, ui
 // KSPLIT = 2 or 4: that many neighbouring waves share a position, each takes a run of the workers (as
 // equal as K allows, the longer runs first), and they add their sums through LDS before the update
 // (for layouts with too few positions to fill the GPU's wave slots).
-template <DecMode MODE, bool PREV, bool TWO, bool WIDE, int KSPLIT = 1>
-__global__ __launch_bounds__(kDecWaves * kWave) __attribute__((amdgpu_waves_per_eu(MODE == DecMode::Half1 ? 2 : 4)))
-void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArgs a)
+// The kernel's body, for workgroup `block` of the full positions' grid; the LDS arrays are the caller's:
+// s_dyn [waves][1 or 2][stage_stride], s_tab and (TWO) s_tab2 of kTabBytes, s_sd [kDecWaves] (KSPLIT > 1).
+template <DecMode MODE, bool PREV, bool TWO, bool WIDE, int KSPLIT>
+__device__ __forceinline__ void decode_full_body(const Layout& lay, const Tables* __restrict__ tab, Scalars* sc,
+                                                 const DecodeArgs& a, uint32_t block, uint32_t* s_dyn,
+                                                 unsigned char* s_tab, unsigned char* s_tab2, double* s_sd)
 {
     static_assert(!PREV || MODE == DecMode::Half1, "only the second half-step reads two streams");
     static_assert(!TWO || PREV, "a second table only comes with a second stream");
     static_assert(KSPLIT == 1 || KSPLIT == 2 || KSPLIT == 4, "the waves of a workgroup in groups of 1, 2 or 4");
     static_assert(KSPLIT == 1 || MODE != DecMode::Decode, "plain decoding has nothing to add up");
-    __shared__ double s_sd[KSPLIT > 1 ? kDecWaves : 1];
-    extern __shared__ __align__(16) uint32_t s_dyn[];    // [waves][1 or 2][stage_stride]
-    __shared__ __align__(16) unsigned char s_tab[kTabBytes];
-    __shared__ __align__(16) unsigned char s_tab2[TWO ? kTabBytes : 16];
     const unsigned char* s_tab_p = TWO ? s_tab2 : s_tab;
 
     const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
@@ -286,13 +285,13 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
             return;
         }
     }
-    load_tables<WIDE>(s_tab, tab, tid, (int)blockDim.x);
-    if constexpr (TWO) load_tables<WIDE>(s_tab2, a.tab_p, tid, (int)blockDim.x);
+    load_tables<WIDE>(s_tab, tab, tid, kDecWaves * kWave);
+    if constexpr (TWO) load_tables<WIDE>(s_tab2, a.tab_p, tid, kDecWaves * kWave);
     // words past a chunk's end are read by the window of its last symbols: keep them defined
     for (uint32_t q = (uint32_t)lane; q < kBufs * stage_stride; q += kWave) stage[q] = 0;
     __syncthreads();
 
-    const uint32_t g = (uint32_t)blockIdx.x * (blockDim.x >> 6) + (uint32_t)w;   // global wave number
+    const uint32_t g = block * (uint32_t)kDecWaves + (uint32_t)w;                // global wave number
     const uint32_t n_pos = lay.NC;
     uint32_t c, k_first, k_count;
     bool mine;                                           // wave-uniform: a full position that this launch covers
@@ -605,6 +604,17 @@ void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArg
     }
 }
 
+template <DecMode MODE, bool PREV, bool TWO, bool WIDE, int KSPLIT = 1>
+__global__ __launch_bounds__(kDecWaves * kWave) __attribute__((amdgpu_waves_per_eu(MODE == DecMode::Half1 ? 2 : 4)))
+void k_decode(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArgs a)
+{
+    __shared__ double s_sd[KSPLIT > 1 ? kDecWaves : 1];
+    extern __shared__ __align__(16) uint32_t s_dyn[];    // [waves][1 or 2][stage_stride]
+    __shared__ __align__(16) unsigned char s_tab[kTabBytes];
+    __shared__ __align__(16) unsigned char s_tab2[TWO ? kTabBytes : 16];
+    decode_full_body<MODE, PREV, TWO, WIDE, KSPLIT>(lay, tab, sc, a, blockIdx.x, s_dyn, s_tab, s_tab2, s_sd);
+}
+
 // ---- chunk positions with fewer than 4096 coordinates --------------------------------------------
 // They are the tails of buckets and tensors: few, but a wave that walked all K workers of one, symbol
 // by symbol, would take as long as the whole launch of the full positions.  So a position gets a
@@ -617,9 +627,13 @@ constexpr int kAccPitch = 65;                         // s_acc[s][lane], padded:
 template <bool PREV>
 constexpr int ragged_waves() { return PREV ? 4 : 8; } // two staging buffers per wave with two streams
 
+// The body, for ragged position `index` (of lay.ragged_chunk) and the first ragged_waves() waves of the workgroup
+// (further waves leave at once, before any barrier); the LDS arrays are the caller's: s_dyn [waves][1 or 2]
+// [rag_stride], s_tab and (TWO) s_tab2 of kTabBytes, s_acc [kLaneCoords * kAccPitch], s_sd [ragged_waves()].
 template <DecMode MODE, bool PREV, bool TWO>
-__global__ __launch_bounds__(ragged_waves<PREV>() * kWave)
-void k_decode_ragged(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArgs a)
+__device__ __forceinline__ void decode_ragged_body(const Layout& lay, const Tables* __restrict__ tab, Scalars* sc,
+                                                   const DecodeArgs& a, uint32_t index, uint32_t* s_dyn,
+                                                   unsigned char* s_tab, unsigned char* s_tab2, float* s_acc, double* s_sd)
 {
     static_assert(!PREV || MODE == DecMode::Half1, "only the second half-step reads two streams");
     static_assert(!TWO || PREV, "a second table only comes with a second stream");
@@ -627,14 +641,10 @@ void k_decode_ragged(Layout lay, const Tables* __restrict__ tab, Scalars* sc, De
     constexpr int kBufs = PREV ? 2 : 1;
     constexpr bool kExact = MODE == DecMode::Decode;
     constexpr int kHalf = kLaneCoords / 2;
-    extern __shared__ __align__(16) uint32_t s_dyn[];    // [waves][1 or 2][rag_stride]
-    __shared__ __align__(16) unsigned char s_tab[kTabBytes];
-    __shared__ __align__(16) unsigned char s_tab2[TWO ? kTabBytes : 16];
     const unsigned char* s_tab_p = TWO ? s_tab2 : s_tab;
-    __shared__ float s_acc[kLaneCoords * kAccPitch];
-    __shared__ double s_sd[W];
 
     const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
+    if (w >= W) return;
     const uint32_t stage_words = a.rag_words, stage_stride = a.rag_stride;
     uint32_t* stage = s_dyn + (size_t)w * kBufs * stage_stride;
     uint32_t* stage_p = stage + stage_stride;
@@ -645,7 +655,7 @@ void k_decode_ragged(Layout lay, const Tables* __restrict__ tab, Scalars* sc, De
     for (uint32_t q = (uint32_t)lane; q < kBufs * stage_stride; q += kWave) stage[q] = 0;
     __syncthreads();
 
-    const uint32_t c = lay.ragged_chunk[blockIdx.x];
+    const uint32_t c = lay.ragged_chunk[index];
     uint32_t clo, clen, bkt;
     chunk_geometry(lay, c, clo, clen, bkt);
     const int cnt = (int)min(64u, clen > 64u * (uint32_t)lane ? clen - 64u * (uint32_t)lane : 0u);
@@ -785,6 +795,38 @@ void k_decode_ragged(Layout lay, const Tables* __restrict__ tab, Scalars* sc, De
     }
 }
 
+template <DecMode MODE, bool PREV, bool TWO>
+__global__ __launch_bounds__(ragged_waves<PREV>() * kWave)
+void k_decode_ragged(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArgs a)
+{
+    extern __shared__ __align__(16) uint32_t s_dyn[];    // [waves][1 or 2][rag_stride]
+    __shared__ __align__(16) unsigned char s_tab[kTabBytes];
+    __shared__ __align__(16) unsigned char s_tab2[TWO ? kTabBytes : 16];
+    __shared__ float s_acc[kLaneCoords * kAccPitch];
+    __shared__ double s_sd[ragged_waves<PREV>()];
+    decode_ragged_body<MODE, PREV, TWO>(lay, tab, sc, a, blockIdx.x, s_dyn, s_tab, s_tab2, s_acc, s_sd);
+}
+
+// Layouts with both kinds of positions: one launch, a workgroup per ragged position first and the workgroups
+// of the full positions after them, so that the few, slow ragged ones (a cold instruction cache and the
+// tables' load for a single position each) start at once and run beside the full ones, not before or after
+// them.  The ragged workgroups take their sums' array from the dynamic LDS, behind their staging buffers.
+template <DecMode MODE, bool PREV, bool TWO, bool WIDE, int KSPLIT>
+__global__ __launch_bounds__(kDecWaves * kWave) __attribute__((amdgpu_waves_per_eu(MODE == DecMode::Half1 ? 2 : 4)))
+void k_decode_both(Layout lay, const Tables* __restrict__ tab, Scalars* sc, DecodeArgs a)
+{
+    __shared__ double s_sd[kDecWaves];
+    extern __shared__ __align__(16) uint32_t s_dyn[];
+    __shared__ __align__(16) unsigned char s_tab[kTabBytes];
+    __shared__ __align__(16) unsigned char s_tab2[TWO ? kTabBytes : 16];
+    if (blockIdx.x >= lay.n_ragged) {
+        decode_full_body<MODE, PREV, TWO, WIDE, KSPLIT>(lay, tab, sc, a, blockIdx.x - lay.n_ragged, s_dyn, s_tab, s_tab2, s_sd);
+    } else {
+        float* s_acc = reinterpret_cast<float*>(s_dyn + (size_t)ragged_waves<PREV>() * (PREV ? 2 : 1) * a.rag_stride);
+        decode_ragged_body<MODE, PREV, TWO>(lay, tab, sc, a, blockIdx.x, s_dyn, s_tab, s_tab2, s_acc, s_sd);
+    }
+}
+
 template <DecMode MODE, bool PREV, bool TWO, bool WIDE, int KSPLIT>
 static hipError_t launch_full_as(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
 {
@@ -829,38 +871,64 @@ static hipError_t launch_ragged(const Layout& lay, const Tables* tab, Scalars* s
     return hipGetLastError();
 }
 
-// Two launches cover the chunk positions: the full ones and, if the layout has any, the ragged ones,
-// which go first and on the side queue, where they run beside the full ones instead of after them.
-template <DecMode MODE, bool PREV, bool TWO = false>
-static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st,
-                              const SideQueue* side)
+// Both kinds of positions in one launch (k_decode_both).
+template <DecMode MODE, bool PREV, bool TWO, bool WIDE, int KSPLIT>
+static hipError_t launch_both_as(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
 {
-    const bool both = lay.n_ragged != 0 && lay.n_ragged != lay.NC;
-    if (!both || side == nullptr) {
-        hipError_t e = launch_ragged<MODE, PREV, TWO>(lay, tab, sc, a, st);
-        if (e != hipSuccess) return e;
-        return launch_full<MODE, PREV, TWO>(lay, tab, sc, a, st);
+    constexpr int W = ragged_waves<PREV>();
+    constexpr size_t bufs = PREV ? 2 : 1;
+    const size_t lds_full = (size_t)kDecWaves * bufs * a.stage_stride * sizeof(uint32_t);
+    const size_t lds_ragged = (size_t)W * bufs * a.rag_stride * sizeof(uint32_t) + (size_t)kLaneCoords * kAccPitch * sizeof(float);
+    const size_t lds = lds_full > lds_ragged ? lds_full : lds_ragged;
+    static LdsLimit limit;
+    hipError_t e = limit.ensure(reinterpret_cast<const void*>(&k_decode_both<MODE, PREV, TWO, WIDE, KSPLIT>), lds);
+    if (e != hipSuccess) return e;
+    const uint64_t nwork = (MODE == DecMode::Decode) ? (uint64_t)lay.K * lay.NC : (uint64_t)lay.NC * (uint32_t)KSPLIT;
+    const uint32_t full_blocks = (uint32_t)((nwork + kDecWaves - 1) / kDecWaves);
+    hipLaunchKernelGGL((k_decode_both<MODE, PREV, TWO, WIDE, KSPLIT>), dim3(lay.n_ragged + full_blocks), dim3(kDecWaves * kWave),
+                       lds, st, lay, tab, sc, a);
+    return hipGetLastError();
+}
+
+template <DecMode MODE, bool PREV, bool TWO>
+static hipError_t launch_both(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
+{
+    if constexpr (MODE != DecMode::Decode) {
+        if (a.ksplit == 2u) {
+            if (a.wide) return launch_both_as<MODE, PREV, TWO, true, 2>(lay, tab, sc, a, st);
+            return launch_both_as<MODE, PREV, TWO, false, 2>(lay, tab, sc, a, st);
+        }
+        if (a.ksplit == 4u) {
+            if (a.wide) return launch_both_as<MODE, PREV, TWO, true, 4>(lay, tab, sc, a, st);
+            return launch_both_as<MODE, PREV, TWO, false, 4>(lay, tab, sc, a, st);
+        }
     }
-    hipError_t e = hipEventRecord(side->fork, st);
-    if (e == hipSuccess) e = hipStreamWaitEvent(side->stream, side->fork, 0);
-    if (e == hipSuccess) e = launch_ragged<MODE, PREV, TWO>(lay, tab, sc, a, side->stream);
-    if (e == hipSuccess) e = hipEventRecord(side->join, side->stream);
-    if (e == hipSuccess) e = launch_full<MODE, PREV, TWO>(lay, tab, sc, a, st);
-    if (e == hipSuccess) e = hipStreamWaitEvent(st, side->join, 0);
-    return e;
+    if (a.wide) return launch_both_as<MODE, PREV, TWO, true, 1>(lay, tab, sc, a, st);
+    return launch_both_as<MODE, PREV, TWO, false, 1>(lay, tab, sc, a, st);
+}
+
+// A layout's full positions go to k_decode, its ragged ones to k_decode_ragged; a layout that has both
+// takes one launch of the kernel that holds both bodies.
+template <DecMode MODE, bool PREV, bool TWO = false>
+static hipError_t launch_mode(const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a, hipStream_t st)
+{
+    if (lay.n_ragged != 0 && lay.n_ragged != lay.NC) return launch_both<MODE, PREV, TWO>(lay, tab, sc, a, st);
+    hipError_t e = launch_ragged<MODE, PREV, TWO>(lay, tab, sc, a, st);
+    if (e != hipSuccess) return e;
+    return launch_full<MODE, PREV, TWO>(lay, tab, sc, a, st);
 }
 
 hipError_t launch_decode(DecMode mode, const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a,
-                         hipStream_t st, const SideQueue* side)
+                         hipStream_t st)
 {
     switch (mode) {
-        case DecMode::Decode: return launch_mode<DecMode::Decode, false>(lay, tab, sc, a, st, side);
-        case DecMode::Average: return launch_mode<DecMode::Average, false>(lay, tab, sc, a, st, side);
-        case DecMode::Half0: return launch_mode<DecMode::Half0, false>(lay, tab, sc, a, st, side);
+        case DecMode::Decode: return launch_mode<DecMode::Decode, false>(lay, tab, sc, a, st);
+        case DecMode::Average: return launch_mode<DecMode::Average, false>(lay, tab, sc, a, st);
+        case DecMode::Half0: return launch_mode<DecMode::Half0, false>(lay, tab, sc, a, st);
         default:
-            if (a.payload_p == nullptr) return launch_mode<DecMode::Half1, false>(lay, tab, sc, a, st, side);
-            return a.tab_p ? launch_mode<DecMode::Half1, true, true>(lay, tab, sc, a, st, side)
-                           : launch_mode<DecMode::Half1, true>(lay, tab, sc, a, st, side);
+            if (a.payload_p == nullptr) return launch_mode<DecMode::Half1, false>(lay, tab, sc, a, st);
+            return a.tab_p ? launch_mode<DecMode::Half1, true, true>(lay, tab, sc, a, st)
+                           : launch_mode<DecMode::Half1, true>(lay, tab, sc, a, st);
     }
 }
 

@@ -202,14 +202,8 @@ struct LdsLimit {
 hipError_t launch_build_tables(Tables* tab, hipStream_t st);
 hipError_t launch_encode(EncMode mode, const Layout& lay, const Tables* tab, Scalars* sc, const EncodeArgs& a,
                          hipStream_t st);
-// A second queue for work that should overlap the caller's stream (fork: the side waits for what the
-// caller's stream holds so far; join: the caller's stream waits for the side).
-struct SideQueue {
-    hipStream_t stream;
-    hipEvent_t fork, join;
-};
 hipError_t launch_decode(DecMode mode, const Layout& lay, const Tables* tab, Scalars* sc, const DecodeArgs& a,
-                         hipStream_t st, const SideQueue* side);
+                         hipStream_t st);
 hipError_t launch_finish_half1(const Layout& lay, Scalars* sc, const double* s_partial, const float* Y,
                                const float* anchor, float* X_out, hipStream_t st);
 hipError_t launch_state_init(const Layout& lay, Scalars* sc, float* Y, float* anchor, const float* X1,

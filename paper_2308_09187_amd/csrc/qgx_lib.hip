@@ -75,8 +75,6 @@ struct qgx_ctx {
     double* d_prob = nullptr;       // [kSymMax] symbol probabilities of the last qgx_fit_code
     double* d_norm = nullptr;       // [2 kNormBlocks + 2] partial sums and results of qgx_norm2 and qgx_game_gap
     double* d_metrics = nullptr;    // [K][3][kMetricBlocks] partial sums, then [K][3] results of qgx_quantization_metrics
-    SideQueue side{};               // for the ragged chunk positions of the decoding kernels
-    bool side_ok = false;
     double* d_xsum = nullptr;       // [d] sum of the X_{t+1/2} since qgx_average_reset (allocated there)
     bool xsum_on = false;
     uint32_t hist_bins = 0;         // bins of the histogram d_hist holds (0: none yet)
@@ -190,12 +188,6 @@ void free_all(qgx_ctx* c)
 {
     void* all[] = {c->d_layout, c->d_tabs, c->d_sc, c->d_Y, c->d_anchor, c->d_scan, c->d_xch, c->d_tickets, c->d_spartial, c->d_hpartial, c->d_hist, c->d_prob, c->d_norm, c->d_metrics, c->d_xsum};
     for (void* p : all) (void)hipFree(p);
-    if (c->side_ok) {
-        (void)hipEventDestroy(c->side.fork);
-        (void)hipEventDestroy(c->side.join);
-        (void)hipStreamDestroy(c->side.stream);
-        c->side_ok = false;
-    }
 }
 
 }  // namespace
@@ -331,12 +323,6 @@ qgx_status qgx_create(qgx_ctx** out, const qgx_config* cfg)
         const uint32_t kind = (uint32_t)cfg->code;
         for (int t = 0; ok && t < QGX_TABLES; ++t)
             ok = hipMemcpy(&c->d_tabs[t].code_kind, &kind, sizeof(kind), hipMemcpyHostToDevice) == hipSuccess;
-    }
-    if (ok && c->lay.n_ragged != 0 && c->lay.n_ragged != NC) {      // default priority, as every stream here
-        ok = hipStreamCreateWithFlags(&c->side.stream, hipStreamNonBlocking) == hipSuccess;
-        ok = ok && hipEventCreateWithFlags(&c->side.fork, hipEventDisableTiming) == hipSuccess;
-        ok = ok && hipEventCreateWithFlags(&c->side.join, hipEventDisableTiming) == hipSuccess;
-        c->side_ok = ok;
     }
     ok = ok && hipDeviceSynchronize() == hipSuccess;
     if (!ok) { free_all(c); delete c; return QGX_ERR_HIP; }
@@ -689,7 +675,7 @@ qgx_status qgx_decode(qgx_ctx* ctx, const qgx_stream* in, float* Vhat, void* str
     DecodeArgs a{};
     fill_decode_args(ctx, a, in, nullptr);
     a.out = Vhat;
-    QGX_HIP(ctx, launch_decode(DecMode::Decode, ctx->lay, tab_of(ctx), ctx->d_sc, a, (hipStream_t)stream, ctx->side_ok ? &ctx->side : nullptr));
+    QGX_HIP(ctx, launch_decode(DecMode::Decode, ctx->lay, tab_of(ctx), ctx->d_sc, a, (hipStream_t)stream));
     return QGX_OK;
 }
 
@@ -702,8 +688,7 @@ qgx_status qgx_decode_average(qgx_ctx* ctx, const qgx_stream* in, float* mean, v
     DecodeArgs a{};
     fill_decode_args(ctx, a, in, nullptr);
     a.out = mean;
-    QGX_HIP(ctx, launch_decode(DecMode::Average, ctx->lay, tab_of(ctx), ctx->d_sc, a, (hipStream_t)stream,
-                               ctx->side_ok ? &ctx->side : nullptr));
+    QGX_HIP(ctx, launch_decode(DecMode::Average, ctx->lay, tab_of(ctx), ctx->d_sc, a, (hipStream_t)stream));
     return QGX_OK;
 }
 
@@ -782,13 +767,13 @@ static qgx_status eg_step_with(qgx_ctx* ctx, int half, const qgx_stream* cur, co
         fill_decode_args(ctx, a, cur, nullptr);
         a.out = X_out;
         a.x_sum = ctx->xsum_on ? ctx->d_xsum : nullptr;
-        QGX_HIP(ctx, launch_decode(DecMode::Half0, ctx->lay, tab_of(ctx), ctx->d_sc, a, st, ctx->side_ok ? &ctx->side : nullptr));
+        QGX_HIP(ctx, launch_decode(DecMode::Half0, ctx->lay, tab_of(ctx), ctx->d_sc, a, st));
         if (ctx->xsum_on) QGX_HIP(ctx, launch_average_count(ctx->d_sc, st));
         return QGX_OK;
     }
     fill_decode_args(ctx, a, cur, prev);
     a.s_partial = s_partial;
-    QGX_HIP(ctx, launch_decode(DecMode::Half1, ctx->lay, tab_of(ctx), ctx->d_sc, a, st, ctx->side_ok ? &ctx->side : nullptr));
+    QGX_HIP(ctx, launch_decode(DecMode::Half1, ctx->lay, tab_of(ctx), ctx->d_sc, a, st));
     QGX_HIP(ctx, launch_finish_half1(ctx->lay, ctx->d_sc, s_partial, ctx->d_Y, a.anchor, X_out, st));
     return QGX_OK;
 }

@@ -1291,8 +1291,8 @@ def test_iteration_as_a_replayed_hip_graph(qgx, d, bucket, slotted):
     QGX_CALL_FIRST_HALF / QGX_CALL_SECOND_HALF, the number of the quantisation call live on the device, so
     every replay is the next iteration with fresh draws.  Between replays the test does eager work (new
     noise, compaction, copies) and synchronises; every iteration is compared with the oracle, which is
-    given call numbers 2(t-1) and 2(t-1)+1.  The second layout has a ragged chunk position, whose kernel
-    runs on the library's side queue inside the capture; the third has buckets shared by two workgroups
+    given call numbers 2(t-1) and 2(t-1)+1.  The second layout has a ragged chunk position, whose workgroup
+    runs in the same launch as the full positions'; the third has buckets shared by two workgroups
     and compact placement, whose workgroups are ordered by tickets and tags that a kernel of the capture
     renews; the fourth buckets that share chunks.  The running average is on: its count is on the device."""
     K, seed, T = 3, 41, 5

@@ -40,7 +40,7 @@ def test_static_scratch_variant_matches_the_allocating_one():
         pytest.skip("no GPU")
     from paper_2308_09187_amd import qgx
     qgx.load()
-    # the first layout has full and ragged chunk positions (side queue) and many chunks; the second is smaller,
+    # the first layout has full and ragged chunk positions (one launch for both) and many chunks; the second is smaller,
     # so the static array still holds the first call's partial sums beyond the entries the second one uses
     cases = [((1 << 17) + 4096 + 520, 5, 8192, [1 << 16, 4096 + 520, 1 << 16], True),
              (3 * 4096 + 300, 3, 4096, None, True),
