@@ -136,15 +136,26 @@ __global__ __launch_bounds__(MAXW * kWave) void k_histogram(Layout lay, const fl
         if (anybad != 0 && tid == 0) raise_error(sc, QGX_EBIT_NONFINITE);
         if (usable) {
             const float rinv = 1.0f / n;
+            if (clen == (uint32_t)kChunk) {
+                // a whole chunk: no coordinate to leave out, and u above 1 (by a rounding) ends in the last bin
+                // with the clamp of the bin number alone
 #pragma unroll
-            for (int r = 0; r < kRows; ++r) {
-                const uint32_t i0 = clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
-                const float e[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
+                for (int r = 0; r < kRows; ++r) {
+                    const float e[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    if (i0 + (uint32_t)q < cend) {
-                        const float u = fminf(fabsf(e[q]) * rinv, 1.0f);
-                        atomicAdd(&s_cnt[bin_of(u, n_bins)], 1u);
+                    for (int q = 0; q < 4; ++q) atomicAdd(&s_cnt[bin_of(fabsf(e[q]) * rinv, n_bins)], 1u);
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < kRows; ++r) {
+                    const uint32_t i0 = clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
+                    const float e[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        if (i0 + (uint32_t)q < cend) {
+                            const float u = fminf(fabsf(e[q]) * rinv, 1.0f);
+                            atomicAdd(&s_cnt[bin_of(u, n_bins)], 1u);
+                        }
                     }
                 }
             }
