@@ -386,12 +386,12 @@ struct Tree {
 
 constexpr uint32_t kRow = 16;     // lanes per update
 
-__device__ uint32_t bin_containing(uint32_t n_bins, double x)
+// The bin whose half-open interval [edge, next edge) holds x >= 0: the bins are 64 to an octave, so the bin
+// number is the exponent and the top six fraction bits, which a binary64 number shows as its bits 46 and up.
+__device__ __forceinline__ uint32_t bin_containing(uint32_t n_bins, double x)
 {
-    uint32_t b = bin_of((float)x, n_bins);
-    while (b + 1 < n_bins && bin_edge(b + 1, n_bins) <= x) ++b;
-    while (b > 0 && bin_edge(b, n_bins) > x) --b;
-    return b;
+    const int key = (int)((unsigned long long)__double_as_longlong(x) >> 46) - (1023 * 64 - (int)n_bins);
+    return (uint32_t)min(max(key, 0), (int)n_bins - 1);
 }
 
 // x of another lane of the row, by a DPP control word; lanes without a source read 0
@@ -493,14 +493,14 @@ __device__ double stationary_point(const Tree& T, double a, double c)
     // the smallest x with mass(a, x) >= t
     if (m_a >= t) return fmin(fmax(a + t / m_a * (a_hi - a), a), c);
     // the runs' prefix sums side by side, then each run's mass on top of the runs before it
-    double cum[5], base[6];
+    double cum[5], base[6], tot[5];
 #pragma unroll
-    for (int s = 0; s < 5; ++s) cum[s] = row_scan(m[s], li);
+    for (int s = 0; s < 5; ++s) { cum[s] = row_scan(m[s], li); tot[s] = row_sum(m[s]); }
     base[0] = m_a;
 #pragma unroll
     for (int s = 0; s < 5; ++s) {
         cum[s] += base[s];
-        base[s + 1] = __shfl(cum[s], (int)kRow - 1, (int)kRow);
+        base[s + 1] = base[s] + tot[s];
     }
     double acc = base[5], prev = 0.0;
     uint32_t at_lvl = 0u, at_idx = 0u;
