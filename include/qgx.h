@@ -204,8 +204,10 @@ qgx_status qgx_decode_average(qgx_ctx* ctx, const qgx_stream* in, float* mean, v
 /* Adaptive levels, eq. (QAda): weighted histogram of the normalised coordinates of V (each bucket
  * weighted by its squared norm) over n_bins bins on the binary32 grid (64 bins per octave, n_bins a
  * multiple of 64, <= QGX_MAX_BINS), then `sweeps` passes that move one interior level at a time to
- * the stationary point between its neighbours, starting from the current table.  n_sym must equal
- * the current table's length.  The new table replaces the context's.  hist_out DEVICE [n_bins]
+ * the stationary point between its neighbours (the smallest one where the condition holds on a whole
+ * interval, i.e. where the histogram has no mass; the lower neighbour itself when there is none between
+ * the two), starting from the current table; levels stay in binary64 between the passes and are rounded
+ * to binary32, gaps at least 2^-24, at the end.  n_sym must equal the current table's length.  The new table replaces the context's.  hist_out DEVICE [n_bins]
  * doubles or NULL. */
 qgx_status qgx_fit_levels(qgx_ctx* ctx, const float* V, uint32_t n_sym, uint32_t n_bins, uint32_t sweeps,
                           double* hist_out, void* stream);
