@@ -539,6 +539,26 @@ __device__ __forceinline__ void decode_full_body(const Layout& lay, const Tables
     const float* tr0 = KSPLIT > 1 ? reinterpret_cast<const float*>(s_dyn + (size_t)(w - part) * kBufs * stage_stride) : tr;
     const size_t tr_step = (size_t)kBufs * stage_stride;  // from one wave's buffer to the next, in words
     const float scale = KSPLIT > 1 ? 1.0f : invK;         // KSPLIT: the division comes after the group's sum
+    // Where this lane's i-th float4 of pass q lies in the vectors.
+    auto place = [&](int q, int i) -> uint32_t {
+        const int first_lane = kPiece == 32 ? 32 * (q >> 1) : 0, first_sym = kPiece == 32 ? 32 * (q & 1) : 16 * q;
+        const int row = lane / kRowLanes + kRowsPerRead * i, col = lane % kRowLanes;
+        return clo + 64u * (uint32_t)(first_lane + row) + (uint32_t)first_sym + 4u * (uint32_t)col;
+    };
+    // A piece of Y is asked for as soon as the piece before it in the same registers has been used, a pass
+    // ahead of its own use: every wave of the launch reaches this stage at about the same time, and a load
+    // issued where it is used would be waited for in full, four times over.
+    constexpr bool kReadsY = MODE == DecMode::Half0 || MODE == DecMode::Half1;
+    float4 y_ahead[4];
+    auto load_y = [&](int q, int i) {
+        y_ahead[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (KSPLIT > 1 && i * KSPLIT / 4 != part) return;
+        if (mine) y_ahead[i] = *reinterpret_cast<const float4*>(a.Y + place(q, i));
+    };
+    if constexpr (kReadsY) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) load_y(0, i);
+    }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int first_lane = kPiece == 32 ? 32 * (q >> 1) : 0;    // the lanes whose symbols this pass turns
@@ -573,11 +593,11 @@ __device__ __forceinline__ void decode_full_body(const Layout& lay, const Tables
                 }
                 m.x *= invK; m.y *= invK; m.z *= invK; m.w *= invK;
             }
-            const uint32_t at = clo + 64u * (uint32_t)(first_lane + row) + (uint32_t)first_sym + 4u * (uint32_t)col;
+            const uint32_t at = place(q, i);
             if (MODE == DecMode::Average) {
                 *reinterpret_cast<float4*>(a.out + at) = m;
             } else if (MODE == DecMode::Half0) {
-                const float4 y = *reinterpret_cast<const float4*>(a.Y + at);
+                const float4 y = y_ahead[i];
                 float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (a.anchor) x = *reinterpret_cast<const float4*>(a.anchor + at);
                 x.x = (x.x + gam * y.x) - gam * m.x;
@@ -585,6 +605,7 @@ __device__ __forceinline__ void decode_full_body(const Layout& lay, const Tables
                 x.z = (x.z + gam * y.z) - gam * m.z;
                 x.w = (x.w + gam * y.w) - gam * m.w;
                 *reinterpret_cast<float4*>(a.out + at) = x;
+                if (q < 3) load_y(q + 1, i);
                 if (a.x_sum) {                                   // ergodic average: sum of the half-step iterates
                     double2* xs = reinterpret_cast<double2*>(a.x_sum + at);
                     double2 s0 = xs[0], s1 = xs[1];
@@ -592,9 +613,10 @@ __device__ __forceinline__ void decode_full_body(const Layout& lay, const Tables
                     xs[0] = s0; xs[1] = s1;
                 }
             } else {
-                float4 y = *reinterpret_cast<const float4*>(a.Y + at);
+                float4 y = y_ahead[i];
                 y.x -= m.x; y.y -= m.y; y.z -= m.z; y.w -= m.w;
                 *reinterpret_cast<float4*>(a.Y + at) = y;
+                if (q < 3) load_y(q + 1, i);
             }
         }
         wave_lds_fence();                                     // ... and written again in the next pass
