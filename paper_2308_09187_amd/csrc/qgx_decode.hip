@@ -20,7 +20,6 @@ namespace qgx {
 
 constexpr int kPre = kChunkWordsMax / (kWave * 4);   // 7 x uint4 per lane cover a worst-case chunk
 constexpr int kDecWaves = 8;                          // waves per workgroup: they share the decode table
-constexpr int kLead = 4;                              // zero words in front of a staged chunk (full positions)
 
 // Staged chunk layout in LDS.  Lane j parses the j-th run of 64 coordinates, whose bits start roughly
 // 64 * (bits per coordinate) / 32 words after lane j-1's: a power-of-two stride that would put all
@@ -62,22 +61,47 @@ __device__ __forceinline__ void prefetch_chunk(const ChunkRef& cr, uint4 (&pre)[
     }
 }
 
-// LEAD: words of zeros kept in front of the chunk (0 or kLead), so that a cursor may point one bit
-// before the chunk's first bit.
-template <int LEAD = 0>
 __device__ __forceinline__ void commit_chunk(uint32_t* stage, const uint4 (&pre)[kPre], uint32_t stage_words)
 {
-    static_assert(LEAD % 4 == 0, "16-byte pieces stay aligned");
     const uint32_t lane = (uint32_t)lane_id();
 #pragma unroll
     for (int q = 0; q < kPre; ++q) {
         const uint32_t i0 = (lane + (uint32_t)q * kWave) * 4u;
         if (i0 < stage_words) {
-            const uint32_t j0 = i0 + (uint32_t)LEAD;
-            uint2* at = reinterpret_cast<uint2*>(stage + staged(j0));          // even slot: 8-byte aligned
+            uint2* at = reinterpret_cast<uint2*>(stage + staged(i0));          // even slot: 8-byte aligned
             at[0] = make_uint2(pre[q].x, pre[q].y);
             at[1] = make_uint2(pre[q].z, pre[q].w);
-            if ((j0 & 31u) == 0u && j0 != 0u) at[-1] = make_uint2(pre[q].x, pre[q].y);   // pads repeat their successors
+            if ((i0 & 31u) == 0u && i0 != 0u) at[-1] = make_uint2(pre[q].x, pre[q].y);   // pads repeat their successors
+        }
+    }
+}
+
+// The chunk back to front, for the parse of the full positions: stream bit t goes to bit
+// 32 (kTail + stage_words) - 1 - t of the buffer (word w to place kTail + stage_words - 1 - w, its bits
+// turned round), so that a plain funnel shift of buffer words gives a window with the FIRST stream bit on
+// top, which is how the decode tables are indexed, and no window has to be turned round when it is read:
+// a word is turned once here instead of twice per three symbols there.  kTail zero words lie below the
+// chunk's end (the windows of its last symbols reach there), and the buffer's slack above its first word
+// stays zero as well (a cursor may point one bit before the chunk).  The pads are as in the forward layout.
+// `words`: the chunk's own size; pieces of 256 words that lie beyond it are left as they are (a valid
+// stream's symbols never depend on what follows its last bit).
+constexpr int kTail = 4;
+__device__ __forceinline__ void commit_chunk_reversed(uint32_t* stage, const uint4 (&pre)[kPre], uint32_t stage_words,
+                                                      uint32_t words)
+{
+    static_assert(kTail % 4 == 0 && kChunkWordsMax % 4 == 0, "16-byte pieces stay aligned");
+    const uint32_t lane = (uint32_t)lane_id();
+#pragma unroll
+    for (int q = 0; q < kPre; ++q) {
+        if ((uint32_t)q * (kWave * 4u) >= words) break;                       // (wave-uniform)
+        const uint32_t i0 = (lane + (uint32_t)q * kWave) * 4u;
+        if (i0 < stage_words) {
+            const uint32_t j0 = (uint32_t)kTail + stage_words - 4u - i0;      // place of the piece's LAST word
+            uint2* at = reinterpret_cast<uint2*>(stage + staged(j0));
+            const uint2 low = make_uint2(__brev(pre[q].w), __brev(pre[q].z));
+            at[0] = low;
+            at[1] = make_uint2(__brev(pre[q].y), __brev(pre[q].x));
+            if ((j0 & 31u) == 0u) at[-1] = low;                               // (j0 >= kTail: never the buffer's first word)
         }
     }
 }
@@ -88,9 +112,10 @@ constexpr int kTabLvalBytes = kSymMax * 4;
 constexpr int kTabBytes = kTabLvalBytes + kDlut * 2;
 
 // Symbols are parsed in groups of up to three from one 64-bit window (three LDS words): a symbol
-// takes at most 14 bits, so the third one still starts inside the first word.  A table entry is
-// (bits of the symbol incl. sign - 1) | 4 idx << 4 with bits 4 and 5 clear, so sums of entries carry
-// the consumed bits in their low six bits and an entry can be used as a shift count as it is.
+// takes at most 15 bits with its sign, so the third one still starts inside the first word.  A table
+// entry is a bit count | 4 idx << 4 with bits 4 and 5 clear (the 13-bit table counts the symbol's bits
+// incl. sign less one, the 8-byte table all of them), so sums of entries carry the consumed bits in
+// their low six bits and an entry can be used as a shift count as it is.
 // The three steps are separate so that the caller can issue the next group's window reads before
 // it turns the current group's entries into values.
 struct Window { uint32_t w0, w1, w2; };
@@ -106,9 +131,9 @@ __device__ __forceinline__ Window read_window(const uint32_t* stage, uint32_t p)
 // away, its top 13 bits index the table, and a symbol's last bit (the sign) reaches bit 31 by a left
 // shift of (symbol bits - 1), which is what the entry's low bits hold.  `neg` counts the used bits
 // downwards (adding ~e takes off the entry's count plus one); only its low six bits mean anything.
-template <int N, bool WIDE = false>
+template <int N>
 __device__ __forceinline__ void parse_group(const Window& w, const unsigned char* tab, uint32_t& p,
-                                            uint32_t (&win)[3], uint32_t (&e)[3], float (&lv)[3])
+                                            uint32_t (&win)[3], uint32_t (&e)[3])
 {
     const uint32_t top = __brev(__builtin_amdgcn_alignbit(w.w1, w.w0, p));    // shifts use p mod 32
     const uint32_t nxt = __brev(__builtin_amdgcn_alignbit(w.w2, w.w1, p));
@@ -116,41 +141,31 @@ __device__ __forceinline__ void parse_group(const Window& w, const unsigned char
 #pragma unroll
     for (int i = 0; i < N; ++i) {
         win[i] = i == 0 ? top : __builtin_amdgcn_alignbit(top, nxt, neg);     // (top:nxt) << used, upper word
-        if constexpr (WIDE) {                                                 // entry and level in one look-up
-            const uint2 t = *reinterpret_cast<const uint2*>(tab + kTabLvalBytes + ((win[i] >> 18) & 0x3FF8u));
-            e[i] = t.x;
-            lv[i] = __uint_as_float(t.y);
-        } else {
-            e[i] = *reinterpret_cast<const uint16_t*>(tab + kTabLvalBytes + ((win[i] >> 18) & 0x3FFEu));
-        }
+        e[i] = *reinterpret_cast<const uint16_t*>(tab + kTabLvalBytes + ((win[i] >> 18) & 0x3FFEu));
         neg += ~e[i];
     }
     p -= neg | 0xFFFFFFC0u;                                                   // minus (minus the bits used)
 }
 
-template <int N>
-__device__ __forceinline__ void parse_group(const Window& w, const unsigned char* tab, uint32_t& p,
-                                            uint32_t (&win)[3], uint32_t (&e)[3])
-{
-    float unused[3];
-    parse_group<N, false>(w, tab, p, win, e, unused);
-}
-
-// The same chain for the kernel of the full positions, with the windows taken one bit early: the cursor
-// q points at the bit BEFORE the next symbol, so bit 31 of a symbol's window is the last bit of the
-// symbol before it, which is that symbol's sign if it has one.  The sign of a symbol is thus read off
-// the window of the next one with a single AND-OR, no shift by its length: W[i + 1] for symbol i, the
-// next group's W[0] for a group's last symbol, and for the last group of a run (LAST, two symbols) the
-// window after its second symbol, W[2].  The table index sits one bit lower (bits 30..20 resp. 30..18).
-// `all_neg` gathers the AND of the groups' (negative) bit counts: a reject entry (bit 15) leaves a zero
-// among its bits 15..31, valid entries (below 0x2000 each) never do, so no per-symbol flag is kept.
+// The same chain for the kernel of the full positions, which stages its chunks back to front
+// (commit_chunk_reversed): the cursor r is a bit position in the buffer and moves DOWN, the three words
+// from it give the 64 bits with the first stream bit on top by two funnel shifts and nothing else.
+// The windows are taken one bit early: r + 63 is the buffer bit of the stream bit BEFORE the next symbol,
+// so bit 31 of a symbol's window is the last bit of the symbol before it, which is that symbol's sign
+// if it has one.  The sign of a symbol is thus read off the window of the next one with a single
+// AND-OR, no shift by its length: W[i + 1] for symbol i, the next group's W[0] for a group's last
+// symbol, and for the last group of a run (LAST, two symbols) the window after its second symbol, W[2].
+// The table index sits one bit lower (bits 30..20 resp. 30..18).
+// `seen` gathers the AND of the groups' (negative) bit counts: a reject entry leaves a zero among bits
+// 15..31, valid entries never do, so no per-symbol flag is kept.
+// WIDE: the 8-byte table's entries are the negative counts themselves and only need adding up.
 template <int N, bool WIDE, bool LAST>
-__device__ __forceinline__ void parse_group_early(const Window& w, const unsigned char* tab, uint32_t& q,
-                                                  uint32_t (&W)[4], uint32_t (&e)[3], float (&lv)[3], uint32_t& all_neg)
+__device__ __forceinline__ void parse_group_early(const Window& w, const unsigned char* tab, uint32_t& r,
+                                                  uint32_t (&W)[4], uint32_t (&e)[3], float (&lv)[3], uint32_t& seen)
 {
     static_assert(!LAST || N == 2, "a run of 32 symbols ends with a group of two");
-    const uint32_t top = __brev(__builtin_amdgcn_alignbit(w.w1, w.w0, q));    // shifts use q mod 32
-    const uint32_t nxt = __brev(__builtin_amdgcn_alignbit(w.w2, w.w1, q));
+    const uint32_t top = __builtin_amdgcn_alignbit(w.w2, w.w1, r);            // shifts use r mod 32
+    const uint32_t nxt = __builtin_amdgcn_alignbit(w.w1, w.w0, r);
     uint32_t neg = 0;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
@@ -159,14 +174,15 @@ __device__ __forceinline__ void parse_group_early(const Window& w, const unsigne
             const uint2 t = *reinterpret_cast<const uint2*>(tab + kTabLvalBytes + ((W[i] >> 17) & 0x3FF8u));
             e[i] = t.x;
             lv[i] = __uint_as_float(t.y);
+            neg = i == 0 ? t.x : neg + t.x;
         } else {
             e[i] = *reinterpret_cast<const uint16_t*>(tab + kTabLvalBytes + ((W[i] >> 17) & 0x3FFEu));
+            neg += ~e[i];
         }
-        neg += ~e[i];
     }
     if constexpr (LAST) W[N] = __builtin_amdgcn_alignbit(top, nxt, neg);     // at least two bits used: never a shift by 0
-    all_neg &= neg;
-    q -= neg | 0xFFFFFFC0u;
+    seen &= neg;
+    r += neg | 0xFFFFFFC0u;                                                   // down by the bits used
 }
 
 // norm with the sign of the symbol whose last bit is bit 31 of `w_next` (norms are not negative)
@@ -176,11 +192,13 @@ __device__ __forceinline__ float signed_norm(uint32_t w_next, float n)
 }
 
 // +-(norm * level), one binary32 product, sign from the window of the next symbol
+// EXACT_ZERO: +0 for the zero symbol, whose sign bit is not in the stream (the level 0 is the only one
+// that is zero)
 template <bool EXACT_ZERO>
-__device__ __forceinline__ float value_early(uint32_t w_next, float lv, uint32_t e, float n)
+__device__ __forceinline__ float value_early(uint32_t w_next, float lv, float n)
 {
     const float val = __uint_as_float((w_next & 0x80000000u) | __float_as_uint(n * lv));
-    if (EXACT_ZERO) return (e >> 4) == 0u ? 0.0f : val;
+    if (EXACT_ZERO) return lv == 0.0f ? 0.0f : val;
     return val;
 }
 
@@ -327,7 +345,7 @@ __device__ __forceinline__ void decode_full_body(const Layout& lay, const Tables
 #pragma unroll
     for (int s = 0; s < kLaneCoords; ++s) acc[s] = 0.0f;
     double sdiff = 0.0;
-    uint32_t all_neg = 0xFFFFFFFFu;
+    uint32_t seen = 0xFFFFFFFFu;
     bool malformed = false;
 
     // Two streams: the next worker's chunks are already in flight in registers while these are parsed.
@@ -336,14 +354,14 @@ __device__ __forceinline__ void decode_full_body(const Layout& lay, const Tables
     constexpr bool kAhead = PREV;
     uint4 pre[kPre];
     uint4 pre_p[PREV ? kPre : 1];
-    ChunkRef cr{nullptr, 0u};
+    ChunkRef cr{nullptr, 0u}, cp{nullptr, 0u};
     SubMeta nxt{0u, 0u, 0u, 0.0f}, nxt_p{0u, 0u, 0u, 0.0f};
     if (k_count != 0u) {                                  // (always, unless KSPLIT left this wave without work)
         cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, a.sub_end, k_first, c, lay.NC, stage_words, sc);
         if constexpr (kAhead) prefetch_chunk(cr, pre);
         nxt = load_meta(a.sub_end, a.norms, k_first, c, bkt, lay, lane);
         if constexpr (PREV) {
-            const ChunkRef cp = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, a.sub_end_p, k_first, c, lay.NC, stage_words, sc);
+            cp = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, a.sub_end_p, k_first, c, lay.NC, stage_words, sc);
             prefetch_chunk(cp, pre_p);
             nxt_p = load_meta(a.sub_end_p, a.norms_p, k_first, c, bkt, lay, lane);
         }
@@ -354,15 +372,16 @@ __device__ __forceinline__ void decode_full_body(const Layout& lay, const Tables
         const SubMeta cur = nxt, prv = nxt_p;
         if constexpr (!kAhead) prefetch_chunk(cr, pre);
         wave_lds_fence();                                     // the last worker's windows have been read
-        commit_chunk<kLead>(stage, pre, stage_words);
-        if constexpr (PREV) commit_chunk<kLead>(stage_p, pre_p, stage_words);
+        commit_chunk_reversed(stage, pre, stage_words, (uint32_t)__builtin_amdgcn_readfirstlane((int)cr.words));
+        if constexpr (PREV)
+            commit_chunk_reversed(stage_p, pre_p, stage_words, (uint32_t)__builtin_amdgcn_readfirstlane((int)cp.words));
         wave_lds_fence();                                     // a lane parses words that other lanes stored
         if (kk + 1 < k_count) {
             cr = chunk_ref(a.payload, a.cap_words, a.chunk_off, a.sub_end, k + 1, c, lay.NC, stage_words, sc);
             nxt = load_meta(a.sub_end, a.norms, k + 1, c, bkt, lay, lane);
             if constexpr (kAhead) prefetch_chunk(cr, pre);
             if constexpr (PREV) {
-                const ChunkRef cp = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, a.sub_end_p, k + 1, c, lay.NC, stage_words, sc);
+                cp = chunk_ref(a.payload_p, a.cap_words_p, a.chunk_off_p, a.sub_end_p, k + 1, c, lay.NC, stage_words, sc);
                 nxt_p = load_meta(a.sub_end_p, a.norms_p, k + 1, c, bkt, lay, lane);
                 prefetch_chunk(cp, pre_p);
             }
@@ -373,24 +392,24 @@ __device__ __forceinline__ void decode_full_body(const Layout& lay, const Tables
         const float n = cur.n, np = prv.n;
         float* vout = nullptr;
         if constexpr (MODE == DecMode::Decode) vout = a.out + (size_t)k * lay.d + clo + 64u * (uint32_t)lane;
-        // From stream bit p to the staged chunk's bit before it: the chunk has kLead zero words in front.
-        constexpr uint32_t kEarly = 32u * (uint32_t)kLead - 1u;
+        // From stream bit p to the buffer bit r with the bit before p on top of the 64 bits from r:
+        // r = r_base - p (the chunk lies back to front).
+        const uint32_t r_base = 32u * ((uint32_t)kTail + stage_words) - 63u;
         constexpr int kHalf = kLaneCoords / 2;
         if constexpr (!PREV) {
             // the lane's two sub-chunks side by side: ten groups of three symbols and one of two each;
             // a group's last symbol is finished when the next group's first window (its sign on top) is there
             uint32_t pb = cur.p_mid;
             if (pb > p_limit) { pb = p_limit; malformed = true; }
-            uint32_t q = p + kEarly, qb = pb + kEarly;
+            uint32_t q = r_base - p, qb = r_base - pb;
             uint32_t W[4], e[3], W_b[4], e_b[3];
             float lv_held = 0.0f, lv_held_b = 0.0f;
-            uint32_t e_held = 0u, e_held_b = 0u;
             Window wn = read_window(stage, q), wn_b = read_window(stage, qb);
-            auto emit = [&](int at, uint32_t w_next, float lv, uint32_t en) {
+            auto emit = [&](int at, uint32_t w_next, float lv) {
                 if constexpr (MODE == DecMode::Decode) {
-                    vout[at] = value_early<true>(w_next, lv, en, n);
+                    vout[at] = value_early<true>(w_next, lv, n);
                 } else if constexpr (MODE == DecMode::Half1) {           // no previous streams: the vectors of t count as zero
-                    const float val = value_early<false>(w_next, lv, en, n);
+                    const float val = value_early<false>(w_next, lv, n);
                     acc[at] += val;
                     sdiff = fma((double)val, (double)val, sdiff);
                 } else {
@@ -401,13 +420,13 @@ __device__ __forceinline__ void decode_full_body(const Layout& lay, const Tables
             for (int s = 0; s < kHalf; s += 3) {
                 float lv[3], lv_b[3];
                 if (s + 3 <= kHalf) {
-                    parse_group_early<3, WIDE, false>(wn, s_tab, q, W, e, lv, all_neg);
+                    parse_group_early<3, WIDE, false>(wn, s_tab, q, W, e, lv, seen);
                     wn = read_window(stage, q);
-                    parse_group_early<3, WIDE, false>(wn_b, s_tab, qb, W_b, e_b, lv_b, all_neg);
+                    parse_group_early<3, WIDE, false>(wn_b, s_tab, qb, W_b, e_b, lv_b, seen);
                     wn_b = read_window(stage, qb);
                 } else {
-                    parse_group_early<2, WIDE, true>(wn, s_tab, q, W, e, lv, all_neg);
-                    parse_group_early<2, WIDE, true>(wn_b, s_tab, qb, W_b, e_b, lv_b, all_neg);
+                    parse_group_early<2, WIDE, true>(wn, s_tab, q, W, e, lv, seen);
+                    parse_group_early<2, WIDE, true>(wn_b, s_tab, qb, W_b, e_b, lv_b, seen);
                 }
                 const int cnt = s + 3 <= kHalf ? 3 : 2;
                 if constexpr (!WIDE) {
@@ -416,21 +435,21 @@ __device__ __forceinline__ void decode_full_body(const Layout& lay, const Tables
                         if (i < cnt) { lv[i] = level_of(s_tab, e[i]); lv_b[i] = level_of(s_tab, e_b[i]); }
                     }
                 }
-                if (s > 0) { emit(s - 1, W[0], lv_held, e_held); emit(kHalf + s - 1, W_b[0], lv_held_b, e_held_b); }
+                if (s > 0) { emit(s - 1, W[0], lv_held); emit(kHalf + s - 1, W_b[0], lv_held_b); }
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
-                    if (i + 1 < cnt || cnt == 2) { emit(s + i, W[i + 1], lv[i], e[i]); emit(kHalf + s + i, W_b[i + 1], lv_b[i], e_b[i]); }
+                    if (i + 1 < cnt || cnt == 2) { emit(s + i, W[i + 1], lv[i]); emit(kHalf + s + i, W_b[i + 1], lv_b[i]); }
                 }
-                if (cnt == 3) { lv_held = lv[2]; e_held = e[2]; lv_held_b = lv_b[2]; e_held_b = e_b[2]; }
+                if (cnt == 3) { lv_held = lv[2]; lv_held_b = lv_b[2]; }
             }
-            if (q - kEarly != cur.p_mid) malformed = true;
-            p = qb - kEarly;
+            if (r_base - q != cur.p_mid) malformed = true;
+            p = r_base - qb;
         } else {
             // two streams, two sub-chunks each: four chains, ten groups of three symbols and one of two
             uint32_t pb = cur.p_mid, ppb = prv.p_mid;
             if (pb > p_limit) { pb = p_limit; malformed = true; }
             if (ppb > p_limit) { ppb = p_limit; malformed = true; }
-            uint32_t q = p + kEarly, qb = pb + kEarly, qp = pp + kEarly, qpb = ppb + kEarly;
+            uint32_t q = r_base - p, qb = r_base - pb, qp = r_base - pp, qpb = r_base - ppb;
             uint32_t W[4], e[3], W_b[4], e_b[3], W_p[4], e_p[3], W_pb[4], e_pb[3];
             float lv_held = 0.0f, lv_held_b = 0.0f, lv_held_p = 0.0f, lv_held_pb = 0.0f;
             Window wn = read_window(stage, q), wn_b = read_window(stage, qb);
@@ -445,28 +464,28 @@ __device__ __forceinline__ void decode_full_body(const Layout& lay, const Tables
             float sd32 = 0.0f;
             double sw = 0.0;
             auto emit2 = [&](int at, uint32_t w_next, float lv, uint32_t w_next_p, float lv_p) {
-                const float val = value_early<false>(w_next, lv, 0u, n);
+                const float val = value_early<false>(w_next, lv, n);
                 acc[at] += val;
-                const float df = (value_early<false>(w_next_p, lv_p, 0u, np) - val) * down;   // (a stray sign on a zero does not show in a difference)
+                const float df = (value_early<false>(w_next_p, lv_p, np) - val) * down;   // (a stray sign on a zero does not show in a difference)
                 sd32 = fmaf(df, df, sd32);
             };
 #pragma unroll
             for (int s = 0; s < kHalf; s += 3) {
                 float lv[3], lv_p[3], lv_b[3], lv_pb[3];
                 if (s + 3 <= kHalf) {
-                    parse_group_early<3, WIDE, false>(wn, s_tab, q, W, e, lv, all_neg);
+                    parse_group_early<3, WIDE, false>(wn, s_tab, q, W, e, lv, seen);
                     wn = read_window(stage, q);
-                    parse_group_early<3, WIDE, false>(wn_p, s_tab_p, qp, W_p, e_p, lv_p, all_neg);
+                    parse_group_early<3, WIDE, false>(wn_p, s_tab_p, qp, W_p, e_p, lv_p, seen);
                     wn_p = read_window(stage_p, qp);
-                    parse_group_early<3, WIDE, false>(wn_b, s_tab, qb, W_b, e_b, lv_b, all_neg);
+                    parse_group_early<3, WIDE, false>(wn_b, s_tab, qb, W_b, e_b, lv_b, seen);
                     wn_b = read_window(stage, qb);
-                    parse_group_early<3, WIDE, false>(wn_pb, s_tab_p, qpb, W_pb, e_pb, lv_pb, all_neg);
+                    parse_group_early<3, WIDE, false>(wn_pb, s_tab_p, qpb, W_pb, e_pb, lv_pb, seen);
                     wn_pb = read_window(stage_p, qpb);
                 } else {
-                    parse_group_early<2, WIDE, true>(wn, s_tab, q, W, e, lv, all_neg);
-                    parse_group_early<2, WIDE, true>(wn_p, s_tab_p, qp, W_p, e_p, lv_p, all_neg);
-                    parse_group_early<2, WIDE, true>(wn_b, s_tab, qb, W_b, e_b, lv_b, all_neg);
-                    parse_group_early<2, WIDE, true>(wn_pb, s_tab_p, qpb, W_pb, e_pb, lv_pb, all_neg);
+                    parse_group_early<2, WIDE, true>(wn, s_tab, q, W, e, lv, seen);
+                    parse_group_early<2, WIDE, true>(wn_p, s_tab_p, qp, W_p, e_p, lv_p, seen);
+                    parse_group_early<2, WIDE, true>(wn_b, s_tab, qb, W_b, e_b, lv_b, seen);
+                    parse_group_early<2, WIDE, true>(wn_pb, s_tab_p, qpb, W_pb, e_pb, lv_pb, seen);
                 }
                 const int cnt = s + 3 <= kHalf ? 3 : 2;
                 if constexpr (!WIDE) {
@@ -496,17 +515,17 @@ __device__ __forceinline__ void decode_full_body(const Layout& lay, const Tables
                 sd32 = 0.0f;
             }
             sdiff = fma(sw, up2, sdiff);
-            if (q - kEarly != cur.p_mid || qp - kEarly != prv.p_mid) malformed = true;
-            p = qb - kEarly;
-            pp = qpb - kEarly;
+            if (r_base - q != cur.p_mid || r_base - qp != prv.p_mid) malformed = true;
+            p = r_base - qb;
+            pp = r_base - qpb;
         }
         if (p != cur.p_end) malformed = true;
         if constexpr (PREV) {
             if (pp != prv.p_end) malformed = true;
         }
     }
-    // a reject entry (bit 15 set) leaves a zero among bits 15..31 of its group's negative bit count
-    malformed = malformed || (all_neg >> 15) != 0x1FFFFu;
+    // a reject entry leaves a zero among bits 15..31 of its group's negative bit count
+    malformed = malformed || (seen >> 15) != 0x1FFFFu;
     if (__any(malformed) && lane == 0) raise_error(sc, QGX_EBIT_STREAM);
     if (MODE == DecMode::Decode) return;
 

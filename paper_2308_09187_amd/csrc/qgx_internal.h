@@ -46,11 +46,14 @@ constexpr int kDlut = 1 << kDlutBits;     // 8192 entries
 constexpr uint32_t kDlutReject = 0x8000u; // no code word starts this window: flag, one bit long, symbol 0
 // When the first kWideBits bits of a code word always tell which word it is (every word at most that
 // long, or longer ones that differ from each other earlier: Elias' code up to 63 symbols), a second
-// table indexed by the next kWideBits stream bits holds the same entry together with the level value,
-// so that one 8-byte look-up per symbol replaces the entry look-up and the level look-up (same
-// footprint: 2^11 entries of 8 bytes).
+// table indexed by the next kWideBits stream bits (first bit on top as well) holds the level value
+// beside the bit count, so that one 8-byte look-up per symbol replaces the entry look-up and the level
+// look-up (same footprint: 2^11 entries of 8 bytes).  Its counts are MINUS the symbol's bits, sign
+// included, as a 32-bit number and nothing else: the parse counts downwards, and sums of these entries
+// are its shift counts as they are.  Its reject entry is minus one bit with bit 15 cleared.
 constexpr int kWideBits = 11;
 constexpr int kWide = 1 << kWideBits;
+constexpr uint32_t kWideReject = 0xFFFF7FFFu;
 
 // Device-resident tables: rebuilt on the device whenever the level table or the code changes.
 struct Tables {
@@ -72,8 +75,8 @@ struct Tables {
     // dlut[next 13 stream bits, first bit on top] = (bits of the symbol incl. sign - 1) | (4 * idx) << 4,
     // or kDlutReject
     uint16_t dlut[kDlut];
-    // dlutw[next 11 stream bits, first bit on top] = {the dlut entry, bits of l_idx}; wide_ok tells
-    // whether 11 bits identify every code word
+    // dlutw[next 11 stream bits, first bit on top] = {-(bits of the symbol incl. sign), bits of l_idx}, or
+    // {kWideReject, 0}; wide_ok tells whether 11 bits identify every code word
     uint2 dlutw[kWide];
     uint32_t wide_ok;
     uint32_t pad2_[3];

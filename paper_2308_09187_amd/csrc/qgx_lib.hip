@@ -637,7 +637,7 @@ qgx_status qgx_quantization_metrics(qgx_ctx* ctx, const float* V, const float* V
 static void fill_decode_args(const qgx_ctx* ctx, DecodeArgs& a, const qgx_stream* cur, const qgx_stream* prev)
 {
     a.stage_words = chunk_slot_words(ctx);
-    a.stage_stride = (a.stage_words + a.stage_words / 16 + 20 + 3) / 4 * 4;   // padded layout, four zero words in front, a window past the end
+    a.stage_stride = (a.stage_words + a.stage_words / 16 + 20 + 3) / 4 * 4;   // padded layout, four zero words below the chunk's end, zero words above its first
     if (a.stage_stride < 1280u) a.stage_stride = 1280u;   // the buffer also turns the output (32 rows of 36 floats)
     a.sym_bits = longest_code(ctx) + 1;
     a.rag_words = ((ctx->lay.max_ragged * a.sym_bits + 31) / 32 + a.sym_bits + 2 + 3) / 4 * 4;

@@ -45,7 +45,7 @@ static __device__ void build_tables_block(Tables* tab)
         }
     }
     for (int i = tid; i < kDlut; i += nt) tab->dlut[i] = (uint16_t)kDlutReject;
-    for (int i = tid; i < kWide; i += nt) tab->dlutw[i] = make_uint2(kDlutReject, 0u);
+    for (int i = tid; i < kWide; i += nt) tab->dlutw[i] = make_uint2(kWideReject, 0u);
     __syncthreads();
 
     for (int j = tid; j < kSymMax; j += nt) {
@@ -94,21 +94,27 @@ static __device__ void build_tables_block(Tables* tab)
         const uint32_t reps = 1u << (kDlutBits - len);
         const uint32_t entry = (j << 6) | (len - (j != 0u ? 0u : 1u));               // symbol bits - 1: sign for j != 0
         for (uint32_t s = (uint32_t)tid; s < reps; s += (uint32_t)nt) tab->dlut[first + s] = (uint16_t)entry;
-        // the same run in the 11-bit table, with the level beside the entry; a longer word takes the one
-        // slot of its first 11 bits (no shorter word's run reaches it: the code is prefix-free)
+        // the same run in the 11-bit table, with minus the symbol's bits (sign included) and the level; a
+        // longer word takes the one slot of its first 11 bits (no shorter word's run reaches it: the code is
+        // prefix-free)
         const uint32_t first_w = first >> (kDlutBits - kWideBits);
         const uint32_t reps_w = len <= (uint32_t)kWideBits ? 1u << (kWideBits - len) : 1u;
+        const uint32_t entry_w = 0u - (len + (j != 0u ? 1u : 0u));
         for (uint32_t s = (uint32_t)tid; s < reps_w; s += (uint32_t)nt)
-            tab->dlutw[first_w + s] = make_uint2(entry, __float_as_uint(lv[j]));
+            tab->dlutw[first_w + s] = make_uint2(entry_w, __float_as_uint(lv[j]));
     }
     __syncthreads();
-    // the 11-bit table is no use if two of the longer words met in one slot: one of them no longer finds itself
+    // the 11-bit table is no use if two of the longer words begin with the same 11 bits: they would meet in
+    // one slot, and one of them would no longer find itself
     for (uint32_t j = (uint32_t)tid; j < n_sym; j += (uint32_t)nt) {
         const uint32_t cw = tab->code[j];
-        const uint32_t len = cw >> 16, bits = cw & 0xFFFFu;
+        const uint32_t len = cw >> 16;
         if (len <= (uint32_t)kWideBits || len > (uint32_t)kMaxCode) continue;
-        const uint32_t first_w = (__brev(bits) >> (32u - len)) >> (len - kWideBits);
-        if ((tab->dlutw[first_w].x >> 6) != j) tab->wide_ok = 0u;
+        const uint32_t head = cw & ((1u << kWideBits) - 1u);                  // (the first-written bit is bit 0)
+        for (uint32_t i = 0; i < n_sym; ++i) {
+            const uint32_t ci = tab->code[i];
+            if (i != j && (ci >> 16) > (uint32_t)kWideBits && (ci & ((1u << kWideBits) - 1u)) == head) tab->wide_ok = 0u;
+        }
     }
     __syncthreads();
 }
