@@ -1106,32 +1106,39 @@ hipError_t launch_sum_bits(const Layout& lay, const uint16_t* sub_end, Scalars* 
 // ---- slotted -> compact ---------------------------------------------------------------------------
 // One workgroup per worker scans the chunk sizes (from the bit lengths) into exclusive offsets; then
 // one wave per chunk copies its words.
+__device__ __forceinline__ uint32_t chunk_words_of(const uint16_t* __restrict__ sub_end, size_t chunk)
+{
+    const uint32_t bits = sub_end[chunk * kSubs + (kSubs - 1)];
+    return (((bits + 31u) >> 5) + 3u) & ~3u;
+}
+
 __global__ __launch_bounds__(1024) void k_compact_offsets(uint32_t NC, const uint16_t* __restrict__ sub_end,
                                                           uint32_t* __restrict__ out_off, uint64_t out_cap, Scalars* sc)
 {
-    __shared__ uint32_t s_part[1024];
+    __shared__ uint32_t s_wave[16];
     const uint32_t k = blockIdx.x, tid = threadIdx.x;
+    const int lane = lane_id(), w = wave_id();
+    // a thread's chunks are consecutive, so its own running sum is all it carries between the two passes
     const uint32_t per = (NC + 1023u) / 1024u;
-    const uint32_t c0 = tid * per, c1 = min(c0 + per, NC);
+    const uint32_t c0 = min(tid * per, NC), c1 = min(c0 + per, NC);
     uint32_t sum = 0;
-    for (uint32_t c = c0; c < c1; ++c) {
-        const uint32_t bits = sub_end[((size_t)k * NC + c) * kSubs + (kSubs - 1)];
-        sum += (((bits + 31u) >> 5) + 3u) & ~3u;
-    }
-    s_part[tid] = sum;
+    for (uint32_t c = c0; c < c1; ++c) sum += chunk_words_of(sub_end, (size_t)k * NC + c);
+    const uint32_t incl = wave_incl_scan(sum);
+    if (lane == kWave - 1) s_wave[w] = incl;
     __syncthreads();
+    uint32_t before = 0, total = 0;
+    for (int i = 0; i < 16; ++i) {
+        if (i == w) before = total;
+        total += s_wave[i];
+    }
     if (tid == 0) {
-        uint32_t run = 0;
-        for (int i = 0; i < 1024; ++i) { const uint32_t t = s_part[i]; s_part[i] = run; run += t; }
-        out_off[(size_t)k * (NC + 1) + NC] = run;
-        if ((uint64_t)run > out_cap) raise_error(sc, QGX_EBIT_CAPACITY);
+        out_off[(size_t)k * (NC + 1) + NC] = total;
+        if ((uint64_t)total > out_cap) raise_error(sc, QGX_EBIT_CAPACITY);
     }
-    __syncthreads();
-    uint32_t run = s_part[tid];
+    uint32_t run = before + incl - sum;
     for (uint32_t c = c0; c < c1; ++c) {
         out_off[(size_t)k * (NC + 1) + c] = run;
-        const uint32_t bits = sub_end[((size_t)k * NC + c) * kSubs + (kSubs - 1)];
-        run += (((bits + 31u) >> 5) + 3u) & ~3u;
+        run += chunk_words_of(sub_end, (size_t)k * NC + c);
     }
 }
 
@@ -1143,8 +1150,7 @@ __global__ __launch_bounds__(256) void k_compact_copy(uint32_t NC, uint32_t K, c
     const uint32_t g = blockIdx.x * (blockDim.x >> 6) + (uint32_t)wave_id();
     if (g >= K * NC) return;
     const uint32_t k = g / NC, c = g - k * NC, lane = (uint32_t)lane_id();
-    const uint32_t bits = sub_end[((size_t)k * NC + c) * kSubs + (kSubs - 1)];
-    const uint32_t words = (((bits + 31u) >> 5) + 3u) & ~3u;
+    const uint32_t words = chunk_words_of(sub_end, (size_t)k * NC + c);
     const uint32_t src = in_off[(size_t)k * (NC + 1) + c], dst = out_off[(size_t)k * (NC + 1) + c];
     if ((src & 3u) || (uint64_t)src + words > in_cap || (uint64_t)dst + words > out_cap) {
         if (lane == 0) raise_error(sc, (uint64_t)dst + words > out_cap ? QGX_EBIT_CAPACITY : QGX_EBIT_STREAM);
@@ -1152,7 +1158,21 @@ __global__ __launch_bounds__(256) void k_compact_copy(uint32_t NC, uint32_t K, c
     }
     const uint4* s = reinterpret_cast<const uint4*>(in_payload + (size_t)k * in_cap + src);
     uint4* d = reinterpret_cast<uint4*>(out_payload + (size_t)k * out_cap + dst);
-    for (uint32_t q = lane; q < (words >> 2); q += kWave) d[q] = s[q];
+    // a chunk of the largest size is kPre pieces per lane: all of a lane's loads are on their way before
+    // its first store (a chunk of some other origin may be longer: the loop goes on)
+    for (uint32_t q0 = 0; q0 < (words >> 2); q0 += (uint32_t)(kPre * kWave)) {
+        uint4 held[kPre];
+#pragma unroll
+        for (int j = 0; j < kPre; ++j) {
+            const uint32_t q = q0 + lane + (uint32_t)j * kWave;
+            held[j] = q < (words >> 2) ? nt_load4u(s + q) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < kPre; ++j) {
+            const uint32_t q = q0 + lane + (uint32_t)j * kWave;
+            if (q < (words >> 2)) d[q] = held[j];
+        }
+    }
 }
 
 hipError_t launch_compact(const Layout& lay, const uint16_t* sub_end, const uint32_t* in_off, const uint32_t* in_payload,
