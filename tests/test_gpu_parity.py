@@ -671,6 +671,71 @@ def test_step_size_sum_at_extreme_scales(qgx, scale, bucket):
     ctx.close()
 
 
+def _vectors_of_very_different_density(d, order):
+    """One vector per entry of `order`: "dense" (every coordinate near the bucket's maximum: the longest code
+    words, chunks of about 13 bits per coordinate), "t3" (the usual mix), "sparse" (one coordinate in 500
+    is not zero: chunks of little more than a bit per coordinate), "zero" (nothing: every bucket dead)."""
+    rows = []
+    for i, kind in enumerate(order):
+        rng = np.random.default_rng(1000 + i)
+        if kind == "dense":
+            v = rng.uniform(0.5, 1.0, d) * rng.choice([-1.0, 1.0], d)
+        elif kind == "t3":
+            v = synth.student_t3(1, d, seed=70 + i)[0].astype(np.float64)
+        elif kind == "sparse":
+            v = np.where(rng.random(d) < 0.002, rng.standard_normal(d), 0.0)
+        else:
+            v = np.zeros(d)
+        rows.append(v.astype(np.float32))
+    return np.stack(rows)
+
+
+@pytest.mark.parametrize("waves", [1, 2])
+def test_chunks_of_very_different_lengths_at_one_position(qgx, monkeypatch, waves):
+    """The decoder's waves stage one worker's chunk after the other in the same LDS buffer and only write the
+    pieces a chunk has, so a short chunk lies on top of what a long one left behind.  Here the workers'
+    chunks at every position go from about 1600 words to 40 and back, in a different order in the two
+    half-steps' streams, on full positions and a ragged one; mean, both updates and S against the oracle."""
+    monkeypatch.setitem(WAVES_PER_POSITION, "waves", waves)
+    d, K, bucket = 3 * 4096 + 1500, 6, 4096
+    levels = synth.levels_uniform(64)                  # Elias' words for 33..65 take 11 and 12 bits, and a sign
+    ctx, lay = make_ctx(qgx, d, K, bucket, oracle.NORM_LINF, levels, seed=5)
+    Va = _vectors_of_very_different_density(d, ["dense", "sparse", "t3", "zero", "dense", "sparse"])
+    Vb = _vectors_of_very_different_density(d, ["sparse", "dense", "zero", "dense", "t3", "dense"])
+    ctx.state_init(None)
+    st = oracle.EGState(d, K)
+    prev, cur, tmp = ctx.new_stream(slotted=True), ctx.new_stream(slotted=True), ctx.new_stream()
+    Xh = torch.empty(d, device="cuda"); Xn = torch.empty(d, device="cuda")
+    ctx.quantize_encode(dev(Va), 0, prev)
+    hp = ctx.compact(prev, tmp).to_host()
+    _, _, _, so = oracle_stream(Va, lay, oracle.NORM_LINF, levels, 5, 0, hp["norms"], ctx.worst_words)
+    assert_stream_equal(hp, so, lay)
+    words = np.diff(so.chunk_off.astype(np.int64), axis=1)[:, :3]         # the full positions
+    assert words.max() >= 1500 and words.min() <= 160, words
+    Vhat0, _, _ = oracle.decode(so, hp["norms"], lay, levels)
+    np.testing.assert_array_equal(ctx.decode(prev).cpu().numpy(), Vhat0)
+    m = ctx.decode_average(prev).cpu().numpy()
+    assert_elementwise(m, oracle.mean(Vhat0), mean_abs(Vhat0), "mean")
+    ctx.eg_step(0, prev, None, Xh)
+    Xh_o = st.half0(Vhat0)
+    assert rel_err(Xh.cpu().numpy(), Xh_o) <= REL
+    ctx.quantize_encode(dev(Vb), 1, cur)
+    ctx.eg_step(1, cur, prev, Xn)
+    hc = ctx.compact(cur, tmp).to_host()
+    _, _, _, so1 = oracle_stream(Vb, lay, oracle.NORM_LINF, levels, 5, 1, hc["norms"], ctx.worst_words)
+    assert_stream_equal(hc, so1, lay)
+    Vhat1, _, _ = oracle.decode(so1, hc["norms"], lay, levels)
+    Xn_o = st.half1(Vhat1, Vhat0)
+    sc = ctx.scalars()
+    assert abs(sc["S"] - st.S) <= REL * st.S
+    assert abs(sc["gamma"] - st.gamma) <= REL * st.gamma
+    assert rel_err(Xn.cpu().numpy(), Xn_o) <= REL
+    Y, _ = ctx.state_export()
+    assert rel_err(Y.cpu().numpy(), st.Y) <= REL
+    assert ctx.poll_error() == 0
+    ctx.close()
+
+
 def test_bilinear_game_100_iterations_lockstep(qgx):
     """Workload 1: x, y in R^512, K = 4, L2, bucket = whole vector, 8 exponential levels, 100 iterations."""
     game = synth.BilinearGame(n=512, K=4, noise=0.1)
