@@ -6,14 +6,14 @@
 // One wave per chunk position.  The wave copies a worker's chunk from the payload into LDS with
 // coalesced 16-byte loads, then every lane parses its own 64 coordinates, that is two sub-chunks of
 // 32, each starting at the bit offset the sub-chunk table gives: a 64-bit window from three LDS words
-// per three symbols, one 13-bit table lookup for (symbol, length) each, the sign bit, one multiply by
-// the bucket norm.  A symbol's length decides where the next one starts, so a parse is one long
-// dependent chain of LDS look-ups; what a lane can do about that is to follow two chains at once:
-// its two sub-chunks when there is one stream, the two streams of the second half-step (each over
-// both sub-chunks in turn).  The K decoded values of a coordinate are summed in registers, so decoded
-// vectors never go to HBM in the fused modes.  Chunk positions with fewer than 4096 coordinates are
-// few and go to a kernel of their own (k_decode_ragged), which spreads a position's workers over the
-// waves of a workgroup.
+// per three symbols, one table look-up by the next 13 (or 11) stream bits for each symbol's length and
+// level, the sign bit, one multiply by the bucket norm.  A symbol's length decides where the next one
+// starts, so a parse is one long dependent chain of LDS look-ups; what a lane can do about that is to
+// follow several chains at once: its two sub-chunks, of one stream or (second half-step) of both.
+// The K decoded values of a coordinate are summed in registers, so decoded vectors never go to HBM in
+// the fused modes.  Chunk positions with fewer than 4096 coordinates are few and have a body of their
+// own (decode_ragged_body), which spreads a position's workers over the waves of a workgroup; it runs
+// in the same launch as the full positions' body when a layout has both.
 #include "qgx_device.h"
 
 namespace qgx {
@@ -270,7 +270,8 @@ __device__ __forceinline__ void chunk_geometry(const Layout& lay, uint32_t c, ui
 // LDS); the others are k_decode_ragged's.
 // PREV (Half1): the previous half-step's streams are there; without them the vectors count as zero.
 // TWO: those were coded with another level table and code (a.tab_p) than the current ones.
-// WIDE: no code word has more than kWideBits bits, so the 8-byte decode table is there (one stream).
+// WIDE: the first kWideBits bits of a code word always tell which one it is, so the 8-byte decode table
+// is there (of both codes, with TWO).
 // KSPLIT = 2 or 4: that many neighbouring waves share a position, each takes a run of the workers (as
 // equal as K allows, the longer runs first), and they add their sums through LDS before the update
 // (for layouts with too few positions to fill the GPU's wave slots).
