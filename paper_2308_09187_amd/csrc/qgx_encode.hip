@@ -168,7 +168,9 @@ __device__ __forceinline__ uint32_t quantize_one(float x, float rinv, uint32_t r
                                                  uint32_t& idx_out)
 {
     float u = fabsf(x) * rinv;                          // |v| / ||v||
-    const uint32_t sg = (__float_as_uint(x) >> L.sign_shift) & L.lev_stride;   // sign selects the table half
+    // the sign selects the table half (by constants where the cell size is one)
+    const uint32_t sg = CM != 0 ? (__float_as_uint(x) >> lev_sign_shift_of(CM)) & lev_stride_of(CM)
+                                : (__float_as_uint(x) >> L.sign_shift) & L.lev_stride;
     float4 t;
     uint32_t row;                                       // byte offset of the level row in its half
     if (FAST) {
@@ -185,7 +187,7 @@ __device__ __forceinline__ uint32_t quantize_one(float x, float rinv, uint32_t r
         // the cell's lower row, or the next one from the boundary level on (one level per cell at most)
         const uint32_t at = sg + c.y + (u >= __uint_as_float(c.x) ? 16u : 0u);
         t = lds_load_f4(at);
-        row = (at - L.lev_addr) & (L.lev_stride - 1u);
+        row = (at - L.lev_addr) & ((CM != 0 ? lev_stride_of(CM) : L.lev_stride) - 1u);
     } else {
         u = fminf(u, 1.0f);
         row = level_row_general(L, u, n_sym);

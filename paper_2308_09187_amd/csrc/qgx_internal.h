@@ -33,6 +33,11 @@ constexpr int kCellMantMax = 6;
 constexpr int kCellsMax = (kCellOct << kCellMantMax) + 1;    // 1537
 constexpr int kCellsPadMax = 1540;
 inline __host__ __device__ int cell_mant(uint32_t n_sym) { return n_sym <= 33u ? 4 : n_sym <= 65u ? 5 : 6; }
+// Bytes between the two sign halves of the encoder's level rows in LDS, by cell size (that is, by the
+// largest table of the class): a power of two that the kernel knows at compile time, so that the sign of
+// a coordinate picks its half with a shift and a mask by constants.
+inline __host__ __device__ constexpr uint32_t lev_stride_of(int mant) { return mant == 4 ? 1024u : 2048u; }
+inline __host__ __device__ constexpr uint32_t lev_sign_shift_of(int mant) { return mant == 4 ? 21u : 20u; }
 inline __host__ __device__ int cell_count(int mant) { return (kCellOct << mant) + 1; }
 inline __host__ __device__ int cell_count_padded(int mant) { return (cell_count(mant) + 3) / 4 * 4; }
 constexpr int kLevRegion = kSymMax * 16;                // bytes between the two sign halves of lev2
@@ -149,7 +154,7 @@ struct EncodeArgs {
     int norm_kind;
     // LDS plan of the launch (bytes): [cell][lev: two sign halves lev_stride apart][misc][stage x waves]
     uint32_t cell_mant;         // cell_mant(n_sym) of the table in use
-    uint32_t lev_stride;        // power of two >= 16 * n_sym
+    uint32_t lev_stride;        // lev_stride_of(cell_mant): a power of two >= 16 * n_sym
     uint32_t lev_bytes;         // lev_stride + 16 * n_sym: the second half ends with its last row
     uint32_t sign_shift;        // (bits of v) >> sign_shift puts the sign bit on lev_stride
     uint32_t stage_bytes;       // per wave, multiple of 16, covers 4096 symbols of the longest code + sign

@@ -472,12 +472,10 @@ static qgx_status run_encode(qgx_ctx* ctx, EncMode mode, const float* V, uint32_
     a.seed_lo = (uint32_t)ctx->cfg.seed; a.seed_hi = (uint32_t)(ctx->cfg.seed >> 32); a.call_id = call_id;
     a.call_mode = call_id == QGX_CALL_FIRST_HALF ? 1u : call_id == QGX_CALL_SECOND_HALF ? 2u : 0u;
     a.norm_kind = ctx->cfg.norm;
-    a.lev_stride = 16;
-    while (a.lev_stride < 16u * T(ctx).n_sym) a.lev_stride <<= 1;
-    a.lev_bytes = a.lev_stride + 16u * T(ctx).n_sym;
     a.cell_mant = (uint32_t)cell_mant(T(ctx).n_sym);
-    a.sign_shift = 31;
-    while ((1u << (31 - a.sign_shift)) < a.lev_stride) --a.sign_shift;
+    a.lev_stride = lev_stride_of((int)a.cell_mant);
+    a.lev_bytes = a.lev_stride + 16u * T(ctx).n_sym;
+    a.sign_shift = lev_sign_shift_of((int)a.cell_mant);
     {
         const uint32_t words = (kChunk * (T(ctx).max_code_len + 1) + 31) / 32 + 4;
         a.stage_bytes = (words + 3) / 4 * 16;
