@@ -294,30 +294,39 @@ __global__ __launch_bounds__(256) void k_histogram_small(Layout lay, const float
         partial[(size_t)blockIdx.x * n_bins + i] = s_acc[i];
 }
 
-// Workgroup sums -> histogram, in an order that does not depend on timing: a thread adds a run of
-// kRedRun consecutive workgroups' values of one bin, then the runs of a bin are added in order.
-constexpr uint32_t kRedRun = 32;
-constexpr uint32_t kRedBins = 32;      // bins per workgroup of 256 threads: 8 runs in flight per bin
+// Workgroup sums -> histogram, in an order that does not depend on timing: the workgroups' values of a
+// bin are cut into kRedSegs runs of consecutive workgroups, a thread adds one run, then the runs of a bin
+// are added in order.  16 bins to a workgroup: 256 workgroups for the largest histogram, a row of 16 lanes
+// reads 128 consecutive bytes of one workgroup's sums.
+constexpr uint32_t kRedBins = 16;
+constexpr uint32_t kRedSegs = 16;
 
-__global__ __launch_bounds__(256) void k_hist_reduce(uint32_t n_bins, uint32_t n_partial,
-                                                     const double* __restrict__ partial, double* __restrict__ hist)
+__global__ __launch_bounds__(kRedBins * kRedSegs) void k_hist_reduce(uint32_t n_bins, uint32_t n_partial,
+                                                                     const double* __restrict__ partial,
+                                                                     double* __restrict__ hist)
 {
-    __shared__ double s_run[8][kRedBins];
-    const uint32_t bl = threadIdx.x & (kRedBins - 1u), seg = threadIdx.x / kRedBins;     // 8 segments
+    __shared__ double s_run[kRedSegs][kRedBins];
+    const uint32_t bl = threadIdx.x & (kRedBins - 1u), seg = threadIdx.x / kRedBins;
     const uint32_t i = blockIdx.x * kRedBins + bl;
-    double tot = 0.0;
-    for (uint32_t g0 = 0; g0 < n_partial; g0 += 8u * kRedRun) {
-        const uint32_t lo = g0 + seg * kRedRun, hi = min(lo + kRedRun, n_partial);
-        double acc = 0.0;
-        if (i < n_bins)
-            for (uint32_t g = lo; g < hi; ++g) acc += partial[(size_t)g * n_bins + i];
-        s_run[seg][bl] = acc;
-        __syncthreads();
-        if (seg == 0)
-            for (int q = 0; q < 8; ++q) tot += s_run[q][bl];
-        __syncthreads();
+    const uint32_t run = (n_partial + kRedSegs - 1u) / kRedSegs;
+    const uint32_t lo = min(seg * run, n_partial), hi = min(lo + run, n_partial);
+    double acc = 0.0;
+    if (i < n_bins) {
+        uint32_t g = lo;
+        for (; g + 4u <= hi; g += 4u) {                   // four loads on their way, added in order
+            const double v0 = partial[(size_t)g * n_bins + i], v1 = partial[(size_t)(g + 1u) * n_bins + i];
+            const double v2 = partial[(size_t)(g + 2u) * n_bins + i], v3 = partial[(size_t)(g + 3u) * n_bins + i];
+            acc += v0; acc += v1; acc += v2; acc += v3;
+        }
+        for (; g < hi; ++g) acc += partial[(size_t)g * n_bins + i];
     }
-    if (seg == 0 && i < n_bins) hist[i] = tot;
+    s_run[seg][bl] = acc;
+    __syncthreads();
+    if (seg == 0 && i < n_bins) {
+        double tot = 0.0;
+        for (uint32_t q = 0; q < kRedSegs; ++q) tot += s_run[q][bl];
+        hist[i] = tot;
+    }
 }
 
 uint32_t histogram_groups(const Layout& lay)
@@ -350,7 +359,7 @@ hipError_t launch_histogram(const Layout& lay, const float* V, int norm_kind, ui
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_hist_reduce, dim3((n_bins + kRedBins - 1u) / kRedBins), dim3(256), 0, st, n_bins, n_partial,
+    hipLaunchKernelGGL(k_hist_reduce, dim3((n_bins + kRedBins - 1u) / kRedBins), dim3(kRedBins * kRedSegs), 0, st, n_bins, n_partial,
                        partial, hist);
     return hipGetLastError();
 }
