@@ -62,7 +62,7 @@ __global__ __launch_bounds__(MAXW * kWave) void k_histogram(Layout lay, const fl
             const uint32_t i0 = clo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
             float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
             if (i0 + 4u <= cend) {
-                if (vec_ok) x = *reinterpret_cast<const float4*>(Vk + i0);
+                if (vec_ok) x = nt_load4(Vk + i0);                // (read once)
                 else x = make_float4(Vk[i0], Vk[i0 + 1], Vk[i0 + 2], Vk[i0 + 3]);
             } else if (i0 < cend) {
                 x.x = Vk[i0];
@@ -214,7 +214,7 @@ __global__ __launch_bounds__(256) void k_histogram_small(Layout lay, const float
             const uint32_t i0 = lo + (uint32_t)r * 256u + (uint32_t)lane * 4u;
             float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
             if (i0 + 4u <= hi) {
-                if (vec_ok) x = *reinterpret_cast<const float4*>(Vk + i0);
+                if (vec_ok) x = nt_load4(Vk + i0);                // (read once)
                 else x = make_float4(Vk[i0], Vk[i0 + 1], Vk[i0 + 2], Vk[i0 + 3]);
             } else if (i0 < hi) {
                 x.x = Vk[i0];
