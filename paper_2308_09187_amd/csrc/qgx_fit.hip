@@ -572,7 +572,6 @@ __global__ __launch_bounds__(256) void k_fit(Tables* tab, const double* __restri
     __shared__ double s_m2[QGX_MAX_BINS / 256], s_r2[QGX_MAX_BINS / 256];
     __shared__ double s_lev[kSymMax + 1];                         // the table between passes
     __shared__ double s_moved[2][kRow];                           // what each row moved in the last two steps
-    __shared__ double s_total;
 
     const uint32_t tid = threadIdx.x;
     for (uint32_t b = tid; b < n_bins; b += 256u) H[b] = hist[b];
@@ -602,17 +601,15 @@ __global__ __launch_bounds__(256) void k_fit(Tables* tab, const double* __restri
     }
     const uint32_t n_sym = tab->n_sym;
     if (tid < n_sym) s_lev[tid] = (double)tab->levels[tid];
-    if (tid == 0) {
-        double total = 0.0;
-        for (uint32_t i = 0; i < n1; ++i) total += s_m1[i];
-        s_total = total;
-    }
     __syncthreads();
+    // is there any mass at all?  (terms that are not negative: the order of the sum does not matter to that)
+    double total = 0.0;
+    for (uint32_t i = 0; i < (n_bins + 255u) >> 8; ++i) total += s_m2[i];
     (void)n2;
 
     const Tree T = {H, s_m1, s_r1, s_m2, s_r2, n_bins};
     const uint32_t row = tid >> 4, top = n_sym - 1u;
-    if (s_total > 0.0 && n_sym > 2u) {
+    if (total > 0.0 && n_sym > 2u) {
         for (uint32_t first = 0; first < sweeps; first += kRow) {
             const uint32_t ns = min(kRow, sweeps - first);               // sweeps of this pass, one per row
             double mine = 0.0;                      // the level this row moved in its last step
